@@ -1,0 +1,463 @@
+"""Pins for the CPU oracle: every function is checked against something other than itself —
+closed forms, exact integer brute force, library routines, printed table values, invariants.
+Each pin names the mistake it would catch.  CPU only."""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _int_case(seed, n, d, lo=-3, hi=4):
+    g = np.random.default_rng(seed)
+    K = g.integers(lo, hi, size=(n, d)).astype(np.float32)
+    q = g.integers(lo, hi, size=d).astype(np.float32)
+    return q, K
+
+
+# ------------------------------------------------------------------ scores and the range set
+def test_scores_exact_integer_bruteforce(oracle):
+    """Small integer vectors: Python integer arithmetic gives the exact dot product, both
+    score routines must reproduce it exactly (catches wrong index, transposed K, dropped term)."""
+    for seed in range(20):
+        q, K = _int_case(seed, n=13, d=5)
+        exact = [sum(int(q[c]) * int(K[j, c]) for c in range(5)) for j in range(13)]
+        assert oracle.scores_f64(q, K).tolist() == exact
+        assert oracle.scores_f32(q, K).tolist() == exact
+
+
+def test_scores_unit_vectors(oracle):
+    """Keys that are scaled basis vectors: the score is a single product q_c * a."""
+    d = 7
+    q = np.arange(1, d + 1, dtype=np.float32) * 0.5
+    K = np.zeros((d, d), dtype=np.float32)
+    for c in range(d):
+        K[c, c] = c - 3.0
+    assert np.array_equal(oracle.scores_f32(q, K), q * (np.arange(d) - 3.0))
+
+
+def test_scores_match_library_matmul(oracle):
+    g = np.random.default_rng(1)
+    K = g.standard_normal((300, 128)).astype(np.float32)
+    q = g.standard_normal(128).astype(np.float32)
+    lib = K.astype(np.float64) @ q.astype(np.float64)
+    assert np.allclose(oracle.scores_f64(q, K), lib, rtol=0, atol=1e-12 * np.abs(lib).max() + 1e-12)
+    # fp32 sequential sum stays within the classical bound d * eps * sum |terms|
+    terms = np.abs(K.astype(np.float64) * q.astype(np.float64)).sum(axis=1)
+    assert np.all(np.abs(oracle.scores_f32(q, K) - lib) <= 128 * 2.0 ** -24 * terms)
+
+
+def test_scores_f32_is_sequential_unfused(oracle):
+    """(1 + 2^-24) + (-1): a fused or reordered sum gives a different answer from one fp32
+    accumulator taken left to right (catches -ffast-math style reassociation and FMA)."""
+    q = np.array([1.0, 1.0, 1.0], dtype=np.float32)
+    K = np.array([[1.0, 2.0 ** -24, -1.0]], dtype=np.float32)
+    assert oracle.scores_f32(q, K)[0] == 0.0          # 1 + 2^-24 rounds to 1 (ties to even)
+    assert oracle.scores_f64(q, K)[0] == 2.0 ** -24
+    # product rounding: (1+2^-12)^2 = 1 + 2^-11 + 2^-24 rounds to 1 + 2^-11 before the add
+    # and -1 + that product: rounding the product first loses the 2^-24 a fused multiply-add
+    # (or a wider product) would keep
+    a = np.float32(1.0 + 2.0 ** -12)
+    q = np.array([1.0, a], dtype=np.float32)
+    K = np.array([[-1.0, a]], dtype=np.float32)
+    assert oracle.scores_f32(q, K)[0] == 2.0 ** -11
+    assert oracle.scores_f64(q, K)[0] == 2.0 ** -11 + 2.0 ** -24
+
+
+def test_bf16_storage_is_widened_exactly(oracle):
+    g = np.random.default_rng(2)
+    K = W.round_to_bf16(g.standard_normal((50, 16)).astype(np.float32))
+    q = g.standard_normal(16).astype(np.float32)
+    bits = W.f32_to_bf16_bits(K).reshape(K.shape)
+    assert np.array_equal(oracle.scores_f32(q, bits), oracle.scores_f32(q, K))
+    assert np.array_equal(oracle.scores_f64(q, bits), oracle.scores_f64(q, K))
+
+
+def test_range_set_exhaustive_tiny(oracle):
+    """All thresholds between and at the score values of tiny integer cases: the set is
+    exactly the positions whose exact integer score is >= tau; a tie at tau is included
+    (catches > instead of >=, wrong sign, off-by-one in the compaction)."""
+    for seed in range(10):
+        q, K = _int_case(100 + seed, n=9, d=3)
+        exact = [sum(int(q[c]) * int(K[j, c]) for c in range(3)) for j in range(9)]
+        for tau in sorted(set(exact)) + [min(exact) - 1, max(exact) + 1] + [e + 0.5 for e in exact]:
+            want = [j for j in range(9) if exact[j] >= tau]
+            assert oracle.range_query(q, K, tau).tolist() == want
+
+
+def test_range_set_count_identity_and_monotone(oracle):
+    g = np.random.default_rng(3)
+    K = g.standard_normal((2000, 128)).astype(np.float32)
+    q = g.standard_normal(128).astype(np.float32)
+    s = oracle.scores_f32(q, K)
+    prev = None
+    for k in (0, 1, 7, 40, 500, 2000):
+        tau = W.tau_for_count(s, k)
+        got = oracle.range_query(q, K, tau)
+        assert got.size == k                      # midpoint threshold -> exactly k keys
+        assert np.all(np.diff(got) > 0)           # ascending positions
+        if prev is not None:
+            assert set(prev.tolist()) <= set(got.tolist())   # lowering tau only adds keys
+        prev = got
+    assert oracle.range_query(q, K, -np.inf).size == 2000
+    assert oracle.range_query(q, K, np.inf).size == 0
+
+
+def test_planted_keys_are_retrieved(oracle):
+    """Config-1 recipe: keys rescaled to score tau + delta are in the set by construction."""
+    cache = W.make_cache(1)
+    K = cache.K[0, 0]
+    q = W.make_queries(1)[0, 0]
+    s = oracle.scores_f32(q, K)
+    tau = float(W.tau_for_fraction(s, 0.02))
+    rows = W.planted_positions(1, K.shape[0], 8)
+    W.plant_rows(K, rows, (tau + 0.5) / s[rows], "f32")
+    got = set(oracle.range_query(q, K, tau).tolist())
+    assert set(rows.tolist()) <= got
+
+
+# ------------------------------------------------------------------ attention on a set
+def _sdpa(q, K, V, sigma):
+    qt = torch.tensor(q, dtype=torch.float64)[None, None, None, :]
+    Kt = torch.tensor(K, dtype=torch.float64)[None, None]
+    Vt = torch.tensor(V, dtype=torch.float64)[None, None]
+    return torch.nn.functional.scaled_dot_product_attention(qt, Kt, Vt, scale=sigma)[0, 0, 0].numpy()
+
+
+def test_attention_full_set_equals_library_sdpa(oracle):
+    """tau = -inf retrieves everything, and attention on everything is textbook attention:
+    compare with torch's scaled_dot_product_attention in fp64, at the default and at a
+    non-default scale (catches K/V swapped, missing scale, wrong normaliser)."""
+    g = np.random.default_rng(4)
+    K = g.standard_normal((257, 128)).astype(np.float32)
+    V = g.standard_normal((257, 128)).astype(np.float32)
+    q = g.standard_normal(128).astype(np.float32)
+    idx = oracle.range_query(q, K, -np.inf)
+    assert idx.tolist() == list(range(257))
+    for sigma in (1.0 / math.sqrt(128), 0.37):
+        got = oracle.attention_on_list(q, K, V, idx, sigma)
+        assert np.allclose(got, _sdpa(q, K, V, sigma), rtol=2e-6, atol=1e-7)
+
+
+def test_attention_subset_equals_sdpa_on_subset(oracle):
+    g = np.random.default_rng(5)
+    K = g.standard_normal((100, 32)).astype(np.float32)
+    V = g.standard_normal((100, 32)).astype(np.float32)
+    q = g.standard_normal(32).astype(np.float32)
+    idx = np.array([3, 17, 18, 64, 99], dtype=np.int32)
+    got = oracle.attention_on_list(q, K, V, idx, 0.2)
+    assert np.allclose(got, _sdpa(q, K[idx], V[idx], 0.2), rtol=2e-6, atol=1e-7)
+    # order of the list is irrelevant
+    perm = idx[[4, 0, 3, 1, 2]]
+    assert np.allclose(oracle.attention_on_list(q, K, V, perm, 0.2), got, rtol=1e-6, atol=1e-7)
+
+
+def test_attention_closed_forms(oracle):
+    g = np.random.default_rng(6)
+    K = g.standard_normal((10, 8)).astype(np.float32)
+    V = g.standard_normal((10, 8)).astype(np.float32)
+    q = g.standard_normal(8).astype(np.float32)
+    # one key: the output is its value row
+    assert np.array_equal(oracle.attention_on_list(q, K, V, [4], 0.3), V[4])
+    # two keys: logistic mix of the two value rows
+    s = K.astype(np.float64) @ q.astype(np.float64)
+    w = 1.0 / (1.0 + math.exp(-0.3 * (s[2] - s[7])))
+    want = w * V[2].astype(np.float64) + (1 - w) * V[7].astype(np.float64)
+    assert np.allclose(oracle.attention_on_list(q, K, V, [2, 7], 0.3), want, rtol=1e-6, atol=1e-7)
+    # zero query: uniform weights -> plain mean of the selected value rows
+    z = np.zeros(8, dtype=np.float32)
+    assert np.allclose(oracle.attention_on_list(z, K, V, [1, 2, 3, 9], 0.3), V[[1, 2, 3, 9]].mean(0),
+                       rtol=1e-6, atol=1e-7)
+    # empty set: zeros
+    assert np.array_equal(oracle.attention_on_list(q, K, V, [], 0.3), np.zeros(8, np.float32))
+    # huge logits do not overflow (max subtraction)
+    big = (K * 1000).astype(np.float32)
+    out = oracle.attention_on_list(q * 10, big, V, list(range(10)), 1.0)
+    assert np.all(np.isfinite(out))
+    assert np.allclose(out, V[int(np.argmax(big.astype(np.float64) @ (q * 10).astype(np.float64)))], atol=1e-6)
+
+
+def test_decode_step_layout_and_gqa_mapping(oracle):
+    """Batched entry point against per-head calls, and the head map h_kv = h_q // G pinned by
+    value rows that name their own KV head."""
+    g = np.random.default_rng(7)
+    batch, hq, hkv, n, d = 2, 6, 3, 40, 16
+    K = g.standard_normal((batch, hkv, n, d)).astype(np.float32)
+    V = np.zeros((batch, hkv, n, d), dtype=np.float32)
+    for b in range(batch):
+        for h in range(hkv):
+            V[b, h] = 10 * b + h          # every value row of KV head (b,h) is the constant 10b+h
+    q = g.standard_normal((batch, hq, d)).astype(np.float32)
+    tau = np.full((batch, hq), -np.inf, dtype=np.float32)
+    sets, count, out = oracle.decode_step(K, V, q, tau, 0.25, hq)
+    for b in range(batch):
+        for h in range(hq):
+            assert np.allclose(out[b, h], 10 * b + h // 2)
+            assert count[b, h] == n
+    V = g.standard_normal((batch, hkv, n, d)).astype(np.float32)
+    s_all = np.einsum("bhnd,bhgd->bhgn", K.astype(np.float64), q.reshape(batch, hkv, 2, d).astype(np.float64))
+    tau = W.tau_for_count(s_all.reshape(batch, hq, n), 5)
+    sets, count, out = oracle.decode_step(K, V, q, tau, 0.25, hq)
+    for b in range(batch):
+        for h in range(hq):
+            want = oracle.range_query(q[b, h], K[b, h // 2], tau[b, h])
+            assert sets[b][h].tolist() == want.tolist() and count[b, h] == 5
+            assert np.array_equal(out[b, h], oracle.attention_on_list(q[b, h], K[b, h // 2], V[b, h // 2], want, 0.25))
+    # recent-keys-always-attended variant: positions >= extra_from join the set
+    sets2, count2, _ = oracle.decode_step(K, V, q, tau, 0.25, hq, extra_from=n - 3)
+    for b in range(batch):
+        for h in range(hq):
+            assert set(sets2[b][h].tolist()) == set(sets[b][h].tolist()) | {n - 3, n - 2, n - 1}
+    # dense entry point = everything retrieved
+    dense = oracle.dense_attention(K, V, q, 0.25, hq)
+    for b in range(batch):
+        for h in range(hq):
+            assert np.allclose(dense[b, h], _sdpa(q[b, h], K[b, h // 2], V[b, h // 2], 0.25), rtol=2e-6, atol=1e-7)
+
+
+# ------------------------------------------------------------------ ball index and bound
+def test_subspace_blocks_partition_coordinates(oracle):
+    for d, S in [(128, 4), (128, 16), (10, 3), (7, 7), (5, 1)]:
+        blocks = [oracle.subspace_range(d, S, s) for s in range(S)]
+        assert blocks[0][0] == 0 and blocks[-1][1] == d
+        assert all(blocks[i][1] == blocks[i + 1][0] for i in range(S - 1))
+        widths = [hi - lo for lo, hi in blocks]
+        assert set(widths) <= {d // S, -(-d // S)}
+
+
+def test_ball_index_closed_forms(oracle):
+    """Two-point group: centre = midpoint, radius = half the distance (per subspace).
+    One-point group: radius 0.  Catches dividing by r instead of the member count and a
+    radius taken over the wrong coordinates."""
+    K = np.array([[0, 0, 0, 0], [6, 8, 2, 0], [1, 1, 1, 1]], dtype=np.float32)
+    label = np.array([0, 0, 1], dtype=np.int32)
+    centre, radius = oracle.ball_index(K, label, 2, S=2)
+    assert np.array_equal(centre, [[3, 4, 1, 0], [1, 1, 1, 1]])
+    assert np.allclose(radius, [[5.0, 1.0], [0.0, 0.0]])
+    centre, radius = oracle.ball_index(K, label, 2, S=1)
+    assert np.allclose(radius, [[math.sqrt(26.0)], [0.0]])
+
+
+def test_ball_enclosure_and_bound_dominate_members(oracle):
+    """Eq. (1) enclosure and the upper-bound chain: every member lies in its ball in every
+    subspace; each f_{s,a(j)} >= the member's subspace dot product; their sum >= <q,k_j>."""
+    g = np.random.default_rng(8)
+    n, d, S, r = 96, 16, 4, 4
+    K = g.standard_normal((n, d)).astype(np.float32) * g.uniform(0.2, 5, size=d).astype(np.float32)
+    label = (g.permutation(n) // r).astype(np.int32)
+    centre, radius = oracle.ball_index(K, label, n // r, S)
+    for _ in range(5):
+        q = g.standard_normal(d).astype(np.float32)
+        f = oracle.ball_bounds(q, centre, radius)
+        tot = np.zeros(n)
+        for s in range(S):
+            lo, hi = oracle.subspace_range(d, S, s)
+            part = K[:, lo:hi].astype(np.float64) @ q[lo:hi].astype(np.float64)
+            dist = np.linalg.norm(K[:, lo:hi] - centre[label, lo:hi], axis=1)
+            assert np.all(dist <= radius[label, s] * (1 + 1e-12))
+            assert np.all(f[s, label] >= part - 1e-9)
+            tot += f[s, label]
+        assert np.all(tot >= oracle.scores_f64(q, K) - 1e-9)
+    # the radius is attained by some member (it is a max, not a looser bound)
+    for s in range(S):
+        lo, hi = oracle.subspace_range(d, S, s)
+        dist = np.linalg.norm(K[:, lo:hi].astype(np.float64) - centre[label, lo:hi], axis=1)
+        for gi in range(n // r):
+            assert math.isclose(dist[label == gi].max(), radius[gi, s], rel_tol=1e-12)
+
+
+def test_ball_bound_is_the_maximum_over_the_ball(oracle):
+    """Eq. (2) against brute force: f equals <q, x*> at the maximiser x* = c + rho q/|q| and no
+    point sampled on or inside the ball exceeds it (catches minus instead of plus, a missing
+    norm, a norm over the full space instead of the subspace)."""
+    g = np.random.default_rng(9)
+    d = 6
+    centre = g.standard_normal((3, d))
+    radius = g.uniform(0.1, 2.0, size=(3, 1))
+    q = g.standard_normal(d).astype(np.float32)
+    f = oracle.ball_bounds(q, centre, radius)[0]
+    qd = q.astype(np.float64)
+    for i in range(3):
+        xstar = centre[i] + radius[i, 0] * qd / np.linalg.norm(qd)
+        assert math.isclose(f[i], float(qd @ xstar), rel_tol=1e-12)
+        u = g.standard_normal((20000, d))
+        u /= np.linalg.norm(u, axis=1, keepdims=True)
+        pts = centre[i] + radius[i, 0] * u * g.uniform(0, 1, size=(20000, 1)) ** (1 / d)
+        assert np.all(pts @ qd <= f[i] + 1e-12)
+        assert (centre[i] + radius[i, 0] * u).dot(qd).max() > f[i] - 0.25 * radius[i, 0] * np.linalg.norm(qd)
+    # two subspaces: each bound uses its own coordinate block and its own |pi_s q|
+    radius2 = g.uniform(0.1, 2.0, size=(3, 2))
+    f2 = oracle.ball_bounds(q, centre, radius2)
+    for s, (lo, hi) in enumerate([(0, 3), (3, 6)]):
+        want = centre[:, lo:hi] @ qd[lo:hi] + radius2[:, s] * np.linalg.norm(qd[lo:hi])
+        assert np.allclose(f2[s], want, rtol=1e-12)
+
+
+def test_group_of_one_bound_is_exact_score(oracle):
+    g = np.random.default_rng(10)
+    K = g.standard_normal((30, 12)).astype(np.float32)
+    q = g.standard_normal(12).astype(np.float32)
+    centre, radius = oracle.ball_index(K, np.arange(30, dtype=np.int32), 30, S=3)
+    assert np.all(radius == 0)
+    assert np.allclose(oracle.ball_bounds(q, centre, radius).sum(0), oracle.scores_f64(q, K), rtol=1e-12, atol=1e-12)
+
+
+def test_radii_for_stored_centres(oracle):
+    """Moving a centre off the mean must grow the radius by what the enclosure needs."""
+    K = np.array([[0.0, 0.0], [2.0, 0.0]], dtype=np.float32)
+    label = np.zeros(2, dtype=np.int32)
+    assert np.allclose(oracle.ball_radii_for_centres(K, label, np.array([[1.0, 0.0]]), 1), [[1.0]])
+    assert np.allclose(oracle.ball_radii_for_centres(K, label, np.array([[1.5, 0.0]]), 1), [[1.5]])
+
+
+# ------------------------------------------------------------------ TA filter (Alg. 4)
+def _ta_bruteforce(f, label, tau):
+    """Independent transcription for tiny inputs, written with python lists."""
+    S, G = f.shape
+    ranked = [sorted(range(G), key=lambda i: (-f[s, i], i)) for s in range(S)]
+    seen = [set() for _ in range(S)]
+    depth = 0
+    while depth < G:
+        U = 0.0
+        for s in range(S):
+            seen[s].add(ranked[s][depth])
+            U += f[s, ranked[s][depth]]
+        depth += 1
+        if U < tau:
+            break
+    n = label.shape[1]
+    return [any(label[s, j] in seen[s] for s in range(S)) for j in range(n)], depth
+
+
+def test_ta_filter_no_false_negatives_and_sandwich(oracle):
+    """K* is inside {j : sum_s f_{s,a(s,j)} >= tau}, which is inside the TA live set; the TA
+    live set matches a list-based transcription; the depth grows as tau falls."""
+    g = np.random.default_rng(11)
+    n, d, S, r = 64, 8, 2, 4
+    for trial in range(20):
+        K = (g.standard_normal((n, d)) * g.uniform(0.3, 3, size=d)).astype(np.float32)
+        q = g.standard_normal(d).astype(np.float32)
+        label = np.stack([(g.permutation(n) // r) for _ in range(S)]).astype(np.int32)
+        f = np.zeros((S, n // r))
+        for s in range(S):
+            lo, hi = oracle.subspace_range(d, S, s)
+            Ks = np.zeros_like(K)
+            Ks[:, lo:hi] = K[:, lo:hi]
+            c, rad = oracle.ball_index(Ks, label[s], n // r, S)
+            f[s] = oracle.ball_bounds(q, c, rad)[s]
+        score = oracle.scores_f64(q, K)
+        ub = sum(f[s, label[s]] for s in range(S))
+        assert np.all(ub >= score - 1e-9)
+        last_depth = 0
+        for tau in sorted(np.quantile(score, [0.999, 0.9, 0.5, 0.1]).tolist(), reverse=True):
+            alive, depth = oracle.ta_filter(f, label, tau)
+            want_alive, want_depth = _ta_bruteforce(f, label, tau)
+            assert alive.tolist() == want_alive and depth == want_depth
+            assert np.all(alive[score >= tau])                 # zero false negatives
+            assert np.all(alive[ub >= tau])                    # per-key sum rule is inside TA's set
+            assert depth >= last_depth
+            last_depth = depth
+        alive, depth = oracle.ta_filter(f, label, -np.inf)
+        assert alive.all() and depth == n // r
+        alive, depth = oracle.ta_filter(f, label, np.inf)
+        assert depth == 1
+
+
+def test_ta_filter_stops_only_when_strictly_below(oracle):
+    """The scan stops at the first depth with U < tau; U == tau must keep scanning, because an
+    unseen key may score exactly tau.  Integer bounds make the tie exact."""
+    f = np.array([[5.0, 3.0, 1.0]])
+    label = np.array([[0, 1, 2]], dtype=np.int32)
+    alive, depth = oracle.ta_filter(f, label, 5.0)
+    assert depth == 2 and alive.tolist() == [True, True, False]
+    alive, depth = oracle.ta_filter(f, label, 5.5)
+    assert depth == 1 and alive.tolist() == [True, False, False]
+    # two subspaces: U(1) = 4 + 6 = 10 == tau -> continue; U(2) = 2 + 1 = 3 < tau -> stop
+    f = np.array([[4.0, 2.0, 0.0], [1.0, 6.0, 0.0]])
+    label = np.array([[0, 1, 2], [0, 1, 2]], dtype=np.int32)
+    alive, depth = oracle.ta_filter(f, label, 10.0)
+    assert depth == 2 and alive.tolist() == [True, True, False]
+
+
+# ------------------------------------------------------------------ balanced tree (Alg. 2)
+def test_tree_on_a_line_is_sorted_chunks(oracle):
+    """One informative axis: recursive median splits reduce to cutting the sorted order into
+    consecutive runs, so with n = r 2^k every leaf is a run of r consecutive ranks."""
+    g = np.random.default_rng(12)
+    n, r = 64, 4
+    K = np.zeros((n, 3), dtype=np.float32)
+    K[:, 1] = g.permutation(n).astype(np.float32)
+    label, order, leaves = oracle.balanced_tree(K, r)
+    assert leaves == n // r
+    assert np.array_equal(K[order, 1], np.arange(n))
+    assert np.array_equal(label[order], np.arange(n) // r)
+
+
+def test_tree_partition_valid_any_n(oracle):
+    g = np.random.default_rng(13)
+    for n, r in [(1, 4), (3, 4), (24, 4), (37, 4), (100, 8), (31, 2), (16, 1)]:
+        K = g.standard_normal((n, 5)).astype(np.float32)
+        label, order, leaves = oracle.balanced_tree(K, r)
+        sizes = np.bincount(label, minlength=leaves)
+        assert sizes.sum() == n and sizes.min() >= 1 and sizes.max() <= r
+        assert sorted(order.tolist()) == list(range(n))
+        assert np.array_equal(np.unique(label), np.arange(leaves))   # ids are dense, no collisions
+        if n % r == 0 and (n // r) & (n // r - 1) == 0:
+            assert leaves == n // r and sizes.min() == r
+
+
+def test_tree_left_subtree_gets_floor_half(oracle):
+    """Three points, r = 2: the left child takes floor(3/2) = 1 point (the smallest), the right
+    child the other two."""
+    K = np.array([[2.0], [0.0], [1.0]], dtype=np.float32)
+    label, order, leaves = oracle.balanced_tree(K, r=2)
+    assert leaves == 2 and order.tolist() == [1, 2, 0] and label.tolist() == [1, 0, 1]
+
+
+def test_tree_first_split_uses_max_variance_axis(oracle):
+    g = np.random.default_rng(14)
+    n = 32
+    K = g.standard_normal((n, 4)).astype(np.float32)
+    K[:, 2] *= 50                                  # dominant axis
+    label, order, leaves = oracle.balanced_tree(K, r=16)
+    assert leaves == 2
+    med = np.sort(K[:, 2])
+    assert np.all(K[label == 0, 2] <= med[15]) and np.all(K[label == 1, 2] >= med[16])
+    # restricted to coordinates [0,2) the dominant axis is ignored
+    label2, _, _ = oracle.balanced_tree(K, r=16, lo=0, hi=2)
+    ax = int(np.argmax(K[:, :2].var(axis=0)))
+    med2 = np.sort(K[:, ax])
+    assert np.all(K[label2 == 0, ax] <= med2[15]) and np.all(K[label2 == 1, ax] >= med2[16])
+
+
+# ------------------------------------------------------------------ cost model (printed values)
+def test_cost_model_reproduces_printed_table(oracle):
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "table7_scan_speedup.txt")) if not l.startswith("#")]
+    assert len(rows) == 16
+    for _, _, scan, speed in rows:
+        # scan is printed to 0.1 %, speed-up to 0.01
+        lo = oracle.predicted_speedup(1, 4, (float(scan) + 0.05) / 100)
+        hi = oracle.predicted_speedup(1, 4, (float(scan) - 0.05) / 100)
+        assert lo - 0.005 <= float(speed) <= hi + 0.005
+
+
+# ------------------------------------------------------------------ workload generators
+def test_generators_are_seeded_and_bf16_exact():
+    a = W.make_cache(2, n=64)
+    b = W.make_cache(2, n=64)
+    assert np.array_equal(a.K, b.K) and np.array_equal(a.V, b.V)
+    assert np.array_equal(W.bf16_bits_to_f32(a.K_bits()).reshape(a.K.shape), a.K)
+    t = torch.tensor(np.random.default_rng(0).standard_normal(1000).astype(np.float32))
+    assert np.array_equal(W.round_to_bf16(t.numpy()), t.to(torch.bfloat16).float().numpy())
+    # four dominant channels per head
+    sc = a.channel_scale[0, 0]
+    assert (sc > 4 * np.median(sc)).sum() >= 3
+    q = W.drift_queries(3, 5, n_q_heads=2)
+    assert q.shape == (5, 1, 2, 128)
+    assert np.array_equal(W.round_to_bf16(q), q)
