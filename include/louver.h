@@ -1,0 +1,169 @@
+/*
+ * louver.h — C ABI of the MI355X (gfx950) library for the decode-time hot path of the Louver
+ * KV-cache index: build/append an index of bounding balls over the cached keys, answer the
+ * halfspace range query { k : <q,k> >= tau } per query head with no false negatives, and run
+ * softmax attention over only the retrieved keys and values.
+ *
+ * Conventions
+ *   - Every pointer named *_dev is DEVICE memory on the GPU that was current at lvr_create;
+ *     every pointer named *_host is HOST memory.  The caller owns all buffers it passes in;
+ *     the library owns the index arena (its own copy of K and V, centres, radii, work lists).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All device work
+ *     of a call is enqueued on that stream and the hot-path calls never synchronise with the
+ *     host; results are valid once the stream reaches the end of the call's work.
+ *     Calls that touch the same index must be ordered by the caller (same stream, or events).
+ *   - Return value: 0 on success, a negative lvr_error otherwise.  Nothing is thrown across
+ *     the ABI.  lvr_strerror gives a static string for every code.
+ *   - Layouts are row-major with the last index contiguous.  Head mapping for grouped-query
+ *     attention: query head h reads KV head h / (n_q_heads / n_kv_heads)  (Sec. 2, "KV Cache").
+ *   - tau is in RAW dot-product units (Problem 1, Sec. 2); the softmax scale sigma multiplies
+ *     the logits only inside the attention (Alg. 3 / Alg. 4, input "scale sigma").
+ *   - Positions reported in index lists are token positions in order of arrival
+ *     (0 .. n-1 for the keys given to lvr_build, then one more per appended token).
+ */
+#ifndef LOUVER_H_
+#define LOUVER_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lvr_index lvr_index; /* opaque, owned by the library */
+
+enum lvr_dtype { LVR_BF16 = 0, LVR_F32 = 1 };
+
+/* How keys are put into groups of r (Def. 2 of the appendix "Ablation on Index Design";
+ * the query result does not depend on the choice, only the pruning power does).
+ *   CONTIGUOUS: r consecutive token positions form a group (the appendix's best performer).
+ *   TREE:       recursive median split on the coordinate axis of largest variance (Alg. 2),
+ *               one tree over the full key shared by all subspaces; rows are stored regrouped. */
+enum lvr_grouping { LVR_GROUP_CONTIGUOUS = 0, LVR_GROUP_TREE = 1 };
+
+enum lvr_flags {
+    /* Keys not yet in the index (the buffer of Sec. 4.3 "Dynamic Updates") are retrieved
+     * whatever their score, as in Alg. 3 / Alg. 4's  K[L*] ∪ B.  Default (flag clear): they are
+     * scored exactly and thresholded like every other key, so the result is Problem 1's set. */
+    LVR_ATTEND_BUFFER_DENSE = 1u
+};
+
+enum lvr_error {
+    LVR_OK = 0,
+    LVR_E_INVALID = -1,     /* bad argument (NULL, negative size, unsupported shape)          */
+    LVR_E_UNSUPPORTED = -2, /* valid request this build has no kernel for                      */
+    LVR_E_CAPACITY = -3,    /* more keys than lvr_config.capacity                               */
+    LVR_E_OVERFLOW = -4,    /* a retrieved set was larger than the caller's `cap` (sticky)      */
+    LVR_E_HIP = -5,         /* a HIP runtime call failed; see lvr_last_hip_error                */
+    LVR_E_NOMEM = -6,
+    LVR_E_STATE = -7        /* call order wrong (e.g. query before build)                       */
+};
+
+typedef struct lvr_config {
+    int32_t batch;       /* independent sequences, each with its own cache                      */
+    int32_t n_q_heads;   /* H_q                                                                  */
+    int32_t n_kv_heads;  /* H_kv, divides H_q; G = H_q / H_kv in {1,2,4,8}                       */
+    int32_t head_dim;    /* d; this build supports 128                                           */
+    int32_t kv_dtype;    /* lvr_dtype of K, V and of the stored centres                          */
+    int32_t group_size;  /* r in {1,2,4,8,16}  (Def. 2)                                          */
+    int32_t n_subspaces; /* S in {1,2,4,8,16}: contiguous coordinate blocks of d/S (Sec. 4.1)    */
+    int32_t buffer_size; /* B: appended keys are indexed B at a time; multiple of 16 and of r    */
+    int32_t grouping;    /* lvr_grouping                                                         */
+    uint32_t flags;      /* lvr_flags                                                            */
+    int64_t capacity;    /* max keys per (sequence, KV head): the arena is sized once (App. "GPU Update") */
+    float scale;         /* sigma; 0 means 1/sqrt(head_dim)  (Sec. 2, "Attention")               */
+    int32_t attn_splits; /* P partial-softmax splits per query head (0 = default)                */
+} lvr_config;
+
+/* Counters of the most recent lvr_query / lvr_decode_step, summed over batch and heads. */
+typedef struct lvr_stats {
+    int64_t n_keys;           /* keys per (sequence, KV head) currently held                     */
+    int64_t n_indexed;        /* of which inside index groups (the rest is the buffer)           */
+    int64_t groups_scored;    /* balls tested                                                    */
+    int64_t groups_surviving; /* balls whose bound reached tau for at least one head of the group */
+    int64_t keys_scanned;     /* keys given the exact dot product (survivors * r + buffer)       */
+    int64_t keys_emitted;     /* sum of retrieved-set sizes                                      */
+    int64_t bytes_index;      /* centre + radius bytes read                                      */
+    int64_t bytes_keys;       /* candidate key bytes read by the exact filter                    */
+    int64_t bytes_attention;  /* K and V bytes gathered by the sparse attention                  */
+    int32_t overflow;         /* 1 if some retrieved set exceeded cap since the last call here   */
+    int32_t reserved;
+} lvr_stats;
+
+/* Allocate an index (arena for `capacity` keys per sequence and KV head, plus work space) on
+ * the current device.  *out is set only on success. */
+int lvr_create(const lvr_config *cfg_host, lvr_index **out);
+int lvr_destroy(lvr_index *ix);
+
+/* Device bytes lvr_create would allocate for this configuration (0 if it is invalid). */
+size_t lvr_arena_bytes(const lvr_config *cfg_host);
+
+/* Index construction (Sec. 4.1, Alg. 1; grouping per lvr_config.grouping; Eq. (1) balls).
+ * K_dev, V_dev: [batch][n_kv_heads][n][head_dim] of kv_dtype, addressed with ELEMENT strides
+ * k_strides_host / v_strides_host = {batch, kv head, token}; the head_dim axis is contiguous.
+ * Copies K and V into the arena, forms floor(n/r) groups; a tail of n mod r keys waits in the
+ * buffer and is scanned exactly.  Discards any earlier content.  n <= capacity. */
+int lvr_build(lvr_index *ix, const void *K_dev, const void *V_dev, int64_t n,
+              const int64_t k_strides_host[3], const int64_t v_strides_host[3], void *stream);
+
+/* Dynamic update (Sec. 4.3; App. "GPU Update", single-stream form): m new tokens per
+ * (sequence, KV head), k_new_dev / v_new_dev: [batch][n_kv_heads][m][head_dim] contiguous.
+ * New keys join the buffer; whenever the buffer holds B keys they are grouped and their
+ * balls appended to the index. */
+int lvr_append(lvr_index *ix, const void *k_new_dev, const void *v_new_dev, int64_t m, void *stream);
+
+/* Range query (Problem 1; Sec. 4.2): bound test of every ball against the halfspace
+ * (Eq. (2), summed over subspaces as in "Query 2"), then the exact dot product on the keys
+ * of surviving groups and on the buffer.
+ *   q_dev   [batch][n_q_heads][head_dim] fp32
+ *   tau_dev [batch][n_q_heads] fp32, -INFINITY allowed (retrieves everything)
+ *   out_idx_dev   [batch][n_q_heads][cap] int32 positions, order within a head unspecified
+ *   out_count_dev [batch][n_q_heads] int32, the TRUE set size even when it exceeds cap
+ * A key is emitted iff its fp32 score >= tau - 0.5e-4*|tau| (the comparison leans towards
+ * inclusion so that rounding-order differences never lose a key).  If a set exceeds cap the
+ * list is truncated and a sticky overflow flag is raised (reported by lvr_get_stats). */
+int lvr_query(lvr_index *ix, const float *q_dev, const float *tau_dev, int32_t *out_idx_dev,
+              int32_t *out_count_dev, int64_t cap, void *stream);
+
+/* Attention over given index lists (Sec. 2 "Sparse Attention"; App. "GPU Sparse Attention
+ * Kernel": P splits with partial (m, l, o), then a combine pass).  Softmax is normalised over
+ * the listed keys only.  idx_dev / count_dev as produced by lvr_query (count is clamped to
+ * cap; positions outside [0, n) are skipped).  out_dev [batch][n_q_heads][head_dim] fp32;
+ * an empty list gives zeros. */
+int lvr_sparse_attention(lvr_index *ix, const float *q_dev, const int32_t *idx_dev,
+                         const int32_t *count_dev, int64_t cap, float *out_dev, void *stream);
+
+/* lvr_query followed by lvr_sparse_attention on its result, in one call. */
+int lvr_decode_step(lvr_index *ix, const float *q_dev, const float *tau_dev, float *out_dev,
+                    int32_t *out_idx_dev, int32_t *out_count_dev, int64_t cap, void *stream);
+
+/* Dense attention over all held keys (Sec. 2 "Attention"): the baseline the sparse path is
+ * measured against, on the same arena. */
+int lvr_dense_attention(lvr_index *ix, const float *q_dev, float *out_dev, void *stream);
+
+/* Synchronises the device, then reports counters of the last query and clears the overflow
+ * flag.  Returns LVR_E_OVERFLOW (with *out_host filled) if the flag was set. */
+int lvr_get_stats(lvr_index *ix, lvr_stats *out_host);
+
+/* Synchronises the device and copies the index to host memory for inspection (tests check the
+ * enclosure invariant on it).  Any pointer may be NULL to skip that part.
+ *   centres_host  [batch][n_kv_heads][n_groups][head_dim] of kv_dtype
+ *   radii_host    [batch][n_kv_heads][n_groups][n_subspaces] fp32
+ *   slot_pos_host [batch][n_kv_heads][n] int32: token position stored in arena row `slot`
+ *                 (group g owns rows g*r .. g*r+r-1; rows >= n_indexed are the buffer)
+ *   keys_host     [batch][n_kv_heads][n][head_dim] of kv_dtype, arena row order */
+int lvr_export_index(lvr_index *ix, void *centres_host, float *radii_host, int32_t *slot_pos_host,
+                     void *keys_host);
+
+/* n = keys held per (sequence, KV head); n_indexed = keys inside groups. */
+int lvr_length(const lvr_index *ix, int64_t *n_host, int64_t *n_indexed_host);
+
+const char *lvr_strerror(int code);
+/* hipError_t value of the most recent failing HIP call made by this library on this thread. */
+int lvr_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOUVER_H_ */

@@ -1,0 +1,207 @@
+"""ctypes binding of liblouver: one Python function per C entry point, same names.
+
+Only argument marshalling happens here (tensor -> device pointer, strides, stream handle);
+every step of the path runs in the library's kernels.  There is no CPU fallback: if the
+library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+from .build import LIB_PATH
+
+LVR_BF16, LVR_F32 = 0, 1
+LVR_GROUP_CONTIGUOUS, LVR_GROUP_TREE = 0, 1
+LVR_ATTEND_BUFFER_DENSE = 1
+LVR_OK, LVR_E_INVALID, LVR_E_UNSUPPORTED, LVR_E_CAPACITY = 0, -1, -2, -3
+LVR_E_OVERFLOW, LVR_E_HIP, LVR_E_NOMEM, LVR_E_STATE = -4, -5, -6, -7
+
+
+class lvr_config(C.Structure):
+    _fields_ = [
+        ("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+        ("kv_dtype", C.c_int32), ("group_size", C.c_int32), ("n_subspaces", C.c_int32),
+        ("buffer_size", C.c_int32), ("grouping", C.c_int32), ("flags", C.c_uint32),
+        ("capacity", C.c_int64), ("scale", C.c_float), ("attn_splits", C.c_int32),
+    ]
+
+
+class lvr_stats(C.Structure):
+    _fields_ = [
+        ("n_keys", C.c_int64), ("n_indexed", C.c_int64), ("groups_scored", C.c_int64),
+        ("groups_surviving", C.c_int64), ("keys_scanned", C.c_int64), ("keys_emitted", C.c_int64),
+        ("bytes_index", C.c_int64), ("bytes_keys", C.c_int64), ("bytes_attention", C.c_int64),
+        ("overflow", C.c_int32), ("reserved", C.c_int32),
+    ]
+
+    def as_dict(self):
+        return {k: int(getattr(self, k)) for k, _ in self._fields_ if k != "reserved"}
+
+
+EXPORTS = [
+    "lvr_create", "lvr_destroy", "lvr_arena_bytes", "lvr_build", "lvr_append", "lvr_query",
+    "lvr_sparse_attention", "lvr_decode_step", "lvr_dense_attention", "lvr_get_stats",
+    "lvr_export_index", "lvr_length", "lvr_strerror", "lvr_last_hip_error",
+]
+
+_lib = None
+
+
+class LouverError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = lib().lvr_strerror(code).decode()
+        if code == LVR_E_HIP:
+            msg += f" (hipError {lib().lvr_last_hip_error()})"
+        super().__init__(f"{where}: {msg} [{code}]")
+
+
+def lib():
+    """The loaded shared library.  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it first (python -m paper_2605_06763_amd.build "
+                           "or __graft_entry__.build()); there is no fallback path")
+    L = C.CDLL(LIB_PATH)
+    vp, i64 = C.c_void_p, C.c_int64
+    L.lvr_create.argtypes = [C.POINTER(lvr_config), C.POINTER(vp)]
+    L.lvr_destroy.argtypes = [vp]
+    L.lvr_arena_bytes.argtypes = [C.POINTER(lvr_config)]
+    L.lvr_arena_bytes.restype = C.c_size_t
+    L.lvr_build.argtypes = [vp, vp, vp, i64, C.POINTER(i64), C.POINTER(i64), vp]
+    L.lvr_append.argtypes = [vp, vp, vp, i64, vp]
+    L.lvr_query.argtypes = [vp, vp, vp, vp, vp, i64, vp]
+    L.lvr_sparse_attention.argtypes = [vp, vp, vp, vp, i64, vp, vp]
+    L.lvr_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, i64, vp]
+    L.lvr_dense_attention.argtypes = [vp, vp, vp, vp]
+    L.lvr_get_stats.argtypes = [vp, C.POINTER(lvr_stats)]
+    L.lvr_export_index.argtypes = [vp, vp, vp, vp, vp]
+    L.lvr_length.argtypes = [vp, C.POINTER(i64), C.POINTER(i64)]
+    L.lvr_strerror.argtypes = [C.c_int]
+    L.lvr_strerror.restype = C.c_char_p
+    L.lvr_last_hip_error.restype = C.c_int
+    _lib = L
+    return L
+
+
+def _check(code: int, where: str):
+    if code != LVR_OK:
+        raise LouverError(code, where)
+
+
+def _stream(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _dev(t: torch.Tensor, dtype=None, name="tensor"):
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return C.c_void_p(t.data_ptr())
+
+
+def make_config(*, batch, n_q_heads, n_kv_heads, head_dim=128, kv_dtype=LVR_BF16, group_size=4,
+                n_subspaces=4, buffer_size=256, grouping=LVR_GROUP_CONTIGUOUS, flags=0, capacity,
+                scale=0.0, attn_splits=0) -> lvr_config:
+    return lvr_config(batch, n_q_heads, n_kv_heads, head_dim, kv_dtype, group_size, n_subspaces,
+                      buffer_size, grouping, flags, capacity, scale, attn_splits)
+
+
+def lvr_arena_bytes(cfg: lvr_config) -> int:
+    return int(lib().lvr_arena_bytes(C.byref(cfg)))
+
+
+def lvr_create(cfg: lvr_config) -> C.c_void_p:
+    h = C.c_void_p()
+    _check(lib().lvr_create(C.byref(cfg), C.byref(h)), "lvr_create")
+    return h
+
+
+def lvr_destroy(h) -> None:
+    _check(lib().lvr_destroy(h), "lvr_destroy")
+
+
+def lvr_build(h, K: torch.Tensor, V: torch.Tensor, stream=None) -> None:
+    """K, V: device tensors [batch][n_kv_heads][n][head_dim] (bf16 or fp32), last axis contiguous."""
+    if K.dim() != 4 or V.shape != K.shape or (K.numel() > 0 and (K.stride(3) != 1 or V.stride(3) != 1)):
+        raise ValueError("K and V must be [batch][n_kv_heads][n][head_dim] with a contiguous last axis")
+    if not (K.is_cuda and V.is_cuda):
+        raise ValueError("K and V must be device tensors")
+    ks = (C.c_int64 * 3)(*K.stride()[:3])
+    vs = (C.c_int64 * 3)(*V.stride()[:3])
+    _check(lib().lvr_build(h, C.c_void_p(K.data_ptr()), C.c_void_p(V.data_ptr()), K.shape[2], ks, vs,
+                           _stream(stream)), "lvr_build")
+
+
+def lvr_append(h, k_new: torch.Tensor, v_new: torch.Tensor, stream=None) -> None:
+    """k_new, v_new: contiguous device tensors [batch][n_kv_heads][m][head_dim]."""
+    _check(lib().lvr_append(h, _dev(k_new, name="k_new"), _dev(v_new, name="v_new"), k_new.shape[2],
+                            _stream(stream)), "lvr_append")
+
+
+def lvr_query(h, q, tau, out_idx, out_count, stream=None) -> None:
+    cap = out_idx.shape[-1]
+    _check(lib().lvr_query(h, _dev(q, torch.float32, "q"), _dev(tau, torch.float32, "tau"),
+                           _dev(out_idx, torch.int32, "out_idx"), _dev(out_count, torch.int32, "out_count"),
+                           cap, _stream(stream)), "lvr_query")
+
+
+def lvr_sparse_attention(h, q, idx, count, out, stream=None) -> None:
+    cap = idx.shape[-1]
+    _check(lib().lvr_sparse_attention(h, _dev(q, torch.float32, "q"), _dev(idx, torch.int32, "idx"),
+                                      _dev(count, torch.int32, "count"), cap, _dev(out, torch.float32, "out"),
+                                      _stream(stream)), "lvr_sparse_attention")
+
+
+def lvr_decode_step(h, q, tau, out, out_idx, out_count, stream=None) -> None:
+    cap = out_idx.shape[-1]
+    _check(lib().lvr_decode_step(h, _dev(q, torch.float32, "q"), _dev(tau, torch.float32, "tau"),
+                                 _dev(out, torch.float32, "out"), _dev(out_idx, torch.int32, "out_idx"),
+                                 _dev(out_count, torch.int32, "out_count"), cap, _stream(stream)),
+           "lvr_decode_step")
+
+
+def lvr_dense_attention(h, q, out, stream=None) -> None:
+    _check(lib().lvr_dense_attention(h, _dev(q, torch.float32, "q"), _dev(out, torch.float32, "out"),
+                                     _stream(stream)), "lvr_dense_attention")
+
+
+def lvr_get_stats(h, raise_on_overflow: bool = True) -> dict:
+    st = lvr_stats()
+    rc = lib().lvr_get_stats(h, C.byref(st))
+    if rc == LVR_E_OVERFLOW and not raise_on_overflow:
+        return st.as_dict()
+    _check(rc, "lvr_get_stats")
+    return st.as_dict()
+
+
+def lvr_length(h):
+    n, ni = C.c_int64(), C.c_int64()
+    _check(lib().lvr_length(h, C.byref(n), C.byref(ni)), "lvr_length")
+    return n.value, ni.value
+
+
+def lvr_export_index(h, cfg: lvr_config):
+    """Host copies (numpy) of centres [b][h][groups][d], radii [b][h][groups][S],
+    slot_pos [b][h][n], keys [b][h][n][d].  bf16 data comes back as uint16 bit patterns."""
+    import numpy as np
+    n, ni = lvr_length(h)
+    ng = ni // cfg.group_size
+    dt = np.uint16 if cfg.kv_dtype == LVR_BF16 else np.float32
+    centres = np.zeros((cfg.batch, cfg.n_kv_heads, ng, cfg.head_dim), dtype=dt)
+    radii = np.zeros((cfg.batch, cfg.n_kv_heads, ng, cfg.n_subspaces), dtype=np.float32)
+    slot_pos = np.zeros((cfg.batch, cfg.n_kv_heads, n), dtype=np.int32)
+    keys = np.zeros((cfg.batch, cfg.n_kv_heads, n, cfg.head_dim), dtype=dt)
+    _check(lib().lvr_export_index(h, centres.ctypes.data_as(C.c_void_p), radii.ctypes.data_as(C.c_void_p),
+                                  slot_pos.ctypes.data_as(C.c_void_p), keys.ctypes.data_as(C.c_void_p)),
+           "lvr_export_index")
+    return centres, radii, slot_pos, keys

@@ -1,0 +1,321 @@
+// C ABI of liblouver: argument checking, arena ownership, and the order in which the kernels
+// of one call are enqueued.  No kernel lives here.
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+
+#include "lvr_internal.h"
+
+hipError_t lvr_launch_iota_rows(lvr_index *ix, int64_t row0, int64_t rows, hipStream_t st);
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+inline int hip_fail(hipError_t e) {
+    g_last_hip_error = (int)e;
+    return LVR_E_HIP;
+}
+
+#define LVR_HIP(expr)                                   \
+    do {                                                \
+        hipError_t e__ = (expr);                        \
+        if (e__ != hipSuccess) return hip_fail(e__);    \
+    } while (0)
+
+inline bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
+
+int check_config(const lvr_config *c) {
+    if (!c) return LVR_E_INVALID;
+    if (c->batch <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->capacity <= 0) return LVR_E_INVALID;
+    if (c->n_q_heads % c->n_kv_heads != 0) return LVR_E_INVALID;
+    if (c->kv_dtype != LVR_BF16 && c->kv_dtype != LVR_F32) return LVR_E_INVALID;
+    if (c->grouping != LVR_GROUP_CONTIGUOUS && c->grouping != LVR_GROUP_TREE) return LVR_E_INVALID;
+    if (c->scale < 0.f || c->attn_splits < 0) return LVR_E_INVALID;
+    if (c->head_dim != LVR_D) return LVR_E_UNSUPPORTED;
+    const int G = c->n_q_heads / c->n_kv_heads;
+    if (!(G == 1 || G == 2 || G == 4 || G == 8)) return LVR_E_UNSUPPORTED;
+    if (!is_pow2(c->group_size) || c->group_size > 16) return LVR_E_UNSUPPORTED;
+    if (!is_pow2(c->n_subspaces) || c->n_subspaces > 16) return LVR_E_UNSUPPORTED;
+    if (c->buffer_size <= 0 || c->buffer_size % 16 != 0 || c->buffer_size % c->group_size != 0) return LVR_E_INVALID;
+    if (c->attn_splits > 256) return LVR_E_INVALID;
+    if (c->capacity > (int64_t)1 << 30) return LVR_E_UNSUPPORTED;   // positions are int32
+    if (c->grouping == LVR_GROUP_TREE) return LVR_E_UNSUPPORTED;     // not built yet
+    return LVR_OK;
+}
+
+struct Sizes {
+    int64_t cap_rows, max_groups;
+    int P, P_dense, Pmax;
+    size_t kv, centres, radii, list, counters, part_ml, part_o, total;
+};
+
+Sizes sizes_of(const lvr_config *c) {
+    Sizes s;
+    const size_t elt = c->kv_dtype == LVR_BF16 ? 2 : 4;
+    const int64_t n_bh = (int64_t)c->batch * c->n_kv_heads, n_bhq = (int64_t)c->batch * c->n_q_heads;
+    s.cap_rows = (c->capacity + 63) / 64 * 64;
+    s.max_groups = s.cap_rows / c->group_size;
+    s.P = c->attn_splits > 0 ? c->attn_splits : 16;
+    int64_t pd = 2048 / n_bh;
+    s.P_dense = (int)(pd < 4 ? 4 : (pd > 256 ? 256 : pd));
+    s.Pmax = s.P > s.P_dense ? s.P : s.P_dense;
+    auto al = [](size_t b) { return (b + 255) / 256 * 256; };
+    s.kv = al((size_t)n_bh * s.cap_rows * LVR_D * elt);
+    s.centres = al((size_t)n_bh * s.max_groups * LVR_D * elt);
+    s.radii = al((size_t)n_bh * s.max_groups * c->n_subspaces * sizeof(float));
+    s.list = al((size_t)n_bh * s.max_groups * sizeof(int32_t));
+    s.counters = al((size_t)(2 * n_bh + 1) * sizeof(int32_t));
+    s.part_ml = al((size_t)n_bhq * s.Pmax * 2 * sizeof(float));
+    s.part_o = al((size_t)n_bhq * s.Pmax * LVR_D * sizeof(float));
+    s.total = 2 * s.kv + s.centres + s.radii + s.list + s.counters + s.part_ml + s.part_o;
+    return s;
+}
+
+void free_all(lvr_index *ix) {
+    void *ptrs[] = {ix->K, ix->V, ix->centres, ix->radii, ix->slot_pos, ix->pos_slot,
+                    ix->surv_list, ix->counters, ix->part_ml, ix->part_o};
+    for (void *p : ptrs)
+        if (p) (void)hipFree(p);
+}
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+extern "C" {
+
+size_t lvr_arena_bytes(const lvr_config *cfg) {
+    if (check_config(cfg) != LVR_OK) return 0;
+    return sizes_of(cfg).total;
+}
+
+int lvr_create(const lvr_config *cfg, lvr_index **out) {
+    if (!out) return LVR_E_INVALID;
+    int rc = check_config(cfg);
+    if (rc != LVR_OK) return rc;
+    lvr_index *ix = new (std::nothrow) lvr_index();
+    if (!ix) return LVR_E_NOMEM;
+    memset(ix, 0, sizeof(*ix));
+    ix->cfg = *cfg;
+    const Sizes s = sizes_of(cfg);
+    ix->G = cfg->n_q_heads / cfg->n_kv_heads;
+    ix->cap_rows = s.cap_rows;
+    ix->max_groups = s.max_groups;
+    ix->P = s.P;
+    ix->P_dense = s.P_dense;
+    ix->elt = cfg->kv_dtype == LVR_BF16 ? 2 : 4;
+    ix->sigma = cfg->scale > 0.f ? cfg->scale : 1.0f / sqrtf((float)cfg->head_dim);
+    hipError_t e = hipGetDevice(&ix->device);
+    struct { void **p; size_t bytes; } allocs[] = {
+        {&ix->K, s.kv}, {&ix->V, s.kv}, {&ix->centres, s.centres}, {(void **)&ix->radii, s.radii},
+        {(void **)&ix->surv_list, s.list}, {(void **)&ix->counters, s.counters},
+        {(void **)&ix->part_ml, s.part_ml}, {(void **)&ix->part_o, s.part_o}};
+    for (auto &a : allocs) {
+        if (e != hipSuccess) break;
+        e = hipMalloc(a.p, a.bytes);
+    }
+    if (e == hipSuccess) e = hipMemset(ix->counters, 0, s.counters);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        free_all(ix);
+        delete ix;
+        if (e == hipErrorOutOfMemory) {
+            g_last_hip_error = (int)e;
+            return LVR_E_NOMEM;
+        }
+        return hip_fail(e);
+    }
+    *out = ix;
+    return LVR_OK;
+}
+
+int lvr_destroy(lvr_index *ix) {
+    if (!ix) return LVR_E_INVALID;
+    (void)hipDeviceSynchronize();
+    free_all(ix);
+    delete ix;
+    return LVR_OK;
+}
+
+int lvr_build(lvr_index *ix, const void *K, const void *V, int64_t n, const int64_t ks[3], const int64_t vs[3],
+              void *stream) {
+    if (!ix || n < 0 || (n > 0 && (!K || !V || !ks || !vs))) return LVR_E_INVALID;
+    if (n > ix->cfg.capacity) return LVR_E_CAPACITY;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int64_t per16 = 16 / (int64_t)ix->elt;
+    if (n > 0) {
+        if (!aligned16(K) || !aligned16(V)) return LVR_E_INVALID;
+        for (int i = 0; i < 3; ++i)
+            if (ks[i] < 0 || vs[i] < 0 || ks[i] % per16 || vs[i] % per16) return LVR_E_INVALID;
+        if (ks[2] < LVR_D || vs[2] < LVR_D) return LVR_E_INVALID;
+    }
+    ix->built = 0;
+    ix->n_total = 0;
+    ix->n_indexed = 0;
+    if (n > 0) {
+        LVR_HIP(lvr_launch_copy_rows(ix, K, ks, ix->K, 0, n, st));
+        LVR_HIP(lvr_launch_copy_rows(ix, V, vs, ix->V, 0, n, st));
+    }
+    const int r = ix->cfg.group_size;
+    const int64_t n_groups = n / r;
+    LVR_HIP(lvr_launch_build_groups(ix, 0, n_groups, st));
+    ix->n_total = n;
+    ix->n_indexed = n_groups * r;
+    ix->built = 1;
+    return LVR_OK;
+}
+
+int lvr_append(lvr_index *ix, const void *k_new, const void *v_new, int64_t m, void *stream) {
+    if (!ix || m < 0 || (m > 0 && (!k_new || !v_new))) return LVR_E_INVALID;
+    if (!ix->built) return LVR_E_STATE;
+    if (m == 0) return LVR_OK;
+    if (ix->n_total + m > ix->cfg.capacity) return LVR_E_CAPACITY;
+    if (!aligned16(k_new) || !aligned16(v_new)) return LVR_E_INVALID;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int64_t strides[3] = {(int64_t)ix->cfg.n_kv_heads * m * LVR_D, m * LVR_D, LVR_D};
+    LVR_HIP(lvr_launch_copy_rows(ix, k_new, strides, ix->K, ix->n_total, m, st));
+    LVR_HIP(lvr_launch_copy_rows(ix, v_new, strides, ix->V, ix->n_total, m, st));
+    ix->n_total += m;
+    // every full buffer of B keys becomes B/r new groups at the tail of the index
+    const int64_t B = ix->cfg.buffer_size;
+    const int r = ix->cfg.group_size;
+    const int64_t full = (ix->n_total - ix->n_indexed) / B;
+    if (full > 0) {
+        const int64_t g0 = ix->n_indexed / r, g1 = g0 + full * (B / r);
+        LVR_HIP(lvr_launch_build_groups(ix, g0, g1, st));
+        ix->n_indexed += full * B;
+    }
+    return LVR_OK;
+}
+
+int lvr_query(lvr_index *ix, const float *q, const float *tau, int32_t *out_idx, int32_t *out_count, int64_t cap,
+              void *stream) {
+    if (!ix || !q || !tau || !out_count || cap < 0 || (cap > 0 && !out_idx)) return LVR_E_INVALID;
+    if (!ix->built) return LVR_E_STATE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    LVR_HIP(lvr_launch_reset(ix, out_count, st));
+    LVR_HIP(lvr_launch_prune(ix, q, tau, st));
+    LVR_HIP(lvr_launch_filter(ix, q, tau, out_idx, out_count, cap, st));
+    ix->last_buffer_rows = ix->n_total - ix->n_indexed;
+    return LVR_OK;
+}
+
+int lvr_sparse_attention(lvr_index *ix, const float *q, const int32_t *idx, const int32_t *count, int64_t cap,
+                         float *out, void *stream) {
+    if (!ix || !q || !count || !out || cap < 0 || (cap > 0 && !idx)) return LVR_E_INVALID;
+    if (!ix->built) return LVR_E_STATE;
+    LVR_HIP(lvr_launch_sparse_attention(ix, q, idx, count, cap, out, static_cast<hipStream_t>(stream)));
+    return LVR_OK;
+}
+
+int lvr_decode_step(lvr_index *ix, const float *q, const float *tau, float *out, int32_t *out_idx, int32_t *out_count,
+                    int64_t cap, void *stream) {
+    int rc = lvr_query(ix, q, tau, out_idx, out_count, cap, stream);
+    if (rc != LVR_OK) return rc;
+    return lvr_sparse_attention(ix, q, out_idx, out_count, cap, out, stream);
+}
+
+int lvr_dense_attention(lvr_index *ix, const float *q, float *out, void *stream) {
+    if (!ix || !q || !out) return LVR_E_INVALID;
+    if (!ix->built) return LVR_E_STATE;
+    LVR_HIP(lvr_launch_dense_attention(ix, q, out, static_cast<hipStream_t>(stream)));
+    return LVR_OK;
+}
+
+int lvr_get_stats(lvr_index *ix, lvr_stats *out) {
+    if (!ix || !out) return LVR_E_INVALID;
+    LVR_HIP(hipDeviceSynchronize());
+    const int n_bh = lvr_n_bh(ix);
+    int32_t *host = static_cast<int32_t *>(malloc(sizeof(int32_t) * (2 * n_bh + 1)));
+    if (!host) return LVR_E_NOMEM;
+    hipError_t e = hipMemcpy(host, ix->counters, sizeof(int32_t) * (2 * n_bh + 1), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) {
+        free(host);
+        return hip_fail(e);
+    }
+    memset(out, 0, sizeof(*out));
+    const int r = ix->cfg.group_size;
+    int64_t surv = 0, emitted = 0;
+    for (int i = 0; i < n_bh; ++i) {
+        surv += host[i];
+        emitted += host[n_bh + i];
+    }
+    const int overflow = host[2 * n_bh];
+    free(host);
+    const int64_t row_bytes = (int64_t)LVR_D * (int64_t)ix->elt;
+    out->n_keys = ix->n_total;
+    out->n_indexed = ix->n_indexed;
+    out->groups_scored = (ix->n_indexed / r) * n_bh;
+    out->groups_surviving = surv;
+    out->keys_scanned = surv * r + ix->last_buffer_rows * n_bh;
+    out->keys_emitted = emitted;
+    out->bytes_index = out->groups_scored * (row_bytes + (int64_t)ix->cfg.n_subspaces * 4);
+    out->bytes_keys = out->keys_scanned * row_bytes;
+    out->bytes_attention = emitted * 2 * row_bytes;
+    out->overflow = overflow;
+    if (overflow) {
+        LVR_HIP(hipMemset(lvr_overflow_flag(ix), 0, sizeof(int32_t)));
+        return LVR_E_OVERFLOW;
+    }
+    return LVR_OK;
+}
+
+int lvr_export_index(lvr_index *ix, void *centres, float *radii, int32_t *slot_pos, void *keys) {
+    if (!ix) return LVR_E_INVALID;
+    if (!ix->built) return LVR_E_STATE;
+    LVR_HIP(hipDeviceSynchronize());
+    const int n_bh = lvr_n_bh(ix);
+    const int r = ix->cfg.group_size, S = ix->cfg.n_subspaces;
+    const int64_t ng = ix->n_indexed / r, n = ix->n_total;
+    const size_t row_bytes = LVR_D * ix->elt;
+    for (int bh = 0; bh < n_bh; ++bh) {
+        if (centres && ng > 0)
+            LVR_HIP(hipMemcpy(static_cast<char *>(centres) + (size_t)bh * ng * row_bytes,
+                              static_cast<char *>(ix->centres) + (size_t)bh * ix->max_groups * row_bytes,
+                              (size_t)ng * row_bytes, hipMemcpyDeviceToHost));
+        if (radii && ng > 0)
+            LVR_HIP(hipMemcpy(radii + (size_t)bh * ng * S, ix->radii + (size_t)bh * ix->max_groups * S,
+                              (size_t)ng * S * sizeof(float), hipMemcpyDeviceToHost));
+        if (keys && n > 0)
+            LVR_HIP(hipMemcpy(static_cast<char *>(keys) + (size_t)bh * n * row_bytes,
+                              static_cast<char *>(ix->K) + (size_t)bh * ix->cap_rows * row_bytes, (size_t)n * row_bytes,
+                              hipMemcpyDeviceToHost));
+        if (slot_pos && n > 0) {
+            if (ix->slot_pos) {
+                LVR_HIP(hipMemcpy(slot_pos + (size_t)bh * n, ix->slot_pos + (size_t)bh * ix->cap_rows,
+                                  (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost));
+            } else {
+                for (int64_t i = 0; i < n; ++i) slot_pos[(size_t)bh * n + i] = (int32_t)i;
+            }
+        }
+    }
+    return LVR_OK;
+}
+
+int lvr_length(const lvr_index *ix, int64_t *n, int64_t *n_indexed) {
+    if (!ix) return LVR_E_INVALID;
+    if (n) *n = ix->n_total;
+    if (n_indexed) *n_indexed = ix->n_indexed;
+    return LVR_OK;
+}
+
+const char *lvr_strerror(int code) {
+    switch (code) {
+        case LVR_OK: return "ok";
+        case LVR_E_INVALID: return "invalid argument";
+        case LVR_E_UNSUPPORTED: return "unsupported configuration";
+        case LVR_E_CAPACITY: return "index capacity exceeded";
+        case LVR_E_OVERFLOW: return "a retrieved set exceeded the output capacity (list truncated)";
+        case LVR_E_HIP: return "HIP runtime error";
+        case LVR_E_NOMEM: return "out of memory";
+        case LVR_E_STATE: return "call out of order (index not built)";
+        default: return "unknown error";
+    }
+}
+
+int lvr_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

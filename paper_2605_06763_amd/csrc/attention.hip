@@ -1,0 +1,270 @@
+// Attention kernels.
+//
+//  sparse_partial_kernel  attention restricted to a per-head index list (Sec. 2 "Sparse
+//                         Attention"; App. "GPU Sparse Attention Kernel"): the list is cut into
+//                         P splits, each wave gathers its K and V rows (256 B each for bf16),
+//                         keeps running softmax statistics (m, l) and an fp32 accumulator o.
+//  dense_partial_kernel   the dense baseline (Sec. 2 "Attention"): every held key, contiguous
+//                         streaming, the G query heads of a KV head served from one read.
+//  combine_kernel         merges the P partial triples (m_p, l_p, o_p) into the output.
+//
+// Logits are kept in base-2 units (q is pre-multiplied by sigma * log2 e) so the exponentials
+// are single exp2 instructions; the softmax is unchanged by the change of base.
+#include "lvr_internal.h"
+
+namespace {
+
+constexpr float LOG2E = 1.4426950408889634f;
+
+__device__ __forceinline__ float exp2_safe(float a, float b) {   // 2^(a-b) with (-inf) - (-inf) -> 0
+    return (a == -INFINITY) ? 0.f : exp2f(a - b);
+}
+
+template <typename KT>
+__global__ void __launch_bounds__(64)
+sparse_partial_kernel(const void *__restrict__ K, const void *__restrict__ V, const int32_t *__restrict__ pos_slot,
+                      const float *__restrict__ q, const int32_t *__restrict__ idx, const int32_t *__restrict__ count,
+                      int64_t cap, float *__restrict__ part_ml, float *__restrict__ part_o, int64_t cap_rows,
+                      int64_t n_total, int P, int n_q_heads, int n_kv_heads, int G, float qscale) {
+    const int64_t hq = blockIdx.y;
+    const int p = blockIdx.x;
+    const int b = (int)(hq / n_q_heads), h = (int)(hq % n_q_heads);
+    const int bh = b * n_kv_heads + h / G;
+    const int lane = threadIdx.x & 63, sub = lane >> 4, li = lane & 15;
+
+    int64_t cnt = count[hq];
+    if (cnt > cap) cnt = cap;
+    if (cnt < 0) cnt = 0;
+    const int64_t L = (((cnt + P - 1) / P) + 3) & ~(int64_t)3;
+    const int64_t start = (int64_t)p * L;
+    const int64_t end = (start + L < cnt) ? start + L : cnt;
+
+    float qv[8];
+    {
+        const float *qh = q + hq * LVR_D + li * 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qv[e] = qh[e] * qscale;
+    }
+    const char *Kb = static_cast<const char *>(K) + (int64_t)bh * cap_rows * LVR_D * sizeof(KT);
+    const char *Vb = static_cast<const char *>(V) + (int64_t)bh * cap_rows * LVR_D * sizeof(KT);
+    const int32_t *my_idx = idx + hq * cap;
+    const int32_t *pslot = pos_slot ? pos_slot + (int64_t)bh * cap_rows : nullptr;
+
+    float m = -INFINITY, l = 0.f, acc[8];
+    lvr_zero8(acc);
+    for (int64_t e0 = start; e0 < end; e0 += 4) {          // uniform trip count over the wave
+        const int64_t e = e0 + sub;
+        bool valid = e < end;
+        int64_t pos = valid ? (int64_t)my_idx[e] : 0;
+        valid = valid && pos >= 0 && pos < n_total;
+        if (!valid) pos = 0;
+        const int64_t slot = pslot ? (int64_t)pslot[pos] : pos;
+        float kx[8], vx[8];
+        lvr_load8<KT>(Kb, slot, li, kx);
+        lvr_load8<KT>(Vb, slot, li, vx);
+        float d = 0.f;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) d += qv[c] * kx[c];
+        float s = lvr_row16_sum(d);
+        s = valid ? s : -INFINITY;
+        const float m_new = fmaxf(m, s);
+        const float alpha = exp2_safe(m, m_new);
+        const float w = exp2_safe(s, m_new);
+        l = l * alpha + w;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[c] = acc[c] * alpha + w * vx[c];
+        m = m_new;
+    }
+    // merge the four quarter rows of the wave
+    float m_all = fmaxf(m, __shfl_xor(m, 16, 64));
+    m_all = fmaxf(m_all, __shfl_xor(m_all, 32, 64));
+    const float sc = exp2_safe(m, m_all);
+    l *= sc;
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+        float a = acc[c] * sc;
+        a += __shfl_xor(a, 16, 64);
+        a += __shfl_xor(a, 32, 64);
+        acc[c] = a;
+    }
+    if (sub == 0) {
+        float *o = part_o + (hq * P + p) * LVR_D + li * 8;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) o[c] = acc[c];
+        if (li == 0) {
+            part_ml[(hq * P + p) * 2] = m_all;
+            part_ml[(hq * P + p) * 2 + 1] = l;
+        }
+    }
+}
+
+__global__ void __launch_bounds__(128)
+combine_kernel(const float *__restrict__ part_ml, const float *__restrict__ part_o, float *__restrict__ out, int P) {
+    const int64_t hq = blockIdx.x;
+    const int c = threadIdx.x;
+    float M = -INFINITY;
+    for (int p = 0; p < P; ++p) M = fmaxf(M, part_ml[(hq * P + p) * 2]);
+    float num = 0.f, den = 0.f;
+    if (M != -INFINITY) {
+        for (int p = 0; p < P; ++p) {
+            const float w = exp2_safe(part_ml[(hq * P + p) * 2], M);
+            den += w * part_ml[(hq * P + p) * 2 + 1];
+            num += w * part_o[(hq * P + p) * LVR_D + c];
+        }
+    }
+    out[hq * LVR_D + c] = (den > 0.f) ? num / den : 0.f;
+}
+
+template <typename KT, int G>
+__global__ void __launch_bounds__(256)
+dense_partial_kernel(const void *__restrict__ K, const void *__restrict__ V, const float *__restrict__ q,
+                     float *__restrict__ part_ml, float *__restrict__ part_o, int64_t cap_rows, int64_t n_total,
+                     int P, int n_q_heads, int n_kv_heads, float qscale) {
+    __shared__ float sm_m[4][G], sm_l[4][G];
+    __shared__ float sm_o[4][G][LVR_D];
+    const int bh = blockIdx.y, p = blockIdx.x;
+    const int b = bh / n_kv_heads, kvh = bh % n_kv_heads;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int sub = lane >> 4, li = lane & 15;
+    const int64_t hq0 = (int64_t)b * n_q_heads + kvh * G;
+
+    const int64_t R = (((n_total + P - 1) / P) + 15) & ~(int64_t)15;
+    const int64_t start = (int64_t)p * R;
+    const int64_t end = (start + R < n_total) ? start + R : n_total;
+
+    float qv[G][8];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        const float *qh = q + (hq0 + h) * LVR_D + li * 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qv[h][e] = qh[e] * qscale;
+    }
+    const char *Kb = static_cast<const char *>(K) + (int64_t)bh * cap_rows * LVR_D * sizeof(KT);
+    const char *Vb = static_cast<const char *>(V) + (int64_t)bh * cap_rows * LVR_D * sizeof(KT);
+
+    float m[G], l[G], acc[G][8];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        m[h] = -INFINITY;
+        l[h] = 0.f;
+        lvr_zero8(acc[h]);
+    }
+    for (int64_t r0 = start + wave * 4; r0 < end; r0 += 16) {   // uniform over the wave
+        const int64_t row = r0 + sub;
+        const bool valid = row < end;
+        const int64_t rc = valid ? row : 0;
+        float kx[8], vx[8];
+        lvr_load8<KT>(Kb, rc, li, kx);
+        lvr_load8<KT>(Vb, rc, li, vx);
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            float d = 0.f;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) d += qv[h][c] * kx[c];
+            float s = lvr_row16_sum(d);
+            s = valid ? s : -INFINITY;
+            const float m_new = fmaxf(m[h], s);
+            const float alpha = exp2_safe(m[h], m_new);
+            const float w = exp2_safe(s, m_new);
+            l[h] = l[h] * alpha + w;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) acc[h][c] = acc[h][c] * alpha + w * vx[c];
+            m[h] = m_new;
+        }
+    }
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        float m_all = fmaxf(m[h], __shfl_xor(m[h], 16, 64));
+        m_all = fmaxf(m_all, __shfl_xor(m_all, 32, 64));
+        const float sc = exp2_safe(m[h], m_all);
+        float lh = l[h] * sc;
+        lh += __shfl_xor(lh, 16, 64);
+        lh += __shfl_xor(lh, 32, 64);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            float a = acc[h][c] * sc;
+            a += __shfl_xor(a, 16, 64);
+            a += __shfl_xor(a, 32, 64);
+            if (sub == 0) sm_o[wave][h][li * 8 + c] = a;
+        }
+        if (lane == 0) {
+            sm_m[wave][h] = m_all;
+            sm_l[wave][h] = lh;
+        }
+    }
+    __syncthreads();
+    // 256 threads merge the four waves: thread -> (head pair, channel)
+    for (int item = threadIdx.x; item < G * LVR_D; item += 256) {
+        const int h = item / LVR_D, c = item % LVR_D;
+        float M = fmaxf(fmaxf(sm_m[0][h], sm_m[1][h]), fmaxf(sm_m[2][h], sm_m[3][h]));
+        float o = 0.f, lt = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float sc = exp2_safe(sm_m[w][h], M);
+            o += sc * sm_o[w][h][c];
+            lt += sc * sm_l[w][h];
+        }
+        part_o[((hq0 + h) * P + p) * LVR_D + c] = o;
+        if (c == 0) {
+            part_ml[((hq0 + h) * P + p) * 2] = M;
+            part_ml[((hq0 + h) * P + p) * 2 + 1] = lt;
+        }
+    }
+}
+
+template <typename KT>
+hipError_t launch_dense_t(lvr_index *ix, const float *q, float *out, int P, hipStream_t st) {
+    dim3 grid((unsigned)P, (unsigned)lvr_n_bh(ix));
+    const float qscale = ix->sigma * LOG2E;
+#define LVR_DENSE_CASE(GG)                                                                                     \
+    case GG:                                                                                                   \
+        hipLaunchKernelGGL((dense_partial_kernel<KT, GG>), grid, dim3(256), 0, st, ix->K, ix->V, q, ix->part_ml, \
+                           ix->part_o, ix->cap_rows, ix->n_total, P, ix->cfg.n_q_heads, ix->cfg.n_kv_heads,    \
+                           qscale);                                                                            \
+        break;
+    switch (ix->G) {
+        LVR_DENSE_CASE(1)
+        LVR_DENSE_CASE(2)
+        LVR_DENSE_CASE(4)
+        LVR_DENSE_CASE(8)
+        default: return hipErrorInvalidValue;
+    }
+#undef LVR_DENSE_CASE
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t lvr_launch_sparse_attention(lvr_index *ix, const float *q, const int32_t *idx, const int32_t *count,
+                                       int64_t cap, float *out, hipStream_t st) {
+    const int n_bhq = ix->cfg.batch * ix->cfg.n_q_heads;
+    const int P = ix->P;
+    dim3 grid((unsigned)P, (unsigned)n_bhq);
+    const float qscale = ix->sigma * LOG2E;
+    if (ix->cfg.kv_dtype == LVR_BF16)
+        hipLaunchKernelGGL(sparse_partial_kernel<lvr_bf16_t>, grid, dim3(64), 0, st, ix->K, ix->V, ix->pos_slot, q, idx,
+                           count, cap, ix->part_ml, ix->part_o, ix->cap_rows, ix->n_total, P, ix->cfg.n_q_heads,
+                           ix->cfg.n_kv_heads, ix->G, qscale);
+    else
+        hipLaunchKernelGGL(sparse_partial_kernel<lvr_f32_t>, grid, dim3(64), 0, st, ix->K, ix->V, ix->pos_slot, q, idx,
+                           count, cap, ix->part_ml, ix->part_o, ix->cap_rows, ix->n_total, P, ix->cfg.n_q_heads,
+                           ix->cfg.n_kv_heads, ix->G, qscale);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)n_bhq), dim3(128), 0, st, ix->part_ml, ix->part_o, out, P);
+    return hipGetLastError();
+}
+
+hipError_t lvr_launch_dense_attention(lvr_index *ix, const float *q, float *out, hipStream_t st) {
+    const int n_bhq = ix->cfg.batch * ix->cfg.n_q_heads;
+    int64_t P = (ix->n_total + 63) / 64;
+    if (P > ix->P_dense) P = ix->P_dense;
+    if (P < 1) P = 1;
+    hipError_t e = ix->cfg.kv_dtype == LVR_BF16 ? launch_dense_t<lvr_bf16_t>(ix, q, out, (int)P, st)
+                                                : launch_dense_t<lvr_f32_t>(ix, q, out, (int)P, st);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)n_bhq), dim3(128), 0, st, ix->part_ml, ix->part_o, out, (int)P);
+    return hipGetLastError();
+}

@@ -1,0 +1,144 @@
+// Index construction kernels: copy K/V rows into the arena and compute, for every group of r
+// consecutive arena rows, the ball of Sec. 4.1 "Ball enclosing" / Eq. (1) in each of the S
+// coordinate blocks: centre = mean of the members, radius = largest member distance.
+//
+// Zero false negatives under rounding: the centre is stored in the cache's own format
+// (bf16 or fp32), the radius is measured against the centre AS STORED, in fp32, and then
+// widened to  rho * (1 + 2^-12) + 2^-12 * |centre_s|  (+1 ulp).  The widening exceeds every
+// fp32 rounding error of the bound <q,c> + sum_s rho_s |pi_s q| evaluated at query time
+// (at most ~(d+S) 2^-24 of the sum of term magnitudes), so a computed bound never falls
+// below the exact score of a member.
+#include <type_traits>
+
+#include "lvr_internal.h"
+
+namespace {
+
+// 16 bytes per thread, arbitrary source strides (in elements) for (batch, head, token).
+__global__ void copy_rows_kernel(const char *__restrict__ src, char *__restrict__ dst, int64_t sb, int64_t sh,
+                                 int64_t st, int n_kv_heads, int64_t cap_rows, int64_t dst_row0, int64_t rows,
+                                 int row_bytes, int elt) {
+    const int chunks = row_bytes / 16;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= rows * chunks) return;
+    int bh = blockIdx.y;
+    int b = bh / n_kv_heads, h = bh % n_kv_heads;
+    int64_t row = i / chunks;
+    int c = (int)(i % chunks);
+    const uint4 *s = reinterpret_cast<const uint4 *>(src + (b * sb + h * sh + row * st) * elt) + c;
+    uint4 *d = reinterpret_cast<uint4 *>(dst + ((int64_t)bh * cap_rows + dst_row0 + row) * row_bytes) + c;
+    *d = *s;
+}
+
+__device__ __forceinline__ float seg_sum(float v, int lanes_per_sub) {
+    for (int off = 1; off < lanes_per_sub; off <<= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+template <typename KT>
+__global__ void __launch_bounds__(256)
+build_groups_kernel(const void *__restrict__ K, void *__restrict__ centres, float *__restrict__ radii,
+                    int64_t cap_rows, int64_t max_groups, int64_t g0, int64_t g1, int r, int S) {
+    const int bh = blockIdx.y;
+    const int li = threadIdx.x & 15;
+    int64_t g = g0 + (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    const bool valid = g < g1;
+    if (!valid) g = g0;   // keep every lane busy so the shuffles below see defined data
+    const char *Kb = static_cast<const char *>(K) + (int64_t)bh * cap_rows * LVR_D * sizeof(KT);
+
+    float c[8];
+    lvr_zero8(c);
+    for (int m = 0; m < r; ++m) {          // members in ascending row order
+        float x[8];
+        lvr_load8<KT>(Kb, g * r + m, li, x);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) c[e] += x[e];
+    }
+    const float inv = 1.0f / (float)r;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) c[e] *= inv;
+
+    char *Cb = static_cast<char *>(centres) + ((int64_t)bh * max_groups + g) * LVR_D * sizeof(KT);
+    if constexpr (std::is_same<KT, lvr_bf16_t>::value) {
+        uint32_t b[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            b[e] = lvr_f32_to_bf16_bits(c[e]);
+            c[e] = __uint_as_float(b[e] << 16);   // from here on: the centre as stored
+        }
+        if (valid)
+            reinterpret_cast<uint4 *>(Cb)[li] =
+                make_uint4(b[0] | (b[1] << 16), b[2] | (b[3] << 16), b[4] | (b[5] << 16), b[6] | (b[7] << 16));
+    } else {
+        if (valid) {
+            reinterpret_cast<float4 *>(Cb)[2 * li] = make_float4(c[0], c[1], c[2], c[3]);
+            reinterpret_cast<float4 *>(Cb)[2 * li + 1] = make_float4(c[4], c[5], c[6], c[7]);
+        }
+    }
+
+    const int lanes_per_sub = 16 / S;
+    float cn2 = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) cn2 += c[e] * c[e];
+    cn2 = seg_sum(cn2, lanes_per_sub);
+
+    float max_d2 = 0.f;
+    for (int m = 0; m < r; ++m) {
+        float x[8];
+        lvr_load8<KT>(Kb, g * r + m, li, x);
+        float d2 = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float t = x[e] - c[e];
+            d2 += t * t;
+        }
+        d2 = seg_sum(d2, lanes_per_sub);
+        max_d2 = fmaxf(max_d2, d2);
+    }
+    float rho = sqrtf(max_d2) * (1.0f + 0x1p-12f) + sqrtf(cn2) * 0x1p-12f;
+    rho = __uint_as_float(__float_as_uint(rho) + 1u);    // one ulp up (rho >= 0)
+    if (valid && (li % lanes_per_sub) == 0) radii[((int64_t)bh * max_groups + g) * S + li / lanes_per_sub] = rho;
+}
+
+// Identity position map for rows [row0, row0+rows) (used when rows are stored in arrival order
+// but a map is kept, i.e. the buffer of a regrouped arena).
+__global__ void iota_rows_kernel(int32_t *slot_pos, int32_t *pos_slot, int64_t cap_rows, int64_t row0, int64_t rows) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= rows) return;
+    int64_t o = (int64_t)blockIdx.y * cap_rows + row0 + i;
+    slot_pos[o] = (int32_t)(row0 + i);
+    pos_slot[o] = (int32_t)(row0 + i);
+}
+
+}  // namespace
+
+hipError_t lvr_launch_copy_rows(lvr_index *ix, const void *src, const int64_t strides[3], void *dst_base,
+                                int64_t dst_row0, int64_t rows, hipStream_t st) {
+    if (rows <= 0) return hipSuccess;
+    const int row_bytes = (int)(LVR_D * ix->elt);
+    const int64_t total = rows * (row_bytes / 16);
+    dim3 grid((unsigned)((total + 255) / 256), (unsigned)lvr_n_bh(ix));
+    hipLaunchKernelGGL(copy_rows_kernel, grid, dim3(256), 0, st, static_cast<const char *>(src),
+                       static_cast<char *>(dst_base), strides[0], strides[1], strides[2], ix->cfg.n_kv_heads,
+                       ix->cap_rows, dst_row0, rows, row_bytes, (int)ix->elt);
+    return hipGetLastError();
+}
+
+hipError_t lvr_launch_build_groups(lvr_index *ix, int64_t g0, int64_t g1, hipStream_t st) {
+    if (g1 <= g0) return hipSuccess;
+    dim3 grid((unsigned)((g1 - g0 + 15) / 16), (unsigned)lvr_n_bh(ix));
+    if (ix->cfg.kv_dtype == LVR_BF16)
+        hipLaunchKernelGGL(build_groups_kernel<lvr_bf16_t>, grid, dim3(256), 0, st, ix->K, ix->centres, ix->radii,
+                           ix->cap_rows, ix->max_groups, g0, g1, ix->cfg.group_size, ix->cfg.n_subspaces);
+    else
+        hipLaunchKernelGGL(build_groups_kernel<lvr_f32_t>, grid, dim3(256), 0, st, ix->K, ix->centres, ix->radii,
+                           ix->cap_rows, ix->max_groups, g0, g1, ix->cfg.group_size, ix->cfg.n_subspaces);
+    return hipGetLastError();
+}
+
+hipError_t lvr_launch_iota_rows(lvr_index *ix, int64_t row0, int64_t rows, hipStream_t st) {
+    if (rows <= 0 || !ix->slot_pos) return hipSuccess;
+    dim3 grid((unsigned)((rows + 255) / 256), (unsigned)lvr_n_bh(ix));
+    hipLaunchKernelGGL(iota_rows_kernel, grid, dim3(256), 0, st, ix->slot_pos, ix->pos_slot, ix->cap_rows, row0, rows);
+    return hipGetLastError();
+}

@@ -1,0 +1,131 @@
+// Internal declarations shared by the translation units of liblouver: the index object,
+// host-side launcher prototypes and the device helpers every kernel uses.
+//
+// Thread mapping used throughout: a 64-lane wavefront is split into four "quarter rows" of
+// 16 lanes; one head_dim = 128 row (a key, a value or a centre) is spread over the 16 lanes
+// of a quarter, 8 consecutive elements per lane, so one wave-wide 16-byte load covers four
+// bf16 rows (1 KiB) fully coalesced.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/louver.h"
+
+#define LVR_D 128          // head_dim this build is specialised for
+#define LVR_LANES_PER_ROW 16
+#define LVR_ELEMS_PER_LANE 8
+#define LVR_MAX_G 8
+
+struct lvr_index {
+    lvr_config cfg;
+    int device;
+    int G;                 // query heads per KV head
+    int64_t cap_rows;      // arena rows per (sequence, KV head), multiple of 64
+    int64_t max_groups;    // cap_rows / r
+    int64_t n_total;       // keys held
+    int64_t n_indexed;     // keys inside groups (multiple of r)
+    int built;
+    int P;                 // attention splits
+    int P_dense;           // splits of the dense baseline
+    float sigma;
+    size_t elt;            // bytes per K/V element
+    // arena (device)
+    void *K;               // [batch][H_kv][cap_rows][d]
+    void *V;
+    void *centres;         // [batch][H_kv][max_groups][d]
+    float *radii;          // [batch][H_kv][max_groups][S]
+    int32_t *slot_pos;     // [batch][H_kv][cap_rows] token position of arena row (TREE grouping), else NULL
+    int32_t *pos_slot;     // inverse map, or NULL
+    // work space (device)
+    int32_t *surv_list;    // [batch][H_kv][max_groups]
+    int32_t *counters;     // [batch*H_kv] surviving groups, then [batch*H_kv] emitted, then [1] overflow
+    float *part_ml;        // [batch][H_q][Pmax][2]
+    float *part_o;         // [batch][H_q][Pmax][d]
+    int64_t last_buffer_rows; // buffer rows scanned by the last query (host copy for stats)
+    int64_t last_attn_cap;
+};
+
+static inline int lvr_n_bh(const lvr_index *ix) { return ix->cfg.batch * ix->cfg.n_kv_heads; }
+static inline int32_t *lvr_surv_count(const lvr_index *ix) { return ix->counters; }
+static inline int32_t *lvr_emit_count(const lvr_index *ix) { return ix->counters + lvr_n_bh(ix); }
+static inline int32_t *lvr_overflow_flag(const lvr_index *ix) { return ix->counters + 2 * lvr_n_bh(ix); }
+
+// ---- launchers (each returns a hipError_t from hipGetLastError after the launch) ----
+hipError_t lvr_launch_copy_rows(lvr_index *ix, const void *src, const int64_t strides[3], void *dst_base,
+                                int64_t dst_row0, int64_t rows, hipStream_t st);
+hipError_t lvr_launch_build_groups(lvr_index *ix, int64_t g0, int64_t g1, hipStream_t st);
+hipError_t lvr_launch_reset(lvr_index *ix, int32_t *out_count, hipStream_t st);
+hipError_t lvr_launch_prune(lvr_index *ix, const float *q, const float *tau, hipStream_t st);
+hipError_t lvr_launch_filter(lvr_index *ix, const float *q, const float *tau, int32_t *out_idx,
+                             int32_t *out_count, int64_t cap, hipStream_t st);
+hipError_t lvr_launch_sparse_attention(lvr_index *ix, const float *q, const int32_t *idx, const int32_t *count,
+                                       int64_t cap, float *out, hipStream_t st);
+hipError_t lvr_launch_dense_attention(lvr_index *ix, const float *q, float *out, hipStream_t st);
+
+#ifdef __HIPCC__
+// ------------------------------------------------------------------------------------------
+// Device helpers
+// ------------------------------------------------------------------------------------------
+struct lvr_bf16_t { uint16_t bits; };   // tag types for the two storage formats
+struct lvr_f32_t { float v; };
+
+__device__ __forceinline__ float lvr_bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float lvr_bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// Round-to-nearest-even fp32 -> bf16 bit pattern (finite inputs).
+__device__ __forceinline__ uint32_t lvr_f32_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+// Load the 8 consecutive elements of a row that belong to this lane (lane-in-row li).
+template <typename KT>
+__device__ __forceinline__ void lvr_load8(const void *base, int64_t row, int li, float (&x)[8]);
+
+template <>
+__device__ __forceinline__ void lvr_load8<lvr_bf16_t>(const void *base, int64_t row, int li, float (&x)[8]) {
+    const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(base) + row * LVR_D) + li;
+    uint4 w = *p;
+    x[0] = lvr_bf16_lo(w.x); x[1] = lvr_bf16_hi(w.x);
+    x[2] = lvr_bf16_lo(w.y); x[3] = lvr_bf16_hi(w.y);
+    x[4] = lvr_bf16_lo(w.z); x[5] = lvr_bf16_hi(w.z);
+    x[6] = lvr_bf16_lo(w.w); x[7] = lvr_bf16_hi(w.w);
+}
+
+template <>
+__device__ __forceinline__ void lvr_load8<lvr_f32_t>(const void *base, int64_t row, int li, float (&x)[8]) {
+    const float4 *p = reinterpret_cast<const float4 *>(static_cast<const float *>(base) + row * LVR_D) + 2 * li;
+    float4 a = p[0], b = p[1];
+    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
+    x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+}
+
+__device__ __forceinline__ void lvr_zero8(float (&x)[8]) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = 0.f;
+}
+
+// Sum over the 16 lanes of a quarter row; every lane of the quarter gets the total.
+// DPP data movement inside a row of 16 lanes: two quad permutes, then the half-row and
+// full-row mirrors.
+template <int CTRL>
+__device__ __forceinline__ float lvr_dpp(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+
+__device__ __forceinline__ float lvr_row16_sum(float v) {
+    v += lvr_dpp<0xB1>(v);    // quad_perm [1,0,3,2]  : lane ^ 1
+    v += lvr_dpp<0x4E>(v);    // quad_perm [2,3,0,1]  : lane ^ 2
+    v += lvr_dpp<0x141>(v);   // row_half_mirror      : 7 - lane within 8
+    v += lvr_dpp<0x140>(v);   // row_mirror           : 15 - lane within 16
+    return v;
+}
+
+__device__ __forceinline__ int lvr_lane() { return threadIdx.x & 63; }
+
+// Threshold the kernels compare against: tau lowered by half of the 1e-4*|tau| tolerance band,
+// so that keys whose score differs from tau only by summation order are kept.
+__device__ __forceinline__ float lvr_effective_tau(float tau) {
+    return (tau == -INFINITY) ? tau : tau - 0.5e-4f * fabsf(tau);
+}
+#endif  // __HIPCC__

@@ -1,0 +1,76 @@
+"""CPU-only checks of the boundary: the shared library loads, exports every entry point the
+public header declares, and rejects bad configurations without touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "louver.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lvr_[a-z_0-9]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_2605_06763_amd as L
+    if not os.path.exists(L.binding.LIB_PATH):
+        from paper_2605_06763_amd.build import build_library
+        build_library()
+    return L
+
+
+def test_header_and_library_agree(L):
+    names = _declared()
+    assert len(names) >= 12
+    lib = L.lib()
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in include/louver.h but not exported"
+    assert sorted(L.EXPORTS) == names
+    for n in names:
+        if n not in ("lvr_strerror", "lvr_last_hip_error", "lvr_arena_bytes"):
+            assert callable(getattr(L, n)), f"binding lacks {n}"
+
+
+def test_config_struct_matches_header(L):
+    """Field order of the ctypes mirror equals the header's struct (argument marshalling only
+    works if both sides agree on the layout)."""
+    text = open(os.path.join(ROOT, "include", "louver.h")).read()
+    body = re.search(r"typedef struct lvr_config \{(.*?)\} lvr_config;", text, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"\b(?:int32_t|uint32_t|int64_t|float)\s+([a-z_]+)\s*;", body)
+    assert fields == [f for f, _ in L.lvr_config._fields_]
+    body = re.search(r"typedef struct lvr_stats \{(.*?)\} lvr_stats;", text, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"\b(?:int32_t|uint32_t|int64_t|float)\s+([a-z_]+)\s*;", body)
+    assert fields == [f for f, _ in L.lvr_stats._fields_]
+
+
+def test_bad_configs_are_rejected_on_the_host(L):
+    ok = dict(batch=1, n_q_heads=32, n_kv_heads=8, capacity=1024)
+    assert L.lvr_arena_bytes(L.make_config(**ok)) > 2 * 8 * 1024 * 128 * 2
+    for bad in (dict(ok, head_dim=64), dict(ok, n_q_heads=30), dict(ok, group_size=3), dict(ok, n_subspaces=32),
+                dict(ok, buffer_size=100), dict(ok, capacity=0), dict(ok, n_q_heads=24, n_kv_heads=8),
+                dict(ok, kv_dtype=7)):
+        cfg = L.make_config(**bad)
+        assert L.lvr_arena_bytes(cfg) == 0
+        h = C.c_void_p()
+        assert L.lib().lvr_create(C.byref(cfg), C.byref(h)) < 0 and not h.value
+    assert L.lib().lvr_strerror(L.LVR_E_OVERFLOW).decode().startswith("a retrieved set")
+    assert L.lib().lvr_strerror(-99).decode() == "unknown error"
+    # NULL handles are refused, not dereferenced
+    assert L.lib().lvr_query(None, None, None, None, None, 0, None) == L.LVR_E_INVALID
+    assert L.lib().lvr_destroy(None) == L.LVR_E_INVALID
+
+
+def test_product_path_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2605_06763_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in src.lower().replace("threshold oracle", ""), f

@@ -1,0 +1,361 @@
+"""GPU parity tests at sizes the oracle finishes in seconds: every entry point goes through the
+C ABI (ctypes binding) and is compared element by element with the CPU oracle."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G():
+    import gpu_util
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return gpu_util
+
+
+def _small_cache(config_id, n, hkv=2, batch=1):
+    c = W.make_cache(config_id, n=n, n_kv_heads=hkv, batch=batch)
+    return c
+
+
+# ------------------------------------------------------------------ config 1 (fp32, whole size)
+def test_config1_fp32_single_head(G, oracle):
+    """Single head, d=128, n=4096, fp32, about 2 % qualify, 8 planted keys."""
+    G.say("config1: build inputs")
+    cache = W.make_cache(1)
+    q = W.make_queries(1)
+    K = cache.K[0, 0]
+    s = oracle.scores_f32(q[0, 0], K)
+    tau = float(W.tau_for_fraction(s, 0.02))
+    rows = W.planted_positions(1, K.shape[0], 8)
+    W.plant_rows(K, rows, (tau + 0.25) / s[rows], "f32")
+    with G.Index(cache.K, cache.V, "f32", 1) as ix:
+        taus = np.full((1, 1), tau, dtype=np.float32)
+        for fused in (False, True):
+            idx, cnt, out = ix.query(q, taus, fused=fused)
+            r = G.check_step(oracle, ix, q, taus, idx, cnt, out, tag=f"config1 fused={fused}")
+            assert set(rows.tolist()) <= set(idx[0, 0, :cnt[0, 0]].tolist())
+            assert 82 <= cnt[0, 0] <= 82 + 8
+            G.say("config1", r, ix.stats())
+
+
+# ------------------------------------------------------------------ bf16 GQA, ragged sizes
+@pytest.mark.parametrize("n", [1, 3, 64, 1000, 2051, 4096])
+def test_gqa_bf16_sets_and_attention(G, oracle, n):
+    G.say(f"gqa bf16 n={n}")
+    cache = _small_cache(2, n)
+    q = W.make_queries(2, n_q_heads=8)
+    with G.Index(cache.K, cache.V, "bf16", 8) as ix:
+        for frac in (0.01, 0.2):
+            tau = G.oracle_taus(oracle, ix, q, frac=frac)
+            idx, cnt, out = ix.query(q, tau)
+            r = G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=f"n={n} frac={frac}")
+            st = ix.stats()
+            assert st["keys_emitted"] == int(cnt.sum())
+            assert st["n_keys"] == n and st["n_indexed"] == n // 4 * 4
+            G.say(f"  frac={frac}", r, {k: st[k] for k in ("groups_scored", "groups_surviving", "keys_scanned")})
+        # dense baseline against the oracle's dense attention
+        ref = oracle.dense_attention(ix.K, ix.V, q, ix.sigma, 8)
+        got = ix.dense(q)
+        err = np.abs(got - ref).max(axis=-1) / np.abs(ref).max(axis=-1)
+        assert err.max() <= G.ATTN_TOL, err
+
+
+def test_tau_extremes(G, oracle):
+    """tau = -inf retrieves every key and reproduces dense attention; tau above every score
+    retrieves nothing and returns zeros."""
+    n = 777
+    cache = _small_cache(2, n)
+    q = W.make_queries(2, n_q_heads=8)
+    with G.Index(cache.K, cache.V, "bf16", 8) as ix:
+        tau = np.full((1, 8), -np.inf, dtype=np.float32)
+        idx, cnt, out = ix.query(q, tau)
+        assert (cnt == n).all()
+        for h in range(8):
+            assert sorted(idx[0, h, :n].tolist()) == list(range(n))
+        ref = oracle.dense_attention(ix.K, ix.V, q, ix.sigma, 8)
+        assert (np.abs(out - ref).max(axis=-1) / np.abs(ref).max(axis=-1)).max() <= G.ATTN_TOL
+        assert (np.abs(ix.dense(q) - ref).max(axis=-1) / np.abs(ref).max(axis=-1)).max() <= G.ATTN_TOL
+        tau = np.full((1, 8), np.inf, dtype=np.float32)
+        idx, cnt, out = ix.query(q, tau)
+        assert (cnt == 0).all() and (out == 0).all()
+        assert ix.stats()["groups_surviving"] == 0
+        # mixed: one head takes everything, its neighbours nothing
+        tau = np.full((1, 8), np.inf, dtype=np.float32)
+        tau[0, 5] = -np.inf
+        idx, cnt, out = ix.query(q, tau)
+        assert cnt[0].tolist() == [0, 0, 0, 0, 0, n, 0, 0]
+        assert np.abs(out[0, 5] - ref[0, 5]).max() / np.abs(ref[0, 5]).max() <= G.ATTN_TOL
+
+
+def test_empty_index(G, oracle):
+    cache = _small_cache(2, 0)
+    q = W.make_queries(2, n_q_heads=8)
+    with G.Index(cache.K, cache.V, "bf16", 8, capacity=64) as ix:
+        idx, cnt, out = ix.query(q, np.zeros((1, 8), np.float32), cap=4)
+        assert (cnt == 0).all() and (out == 0).all()
+        assert (ix.dense(q) == 0).all()
+
+
+def test_exact_ties_integer_data(G, oracle):
+    """Integer-valued keys and queries: fp32 dot products are exact in any summation order, so
+    the sets must equal the oracle's exactly, ties at tau included (>=, not >)."""
+    g = np.random.default_rng(5)
+    n = 1024
+    K = g.integers(-4, 5, size=(1, 2, n, 128)).astype(np.float32)
+    V = g.integers(-4, 5, size=(1, 2, n, 128)).astype(np.float32)
+    q = g.integers(-3, 4, size=(1, 4, 128)).astype(np.float32)
+    for dtype in ("bf16", "f32"):
+        with G.Index(K, V, dtype, 4) as ix:
+            for quant in (0.99, 0.9):
+                tau = np.zeros((1, 4), dtype=np.float32)
+                for h in range(4):
+                    s = oracle.scores_f32(q[0, h], K[0, h // 2])
+                    # a value that occurs among the scores; scaled so tau - 0.5e-4|tau| stays above the next integer
+                    tau[0, h] = np.sort(s)[int(quant * n)]
+                idx, cnt, out = ix.query(q, tau)
+                for h in range(4):
+                    want = oracle.range_query(q[0, h], K[0, h // 2], tau[0, h])
+                    assert sorted(idx[0, h, :cnt[0, h]].tolist()) == want.tolist(), (dtype, quant, h)
+
+
+@pytest.mark.parametrize("r,S", [(1, 4), (2, 1), (8, 16), (16, 2), (4, 8)])
+def test_group_size_and_subspaces(G, oracle, r, S):
+    n = 1500
+    cache = _small_cache(2, n)
+    q = W.make_queries(2, n_q_heads=8)
+    with G.Index(cache.K, cache.V, "bf16", 8, group_size=r, n_subspaces=S, buffer_size=64) as ix:
+        tau = G.oracle_taus(oracle, ix, q, frac=0.03)
+        idx, cnt, out = ix.query(q, tau)
+        G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=f"r={r} S={S}")
+        st = ix.stats()
+        assert st["n_indexed"] == n // r * r
+
+
+@pytest.mark.parametrize("hq,hkv", [(2, 2), (4, 2), (16, 2), (8, 1)])
+def test_head_group_sizes(G, oracle, hq, hkv):
+    n = 900
+    cache = _small_cache(2, n, hkv=hkv, batch=2)
+    q = W.make_queries(2, n_q_heads=hq, batch=2)
+    with G.Index(cache.K, cache.V, "bf16", hq) as ix:
+        tau = G.oracle_taus(oracle, ix, q, frac=0.05)
+        idx, cnt, out = ix.query(q, tau, fused=True)
+        G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=f"hq={hq} hkv={hkv}")
+        ref = oracle.dense_attention(ix.K, ix.V, q, ix.sigma, hq)
+        assert (np.abs(ix.dense(q) - ref).max(axis=-1) / np.abs(ref).max(axis=-1)).max() <= G.ATTN_TOL
+
+
+def test_non_default_scale_and_general_fp32_query(G, oracle):
+    n = 1200
+    cache = _small_cache(2, n)
+    q = W.make_queries(2, n_q_heads=8, exact_bf16=False)      # full fp32 query values
+    with G.Index(cache.K, cache.V, "bf16", 8, scale=0.031) as ix:
+        tau = G.oracle_taus(oracle, ix, q, frac=0.04)
+        idx, cnt, out = ix.query(q, tau)
+        G.check_step(oracle, ix, q, tau, idx, cnt, out, tag="scale=0.031")
+
+
+def test_overflow_is_reported_not_silent(G, oracle):
+    import paper_2605_06763_amd as L
+    n = 512
+    cache = _small_cache(2, n)
+    q = W.make_queries(2, n_q_heads=8)
+    with G.Index(cache.K, cache.V, "bf16", 8) as ix:
+        tau = G.oracle_taus(oracle, ix, q, k_count=40)
+        idx, cnt, out = ix.query(q, tau, cap=16)
+        assert (cnt == 40).all()                      # true sizes even though lists are truncated
+        with pytest.raises(L.LouverError) as e:
+            ix.stats()
+        assert e.value.code == L.LVR_E_OVERFLOW
+        for h in range(8):                            # what was written is a subset of the true set
+            want = set(oracle.range_query(q[0, h], ix.K[0, h // 4], tau[0, h]).tolist())
+            assert set(idx[0, h, :16].tolist()) <= want
+        idx, cnt, out = ix.query(q, tau, cap=64)      # flag is cleared, a roomy call is clean
+        assert ix.stats()["overflow"] == 0
+
+
+def test_sparse_attention_on_caller_lists(G, oracle):
+    """lvr_sparse_attention on lists the caller made up (unsorted, with out-of-range entries,
+    uneven lengths including empty)."""
+    import paper_2605_06763_amd as L
+    n = 640
+    cache = _small_cache(2, n)
+    q = W.make_queries(2, n_q_heads=8)
+    g = np.random.default_rng(3)
+    with G.Index(cache.K, cache.V, "bf16", 8) as ix:
+        cap = 300
+        idx = np.zeros((1, 8, cap), dtype=np.int32)
+        cnt = np.array([[0, 1, 2, 5, 64, 65, 299, 300]], dtype=np.int32)
+        lists = []
+        for h in range(8):
+            l = g.permutation(n)[:cnt[0, h]].astype(np.int32)
+            idx[0, h, :cnt[0, h]] = l
+            lists.append(l)
+        idx[0, 6, 10] = n + 5          # out of range entries are skipped
+        idx[0, 6, 11] = -1
+        lists[6] = np.delete(lists[6], [10, 11])
+        qd = torch.from_numpy(q).cuda()
+        out = torch.zeros((1, 8, 128), device="cuda")
+        L.lvr_sparse_attention(ix.h, qd, torch.from_numpy(idx).cuda(), torch.from_numpy(cnt).cuda(), out)
+        torch.cuda.synchronize()
+        out = out.cpu().numpy()
+        for h in range(8):
+            ref = oracle.attention_on_list(q[0, h], ix.K[0, h // 4], ix.V[0, h // 4], lists[h], ix.sigma)
+            if lists[h].size == 0:
+                assert (out[0, h] == 0).all()
+            else:
+                assert np.abs(out[0, h] - ref).max() / np.abs(ref).max() <= G.ATTN_TOL, h
+
+
+# ------------------------------------------------------------------ the index itself
+def test_index_balls_enclose_members(G, oracle):
+    """Eq. (1) on the exported index: stored centres are the group means (to storage rounding),
+    stored radii enclose every member measured against the centres AS STORED, and are not
+    looser than the documented widening."""
+    n, r, S = 1024, 4, 4
+    cache = _small_cache(2, n)
+    for dtype, Kc in (("bf16", cache.K), ("f32", W.make_cache(1, n=n).K)):
+        hkv = Kc.shape[1]
+        with G.Index(Kc, Kc, dtype, hkv, group_size=r, n_subspaces=S) as ix:
+            centres, radii, slot_pos, keys = ix.export()
+            for h in range(hkv):
+                c = W.bf16_bits_to_f32(centres[0, h]).reshape(n // r, 128) if dtype == "bf16" else centres[0, h]
+                label = (np.arange(n) // r).astype(np.int32)
+                assert np.array_equal(slot_pos[0, h], np.arange(n))
+                mean, _ = oracle.ball_index(Kc[0, h], label, n // r, S)
+                ulp = 2.0 ** -8 if dtype == "bf16" else 2.0 ** -22
+                # storage rounding of the mean, plus the fp32 summation error of r terms
+                absmean = np.abs(Kc[0, h]).reshape(n // r, r, 128).mean(axis=1)
+                assert np.all(np.abs(c - mean) <= ulp * np.abs(mean) + r * 2.0 ** -24 * absmean + 1e-30)
+                need = oracle.ball_radii_for_centres(Kc[0, h], label, c.astype(np.float64), S)
+                assert np.all(radii[0, h] >= need), "a member lies outside its ball"
+                cn = np.stack([np.linalg.norm(c[:, lo:hi].astype(np.float64), axis=1)
+                               for lo, hi in (oracle.subspace_range(128, S, s) for s in range(S))], axis=1)
+                assert np.all(radii[0, h] <= need * (1 + 2.0 ** -11) + cn * 2.0 ** -11 + 1e-30)
+
+
+def test_surviving_groups_match_oracle_bounds(G, oracle):
+    """The number of groups the bound test keeps equals the number whose Eq. (2) bound, evaluated
+    by the oracle on the exported index, reaches tau for some head of the KV group (up to
+    groups whose bound is within rounding of tau)."""
+    n, r, S = 2048, 4, 4
+    cache = _small_cache(2, n, hkv=1)
+    q = W.make_queries(2, n_q_heads=4)
+    with G.Index(cache.K, cache.V, "bf16", 4, group_size=r, n_subspaces=S) as ix:
+        centres, radii, _, _ = ix.export()
+        c = W.bf16_bits_to_f32(centres[0, 0]).reshape(n // r, 128).astype(np.float64)
+        for frac in (0.001, 0.01, 0.3):
+            tau = G.oracle_taus(oracle, ix, q, frac=frac)
+            # scale tau up so that a real share of the balls is pruned on this data
+            for boost in (1.0, 3.0, 6.0):
+                t = (tau * boost).astype(np.float32)
+                ix.query(q, t)
+                st = ix.stats()
+                ub = np.stack([oracle.ball_bounds(q[0, h], c, radii[0, 0].astype(np.float64)).sum(0) for h in range(4)])
+                te = t[0] - 0.5e-4 * np.abs(t[0])
+                lo = int(np.any(ub >= te[:, None] * (1 + 1e-5) + 1e-4, axis=0).sum())
+                hi = int(np.any(ub >= te[:, None] * (1 - 1e-5) - 1e-4, axis=0).sum())
+                assert lo <= st["groups_surviving"] <= hi, (frac, boost, lo, st["groups_surviving"], hi)
+                G.say(f"  frac={frac} boost={boost}: surviving {st['groups_surviving']} of {st['groups_scored']}")
+
+
+def test_key_on_ball_surface_is_never_lost(G, oracle):
+    """Adversarial placement: in every group one member sits exactly at centre + rho * q/|q|,
+    so its score equals the ball bound; with tau equal to that score the key must come back."""
+    g = np.random.default_rng(11)
+    n, r = 512, 4
+    qdir = np.zeros(128, dtype=np.float32)
+    qdir[[3, 40, 77, 120]] = [1.0, -1.0, 1.0, 1.0]          # |q| = 2, exactly representable
+    K = np.zeros((1, 1, n, 128), dtype=np.float32)
+    for gi in range(n // r):
+        centre = W.round_to_bf16(g.integers(-8, 9, size=128).astype(np.float32))
+        step = float(g.integers(1, 5)) * 0.5
+        K[0, 0, gi * r + 0] = centre + step * qdir
+        K[0, 0, gi * r + 1] = centre - step * qdir
+        K[0, 0, gi * r + 2] = centre
+        K[0, 0, gi * r + 3] = centre
+    V = g.standard_normal((1, 1, n, 128)).astype(np.float32)
+    q = (qdir * 3.0)[None, None, :]
+    for S in (1, 4, 16):
+        with G.Index(K, W.round_to_bf16(V), "bf16", 1, n_subspaces=S) as ix:
+            s = oracle.scores_f32(q[0, 0], K[0, 0])
+            for tau in np.unique(s)[-6:]:
+                t = np.full((1, 1), tau, dtype=np.float32)
+                idx, cnt, out = ix.query(q, t)
+                G.check_step(oracle, ix, q, t, idx, cnt, out, tag=f"surface S={S} tau={tau}")
+
+
+def test_pruning_happens_on_clustered_keys(G, oracle):
+    """Keys with positional locality (consecutive tokens share a slowly changing mean): most
+    balls are pruned, the result still equals the oracle's."""
+    g = np.random.default_rng(21)
+    n, hkv, hq = 8192, 2, 8
+    base = np.repeat(g.standard_normal((1, hkv, n // 64, 128)).astype(np.float32) * 3.0, 64, axis=2)
+    K = W.round_to_bf16(base + 0.05 * g.standard_normal((1, hkv, n, 128)).astype(np.float32))
+    V = W.round_to_bf16(g.standard_normal((1, hkv, n, 128)).astype(np.float32))
+    q = W.make_queries(2, n_q_heads=hq)
+    with G.Index(K, V, "bf16", hq, n_subspaces=4) as ix:
+        tau = G.oracle_taus(oracle, ix, q, frac=0.02)
+        idx, cnt, out = ix.query(q, tau, fused=True)
+        G.check_step(oracle, ix, q, tau, idx, cnt, out, tag="clustered")
+        st = ix.stats()
+        G.say("clustered keys:", st)
+        assert st["groups_surviving"] < 0.25 * st["groups_scored"]
+        assert st["keys_scanned"] == st["groups_surviving"] * 4
+
+
+# ------------------------------------------------------------------ append
+@pytest.mark.parametrize("flags", [0, 1])
+def test_append_matches_oracle_on_grown_cache(G, oracle, flags):
+    """Prompt of 200 keys, then single-token appends across several buffer flushes (B = 32);
+    after every step the query over the grown cache equals the oracle's.  With the
+    attend-buffer flag the not-yet-indexed tail is retrieved whatever its score."""
+    n0, steps, B = 203, 75, 32
+    cache = _small_cache(5, n0)
+    k_new, v_new = W.make_append_stream(5, steps, cache)
+    qs = W.drift_queries(5, steps, n_q_heads=8)
+    with G.Index(cache.K, cache.V, "bf16", 8, capacity=n0 + steps, buffer_size=B, flags=flags) as ix:
+        import paper_2605_06763_amd as L
+        for t in range(steps):
+            ix.append(k_new[t][:, :, None, :], v_new[t][:, :, None, :])
+            n, n_indexed = L.lvr_length(ix.h)
+            assert n == n0 + t + 1
+            assert n_indexed % 4 == 0 and 0 <= n - n_indexed < B + 4
+            if t % 7 == 0 or t == steps - 1:
+                tau = G.oracle_taus(oracle, ix, qs[t], frac=0.05)
+                idx, cnt, out = ix.query(qs[t], tau, fused=(t % 2 == 0))
+                G.check_step(oracle, ix, qs[t], tau, idx, cnt, out, tag=f"append t={t}",
+                             extra_from=(n_indexed if flags else -1))
+        assert n_indexed >= n0 // 4 * 4 + 2 * B      # at least two flushes happened
+        # bulk append of many tokens at once
+    with G.Index(cache.K, cache.V, "bf16", 8, capacity=n0 + steps, buffer_size=B) as ix:
+        kk = np.ascontiguousarray(k_new.transpose(1, 2, 0, 3))
+        vv = np.ascontiguousarray(v_new.transpose(1, 2, 0, 3))
+        ix.append(kk, vv)
+        tau = G.oracle_taus(oracle, ix, qs[-1], frac=0.05)
+        idx, cnt, out = ix.query(qs[-1], tau)
+        G.check_step(oracle, ix, qs[-1], tau, idx, cnt, out, tag="bulk append")
+        import paper_2605_06763_amd as L
+        with pytest.raises(L.LouverError) as e:
+            ix.append(kk[:, :, :1], vv[:, :, :1])
+        assert e.value.code == L.LVR_E_CAPACITY
+
+
+def test_strided_build_input(G, oracle):
+    """K and V handed over as views with non-trivial strides (a slice of a longer cache)."""
+    import paper_2605_06763_amd as L
+    n = 300
+    cache = _small_cache(2, 400)
+    q = W.make_queries(2, n_q_heads=8)
+    Kd = G.to_device(cache.K, "bf16")[:, :, 50:50 + n]
+    Vd = G.to_device(cache.V, "bf16")[:, :, 50:50 + n]
+    with G.Index(cache.K[:, :, 50:50 + n], cache.V[:, :, 50:50 + n], "bf16", 8) as ix:
+        L.lvr_build(ix.h, Kd, Vd)          # rebuild from the strided views
+        tau = G.oracle_taus(oracle, ix, q, frac=0.05)
+        idx, cnt, out = ix.query(q, tau)
+        G.check_step(oracle, ix, q, tau, idx, cnt, out, tag="strided")
