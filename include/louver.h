@@ -156,6 +156,24 @@ int lvr_get_stats(lvr_index *ix, lvr_stats *out_host);
 int lvr_export_index(lvr_index *ix, void *centres_host, float *radii_host, int32_t *slot_pos_host,
                      void *keys_host);
 
+/* Per-kernel GPU time, for measurement (App. "Kernel Implementation Details" names the stages).
+ * While enabled, every kernel launch of every call is bracketed by a pair of HIP events on the
+ * call's stream (events come from a pool allocated by lvr_profile_enable, so the hot-path
+ * calls still allocate nothing); when the pool of `max_launches` pairs is used up further
+ * launches are simply not timed.  lvr_profile_read synchronises the device, adds up the
+ * elapsed time of each pair by kernel, and empties the pool. */
+typedef struct lvr_profile {
+    double ms[9];      /* total milliseconds per kernel, indexed by lvr_kernel                */
+    int64_t launches[9];
+} lvr_profile;
+enum lvr_kernel {
+    LVR_KERNEL_COPY = 0, LVR_KERNEL_BUILD = 1, LVR_KERNEL_RESET = 2, LVR_KERNEL_PRUNE = 3,
+    LVR_KERNEL_FILTER = 4, LVR_KERNEL_ATTN_PARTIAL = 5, LVR_KERNEL_ATTN_COMBINE = 6,
+    LVR_KERNEL_DENSE_PARTIAL = 7, LVR_KERNEL_DENSE_COMBINE = 8
+};
+int lvr_profile_enable(lvr_index *ix, int max_launches); /* 0 turns timing off and frees the pool */
+int lvr_profile_read(lvr_index *ix, lvr_profile *out_host);
+
 /* n = keys held per (sequence, KV head); n_indexed = keys inside groups. */
 int lvr_length(const lvr_index *ix, int64_t *n_host, int64_t *n_indexed_host);
 

@@ -41,10 +41,18 @@ class lvr_stats(C.Structure):
         return {k: int(getattr(self, k)) for k, _ in self._fields_ if k != "reserved"}
 
 
+class lvr_profile(C.Structure):
+    _fields_ = [("ms", C.c_double * 9), ("launches", C.c_int64 * 9)]
+
+
+KERNEL_NAMES = ["copy", "build", "reset", "prune", "filter", "attn_partial", "attn_combine",
+                "dense_partial", "dense_combine"]
+
 EXPORTS = [
     "lvr_create", "lvr_destroy", "lvr_arena_bytes", "lvr_build", "lvr_append", "lvr_query",
     "lvr_sparse_attention", "lvr_decode_step", "lvr_dense_attention", "lvr_get_stats",
     "lvr_export_index", "lvr_length", "lvr_strerror", "lvr_last_hip_error",
+    "lvr_profile_enable", "lvr_profile_read",
 ]
 
 _lib = None
@@ -82,6 +90,8 @@ def lib():
     L.lvr_get_stats.argtypes = [vp, C.POINTER(lvr_stats)]
     L.lvr_export_index.argtypes = [vp, vp, vp, vp, vp]
     L.lvr_length.argtypes = [vp, C.POINTER(i64), C.POINTER(i64)]
+    L.lvr_profile_enable.argtypes = [vp, C.c_int]
+    L.lvr_profile_read.argtypes = [vp, C.POINTER(lvr_profile)]
     L.lvr_strerror.argtypes = [C.c_int]
     L.lvr_strerror.restype = C.c_char_p
     L.lvr_last_hip_error.restype = C.c_int
@@ -182,6 +192,17 @@ def lvr_get_stats(h, raise_on_overflow: bool = True) -> dict:
         return st.as_dict()
     _check(rc, "lvr_get_stats")
     return st.as_dict()
+
+
+def lvr_profile_enable(h, max_launches: int) -> None:
+    _check(lib().lvr_profile_enable(h, int(max_launches)), "lvr_profile_enable")
+
+
+def lvr_profile_read(h) -> dict:
+    """{kernel name: (total ms, launches)} since the last read."""
+    p = lvr_profile()
+    _check(lib().lvr_profile_read(h, C.byref(p)), "lvr_profile_read")
+    return {KERNEL_NAMES[i]: (float(p.ms[i]), int(p.launches[i])) for i in range(9)}
 
 
 def lvr_length(h):

@@ -8,8 +8,6 @@
 
 #include "lvr_internal.h"
 
-hipError_t lvr_launch_iota_rows(lvr_index *ix, int64_t row0, int64_t rows, hipStream_t st);
-
 namespace {
 
 thread_local int g_last_hip_error = 0;
@@ -81,6 +79,33 @@ void free_all(lvr_index *ix) {
         if (p) (void)hipFree(p);
 }
 
+// Optional event pair around one kernel launch.
+struct Timed {
+    lvr_index *ix;
+    hipStream_t st;
+    int slot;
+    Timed(lvr_index *ix_, int kind, hipStream_t st_) : ix(ix_), st(st_), slot(-1) {
+        if (ix->prof_on && ix->prof_used + 2 <= ix->prof_cap) {
+            slot = ix->prof_used;
+            ix->prof_used += 2;
+            ix->prof_kind[slot / 2] = (uint8_t)kind;
+            (void)hipEventRecord(ix->prof_events[slot], st);
+        }
+    }
+    ~Timed() {
+        if (slot >= 0) (void)hipEventRecord(ix->prof_events[slot + 1], st);
+    }
+};
+
+void prof_free(lvr_index *ix) {
+    for (int i = 0; i < ix->prof_cap; ++i) (void)hipEventDestroy(ix->prof_events[i]);
+    free(ix->prof_events);
+    free(ix->prof_kind);
+    ix->prof_events = nullptr;
+    ix->prof_kind = nullptr;
+    ix->prof_cap = ix->prof_used = ix->prof_on = 0;
+}
+
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 }  // namespace
@@ -135,6 +160,7 @@ int lvr_create(const lvr_config *cfg, lvr_index **out) {
 int lvr_destroy(lvr_index *ix) {
     if (!ix) return LVR_E_INVALID;
     (void)hipDeviceSynchronize();
+    prof_free(ix);
     free_all(ix);
     delete ix;
     return LVR_OK;
@@ -156,12 +182,16 @@ int lvr_build(lvr_index *ix, const void *K, const void *V, int64_t n, const int6
     ix->n_total = 0;
     ix->n_indexed = 0;
     if (n > 0) {
+        Timed t(ix, LVR_K_COPY, st);
         LVR_HIP(lvr_launch_copy_rows(ix, K, ks, ix->K, 0, n, st));
         LVR_HIP(lvr_launch_copy_rows(ix, V, vs, ix->V, 0, n, st));
     }
     const int r = ix->cfg.group_size;
     const int64_t n_groups = n / r;
-    LVR_HIP(lvr_launch_build_groups(ix, 0, n_groups, st));
+    {
+        Timed t(ix, LVR_K_BUILD, st);
+        LVR_HIP(lvr_launch_build_groups(ix, 0, n_groups, st));
+    }
     ix->n_total = n;
     ix->n_indexed = n_groups * r;
     ix->built = 1;
@@ -176,8 +206,11 @@ int lvr_append(lvr_index *ix, const void *k_new, const void *v_new, int64_t m, v
     if (!aligned16(k_new) || !aligned16(v_new)) return LVR_E_INVALID;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int64_t strides[3] = {(int64_t)ix->cfg.n_kv_heads * m * LVR_D, m * LVR_D, LVR_D};
-    LVR_HIP(lvr_launch_copy_rows(ix, k_new, strides, ix->K, ix->n_total, m, st));
-    LVR_HIP(lvr_launch_copy_rows(ix, v_new, strides, ix->V, ix->n_total, m, st));
+    {
+        Timed t(ix, LVR_K_COPY, st);
+        LVR_HIP(lvr_launch_copy_rows(ix, k_new, strides, ix->K, ix->n_total, m, st));
+        LVR_HIP(lvr_launch_copy_rows(ix, v_new, strides, ix->V, ix->n_total, m, st));
+    }
     ix->n_total += m;
     // every full buffer of B keys becomes B/r new groups at the tail of the index
     const int64_t B = ix->cfg.buffer_size;
@@ -185,6 +218,7 @@ int lvr_append(lvr_index *ix, const void *k_new, const void *v_new, int64_t m, v
     const int64_t full = (ix->n_total - ix->n_indexed) / B;
     if (full > 0) {
         const int64_t g0 = ix->n_indexed / r, g1 = g0 + full * (B / r);
+        Timed t(ix, LVR_K_BUILD, st);
         LVR_HIP(lvr_launch_build_groups(ix, g0, g1, st));
         ix->n_indexed += full * B;
     }
@@ -196,9 +230,18 @@ int lvr_query(lvr_index *ix, const float *q, const float *tau, int32_t *out_idx,
     if (!ix || !q || !tau || !out_count || cap < 0 || (cap > 0 && !out_idx)) return LVR_E_INVALID;
     if (!ix->built) return LVR_E_STATE;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    LVR_HIP(lvr_launch_reset(ix, out_count, st));
-    LVR_HIP(lvr_launch_prune(ix, q, tau, st));
-    LVR_HIP(lvr_launch_filter(ix, q, tau, out_idx, out_count, cap, st));
+    {
+        Timed t(ix, LVR_K_RESET, st);
+        LVR_HIP(lvr_launch_reset(ix, out_count, st));
+    }
+    {
+        Timed t(ix, LVR_K_PRUNE, st);
+        LVR_HIP(lvr_launch_prune(ix, q, tau, st));
+    }
+    {
+        Timed t(ix, LVR_K_FILTER, st);
+        LVR_HIP(lvr_launch_filter(ix, q, tau, out_idx, out_count, cap, st));
+    }
     ix->last_buffer_rows = ix->n_total - ix->n_indexed;
     return LVR_OK;
 }
@@ -207,7 +250,15 @@ int lvr_sparse_attention(lvr_index *ix, const float *q, const int32_t *idx, cons
                          float *out, void *stream) {
     if (!ix || !q || !count || !out || cap < 0 || (cap > 0 && !idx)) return LVR_E_INVALID;
     if (!ix->built) return LVR_E_STATE;
-    LVR_HIP(lvr_launch_sparse_attention(ix, q, idx, count, cap, out, static_cast<hipStream_t>(stream)));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    {
+        Timed t(ix, LVR_K_ATTN_PARTIAL, st);
+        LVR_HIP(lvr_launch_sparse_partial(ix, q, idx, count, cap, st));
+    }
+    {
+        Timed t(ix, LVR_K_ATTN_COMBINE, st);
+        LVR_HIP(lvr_launch_combine(ix, out, ix->P, st));
+    }
     return LVR_OK;
 }
 
@@ -221,7 +272,15 @@ int lvr_decode_step(lvr_index *ix, const float *q, const float *tau, float *out,
 int lvr_dense_attention(lvr_index *ix, const float *q, float *out, void *stream) {
     if (!ix || !q || !out) return LVR_E_INVALID;
     if (!ix->built) return LVR_E_STATE;
-    LVR_HIP(lvr_launch_dense_attention(ix, q, out, static_cast<hipStream_t>(stream)));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    {
+        Timed t(ix, LVR_K_DENSE_PARTIAL, st);
+        LVR_HIP(lvr_launch_dense_partial(ix, q, st));
+    }
+    {
+        Timed t(ix, LVR_K_DENSE_COMBINE, st);
+        LVR_HIP(lvr_launch_combine(ix, out, lvr_dense_splits(ix), st));
+    }
     return LVR_OK;
 }
 
@@ -292,6 +351,45 @@ int lvr_export_index(lvr_index *ix, void *centres, float *radii, int32_t *slot_p
             }
         }
     }
+    return LVR_OK;
+}
+
+int lvr_profile_enable(lvr_index *ix, int max_launches) {
+    if (!ix || max_launches < 0 || max_launches > (1 << 20)) return LVR_E_INVALID;
+    LVR_HIP(hipDeviceSynchronize());
+    prof_free(ix);
+    if (max_launches == 0) return LVR_OK;
+    ix->prof_events = static_cast<hipEvent_t *>(calloc((size_t)2 * max_launches, sizeof(hipEvent_t)));
+    ix->prof_kind = static_cast<uint8_t *>(calloc((size_t)max_launches, 1));
+    if (!ix->prof_events || !ix->prof_kind) {
+        prof_free(ix);
+        return LVR_E_NOMEM;
+    }
+    for (int i = 0; i < 2 * max_launches; ++i) {
+        hipError_t e = hipEventCreate(&ix->prof_events[i]);
+        if (e != hipSuccess) {
+            ix->prof_cap = i;
+            prof_free(ix);
+            return hip_fail(e);
+        }
+    }
+    ix->prof_cap = 2 * max_launches;
+    ix->prof_on = 1;
+    return LVR_OK;
+}
+
+int lvr_profile_read(lvr_index *ix, lvr_profile *out) {
+    if (!ix || !out) return LVR_E_INVALID;
+    memset(out, 0, sizeof(*out));
+    LVR_HIP(hipDeviceSynchronize());
+    for (int s = 0; s + 1 < ix->prof_used; s += 2) {
+        float ms = 0.f;
+        LVR_HIP(hipEventElapsedTime(&ms, ix->prof_events[s], ix->prof_events[s + 1]));
+        const int k = ix->prof_kind[s / 2];
+        out->ms[k] += ms;
+        out->launches[k] += 1;
+    }
+    ix->prof_used = 0;
     return LVR_OK;
 }
 

@@ -237,8 +237,8 @@ hipError_t launch_dense_t(lvr_index *ix, const float *q, float *out, int P, hipS
 
 }  // namespace
 
-hipError_t lvr_launch_sparse_attention(lvr_index *ix, const float *q, const int32_t *idx, const int32_t *count,
-                                       int64_t cap, float *out, hipStream_t st) {
+hipError_t lvr_launch_sparse_partial(lvr_index *ix, const float *q, const int32_t *idx, const int32_t *count,
+                                     int64_t cap, hipStream_t st) {
     const int n_bhq = ix->cfg.batch * ix->cfg.n_q_heads;
     const int P = ix->P;
     dim3 grid((unsigned)P, (unsigned)n_bhq);
@@ -251,20 +251,24 @@ hipError_t lvr_launch_sparse_attention(lvr_index *ix, const float *q, const int3
         hipLaunchKernelGGL(sparse_partial_kernel<lvr_f32_t>, grid, dim3(64), 0, st, ix->K, ix->V, ix->pos_slot, q, idx,
                            count, cap, ix->part_ml, ix->part_o, ix->cap_rows, ix->n_total, P, ix->cfg.n_q_heads,
                            ix->cfg.n_kv_heads, ix->G, qscale);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)n_bhq), dim3(128), 0, st, ix->part_ml, ix->part_o, out, P);
     return hipGetLastError();
 }
 
-hipError_t lvr_launch_dense_attention(lvr_index *ix, const float *q, float *out, hipStream_t st) {
-    const int n_bhq = ix->cfg.batch * ix->cfg.n_q_heads;
+int lvr_dense_splits(const lvr_index *ix) {
     int64_t P = (ix->n_total + 63) / 64;
     if (P > ix->P_dense) P = ix->P_dense;
     if (P < 1) P = 1;
-    hipError_t e = ix->cfg.kv_dtype == LVR_BF16 ? launch_dense_t<lvr_bf16_t>(ix, q, out, (int)P, st)
-                                                : launch_dense_t<lvr_f32_t>(ix, q, out, (int)P, st);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)n_bhq), dim3(128), 0, st, ix->part_ml, ix->part_o, out, (int)P);
+    return (int)P;
+}
+
+hipError_t lvr_launch_dense_partial(lvr_index *ix, const float *q, hipStream_t st) {
+    const int P = lvr_dense_splits(ix);
+    return ix->cfg.kv_dtype == LVR_BF16 ? launch_dense_t<lvr_bf16_t>(ix, q, nullptr, P, st)
+                                        : launch_dense_t<lvr_f32_t>(ix, q, nullptr, P, st);
+}
+
+hipError_t lvr_launch_combine(lvr_index *ix, float *out, int P, hipStream_t st) {
+    const int n_bhq = ix->cfg.batch * ix->cfg.n_q_heads;
+    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)n_bhq), dim3(128), 0, st, ix->part_ml, ix->part_o, out, P);
     return hipGetLastError();
 }

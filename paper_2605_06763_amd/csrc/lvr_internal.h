@@ -42,7 +42,17 @@ struct lvr_index {
     float *part_ml;        // [batch][H_q][Pmax][2]
     float *part_o;         // [batch][H_q][Pmax][d]
     int64_t last_buffer_rows; // buffer rows scanned by the last query (host copy for stats)
-    int64_t last_attn_cap;
+    // optional per-kernel timing (lvr_profile_enable): pairs of events around every launch
+    int prof_on;
+    int prof_used;            // events handed out so far
+    int prof_cap;             // events allocated
+    hipEvent_t *prof_events;  // [prof_cap]
+    uint8_t *prof_kind;       // [prof_cap / 2] kernel kind of each pair
+};
+
+enum lvr_kernel_kind {
+    LVR_K_COPY = 0, LVR_K_BUILD, LVR_K_RESET, LVR_K_PRUNE, LVR_K_FILTER, LVR_K_ATTN_PARTIAL, LVR_K_ATTN_COMBINE,
+    LVR_K_DENSE_PARTIAL, LVR_K_DENSE_COMBINE, LVR_K_COUNT
 };
 
 static inline int lvr_n_bh(const lvr_index *ix) { return ix->cfg.batch * ix->cfg.n_kv_heads; }
@@ -58,9 +68,12 @@ hipError_t lvr_launch_reset(lvr_index *ix, int32_t *out_count, hipStream_t st);
 hipError_t lvr_launch_prune(lvr_index *ix, const float *q, const float *tau, hipStream_t st);
 hipError_t lvr_launch_filter(lvr_index *ix, const float *q, const float *tau, int32_t *out_idx,
                              int32_t *out_count, int64_t cap, hipStream_t st);
-hipError_t lvr_launch_sparse_attention(lvr_index *ix, const float *q, const int32_t *idx, const int32_t *count,
-                                       int64_t cap, float *out, hipStream_t st);
-hipError_t lvr_launch_dense_attention(lvr_index *ix, const float *q, float *out, hipStream_t st);
+hipError_t lvr_launch_sparse_partial(lvr_index *ix, const float *q, const int32_t *idx, const int32_t *count,
+                                     int64_t cap, hipStream_t st);
+hipError_t lvr_launch_dense_partial(lvr_index *ix, const float *q, hipStream_t st);
+hipError_t lvr_launch_combine(lvr_index *ix, float *out, int P, hipStream_t st);
+hipError_t lvr_launch_iota_rows(lvr_index *ix, int64_t row0, int64_t rows, hipStream_t st);
+int lvr_dense_splits(const lvr_index *ix);
 
 #ifdef __HIPCC__
 // ------------------------------------------------------------------------------------------
