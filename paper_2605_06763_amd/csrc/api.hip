@@ -56,7 +56,7 @@ Sizes sizes_of(const lvr_config *c) {
     const int64_t n_bh = (int64_t)c->batch * c->n_kv_heads, n_bhq = (int64_t)c->batch * c->n_q_heads;
     s.cap_rows = (c->capacity + 63) / 64 * 64;
     s.max_groups = s.cap_rows / c->group_size;
-    s.P = c->attn_splits > 0 ? c->attn_splits : 16;
+    s.P = c->attn_splits > 0 ? c->attn_splits : 32;
     int64_t pd = 2048 / n_bh;
     s.P_dense = (int)(pd < 4 ? 4 : (pd > 256 ? 256 : pd));
     s.Pmax = s.P > s.P_dense ? s.P : s.P_dense;
@@ -65,7 +65,7 @@ Sizes sizes_of(const lvr_config *c) {
     s.centres = al((size_t)n_bh * s.max_groups * LVR_D * elt);
     s.radii = al((size_t)n_bh * s.max_groups * c->n_subspaces * sizeof(float));
     s.list = al((size_t)n_bh * s.max_groups * sizeof(int32_t));
-    s.counters = al((size_t)(2 * n_bh + 1) * sizeof(int32_t));
+    s.counters = al(lvr_counter_ints((int)n_bh, (int)n_bhq, s.max_groups) * sizeof(int32_t));
     s.part_ml = al((size_t)n_bhq * s.Pmax * 2 * sizeof(float));
     s.part_o = al((size_t)n_bhq * s.Pmax * LVR_D * sizeof(float));
     s.total = 2 * s.kv + s.centres + s.radii + s.list + s.counters + s.part_ml + s.part_o;
@@ -225,24 +225,42 @@ int lvr_append(lvr_index *ix, const void *k_new, const void *v_new, int64_t m, v
     return LVR_OK;
 }
 
+}  // extern "C"
+
+namespace {
+
+// bound test + exact filter; leaves the set sizes in the internal per-head counters
+int enqueue_query(lvr_index *ix, const float *q, const float *tau, int32_t *out_idx, int64_t cap, hipStream_t st) {
+    if (ix->n_indexed > 0) {   // the bound kernel also clears the per-head counters
+        Timed t(ix, LVR_K_PRUNE, st);
+        LVR_HIP(lvr_launch_prune(ix, q, tau, st));
+    } else {
+        Timed t(ix, LVR_K_RESET, st);
+        LVR_HIP(lvr_launch_reset(ix, st));
+    }
+    {
+        Timed t(ix, LVR_K_FILTER, st);
+        LVR_HIP(lvr_launch_filter(ix, q, tau, out_idx, cap, st));
+    }
+    ix->last_buffer_rows = ix->n_total - ix->n_indexed;
+    return LVR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
 int lvr_query(lvr_index *ix, const float *q, const float *tau, int32_t *out_idx, int32_t *out_count, int64_t cap,
               void *stream) {
     if (!ix || !q || !tau || !out_count || cap < 0 || (cap > 0 && !out_idx)) return LVR_E_INVALID;
     if (!ix->built) return LVR_E_STATE;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    int rc = enqueue_query(ix, q, tau, out_idx, cap, st);
+    if (rc != LVR_OK) return rc;
     {
         Timed t(ix, LVR_K_RESET, st);
-        LVR_HIP(lvr_launch_reset(ix, out_count, st));
+        LVR_HIP(lvr_launch_publish_counts(ix, out_count, st));
     }
-    {
-        Timed t(ix, LVR_K_PRUNE, st);
-        LVR_HIP(lvr_launch_prune(ix, q, tau, st));
-    }
-    {
-        Timed t(ix, LVR_K_FILTER, st);
-        LVR_HIP(lvr_launch_filter(ix, q, tau, out_idx, out_count, cap, st));
-    }
-    ix->last_buffer_rows = ix->n_total - ix->n_indexed;
     return LVR_OK;
 }
 
@@ -253,20 +271,31 @@ int lvr_sparse_attention(lvr_index *ix, const float *q, const int32_t *idx, cons
     hipStream_t st = static_cast<hipStream_t>(stream);
     {
         Timed t(ix, LVR_K_ATTN_PARTIAL, st);
-        LVR_HIP(lvr_launch_sparse_partial(ix, q, idx, count, cap, st));
+        LVR_HIP(lvr_launch_sparse_partial(ix, q, idx, count, 1, cap, st));
     }
     {
         Timed t(ix, LVR_K_ATTN_COMBINE, st);
-        LVR_HIP(lvr_launch_combine(ix, out, ix->P, st));
+        LVR_HIP(lvr_launch_combine(ix, out, ix->P, nullptr, st));
     }
     return LVR_OK;
 }
 
 int lvr_decode_step(lvr_index *ix, const float *q, const float *tau, float *out, int32_t *out_idx, int32_t *out_count,
                     int64_t cap, void *stream) {
-    int rc = lvr_query(ix, q, tau, out_idx, out_count, cap, stream);
+    if (!ix || !q || !tau || !out || !out_count || cap < 0 || (cap > 0 && !out_idx)) return LVR_E_INVALID;
+    if (!ix->built) return LVR_E_STATE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int rc = enqueue_query(ix, q, tau, out_idx, cap, st);
     if (rc != LVR_OK) return rc;
-    return lvr_sparse_attention(ix, q, out_idx, out_count, cap, out, stream);
+    {   // the attention reads the set sizes straight from the internal counters ...
+        Timed t(ix, LVR_K_ATTN_PARTIAL, st);
+        LVR_HIP(lvr_launch_sparse_partial(ix, q, out_idx, lvr_head_count(ix), LVR_CNT_STRIDE, cap, st));
+    }
+    {   // ... and the combine pass hands them to the caller
+        Timed t(ix, LVR_K_ATTN_COMBINE, st);
+        LVR_HIP(lvr_launch_combine(ix, out, ix->P, out_count, st));
+    }
+    return LVR_OK;
 }
 
 int lvr_dense_attention(lvr_index *ix, const float *q, float *out, void *stream) {
@@ -279,7 +308,7 @@ int lvr_dense_attention(lvr_index *ix, const float *q, float *out, void *stream)
     }
     {
         Timed t(ix, LVR_K_DENSE_COMBINE, st);
-        LVR_HIP(lvr_launch_combine(ix, out, lvr_dense_splits(ix), st));
+        LVR_HIP(lvr_launch_combine(ix, out, lvr_dense_splits(ix), nullptr, st));
     }
     return LVR_OK;
 }
@@ -287,10 +316,11 @@ int lvr_dense_attention(lvr_index *ix, const float *q, float *out, void *stream)
 int lvr_get_stats(lvr_index *ix, lvr_stats *out) {
     if (!ix || !out) return LVR_E_INVALID;
     LVR_HIP(hipDeviceSynchronize());
-    const int n_bh = lvr_n_bh(ix);
-    int32_t *host = static_cast<int32_t *>(malloc(sizeof(int32_t) * (2 * n_bh + 1)));
+    const int n_bh = lvr_n_bh(ix), n_bhq = lvr_n_bhq(ix);
+    const size_t n_ints = lvr_counter_ints(n_bh, n_bhq, ix->max_groups);
+    int32_t *host = static_cast<int32_t *>(malloc(sizeof(int32_t) * n_ints));
     if (!host) return LVR_E_NOMEM;
-    hipError_t e = hipMemcpy(host, ix->counters, sizeof(int32_t) * (2 * n_bh + 1), hipMemcpyDeviceToHost);
+    hipError_t e = hipMemcpy(host, ix->counters, sizeof(int32_t) * n_ints, hipMemcpyDeviceToHost);
     if (e != hipSuccess) {
         free(host);
         return hip_fail(e);
@@ -298,11 +328,12 @@ int lvr_get_stats(lvr_index *ix, lvr_stats *out) {
     memset(out, 0, sizeof(*out));
     const int r = ix->cfg.group_size;
     int64_t surv = 0, emitted = 0;
-    for (int i = 0; i < n_bh; ++i) {
-        surv += host[i];
-        emitted += host[n_bh + i];
-    }
-    const int overflow = host[2 * n_bh];
+    for (int i = 0; i < n_bhq; ++i) emitted += host[(size_t)i * LVR_CNT_STRIDE];
+    const int overflow = host[(size_t)n_bhq * LVR_CNT_STRIDE];
+    const int32_t *seg = host + ((size_t)n_bhq + 1) * LVR_CNT_STRIDE;
+    const int64_t max_segs = lvr_max_segs(ix->max_groups);
+    for (int i = 0; i < n_bh; ++i)
+        for (int x = 0; x < ix->n_segs; ++x) surv += seg[(size_t)i * max_segs + x];
     free(host);
     const int64_t row_bytes = (int64_t)LVR_D * (int64_t)ix->elt;
     out->n_keys = ix->n_total;

@@ -1,6 +1,6 @@
 // Attention kernels.
 //
-//  sparse_partial_kernel  attention restricted to a per-head index list (Sec. 2 "Sparse
+//  sparse_attention_kernel attention restricted to a per-head index list (Sec. 2 "Sparse
 //                         Attention"; App. "GPU Sparse Attention Kernel"): the list is cut into
 //                         P splits, each wave gathers its K and V rows (256 B each for bf16),
 //                         keeps running softmax statistics (m, l) and an fp32 accumulator o.
@@ -20,22 +20,28 @@ __device__ __forceinline__ float exp2_safe(float a, float b) {   // 2^(a-b) with
     return (a == -INFINITY) ? 0.f : exp2f(a - b);
 }
 
+// One wave per (query head, split).  The split's positions are fetched with one coalesced load,
+// then rows are gathered 16 at a time (K and V of four row-quads in flight together).  The
+// partials are merged by combine_kernel in a launch of its own: making them visible to a
+// "last wave" inside this launch would take a device-scope fence per wave, which costs more
+// on this multi-die part than the extra launch does.
 template <typename KT>
 __global__ void __launch_bounds__(64)
-sparse_partial_kernel(const void *__restrict__ K, const void *__restrict__ V, const int32_t *__restrict__ pos_slot,
-                      const float *__restrict__ q, const int32_t *__restrict__ idx, const int32_t *__restrict__ count,
-                      int64_t cap, float *__restrict__ part_ml, float *__restrict__ part_o, int64_t cap_rows,
-                      int64_t n_total, int P, int n_q_heads, int n_kv_heads, int G, float qscale) {
+sparse_attention_kernel(const void *__restrict__ K, const void *__restrict__ V, const int32_t *__restrict__ pos_slot,
+                        const float *__restrict__ q, const int32_t *__restrict__ idx,
+                        const int32_t *__restrict__ count, int count_stride, int64_t cap,
+                        float *__restrict__ part_ml, float *__restrict__ part_o, int64_t cap_rows, int64_t n_total,
+                        int P, int n_q_heads, int n_kv_heads, int G, float qscale) {
     const int64_t hq = blockIdx.y;
     const int p = blockIdx.x;
     const int b = (int)(hq / n_q_heads), h = (int)(hq % n_q_heads);
     const int bh = b * n_kv_heads + h / G;
     const int lane = threadIdx.x & 63, sub = lane >> 4, li = lane & 15;
 
-    int64_t cnt = count[hq];
+    int64_t cnt = count[hq * count_stride];
     if (cnt > cap) cnt = cap;
     if (cnt < 0) cnt = 0;
-    const int64_t L = (((cnt + P - 1) / P) + 3) & ~(int64_t)3;
+    const int64_t L = (((cnt + P - 1) / P) + 15) & ~(int64_t)15;
     const int64_t start = (int64_t)p * L;
     const int64_t end = (start + L < cnt) ? start + L : cnt;
 
@@ -52,28 +58,45 @@ sparse_partial_kernel(const void *__restrict__ K, const void *__restrict__ V, co
 
     float m = -INFINITY, l = 0.f, acc[8];
     lvr_zero8(acc);
-    for (int64_t e0 = start; e0 < end; e0 += 4) {          // uniform trip count over the wave
-        const int64_t e = e0 + sub;
-        bool valid = e < end;
-        int64_t pos = valid ? (int64_t)my_idx[e] : 0;
-        valid = valid && pos >= 0 && pos < n_total;
-        if (!valid) pos = 0;
-        const int64_t slot = pslot ? (int64_t)pslot[pos] : pos;
-        float kx[8], vx[8];
-        lvr_load8<KT>(Kb, slot, li, kx);
-        lvr_load8<KT>(Vb, slot, li, vx);
-        float d = 0.f;
+    for (int64_t c0 = start; c0 < end; c0 += 64) {          // uniform over the wave
+        // positions of up to 64 entries, validated and mapped to arena rows once
+        int64_t e = c0 + lane;
+        int myslot = -1;
+        if (e < end) {
+            const int64_t pos = my_idx[e];
+            if (pos >= 0 && pos < n_total) myslot = pslot ? pslot[pos] : (int)pos;
+        }
+        const int chunk = (int)((end - c0 < 64) ? end - c0 : 64);
+        for (int b0 = 0; b0 < chunk; b0 += 16) {
+            lvr_raw8<KT> kr[4], vr[4];
+            int slot[4];
 #pragma unroll
-        for (int c = 0; c < 8; ++c) d += qv[c] * kx[c];
-        float s = lvr_row16_sum(d);
-        s = valid ? s : -INFINITY;
-        const float m_new = fmaxf(m, s);
-        const float alpha = exp2_safe(m, m_new);
-        const float w = exp2_safe(s, m_new);
-        l = l * alpha + w;
+            for (int i = 0; i < 4; ++i) {
+                slot[i] = __shfl(myslot, (b0 + i * 4 + sub) & 63, 64);
+                if (b0 + i * 4 + sub >= chunk) slot[i] = -1;
+                const int64_t sl = slot[i] < 0 ? 0 : slot[i];
+                lvr_load_raw(Kb, sl, li, kr[i]);
+                lvr_load_raw(Vb, sl, li, vr[i]);
+            }
 #pragma unroll
-        for (int c = 0; c < 8; ++c) acc[c] = acc[c] * alpha + w * vx[c];
-        m = m_new;
+            for (int i = 0; i < 4; ++i) {
+                float kx[8], vx[8];
+                lvr_unpack(kr[i], kx);
+                lvr_unpack(vr[i], vx);
+                float d = 0.f;
+#pragma unroll
+                for (int c = 0; c < 8; ++c) d += qv[c] * kx[c];
+                float s = lvr_row16_sum(d);
+                s = (slot[i] >= 0) ? s : -INFINITY;
+                const float m_new = fmaxf(m, s);
+                const float alpha = exp2_safe(m, m_new);
+                const float w = exp2_safe(s, m_new);
+                l = l * alpha + w;
+#pragma unroll
+                for (int c = 0; c < 8; ++c) acc[c] = acc[c] * alpha + w * vx[c];
+                m = m_new;
+            }
+        }
     }
     // merge the four quarter rows of the wave
     float m_all = fmaxf(m, __shfl_xor(m, 16, 64));
@@ -101,9 +124,11 @@ sparse_partial_kernel(const void *__restrict__ K, const void *__restrict__ V, co
 }
 
 __global__ void __launch_bounds__(128)
-combine_kernel(const float *__restrict__ part_ml, const float *__restrict__ part_o, float *__restrict__ out, int P) {
+combine_kernel(const float *__restrict__ part_ml, const float *__restrict__ part_o, float *__restrict__ out, int P,
+               const int32_t *__restrict__ head_count, int32_t *__restrict__ publish_count) {
     const int64_t hq = blockIdx.x;
     const int c = threadIdx.x;
+    if (publish_count && c == 0) publish_count[hq] = head_count[hq * LVR_CNT_STRIDE];
     float M = -INFINITY;
     for (int p = 0; p < P; ++p) M = fmaxf(M, part_ml[(hq * P + p) * 2]);
     float num = 0.f, den = 0.f;
@@ -238,19 +263,19 @@ hipError_t launch_dense_t(lvr_index *ix, const float *q, float *out, int P, hipS
 }  // namespace
 
 hipError_t lvr_launch_sparse_partial(lvr_index *ix, const float *q, const int32_t *idx, const int32_t *count,
-                                     int64_t cap, hipStream_t st) {
-    const int n_bhq = ix->cfg.batch * ix->cfg.n_q_heads;
+                                     int count_stride, int64_t cap, hipStream_t st) {
+    const int n_bhq = lvr_n_bhq(ix);
     const int P = ix->P;
     dim3 grid((unsigned)P, (unsigned)n_bhq);
     const float qscale = ix->sigma * LOG2E;
     if (ix->cfg.kv_dtype == LVR_BF16)
-        hipLaunchKernelGGL(sparse_partial_kernel<lvr_bf16_t>, grid, dim3(64), 0, st, ix->K, ix->V, ix->pos_slot, q, idx,
-                           count, cap, ix->part_ml, ix->part_o, ix->cap_rows, ix->n_total, P, ix->cfg.n_q_heads,
-                           ix->cfg.n_kv_heads, ix->G, qscale);
+        hipLaunchKernelGGL(sparse_attention_kernel<lvr_bf16_t>, grid, dim3(64), 0, st, ix->K, ix->V, ix->pos_slot, q,
+                           idx, count, count_stride, cap, ix->part_ml, ix->part_o, ix->cap_rows, ix->n_total, P,
+                           ix->cfg.n_q_heads, ix->cfg.n_kv_heads, ix->G, qscale);
     else
-        hipLaunchKernelGGL(sparse_partial_kernel<lvr_f32_t>, grid, dim3(64), 0, st, ix->K, ix->V, ix->pos_slot, q, idx,
-                           count, cap, ix->part_ml, ix->part_o, ix->cap_rows, ix->n_total, P, ix->cfg.n_q_heads,
-                           ix->cfg.n_kv_heads, ix->G, qscale);
+        hipLaunchKernelGGL(sparse_attention_kernel<lvr_f32_t>, grid, dim3(64), 0, st, ix->K, ix->V, ix->pos_slot, q,
+                           idx, count, count_stride, cap, ix->part_ml, ix->part_o, ix->cap_rows, ix->n_total, P,
+                           ix->cfg.n_q_heads, ix->cfg.n_kv_heads, ix->G, qscale);
     return hipGetLastError();
 }
 
@@ -267,8 +292,9 @@ hipError_t lvr_launch_dense_partial(lvr_index *ix, const float *q, hipStream_t s
                                         : launch_dense_t<lvr_f32_t>(ix, q, nullptr, P, st);
 }
 
-hipError_t lvr_launch_combine(lvr_index *ix, float *out, int P, hipStream_t st) {
-    const int n_bhq = ix->cfg.batch * ix->cfg.n_q_heads;
-    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)n_bhq), dim3(128), 0, st, ix->part_ml, ix->part_o, out, P);
+hipError_t lvr_launch_combine(lvr_index *ix, float *out, int P, int32_t *publish_count, hipStream_t st) {
+    const int n_bhq = lvr_n_bhq(ix);
+    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)n_bhq), dim3(128), 0, st, ix->part_ml, ix->part_o, out, P,
+                       lvr_head_count(ix), publish_count);
     return hipGetLastError();
 }

@@ -3,141 +3,319 @@
 // L*).  It streams the key rows of the groups that survived the bound test, plus the rows of
 // the not-yet-indexed buffer (Sec. 4.3), computes <q_h, k> in fp32 for the G query heads that
 // share the KV head (each row is read once), and emits the token positions with
-// <q_h, k> >= tau_h into per-head lists using wave-aggregated atomics.
+// <q_h, k> >= tau_h into per-head lists.
 //
-// Work unit: a tile of 16 rows = four wave-wide loads (4 rows each).  Tiles [0, T_s) walk the
-// compacted survivor list (16/r groups per tile), tiles [T_s, T_s + T_b) walk the buffer.
-// The survivor count is read from device memory, so the grid is fixed and waves stride over
-// the tiles; a wave whose first tile is past the end exits at once.
-#include "lvr_internal.h"
+// Work split: one workgroup per segment of the survivor list (the bound test left a count per
+// segment, so no device-wide counter is read), one more per (sequence, KV head) for the buffer.
+// A wave takes tiles of 16 rows, two tiles (8 KiB) in flight.
+//
+// Emission: qualifying positions go to a small per-wave queue in LDS first; a queue is flushed
+// with ONE atomic per head on a counter that owns its cache line, so a launch issues a few
+// thousand atomics spread over many lines instead of one per hit on a few lines (atomics on
+// one line are served serially by the memory side).
+//
+// Two bodies: bf16 rows are scored on the matrix cores (mfma_score.h); fp32 rows (the small
+// single-head workload) on the vector ALU.
+#include "mfma_score.h"
 
 namespace {
 
+constexpr int QCAP = 64;   // queue entries per (wave, head)
+
+struct FilterArgs {
+    const void *K;
+    const int32_t *slot_pos;
+    const float *q;
+    const float *tau;
+    const int32_t *surv_list;
+    const int32_t *seg_count;
+    int32_t *out_idx;
+    int32_t *head_count;     // padded, LVR_CNT_STRIDE ints apart
+    int32_t *overflow;
+    int64_t cap_rows, max_groups, max_segs, n_indexed, n_total, cap;
+    int log2r, n_q_heads, n_kv_heads, G, buffer_dense, n_segs, seg_groups;
+};
+
+// Per-wave emission queue for NH heads.  The lanes with (lane % 16) in [rep_base, rep_base+NH)
+// report head (lane % 16) - rep_base; the four lanes (one per quarter) that report the same
+// head keep identical counts.
+template <int NH>
+struct Emitter {
+    int32_t (*q)[QCAP];   // LDS, [NH][QCAP], private to the wave
+    int count;            // queued entries of my head (0 on lanes that report nothing)
+    int rep_base;
+    int64_t hq_base;      // flat index of head 0
+
+    __device__ __forceinline__ void flush(const FilterArgs &a, int lane, bool reporting) {
+        const int hl = (lane & 15) - rep_base;
+        int base = 0;
+        if (reporting && (lane >> 4) == 0 && count > 0)
+            base = atomicAdd(&a.head_count[(hq_base + hl) * LVR_CNT_STRIDE], count);
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+            const int b_h = __shfl(base, rep_base + h, 64);
+            const int c_h = __shfl(count, rep_base + h, 64);
+            if (lane < c_h) {
+                const int64_t p = (int64_t)b_h + lane;
+                if (p < a.cap)
+                    a.out_idx[(hq_base + h) * a.cap + p] = q[h][lane];
+                else
+                    *a.overflow = 1;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        count = 0;
+    }
+
+    // pred: this lane's (row, head) qualifies; the row's arena slot is held by lane `src_lane`.
+    __device__ __forceinline__ void push(const FilterArgs &a, int lane, bool reporting, bool pred, int my_slot,
+                                         int src_lane, const int32_t *spos) {
+        const uint64_t any = __ballot(pred);
+        if (!any) return;   // wave-uniform
+        const int slot = __shfl(my_slot, src_lane, 64);
+        const uint64_t mh = reporting ? (any & (0x0001000100010001ull << (lane & 15))) : 0ull;
+        if (pred) {
+            const int hl = (lane & 15) - rep_base;
+            q[hl][count + __popcll(mh & ((1ull << lane) - 1ull))] = spos ? spos[slot] : slot;
+        }
+        count += __popcll(mh);
+        if (__ballot(count > QCAP - 4)) flush(a, lane, reporting);
+    }
+};
+
+struct SegWork {
+    int64_t rows;        // rows of surviving groups in this segment (0 for the buffer workgroup)
+    int64_t tiles;
+    const int32_t *list;
+    bool buffer;         // this workgroup scans the buffer rows instead
+    int64_t buf_row0, buf_rows;
+};
+
+__device__ __forceinline__ SegWork seg_work(const FilterArgs &a, int bh) {
+    SegWork w;
+    w.buffer = (int)blockIdx.x >= a.n_segs;
+    if (!w.buffer) {
+        w.rows = (int64_t)a.seg_count[(int64_t)bh * a.max_segs + blockIdx.x] << a.log2r;
+        w.list = a.surv_list + (int64_t)bh * a.max_groups + (int64_t)blockIdx.x * a.seg_groups;
+        w.buf_row0 = w.buf_rows = 0;
+    } else {
+        w.rows = a.n_total - a.n_indexed;
+        w.list = a.surv_list;
+        w.buf_row0 = a.n_indexed;
+        w.buf_rows = w.rows;
+    }
+    w.tiles = (w.rows + 15) >> 4;
+    return w;
+}
+
+// ------------------------------------------------------------------------------------------
+// bf16 rows, matrix cores.  HB = number of 4-head blocks (G <= 4: 1, G = 8: 2).
+// ------------------------------------------------------------------------------------------
+template <int HB>
+__global__ void __launch_bounds__(256)
+filter_mfma_kernel(const FilterArgs a) {
+    __shared__ uint4 s_bq[HB][4][64];
+    __shared__ int32_t s_queue[4][HB][4][QCAP];
+    const int bh = blockIdx.y;
+    const int b = bh / a.n_kv_heads, kvh = bh % a.n_kv_heads;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 15, kq = lane >> 4;
+    const int64_t hq0 = (int64_t)b * a.n_q_heads + kvh * a.G;
+
+    const SegWork w = seg_work(a, bh);
+    if (w.tiles == 0) return;   // uniform over the workgroup
+
+    lvr_bf16x8 bq[HB][4];
+    lvr_build_q_frags_wg<HB>(a.q + hq0 * LVR_D, a.G, 1.0f, s_bq, bq);
+    float my_tau[HB];
+    bool rep[HB];
+    Emitter<4> em[HB];
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) {
+        const int h = hb * 4 + n - 8;
+        rep[hb] = n >= 8 && n < 12 && h < a.G;
+        my_tau[hb] = rep[hb] ? lvr_effective_tau(a.tau[hq0 + h]) : INFINITY;
+        em[hb].q = s_queue[wave][hb];
+        em[hb].count = 0;
+        em[hb].rep_base = 8;
+        em[hb].hq_base = hq0 + hb * 4;
+    }
+    const char *Kb = static_cast<const char *>(a.K) + (int64_t)bh * a.cap_rows * LVR_D * 2;
+    const int32_t *spos = a.slot_pos ? a.slot_pos + (int64_t)bh * a.cap_rows : nullptr;
+    const int rmask = (1 << a.log2r) - 1;
+
+    // two tiles per trip: t and t + 4 (the four waves interleave)
+    for (int64_t t0 = wave; t0 < w.tiles; t0 += 8) {
+        int slot[2], nvalid[2];
+        int32_t gid[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int64_t t = t0 + 4 * u;
+            int64_t rowidx = t * 16 + n;
+            const int64_t left = w.rows - t * 16;
+            nvalid[u] = left <= 0 ? 0 : (left < 16 ? (int)left : 16);
+            if (rowidx >= w.rows) rowidx = 0;
+            gid[u] = w.buffer ? 0 : w.list[rowidx >> a.log2r];
+            slot[u] = (int)rowidx;   // finished below once gid has arrived
+        }
+        uint4 av[2][4];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int rowidx = slot[u];
+            slot[u] = w.buffer ? (int)(w.buf_row0 + rowidx) : (int)(((int64_t)gid[u] << a.log2r) + (rowidx & rmask));
+            lvr_load_a_frags(Kb, slot[u], av[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            if (nvalid[u] == 0) continue;   // wave-uniform
+#pragma unroll
+            for (int hb = 0; hb < HB; ++hb) {
+                const lvr_f32x4 s = lvr_score_tile(av[u], bq[hb]);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int trow = 4 * kq + j;
+                    const bool pred = trow < nvalid[u] && rep[hb] &&
+                                      (s[j] >= my_tau[hb] || (w.buffer && a.buffer_dense));
+                    em[hb].push(a, lane, rep[hb], pred, slot[u], trow, spos);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb)
+        if (__ballot(em[hb].count > 0)) em[hb].flush(a, lane, rep[hb]);
+}
+
+// ------------------------------------------------------------------------------------------
+// Generic rows (fp32 storage), vector ALU: 16 lanes per row, four rows per wave-wide load.
+// ------------------------------------------------------------------------------------------
 template <typename KT, int G>
 __global__ void __launch_bounds__(256)
-filter_kernel(const void *__restrict__ K, const int32_t *__restrict__ slot_pos, const float *__restrict__ q,
-              const float *__restrict__ tau, const int32_t *__restrict__ surv_list,
-              const int32_t *__restrict__ surv_count, int32_t *__restrict__ out_idx, int32_t *__restrict__ out_count,
-              int32_t *__restrict__ emit_count, int32_t *__restrict__ overflow, int64_t cap_rows, int64_t max_groups,
-              int64_t n_indexed, int64_t n_total, int log2r, int64_t cap, int n_q_heads, int n_kv_heads,
-              int buffer_dense) {
+filter_valu_kernel(const FilterArgs a) {
+    __shared__ int32_t s_queue[4][G][QCAP];
     const int bh = blockIdx.y;
-    const int b = bh / n_kv_heads, kvh = bh % n_kv_heads;
+    const int b = bh / a.n_kv_heads, kvh = bh % a.n_kv_heads;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sub = lane >> 4, li = lane & 15;
-    const int64_t hq0 = (int64_t)b * n_q_heads + kvh * G;
+    const int64_t hq0 = (int64_t)b * a.n_q_heads + kvh * G;
+
+    const SegWork w = seg_work(a, bh);
+    if (w.tiles == 0) return;
 
     float qv[G][8];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
-        const float *qh = q + (hq0 + h) * LVR_D + li * 8;
+        const float *qh = a.q + (hq0 + h) * LVR_D + li * 8;
 #pragma unroll
         for (int e = 0; e < 8; ++e) qv[h][e] = qh[e];
     }
-    // lane li < G reports head li
-    const float my_tau = (li < G) ? lvr_effective_tau(tau[hq0 + li]) : INFINITY;
+    const bool rep = li < G;
+    const float my_tau = rep ? lvr_effective_tau(a.tau[hq0 + li]) : INFINITY;
+    Emitter<G> em;
+    em.q = s_queue[wave];
+    em.count = 0;
+    em.rep_base = 0;
+    em.hq_base = hq0;
+    const char *Kb = static_cast<const char *>(a.K) + (int64_t)bh * a.cap_rows * LVR_D * sizeof(KT);
+    const int32_t *spos = a.slot_pos ? a.slot_pos + (int64_t)bh * a.cap_rows : nullptr;
+    const int rmask = (1 << a.log2r) - 1;
 
-    const int64_t rows_surv = (int64_t)surv_count[bh] << log2r;
-    const int64_t surv_tiles = (rows_surv + 15) >> 4;
-    const int64_t buf_tiles = (n_total - n_indexed + 15) >> 4;
-    const int64_t total_tiles = surv_tiles + buf_tiles;
-    const char *Kb = static_cast<const char *>(K) + (int64_t)bh * cap_rows * LVR_D * sizeof(KT);
-    const int32_t *list = surv_list + (int64_t)bh * max_groups;
-    const int32_t *spos = slot_pos ? slot_pos + (int64_t)bh * cap_rows : nullptr;
-    const int rmask = (1 << log2r) - 1;
-
-    for (int64_t t = (int64_t)blockIdx.x * 4 + wave; t < total_tiles; t += (int64_t)gridDim.x * 4) {
-        const bool in_buf = t >= surv_tiles;
-        int64_t slot[4];
+    for (int64_t t = wave; t < w.tiles; t += 4) {
+        int slot[4];
         bool valid[4];
-        float x[4][8];
+        int32_t gid[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int ri = i * 4 + sub;
-            if (!in_buf) {
-                const int64_t rowidx = t * 16 + ri;
-                valid[i] = rowidx < rows_surv;
-                const int32_t gid = valid[i] ? list[rowidx >> log2r] : 0;
-                slot[i] = ((int64_t)gid << log2r) + (rowidx & rmask);
-            } else {
-                slot[i] = n_indexed + (t - surv_tiles) * 16 + ri;
-                valid[i] = slot[i] < n_total;
-                if (!valid[i]) slot[i] = 0;
-            }
+            int64_t rowidx = t * 16 + i * 4 + sub;
+            valid[i] = rowidx < w.rows;
+            if (!valid[i]) rowidx = 0;
+            gid[i] = w.buffer ? 0 : w.list[rowidx >> a.log2r];
+            slot[i] = (int)rowidx;
+        }
+        lvr_raw8<KT> raw[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int rowidx = slot[i];
+            slot[i] = w.buffer ? (int)(w.buf_row0 + rowidx) : (int)(((int64_t)gid[i] << a.log2r) + (rowidx & rmask));
+            lvr_load_raw(Kb, slot[i], li, raw[i]);
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) lvr_load8<KT>(Kb, slot[i], li, x[i]);
-
-#pragma unroll
         for (int i = 0; i < 4; ++i) {
+            float x[8];
+            lvr_unpack(raw[i], x);
             float mine = 0.f;
 #pragma unroll
             for (int h = 0; h < G; ++h) {
                 float p = 0.f;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) p += qv[h][e] * x[i][e];
+                for (int e = 0; e < 8; ++e) p += qv[h][e] * x[e];
                 const float s = lvr_row16_sum(p);
                 mine = (li == h) ? s : mine;
             }
-            const bool pred = valid[i] && li < G && (mine >= my_tau || (in_buf && buffer_dense));
-            const uint64_t any = __ballot(pred);
-            if (any) {   // wave-uniform
-                // lanes li, li+16, li+32, li+48 hold the four rows' results for head li
-                const uint64_t mh = (li < G) ? (any & (0x0001000100010001ull << li)) : 0ull;
-                const int cnt = __popcll(mh);
-                const int leader = cnt ? (__ffsll((unsigned long long)mh) - 1) : lane;
-                int base = 0;
-                if (cnt && lane == leader) {
-                    base = atomicAdd(&out_count[hq0 + li], cnt);
-                    atomicAdd(&emit_count[bh], cnt);
-                }
-                base = __shfl(base, leader, 64);
-                if (pred) {
-                    const int64_t p = base + __popcll(mh & ((1ull << lane) - 1ull));
-                    if (p < cap)
-                        out_idx[(hq0 + li) * cap + p] = spos ? spos[slot[i]] : (int32_t)slot[i];
-                    else
-                        *overflow = 1;
-                }
-            }
+            const bool pred = valid[i] && rep && (mine >= my_tau || (w.buffer && a.buffer_dense));
+            em.push(a, lane, rep, pred, slot[i], lane, spos);   // the reporting lane holds the row's slot itself
         }
     }
+    if (__ballot(em.count > 0)) em.flush(a, lane, rep);
 }
 
-template <typename KT>
-hipError_t launch_filter_t(lvr_index *ix, const float *q, const float *tau, int32_t *out_idx, int32_t *out_count,
-                           int64_t cap, hipStream_t st) {
-    const int64_t max_tiles = (ix->n_total + 15) / 16 + 1;
-    int64_t gx = (max_tiles + 15) / 16;   // 4 waves x ~4 tiles each when every group survives
-    if (gx < 1) gx = 1;
-    if (gx > 2048) gx = 2048;
-    dim3 grid((unsigned)gx, (unsigned)lvr_n_bh(ix));
-    int log2r = 0;
-    while ((1 << log2r) < ix->cfg.group_size) ++log2r;
-    const int dense = (ix->cfg.flags & LVR_ATTEND_BUFFER_DENSE) ? 1 : 0;
-#define LVR_FILTER_CASE(GG)                                                                                        \
-    case GG:                                                                                                       \
-        hipLaunchKernelGGL((filter_kernel<KT, GG>), grid, dim3(256), 0, st, ix->K, ix->slot_pos, q, tau,           \
-                           ix->surv_list, lvr_surv_count(ix), out_idx, out_count, lvr_emit_count(ix),              \
-                           lvr_overflow_flag(ix), ix->cap_rows, ix->max_groups, ix->n_indexed, ix->n_total, log2r, \
-                           cap, ix->cfg.n_q_heads, ix->cfg.n_kv_heads, dense);                                     \
-        break;
-    switch (ix->G) {
-        LVR_FILTER_CASE(1)
-        LVR_FILTER_CASE(2)
-        LVR_FILTER_CASE(4)
-        LVR_FILTER_CASE(8)
-        default: return hipErrorInvalidValue;
-    }
-#undef LVR_FILTER_CASE
-    return hipGetLastError();
+__global__ void publish_counts_kernel(const int32_t *__restrict__ head_count, int32_t *__restrict__ out_count, int n_bhq) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_bhq) out_count[i] = head_count[(size_t)i * LVR_CNT_STRIDE];
 }
 
 }  // namespace
 
-hipError_t lvr_launch_filter(lvr_index *ix, const float *q, const float *tau, int32_t *out_idx, int32_t *out_count,
-                             int64_t cap, hipStream_t st) {
-    if (ix->n_total <= 0) return hipSuccess;
-    return ix->cfg.kv_dtype == LVR_BF16 ? launch_filter_t<lvr_bf16_t>(ix, q, tau, out_idx, out_count, cap, st)
-                                        : launch_filter_t<lvr_f32_t>(ix, q, tau, out_idx, out_count, cap, st);
+hipError_t lvr_launch_filter(lvr_index *ix, const float *q, const float *tau, int32_t *out_idx, int64_t cap,
+                             hipStream_t st) {
+    FilterArgs a;
+    a.K = ix->K;
+    a.slot_pos = ix->slot_pos;
+    a.q = q;
+    a.tau = tau;
+    a.surv_list = ix->surv_list;
+    a.seg_count = lvr_seg_count(ix);
+    a.out_idx = out_idx;
+    a.head_count = lvr_head_count(ix);
+    a.overflow = lvr_overflow_flag(ix);
+    a.cap_rows = ix->cap_rows;
+    a.max_groups = ix->max_groups;
+    a.max_segs = lvr_max_segs(ix->max_groups);
+    a.n_indexed = ix->n_indexed;
+    a.n_total = ix->n_total;
+    a.cap = cap;
+    a.log2r = 0;
+    while ((1 << a.log2r) < ix->cfg.group_size) ++a.log2r;
+    a.n_q_heads = ix->cfg.n_q_heads;
+    a.n_kv_heads = ix->cfg.n_kv_heads;
+    a.G = ix->G;
+    a.buffer_dense = (ix->cfg.flags & LVR_ATTEND_BUFFER_DENSE) ? 1 : 0;
+    a.n_segs = ix->n_indexed > 0 ? ix->n_segs : 0;
+    a.seg_groups = ix->seg_groups;
+    const int has_buffer = ix->n_total > ix->n_indexed ? 1 : 0;
+    if (a.n_segs + has_buffer == 0) return hipSuccess;
+    dim3 grid((unsigned)(a.n_segs + has_buffer), (unsigned)lvr_n_bh(ix));
+    if (ix->cfg.kv_dtype == LVR_BF16) {
+        if (ix->G <= 4)
+            hipLaunchKernelGGL(filter_mfma_kernel<1>, grid, dim3(256), 0, st, a);
+        else
+            hipLaunchKernelGGL(filter_mfma_kernel<2>, grid, dim3(256), 0, st, a);
+    } else {
+        switch (ix->G) {
+            case 1: hipLaunchKernelGGL((filter_valu_kernel<lvr_f32_t, 1>), grid, dim3(256), 0, st, a); break;
+            case 2: hipLaunchKernelGGL((filter_valu_kernel<lvr_f32_t, 2>), grid, dim3(256), 0, st, a); break;
+            case 4: hipLaunchKernelGGL((filter_valu_kernel<lvr_f32_t, 4>), grid, dim3(256), 0, st, a); break;
+            case 8: hipLaunchKernelGGL((filter_valu_kernel<lvr_f32_t, 8>), grid, dim3(256), 0, st, a); break;
+            default: return hipErrorInvalidValue;
+        }
+    }
+    return hipGetLastError();
+}
+
+hipError_t lvr_launch_publish_counts(lvr_index *ix, int32_t *out_count, hipStream_t st) {
+    const int n_bhq = lvr_n_bhq(ix);
+    hipLaunchKernelGGL(publish_counts_kernel, dim3((n_bhq + 255) / 256), dim3(256), 0, st, lvr_head_count(ix), out_count,
+                       n_bhq);
+    return hipGetLastError();
 }

@@ -37,8 +37,10 @@ struct lvr_index {
     int32_t *slot_pos;     // [batch][H_kv][cap_rows] token position of arena row (TREE grouping), else NULL
     int32_t *pos_slot;     // inverse map, or NULL
     // work space (device)
-    int32_t *surv_list;    // [batch][H_kv][max_groups]
-    int32_t *counters;     // [batch*H_kv] surviving groups, then [batch*H_kv] emitted, then [1] overflow
+    int32_t *surv_list;    // [batch][H_kv][max_groups]: segment x owns entries [x*seg_groups, (x+1)*seg_groups)
+    int32_t *counters;     // see lvr_head_count / lvr_overflow_flag / lvr_seg_count
+    int seg_groups;        // groups per segment used by the last bound test
+    int n_segs;            // segments per (sequence, KV head) filled by the last bound test (0: none)
     float *part_ml;        // [batch][H_q][Pmax][2]
     float *part_o;         // [batch][H_q][Pmax][d]
     int64_t last_buffer_rows; // buffer rows scanned by the last query (host copy for stats)
@@ -56,23 +58,42 @@ enum lvr_kernel_kind {
 };
 
 static inline int lvr_n_bh(const lvr_index *ix) { return ix->cfg.batch * ix->cfg.n_kv_heads; }
-static inline int32_t *lvr_surv_count(const lvr_index *ix) { return ix->counters; }
-static inline int32_t *lvr_emit_count(const lvr_index *ix) { return ix->counters + lvr_n_bh(ix); }
-static inline int32_t *lvr_overflow_flag(const lvr_index *ix) { return ix->counters + 2 * lvr_n_bh(ix); }
+static inline int lvr_n_bhq(const lvr_index *ix) { return ix->cfg.batch * ix->cfg.n_q_heads; }
+
+// Device counters.  Atomics that hit one 128-byte line are served one after the other
+// (about 12 ns each on this part), so every counter that takes atomics owns a whole line.
+#define LVR_CNT_STRIDE 32   // ints per counter slot (128 bytes)
+#define LVR_MIN_SEG_GROUPS 128
+// per query head: size of the retrieved set of the running query (padded)
+static inline int32_t *lvr_head_count(const lvr_index *ix) { return ix->counters; }
+static inline int32_t *lvr_overflow_flag(const lvr_index *ix) { return ix->counters + (size_t)lvr_n_bhq(ix) * LVR_CNT_STRIDE; }
+// per (sequence, KV head, segment): surviving groups of the segment (plain stores, no atomics)
+static inline int32_t *lvr_seg_count(const lvr_index *ix) { return ix->counters + ((size_t)lvr_n_bhq(ix) + 1) * LVR_CNT_STRIDE; }
+static inline int64_t lvr_max_segs(int64_t max_groups) { return max_groups / LVR_MIN_SEG_GROUPS + 2; }
+static inline size_t lvr_counter_ints(int n_bh, int n_bhq, int64_t max_groups) {
+    return ((size_t)n_bhq + 1) * LVR_CNT_STRIDE + (size_t)n_bh * (size_t)lvr_max_segs(max_groups);
+}
 
 // ---- launchers (each returns a hipError_t from hipGetLastError after the launch) ----
 hipError_t lvr_launch_copy_rows(lvr_index *ix, const void *src, const int64_t strides[3], void *dst_base,
                                 int64_t dst_row0, int64_t rows, hipStream_t st);
 hipError_t lvr_launch_build_groups(lvr_index *ix, int64_t g0, int64_t g1, hipStream_t st);
-hipError_t lvr_launch_reset(lvr_index *ix, int32_t *out_count, hipStream_t st);
-hipError_t lvr_launch_prune(lvr_index *ix, const float *q, const float *tau, hipStream_t st);
-hipError_t lvr_launch_filter(lvr_index *ix, const float *q, const float *tau, int32_t *out_idx,
-                             int32_t *out_count, int64_t cap, hipStream_t st);
-hipError_t lvr_launch_sparse_partial(lvr_index *ix, const float *q, const int32_t *idx, const int32_t *count,
-                                     int64_t cap, hipStream_t st);
-hipError_t lvr_launch_dense_partial(lvr_index *ix, const float *q, hipStream_t st);
-hipError_t lvr_launch_combine(lvr_index *ix, float *out, int P, hipStream_t st);
 hipError_t lvr_launch_iota_rows(lvr_index *ix, int64_t row0, int64_t rows, hipStream_t st);
+// clears the per-head counters (used when there is no index to prune)
+hipError_t lvr_launch_reset(lvr_index *ix, hipStream_t st);
+// bound test; clears the per-head counters; fills the per-segment survivor lists
+hipError_t lvr_launch_prune(lvr_index *ix, const float *q, const float *tau, hipStream_t st);
+// exact check on survivors and buffer; fills out_idx and the internal per-head counters
+hipError_t lvr_launch_filter(lvr_index *ix, const float *q, const float *tau, int32_t *out_idx, int64_t cap,
+                             hipStream_t st);
+// internal per-head counters -> caller's array
+hipError_t lvr_launch_publish_counts(lvr_index *ix, int32_t *out_count, hipStream_t st);
+// partial softmax per (head, split); count is read with the given stride (1 = caller's array)
+hipError_t lvr_launch_sparse_partial(lvr_index *ix, const float *q, const int32_t *idx, const int32_t *count,
+                                     int count_stride, int64_t cap, hipStream_t st);
+hipError_t lvr_launch_dense_partial(lvr_index *ix, const float *q, hipStream_t st);
+// merge P partials; if publish_count is not NULL also copies the internal per-head counters to it
+hipError_t lvr_launch_combine(lvr_index *ix, float *out, int P, int32_t *publish_count, hipStream_t st);
 int lvr_dense_splits(const lvr_index *ix);
 
 #ifdef __HIPCC__
@@ -111,6 +132,31 @@ __device__ __forceinline__ void lvr_load8<lvr_f32_t>(const void *base, int64_t r
     float4 a = p[0], b = p[1];
     x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
     x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+}
+
+// Two-step form of lvr_load8: issue the load now, unpack later, so that a run of loads can be
+// put in flight before the first use.
+template <typename KT> struct lvr_raw8;
+template <> struct lvr_raw8<lvr_bf16_t> { uint4 a; };
+template <> struct lvr_raw8<lvr_f32_t> { float4 a, b; };
+
+__device__ __forceinline__ void lvr_load_raw(const void *base, int64_t row, int li, lvr_raw8<lvr_bf16_t> &r) {
+    r.a = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(base) + row * LVR_D)[li];
+}
+__device__ __forceinline__ void lvr_load_raw(const void *base, int64_t row, int li, lvr_raw8<lvr_f32_t> &r) {
+    const float4 *p = reinterpret_cast<const float4 *>(static_cast<const float *>(base) + row * LVR_D) + 2 * li;
+    r.a = p[0];
+    r.b = p[1];
+}
+__device__ __forceinline__ void lvr_unpack(const lvr_raw8<lvr_bf16_t> &r, float (&x)[8]) {
+    x[0] = lvr_bf16_lo(r.a.x); x[1] = lvr_bf16_hi(r.a.x);
+    x[2] = lvr_bf16_lo(r.a.y); x[3] = lvr_bf16_hi(r.a.y);
+    x[4] = lvr_bf16_lo(r.a.z); x[5] = lvr_bf16_hi(r.a.z);
+    x[6] = lvr_bf16_lo(r.a.w); x[7] = lvr_bf16_hi(r.a.w);
+}
+__device__ __forceinline__ void lvr_unpack(const lvr_raw8<lvr_f32_t> &r, float (&x)[8]) {
+    x[0] = r.a.x; x[1] = r.a.y; x[2] = r.a.z; x[3] = r.a.w;
+    x[4] = r.b.x; x[5] = r.b.y; x[6] = r.b.z; x[7] = r.b.w;
 }
 
 __device__ __forceinline__ void lvr_zero8(float (&x)[8]) {

@@ -1,0 +1,103 @@
+// Scoring a tile of 16 bf16 rows (keys or centres) against the query heads of one KV head on
+// the matrix cores.
+//
+// The scores S[row][head] = <q_head, row> of the G query heads that share a KV head form a
+// skinny dense contraction  [16 rows x 128] . [128 x heads].  On the vector ALU this costs a
+// multiply-add per element and head plus a 16-lane reduction per row and head, which at HBM
+// rate would take most of the ALU issue slots; one v_mfma_f32_16x16x32_bf16 per 32 coordinates
+// does the same work in a handful of cycles.
+//
+// Full fp32 query precision on a bf16 matrix core: each fp32 q value is split exactly into
+// three bf16 terms  q = hi + mid + lo  (8 + 8 + 8 significant bits).  The three terms of four
+// heads fill 12 of the 16 columns of the B operand: column n = part * 4 + head.  Products of
+// two bf16 numbers are exact in fp32 and the unit accumulates in fp32, so summing the three
+// columns of a head gives <q, row> to fp32 accuracy.
+//
+// Operand layout of v_mfma_f32_16x16x32_bf16 (lane l of the wave, j = 0..7):
+//   A[i = l % 16][k = 8 * (l / 16) + j]      one 16-byte load per lane straight from a row
+//   B[k = 8 * (l / 16) + j][n = l % 16]      built once per wave from q
+//   D[i = 4 * (l / 16) + j'][n = l % 16]     j' = 0..3
+// After  d + row_shr:4(d) + row_shr:8(d)  the lanes with n in [8, 12) hold the finished score of
+// head n - 8 for rows 4 * (l / 16) + j'.
+#pragma once
+#include "lvr_internal.h"
+
+#ifdef __HIPCC__
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 lvr_bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float lvr_f32x4;
+
+// Exact three-way split of an fp32 value into bf16 bit patterns (part 0 = leading term).
+__device__ __forceinline__ uint32_t lvr_split_part(float x, int part) {
+    const uint32_t hi = lvr_f32_to_bf16_bits(x);
+    const float r1 = x - __uint_as_float(hi << 16);
+    const uint32_t mid = lvr_f32_to_bf16_bits(r1);
+    const float r2 = r1 - __uint_as_float(mid << 16);
+    const uint32_t lo = lvr_f32_to_bf16_bits(r2);
+    return part == 0 ? hi : (part == 1 ? mid : lo);
+}
+
+// One B fragment: head block hb (heads hb*4 .. hb*4+3 of the KV group, those >= G are zero),
+// coordinates kk*32 .. kk*32+31.  `scale` multiplies q first (1 for the range query;
+// sigma*log2(e) for attention logits).
+__device__ __forceinline__ void lvr_build_q_frag_one(const float *__restrict__ q_group, int G, int hb, int kk,
+                                                     float scale, lvr_bf16x8 &out) {
+    const int lane = threadIdx.x & 63;
+    const int n = lane & 15, kq = lane >> 4;
+    const int part = n >> 2, h = hb * 4 + (n & 3);
+    const bool live = part < 3 && h < G;
+    uint32_t w[8];
+    const float *src = q_group + (int64_t)(live ? h : 0) * LVR_D + kk * 32 + kq * 8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) w[e] = live ? lvr_split_part(src[e] * scale, part) : 0u;
+    uint4 packed = make_uint4(w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16));
+    out = __builtin_bit_cast(lvr_bf16x8, packed);
+}
+
+// All B fragments of a KV group, built once per 256-thread workgroup: wave w builds the
+// fragment of coordinates w*32 .. w*32+31 for every head block, the four waves exchange them
+// through LDS.  Contains a __syncthreads(): every thread of the workgroup must call it.
+template <int HB>
+__device__ __forceinline__ void lvr_build_q_frags_wg(const float *__restrict__ q_group, int G, float scale,
+                                                     uint4 (&s_bq)[HB][4][64], lvr_bf16x8 (&bq)[HB][4]) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) {
+        lvr_bf16x8 f;
+        lvr_build_q_frag_one(q_group, G, hb, wave, scale, f);
+        s_bq[hb][wave][lane] = __builtin_bit_cast(uint4, f);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) bq[hb][kk] = __builtin_bit_cast(lvr_bf16x8, s_bq[hb][kk][lane]);
+}
+
+// The four 16-byte pieces of the A operand for row `row` (lane's row = lane % 16):
+// coordinates kk*32 + 8*(lane/16) .. +7 for kk = 0..3.
+__device__ __forceinline__ void lvr_load_a_frags(const char *__restrict__ base, int64_t row, uint4 (&a)[4]) {
+    const int kq = (threadIdx.x & 63) >> 4;
+    const uint4 *p = reinterpret_cast<const uint4 *>(base + row * (LVR_D * 2)) + kq;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) a[kk] = p[kk * 4];
+}
+
+// D = A . B over the 128 coordinates, then the three query parts are added up.
+// Result valid in lanes with (lane % 16) in [8, 12): score of head hb*4 + lane%16 - 8 for rows
+// 4*(lane/16) + j, j = 0..3.
+__device__ __forceinline__ lvr_f32x4 lvr_score_tile(const uint4 (&a)[4], const lvr_bf16x8 (&bq)[4]) {
+    lvr_f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lvr_bf16x8, a[kk]), bq[kk], acc, 0, 0, 0);
+    lvr_f32x4 s;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float v = acc[j];
+        float t = v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x114, 0xf, 0xf, true));
+        t += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x118, 0xf, 0xf, true));
+        s[j] = t;
+    }
+    return s;
+}
+#endif
