@@ -205,21 +205,22 @@ def main():
     copy_gbs = 10 * 2 * src.numel() / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
     del src, dst
 
-    # ---- algorithmic bytes of the dominant kernel (exact filter): 256 B per scanned key ----
+    # ---- algorithmic bytes of the dominant kernel ----
+    # fused range-query kernel (bound test + exact check): per (sequence, KV head)
+    #   groups * (d*2 + S*4) bytes of centres and radii  +  keys_scanned * d*2 bytes of key rows
     n_bh = B * Hkv
     filt = kern.get("filter", dict(avg_us=float("nan")))
-    filter_bytes = st["bytes_keys"]                      # keys_scanned * d * 2 for one launch
-    prune_bytes = st["bytes_index"]
-    achieved = filter_bytes / (filt["avg_us"] * 1e-6) / 1e9
+    query_bytes = st["bytes_index"] + st["bytes_keys"]
+    achieved = query_bytes / (filt["avg_us"] * 1e-6) / 1e9
     step_bytes = st["bytes_index"] + st["bytes_keys"] + st["bytes_attention"]
-    roofline = dict(bound="hbm", kernel="filter_kernel", achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
-                    bytes_per_launch=int(filter_bytes), avg_launch_us=round(filt["avg_us"], 2))
+    roofline = dict(bound="hbm", kernel="query_fused_kernel", achieved=round(achieved, 1), peak=HBM_PEAK_GBS,
+                    unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
+                    bytes_per_launch=int(query_bytes), avg_launch_us=round(filt["avg_us"], 2))
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
             tj = json.load(open(tpath))
-            roofline["traffic"] = tj.get(f"config{cid}", {}).get("filter_kernel_bytes")
+            roofline["traffic"] = tj.get(f"config{cid}", {}).get("query_fused_kernel_bytes")
         except Exception:
             pass
 

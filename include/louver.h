@@ -46,7 +46,11 @@ enum lvr_flags {
     /* Keys not yet in the index (the buffer of Sec. 4.3 "Dynamic Updates") are retrieved
      * whatever their score, as in Alg. 3 / Alg. 4's  K[L*] ∪ B.  Default (flag clear): they are
      * scored exactly and thresholded like every other key, so the result is Problem 1's set. */
-    LVR_ATTEND_BUFFER_DENSE = 1u
+    LVR_ATTEND_BUFFER_DENSE = 1u,
+    /* Run the bound test and the exact check as two kernel launches (survivor list through
+     * HBM) instead of the fused single launch.  Same results; lets the two stages be timed
+     * apart.  fp32 caches always run this way. */
+    LVR_SEPARATE_KERNELS = 2u
 };
 
 enum lvr_error {

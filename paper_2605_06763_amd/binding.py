@@ -16,6 +16,7 @@ from .build import LIB_PATH
 LVR_BF16, LVR_F32 = 0, 1
 LVR_GROUP_CONTIGUOUS, LVR_GROUP_TREE = 0, 1
 LVR_ATTEND_BUFFER_DENSE = 1
+LVR_SEPARATE_KERNELS = 2
 LVR_OK, LVR_E_INVALID, LVR_E_UNSUPPORTED, LVR_E_CAPACITY = 0, -1, -2, -3
 LVR_E_OVERFLOW, LVR_E_HIP, LVR_E_NOMEM, LVR_E_STATE = -4, -5, -6, -7
 

@@ -231,14 +231,22 @@ namespace {
 
 // bound test + exact filter; leaves the set sizes in the internal per-head counters
 int enqueue_query(lvr_index *ix, const float *q, const float *tau, int32_t *out_idx, int64_t cap, hipStream_t st) {
-    if (ix->n_indexed > 0) {   // the bound kernel also clears the per-head counters
-        Timed t(ix, LVR_K_PRUNE, st);
-        LVR_HIP(lvr_launch_prune(ix, q, tau, st));
-    } else {
+    const bool fused = ix->cfg.kv_dtype == LVR_BF16 && !(ix->cfg.flags & LVR_SEPARATE_KERNELS);
+    if (ix->counters_dirty) {   // an earlier query never published its counts: start from zero again
         Timed t(ix, LVR_K_RESET, st);
         LVR_HIP(lvr_launch_reset(ix, st));
     }
-    {
+    ix->counters_dirty = 1;
+    if (fused) {
+        Timed t(ix, LVR_K_FILTER, st);
+        LVR_HIP(lvr_launch_query_fused(ix, q, tau, out_idx, cap, st));
+    } else {
+        if (ix->n_indexed > 0) {
+            Timed t(ix, LVR_K_PRUNE, st);
+            LVR_HIP(lvr_launch_prune(ix, q, tau, st));
+        } else {
+            ix->n_segs = 0;
+        }
         Timed t(ix, LVR_K_FILTER, st);
         LVR_HIP(lvr_launch_filter(ix, q, tau, out_idx, cap, st));
     }
@@ -261,6 +269,7 @@ int lvr_query(lvr_index *ix, const float *q, const float *tau, int32_t *out_idx,
         Timed t(ix, LVR_K_RESET, st);
         LVR_HIP(lvr_launch_publish_counts(ix, out_count, st));
     }
+    ix->counters_dirty = 0;
     return LVR_OK;
 }
 
@@ -295,6 +304,7 @@ int lvr_decode_step(lvr_index *ix, const float *q, const float *tau, float *out,
         Timed t(ix, LVR_K_ATTN_COMBINE, st);
         LVR_HIP(lvr_launch_combine(ix, out, ix->P, out_count, st));
     }
+    ix->counters_dirty = 0;
     return LVR_OK;
 }
 
@@ -328,9 +338,10 @@ int lvr_get_stats(lvr_index *ix, lvr_stats *out) {
     memset(out, 0, sizeof(*out));
     const int r = ix->cfg.group_size;
     int64_t surv = 0, emitted = 0;
-    for (int i = 0; i < n_bhq; ++i) emitted += host[(size_t)i * LVR_CNT_STRIDE];
+    const int32_t *stat = host + ((size_t)n_bhq + 1) * LVR_CNT_STRIDE;
+    for (int i = 0; i < n_bhq; ++i) emitted += stat[i];
     const int overflow = host[(size_t)n_bhq * LVR_CNT_STRIDE];
-    const int32_t *seg = host + ((size_t)n_bhq + 1) * LVR_CNT_STRIDE;
+    const int32_t *seg = stat + n_bhq;
     const int64_t max_segs = lvr_max_segs(ix->max_groups);
     for (int i = 0; i < n_bh; ++i)
         for (int x = 0; x < ix->n_segs; ++x) surv += seg[(size_t)i * max_segs + x];

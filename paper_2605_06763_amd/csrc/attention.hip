@@ -123,23 +123,57 @@ sparse_attention_kernel(const void *__restrict__ K, const void *__restrict__ V, 
     }
 }
 
-__global__ void __launch_bounds__(128)
+// Merge of the P partial triples of one query head.  512 threads: the weights
+// w_p = 2^(m_p - M) are computed once into LDS, then thread (slice s, channel c) sums every
+// fourth partial of channel c and the four slices are added through LDS.
+constexpr int COMBINE_MAX_P = 256;
+
+__global__ void __launch_bounds__(512)
 combine_kernel(const float *__restrict__ part_ml, const float *__restrict__ part_o, float *__restrict__ out, int P,
-               const int32_t *__restrict__ head_count, int32_t *__restrict__ publish_count) {
+               int32_t *__restrict__ head_count, int32_t *__restrict__ head_stat, int32_t *__restrict__ publish_count) {
+    __shared__ float s_w[COMBINE_MAX_P];
+    __shared__ float s_red[8];
+    __shared__ float s_num[4][LVR_D];
     const int64_t hq = blockIdx.x;
-    const int c = threadIdx.x;
-    if (publish_count && c == 0) publish_count[hq] = head_count[hq * LVR_CNT_STRIDE];
-    float M = -INFINITY;
-    for (int p = 0; p < P; ++p) M = fmaxf(M, part_ml[(hq * P + p) * 2]);
-    float num = 0.f, den = 0.f;
-    if (M != -INFINITY) {
-        for (int p = 0; p < P; ++p) {
-            const float w = exp2_safe(part_ml[(hq * P + p) * 2], M);
-            den += w * part_ml[(hq * P + p) * 2 + 1];
-            num += w * part_o[(hq * P + p) * LVR_D + c];
-        }
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    if (publish_count && t == 0) {
+        const int32_t c = head_count[hq * LVR_CNT_STRIDE];
+        publish_count[hq] = c;
+        head_stat[hq] = c;
+        head_count[hq * LVR_CNT_STRIDE] = 0;
     }
-    out[hq * LVR_D + c] = (den > 0.f) ? num / den : 0.f;
+    const float m = (t < P) ? part_ml[(hq * P + t) * 2] : -INFINITY;
+    const float l = (t < P) ? part_ml[(hq * P + t) * 2 + 1] : 0.f;
+    float mx = m;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+    if (lane == 0) s_red[wave] = mx;
+    __syncthreads();
+    float M = s_red[0];
+#pragma unroll
+    for (int w = 1; w < 8; ++w) M = fmaxf(M, s_red[w]);
+    __syncthreads();
+    const float w_p = exp2_safe(m, M);
+    if (t < COMBINE_MAX_P) s_w[t] = w_p;
+    float dn = w_p * l;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) dn += __shfl_xor(dn, off, 64);
+    if (lane == 0) s_red[wave] = dn;
+    __syncthreads();
+    float den = 0.f;
+#pragma unroll
+    for (int w = 0; w < 8; ++w) den += s_red[w];
+    const int c = t & (LVR_D - 1), sl = t >> 7;
+    float num = 0.f;
+    const float *po = part_o + hq * P * LVR_D + c;
+#pragma unroll 4
+    for (int p = sl; p < P; p += 4) num += s_w[p] * po[(int64_t)p * LVR_D];
+    s_num[sl][c] = num;
+    __syncthreads();
+    if (t < LVR_D) {
+        const float tot = s_num[0][t] + s_num[1][t] + s_num[2][t] + s_num[3][t];
+        out[hq * LVR_D + t] = (den > 0.f && M != -INFINITY) ? tot / den : 0.f;
+    }
 }
 
 template <typename KT, int G>
@@ -294,7 +328,7 @@ hipError_t lvr_launch_dense_partial(lvr_index *ix, const float *q, hipStream_t s
 
 hipError_t lvr_launch_combine(lvr_index *ix, float *out, int P, int32_t *publish_count, hipStream_t st) {
     const int n_bhq = lvr_n_bhq(ix);
-    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)n_bhq), dim3(128), 0, st, ix->part_ml, ix->part_o, out, P,
-                       lvr_head_count(ix), publish_count);
+    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)n_bhq), dim3(512), 0, st, ix->part_ml, ix->part_o, out, P,
+                       lvr_head_count(ix), lvr_head_stat(ix), publish_count);
     return hipGetLastError();
 }

@@ -1,0 +1,66 @@
+// Per-wave emission queue shared by the exact-filter kernels.
+//
+// Qualifying positions go to a small per-wave queue in LDS first; a queue is flushed with ONE
+// atomic per head on a counter that owns its cache line, so a launch issues a few thousand
+// atomics spread over many lines instead of one per hit on a few lines (atomics that hit one
+// line are served one after the other by the memory side).
+#pragma once
+#include "lvr_internal.h"
+
+#ifdef __HIPCC__
+constexpr int LVR_QCAP = 64;   // queue entries per (wave, head)
+
+struct lvr_emit_target {
+    int32_t *out_idx;        // [n_bhq][cap]
+    int32_t *head_count;     // padded, LVR_CNT_STRIDE ints apart
+    int32_t *overflow;
+    int64_t cap;
+};
+
+// The lanes with (lane % 16) in [rep_base, rep_base+NH) report head (lane % 16) - rep_base; the
+// four lanes (one per quarter of the wave) that report the same head keep identical counts.
+template <int NH>
+struct lvr_emitter {
+    int32_t (*q)[LVR_QCAP];   // LDS, [NH][LVR_QCAP], private to the wave
+    int count;                // queued entries of my head (0 on lanes that report nothing)
+    int rep_base;
+    int64_t hq_base;          // flat index of head 0
+
+    __device__ __forceinline__ void flush(const lvr_emit_target &a, int lane, bool reporting) {
+        const int hl = (lane & 15) - rep_base;
+        int base = 0;
+        if (reporting && (lane >> 4) == 0 && count > 0)
+            base = atomicAdd(&a.head_count[(hq_base + hl) * LVR_CNT_STRIDE], count);
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+            const int b_h = __shfl(base, rep_base + h, 64);
+            const int c_h = __shfl(count, rep_base + h, 64);
+            if (lane < c_h) {
+                const int64_t p = (int64_t)b_h + lane;
+                if (p < a.cap)
+                    a.out_idx[(hq_base + h) * a.cap + p] = q[h][lane];
+                else
+                    *a.overflow = 1;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        count = 0;
+    }
+
+    // pred: this lane's (row, head) qualifies; the row's arena slot is held by lane `src_lane`.
+    __device__ __forceinline__ void push(const lvr_emit_target &a, int lane, bool reporting, bool pred, int my_slot,
+                                         int src_lane, const int32_t *spos) {
+        const uint64_t any = __ballot(pred);
+        if (!any) return;   // wave-uniform
+        const int slot = __shfl(my_slot, src_lane, 64);
+        const uint64_t mh = reporting ? (any & (0x0001000100010001ull << (lane & 15))) : 0ull;
+        if (pred) {
+            const int hl = (lane & 15) - rep_base;
+            q[hl][count + __popcll(mh & ((1ull << lane) - 1ull))] = spos ? spos[slot] : slot;
+        }
+        count += __popcll(mh);
+        if (__ballot(count > LVR_QCAP - 4)) flush(a, lane, reporting);
+    }
+};
+#endif

@@ -16,11 +16,12 @@
 //
 // Two bodies: bf16 rows are scored on the matrix cores (mfma_score.h); fp32 rows (the small
 // single-head workload) on the vector ALU.
+#include "emitter.h"
 #include "mfma_score.h"
 
 namespace {
 
-constexpr int QCAP = 64;   // queue entries per (wave, head)
+constexpr int QCAP = LVR_QCAP;
 
 struct FilterArgs {
     const void *K;
@@ -29,59 +30,9 @@ struct FilterArgs {
     const float *tau;
     const int32_t *surv_list;
     const int32_t *seg_count;
-    int32_t *out_idx;
-    int32_t *head_count;     // padded, LVR_CNT_STRIDE ints apart
-    int32_t *overflow;
-    int64_t cap_rows, max_groups, max_segs, n_indexed, n_total, cap;
+    lvr_emit_target emit;
+    int64_t cap_rows, max_groups, max_segs, n_indexed, n_total;
     int log2r, n_q_heads, n_kv_heads, G, buffer_dense, n_segs, seg_groups;
-};
-
-// Per-wave emission queue for NH heads.  The lanes with (lane % 16) in [rep_base, rep_base+NH)
-// report head (lane % 16) - rep_base; the four lanes (one per quarter) that report the same
-// head keep identical counts.
-template <int NH>
-struct Emitter {
-    int32_t (*q)[QCAP];   // LDS, [NH][QCAP], private to the wave
-    int count;            // queued entries of my head (0 on lanes that report nothing)
-    int rep_base;
-    int64_t hq_base;      // flat index of head 0
-
-    __device__ __forceinline__ void flush(const FilterArgs &a, int lane, bool reporting) {
-        const int hl = (lane & 15) - rep_base;
-        int base = 0;
-        if (reporting && (lane >> 4) == 0 && count > 0)
-            base = atomicAdd(&a.head_count[(hq_base + hl) * LVR_CNT_STRIDE], count);
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int h = 0; h < NH; ++h) {
-            const int b_h = __shfl(base, rep_base + h, 64);
-            const int c_h = __shfl(count, rep_base + h, 64);
-            if (lane < c_h) {
-                const int64_t p = (int64_t)b_h + lane;
-                if (p < a.cap)
-                    a.out_idx[(hq_base + h) * a.cap + p] = q[h][lane];
-                else
-                    *a.overflow = 1;
-            }
-        }
-        __builtin_amdgcn_wave_barrier();
-        count = 0;
-    }
-
-    // pred: this lane's (row, head) qualifies; the row's arena slot is held by lane `src_lane`.
-    __device__ __forceinline__ void push(const FilterArgs &a, int lane, bool reporting, bool pred, int my_slot,
-                                         int src_lane, const int32_t *spos) {
-        const uint64_t any = __ballot(pred);
-        if (!any) return;   // wave-uniform
-        const int slot = __shfl(my_slot, src_lane, 64);
-        const uint64_t mh = reporting ? (any & (0x0001000100010001ull << (lane & 15))) : 0ull;
-        if (pred) {
-            const int hl = (lane & 15) - rep_base;
-            q[hl][count + __popcll(mh & ((1ull << lane) - 1ull))] = spos ? spos[slot] : slot;
-        }
-        count += __popcll(mh);
-        if (__ballot(count > QCAP - 4)) flush(a, lane, reporting);
-    }
 };
 
 struct SegWork {
@@ -130,7 +81,7 @@ filter_mfma_kernel(const FilterArgs a) {
     lvr_build_q_frags_wg<HB>(a.q + hq0 * LVR_D, a.G, 1.0f, s_bq, bq);
     float my_tau[HB];
     bool rep[HB];
-    Emitter<4> em[HB];
+    lvr_emitter<4> em[HB];
 #pragma unroll
     for (int hb = 0; hb < HB; ++hb) {
         const int h = hb * 4 + n - 8;
@@ -177,14 +128,14 @@ filter_mfma_kernel(const FilterArgs a) {
                     const int trow = 4 * kq + j;
                     const bool pred = trow < nvalid[u] && rep[hb] &&
                                       (s[j] >= my_tau[hb] || (w.buffer && a.buffer_dense));
-                    em[hb].push(a, lane, rep[hb], pred, slot[u], trow, spos);
+                    em[hb].push(a.emit, lane, rep[hb], pred, slot[u], trow, spos);
                 }
             }
         }
     }
 #pragma unroll
     for (int hb = 0; hb < HB; ++hb)
-        if (__ballot(em[hb].count > 0)) em[hb].flush(a, lane, rep[hb]);
+        if (__ballot(em[hb].count > 0)) em[hb].flush(a.emit, lane, rep[hb]);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -212,7 +163,7 @@ filter_valu_kernel(const FilterArgs a) {
     }
     const bool rep = li < G;
     const float my_tau = rep ? lvr_effective_tau(a.tau[hq0 + li]) : INFINITY;
-    Emitter<G> em;
+    lvr_emitter<G> em;
     em.q = s_queue[wave];
     em.count = 0;
     em.rep_base = 0;
@@ -254,15 +205,21 @@ filter_valu_kernel(const FilterArgs a) {
                 mine = (li == h) ? s : mine;
             }
             const bool pred = valid[i] && rep && (mine >= my_tau || (w.buffer && a.buffer_dense));
-            em.push(a, lane, rep, pred, slot[i], lane, spos);   // the reporting lane holds the row's slot itself
+            em.push(a.emit, lane, rep, pred, slot[i], lane, spos);   // the reporting lane holds the row's slot itself
         }
     }
-    if (__ballot(em.count > 0)) em.flush(a, lane, rep);
+    if (__ballot(em.count > 0)) em.flush(a.emit, lane, rep);
 }
 
-__global__ void publish_counts_kernel(const int32_t *__restrict__ head_count, int32_t *__restrict__ out_count, int n_bhq) {
+__global__ void publish_counts_kernel(int32_t *__restrict__ head_count, int32_t *__restrict__ head_stat,
+                                      int32_t *__restrict__ out_count, int n_bhq) {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n_bhq) out_count[i] = head_count[(size_t)i * LVR_CNT_STRIDE];
+    if (i < n_bhq) {
+        const int32_t c = head_count[(size_t)i * LVR_CNT_STRIDE];
+        out_count[i] = c;
+        head_stat[i] = c;
+        head_count[(size_t)i * LVR_CNT_STRIDE] = 0;
+    }
 }
 
 }  // namespace
@@ -276,15 +233,15 @@ hipError_t lvr_launch_filter(lvr_index *ix, const float *q, const float *tau, in
     a.tau = tau;
     a.surv_list = ix->surv_list;
     a.seg_count = lvr_seg_count(ix);
-    a.out_idx = out_idx;
-    a.head_count = lvr_head_count(ix);
-    a.overflow = lvr_overflow_flag(ix);
+    a.emit.out_idx = out_idx;
+    a.emit.head_count = lvr_head_count(ix);
+    a.emit.overflow = lvr_overflow_flag(ix);
+    a.emit.cap = cap;
     a.cap_rows = ix->cap_rows;
     a.max_groups = ix->max_groups;
     a.max_segs = lvr_max_segs(ix->max_groups);
     a.n_indexed = ix->n_indexed;
     a.n_total = ix->n_total;
-    a.cap = cap;
     a.log2r = 0;
     while ((1 << a.log2r) < ix->cfg.group_size) ++a.log2r;
     a.n_q_heads = ix->cfg.n_q_heads;
@@ -315,7 +272,7 @@ hipError_t lvr_launch_filter(lvr_index *ix, const float *q, const float *tau, in
 
 hipError_t lvr_launch_publish_counts(lvr_index *ix, int32_t *out_count, hipStream_t st) {
     const int n_bhq = lvr_n_bhq(ix);
-    hipLaunchKernelGGL(publish_counts_kernel, dim3((n_bhq + 255) / 256), dim3(256), 0, st, lvr_head_count(ix), out_count,
-                       n_bhq);
+    hipLaunchKernelGGL(publish_counts_kernel, dim3((n_bhq + 255) / 256), dim3(256), 0, st, lvr_head_count(ix),
+                       lvr_head_stat(ix), out_count, n_bhq);
     return hipGetLastError();
 }

@@ -41,6 +41,7 @@ struct lvr_index {
     int32_t *counters;     // see lvr_head_count / lvr_overflow_flag / lvr_seg_count
     int seg_groups;        // groups per segment used by the last bound test
     int n_segs;            // segments per (sequence, KV head) filled by the last bound test (0: none)
+    int counters_dirty;    // a query was started but its counts were never published (a launch failed)
     float *part_ml;        // [batch][H_q][Pmax][2]
     float *part_o;         // [batch][H_q][Pmax][d]
     int64_t last_buffer_rows; // buffer rows scanned by the last query (host copy for stats)
@@ -64,14 +65,17 @@ static inline int lvr_n_bhq(const lvr_index *ix) { return ix->cfg.batch * ix->cf
 // (about 12 ns each on this part), so every counter that takes atomics owns a whole line.
 #define LVR_CNT_STRIDE 32   // ints per counter slot (128 bytes)
 #define LVR_MIN_SEG_GROUPS 128
-// per query head: size of the retrieved set of the running query (padded)
+// per query head: size of the retrieved set of the running query (padded).  Zero between
+// queries: the kernel that publishes the counts clears them.
 static inline int32_t *lvr_head_count(const lvr_index *ix) { return ix->counters; }
 static inline int32_t *lvr_overflow_flag(const lvr_index *ix) { return ix->counters + (size_t)lvr_n_bhq(ix) * LVR_CNT_STRIDE; }
+// per query head: set size of the last finished query (kept for statistics)
+static inline int32_t *lvr_head_stat(const lvr_index *ix) { return ix->counters + ((size_t)lvr_n_bhq(ix) + 1) * LVR_CNT_STRIDE; }
 // per (sequence, KV head, segment): surviving groups of the segment (plain stores, no atomics)
-static inline int32_t *lvr_seg_count(const lvr_index *ix) { return ix->counters + ((size_t)lvr_n_bhq(ix) + 1) * LVR_CNT_STRIDE; }
+static inline int32_t *lvr_seg_count(const lvr_index *ix) { return ix->counters + ((size_t)lvr_n_bhq(ix) + 1) * LVR_CNT_STRIDE + (size_t)lvr_n_bhq(ix); }
 static inline int64_t lvr_max_segs(int64_t max_groups) { return max_groups / LVR_MIN_SEG_GROUPS + 2; }
 static inline size_t lvr_counter_ints(int n_bh, int n_bhq, int64_t max_groups) {
-    return ((size_t)n_bhq + 1) * LVR_CNT_STRIDE + (size_t)n_bh * (size_t)lvr_max_segs(max_groups);
+    return ((size_t)n_bhq + 1) * LVR_CNT_STRIDE + (size_t)n_bhq + (size_t)n_bh * (size_t)lvr_max_segs(max_groups);
 }
 
 // ---- launchers (each returns a hipError_t from hipGetLastError after the launch) ----
@@ -86,13 +90,17 @@ hipError_t lvr_launch_prune(lvr_index *ix, const float *q, const float *tau, hip
 // exact check on survivors and buffer; fills out_idx and the internal per-head counters
 hipError_t lvr_launch_filter(lvr_index *ix, const float *q, const float *tau, int32_t *out_idx, int64_t cap,
                              hipStream_t st);
-// internal per-head counters -> caller's array
+// bf16 caches: bound test + exact check in one launch (per-head counters must be zero on entry)
+hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *tau, int32_t *out_idx, int64_t cap,
+                                  hipStream_t st);
+// internal per-head counters -> caller's array and the statistics copy; clears the counters
 hipError_t lvr_launch_publish_counts(lvr_index *ix, int32_t *out_count, hipStream_t st);
 // partial softmax per (head, split); count is read with the given stride (1 = caller's array)
 hipError_t lvr_launch_sparse_partial(lvr_index *ix, const float *q, const int32_t *idx, const int32_t *count,
                                      int count_stride, int64_t cap, hipStream_t st);
 hipError_t lvr_launch_dense_partial(lvr_index *ix, const float *q, hipStream_t st);
-// merge P partials; if publish_count is not NULL also copies the internal per-head counters to it
+// merge P partials; if publish_count is not NULL also publishes the internal per-head counters to it
+// (and to the statistics copy) and clears them
 hipError_t lvr_launch_combine(lvr_index *ix, float *out, int P, int32_t *publish_count, hipStream_t st);
 int lvr_dense_splits(const lvr_index *ix);
 

@@ -1,0 +1,295 @@
+// Fused range-query kernel for bf16 caches: bound test and exact check in one launch.
+//
+// A workgroup owns a segment of consecutive groups of one (sequence, KV head):
+//   phase A  (Sec. 4.2 "Query 2" bound, Eq. (2) per coordinate block, summed): every wave
+//            scores its tiles of 16 centres on the matrix cores, adds the radius terms and
+//            keeps a bit per group; the four waves compact the surviving group ids into LDS
+//            (ballot + prefix sum, no global traffic).
+//   phase B  (the exact dot-product check of Alg. 3 / Alg. 4): the waves walk the surviving
+//            groups' key rows in tiles of 16 rows, two tiles in flight, score them for the G
+//            heads of the KV head and queue the qualifying positions (emitter.h).
+// One extra workgroup per (sequence, KV head) scans the not-yet-indexed buffer rows (Sec. 4.3).
+//
+// Compared with two launches this keeps the survivor list on chip, builds the query operand
+// once per segment instead of twice, and removes one kernel tail from the step.
+// The per-head counters must be zero when the kernel starts; the kernels that publish the
+// counts (publish_counts_kernel, combine_kernel) clear them for the next query.
+#include "emitter.h"
+#include "mfma_score.h"
+
+namespace {
+
+constexpr int SEG_MAX_GROUPS = 1024;   // 4 waves x 16 tiles x 16 groups
+
+struct FusedArgs {
+    const void *centres;
+    const float *radii;
+    const void *K;
+    const int32_t *slot_pos;
+    const float *q;
+    const float *tau;
+    int32_t *seg_count;      // survivors per segment, for statistics only
+    lvr_emit_target emit;
+    int64_t n_groups, max_groups, max_segs, cap_rows, n_indexed, n_total;
+    int log2r, n_q_heads, n_kv_heads, G, buffer_dense, n_segs, tiles_per_wave;
+};
+
+template <int HB, int S>
+__global__ void __launch_bounds__(256)
+query_fused_kernel(const FusedArgs a) {
+    __shared__ uint4 s_bq[HB][4][64];
+    __shared__ float s_qn[HB * 4][16];
+    __shared__ int32_t s_queue[4][HB][4][LVR_QCAP];
+    __shared__ int32_t s_list[SEG_MAX_GROUPS];
+    __shared__ int s_tot[4];
+    const int bh = blockIdx.y;
+    const int b = bh / a.n_kv_heads, kvh = bh % a.n_kv_heads;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 15, kq = lane >> 4;
+    const int64_t hq0 = (int64_t)b * a.n_q_heads + kvh * a.G;
+    const bool buffer_wg = (int)blockIdx.x >= a.n_segs;
+
+    // ---- prologue: subspace norms of q (phase A only) and the B operand of q ----
+    if (!buffer_wg && (int)threadIdx.x < HB * 64) {
+        const int h = threadIdx.x >> 4, li = threadIdx.x & 15;
+        float ss = 0.f;
+        if (h < a.G) {
+            const float *qh = a.q + (hq0 + h) * LVR_D + li * 8;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ss += qh[e] * qh[e];
+        }
+        constexpr int lanes_per_sub = 16 / S;
+#pragma unroll
+        for (int off = 1; off < lanes_per_sub; off <<= 1) ss += __shfl_xor(ss, off, 64);
+        if ((li % lanes_per_sub) == 0) s_qn[h][li / lanes_per_sub] = sqrtf(ss) * (1.0f + 0x1p-20f);   // rounded up
+    }
+    lvr_bf16x8 bq[HB][4];
+    lvr_build_q_frags_wg<HB>(a.q + hq0 * LVR_D, a.G, 1.0f, s_bq, bq);   // syncs
+    float taue[HB];
+    bool rep[HB];
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) {
+        const int h = hb * 4 + n - 8;
+        rep[hb] = n >= 8 && n < 12 && h < a.G;
+        taue[hb] = rep[hb] ? lvr_effective_tau(a.tau[hq0 + h]) : INFINITY;
+    }
+
+    int64_t rows;          // key rows phase B has to check
+    int64_t buf_row0 = 0;
+    if (!buffer_wg) {
+        // ---------------- phase A: bound test over this segment's centres ----------------
+        float qn[HB][S];
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+            for (int s = 0; s < S; ++s) qn[hb][s] = rep[hb] ? s_qn[hb * 4 + n - 8][s] : 0.f;
+        const char *Cb = static_cast<const char *>(a.centres) + (int64_t)bh * a.max_groups * LVR_D * 2;
+        const float *Rb = a.radii + (int64_t)bh * a.max_groups * S;
+        const int64_t n_tiles = (a.n_groups + 15) >> 4;
+        const int64_t seg_tile0 = (int64_t)blockIdx.x * 4 * a.tiles_per_wave;
+        const int64_t tile0 = seg_tile0 + (int64_t)wave * a.tiles_per_wave;
+        uint32_t mybits = 0;   // lane `it` keeps the 16-bit survivor mask of the wave's tile `it`
+        for (int it = 0; it < a.tiles_per_wave; it += 2) {
+            if (tile0 + it >= n_tiles) break;   // wave-uniform
+            constexpr int SP = (S <= 4) ? S : 1;
+            uint4 av[2][4];
+            float rad[2][4][SP];
+            int64_t g_row[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int64_t g0 = (tile0 + it + u) * 16;
+                int64_t g = g0 + n;
+                if (g >= a.n_groups) g = a.n_groups - 1;
+                g_row[u] = g0;
+                lvr_load_a_frags(Cb, g, av[u]);
+                if constexpr (S <= 4) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        int64_t gj = g0 + 4 * kq + j;
+                        if (gj >= a.n_groups) gj = a.n_groups - 1;
+                        const float *rp = Rb + gj * S;
+                        if constexpr (S == 4) {
+                            const float4 r = *reinterpret_cast<const float4 *>(rp);
+                            rad[u][j][0] = r.x; rad[u][j][1] = r.y; rad[u][j][2] = r.z; rad[u][j][3] = r.w;
+                        } else {
+#pragma unroll
+                            for (int s = 0; s < S; ++s) rad[u][j][s] = rp[s];
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                uint32_t alive4 = 0;
+#pragma unroll
+                for (int hb = 0; hb < HB; ++hb) {
+                    const lvr_f32x4 sc = lvr_score_tile(av[u], bq[hb]);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        float ub = sc[j];
+                        if constexpr (S <= 4) {
+#pragma unroll
+                            for (int s = 0; s < S; ++s) ub += rad[u][j][s] * qn[hb][s];
+                        } else {
+                            int64_t gj = g_row[u] + 4 * kq + j;
+                            if (gj >= a.n_groups) gj = a.n_groups - 1;
+                            const float4 *rp = reinterpret_cast<const float4 *>(Rb + gj * S);
+#pragma unroll
+                            for (int s4 = 0; s4 < S / 4; ++s4) {
+                                const float4 r = rp[s4];
+                                ub += r.x * qn[hb][4 * s4] + r.y * qn[hb][4 * s4 + 1] + r.z * qn[hb][4 * s4 + 2] +
+                                      r.w * qn[hb][4 * s4 + 3];
+                            }
+                        }
+                        const bool ok = rep[hb] && ub >= taue[hb] && (g_row[u] + 4 * kq + j) < a.n_groups;
+                        alive4 |= ok ? (1u << j) : 0u;
+                    }
+                }
+                uint32_t mask16 = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint64_t bal = __ballot((alive4 >> j) & 1u);
+#pragma unroll
+                    for (int qd = 0; qd < 4; ++qd)
+                        mask16 |= ((bal >> (16 * qd)) & 0xffffull) ? (1u << (4 * qd + j)) : 0u;
+                }
+                if (lane == it + u) mybits = mask16;
+            }
+        }
+        // compaction of the four waves' masks into the LDS list
+        const int cnt = __popc(mybits);
+        int incl = cnt;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            int t = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += t;
+        }
+        if (lane == 63) s_tot[wave] = incl;
+        __syncthreads();
+        int before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            before += (w < wave) ? s_tot[w] : 0;
+            total += s_tot[w];
+        }
+        {
+            int o = before + (incl - cnt);
+#pragma unroll
+            for (int k = 0; k < 16; ++k)
+                if (mybits & (1u << k)) s_list[o++] = (int32_t)(tile0 * 16 + (int64_t)lane * 16 + k);
+        }
+        if (threadIdx.x == 0) a.seg_count[(int64_t)bh * a.max_segs + blockIdx.x] = total;
+        __syncthreads();
+        rows = (int64_t)total << a.log2r;
+    } else {
+        rows = a.n_total - a.n_indexed;
+        buf_row0 = a.n_indexed;
+    }
+
+    // ---------------- phase B: exact check of the surviving rows ----------------
+    lvr_emitter<4> em[HB];
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) {
+        em[hb].q = s_queue[wave][hb];
+        em[hb].count = 0;
+        em[hb].rep_base = 8;
+        em[hb].hq_base = hq0 + hb * 4;
+    }
+    const char *Kb = static_cast<const char *>(a.K) + (int64_t)bh * a.cap_rows * LVR_D * 2;
+    const int32_t *spos = a.slot_pos ? a.slot_pos + (int64_t)bh * a.cap_rows : nullptr;
+    const int rmask = (1 << a.log2r) - 1;
+    const int64_t tiles = (rows + 15) >> 4;
+    for (int64_t t0 = wave; t0 < tiles; t0 += 8) {
+        int slot[2], nvalid[2];
+        uint4 av[2][4];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int64_t t = t0 + 4 * u;
+            int64_t rowidx = t * 16 + n;
+            const int64_t left = rows - t * 16;
+            nvalid[u] = left <= 0 ? 0 : (left < 16 ? (int)left : 16);
+            if (rowidx >= rows) rowidx = 0;
+            slot[u] = buffer_wg ? (int)(buf_row0 + rowidx)
+                                : (int)(((int64_t)s_list[rowidx >> a.log2r] << a.log2r) + (rowidx & rmask));
+            lvr_load_a_frags(Kb, slot[u], av[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            if (nvalid[u] == 0) continue;   // wave-uniform
+#pragma unroll
+            for (int hb = 0; hb < HB; ++hb) {
+                const lvr_f32x4 s = lvr_score_tile(av[u], bq[hb]);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int trow = 4 * kq + j;
+                    const bool pred = trow < nvalid[u] && rep[hb] &&
+                                      (s[j] >= taue[hb] || (buffer_wg && a.buffer_dense));
+                    em[hb].push(a.emit, lane, rep[hb], pred, slot[u], trow, spos);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb)
+        if (__ballot(em[hb].count > 0)) em[hb].flush(a.emit, lane, rep[hb]);
+}
+
+template <int HB>
+void launch_s(dim3 grid, hipStream_t st, const FusedArgs &a, int S) {
+    switch (S) {
+        case 1: hipLaunchKernelGGL((query_fused_kernel<HB, 1>), grid, dim3(256), 0, st, a); break;
+        case 2: hipLaunchKernelGGL((query_fused_kernel<HB, 2>), grid, dim3(256), 0, st, a); break;
+        case 4: hipLaunchKernelGGL((query_fused_kernel<HB, 4>), grid, dim3(256), 0, st, a); break;
+        case 8: hipLaunchKernelGGL((query_fused_kernel<HB, 8>), grid, dim3(256), 0, st, a); break;
+        default: hipLaunchKernelGGL((query_fused_kernel<HB, 16>), grid, dim3(256), 0, st, a); break;
+    }
+}
+
+}  // namespace
+
+hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *tau, int32_t *out_idx, int64_t cap,
+                                  hipStream_t st) {
+    if (ix->cfg.kv_dtype != LVR_BF16) return hipErrorInvalidValue;
+    FusedArgs a;
+    a.centres = ix->centres;
+    a.radii = ix->radii;
+    a.K = ix->K;
+    a.slot_pos = ix->slot_pos;
+    a.q = q;
+    a.tau = tau;
+    a.seg_count = lvr_seg_count(ix);
+    a.emit.out_idx = out_idx;
+    a.emit.head_count = lvr_head_count(ix);
+    a.emit.overflow = lvr_overflow_flag(ix);
+    a.emit.cap = cap;
+    a.n_groups = ix->n_indexed / ix->cfg.group_size;
+    a.max_groups = ix->max_groups;
+    a.max_segs = lvr_max_segs(ix->max_groups);
+    a.cap_rows = ix->cap_rows;
+    a.n_indexed = ix->n_indexed;
+    a.n_total = ix->n_total;
+    a.log2r = 0;
+    while ((1 << a.log2r) < ix->cfg.group_size) ++a.log2r;
+    a.n_q_heads = ix->cfg.n_q_heads;
+    a.n_kv_heads = ix->cfg.n_kv_heads;
+    a.G = ix->G;
+    a.buffer_dense = (ix->cfg.flags & LVR_ATTEND_BUFFER_DENSE) ? 1 : 0;
+    const int n_bh = lvr_n_bh(ix);
+    // segment = 4 waves x tiles_per_wave tiles x 16 groups; aim at ~1024 workgroups per launch
+    const int64_t want = a.n_groups * n_bh / 1024;
+    int tpw = 2;
+    while (tpw < 16 && (int64_t)tpw * 64 < want) tpw *= 2;
+    a.tiles_per_wave = tpw;
+    const int seg_groups = tpw * 64;
+    a.n_segs = (int)((a.n_groups + seg_groups - 1) / seg_groups);
+    const int has_buffer = ix->n_total > ix->n_indexed ? 1 : 0;
+    ix->seg_groups = seg_groups;
+    ix->n_segs = a.n_segs;
+    if (a.n_segs + has_buffer == 0) return hipSuccess;
+    dim3 grid((unsigned)(a.n_segs + has_buffer), (unsigned)n_bh);
+    if (ix->G <= 4)
+        launch_s<1>(grid, st, a, ix->cfg.n_subspaces);
+    else
+        launch_s<2>(grid, st, a, ix->cfg.n_subspaces);
+    return hipGetLastError();
+}

@@ -45,12 +45,13 @@ def test_config1_fp32_single_head(G, oracle):
 
 
 # ------------------------------------------------------------------ bf16 GQA, ragged sizes
+@pytest.mark.parametrize("separate", [0, 2], ids=["fused", "two_kernels"])
 @pytest.mark.parametrize("n", [1, 3, 64, 1000, 2051, 4096])
-def test_gqa_bf16_sets_and_attention(G, oracle, n):
-    G.say(f"gqa bf16 n={n}")
+def test_gqa_bf16_sets_and_attention(G, oracle, n, separate):
+    G.say(f"gqa bf16 n={n} flags={separate}")
     cache = _small_cache(2, n)
     q = W.make_queries(2, n_q_heads=8)
-    with G.Index(cache.K, cache.V, "bf16", 8) as ix:
+    with G.Index(cache.K, cache.V, "bf16", 8, flags=separate) as ix:
         for frac in (0.01, 0.2):
             tau = G.oracle_taus(oracle, ix, q, frac=frac)
             idx, cnt, out = ix.query(q, tau)
@@ -124,12 +125,13 @@ def test_exact_ties_integer_data(G, oracle):
                     assert sorted(idx[0, h, :cnt[0, h]].tolist()) == want.tolist(), (dtype, quant, h)
 
 
+@pytest.mark.parametrize("separate", [0, 2], ids=["fused", "two_kernels"])
 @pytest.mark.parametrize("r,S", [(1, 4), (2, 1), (8, 16), (16, 2), (4, 8)])
-def test_group_size_and_subspaces(G, oracle, r, S):
+def test_group_size_and_subspaces(G, oracle, r, S, separate):
     n = 1500
     cache = _small_cache(2, n)
     q = W.make_queries(2, n_q_heads=8)
-    with G.Index(cache.K, cache.V, "bf16", 8, group_size=r, n_subspaces=S, buffer_size=64) as ix:
+    with G.Index(cache.K, cache.V, "bf16", 8, group_size=r, n_subspaces=S, buffer_size=64, flags=separate) as ix:
         tau = G.oracle_taus(oracle, ix, q, frac=0.03)
         idx, cnt, out = ix.query(q, tau)
         G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=f"r={r} S={S}")
@@ -137,12 +139,13 @@ def test_group_size_and_subspaces(G, oracle, r, S):
         assert st["n_indexed"] == n // r * r
 
 
+@pytest.mark.parametrize("separate", [0, 2], ids=["fused", "two_kernels"])
 @pytest.mark.parametrize("hq,hkv", [(2, 2), (4, 2), (16, 2), (8, 1)])
-def test_head_group_sizes(G, oracle, hq, hkv):
+def test_head_group_sizes(G, oracle, hq, hkv, separate):
     n = 900
     cache = _small_cache(2, n, hkv=hkv, batch=2)
     q = W.make_queries(2, n_q_heads=hq, batch=2)
-    with G.Index(cache.K, cache.V, "bf16", hq) as ix:
+    with G.Index(cache.K, cache.V, "bf16", hq, flags=separate) as ix:
         tau = G.oracle_taus(oracle, ix, q, frac=0.05)
         idx, cnt, out = ix.query(q, tau, fused=True)
         G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=f"hq={hq} hkv={hkv}")
@@ -290,7 +293,8 @@ def test_key_on_ball_surface_is_never_lost(G, oracle):
                 G.check_step(oracle, ix, q, t, idx, cnt, out, tag=f"surface S={S} tau={tau}")
 
 
-def test_pruning_happens_on_clustered_keys(G, oracle):
+@pytest.mark.parametrize("separate", [0, 2], ids=["fused", "two_kernels"])
+def test_pruning_happens_on_clustered_keys(G, oracle, separate):
     """Keys with positional locality (consecutive tokens share a slowly changing mean): most
     balls are pruned, the result still equals the oracle's."""
     g = np.random.default_rng(21)
@@ -299,7 +303,7 @@ def test_pruning_happens_on_clustered_keys(G, oracle):
     K = W.round_to_bf16(base + 0.05 * g.standard_normal((1, hkv, n, 128)).astype(np.float32))
     V = W.round_to_bf16(g.standard_normal((1, hkv, n, 128)).astype(np.float32))
     q = W.make_queries(2, n_q_heads=hq)
-    with G.Index(K, V, "bf16", hq, n_subspaces=4) as ix:
+    with G.Index(K, V, "bf16", hq, n_subspaces=4, flags=separate) as ix:
         tau = G.oracle_taus(oracle, ix, q, frac=0.02)
         idx, cnt, out = ix.query(q, tau, fused=True)
         G.check_step(oracle, ix, q, tau, idx, cnt, out, tag="clustered")
@@ -310,7 +314,7 @@ def test_pruning_happens_on_clustered_keys(G, oracle):
 
 
 # ------------------------------------------------------------------ append
-@pytest.mark.parametrize("flags", [0, 1])
+@pytest.mark.parametrize("flags", [0, 1, 2, 3])
 def test_append_matches_oracle_on_grown_cache(G, oracle, flags):
     """Prompt of 200 keys, then single-token appends across several buffer flushes (B = 32);
     after every step the query over the grown cache equals the oracle's.  With the
@@ -330,7 +334,7 @@ def test_append_matches_oracle_on_grown_cache(G, oracle, flags):
                 tau = G.oracle_taus(oracle, ix, qs[t], frac=0.05)
                 idx, cnt, out = ix.query(qs[t], tau, fused=(t % 2 == 0))
                 G.check_step(oracle, ix, qs[t], tau, idx, cnt, out, tag=f"append t={t}",
-                             extra_from=(n_indexed if flags else -1))
+                             extra_from=(n_indexed if flags & 1 else -1))
         assert n_indexed >= n0 // 4 * 4 + 2 * B      # at least two flushes happened
         # bulk append of many tokens at once
     with G.Index(cache.K, cache.V, "bf16", 8, capacity=n0 + steps, buffer_size=B) as ix:
