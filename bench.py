@@ -216,13 +216,13 @@ def main():
     roofline = dict(bound="hbm", kernel="query_fused_kernel", achieved=round(achieved, 1), peak=HBM_PEAK_GBS,
                     unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
                     bytes_per_launch=int(query_bytes), avg_launch_us=round(filt["avg_us"], 2))
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        try:
-            tj = json.load(open(tpath))
-            roofline["traffic"] = tj.get(f"config{cid}", {}).get("query_fused_kernel_bytes")
-        except Exception:
-            pass
+    # HBM bytes per launch measured offline with rocprofv3 --pmc (profiles/), when this workload was profiled
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if os.path.exists(tpath) and args.group_size == 4 and args.subspaces == 4:
+        for line in open(tpath):
+            f = line.split()
+            if len(f) == 3 and f[0] == f"config{cid}" and f[1] == "query_fused_kernel":
+                roofline["traffic"] = int(f[2])
 
     result = {
         "metric": "decode steps/sec (index query + sparse attention)",
