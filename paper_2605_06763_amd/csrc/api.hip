@@ -57,7 +57,7 @@ Sizes sizes_of(const lvr_config *c) {
     s.cap_rows = (c->capacity + 63) / 64 * 64;
     s.max_groups = s.cap_rows / c->group_size;
     s.P = c->attn_splits > 0 ? c->attn_splits : 32;
-    int64_t pd = 2048 / n_bh;
+    int64_t pd = 1024 / n_bh;   // ~1024 workgroups per launch of the dense baseline
     s.P_dense = (int)(pd < 4 ? 4 : (pd > 256 ? 256 : pd));
     s.Pmax = s.P > s.P_dense ? s.P : s.P_dense;
     auto al = [](size_t b) { return (b + 255) / 256 * 256; };

@@ -10,7 +10,7 @@
 //
 // Logits are kept in base-2 units (q is pre-multiplied by sigma * log2 e) so the exponentials
 // are single exp2 instructions; the softmax is unchanged by the change of base.
-#include "lvr_internal.h"
+#include "mfma_score.h"
 
 namespace {
 
@@ -273,6 +273,147 @@ dense_partial_kernel(const void *__restrict__ K, const void *__restrict__ V, con
     }
 }
 
+// Dense baseline for bf16 caches with the logits on the matrix cores.  A wave takes tiles of 16
+// rows: K in MFMA operand layout (scores as in mfma_score.h, q pre-scaled by sigma*log2 e), V in
+// row layout (lane (sub, li): row 4i+sub, channels 8li..8li+7).  The lanes that hold the scores
+// keep the running maximum, turn the tile's scores into weights and hand them (and the rescale
+// factor) to the V lanes through LDS; the weighted sum of V runs on the vector ALU.
+template <int HB>
+__global__ void __launch_bounds__(256)
+dense_mfma_kernel(const void *__restrict__ K, const void *__restrict__ V, const float *__restrict__ q,
+                  float *__restrict__ part_ml, float *__restrict__ part_o, int64_t cap_rows, int64_t n_total, int P,
+                  int n_q_heads, int n_kv_heads, int G, float qscale) {
+    constexpr int NH = HB * 4;
+    __shared__ uint4 s_bq[HB][4][64];
+    __shared__ float s_p[4][NH][4][4];      // [wave][head][row % 4][row / 4]
+    __shared__ float s_alpha[4][NH];
+    __shared__ float sm_m[4][NH], sm_l[4][NH];
+    __shared__ float sm_o[4][NH][LVR_D];
+    const int bh = blockIdx.y, p = blockIdx.x;
+    const int b = bh / n_kv_heads, kvh = bh % n_kv_heads;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 15, kq = lane >> 4;     // MFMA roles
+    const int sub = kq, li = n;                  // V roles
+    const int64_t hq0 = (int64_t)b * n_q_heads + kvh * G;
+
+    const int64_t R = (((n_total + P - 1) / P) + 15) & ~(int64_t)15;
+    const int64_t start = (int64_t)p * R;
+    const int64_t end = (start + R < n_total) ? start + R : n_total;
+
+    lvr_bf16x8 bq[HB][4];
+    lvr_build_q_frags_wg<HB>(q + hq0 * LVR_D, G, qscale, s_bq, bq);
+    const bool rep = n >= 8 && n < 12;           // this lane holds scores of head hb*4 + n - 8
+    const char *Kb = static_cast<const char *>(K) + (int64_t)bh * cap_rows * LVR_D * 2;
+    const char *Vb = static_cast<const char *>(V) + (int64_t)bh * cap_rows * LVR_D * 2;
+
+    float m_run[HB], l_run[HB], acc[NH][8];
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) {
+        m_run[hb] = -INFINITY;
+        l_run[hb] = 0.f;
+    }
+#pragma unroll
+    for (int h = 0; h < NH; ++h) lvr_zero8(acc[h]);
+
+    for (int64_t r0 = start + wave * 16; r0 < end; r0 += 64) {   // uniform over the wave
+        uint4 av[4];
+        lvr_raw8<lvr_bf16_t> vr[4];
+        {
+            int64_t row = r0 + n;
+            if (row >= end) row = end - 1;
+            lvr_load_a_frags(Kb, row, av);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int64_t row = r0 + 4 * i + sub;
+            if (row >= end) row = end - 1;
+            lvr_load_raw(Vb, row, li, vr[i]);
+        }
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb) {
+            lvr_f32x4 s = lvr_score_tile(av, bq[hb]);
+            float tmax = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (r0 + 4 * kq + j >= end) s[j] = -INFINITY;
+                tmax = fmaxf(tmax, s[j]);
+            }
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+            const float m_new = fmaxf(m_run[hb], tmax);
+            const float alpha = exp2_safe(m_run[hb], m_new);
+            float psum = 0.f;
+            float pj[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                pj[j] = exp2_safe(s[j], m_new);
+                psum += pj[j];
+            }
+            l_run[hb] = l_run[hb] * alpha + psum;
+            m_run[hb] = m_new;
+            if (rep) {
+                const int h = hb * 4 + n - 8;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) s_p[wave][h][j][kq] = pj[j];
+                if (kq == 0) s_alpha[wave][h] = alpha;
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        float vx[4][8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) lvr_unpack(vr[i], vx[i]);
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+            const float4 pw = *reinterpret_cast<const float4 *>(&s_p[wave][h][sub][0]);
+            const float al = s_alpha[wave][h];
+#pragma unroll
+            for (int c = 0; c < 8; ++c)
+                acc[h][c] = acc[h][c] * al + pw.x * vx[0][c] + pw.y * vx[1][c] + pw.z * vx[2][c] + pw.w * vx[3][c];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+    // per wave: add the four row subsets (same running maximum), collect l over the score lanes
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            float a = acc[h][c];
+            a += __shfl_xor(a, 16, 64);
+            a += __shfl_xor(a, 32, 64);
+            if (sub == 0) sm_o[wave][h][li * 8 + c] = a;
+        }
+    }
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) {
+        float lh = l_run[hb];
+        lh += __shfl_xor(lh, 16, 64);
+        lh += __shfl_xor(lh, 32, 64);
+        if (rep && kq == 0) {
+            sm_m[wave][hb * 4 + n - 8] = m_run[hb];
+            sm_l[wave][hb * 4 + n - 8] = lh;
+        }
+    }
+    __syncthreads();
+    for (int item = threadIdx.x; item < G * LVR_D; item += 256) {
+        const int h = item / LVR_D, c = item % LVR_D;
+        const float M = fmaxf(fmaxf(sm_m[0][h], sm_m[1][h]), fmaxf(sm_m[2][h], sm_m[3][h]));
+        float o = 0.f, lt = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float sc = exp2_safe(sm_m[w][h], M);
+            o += sc * sm_o[w][h][c];
+            lt += sc * sm_l[w][h];
+        }
+        part_o[((hq0 + h) * P + p) * LVR_D + c] = o;
+        if (c == 0) {
+            part_ml[((hq0 + h) * P + p) * 2] = M;
+            part_ml[((hq0 + h) * P + p) * 2 + 1] = lt;
+        }
+    }
+}
+
 template <typename KT>
 hipError_t launch_dense_t(lvr_index *ix, const float *q, float *out, int P, hipStream_t st) {
     dim3 grid((unsigned)P, (unsigned)lvr_n_bh(ix));
@@ -322,6 +463,17 @@ int lvr_dense_splits(const lvr_index *ix) {
 
 hipError_t lvr_launch_dense_partial(lvr_index *ix, const float *q, hipStream_t st) {
     const int P = lvr_dense_splits(ix);
+    if (ix->cfg.kv_dtype == LVR_BF16 && ix->n_total > 0) {
+        dim3 grid((unsigned)P, (unsigned)lvr_n_bh(ix));
+        const float qscale = ix->sigma * LOG2E;
+        if (ix->G <= 4)
+            hipLaunchKernelGGL(dense_mfma_kernel<1>, grid, dim3(256), 0, st, ix->K, ix->V, q, ix->part_ml, ix->part_o,
+                               ix->cap_rows, ix->n_total, P, ix->cfg.n_q_heads, ix->cfg.n_kv_heads, ix->G, qscale);
+        else
+            hipLaunchKernelGGL(dense_mfma_kernel<2>, grid, dim3(256), 0, st, ix->K, ix->V, q, ix->part_ml, ix->part_o,
+                               ix->cap_rows, ix->n_total, P, ix->cfg.n_q_heads, ix->cfg.n_kv_heads, ix->G, qscale);
+        return hipGetLastError();
+    }
     return ix->cfg.kv_dtype == LVR_BF16 ? launch_dense_t<lvr_bf16_t>(ix, q, nullptr, P, st)
                                         : launch_dense_t<lvr_f32_t>(ix, q, nullptr, P, st);
 }
