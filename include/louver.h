@@ -77,7 +77,9 @@ typedef struct lvr_config {
     uint32_t flags;      /* lvr_flags                                                            */
     int64_t capacity;    /* max keys per (sequence, KV head): the arena is sized once (App. "GPU Update") */
     float scale;         /* sigma; 0 means 1/sqrt(head_dim)  (Sec. 2, "Attention")               */
-    int32_t attn_splits; /* P partial-softmax splits per query head (0 = default)                */
+    int32_t attn_splits; /* P > 0: up to P partial-softmax splits per head, then a combine launch;
+                          * 0: default (64);  -1: one workgroup per head, 16 splits merged in LDS,
+                          * single launch (slower when there are few heads)                    */
 } lvr_config;
 
 /* Counters of the most recent lvr_query / lvr_decode_step, summed over batch and heads. */

@@ -31,7 +31,7 @@ int check_config(const lvr_config *c) {
     if (c->n_q_heads % c->n_kv_heads != 0) return LVR_E_INVALID;
     if (c->kv_dtype != LVR_BF16 && c->kv_dtype != LVR_F32) return LVR_E_INVALID;
     if (c->grouping != LVR_GROUP_CONTIGUOUS && c->grouping != LVR_GROUP_TREE) return LVR_E_INVALID;
-    if (c->scale < 0.f || c->attn_splits < 0) return LVR_E_INVALID;
+    if (c->scale < 0.f || c->attn_splits < -1) return LVR_E_INVALID;
     if (c->head_dim != LVR_D) return LVR_E_UNSUPPORTED;
     const int G = c->n_q_heads / c->n_kv_heads;
     if (!(G == 1 || G == 2 || G == 4 || G == 8)) return LVR_E_UNSUPPORTED;
@@ -56,7 +56,7 @@ Sizes sizes_of(const lvr_config *c) {
     const int64_t n_bh = (int64_t)c->batch * c->n_kv_heads, n_bhq = (int64_t)c->batch * c->n_q_heads;
     s.cap_rows = (c->capacity + 63) / 64 * 64;
     s.max_groups = s.cap_rows / c->group_size;
-    s.P = c->attn_splits > 0 ? c->attn_splits : 32;
+    s.P = c->attn_splits > 0 ? c->attn_splits : 64;
     int64_t pd = 1024 / n_bh;   // ~1024 workgroups per launch of the dense baseline
     s.P_dense = (int)(pd < 4 ? 4 : (pd > 256 ? 256 : pd));
     s.Pmax = s.P > s.P_dense ? s.P : s.P_dense;
@@ -131,6 +131,7 @@ int lvr_create(const lvr_config *cfg, lvr_index **out) {
     ix->max_groups = s.max_groups;
     ix->P = s.P;
     ix->P_dense = s.P_dense;
+    ix->attn_one_launch = cfg->attn_splits < 0;
     ix->elt = cfg->kv_dtype == LVR_BF16 ? 2 : 4;
     ix->sigma = cfg->scale > 0.f ? cfg->scale : 1.0f / sqrtf((float)cfg->head_dim);
     hipError_t e = hipGetDevice(&ix->device);
@@ -278,13 +279,18 @@ int lvr_sparse_attention(lvr_index *ix, const float *q, const int32_t *idx, cons
     if (!ix || !q || !count || !out || cap < 0 || (cap > 0 && !idx)) return LVR_E_INVALID;
     if (!ix->built) return LVR_E_STATE;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (ix->attn_one_launch) {
+        Timed t(ix, LVR_K_ATTN_PARTIAL, st);
+        LVR_HIP(lvr_launch_sparse_attention_wg(ix, q, idx, count, 1, cap, out, nullptr, st));
+        return LVR_OK;
+    }
     {
         Timed t(ix, LVR_K_ATTN_PARTIAL, st);
         LVR_HIP(lvr_launch_sparse_partial(ix, q, idx, count, 1, cap, st));
     }
     {
         Timed t(ix, LVR_K_ATTN_COMBINE, st);
-        LVR_HIP(lvr_launch_combine(ix, out, ix->P, nullptr, st));
+        LVR_HIP(lvr_launch_combine(ix, out, ix->P, count, 1, cap, nullptr, st));
     }
     return LVR_OK;
 }
@@ -296,13 +302,19 @@ int lvr_decode_step(lvr_index *ix, const float *q, const float *tau, float *out,
     hipStream_t st = static_cast<hipStream_t>(stream);
     int rc = enqueue_query(ix, q, tau, out_idx, cap, st);
     if (rc != LVR_OK) return rc;
+    if (ix->attn_one_launch) {   // reads the set sizes from the internal counters and hands them to the caller
+        Timed t(ix, LVR_K_ATTN_PARTIAL, st);
+        LVR_HIP(lvr_launch_sparse_attention_wg(ix, q, out_idx, lvr_head_count(ix), LVR_CNT_STRIDE, cap, out, out_count, st));
+        ix->counters_dirty = 0;
+        return LVR_OK;
+    }
     {   // the attention reads the set sizes straight from the internal counters ...
         Timed t(ix, LVR_K_ATTN_PARTIAL, st);
         LVR_HIP(lvr_launch_sparse_partial(ix, q, out_idx, lvr_head_count(ix), LVR_CNT_STRIDE, cap, st));
     }
     {   // ... and the combine pass hands them to the caller
         Timed t(ix, LVR_K_ATTN_COMBINE, st);
-        LVR_HIP(lvr_launch_combine(ix, out, ix->P, out_count, st));
+        LVR_HIP(lvr_launch_combine(ix, out, ix->P, lvr_head_count(ix), LVR_CNT_STRIDE, cap, out_count, st));
     }
     ix->counters_dirty = 0;
     return LVR_OK;
@@ -318,7 +330,7 @@ int lvr_dense_attention(lvr_index *ix, const float *q, float *out, void *stream)
     }
     {
         Timed t(ix, LVR_K_DENSE_COMBINE, st);
-        LVR_HIP(lvr_launch_combine(ix, out, lvr_dense_splits(ix), nullptr, st));
+        LVR_HIP(lvr_launch_combine(ix, out, lvr_dense_splits(ix), nullptr, 0, 0, nullptr, st));
     }
     return LVR_OK;
 }

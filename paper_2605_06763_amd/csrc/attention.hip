@@ -20,6 +20,16 @@ __device__ __forceinline__ float exp2_safe(float a, float b) {   // 2^(a-b) with
     return (a == -INFINITY) ? 0.f : exp2f(a - b);
 }
 
+// Split geometry of the sparse attention: 16 entries per split (one gather batch) while the
+// list fits in P_max splits, longer splits otherwise.  Returns the split length; *used = splits
+// that hold entries.  The partial and the combine kernel derive it from the same count.
+__device__ __forceinline__ int64_t split_length(int64_t cnt, int P_max, int *used) {
+    int64_t L = (((cnt + P_max - 1) / P_max) + 15) & ~(int64_t)15;
+    if (L < 16) L = 16;
+    *used = (int)((cnt + L - 1) / L);
+    return L;
+}
+
 // One wave per (query head, split).  The split's positions are fetched with one coalesced load,
 // then rows are gathered 16 at a time (K and V of four row-quads in flight together).  The
 // partials are merged by combine_kernel in a launch of its own: making them visible to a
@@ -41,7 +51,9 @@ sparse_attention_kernel(const void *__restrict__ K, const void *__restrict__ V, 
     int64_t cnt = count[hq * count_stride];
     if (cnt > cap) cnt = cap;
     if (cnt < 0) cnt = 0;
-    const int64_t L = (((cnt + P - 1) / P) + 15) & ~(int64_t)15;
+    int used;
+    const int64_t L = split_length(cnt, P, &used);
+    if (p >= used) return;     // the combine pass reads only the `used` partials
     const int64_t start = (int64_t)p * L;
     const int64_t end = (start + L < cnt) ? start + L : cnt;
 
@@ -123,27 +135,164 @@ sparse_attention_kernel(const void *__restrict__ K, const void *__restrict__ V, 
     }
 }
 
-// Merge of the P partial triples of one query head.  512 threads: the weights
-// w_p = 2^(m_p - M) are computed once into LDS, then thread (slice s, channel c) sums every
-// fourth partial of channel c and the four slices are added through LDS.
+// Sparse attention in ONE launch: a 1024-thread workgroup (16 waves) per query head.  Each wave
+// takes a contiguous share of the head's index list exactly as sparse_attention_kernel does,
+// then the 16 partial triples are merged through LDS, so no partials travel through HBM and no
+// combine launch follows.  Thread 0 also publishes (and clears) the head's internal counter
+// when asked to.
+template <typename KT>
+__global__ void __launch_bounds__(1024)
+sparse_attention_wg_kernel(const void *__restrict__ K, const void *__restrict__ V,
+                           const int32_t *__restrict__ pos_slot, const float *__restrict__ q,
+                           const int32_t *__restrict__ idx, const int32_t *__restrict__ count, int count_stride,
+                           int64_t cap, float *__restrict__ out, int64_t cap_rows, int64_t n_total, int n_q_heads,
+                           int n_kv_heads, int G, float qscale, int32_t *__restrict__ head_count,
+                           int32_t *__restrict__ head_stat, int32_t *__restrict__ publish_count) {
+    constexpr int NW = 16;
+    __shared__ float s_m[NW], s_l[NW];
+    __shared__ float s_o[NW][LVR_D];
+    const int64_t hq = blockIdx.x;
+    const int b = (int)(hq / n_q_heads), h = (int)(hq % n_q_heads);
+    const int bh = b * n_kv_heads + h / G;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, sub = lane >> 4, li = lane & 15;
+
+    int64_t cnt = count[hq * count_stride];
+    const int32_t true_cnt = (int32_t)cnt;
+    if (cnt > cap) cnt = cap;
+    if (cnt < 0) cnt = 0;
+    const int64_t L = (((cnt + NW - 1) / NW) + 15) & ~(int64_t)15;
+    const int64_t start = (int64_t)wave * L;
+    const int64_t end = (start + L < cnt) ? start + L : cnt;
+
+    float qv[8];
+    {
+        const float *qh = q + hq * LVR_D + li * 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qv[e] = qh[e] * qscale;
+    }
+    const char *Kb = static_cast<const char *>(K) + (int64_t)bh * cap_rows * LVR_D * sizeof(KT);
+    const char *Vb = static_cast<const char *>(V) + (int64_t)bh * cap_rows * LVR_D * sizeof(KT);
+    const int32_t *my_idx = idx + hq * cap;
+    const int32_t *pslot = pos_slot ? pos_slot + (int64_t)bh * cap_rows : nullptr;
+
+    float m = -INFINITY, l = 0.f, acc[8];
+    lvr_zero8(acc);
+    for (int64_t c0 = start; c0 < end; c0 += 64) {          // uniform over the wave
+        int64_t e = c0 + lane;
+        int myslot = -1;
+        if (e < end) {
+            const int64_t pos = my_idx[e];
+            if (pos >= 0 && pos < n_total) myslot = pslot ? pslot[pos] : (int)pos;
+        }
+        const int chunk = (int)((end - c0 < 64) ? end - c0 : 64);
+        for (int b0 = 0; b0 < chunk; b0 += 16) {
+            lvr_raw8<KT> kr[4], vr[4];
+            int slot[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                slot[i] = __shfl(myslot, (b0 + i * 4 + sub) & 63, 64);
+                if (b0 + i * 4 + sub >= chunk) slot[i] = -1;
+                const int64_t sl = slot[i] < 0 ? 0 : slot[i];
+                lvr_load_raw(Kb, sl, li, kr[i]);
+                lvr_load_raw(Vb, sl, li, vr[i]);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float kx[8], vx[8];
+                lvr_unpack(kr[i], kx);
+                lvr_unpack(vr[i], vx);
+                float d = 0.f;
+#pragma unroll
+                for (int c = 0; c < 8; ++c) d += qv[c] * kx[c];
+                float s = lvr_row16_sum(d);
+                s = (slot[i] >= 0) ? s : -INFINITY;
+                const float m_new = fmaxf(m, s);
+                const float alpha = exp2_safe(m, m_new);
+                const float w = exp2_safe(s, m_new);
+                l = l * alpha + w;
+#pragma unroll
+                for (int c = 0; c < 8; ++c) acc[c] = acc[c] * alpha + w * vx[c];
+                m = m_new;
+            }
+        }
+    }
+    float m_all = fmaxf(m, __shfl_xor(m, 16, 64));
+    m_all = fmaxf(m_all, __shfl_xor(m_all, 32, 64));
+    const float sc = exp2_safe(m, m_all);
+    l *= sc;
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+        float a = acc[c] * sc;
+        a += __shfl_xor(a, 16, 64);
+        a += __shfl_xor(a, 32, 64);
+        if (sub == 0) s_o[wave][li * 8 + c] = a;
+    }
+    if (lane == 0) {
+        s_m[wave] = m_all;
+        s_l[wave] = l;
+    }
+    __syncthreads();
+    if (threadIdx.x < LVR_D) {
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) M = fmaxf(M, s_m[w]);
+        float num = 0.f, den = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float wt = exp2_safe(s_m[w], M);
+            den += wt * s_l[w];
+            num += wt * s_o[w][threadIdx.x];
+        }
+        out[hq * LVR_D + threadIdx.x] = (den > 0.f && M != -INFINITY) ? num / den : 0.f;
+    }
+    if (publish_count && threadIdx.x == 0) {
+        publish_count[hq] = true_cnt;
+        head_stat[hq] = true_cnt;
+        head_count[hq * LVR_CNT_STRIDE] = 0;
+    }
+}
+
+// Merge of the partial triples of one query head.  512 threads: thread (slice s, channel c) owns
+// every fourth partial of channel c; its values are requested first, then the weights
+// w_p = 2^(m_p - M) are computed into LDS, the slices are weighted, and the four slices are
+// added through LDS.  With a count pointer the number of partials in use follows the sparse
+// attention's split geometry; without one all P are merged (dense baseline).
 constexpr int COMBINE_MAX_P = 256;
 
 __global__ void __launch_bounds__(512)
 combine_kernel(const float *__restrict__ part_ml, const float *__restrict__ part_o, float *__restrict__ out, int P,
-               int32_t *__restrict__ head_count, int32_t *__restrict__ head_stat, int32_t *__restrict__ publish_count) {
+               const int32_t *__restrict__ count, int count_stride, int64_t cap, int32_t *__restrict__ head_count,
+               int32_t *__restrict__ head_stat, int32_t *__restrict__ publish_count) {
     __shared__ float s_w[COMBINE_MAX_P];
     __shared__ float s_red[8];
     __shared__ float s_num[4][LVR_D];
     const int64_t hq = blockIdx.x;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    if (publish_count && t == 0) {
-        const int32_t c = head_count[hq * LVR_CNT_STRIDE];
-        publish_count[hq] = c;
-        head_stat[hq] = c;
-        head_count[hq * LVR_CNT_STRIDE] = 0;
+    int used = P;
+    if (count) {
+        int64_t cnt = count[hq * count_stride];
+        if (publish_count && t == 0) {
+            publish_count[hq] = (int32_t)cnt;
+            head_stat[hq] = (int32_t)cnt;
+            head_count[hq * LVR_CNT_STRIDE] = 0;
+        }
+        if (cnt > cap) cnt = cap;
+        if (cnt < 0) cnt = 0;
+        split_length(cnt, P, &used);
     }
-    const float m = (t < P) ? part_ml[(hq * P + t) * 2] : -INFINITY;
-    const float l = (t < P) ? part_ml[(hq * P + t) * 2 + 1] : 0.f;
+    const int c = t & (LVR_D - 1), sl = t >> 7;
+    const float *po = part_o + hq * P * LVR_D + c;
+    // up to 8 partials per thread are fetched before anything depends on them
+    float pv[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int p = sl + 4 * i;
+        pv[i] = (p < used) ? po[(int64_t)p * LVR_D] : 0.f;
+    }
+    const float m = (t < used) ? part_ml[(hq * P + t) * 2] : -INFINITY;
+    const float l = (t < used) ? part_ml[(hq * P + t) * 2 + 1] : 0.f;
     float mx = m;
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
@@ -163,11 +312,14 @@ combine_kernel(const float *__restrict__ part_ml, const float *__restrict__ part
     float den = 0.f;
 #pragma unroll
     for (int w = 0; w < 8; ++w) den += s_red[w];
-    const int c = t & (LVR_D - 1), sl = t >> 7;
     float num = 0.f;
-    const float *po = part_o + hq * P * LVR_D + c;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int p = sl + 4 * i;
+        num += (p < used) ? s_w[p] * pv[i] : 0.f;
+    }
 #pragma unroll 4
-    for (int p = sl; p < P; p += 4) num += s_w[p] * po[(int64_t)p * LVR_D];
+    for (int p = sl + 32; p < used; p += 4) num += s_w[p] * po[(int64_t)p * LVR_D];
     s_num[sl][c] = num;
     __syncthreads();
     if (t < LVR_D) {
@@ -437,6 +589,24 @@ hipError_t launch_dense_t(lvr_index *ix, const float *q, float *out, int P, hipS
 
 }  // namespace
 
+hipError_t lvr_launch_sparse_attention_wg(lvr_index *ix, const float *q, const int32_t *idx, const int32_t *count,
+                                          int count_stride, int64_t cap, float *out, int32_t *publish_count,
+                                          hipStream_t st) {
+    const int n_bhq = lvr_n_bhq(ix);
+    const float qscale = ix->sigma * LOG2E;
+    if (ix->cfg.kv_dtype == LVR_BF16)
+        hipLaunchKernelGGL(sparse_attention_wg_kernel<lvr_bf16_t>, dim3((unsigned)n_bhq), dim3(1024), 0, st, ix->K, ix->V,
+                           ix->pos_slot, q, idx, count, count_stride, cap, out, ix->cap_rows, ix->n_total,
+                           ix->cfg.n_q_heads, ix->cfg.n_kv_heads, ix->G, qscale, lvr_head_count(ix), lvr_head_stat(ix),
+                           publish_count);
+    else
+        hipLaunchKernelGGL(sparse_attention_wg_kernel<lvr_f32_t>, dim3((unsigned)n_bhq), dim3(1024), 0, st, ix->K, ix->V,
+                           ix->pos_slot, q, idx, count, count_stride, cap, out, ix->cap_rows, ix->n_total,
+                           ix->cfg.n_q_heads, ix->cfg.n_kv_heads, ix->G, qscale, lvr_head_count(ix), lvr_head_stat(ix),
+                           publish_count);
+    return hipGetLastError();
+}
+
 hipError_t lvr_launch_sparse_partial(lvr_index *ix, const float *q, const int32_t *idx, const int32_t *count,
                                      int count_stride, int64_t cap, hipStream_t st) {
     const int n_bhq = lvr_n_bhq(ix);
@@ -478,9 +648,10 @@ hipError_t lvr_launch_dense_partial(lvr_index *ix, const float *q, hipStream_t s
                                         : launch_dense_t<lvr_f32_t>(ix, q, nullptr, P, st);
 }
 
-hipError_t lvr_launch_combine(lvr_index *ix, float *out, int P, int32_t *publish_count, hipStream_t st) {
+hipError_t lvr_launch_combine(lvr_index *ix, float *out, int P, const int32_t *count, int count_stride, int64_t cap,
+                              int32_t *publish_count, hipStream_t st) {
     const int n_bhq = lvr_n_bhq(ix);
-    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)n_bhq), dim3(512), 0, st, ix->part_ml, ix->part_o, out, P,
-                       lvr_head_count(ix), lvr_head_stat(ix), publish_count);
+    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)n_bhq), dim3(512), 0, st, ix->part_ml, ix->part_o, out, P, count,
+                       count_stride, cap, lvr_head_count(ix), lvr_head_stat(ix), publish_count);
     return hipGetLastError();
 }

@@ -25,7 +25,8 @@ struct lvr_index {
     int64_t n_total;       // keys held
     int64_t n_indexed;     // keys inside groups (multiple of r)
     int built;
-    int P;                 // attention splits
+    int attn_one_launch;   // sparse attention as one workgroup per head (default) or partials + combine
+    int P;                 // attention splits of the two-launch form
     int P_dense;           // splits of the dense baseline
     float sigma;
     size_t elt;            // bytes per K/V element
@@ -98,10 +99,16 @@ hipError_t lvr_launch_publish_counts(lvr_index *ix, int32_t *out_count, hipStrea
 // partial softmax per (head, split); count is read with the given stride (1 = caller's array)
 hipError_t lvr_launch_sparse_partial(lvr_index *ix, const float *q, const int32_t *idx, const int32_t *count,
                                      int count_stride, int64_t cap, hipStream_t st);
+// whole sparse attention of a head in one workgroup (16 splits merged through LDS), one launch
+hipError_t lvr_launch_sparse_attention_wg(lvr_index *ix, const float *q, const int32_t *idx, const int32_t *count,
+                                          int count_stride, int64_t cap, float *out, int32_t *publish_count,
+                                          hipStream_t st);
 hipError_t lvr_launch_dense_partial(lvr_index *ix, const float *q, hipStream_t st);
-// merge P partials; if publish_count is not NULL also publishes the internal per-head counters to it
-// (and to the statistics copy) and clears them
-hipError_t lvr_launch_combine(lvr_index *ix, float *out, int P, int32_t *publish_count, hipStream_t st);
+// merge the partials of every head.  count == NULL: all P (dense baseline); otherwise as many as the
+// sparse split geometry uses for that count.  publish_count != NULL: also hands the internal
+// per-head counters to the caller (and to the statistics copy) and clears them
+hipError_t lvr_launch_combine(lvr_index *ix, float *out, int P, const int32_t *count, int count_stride, int64_t cap,
+                              int32_t *publish_count, hipStream_t st);
 int lvr_dense_splits(const lvr_index *ix);
 
 #ifdef __HIPCC__

@@ -153,14 +153,17 @@ def test_head_group_sizes(G, oracle, hq, hkv, separate):
         assert (np.abs(ix.dense(q) - ref).max(axis=-1) / np.abs(ref).max(axis=-1)).max() <= G.ATTN_TOL
 
 
-def test_non_default_scale_and_general_fp32_query(G, oracle):
+@pytest.mark.parametrize("splits", [-1, 0, 7])
+def test_non_default_scale_and_general_fp32_query(G, oracle, splits):
     n = 1200
     cache = _small_cache(2, n)
     q = W.make_queries(2, n_q_heads=8, exact_bf16=False)      # full fp32 query values
-    with G.Index(cache.K, cache.V, "bf16", 8, scale=0.031) as ix:
+    with G.Index(cache.K, cache.V, "bf16", 8, scale=0.031, attn_splits=splits) as ix:
         tau = G.oracle_taus(oracle, ix, q, frac=0.04)
-        idx, cnt, out = ix.query(q, tau)
-        G.check_step(oracle, ix, q, tau, idx, cnt, out, tag="scale=0.031")
+        for fused in (False, True):
+            idx, cnt, out = ix.query(q, tau, fused=fused)
+            G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=f"scale=0.031 splits={splits} step={fused}")
+            assert ix.stats()["keys_emitted"] == int(cnt.sum())
 
 
 def test_overflow_is_reported_not_silent(G, oracle):
@@ -182,15 +185,16 @@ def test_overflow_is_reported_not_silent(G, oracle):
         assert ix.stats()["overflow"] == 0
 
 
-def test_sparse_attention_on_caller_lists(G, oracle):
+@pytest.mark.parametrize("splits", [-1, 0, 5, 32], ids=["one_launch", "default", "5_splits", "32_splits"])
+def test_sparse_attention_on_caller_lists(G, oracle, splits):
     """lvr_sparse_attention on lists the caller made up (unsorted, with out-of-range entries,
-    uneven lengths including empty)."""
+    uneven lengths including empty), in the one-launch form and with partials through HBM."""
     import paper_2605_06763_amd as L
     n = 640
     cache = _small_cache(2, n)
     q = W.make_queries(2, n_q_heads=8)
     g = np.random.default_rng(3)
-    with G.Index(cache.K, cache.V, "bf16", 8) as ix:
+    with G.Index(cache.K, cache.V, "bf16", 8, attn_splits=splits) as ix:
         cap = 300
         idx = np.zeros((1, 8, cap), dtype=np.int32)
         cnt = np.array([[0, 1, 2, 5, 64, 65, 299, 300]], dtype=np.int32)
