@@ -184,8 +184,7 @@ int lvr_build(lvr_index *ix, const void *K, const void *V, int64_t n, const int6
     ix->n_indexed = 0;
     if (n > 0) {
         Timed t(ix, LVR_K_COPY, st);
-        LVR_HIP(lvr_launch_copy_rows(ix, K, ks, ix->K, 0, n, st));
-        LVR_HIP(lvr_launch_copy_rows(ix, V, vs, ix->V, 0, n, st));
+        LVR_HIP(lvr_launch_copy_kv(ix, K, ks, V, vs, 0, n, st));
     }
     const int r = ix->cfg.group_size;
     const int64_t n_groups = n / r;
@@ -209,8 +208,7 @@ int lvr_append(lvr_index *ix, const void *k_new, const void *v_new, int64_t m, v
     const int64_t strides[3] = {(int64_t)ix->cfg.n_kv_heads * m * LVR_D, m * LVR_D, LVR_D};
     {
         Timed t(ix, LVR_K_COPY, st);
-        LVR_HIP(lvr_launch_copy_rows(ix, k_new, strides, ix->K, ix->n_total, m, st));
-        LVR_HIP(lvr_launch_copy_rows(ix, v_new, strides, ix->V, ix->n_total, m, st));
+        LVR_HIP(lvr_launch_copy_kv(ix, k_new, strides, v_new, strides, ix->n_total, m, st));
     }
     ix->n_total += m;
     // every full buffer of B keys becomes B/r new groups at the tail of the index

@@ -15,18 +15,25 @@
 namespace {
 
 // 16 bytes per thread, arbitrary source strides (in elements) for (batch, head, token).
-__global__ void copy_rows_kernel(const char *__restrict__ src, char *__restrict__ dst, int64_t sb, int64_t sh,
-                                 int64_t st, int n_kv_heads, int64_t cap_rows, int64_t dst_row0, int64_t rows,
-                                 int row_bytes, int elt) {
+// blockIdx.z = 0 copies keys, 1 copies values, so an append is one launch.
+struct CopySide {
+    const char *src;
+    char *dst;
+    int64_t sb, sh, st;
+};
+
+__global__ void copy_rows_kernel(CopySide k, CopySide v, int n_kv_heads, int64_t cap_rows, int64_t dst_row0,
+                                 int64_t rows, int row_bytes, int elt) {
+    const CopySide c = blockIdx.z == 0 ? k : v;
     const int chunks = row_bytes / 16;
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= rows * chunks) return;
     int bh = blockIdx.y;
     int b = bh / n_kv_heads, h = bh % n_kv_heads;
     int64_t row = i / chunks;
-    int c = (int)(i % chunks);
-    const uint4 *s = reinterpret_cast<const uint4 *>(src + (b * sb + h * sh + row * st) * elt) + c;
-    uint4 *d = reinterpret_cast<uint4 *>(dst + ((int64_t)bh * cap_rows + dst_row0 + row) * row_bytes) + c;
+    int ch = (int)(i % chunks);
+    const uint4 *s = reinterpret_cast<const uint4 *>(c.src + (b * c.sb + h * c.sh + row * c.st) * elt) + ch;
+    uint4 *d = reinterpret_cast<uint4 *>(c.dst + ((int64_t)bh * cap_rows + dst_row0 + row) * row_bytes) + ch;
     *d = *s;
 }
 
@@ -112,15 +119,16 @@ __global__ void iota_rows_kernel(int32_t *slot_pos, int32_t *pos_slot, int64_t c
 
 }  // namespace
 
-hipError_t lvr_launch_copy_rows(lvr_index *ix, const void *src, const int64_t strides[3], void *dst_base,
-                                int64_t dst_row0, int64_t rows, hipStream_t st) {
+hipError_t lvr_launch_copy_kv(lvr_index *ix, const void *K, const int64_t ks[3], const void *V, const int64_t vs[3],
+                              int64_t dst_row0, int64_t rows, hipStream_t st) {
     if (rows <= 0) return hipSuccess;
     const int row_bytes = (int)(LVR_D * ix->elt);
     const int64_t total = rows * (row_bytes / 16);
-    dim3 grid((unsigned)((total + 255) / 256), (unsigned)lvr_n_bh(ix));
-    hipLaunchKernelGGL(copy_rows_kernel, grid, dim3(256), 0, st, static_cast<const char *>(src),
-                       static_cast<char *>(dst_base), strides[0], strides[1], strides[2], ix->cfg.n_kv_heads,
-                       ix->cap_rows, dst_row0, rows, row_bytes, (int)ix->elt);
+    dim3 grid((unsigned)((total + 255) / 256), (unsigned)lvr_n_bh(ix), 2);
+    CopySide k{static_cast<const char *>(K), static_cast<char *>(ix->K), ks[0], ks[1], ks[2]};
+    CopySide v{static_cast<const char *>(V), static_cast<char *>(ix->V), vs[0], vs[1], vs[2]};
+    hipLaunchKernelGGL(copy_rows_kernel, grid, dim3(256), 0, st, k, v, ix->cfg.n_kv_heads, ix->cap_rows, dst_row0, rows,
+                       row_bytes, (int)ix->elt);
     return hipGetLastError();
 }
 

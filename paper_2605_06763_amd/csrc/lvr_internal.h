@@ -65,7 +65,7 @@ static inline int lvr_n_bhq(const lvr_index *ix) { return ix->cfg.batch * ix->cf
 // Device counters.  Atomics that hit one 128-byte line are served one after the other
 // (about 12 ns each on this part), so every counter that takes atomics owns a whole line.
 #define LVR_CNT_STRIDE 32   // ints per counter slot (128 bytes)
-#define LVR_MIN_SEG_GROUPS 128
+#define LVR_MIN_SEG_GROUPS 64
 // per query head: size of the retrieved set of the running query (padded).  Zero between
 // queries: the kernel that publishes the counts clears them.
 static inline int32_t *lvr_head_count(const lvr_index *ix) { return ix->counters; }
@@ -80,8 +80,9 @@ static inline size_t lvr_counter_ints(int n_bh, int n_bhq, int64_t max_groups) {
 }
 
 // ---- launchers (each returns a hipError_t from hipGetLastError after the launch) ----
-hipError_t lvr_launch_copy_rows(lvr_index *ix, const void *src, const int64_t strides[3], void *dst_base,
-                                int64_t dst_row0, int64_t rows, hipStream_t st);
+// copies `rows` key rows and value rows into the arena starting at arena row dst_row0 (one launch)
+hipError_t lvr_launch_copy_kv(lvr_index *ix, const void *K, const int64_t ks[3], const void *V, const int64_t vs[3],
+                              int64_t dst_row0, int64_t rows, hipStream_t st);
 hipError_t lvr_launch_build_groups(lvr_index *ix, int64_t g0, int64_t g1, hipStream_t st);
 hipError_t lvr_launch_iota_rows(lvr_index *ix, int64_t row0, int64_t rows, hipStream_t st);
 // clears the per-head counters (used when there is no index to prune)

@@ -14,6 +14,8 @@
 // once per segment instead of twice, and removes one kernel tail from the step.
 // The per-head counters must be zero when the kernel starts; the kernels that publish the
 // counts (publish_counts_kernel, combine_kernel) clear them for the next query.
+#include <stdlib.h>
+
 #include "emitter.h"
 #include "mfma_score.h"
 
@@ -34,7 +36,7 @@ struct FusedArgs {
     int log2r, n_q_heads, n_kv_heads, G, buffer_dense, n_segs, tiles_per_wave;
 };
 
-template <int HB, int S>
+template <int HB, int S, int UA>   // UA = centre tiles per phase-A trip
 __global__ void __launch_bounds__(256)
 query_fused_kernel(const FusedArgs a) {
     __shared__ uint4 s_bq[HB][4][64];
@@ -48,6 +50,42 @@ query_fused_kernel(const FusedArgs a) {
     const int n = lane & 15, kq = lane >> 4;
     const int64_t hq0 = (int64_t)b * a.n_q_heads + kvh * a.G;
     const bool buffer_wg = (int)blockIdx.x >= a.n_segs;
+
+    // ---- phase A, first trip: the centre and radius loads do not depend on q, so they are put
+    // in flight before the prologue builds the query operand ----
+    constexpr int SP = (S <= 4) ? S : 1;      // radii are fetched ahead only when they are few
+    const char *Cb = static_cast<const char *>(a.centres) + (int64_t)bh * a.max_groups * LVR_D * 2;
+    const float *Rb = a.radii + (int64_t)bh * a.max_groups * S;
+    const int64_t n_tiles = (a.n_groups + 15) >> 4;
+    const int64_t tile0 = ((int64_t)blockIdx.x * 4 + wave) * a.tiles_per_wave;
+    uint4 av[UA][4];
+    float rad[UA][4][SP];
+    auto issueA = [&](int it) {
+#pragma unroll
+        for (int u = 0; u < UA; ++u) {
+            const int64_t g0 = (tile0 + it + u) * 16;
+            int64_t g = g0 + n;
+            if (g >= a.n_groups) g = a.n_groups - 1;
+            lvr_load_a_frags(Cb, g, av[u]);
+            if constexpr (S <= 4) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    int64_t gj = g0 + 4 * kq + j;
+                    if (gj >= a.n_groups) gj = a.n_groups - 1;
+                    const float *rp = Rb + gj * S;
+                    if constexpr (S == 4) {
+                        const float4 r = *reinterpret_cast<const float4 *>(rp);
+                        rad[u][j][0] = r.x; rad[u][j][1] = r.y; rad[u][j][2] = r.z; rad[u][j][3] = r.w;
+                    } else {
+#pragma unroll
+                        for (int s = 0; s < S; ++s) rad[u][j][s] = rp[s];
+                    }
+                }
+            }
+        }
+    };
+    const bool phaseA = !buffer_wg && tile0 < n_tiles && a.n_groups > 0;   // wave-uniform
+    if (phaseA) issueA(0);
 
     // ---- prologue: subspace norms of q (phase A only) and the B operand of q ----
     if (!buffer_wg && (int)threadIdx.x < HB * 64) {
@@ -83,43 +121,13 @@ query_fused_kernel(const FusedArgs a) {
         for (int hb = 0; hb < HB; ++hb)
 #pragma unroll
             for (int s = 0; s < S; ++s) qn[hb][s] = rep[hb] ? s_qn[hb * 4 + n - 8][s] : 0.f;
-        const char *Cb = static_cast<const char *>(a.centres) + (int64_t)bh * a.max_groups * LVR_D * 2;
-        const float *Rb = a.radii + (int64_t)bh * a.max_groups * S;
-        const int64_t n_tiles = (a.n_groups + 15) >> 4;
-        const int64_t seg_tile0 = (int64_t)blockIdx.x * 4 * a.tiles_per_wave;
-        const int64_t tile0 = seg_tile0 + (int64_t)wave * a.tiles_per_wave;
         uint32_t mybits = 0;   // lane `it` keeps the 16-bit survivor mask of the wave's tile `it`
-        for (int it = 0; it < a.tiles_per_wave; it += 2) {
+        for (int it = 0; it < a.tiles_per_wave; it += UA) {
             if (tile0 + it >= n_tiles) break;   // wave-uniform
-            constexpr int SP = (S <= 4) ? S : 1;
-            uint4 av[2][4];
-            float rad[2][4][SP];
-            int64_t g_row[2];
+            if (it > 0) issueA(it);
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const int64_t g0 = (tile0 + it + u) * 16;
-                int64_t g = g0 + n;
-                if (g >= a.n_groups) g = a.n_groups - 1;
-                g_row[u] = g0;
-                lvr_load_a_frags(Cb, g, av[u]);
-                if constexpr (S <= 4) {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        int64_t gj = g0 + 4 * kq + j;
-                        if (gj >= a.n_groups) gj = a.n_groups - 1;
-                        const float *rp = Rb + gj * S;
-                        if constexpr (S == 4) {
-                            const float4 r = *reinterpret_cast<const float4 *>(rp);
-                            rad[u][j][0] = r.x; rad[u][j][1] = r.y; rad[u][j][2] = r.z; rad[u][j][3] = r.w;
-                        } else {
-#pragma unroll
-                            for (int s = 0; s < S; ++s) rad[u][j][s] = rp[s];
-                        }
-                    }
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
+            for (int u = 0; u < UA; ++u) {
+                const int64_t g_row = (tile0 + it + u) * 16;
                 uint32_t alive4 = 0;
 #pragma unroll
                 for (int hb = 0; hb < HB; ++hb) {
@@ -131,7 +139,7 @@ query_fused_kernel(const FusedArgs a) {
 #pragma unroll
                             for (int s = 0; s < S; ++s) ub += rad[u][j][s] * qn[hb][s];
                         } else {
-                            int64_t gj = g_row[u] + 4 * kq + j;
+                            int64_t gj = g_row + 4 * kq + j;
                             if (gj >= a.n_groups) gj = a.n_groups - 1;
                             const float4 *rp = reinterpret_cast<const float4 *>(Rb + gj * S);
 #pragma unroll
@@ -141,7 +149,8 @@ query_fused_kernel(const FusedArgs a) {
                                       r.w * qn[hb][4 * s4 + 3];
                             }
                         }
-                        const bool ok = rep[hb] && ub >= taue[hb] && (g_row[u] + 4 * kq + j) < a.n_groups;
+                        const bool ok = rep[hb] && ub >= taue[hb] && (g_row + 4 * kq + j) < a.n_groups &&
+                                        (it + u) < a.tiles_per_wave;
                         alive4 |= ok ? (1u << j) : 0u;
                     }
                 }
@@ -234,14 +243,14 @@ query_fused_kernel(const FusedArgs a) {
         if (__ballot(em[hb].count > 0)) em[hb].flush(a.emit, lane, rep[hb]);
 }
 
-template <int HB>
+template <int HB, int UA>
 void launch_s(dim3 grid, hipStream_t st, const FusedArgs &a, int S) {
     switch (S) {
-        case 1: hipLaunchKernelGGL((query_fused_kernel<HB, 1>), grid, dim3(256), 0, st, a); break;
-        case 2: hipLaunchKernelGGL((query_fused_kernel<HB, 2>), grid, dim3(256), 0, st, a); break;
-        case 4: hipLaunchKernelGGL((query_fused_kernel<HB, 4>), grid, dim3(256), 0, st, a); break;
-        case 8: hipLaunchKernelGGL((query_fused_kernel<HB, 8>), grid, dim3(256), 0, st, a); break;
-        default: hipLaunchKernelGGL((query_fused_kernel<HB, 16>), grid, dim3(256), 0, st, a); break;
+        case 1: hipLaunchKernelGGL((query_fused_kernel<HB, 1, UA>), grid, dim3(256), 0, st, a); break;
+        case 2: hipLaunchKernelGGL((query_fused_kernel<HB, 2, UA>), grid, dim3(256), 0, st, a); break;
+        case 4: hipLaunchKernelGGL((query_fused_kernel<HB, 4, UA>), grid, dim3(256), 0, st, a); break;
+        case 8: hipLaunchKernelGGL((query_fused_kernel<HB, 8, UA>), grid, dim3(256), 0, st, a); break;
+        default: hipLaunchKernelGGL((query_fused_kernel<HB, 16, UA>), grid, dim3(256), 0, st, a); break;
     }
 }
 
@@ -275,9 +284,14 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
     a.G = ix->G;
     a.buffer_dense = (ix->cfg.flags & LVR_ATTEND_BUFFER_DENSE) ? 1 : 0;
     const int n_bh = lvr_n_bh(ix);
-    // segment = 4 waves x tiles_per_wave tiles x 16 groups; aim at ~1024 workgroups per launch
-    const int64_t want = a.n_groups * n_bh / 1024;
-    int tpw = 2;
+    // segment = 4 waves x tiles_per_wave tiles x 16 groups; aim at a fixed number of workgroups per launch
+    static const int64_t target_wgs = [] {
+        const char *e = getenv("LVR_SEG_TARGET_WGS");
+        const long v = e ? atol(e) : 0;
+        return (int64_t)(v > 0 ? v : 1024);
+    }();
+    const int64_t want = a.n_groups * n_bh / target_wgs;
+    int tpw = 1;
     while (tpw < 16 && (int64_t)tpw * 64 < want) tpw *= 2;
     a.tiles_per_wave = tpw;
     const int seg_groups = tpw * 64;
@@ -287,9 +301,15 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
     ix->n_segs = a.n_segs;
     if (a.n_segs + has_buffer == 0) return hipSuccess;
     dim3 grid((unsigned)(a.n_segs + has_buffer), (unsigned)n_bh);
-    if (ix->G <= 4)
-        launch_s<1>(grid, st, a, ix->cfg.n_subspaces);
-    else
-        launch_s<2>(grid, st, a, ix->cfg.n_subspaces);
+    // one centre tile per trip (fewer registers, five waves per SIMD) for the small segments of short
+    // contexts, two per trip for long ones: measured crossover between 32k and 128k keys
+    const bool one = tpw == 1;
+    if (ix->G <= 4) {
+        if (one) launch_s<1, 1>(grid, st, a, ix->cfg.n_subspaces);
+        else launch_s<1, 2>(grid, st, a, ix->cfg.n_subspaces);
+    } else {
+        if (one) launch_s<2, 1>(grid, st, a, ix->cfg.n_subspaces);
+        else launch_s<2, 2>(grid, st, a, ix->cfg.n_subspaces);
+    }
     return hipGetLastError();
 }
