@@ -40,7 +40,6 @@ int check_config(const lvr_config *c) {
     if (c->buffer_size <= 0 || c->buffer_size % 16 != 0 || c->buffer_size % c->group_size != 0) return LVR_E_INVALID;
     if (c->attn_splits > 256) return LVR_E_INVALID;
     if (c->capacity > (int64_t)1 << 30) return LVR_E_UNSUPPORTED;   // positions are int32
-    if (c->grouping == LVR_GROUP_TREE) return LVR_E_UNSUPPORTED;     // not built yet
     return LVR_OK;
 }
 
@@ -48,6 +47,9 @@ struct Sizes {
     int64_t cap_rows, max_groups;
     int P, P_dense, Pmax;
     size_t kv, centres, radii, list, counters, part_ml, part_o, total;
+    // tree grouping only
+    int64_t tree_keys;
+    size_t maps, tree_keybytes, tree_axis, tree_partial, tree_temp, chunk;
 };
 
 Sizes sizes_of(const lvr_config *c) {
@@ -69,12 +71,28 @@ Sizes sizes_of(const lvr_config *c) {
     s.part_ml = al((size_t)n_bhq * s.Pmax * 2 * sizeof(float));
     s.part_o = al((size_t)n_bhq * s.Pmax * LVR_D * sizeof(float));
     s.total = 2 * s.kv + s.centres + s.radii + s.list + s.counters + s.part_ml + s.part_o;
+    s.tree_keys = 0;
+    s.maps = s.tree_keybytes = s.tree_axis = s.tree_partial = s.tree_temp = s.chunk = 0;
+    if (c->grouping == LVR_GROUP_TREE) {
+        int64_t gp = 1;
+        while (gp < s.max_groups) gp <<= 1;
+        const int64_t np = gp * c->group_size;
+        s.tree_keys = n_bh * np;
+        s.maps = al((size_t)n_bh * s.cap_rows * sizeof(int32_t));
+        s.tree_keybytes = al((size_t)s.tree_keys * sizeof(uint64_t));
+        s.tree_axis = al((size_t)n_bh * gp * sizeof(int32_t));
+        s.tree_partial = al((size_t)n_bh * (np / 1024 + 1) * 258 * sizeof(double));
+        s.tree_temp = 0;   // asked from the sort library at create time
+        s.chunk = al((size_t)n_bh * c->buffer_size * LVR_D * elt);
+        s.total += 2 * s.maps + 2 * s.tree_keybytes + s.tree_axis + s.tree_partial + 2 * s.chunk;
+    }
     return s;
 }
 
 void free_all(lvr_index *ix) {
     void *ptrs[] = {ix->K, ix->V, ix->centres, ix->radii, ix->slot_pos, ix->pos_slot,
-                    ix->surv_list, ix->counters, ix->part_ml, ix->part_o};
+                    ix->surv_list, ix->counters, ix->part_ml, ix->part_o, ix->tree_keys_a, ix->tree_keys_b,
+                    ix->tree_axis, ix->tree_partial, ix->tree_temp, ix->chunk_K, ix->chunk_V};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
 }
@@ -143,6 +161,20 @@ int lvr_create(const lvr_config *cfg, lvr_index **out) {
         if (e != hipSuccess) break;
         e = hipMalloc(a.p, a.bytes);
     }
+    if (e == hipSuccess && cfg->grouping == LVR_GROUP_TREE) {
+        ix->tree_cap_keys = s.tree_keys;
+        ix->tree_temp_bytes = lvr_tree_sort_temp_bytes(s.tree_keys);
+        struct { void **p; size_t bytes; } tallocs[] = {
+            {(void **)&ix->slot_pos, s.maps}, {(void **)&ix->pos_slot, s.maps},
+            {(void **)&ix->tree_keys_a, s.tree_keybytes}, {(void **)&ix->tree_keys_b, s.tree_keybytes},
+            {(void **)&ix->tree_axis, s.tree_axis}, {(void **)&ix->tree_partial, s.tree_partial},
+            {&ix->tree_temp, ix->tree_temp_bytes ? ix->tree_temp_bytes : 256}, {&ix->chunk_K, s.chunk},
+            {&ix->chunk_V, s.chunk}};
+        for (auto &a : tallocs) {
+            if (e != hipSuccess) break;
+            e = hipMalloc(a.p, a.bytes);
+        }
+    }
     if (e == hipSuccess) e = hipMemset(ix->counters, 0, s.counters);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
@@ -182,12 +214,25 @@ int lvr_build(lvr_index *ix, const void *K, const void *V, int64_t n, const int6
     ix->built = 0;
     ix->n_total = 0;
     ix->n_indexed = 0;
-    if (n > 0) {
+    const int r = ix->cfg.group_size;
+    const int64_t n_groups = n / r;
+    if (n > 0 && ix->cfg.grouping == LVR_GROUP_TREE) {
+        // rows of the n_groups*r leading keys go into the arena in tree order; the tail stays in arrival order
+        Timed t(ix, LVR_K_COPY, st);
+        const int64_t n_tree = n_groups * r;
+        hipError_t e = lvr_tree_group(ix, K, ks, V, vs, n_tree, 0, st);
+        if (e == hipErrorInvalidValue) return LVR_E_UNSUPPORTED;   // sort key wider than 64 bits
+        LVR_HIP(e);
+        if (n > n_tree) {
+            const char *Kt = static_cast<const char *>(K) + n_tree * ks[2] * (int64_t)ix->elt;
+            const char *Vt = static_cast<const char *>(V) + n_tree * vs[2] * (int64_t)ix->elt;
+            LVR_HIP(lvr_launch_copy_kv(ix, Kt, ks, Vt, vs, n_tree, n - n_tree, st));
+            LVR_HIP(lvr_launch_iota_rows(ix, n_tree, n - n_tree, st));
+        }
+    } else if (n > 0) {
         Timed t(ix, LVR_K_COPY, st);
         LVR_HIP(lvr_launch_copy_kv(ix, K, ks, V, vs, 0, n, st));
     }
-    const int r = ix->cfg.group_size;
-    const int64_t n_groups = n / r;
     {
         Timed t(ix, LVR_K_BUILD, st);
         LVR_HIP(lvr_launch_build_groups(ix, 0, n_groups, st));
@@ -209,6 +254,7 @@ int lvr_append(lvr_index *ix, const void *k_new, const void *v_new, int64_t m, v
     {
         Timed t(ix, LVR_K_COPY, st);
         LVR_HIP(lvr_launch_copy_kv(ix, k_new, strides, v_new, strides, ix->n_total, m, st));
+        LVR_HIP(lvr_launch_iota_rows(ix, ix->n_total, m, st));   // no-op without position maps
     }
     ix->n_total += m;
     // every full buffer of B keys becomes B/r new groups at the tail of the index
@@ -218,6 +264,24 @@ int lvr_append(lvr_index *ix, const void *k_new, const void *v_new, int64_t m, v
     if (full > 0) {
         const int64_t g0 = ix->n_indexed / r, g1 = g0 + full * (B / r);
         Timed t(ix, LVR_K_BUILD, st);
+        if (ix->cfg.grouping == LVR_GROUP_TREE) {
+            // each chunk of B buffered keys is clustered on its own (Sec. 4.3): stage its rows, then
+            // write them back in tree order
+            const size_t row_bytes = LVR_D * ix->elt;
+            const int64_t cs[3] = {(int64_t)ix->cfg.n_kv_heads * B * LVR_D, B * LVR_D, LVR_D};
+            for (int64_t c = 0; c < full; ++c) {
+                const int64_t row0 = ix->n_indexed + c * B;
+                LVR_HIP(hipMemcpy2DAsync(ix->chunk_K, B * row_bytes, static_cast<char *>(ix->K) + row0 * row_bytes,
+                                         ix->cap_rows * row_bytes, B * row_bytes, lvr_n_bh(ix),
+                                         hipMemcpyDeviceToDevice, st));
+                LVR_HIP(hipMemcpy2DAsync(ix->chunk_V, B * row_bytes, static_cast<char *>(ix->V) + row0 * row_bytes,
+                                         ix->cap_rows * row_bytes, B * row_bytes, lvr_n_bh(ix),
+                                         hipMemcpyDeviceToDevice, st));
+                hipError_t e = lvr_tree_group(ix, ix->chunk_K, cs, ix->chunk_V, cs, B, row0, st);
+                if (e == hipErrorInvalidValue) return LVR_E_UNSUPPORTED;
+                LVR_HIP(e);
+            }
+        }
         LVR_HIP(lvr_launch_build_groups(ix, g0, g1, st));
         ix->n_indexed += full * B;
     }

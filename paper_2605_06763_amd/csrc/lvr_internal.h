@@ -37,6 +37,14 @@ struct lvr_index {
     float *radii;          // [batch][H_kv][max_groups][S]
     int32_t *slot_pos;     // [batch][H_kv][cap_rows] token position of arena row (TREE grouping), else NULL
     int32_t *pos_slot;     // inverse map, or NULL
+    // work space of the tree grouping (TREE grouping only)
+    uint64_t *tree_keys_a, *tree_keys_b;   // [n_bh * padded entries] sort keys, ping-pong
+    int32_t *tree_axis;                    // [n_bh * nodes] split axis per node of the current level
+    double *tree_partial;                  // partial coordinate statistics of large nodes
+    void *tree_temp;                       // rocPRIM sort storage
+    size_t tree_temp_bytes;
+    int64_t tree_cap_keys;                 // keys tree_keys_* can hold
+    void *chunk_K, *chunk_V;               // [n_bh][B][d] staging of a buffer chunk being regrouped
     // work space (device)
     int32_t *surv_list;    // [batch][H_kv][max_groups]: segment x owns entries [x*seg_groups, (x+1)*seg_groups)
     int32_t *counters;     // see lvr_head_count / lvr_overflow_flag / lvr_seg_count
@@ -111,6 +119,10 @@ hipError_t lvr_launch_dense_partial(lvr_index *ix, const float *q, hipStream_t s
 hipError_t lvr_launch_combine(lvr_index *ix, float *out, int P, const int32_t *count, int count_stride, int64_t cap,
                               int32_t *publish_count, hipStream_t st);
 int lvr_dense_splits(const lvr_index *ix);
+// tree grouping (tree.hip)
+size_t lvr_tree_sort_temp_bytes(int64_t total_keys);
+hipError_t lvr_tree_group(lvr_index *ix, const void *Ksrc, const int64_t ks[3], const void *Vsrc, const int64_t vs[3],
+                          int64_t n_real, int64_t row0, hipStream_t st);
 
 #ifdef __HIPCC__
 // ------------------------------------------------------------------------------------------

@@ -367,3 +367,99 @@ def test_strided_build_input(G, oracle):
         tau = G.oracle_taus(oracle, ix, q, frac=0.05)
         idx, cnt, out = ix.query(q, tau)
         G.check_step(oracle, ix, q, tau, idx, cnt, out, tag="strided")
+
+
+# ------------------------------------------------------------------ tree grouping (Alg. 2)
+@pytest.mark.parametrize("dtype,n,r", [("bf16", 1024, 4), ("f32", 512, 4), ("bf16", 2048, 8), ("bf16", 256, 2)])
+def test_tree_grouping_equals_oracle_tree(G, oracle, dtype, n, r):
+    """n = r * 2^k: the arena order produced on the GPU is exactly the left-to-right leaf order of
+    the oracle's balanced tree (axis of largest variance, median split, ties by position)."""
+    import paper_2605_06763_amd as L
+    cache = _small_cache(2 if dtype == "bf16" else 1, n, hkv=2 if dtype == "bf16" else 1)
+    hkv = cache.K.shape[1]
+    with G.Index(cache.K, cache.V, dtype, hkv, group_size=r, grouping=L.LVR_GROUP_TREE) as ix:
+        centres, radii, slot_pos, keys = ix.export()
+        for h in range(hkv):
+            label, order, leaves = oracle.balanced_tree(cache.K[0, h], r)
+            assert leaves == n // r
+            assert np.array_equal(slot_pos[0, h], order), (h, np.nonzero(slot_pos[0, h] != order)[0][:8])
+            stored = W.bf16_bits_to_f32(keys[0, h]).reshape(n, 128) if dtype == "bf16" else keys[0, h]
+            assert np.array_equal(stored, cache.K[0, h][order])        # rows really are regrouped
+
+
+@pytest.mark.parametrize("n,r,S", [(1500, 4, 4), (777, 8, 2), (64, 4, 16), (5, 4, 4)])
+def test_tree_grouping_queries(G, oracle, n, r, S):
+    """Ragged sizes (padded tree): the grouping is a valid partition, balls enclose their members,
+    and query + attention equal the oracle's in original token positions."""
+    import paper_2605_06763_amd as L
+    cache = _small_cache(2, n)
+    q = W.make_queries(2, n_q_heads=8)
+    with G.Index(cache.K, cache.V, "bf16", 8, group_size=r, n_subspaces=S, grouping=L.LVR_GROUP_TREE,
+                 buffer_size=64) as ix:
+        centres, radii, slot_pos, keys = ix.export()
+        n_idx = n // r * r
+        for h in range(2):
+            assert sorted(slot_pos[0, h, :n_idx].tolist()) == list(range(n_idx))
+            assert slot_pos[0, h, n_idx:].tolist() == list(range(n_idx, n))
+            if n_idx:
+                label = np.empty(n_idx, dtype=np.int32)
+                label[slot_pos[0, h, :n_idx]] = np.arange(n_idx) // r
+                c = W.bf16_bits_to_f32(centres[0, h]).reshape(n_idx // r, 128).astype(np.float64)
+                need = oracle.ball_radii_for_centres(cache.K[0, h, :n_idx], label, c, S)
+                assert np.all(radii[0, h] >= need)
+        for frac, fused in ((0.02, True), (0.3, False)):
+            tau = G.oracle_taus(oracle, ix, q, frac=frac)
+            idx, cnt, out = ix.query(q, tau, fused=fused)
+            G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=f"tree n={n} r={r} S={S} frac={frac}")
+        ref = oracle.dense_attention(ix.K, ix.V, q, ix.sigma, 8)
+        assert (np.abs(ix.dense(q) - ref).max(axis=-1) / np.abs(ref).max(axis=-1)).max() <= G.ATTN_TOL
+
+
+def test_tree_grouping_append(G, oracle):
+    """Appends in tree mode: every chunk of B buffered keys is regrouped on its own; positions
+    reported by the query stay the original token positions."""
+    import paper_2605_06763_amd as L
+    n0, steps, B = 131, 70, 32
+    cache = _small_cache(5, n0)
+    k_new, v_new = W.make_append_stream(5, steps, cache)
+    qs = W.drift_queries(5, steps, n_q_heads=8)
+    with G.Index(cache.K, cache.V, "bf16", 8, capacity=n0 + steps, buffer_size=B, grouping=L.LVR_GROUP_TREE) as ix:
+        for t in range(steps):
+            ix.append(k_new[t][:, :, None, :], v_new[t][:, :, None, :])
+            if t % 9 == 0 or t == steps - 1:
+                tau = G.oracle_taus(oracle, ix, qs[t], frac=0.06)
+                idx, cnt, out = ix.query(qs[t], tau, fused=True)
+                G.check_step(oracle, ix, qs[t], tau, idx, cnt, out, tag=f"tree append t={t}")
+        n, n_indexed = L.lvr_length(ix.h)
+        centres, radii, slot_pos, keys = ix.export()
+        assert n_indexed == 128 + 2 * B
+        for h in range(2):
+            assert sorted(slot_pos[0, h, :128].tolist()) == list(range(128))
+            for c0 in (128, 128 + B):                      # each chunk is a permutation of its own rows
+                assert sorted(slot_pos[0, h, c0:c0 + B].tolist()) == list(range(c0, c0 + B))
+            stored = W.bf16_bits_to_f32(keys[0, h]).reshape(n, 128)
+            assert np.array_equal(stored, ix.K[0, h][slot_pos[0, h]])
+
+
+def test_tree_grouping_prunes_where_contiguous_cannot(G, oracle):
+    """Keys drawn from 64 tight clusters but stored in random order: consecutive positions are
+    unrelated, so contiguous groups are wide and survive; the tree regroups neighbours in key space."""
+    import paper_2605_06763_amd as L
+    g = np.random.default_rng(31)
+    n, hkv, hq = 4096, 2, 8
+    cent = g.standard_normal((hkv, 64, 128)).astype(np.float32) * 3.0
+    which = g.integers(0, 64, size=(hkv, n))
+    K = np.stack([cent[h][which[h]] for h in range(hkv)])[None]
+    K = W.round_to_bf16(K + 0.05 * g.standard_normal(K.shape).astype(np.float32))
+    V = W.round_to_bf16(g.standard_normal((1, hkv, n, 128)).astype(np.float32))
+    q = W.make_queries(2, n_q_heads=hq)
+    surv = {}
+    for name, grouping in (("contiguous", L.LVR_GROUP_CONTIGUOUS), ("tree", L.LVR_GROUP_TREE)):
+        with G.Index(K, V, "bf16", hq, grouping=grouping) as ix:
+            tau = G.oracle_taus(oracle, ix, q, frac=0.02)
+            idx, cnt, out = ix.query(q, tau, fused=True)
+            G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=name)
+            st = ix.stats()
+            surv[name] = st["groups_surviving"] / st["groups_scored"]
+    G.say("surviving fraction:", surv)
+    assert surv["tree"] < 0.5 * surv["contiguous"]
