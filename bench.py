@@ -60,6 +60,9 @@ def main():
     ap.add_argument("--config", type=int, default=3, choices=[2, 3, 4, 5])
     ap.add_argument("--group-size", type=int, default=4)
     ap.add_argument("--subspaces", type=int, default=4)
+    ap.add_argument("--keys", choices=["workload", "local"], default="workload",
+                    help="'local': supplementary cache whose keys have positional locality (the pruned regime); "
+                         "not one of the five workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle sample")
     args = ap.parse_args()
@@ -85,7 +88,11 @@ def main():
     appending = cid == 5
     log(f"[bench] config {cid} {c['name']}: generating inputs")
     t0 = time.time()
-    cache = W.make_cache(cid)
+    if args.keys == "local":
+        assert not (cid == 5), "the supplementary cache has no append stream"
+        cache = W.make_local_cache(cid)
+    else:
+        cache = W.make_cache(cid)
     K_bits, V_bits = cache.K_bits(), cache.V_bits()
     Kd = torch.from_numpy(K_bits.view(np.int16)).view(torch.bfloat16).to(dev)
     Vd = torch.from_numpy(V_bits.view(np.int16)).view(torch.bfloat16).to(dev)
@@ -218,7 +225,7 @@ def main():
                     bytes_per_launch=int(query_bytes), avg_launch_us=round(filt["avg_us"], 2))
     # HBM bytes per launch measured offline with rocprofv3 --pmc (profiles/), when this workload was profiled
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
-    if os.path.exists(tpath) and args.group_size == 4 and args.subspaces == 4:
+    if os.path.exists(tpath) and args.group_size == 4 and args.subspaces == 4 and args.keys == "workload":
         for line in open(tpath):
             f = line.split()
             if len(f) == 3 and f[0] == f"config{cid}" and f[1] == "query_fused_kernel":
@@ -239,7 +246,7 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"config{cid}:{c['name']}", "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
+        "config": {"workload": f"config{cid}:{c['name']}" + (" [supplementary: keys with positional locality]" if args.keys == "local" else ""), "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
                    "head_dim": d, "context": int(n_now), "kv_storage": "bf16", "group_size": args.group_size,
                    "subspaces": args.subspaces, "grouping": "contiguous",
                    "step": "append+query+attention" if appending else "query+attention"},

@@ -463,3 +463,20 @@ def test_tree_grouping_prunes_where_contiguous_cannot(G, oracle):
             surv[name] = st["groups_surviving"] / st["groups_scored"]
     G.say("surviving fraction:", surv)
     assert surv["tree"] < 0.5 * surv["contiguous"]
+
+
+def test_everything_qualifies_large(G, oracle):
+    """tau = -inf on 20000 keys: every emission queue flushes hundreds of times; every position
+    must come back exactly once per head and the attention equals the dense result."""
+    n = 20000
+    cache = _small_cache(2, n, hkv=1)
+    q = W.make_queries(2, n_q_heads=4)
+    for flags in (0, 2):
+        with G.Index(cache.K, cache.V, "bf16", 4, flags=flags) as ix:
+            tau = np.full((1, 4), -np.inf, dtype=np.float32)
+            idx, cnt, out = ix.query(q, tau, fused=True)
+            assert (cnt == n).all()
+            for h in range(4):
+                assert np.array_equal(np.sort(idx[0, h]), np.arange(n))
+            ref = oracle.dense_attention(ix.K, ix.V, q, ix.sigma, 4)
+            assert (np.abs(out - ref).max(axis=-1) / np.abs(ref).max(axis=-1)).max() <= G.ATTN_TOL

@@ -12,6 +12,7 @@ from .generators import (  # noqa: F401
     bf16_bits_to_f32,
     f32_to_bf16_bits,
     make_cache,
+    make_local_cache,
     make_queries,
     make_append_stream,
     drift_queries,

@@ -4,7 +4,8 @@ Random streams are counter-based (numpy's Philox) and keyed by
 (1000 * config id + stream id, sequence index), so every consumer that asks for
 the same (config, stream, sequence) sees the same numbers no matter the order of
 calls.  Stream ids: 0 keys, 1 values, 2 queries, 3 channel scales, 4 appended
-keys, 5 appended values, 6 planted positions, 7 query drift noise.
+keys, 5 appended values, 6 planted positions, 7 query drift noise, 8 block means of the
+supplementary cache with positional locality.
 
 Values are drawn in fp32 and, for bf16 workloads, rounded to the nearest bf16
 (ties to even) so the fp32 arrays handed to the CPU side and the 16-bit patterns
@@ -19,6 +20,7 @@ from numpy.random import Generator, Philox
 
 STREAM_K, STREAM_V, STREAM_Q, STREAM_SCALE = 0, 1, 2, 3
 STREAM_APPEND_K, STREAM_APPEND_V, STREAM_PLANT, STREAM_DRIFT = 4, 5, 6, 7
+STREAM_LOCAL = 8
 
 # The five workloads.  "dist": "iid" = N(0,1) entries; "channel" = N(0,1) entries
 # times a per-channel scale exp(0.5 g), g ~ N(0,1), with four seeded channels
@@ -123,6 +125,30 @@ def make_cache(config_id: int, *, n: int | None = None, batch: int | None = None
         V[b] = _draw_rows(config_id, STREAM_V, b, (hkv, n, d), "iid", None, c["dtype"])
     return KVCache(K=K, V=V, dtype=c["dtype"], channel_scale=scales,
                    meta=dict(config=config_id, name=c["name"]))
+
+
+def make_local_cache(config_id: int, *, block: int = 64, spread: float = 3.0, noise: float = 0.05,
+                     n: int | None = None) -> KVCache:
+    """Supplementary workload (not one of the five): keys with positional locality.  Every run of
+    `block` consecutive tokens shares a mean drawn from N(0, spread^2) per coordinate and adds
+    N(0, noise^2) of its own, so neighbouring keys are close in key space and groups of consecutive
+    keys have tight bounding balls.  Values as in the base workload.  Same shapes as config_id."""
+    c = CONFIGS[config_id]
+    n = c["n"] if n is None else int(n)
+    batch, hkv, d = c["batch"], c["n_kv_heads"], c["head_dim"]
+    nb = (n + block - 1) // block
+    K = np.empty((batch, hkv, n, d), dtype=np.float32)
+    V = np.empty((batch, hkv, n, d), dtype=np.float32)
+    for b in range(batch):
+        g = _rng(config_id, STREAM_LOCAL, b)
+        means = g.standard_normal((hkv, nb, d), dtype=np.float32) * np.float32(spread)
+        K[b] = np.repeat(means, block, axis=1)[:, :n]
+        K[b] += np.float32(noise) * g.standard_normal((hkv, n, d), dtype=np.float32)
+        V[b] = _draw_rows(config_id, STREAM_V, b, (hkv, n, d), "iid", None, c["dtype"])
+    if c["dtype"] == "bf16":
+        K = round_to_bf16(K)
+    return KVCache(K=K, V=V, dtype=c["dtype"], channel_scale=None,
+                   meta=dict(config=config_id, name=c["name"] + "_local_keys"))
 
 
 def make_append_stream(config_id: int, steps: int, cache: KVCache) -> tuple[np.ndarray, np.ndarray]:
