@@ -50,6 +50,9 @@ def _load():
     lib.lvo_ball_index.argtypes = [vp, i32, i64, i32, i32, vp, i64, vp, vp]
     lib.lvo_ball_radii_for_centres.argtypes = [vp, i32, i64, i32, i32, vp, i64, vp, vp]
     lib.lvo_ball_bounds.argtypes = [vp, i32, i32, vp, vp, i64, vp]
+    lib.lvo_aabb_index.argtypes = [vp, i32, i64, i32, vp, i64, vp, vp]
+    lib.lvo_aabb_bounds.argtypes = [vp, i32, vp, vp, i64, vp]
+    lib.lvo_query1_filter.argtypes = [vp, vp, i32, i64, i64, vp, vp]
     lib.lvo_ta_filter.argtypes = [vp, vp, i32, i64, i64, f64, vp]
     lib.lvo_ta_filter.restype = i64
     lib.lvo_balanced_tree.argtypes = [vp, i32, i64, i32, i32, i32, i32, vp, vp]
@@ -184,6 +187,39 @@ def ball_bounds(q, centre, radius):
     f = np.empty((S, n_groups), dtype=np.float64)
     _load().lvo_ball_bounds(_p(q), d, S, _p(centre), _p(radius), n_groups, _p(f))
     return f
+
+
+def aabb_index(K, label, n_groups):
+    """Per-group coordinate-wise minimum and maximum: (lo, hi), each [n_groups][d] fp64."""
+    K, bf = _kv(K)
+    n, d = K.shape
+    label = np.ascontiguousarray(label, dtype=np.int32)
+    lo = np.empty((n_groups, d), dtype=np.float64)
+    hi = np.empty((n_groups, d), dtype=np.float64)
+    _load().lvo_aabb_index(_p(K), bf, n, d, _p(label), n_groups, _p(lo), _p(hi))
+    return lo, hi
+
+
+def aabb_bounds(q, lo, hi):
+    """Largest <q, x> over each box: [n_groups] fp64."""
+    lo = np.ascontiguousarray(lo, dtype=np.float64)
+    hi = np.ascontiguousarray(hi, dtype=np.float64)
+    q = np.ascontiguousarray(q, dtype=np.float32)
+    ub = np.empty(lo.shape[0], dtype=np.float64)
+    _load().lvo_aabb_bounds(_p(q), lo.shape[1], _p(lo), _p(hi), lo.shape[0], _p(ub))
+    return ub
+
+
+def query1_filter(f, label, tau_s):
+    """Alg. 3's candidate mask: f [S][n_groups], label [S][n], tau_s [S] -> bool [n]."""
+    f = np.ascontiguousarray(f, dtype=np.float64)
+    label = np.ascontiguousarray(label, dtype=np.int32)
+    tau_s = np.ascontiguousarray(tau_s, dtype=np.float64)
+    S, n_groups = f.shape
+    n = label.shape[1]
+    alive = np.zeros(n, dtype=np.uint8)
+    _load().lvo_query1_filter(_p(f), _p(label), S, n_groups, n, _p(tau_s), _p(alive))
+    return alive.astype(bool)
 
 
 def ta_filter(f, label, tau):

@@ -14,6 +14,10 @@
  *   ball index             Sec. 4.1 "Ball enclosing", Eq. (1): centre = mean of the group's
  *                          projected keys, radius = largest member distance.
  *   ball bound             Eq. (2) and Sec. 4.2 "Query 2": f = <pi_s q, c> + rho ||pi_s q||.
+ *   box index / bound      appendix "Ablation on Index Design", Def. 1 with an axis-aligned
+ *                          bounding box: per coordinate the smallest and largest member value;
+ *                          the largest <q,x> over the box is sum_c max(q_c lo_c, q_c hi_c).
+ *   Query 1                Sec. 4.2 "Query 1", Alg. 3: per-subspace thresholds, AND across subspaces.
  *   TA filter              Sec. 4.2 "Query 2", Alg. 4: sorted per-subspace bounds, depth scan.
  *   balanced tree          Sec. 4.1 "Grouping via balanced PCA trees", Alg. 2, with leaf ids
  *                          handed out by a running counter (the printed id formula collides
@@ -269,6 +273,52 @@ void lvo_ball_bounds(const float *q, int d, int S, const double *centre, const d
             for (int c = lo; c < hi; ++c) dot += (double)q[c] * centre[i * d + c];
             f[(int64_t)s * n_groups + i] = dot + radius[i * S + s] * qn;
         }
+    }
+}
+
+/* ---------------------------------------------------------------- Def. 1 with boxes */
+
+/* lo[i][c] / hi[i][c] = smallest / largest coordinate c over the members of group i.
+ * A group with no member gets lo = +inf, hi = -inf. */
+void lvo_aabb_index(const void *K, int kv_bf16, int64_t n, int d, const int32_t *label, int64_t n_groups,
+                    double *lo, double *hi) {
+    for (int64_t i = 0; i < n_groups * d; ++i) {
+        lo[i] = INFINITY;
+        hi[i] = -INFINITY;
+    }
+    for (int64_t j = 0; j < n; ++j) {
+        int64_t g = label[j];
+        for (int c = 0; c < d; ++c) {
+            double x = (double)load_elem(K, kv_bf16, j * d + c);
+            if (x < lo[g * d + c]) lo[g * d + c] = x;
+            if (x > hi[g * d + c]) hi[g * d + c] = x;
+        }
+    }
+}
+
+/* ub[i] = max over the box [lo_i, hi_i] of <q, x> = sum_c max(q_c lo_ic, q_c hi_ic). */
+void lvo_aabb_bounds(const float *q, int d, const double *lo, const double *hi, int64_t n_groups, double *ub) {
+    for (int64_t i = 0; i < n_groups; ++i) {
+        double acc = 0.0;
+        for (int c = 0; c < d; ++c) {
+            double a = (double)q[c] * lo[i * d + c], b = (double)q[c] * hi[i * d + c];
+            acc += a > b ? a : b;
+        }
+        ub[i] = acc;
+    }
+}
+
+/* ---------------------------------------------------------------- Alg. 3: Query 1 */
+
+/* f: [S][n_groups] ball bounds, label: [S][n], tau_s: [S].  A key is a candidate iff in every
+ * subspace the ball of its cluster reaches that subspace's threshold. */
+void lvo_query1_filter(const double *f, const int32_t *label, int S, int64_t n_groups, int64_t n,
+                       const double *tau_s, uint8_t *alive) {
+    for (int64_t j = 0; j < n; ++j) {
+        uint8_t a = 1;
+        for (int s = 0; s < S; ++s)
+            if (f[(int64_t)s * n_groups + label[(int64_t)s * n + j]] < tau_s[s]) a = 0;
+        alive[j] = a;
     }
 }
 

@@ -461,3 +461,73 @@ def test_generators_are_seeded_and_bf16_exact():
     q = W.drift_queries(3, 5, n_q_heads=2)
     assert q.shape == (5, 1, 2, 128)
     assert np.array_equal(W.round_to_bf16(q), q)
+
+
+# ------------------------------------------------------------------ boxes (Def. 1) and Query 1 (Alg. 3)
+def test_box_bound_is_the_maximum_over_the_corners(oracle):
+    """Brute force over all 2^d corners of tiny boxes: a linear function attains its maximum over
+    a box at a corner, so the bound must equal the best corner (catches min instead of max, lo/hi
+    swapped, a sign slip for negative q)."""
+    g = np.random.default_rng(15)
+    d = 6
+    K = g.standard_normal((12, d)).astype(np.float32)
+    label = np.repeat(np.arange(3), 4).astype(np.int32)
+    lo, hi = oracle.aabb_index(K, label, 3)
+    for i in range(3):
+        assert np.array_equal(lo[i], K[label == i].min(0)) and np.array_equal(hi[i], K[label == i].max(0))
+    for _ in range(5):
+        q = g.standard_normal(d).astype(np.float32)
+        ub = oracle.aabb_bounds(q, lo, hi)
+        for i in range(3):
+            corners = [sum(float(q[c]) * (hi[i, c] if (mask >> c) & 1 else lo[i, c]) for c in range(d))
+                       for mask in range(1 << d)]
+            assert math.isclose(ub[i], max(corners), rel_tol=1e-12, abs_tol=1e-12)
+            assert np.all(K[label == i].astype(np.float64) @ q.astype(np.float64) <= ub[i] + 1e-12)
+    # a one-point group: the box is the point, the bound is its score
+    lo1, hi1 = oracle.aabb_index(K, np.arange(12, dtype=np.int32), 12)
+    assert np.allclose(oracle.aabb_bounds(q, lo1, hi1), oracle.scores_f64(q, K), rtol=1e-12, atol=1e-12)
+
+
+def test_box_bound_never_looser_than_needed_and_compares_with_ball(oracle):
+    """In one dimension box and ball coincide for a two-point group; in general both dominate
+    every member's score."""
+    K = np.array([[1.0], [3.0]], dtype=np.float32)
+    label = np.zeros(2, dtype=np.int32)
+    lo, hi = oracle.aabb_index(K, label, 1)
+    c, rad = oracle.ball_index(K, label, 1, 1)
+    for qv in (2.0, -0.5):
+        q = np.array([qv], dtype=np.float32)
+        assert math.isclose(oracle.aabb_bounds(q, lo, hi)[0], oracle.ball_bounds(q, c, rad)[0, 0])
+        assert math.isclose(oracle.aabb_bounds(q, lo, hi)[0], max(qv * 1.0, qv * 3.0))
+
+
+def test_query1_filter_with_valid_thresholds_keeps_every_relevant_key(oracle):
+    """Alg. 3: with tau_s = tau - sum over the other subspaces of their largest bound (a valid
+    lower bound on a relevant key's subspace term) no relevant key is dropped; with thresholds of
+    -inf everything is a candidate; raising one subspace threshold above all bounds drops all."""
+    g = np.random.default_rng(16)
+    n, d, S, r = 64, 8, 2, 4
+    K = (g.standard_normal((n, d)) * g.uniform(0.3, 3, size=d)).astype(np.float32)
+    q = g.standard_normal(d).astype(np.float32)
+    label = np.stack([(g.permutation(n) // r) for _ in range(S)]).astype(np.int32)
+    f = np.zeros((S, n // r))
+    for s in range(S):
+        lo_, hi_ = oracle.subspace_range(d, S, s)
+        Ks = np.zeros_like(K)
+        Ks[:, lo_:hi_] = K[:, lo_:hi_]
+        c, rad = oracle.ball_index(Ks, label[s], n // r, S)
+        f[s] = oracle.ball_bounds(q, c, rad)[s]
+    score = oracle.scores_f64(q, K)
+    for tau in np.quantile(score, [0.95, 0.5]):
+        tau_s = np.array([tau - sum(f[t].max() for t in range(S) if t != s) for s in range(S)])
+        alive = oracle.query1_filter(f, label, tau_s)
+        assert np.all(alive[score >= tau])
+        want = [all(f[s, label[s, j]] >= tau_s[s] for s in range(S)) for j in range(n)]
+        assert alive.tolist() == want
+    assert oracle.query1_filter(f, label, np.full(S, -np.inf)).all()
+    assert not oracle.query1_filter(f, label, np.array([f[0].max() + 1, -np.inf])).any()
+    # a ball that exactly touches the threshold is kept (a cluster is pruned only when f < tau_s)
+    f1 = np.array([[5.0, 3.0]])
+    lab1 = np.array([[0, 1, 1]], dtype=np.int32)
+    assert oracle.query1_filter(f1, lab1, np.array([5.0])).tolist() == [True, False, False]
+    assert oracle.query1_filter(f1, lab1, np.array([3.0])).tolist() == [True, True, True]
