@@ -60,6 +60,8 @@ def main():
     ap.add_argument("--config", type=int, default=3, choices=[2, 3, 4, 5])
     ap.add_argument("--group-size", type=int, default=4)
     ap.add_argument("--subspaces", type=int, default=4)
+    ap.add_argument("--enclosing", choices=["ball", "aabb"], default="ball")
+    ap.add_argument("--grouping", choices=["contiguous", "tree"], default="contiguous")
     ap.add_argument("--keys", choices=["workload", "local"], default="workload",
                     help="'local': supplementary cache whose keys have positional locality (the pruned regime); "
                          "not one of the five workloads")
@@ -111,7 +113,9 @@ def main():
 
     capacity = n0 + (total_steps + K_steps + 64 if appending else 0)
     cfg = L.make_config(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, kv_dtype=L.LVR_BF16,
-                        group_size=args.group_size, n_subspaces=args.subspaces, buffer_size=256, capacity=capacity)
+                        group_size=args.group_size, n_subspaces=args.subspaces, buffer_size=256, capacity=capacity,
+                        enclosing=L.LVR_ENCLOSE_AABB if args.enclosing == "aabb" else L.LVR_ENCLOSE_BALL,
+                        grouping=L.LVR_GROUP_TREE if args.grouping == "tree" else L.LVR_GROUP_CONTIGUOUS)
     h = L.lvr_create(cfg)
     torch.cuda.synchronize()
     tb = time.time()
@@ -225,7 +229,8 @@ def main():
                     bytes_per_launch=int(query_bytes), avg_launch_us=round(filt["avg_us"], 2))
     # HBM bytes per launch measured offline with rocprofv3 --pmc (profiles/), when this workload was profiled
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
-    if os.path.exists(tpath) and args.group_size == 4 and args.subspaces == 4 and args.keys == "workload":
+    if (os.path.exists(tpath) and args.group_size == 4 and args.subspaces == 4 and args.keys == "workload"
+            and args.enclosing == "ball"):
         for line in open(tpath):
             f = line.split()
             if len(f) == 3 and f[0] == f"config{cid}" and f[1] == "query_fused_kernel":
@@ -248,7 +253,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"config{cid}:{c['name']}" + (" [supplementary: keys with positional locality]" if args.keys == "local" else ""), "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
                    "head_dim": d, "context": int(n_now), "kv_storage": "bf16", "group_size": args.group_size,
-                   "subspaces": args.subspaces, "grouping": "contiguous",
+                   "subspaces": args.subspaces, "grouping": args.grouping, "enclosing": args.enclosing,
                    "step": "append+query+attention" if appending else "query+attention"},
         "roofline": roofline,
         "step_bytes": {"index": int(st["bytes_index"]), "keys": int(st["bytes_keys"]),

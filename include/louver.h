@@ -42,6 +42,13 @@ enum lvr_dtype { LVR_BF16 = 0, LVR_F32 = 1 };
  *               one tree over the full key shared by all subspaces; rows are stored regrouped. */
 enum lvr_grouping { LVR_GROUP_CONTIGUOUS = 0, LVR_GROUP_TREE = 1 };
 
+/* Shape that encloses a group (appendix "Ablation on Index Design", Def. 1).
+ *   BALL: centre + one radius per coordinate block (Sec. 4.1, Eq. (1)); bound of Eq. (2) per block, summed.
+ *   AABB: per coordinate the smallest and largest member value; bound sum_c max(q_c lo_c, q_c hi_c)
+ *         (two dot products per group, usually tighter).  bf16 caches, fused query kernel only;
+ *         n_subspaces is ignored. */
+enum lvr_enclosing { LVR_ENCLOSE_BALL = 0, LVR_ENCLOSE_AABB = 1 };
+
 enum lvr_flags {
     /* Keys not yet in the index (the buffer of Sec. 4.3 "Dynamic Updates") are retrieved
      * whatever their score, as in Alg. 3 / Alg. 4's  K[L*] ∪ B.  Default (flag clear): they are
@@ -74,6 +81,7 @@ typedef struct lvr_config {
     int32_t n_subspaces; /* S in {1,2,4,8,16}: contiguous coordinate blocks of d/S (Sec. 4.1)    */
     int32_t buffer_size; /* B: appended keys are indexed B at a time; multiple of 16 and of r    */
     int32_t grouping;    /* lvr_grouping                                                         */
+    int32_t enclosing;   /* lvr_enclosing                                                        */
     uint32_t flags;      /* lvr_flags                                                            */
     int64_t capacity;    /* max keys per (sequence, KV head): the arena is sized once (App. "GPU Update") */
     float scale;         /* sigma; 0 means 1/sqrt(head_dim)  (Sec. 2, "Attention")               */
@@ -155,7 +163,9 @@ int lvr_get_stats(lvr_index *ix, lvr_stats *out_host);
 /* Synchronises the device and copies the index to host memory for inspection (tests check the
  * enclosure invariant on it).  Any pointer may be NULL to skip that part.
  *   centres_host  [batch][n_kv_heads][n_groups][head_dim] of kv_dtype
+ *                 (AABB: [batch][n_kv_heads][n_groups][2][head_dim], upper corner then lower corner)
  *   radii_host    [batch][n_kv_heads][n_groups][n_subspaces] fp32
+ *                 (AABB: [batch][n_kv_heads][n_groups][1], the rounding allowance of the bound)
  *   slot_pos_host [batch][n_kv_heads][n] int32: token position stored in arena row `slot`
  *                 (group g owns rows g*r .. g*r+r-1; rows >= n_indexed are the buffer)
  *   keys_host     [batch][n_kv_heads][n][head_dim] of kv_dtype, arena row order */

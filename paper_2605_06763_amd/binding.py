@@ -15,6 +15,7 @@ from .build import LIB_PATH
 
 LVR_BF16, LVR_F32 = 0, 1
 LVR_GROUP_CONTIGUOUS, LVR_GROUP_TREE = 0, 1
+LVR_ENCLOSE_BALL, LVR_ENCLOSE_AABB = 0, 1
 LVR_ATTEND_BUFFER_DENSE = 1
 LVR_SEPARATE_KERNELS = 2
 LVR_OK, LVR_E_INVALID, LVR_E_UNSUPPORTED, LVR_E_CAPACITY = 0, -1, -2, -3
@@ -25,7 +26,7 @@ class lvr_config(C.Structure):
     _fields_ = [
         ("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
         ("kv_dtype", C.c_int32), ("group_size", C.c_int32), ("n_subspaces", C.c_int32),
-        ("buffer_size", C.c_int32), ("grouping", C.c_int32), ("flags", C.c_uint32),
+        ("buffer_size", C.c_int32), ("grouping", C.c_int32), ("enclosing", C.c_int32), ("flags", C.c_uint32),
         ("capacity", C.c_int64), ("scale", C.c_float), ("attn_splits", C.c_int32),
     ]
 
@@ -121,10 +122,10 @@ def _dev(t: torch.Tensor, dtype=None, name="tensor"):
 
 
 def make_config(*, batch, n_q_heads, n_kv_heads, head_dim=128, kv_dtype=LVR_BF16, group_size=4,
-                n_subspaces=4, buffer_size=256, grouping=LVR_GROUP_CONTIGUOUS, flags=0, capacity,
+                n_subspaces=4, buffer_size=256, grouping=LVR_GROUP_CONTIGUOUS, enclosing=LVR_ENCLOSE_BALL, flags=0, capacity,
                 scale=0.0, attn_splits=0) -> lvr_config:
     return lvr_config(batch, n_q_heads, n_kv_heads, head_dim, kv_dtype, group_size, n_subspaces,
-                      buffer_size, grouping, flags, capacity, scale, attn_splits)
+                      buffer_size, grouping, enclosing, flags, capacity, scale, attn_splits)
 
 
 def lvr_arena_bytes(cfg: lvr_config) -> int:
@@ -219,8 +220,9 @@ def lvr_export_index(h, cfg: lvr_config):
     n, ni = lvr_length(h)
     ng = ni // cfg.group_size
     dt = np.uint16 if cfg.kv_dtype == LVR_BF16 else np.float32
-    centres = np.zeros((cfg.batch, cfg.n_kv_heads, ng, cfg.head_dim), dtype=dt)
-    radii = np.zeros((cfg.batch, cfg.n_kv_heads, ng, cfg.n_subspaces), dtype=np.float32)
+    box = cfg.enclosing == LVR_ENCLOSE_AABB
+    centres = np.zeros((cfg.batch, cfg.n_kv_heads, ng) + ((2,) if box else ()) + (cfg.head_dim,), dtype=dt)
+    radii = np.zeros((cfg.batch, cfg.n_kv_heads, ng, 1 if box else cfg.n_subspaces), dtype=np.float32)
     slot_pos = np.zeros((cfg.batch, cfg.n_kv_heads, n), dtype=np.int32)
     keys = np.zeros((cfg.batch, cfg.n_kv_heads, n, cfg.head_dim), dtype=dt)
     _check(lib().lvr_export_index(h, centres.ctypes.data_as(C.c_void_p), radii.ctypes.data_as(C.c_void_p),

@@ -40,6 +40,9 @@ int check_config(const lvr_config *c) {
     if (c->buffer_size <= 0 || c->buffer_size % 16 != 0 || c->buffer_size % c->group_size != 0) return LVR_E_INVALID;
     if (c->attn_splits > 256) return LVR_E_INVALID;
     if (c->capacity > (int64_t)1 << 30) return LVR_E_UNSUPPORTED;   // positions are int32
+    if (c->enclosing != LVR_ENCLOSE_BALL && c->enclosing != LVR_ENCLOSE_AABB) return LVR_E_INVALID;
+    if (c->enclosing == LVR_ENCLOSE_AABB && (c->kv_dtype != LVR_BF16 || (c->flags & LVR_SEPARATE_KERNELS)))
+        return LVR_E_UNSUPPORTED;
     return LVR_OK;
 }
 
@@ -64,8 +67,9 @@ Sizes sizes_of(const lvr_config *c) {
     s.Pmax = s.P > s.P_dense ? s.P : s.P_dense;
     auto al = [](size_t b) { return (b + 255) / 256 * 256; };
     s.kv = al((size_t)n_bh * s.cap_rows * LVR_D * elt);
-    s.centres = al((size_t)n_bh * s.max_groups * LVR_D * elt);
-    s.radii = al((size_t)n_bh * s.max_groups * c->n_subspaces * sizeof(float));
+    const bool box = c->enclosing == LVR_ENCLOSE_AABB;
+    s.centres = al((size_t)n_bh * s.max_groups * LVR_D * elt * (box ? 2 : 1));
+    s.radii = al((size_t)n_bh * s.max_groups * (box ? 1 : c->n_subspaces) * sizeof(float));
     s.list = al((size_t)n_bh * s.max_groups * sizeof(int32_t));
     s.counters = al(lvr_counter_ints((int)n_bh, (int)n_bhq, s.max_groups) * sizeof(int32_t));
     s.part_ml = al((size_t)n_bhq * s.Pmax * 2 * sizeof(float));
@@ -145,6 +149,8 @@ int lvr_create(const lvr_config *cfg, lvr_index **out) {
     ix->cfg = *cfg;
     const Sizes s = sizes_of(cfg);
     ix->G = cfg->n_q_heads / cfg->n_kv_heads;
+    ix->box = cfg->enclosing == LVR_ENCLOSE_AABB;
+    ix->S_store = ix->box ? 1 : cfg->n_subspaces;
     ix->cap_rows = s.cap_rows;
     ix->max_groups = s.max_groups;
     ix->P = s.P;
@@ -427,7 +433,7 @@ int lvr_get_stats(lvr_index *ix, lvr_stats *out) {
     out->groups_surviving = surv;
     out->keys_scanned = surv * r + ix->last_buffer_rows * n_bh;
     out->keys_emitted = emitted;
-    out->bytes_index = out->groups_scored * (row_bytes + (int64_t)ix->cfg.n_subspaces * 4);
+    out->bytes_index = out->groups_scored * (row_bytes * (ix->box ? 2 : 1) + (int64_t)ix->S_store * 4);
     out->bytes_keys = out->keys_scanned * row_bytes;
     out->bytes_attention = emitted * 2 * row_bytes;
     out->overflow = overflow;
@@ -443,14 +449,15 @@ int lvr_export_index(lvr_index *ix, void *centres, float *radii, int32_t *slot_p
     if (!ix->built) return LVR_E_STATE;
     LVR_HIP(hipDeviceSynchronize());
     const int n_bh = lvr_n_bh(ix);
-    const int r = ix->cfg.group_size, S = ix->cfg.n_subspaces;
+    const int r = ix->cfg.group_size, S = ix->S_store;
     const int64_t ng = ix->n_indexed / r, n = ix->n_total;
     const size_t row_bytes = LVR_D * ix->elt;
+    const size_t crow = row_bytes * (ix->box ? 2 : 1);   // bytes of one group's enclosure rows
     for (int bh = 0; bh < n_bh; ++bh) {
         if (centres && ng > 0)
-            LVR_HIP(hipMemcpy(static_cast<char *>(centres) + (size_t)bh * ng * row_bytes,
-                              static_cast<char *>(ix->centres) + (size_t)bh * ix->max_groups * row_bytes,
-                              (size_t)ng * row_bytes, hipMemcpyDeviceToHost));
+            LVR_HIP(hipMemcpy(static_cast<char *>(centres) + (size_t)bh * ng * crow,
+                              static_cast<char *>(ix->centres) + (size_t)bh * ix->max_groups * crow,
+                              (size_t)ng * crow, hipMemcpyDeviceToHost));
         if (radii && ng > 0)
             LVR_HIP(hipMemcpy(radii + (size_t)bh * ng * S, ix->radii + (size_t)bh * ix->max_groups * S,
                               (size_t)ng * S * sizeof(float), hipMemcpyDeviceToHost));

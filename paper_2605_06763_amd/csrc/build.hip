@@ -107,6 +107,60 @@ build_groups_kernel(const void *__restrict__ K, void *__restrict__ centres, floa
     if (valid && (li % lanes_per_sub) == 0) radii[((int64_t)bh * max_groups + g) * S + li / lanes_per_sub] = rho;
 }
 
+// Axis-aligned box of every group (appendix "Ablation on Index Design", Def. 1): per coordinate the
+// largest and the smallest member value, stored as two rows (upper corner, lower corner).  The
+// corners are member values, so bf16 storage is exact.  The one float per group in `radii` is a
+// rounding allowance for the bound  sum_c (q+_c hi_c + q-_c lo_c)  evaluated in fp32 over 256
+// terms: 2^-15 * |a|_2 with a_c = max(|lo_c|, |hi_c|); times |q|_2 it exceeds the rounding error
+// by Cauchy-Schwarz, so a computed bound never falls below a member's exact score.
+__global__ void __launch_bounds__(256)
+build_boxes_kernel(const void *__restrict__ K, void *__restrict__ corners, float *__restrict__ allowance,
+                   int64_t cap_rows, int64_t max_groups, int64_t g0, int64_t g1, int r) {
+    const int bh = blockIdx.y;
+    const int li = threadIdx.x & 15;
+    int64_t g = g0 + (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    const bool valid = g < g1;
+    if (!valid) g = g0;
+    const char *Kb = static_cast<const char *>(K) + (int64_t)bh * cap_rows * LVR_D * 2;
+    float lo[8], hi[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        lo[e] = INFINITY;
+        hi[e] = -INFINITY;
+    }
+    for (int m = 0; m < r; ++m) {
+        float x[8];
+        lvr_load8<lvr_bf16_t>(Kb, g * r + m, li, x);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            lo[e] = fminf(lo[e], x[e]);
+            hi[e] = fmaxf(hi[e], x[e]);
+        }
+    }
+    float a2 = 0.f;
+    uint32_t bh_[8], bl_[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float a = fmaxf(fabsf(lo[e]), fabsf(hi[e]));
+        a2 += a * a;
+        bh_[e] = __float_as_uint(hi[e]) >> 16;   // exact: the values are bf16 already
+        bl_[e] = __float_as_uint(lo[e]) >> 16;
+    }
+    a2 = seg_sum(a2, 16);
+    if (valid) {
+        uint4 *dst = reinterpret_cast<uint4 *>(static_cast<char *>(corners) +
+                                               ((int64_t)bh * max_groups + g) * 2 * LVR_D * 2);
+        dst[li] = make_uint4(bh_[0] | (bh_[1] << 16), bh_[2] | (bh_[3] << 16), bh_[4] | (bh_[5] << 16),
+                             bh_[6] | (bh_[7] << 16));
+        dst[16 + li] = make_uint4(bl_[0] | (bl_[1] << 16), bl_[2] | (bl_[3] << 16), bl_[4] | (bl_[5] << 16),
+                                  bl_[6] | (bl_[7] << 16));
+        if (li == 0) {
+            float al = sqrtf(a2) * 0x1p-15f;
+            allowance[(int64_t)bh * max_groups + g] = __uint_as_float(__float_as_uint(al) + 1u);
+        }
+    }
+}
+
 // Identity position map for rows [row0, row0+rows) (used when rows are stored in arrival order
 // but a map is kept, i.e. the buffer of a regrouped arena).
 __global__ void iota_rows_kernel(int32_t *slot_pos, int32_t *pos_slot, int64_t cap_rows, int64_t row0, int64_t rows) {
@@ -135,6 +189,11 @@ hipError_t lvr_launch_copy_kv(lvr_index *ix, const void *K, const int64_t ks[3],
 hipError_t lvr_launch_build_groups(lvr_index *ix, int64_t g0, int64_t g1, hipStream_t st) {
     if (g1 <= g0) return hipSuccess;
     dim3 grid((unsigned)((g1 - g0 + 15) / 16), (unsigned)lvr_n_bh(ix));
+    if (ix->box) {
+        hipLaunchKernelGGL(build_boxes_kernel, grid, dim3(256), 0, st, ix->K, ix->centres, ix->radii, ix->cap_rows,
+                           ix->max_groups, g0, g1, ix->cfg.group_size);
+        return hipGetLastError();
+    }
     if (ix->cfg.kv_dtype == LVR_BF16)
         hipLaunchKernelGGL(build_groups_kernel<lvr_bf16_t>, grid, dim3(256), 0, st, ix->K, ix->centres, ix->radii,
                            ix->cap_rows, ix->max_groups, g0, g1, ix->cfg.group_size, ix->cfg.n_subspaces);

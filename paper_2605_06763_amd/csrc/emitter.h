@@ -26,7 +26,9 @@ struct lvr_emitter {
     int rep_base;
     int64_t hq_base;          // flat index of head 0
 
-    __device__ __forceinline__ void flush(const lvr_emit_target &a, int lane, bool reporting) {
+    // The queue holds arena rows; `spos` (row -> token position, or NULL when rows are stored in
+    // arrival order) is applied here, one gather per flush instead of one dependent load per hit.
+    __device__ __forceinline__ void flush(const lvr_emit_target &a, int lane, bool reporting, const int32_t *spos) {
         const int hl = (lane & 15) - rep_base;
         int base = 0;
         if (reporting && (lane >> 4) == 0 && count > 0)
@@ -38,9 +40,10 @@ struct lvr_emitter {
             const int c_h = __shfl(count, rep_base + h, 64);
             if (lane < c_h) {
                 const int64_t p = (int64_t)b_h + lane;
-                if (p < a.cap)
-                    a.out_idx[(hq_base + h) * a.cap + p] = q[h][lane];
-                else
+                if (p < a.cap) {
+                    const int32_t row = q[h][lane];
+                    a.out_idx[(hq_base + h) * a.cap + p] = spos ? spos[row] : row;
+                } else
                     *a.overflow = 1;
             }
         }
@@ -57,10 +60,10 @@ struct lvr_emitter {
         const uint64_t mh = reporting ? (any & (0x0001000100010001ull << (lane & 15))) : 0ull;
         if (pred) {
             const int hl = (lane & 15) - rep_base;
-            q[hl][count + __popcll(mh & ((1ull << lane) - 1ull))] = spos ? spos[slot] : slot;
+            q[hl][count + __popcll(mh & ((1ull << lane) - 1ull))] = slot;
         }
         count += __popcll(mh);
-        if (__ballot(count > LVR_QCAP - 4)) flush(a, lane, reporting);
+        if (__ballot(count > LVR_QCAP - 4)) flush(a, lane, reporting, spos);
     }
 };
 #endif

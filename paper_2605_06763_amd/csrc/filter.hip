@@ -135,7 +135,7 @@ filter_mfma_kernel(const FilterArgs a) {
     }
 #pragma unroll
     for (int hb = 0; hb < HB; ++hb)
-        if (__ballot(em[hb].count > 0)) em[hb].flush(a.emit, lane, rep[hb]);
+        if (__ballot(em[hb].count > 0)) em[hb].flush(a.emit, lane, rep[hb], spos);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -208,7 +208,7 @@ filter_valu_kernel(const FilterArgs a) {
             em.push(a.emit, lane, rep, pred, slot[i], lane, spos);   // the reporting lane holds the row's slot itself
         }
     }
-    if (__ballot(em.count > 0)) em.flush(a.emit, lane, rep);
+    if (__ballot(em.count > 0)) em.flush(a.emit, lane, rep, spos);
 }
 
 __global__ void publish_counts_kernel(int32_t *__restrict__ head_count, int32_t *__restrict__ head_stat,

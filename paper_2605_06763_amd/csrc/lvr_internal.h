@@ -20,6 +20,8 @@ struct lvr_index {
     lvr_config cfg;
     int device;
     int G;                 // query heads per KV head
+    int box;               // 1: groups are enclosed by axis-aligned boxes (two rows per group in `centres`)
+    int S_store;           // floats per group in `radii` (S for balls, 1 for boxes)
     int64_t cap_rows;      // arena rows per (sequence, KV head), multiple of 64
     int64_t max_groups;    // cap_rows / r
     int64_t n_total;       // keys held
@@ -33,8 +35,8 @@ struct lvr_index {
     // arena (device)
     void *K;               // [batch][H_kv][cap_rows][d]
     void *V;
-    void *centres;         // [batch][H_kv][max_groups][d]
-    float *radii;          // [batch][H_kv][max_groups][S]
+    void *centres;         // [batch][H_kv][max_groups][d]  (boxes: [..][max_groups][2][d], upper then lower corner)
+    float *radii;          // [batch][H_kv][max_groups][S_store]
     int32_t *slot_pos;     // [batch][H_kv][cap_rows] token position of arena row (TREE grouping), else NULL
     int32_t *pos_slot;     // inverse map, or NULL
     // work space of the tree grouping (TREE grouping only)

@@ -39,8 +39,9 @@ __device__ __forceinline__ uint32_t lvr_split_part(float x, int part) {
 // One B fragment: head block hb (heads hb*4 .. hb*4+3 of the KV group, those >= G are zero),
 // coordinates kk*32 .. kk*32+31.  `scale` multiplies q first (1 for the range query;
 // sigma*log2(e) for attention logits).
+// sign: 0 takes q as it is, +1 its positive part max(q, 0), -1 its negative part min(q, 0).
 __device__ __forceinline__ void lvr_build_q_frag_one(const float *__restrict__ q_group, int G, int hb, int kk,
-                                                     float scale, lvr_bf16x8 &out) {
+                                                     float scale, lvr_bf16x8 &out, int sign = 0) {
     const int lane = threadIdx.x & 63;
     const int n = lane & 15, kq = lane >> 4;
     const int part = n >> 2, h = hb * 4 + (n & 3);
@@ -48,7 +49,12 @@ __device__ __forceinline__ void lvr_build_q_frag_one(const float *__restrict__ q
     uint32_t w[8];
     const float *src = q_group + (int64_t)(live ? h : 0) * LVR_D + kk * 32 + kq * 8;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) w[e] = live ? lvr_split_part(src[e] * scale, part) : 0u;
+    for (int e = 0; e < 8; ++e) {
+        float x = live ? src[e] * scale : 0.f;
+        if (sign > 0) x = fmaxf(x, 0.f);
+        if (sign < 0) x = fminf(x, 0.f);
+        w[e] = live ? lvr_split_part(x, part) : 0u;
+    }
     uint4 packed = make_uint4(w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16));
     out = __builtin_bit_cast(lvr_bf16x8, packed);
 }
@@ -58,12 +64,12 @@ __device__ __forceinline__ void lvr_build_q_frag_one(const float *__restrict__ q
 // through LDS.  Contains a __syncthreads(): every thread of the workgroup must call it.
 template <int HB>
 __device__ __forceinline__ void lvr_build_q_frags_wg(const float *__restrict__ q_group, int G, float scale,
-                                                     uint4 (&s_bq)[HB][4][64], lvr_bf16x8 (&bq)[HB][4]) {
+                                                     uint4 (&s_bq)[HB][4][64], lvr_bf16x8 (&bq)[HB][4], int sign = 0) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
     for (int hb = 0; hb < HB; ++hb) {
         lvr_bf16x8 f;
-        lvr_build_q_frag_one(q_group, G, hb, wave, scale, f);
+        lvr_build_q_frag_one(q_group, G, hb, wave, scale, f, sign);
         s_bq[hb][wave][lane] = __builtin_bit_cast(uint4, f);
     }
     __syncthreads();
@@ -90,6 +96,29 @@ __device__ __forceinline__ lvr_f32x4 lvr_score_tile(const uint4 (&a)[4], const l
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lvr_bf16x8, a[kk]), bq[kk], acc, 0, 0, 0);
+    lvr_f32x4 s;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float v = acc[j];
+        float t = v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x114, 0xf, 0xf, true));
+        t += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x118, 0xf, 0xf, true));
+        s[j] = t;
+    }
+    return s;
+}
+
+// Two chains into one accumulator:  D = A1 . B1 + A2 . B2  (box bound: upper corners against the
+// positive part of q, lower corners against the negative part; exact check of a row against
+// q = q+ + q-: the same A twice).
+__device__ __forceinline__ lvr_f32x4 lvr_score_tile2(const uint4 (&a1)[4], const lvr_bf16x8 (&b1)[4],
+                                                     const uint4 (&a2)[4], const lvr_bf16x8 (&b2)[4]) {
+    lvr_f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lvr_bf16x8, a1[kk]), b1[kk], acc, 0, 0, 0);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lvr_bf16x8, a2[kk]), b2[kk], acc, 0, 0, 0);
     lvr_f32x4 s;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {

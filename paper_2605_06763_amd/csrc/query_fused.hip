@@ -36,10 +36,11 @@ struct FusedArgs {
     int log2r, n_q_heads, n_kv_heads, G, buffer_dense, n_segs, tiles_per_wave;
 };
 
-template <int HB, int S, int UA>   // UA = centre tiles per phase-A trip
+template <int HB, int S, int UA, int ENC>   // UA = centre tiles per phase-A trip; ENC = 1: boxes instead of balls
 __global__ void __launch_bounds__(256)
 query_fused_kernel(const FusedArgs a) {
     __shared__ uint4 s_bq[HB][4][64];
+    __shared__ uint4 s_bq2[ENC ? HB : 1][4][64];
     __shared__ float s_qn[HB * 4][16];
     __shared__ int32_t s_queue[4][HB][4][LVR_QCAP];
     __shared__ int32_t s_list[SEG_MAX_GROUPS];
@@ -54,11 +55,12 @@ query_fused_kernel(const FusedArgs a) {
     // ---- phase A, first trip: the centre and radius loads do not depend on q, so they are put
     // in flight before the prologue builds the query operand ----
     constexpr int SP = (S <= 4) ? S : 1;      // radii are fetched ahead only when they are few
-    const char *Cb = static_cast<const char *>(a.centres) + (int64_t)bh * a.max_groups * LVR_D * 2;
+    // balls: one row per group (the centre); boxes: two rows per group (upper corner, lower corner)
+    const char *Cb = static_cast<const char *>(a.centres) + (int64_t)bh * a.max_groups * LVR_D * 2 * (ENC ? 2 : 1);
     const float *Rb = a.radii + (int64_t)bh * a.max_groups * S;
     const int64_t n_tiles = (a.n_groups + 15) >> 4;
     const int64_t tile0 = ((int64_t)blockIdx.x * 4 + wave) * a.tiles_per_wave;
-    uint4 av[UA][4];
+    uint4 av[UA][4], av2[UA][4];
     float rad[UA][4][SP];
     auto issueA = [&](int it) {
 #pragma unroll
@@ -66,7 +68,12 @@ query_fused_kernel(const FusedArgs a) {
             const int64_t g0 = (tile0 + it + u) * 16;
             int64_t g = g0 + n;
             if (g >= a.n_groups) g = a.n_groups - 1;
-            lvr_load_a_frags(Cb, g, av[u]);
+            if constexpr (ENC) {
+                lvr_load_a_frags(Cb, 2 * g, av[u]);
+                lvr_load_a_frags(Cb, 2 * g + 1, av2[u]);
+            } else {
+                lvr_load_a_frags(Cb, g, av[u]);
+            }
             if constexpr (S <= 4) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -101,8 +108,11 @@ query_fused_kernel(const FusedArgs a) {
         for (int off = 1; off < lanes_per_sub; off <<= 1) ss += __shfl_xor(ss, off, 64);
         if ((li % lanes_per_sub) == 0) s_qn[h][li / lanes_per_sub] = sqrtf(ss) * (1.0f + 0x1p-20f);   // rounded up
     }
-    lvr_bf16x8 bq[HB][4];
-    lvr_build_q_frags_wg<HB>(a.q + hq0 * LVR_D, a.G, 1.0f, s_bq, bq);   // syncs
+    // B operands: q itself for balls; for boxes its positive part (meets the upper corners) and its
+    // negative part (meets the lower corners); q = q+ + q- serves the exact check of phase B
+    lvr_bf16x8 bq[HB][4], bq2[ENC ? HB : 1][4];
+    lvr_build_q_frags_wg<HB>(a.q + hq0 * LVR_D, a.G, 1.0f, s_bq, bq, ENC ? 1 : 0);   // syncs
+    if constexpr (ENC) lvr_build_q_frags_wg<HB>(a.q + hq0 * LVR_D, a.G, 1.0f, s_bq2, bq2, -1);
     float taue[HB];
     bool rep[HB];
 #pragma unroll
@@ -131,7 +141,9 @@ query_fused_kernel(const FusedArgs a) {
                 uint32_t alive4 = 0;
 #pragma unroll
                 for (int hb = 0; hb < HB; ++hb) {
-                    const lvr_f32x4 sc = lvr_score_tile(av[u], bq[hb]);
+                    lvr_f32x4 sc;
+                    if constexpr (ENC) sc = lvr_score_tile2(av[u], bq[hb], av2[u], bq2[hb]);
+                    else sc = lvr_score_tile(av[u], bq[hb]);
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         float ub = sc[j];
@@ -227,7 +239,9 @@ query_fused_kernel(const FusedArgs a) {
             if (nvalid[u] == 0) continue;   // wave-uniform
 #pragma unroll
             for (int hb = 0; hb < HB; ++hb) {
-                const lvr_f32x4 s = lvr_score_tile(av[u], bq[hb]);
+                lvr_f32x4 s;
+                if constexpr (ENC) s = lvr_score_tile2(av[u], bq[hb], av[u], bq2[hb]);
+                else s = lvr_score_tile(av[u], bq[hb]);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int trow = 4 * kq + j;
@@ -240,17 +254,17 @@ query_fused_kernel(const FusedArgs a) {
     }
 #pragma unroll
     for (int hb = 0; hb < HB; ++hb)
-        if (__ballot(em[hb].count > 0)) em[hb].flush(a.emit, lane, rep[hb]);
+        if (__ballot(em[hb].count > 0)) em[hb].flush(a.emit, lane, rep[hb], spos);
 }
 
 template <int HB, int UA>
 void launch_s(dim3 grid, hipStream_t st, const FusedArgs &a, int S) {
     switch (S) {
-        case 1: hipLaunchKernelGGL((query_fused_kernel<HB, 1, UA>), grid, dim3(256), 0, st, a); break;
-        case 2: hipLaunchKernelGGL((query_fused_kernel<HB, 2, UA>), grid, dim3(256), 0, st, a); break;
-        case 4: hipLaunchKernelGGL((query_fused_kernel<HB, 4, UA>), grid, dim3(256), 0, st, a); break;
-        case 8: hipLaunchKernelGGL((query_fused_kernel<HB, 8, UA>), grid, dim3(256), 0, st, a); break;
-        default: hipLaunchKernelGGL((query_fused_kernel<HB, 16, UA>), grid, dim3(256), 0, st, a); break;
+        case 1: hipLaunchKernelGGL((query_fused_kernel<HB, 1, UA, 0>), grid, dim3(256), 0, st, a); break;
+        case 2: hipLaunchKernelGGL((query_fused_kernel<HB, 2, UA, 0>), grid, dim3(256), 0, st, a); break;
+        case 4: hipLaunchKernelGGL((query_fused_kernel<HB, 4, UA, 0>), grid, dim3(256), 0, st, a); break;
+        case 8: hipLaunchKernelGGL((query_fused_kernel<HB, 8, UA, 0>), grid, dim3(256), 0, st, a); break;
+        default: hipLaunchKernelGGL((query_fused_kernel<HB, 16, UA, 0>), grid, dim3(256), 0, st, a); break;
     }
 }
 
@@ -304,6 +318,11 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
     // one centre tile per trip (fewer registers, five waves per SIMD) for the small segments of short
     // contexts, two per trip for long ones: measured crossover between 32k and 128k keys
     const bool one = tpw == 1;
+    if (ix->box) {   // boxes: one allowance per group, one tile (two rows per group) per trip
+        if (ix->G <= 4) hipLaunchKernelGGL((query_fused_kernel<1, 1, 1, 1>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((query_fused_kernel<2, 1, 1, 1>), grid, dim3(256), 0, st, a);
+        return hipGetLastError();
+    }
     if (ix->G <= 4) {
         if (one) launch_s<1, 1>(grid, st, a, ix->cfg.n_subspaces);
         else launch_s<1, 2>(grid, st, a, ix->cfg.n_subspaces);

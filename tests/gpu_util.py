@@ -33,7 +33,7 @@ class Index:
 
     def __init__(self, K: np.ndarray, V: np.ndarray, dtype: str, n_q_heads: int, *, capacity=None,
                  group_size=4, n_subspaces=4, buffer_size=256, flags=0, grouping=L.LVR_GROUP_CONTIGUOUS,
-                 scale=0.0, attn_splits=0):
+                 enclosing=L.LVR_ENCLOSE_BALL, scale=0.0, attn_splits=0):
         batch, hkv, n, d = K.shape
         self.dtype = dtype
         self.K, self.V = K.copy(), V.copy()
@@ -43,7 +43,7 @@ class Index:
         self.cfg = L.make_config(batch=batch, n_q_heads=n_q_heads, n_kv_heads=hkv, head_dim=d,
                                  kv_dtype=L.LVR_BF16 if dtype == "bf16" else L.LVR_F32,
                                  group_size=group_size, n_subspaces=n_subspaces, buffer_size=buffer_size,
-                                 grouping=grouping, flags=flags, capacity=capacity or max(n, 1), scale=scale,
+                                 grouping=grouping, enclosing=enclosing, flags=flags, capacity=capacity or max(n, 1), scale=scale,
                                  attn_splits=attn_splits)
         self.h = L.lvr_create(self.cfg)
         self.Kd, self.Vd = to_device(K, dtype), to_device(V, dtype)
