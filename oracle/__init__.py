@@ -54,6 +54,11 @@ def _load():
     lib.lvo_aabb_bounds.argtypes = [vp, i32, vp, vp, i64, vp]
     lib.lvo_query1_filter.argtypes = [vp, vp, i32, i64, i64, vp, vp]
     lib.lvo_ta_filter.argtypes = [vp, vp, i32, i64, i64, f64, vp]
+    lib.lvo_hash32.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64]
+    lib.lvo_hash32.restype = C.c_uint32
+    lib.lvo_reservoir.argtypes = [C.c_uint64, C.c_uint64, i64, i32, vp]
+    lib.lvo_threshold.argtypes = [vp, i32, i32, f64]
+    lib.lvo_threshold.restype = f32
     lib.lvo_ta_filter.restype = i64
     lib.lvo_balanced_tree.argtypes = [vp, i32, i64, i32, i32, i32, i32, vp, vp]
     lib.lvo_balanced_tree.restype = i64
@@ -249,3 +254,22 @@ def predicted_speedup(g: float, r: int, f_scan: float) -> float:
     "Achieving high pruning"): query cost is proportional to g/r + f_scan, so the speed-up
     over brute force is its reciprocal."""
     return 1.0 / (g / r + f_scan)
+
+
+THRESHOLD_MODES = {"sample-max": 0, "sample-mean-max": 1, "sample-gap": 2, "sample-topk": 3, "budget": 4}
+
+
+def hash32(seed: int, stream: int, counter: int) -> int:
+    return int(_load().lvo_hash32(seed, stream, counter))
+
+
+def reservoir(seed: int, stream: int, n: int, R: int = 256):
+    """Positions held by the reservoir after the first n keys (appendix "Threshold Oracle Comparison")."""
+    res = np.full(max(min(n, R), 1), -1, dtype=np.int32)
+    _load().lvo_reservoir(seed, stream, n, R, _p(res))
+    return res[:min(n, R)]
+
+
+def threshold(scores, mode: str, param: float = 0.0) -> float:
+    s = np.ascontiguousarray(scores, dtype=np.float32)
+    return float(_load().lvo_threshold(_p(s), s.size, THRESHOLD_MODES[mode], float(param)))

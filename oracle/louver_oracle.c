@@ -19,6 +19,10 @@
  *                          the largest <q,x> over the box is sum_c max(q_c lo_c, q_c hi_c).
  *   Query 1                Sec. 4.2 "Query 1", Alg. 3: per-subspace thresholds, AND across subspaces.
  *   TA filter              Sec. 4.2 "Query 2", Alg. 4: sorted per-subspace bounds, depth scan.
+ *   reservoir, thresholds  appendix "Threshold Oracle Comparison": a uniform reservoir of past
+ *                          keys kept by reservoir sampling, and tau estimated from the query's
+ *                          dot products with it (sample-max, sample-mean-max, sample-gap,
+ *                          sample-topk(m), budget(alpha)).
  *   balanced tree          Sec. 4.1 "Grouping via balanced PCA trees", Alg. 2, with leaf ids
  *                          handed out by a running counter (the printed id formula collides
  *                          when a subtree yields more leaves than ceil(l/r)).
@@ -438,4 +442,78 @@ int64_t lvo_balanced_tree(const void *K, int kv_bf16, int64_t n, int d, int lo, 
         for (int64_t j = 0; j < n; ++j) order[j] = members[j];
     free(members);
     return next_id;
+}
+
+/* ---------------------------------------------------------------- threshold oracles */
+
+/* Counter-based generator shared (as a published algorithm, re-implemented on each side) with
+ * the GPU library: the splitmix64 finaliser of seed + stream * C1 + counter * C2, top 32 bits. */
+uint32_t lvo_hash32(uint64_t seed, uint64_t stream, uint64_t counter) {
+    uint64_t z = seed + stream * 0xD1B54A32D192ED03ull + counter * 0x9E3779B97F4A7C15ull;
+    z += 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return (uint32_t)(z >> 32);
+}
+
+/* Reservoir sampling over positions 0..n-1 in arrival order (classic algorithm R): the first R
+ * positions fill the reservoir; position i >= R draws j uniform in [0, i] and replaces slot j if
+ * j < R.  j = floor(hash32 * (i+1) / 2^32).  res[0..min(n,R)) holds positions. */
+void lvo_reservoir(uint64_t seed, uint64_t stream, int64_t n, int R, int32_t *res) {
+    for (int64_t i = 0; i < n; ++i) {
+        if (i < R) {
+            res[i] = (int32_t)i;
+        } else {
+            uint64_t j = ((uint64_t)lvo_hash32(seed, stream, (uint64_t)i) * (uint64_t)(i + 1)) >> 32;
+            if (j < (uint64_t)R) res[j] = (int32_t)i;
+        }
+    }
+}
+
+static int cmp_float_desc(const void *a, const void *b) {
+    float x = *(const float *)a, y = *(const float *)b;
+    return (x < y) - (x > y);
+}
+
+/* tau from m reservoir scores.  mode: 0 sample-max, 1 sample-mean-max (mean of the maximum and
+ * the mean score), 2 sample-gap (largest gap between consecutive sorted scores; tau is the
+ * smaller score of the upper side, so everything above the gap qualifies), 3 sample-topk
+ * (param = k: the k-th largest), 4 budget (param = alpha: the ceil(alpha * m)-th largest, the
+ * (1 - alpha) quantile).  m = 0 gives -inf (nothing is known: retrieve everything). */
+float lvo_threshold(const float *scores, int m, int mode, double param) {
+    if (m <= 0) return -INFINITY;
+    float *s = (float *)malloc(sizeof(float) * (size_t)m);
+    memcpy(s, scores, sizeof(float) * (size_t)m);
+    qsort(s, (size_t)m, sizeof(float), cmp_float_desc);
+    float tau = s[0];
+    if (mode == 1) {
+        double mean = 0.0;
+        for (int i = 0; i < m; ++i) mean += (double)s[i];
+        mean /= (double)m;
+        tau = (float)(0.5 * ((double)s[0] + mean));
+    } else if (mode == 2) {
+        int best = 0;
+        float gap = -1.0f;
+        for (int i = 0; i + 1 < m; ++i) {
+            float g = s[i] - s[i + 1];
+            if (g > gap) {
+                gap = g;
+                best = i;
+            }
+        }
+        tau = s[best];
+    } else if (mode == 3) {
+        int k = (int)param;
+        if (k < 1) k = 1;
+        if (k > m) k = m;
+        tau = s[k - 1];
+    } else if (mode == 4) {
+        int k = (int)ceil(param * (double)m);
+        if (k < 1) k = 1;
+        if (k > m) k = m;
+        tau = s[k - 1];
+    }
+    free(s);
+    return tau;
 }

@@ -531,3 +531,58 @@ def test_query1_filter_with_valid_thresholds_keeps_every_relevant_key(oracle):
     lab1 = np.array([[0, 1, 1]], dtype=np.int32)
     assert oracle.query1_filter(f1, lab1, np.array([5.0])).tolist() == [True, False, False]
     assert oracle.query1_filter(f1, lab1, np.array([3.0])).tolist() == [True, True, True]
+
+
+# ------------------------------------------------------------------ threshold oracles and reservoir
+def test_hash_reference_values(oracle):
+    """splitmix64 finaliser: the published generator seeded with 0 produces 0xE220A8397B1DCDAF
+    first; our hash32(seed, stream, counter) is that finaliser applied to
+    seed + stream*C1 + counter*C2, top 32 bits, so hash32(0, 0, 0) is the top half of that word."""
+    assert oracle.hash32(0, 0, 0) == 0xE220A839
+    # second output of the published sequence from seed 0 is 0x6E789E6AA1B965F4: counter advances by the same constant
+    assert oracle.hash32(0, 0, 1) == 0x6E789E6A
+
+
+def test_reservoir_is_algorithm_r_and_uniform(oracle):
+    R = 16
+    assert oracle.reservoir(7, 0, 10, R).tolist() == list(range(10))          # not yet full: arrival order
+    assert oracle.reservoir(7, 0, R, R).tolist() == list(range(R))
+    # transcription with python integers
+    for n in (17, 100, 1000):
+        res = list(range(R))
+        for i in range(R, n):
+            j = (oracle.hash32(7, 3, i) * (i + 1)) >> 32
+            if j < R:
+                res[j] = i
+        assert oracle.reservoir(7, 3, n, R).tolist() == res
+    # every position is kept with probability R/n: frequencies over many streams
+    n, trials = 200, 4000
+    hits = np.zeros(n)
+    for t in range(trials):
+        hits[oracle.reservoir(123, t, n, R)] += 1
+    p = R / n
+    sd = math.sqrt(trials * p * (1 - p))
+    assert np.all(np.abs(hits - trials * p) < 5 * sd)
+    assert len(set(oracle.reservoir(123, 0, n, R).tolist())) == R               # no duplicates
+
+
+def test_threshold_rules_closed_forms(oracle):
+    s = np.array([3.0, 10.0, 9.5, 1.0, 2.0, 9.0, 0.5, 2.5], dtype=np.float32)
+    assert oracle.threshold(s, "sample-max") == 10.0
+    assert math.isclose(oracle.threshold(s, "sample-mean-max"), 0.5 * (10.0 + s.mean()), rel_tol=1e-6)
+    # sorted: 10 9.5 9 | 3 2.5 2 1 0.5  -> largest gap between 9 and 3: tau = 9, three keys qualify
+    assert oracle.threshold(s, "sample-gap") == 9.0
+    assert (s >= oracle.threshold(s, "sample-gap")).sum() == 3
+    for k in (1, 2, 5, 8):
+        assert oracle.threshold(s, "sample-topk", k) == np.sort(s)[::-1][k - 1]
+    assert oracle.threshold(s, "sample-topk", 100) == 0.5
+    # budget(alpha): ceil(alpha m)-th largest, i.e. about a share alpha of the sample qualifies
+    assert oracle.threshold(s, "budget", 0.25) == 9.5
+    assert oracle.threshold(s, "budget", 0.5) == 3.0
+    assert oracle.threshold(s, "budget", 1.0) == 0.5
+    g = np.random.default_rng(17)
+    x = g.standard_normal(256).astype(np.float32)
+    for a in (0.05, 0.10, 0.15):
+        t = oracle.threshold(x, "budget", a)
+        assert (x >= t).sum() == math.ceil(a * 256)
+    assert oracle.threshold(np.zeros(0, np.float32), "sample-max") == -np.inf
