@@ -88,6 +88,9 @@ typedef struct lvr_config {
     int32_t attn_splits; /* P > 0: up to P partial-softmax splits per head, then a combine launch;
                           * 0: default (64);  -1: one workgroup per head, 16 splits merged in LDS,
                           * single launch (slower when there are few heads)                    */
+    int32_t reservoir_size; /* R <= 256 past keys kept per (sequence, KV head) by reservoir sampling for
+                             * lvr_threshold (appendix "Threshold Oracle Comparison"); 0 = none         */
+    uint64_t seed;          /* seed of the counter-based generator behind the reservoir              */
 } lvr_config;
 
 /* Counters of the most recent lvr_query / lvr_decode_step, summed over batch and heads. */
@@ -151,6 +154,27 @@ int lvr_sparse_attention(lvr_index *ix, const float *q_dev, const int32_t *idx_d
 /* lvr_query followed by lvr_sparse_attention on its result, in one call. */
 int lvr_decode_step(lvr_index *ix, const float *q_dev, const float *tau_dev, float *out_dev,
                     int32_t *out_idx_dev, int32_t *out_count_dev, int64_t cap, void *stream);
+
+/* Built-in threshold selection (appendix "Threshold Oracle Comparison"): tau per query head from
+ * the dot products of q with the reservoir of past keys of its KV head.
+ *   SAMPLE_MAX       largest reservoir score
+ *   SAMPLE_MEAN_MAX  mean of the largest and the average reservoir score
+ *   SAMPLE_GAP       cut at the largest gap between consecutive sorted scores: tau = the smallest
+ *                    score above the gap
+ *   SAMPLE_TOPK      param = k: the k-th largest reservoir score
+ *   BUDGET           param = alpha in (0, 1]: the ceil(alpha * m)-th largest of the m reservoir
+ *                    scores, i.e. the (1 - alpha) quantile
+ * tau_out_dev [batch][n_q_heads] fp32.  With an empty reservoir tau is -INFINITY.  Needs
+ * lvr_config.reservoir_size > 0 (LVR_E_STATE otherwise). */
+enum lvr_threshold_mode {
+    LVR_TAU_SAMPLE_MAX = 0, LVR_TAU_SAMPLE_MEAN_MAX = 1, LVR_TAU_SAMPLE_GAP = 2, LVR_TAU_SAMPLE_TOPK = 3,
+    LVR_TAU_BUDGET = 4
+};
+int lvr_threshold(lvr_index *ix, const float *q_dev, int mode, float param, float *tau_out_dev, void *stream);
+
+/* Synchronises the device and copies the reservoir (token positions, [batch][n_kv_heads][R],
+ * unused slots -1) to host memory. */
+int lvr_export_reservoir(lvr_index *ix, int32_t *positions_host);
 
 /* Dense attention over all held keys (Sec. 2 "Attention"): the baseline the sparse path is
  * measured against, on the same arena. */

@@ -28,6 +28,7 @@ class lvr_config(C.Structure):
         ("kv_dtype", C.c_int32), ("group_size", C.c_int32), ("n_subspaces", C.c_int32),
         ("buffer_size", C.c_int32), ("grouping", C.c_int32), ("enclosing", C.c_int32), ("flags", C.c_uint32),
         ("capacity", C.c_int64), ("scale", C.c_float), ("attn_splits", C.c_int32),
+        ("reservoir_size", C.c_int32), ("seed", C.c_uint64),
     ]
 
 
@@ -54,7 +55,7 @@ EXPORTS = [
     "lvr_create", "lvr_destroy", "lvr_arena_bytes", "lvr_build", "lvr_append", "lvr_query",
     "lvr_sparse_attention", "lvr_decode_step", "lvr_dense_attention", "lvr_get_stats",
     "lvr_export_index", "lvr_length", "lvr_strerror", "lvr_last_hip_error",
-    "lvr_profile_enable", "lvr_profile_read",
+    "lvr_profile_enable", "lvr_profile_read", "lvr_threshold", "lvr_export_reservoir",
 ]
 
 _lib = None
@@ -94,6 +95,8 @@ def lib():
     L.lvr_length.argtypes = [vp, C.POINTER(i64), C.POINTER(i64)]
     L.lvr_profile_enable.argtypes = [vp, C.c_int]
     L.lvr_profile_read.argtypes = [vp, C.POINTER(lvr_profile)]
+    L.lvr_threshold.argtypes = [vp, vp, C.c_int, C.c_float, vp, vp]
+    L.lvr_export_reservoir.argtypes = [vp, vp]
     L.lvr_strerror.argtypes = [C.c_int]
     L.lvr_strerror.restype = C.c_char_p
     L.lvr_last_hip_error.restype = C.c_int
@@ -123,9 +126,9 @@ def _dev(t: torch.Tensor, dtype=None, name="tensor"):
 
 def make_config(*, batch, n_q_heads, n_kv_heads, head_dim=128, kv_dtype=LVR_BF16, group_size=4,
                 n_subspaces=4, buffer_size=256, grouping=LVR_GROUP_CONTIGUOUS, enclosing=LVR_ENCLOSE_BALL, flags=0, capacity,
-                scale=0.0, attn_splits=0) -> lvr_config:
+                scale=0.0, attn_splits=0, reservoir_size=0, seed=0) -> lvr_config:
     return lvr_config(batch, n_q_heads, n_kv_heads, head_dim, kv_dtype, group_size, n_subspaces,
-                      buffer_size, grouping, enclosing, flags, capacity, scale, attn_splits)
+                      buffer_size, grouping, enclosing, flags, capacity, scale, attn_splits, reservoir_size, seed)
 
 
 def lvr_arena_bytes(cfg: lvr_config) -> int:
@@ -205,6 +208,22 @@ def lvr_profile_read(h) -> dict:
     p = lvr_profile()
     _check(lib().lvr_profile_read(h, C.byref(p)), "lvr_profile_read")
     return {KERNEL_NAMES[i]: (float(p.ms[i]), int(p.launches[i])) for i in range(9)}
+
+
+TAU_MODES = {"sample-max": 0, "sample-mean-max": 1, "sample-gap": 2, "sample-topk": 3, "budget": 4}
+
+
+def lvr_threshold(h, q, mode, param, tau_out, stream=None) -> None:
+    m = TAU_MODES[mode] if isinstance(mode, str) else int(mode)
+    _check(lib().lvr_threshold(h, _dev(q, torch.float32, "q"), m, float(param), _dev(tau_out, torch.float32, "tau_out"),
+                               _stream(stream)), "lvr_threshold")
+
+
+def lvr_export_reservoir(h, cfg: lvr_config):
+    import numpy as np
+    res = np.full((cfg.batch, cfg.n_kv_heads, max(cfg.reservoir_size, 1)), -1, dtype=np.int32)
+    _check(lib().lvr_export_reservoir(h, res.ctypes.data_as(C.c_void_p)), "lvr_export_reservoir")
+    return res
 
 
 def lvr_length(h):

@@ -41,6 +41,7 @@ int check_config(const lvr_config *c) {
     if (c->attn_splits > 256) return LVR_E_INVALID;
     if (c->capacity > (int64_t)1 << 30) return LVR_E_UNSUPPORTED;   // positions are int32
     if (c->enclosing != LVR_ENCLOSE_BALL && c->enclosing != LVR_ENCLOSE_AABB) return LVR_E_INVALID;
+    if (c->reservoir_size < 0 || c->reservoir_size > 256) return LVR_E_INVALID;
     if (c->enclosing == LVR_ENCLOSE_AABB && (c->kv_dtype != LVR_BF16 || (c->flags & LVR_SEPARATE_KERNELS)))
         return LVR_E_UNSUPPORTED;
     return LVR_OK;
@@ -96,7 +97,7 @@ Sizes sizes_of(const lvr_config *c) {
 void free_all(lvr_index *ix) {
     void *ptrs[] = {ix->K, ix->V, ix->centres, ix->radii, ix->slot_pos, ix->pos_slot,
                     ix->surv_list, ix->counters, ix->part_ml, ix->part_o, ix->tree_keys_a, ix->tree_keys_b,
-                    ix->tree_axis, ix->tree_partial, ix->tree_temp, ix->chunk_K, ix->chunk_V};
+                    ix->tree_axis, ix->tree_partial, ix->tree_temp, ix->chunk_K, ix->chunk_V, ix->reservoir};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
 }
@@ -181,6 +182,11 @@ int lvr_create(const lvr_config *cfg, lvr_index **out) {
             e = hipMalloc(a.p, a.bytes);
         }
     }
+    if (e == hipSuccess && cfg->reservoir_size > 0) {
+        const size_t rb = (size_t)lvr_n_bh(ix) * cfg->reservoir_size * sizeof(int32_t);
+        e = hipMalloc((void **)&ix->reservoir, rb);
+        if (e == hipSuccess) e = hipMemset(ix->reservoir, 0xff, rb);
+    }
     if (e == hipSuccess) e = hipMemset(ix->counters, 0, s.counters);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
@@ -243,6 +249,8 @@ int lvr_build(lvr_index *ix, const void *K, const void *V, int64_t n, const int6
         Timed t(ix, LVR_K_BUILD, st);
         LVR_HIP(lvr_launch_build_groups(ix, 0, n_groups, st));
     }
+    LVR_HIP(lvr_launch_reservoir_reset(ix, st));
+    LVR_HIP(lvr_launch_reservoir_update(ix, 0, n, st));
     ix->n_total = n;
     ix->n_indexed = n_groups * r;
     ix->built = 1;
@@ -261,6 +269,7 @@ int lvr_append(lvr_index *ix, const void *k_new, const void *v_new, int64_t m, v
         Timed t(ix, LVR_K_COPY, st);
         LVR_HIP(lvr_launch_copy_kv(ix, k_new, strides, v_new, strides, ix->n_total, m, st));
         LVR_HIP(lvr_launch_iota_rows(ix, ix->n_total, m, st));   // no-op without position maps
+        LVR_HIP(lvr_launch_reservoir_update(ix, ix->n_total, m, st));
     }
     ix->n_total += m;
     // every full buffer of B keys becomes B/r new groups at the tail of the index
@@ -385,6 +394,24 @@ int lvr_decode_step(lvr_index *ix, const float *q, const float *tau, float *out,
         LVR_HIP(lvr_launch_combine(ix, out, ix->P, lvr_head_count(ix), LVR_CNT_STRIDE, cap, out_count, st));
     }
     ix->counters_dirty = 0;
+    return LVR_OK;
+}
+
+int lvr_threshold(lvr_index *ix, const float *q, int mode, float param, float *tau_out, void *stream) {
+    if (!ix || !q || !tau_out || mode < LVR_TAU_SAMPLE_MAX || mode > LVR_TAU_BUDGET) return LVR_E_INVALID;
+    if (mode == LVR_TAU_BUDGET && !(param > 0.f && param <= 1.f)) return LVR_E_INVALID;
+    if (mode == LVR_TAU_SAMPLE_TOPK && param < 1.f) return LVR_E_INVALID;
+    if (!ix->built || !ix->reservoir) return LVR_E_STATE;
+    LVR_HIP(lvr_launch_threshold(ix, q, mode, param, tau_out, static_cast<hipStream_t>(stream)));
+    return LVR_OK;
+}
+
+int lvr_export_reservoir(lvr_index *ix, int32_t *positions) {
+    if (!ix || !positions) return LVR_E_INVALID;
+    if (!ix->reservoir) return LVR_E_STATE;
+    LVR_HIP(hipDeviceSynchronize());
+    LVR_HIP(hipMemcpy(positions, ix->reservoir, (size_t)lvr_n_bh(ix) * ix->cfg.reservoir_size * sizeof(int32_t),
+                      hipMemcpyDeviceToHost));
     return LVR_OK;
 }
 

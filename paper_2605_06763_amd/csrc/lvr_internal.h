@@ -39,6 +39,7 @@ struct lvr_index {
     float *radii;          // [batch][H_kv][max_groups][S_store]
     int32_t *slot_pos;     // [batch][H_kv][cap_rows] token position of arena row (TREE grouping), else NULL
     int32_t *pos_slot;     // inverse map, or NULL
+    int32_t *reservoir;    // [batch][H_kv][R] token positions kept by reservoir sampling (-1 = unused), or NULL
     // work space of the tree grouping (TREE grouping only)
     uint64_t *tree_keys_a, *tree_keys_b;   // [n_bh * padded entries] sort keys, ping-pong
     int32_t *tree_axis;                    // [n_bh * nodes] split axis per node of the current level
@@ -121,6 +122,10 @@ hipError_t lvr_launch_dense_partial(lvr_index *ix, const float *q, hipStream_t s
 hipError_t lvr_launch_combine(lvr_index *ix, float *out, int P, const int32_t *count, int count_stride, int64_t cap,
                               int32_t *publish_count, hipStream_t st);
 int lvr_dense_splits(const lvr_index *ix);
+// reservoir of past keys and threshold selection (threshold.hip)
+hipError_t lvr_launch_reservoir_reset(lvr_index *ix, hipStream_t st);
+hipError_t lvr_launch_reservoir_update(lvr_index *ix, int64_t pos0, int64_t count, hipStream_t st);
+hipError_t lvr_launch_threshold(lvr_index *ix, const float *q, int mode, float param, float *tau_out, hipStream_t st);
 // tree grouping (tree.hip)
 size_t lvr_tree_sort_temp_bytes(int64_t total_keys);
 hipError_t lvr_tree_group(lvr_index *ix, const void *Ksrc, const int64_t ks[3], const void *Vsrc, const int64_t vs[3],

@@ -33,7 +33,7 @@ class Index:
 
     def __init__(self, K: np.ndarray, V: np.ndarray, dtype: str, n_q_heads: int, *, capacity=None,
                  group_size=4, n_subspaces=4, buffer_size=256, flags=0, grouping=L.LVR_GROUP_CONTIGUOUS,
-                 enclosing=L.LVR_ENCLOSE_BALL, scale=0.0, attn_splits=0):
+                 enclosing=L.LVR_ENCLOSE_BALL, scale=0.0, attn_splits=0, reservoir_size=0, seed=0):
         batch, hkv, n, d = K.shape
         self.dtype = dtype
         self.K, self.V = K.copy(), V.copy()
@@ -44,7 +44,7 @@ class Index:
                                  kv_dtype=L.LVR_BF16 if dtype == "bf16" else L.LVR_F32,
                                  group_size=group_size, n_subspaces=n_subspaces, buffer_size=buffer_size,
                                  grouping=grouping, enclosing=enclosing, flags=flags, capacity=capacity or max(n, 1), scale=scale,
-                                 attn_splits=attn_splits)
+                                 attn_splits=attn_splits, reservoir_size=reservoir_size, seed=seed)
         self.h = L.lvr_create(self.cfg)
         self.Kd, self.Vd = to_device(K, dtype), to_device(V, dtype)
         L.lvr_build(self.h, self.Kd, self.Vd)
@@ -91,6 +91,16 @@ class Index:
         L.lvr_dense_attention(self.h, qd, out)
         torch.cuda.synchronize()
         return out.cpu().numpy()
+
+    def threshold(self, q: np.ndarray, mode: str, param: float = 0.0):
+        qd = torch.from_numpy(np.ascontiguousarray(q, dtype=np.float32)).cuda()
+        tau = torch.full((self.batch, self.hq), float("nan"), dtype=torch.float32, device="cuda")
+        L.lvr_threshold(self.h, qd, mode, param, tau)
+        torch.cuda.synchronize()
+        return tau.cpu().numpy()
+
+    def reservoir(self):
+        return L.lvr_export_reservoir(self.h, self.cfg)
 
     def stats(self, **kw):
         return L.lvr_get_stats(self.h, **kw)

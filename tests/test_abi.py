@@ -42,11 +42,11 @@ def test_config_struct_matches_header(L):
     text = open(os.path.join(ROOT, "include", "louver.h")).read()
     body = re.search(r"typedef struct lvr_config \{(.*?)\} lvr_config;", text, flags=re.S).group(1)
     body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
-    fields = re.findall(r"\b(?:int32_t|uint32_t|int64_t|float)\s+([a-z_]+)\s*;", body)
+    fields = re.findall(r"\b(?:int32_t|uint32_t|int64_t|uint64_t|float)\s+([a-z_]+)\s*;", body)
     assert fields == [f for f, _ in L.lvr_config._fields_]
     body = re.search(r"typedef struct lvr_stats \{(.*?)\} lvr_stats;", text, flags=re.S).group(1)
     body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
-    fields = re.findall(r"\b(?:int32_t|uint32_t|int64_t|float)\s+([a-z_]+)\s*;", body)
+    fields = re.findall(r"\b(?:int32_t|uint32_t|int64_t|uint64_t|float)\s+([a-z_]+)\s*;", body)
     assert fields == [f for f, _ in L.lvr_stats._fields_]
 
 
@@ -55,7 +55,7 @@ def test_bad_configs_are_rejected_on_the_host(L):
     assert L.lvr_arena_bytes(L.make_config(**ok)) > 2 * 8 * 1024 * 128 * 2
     for bad in (dict(ok, head_dim=64), dict(ok, n_q_heads=30), dict(ok, group_size=3), dict(ok, n_subspaces=32),
                 dict(ok, buffer_size=100), dict(ok, capacity=0), dict(ok, n_q_heads=24, n_kv_heads=8),
-                dict(ok, kv_dtype=7)):
+                dict(ok, kv_dtype=7), dict(ok, reservoir_size=257), dict(ok, reservoir_size=-1)):
         cfg = L.make_config(**bad)
         assert L.lvr_arena_bytes(cfg) == 0
         h = C.c_void_p()

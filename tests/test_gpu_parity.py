@@ -571,3 +571,85 @@ def test_box_enclosure_unsupported_combinations():
         cfg = L.make_config(batch=1, n_q_heads=4, n_kv_heads=1, capacity=64, enclosing=L.LVR_ENCLOSE_AABB, **kw)
         h = C.c_void_p()
         assert L.lib().lvr_create(C.byref(cfg), C.byref(h)) == L.LVR_E_UNSUPPORTED
+
+
+# ---------------------------------------------------------------------------------------------
+# Built-in threshold selection over a reservoir of past keys (appendix "Threshold Oracle Comparison")
+# ---------------------------------------------------------------------------------------------
+def _check_reservoir(oracle, ix, seed, R):
+    res = ix.reservoir()
+    m = min(ix.n, R)
+    for b in range(ix.batch):
+        for g in range(ix.hkv):
+            want = oracle.reservoir(seed, b * ix.hkv + g, ix.n, R)
+            assert np.array_equal(res[b, g, :m], want), f"reservoir b={b} g={g} n={ix.n}"
+            assert (res[b, g, m:] == -1).all()
+    return res
+
+
+@pytest.mark.parametrize("n,R", [(100, 256), (256, 256), (5000, 256), (5000, 64), (40000, 256)])
+def test_reservoir_equals_sequential_algorithm_r(G, oracle, n, R):
+    """The parallel update (largest position wins a slot) holds exactly what the sequential
+    sampler holds, after a build and after chunked and single appends."""
+    G.say(f"reservoir n={n} R={R}")
+    seed = 0xC0FFEE + n
+    c = W.make_cache(2, n=n + 300, n_kv_heads=2, batch=2)
+    with G.Index(c.K[:, :, :n], c.V[:, :, :n], "bf16", 8, capacity=n + 300, reservoir_size=R, seed=seed) as ix:
+        _check_reservoir(oracle, ix, seed, R)
+        ix.append(c.K[:, :, n:n + 257], c.V[:, :, n:n + 257])
+        _check_reservoir(oracle, ix, seed, R)
+        for i in range(n + 257, n + 300):
+            ix.append(c.K[:, :, i:i + 1], c.V[:, :, i:i + 1])
+        assert ix.n == n + 300
+        _check_reservoir(oracle, ix, seed, R)
+
+
+@pytest.mark.parametrize("dtype,grouping", [("bf16", "contiguous"), ("bf16", "tree"), ("f32", "contiguous")])
+@pytest.mark.parametrize("n", [37, 9000])
+def test_threshold_rules_equal_the_oracle(G, oracle, dtype, grouping, n):
+    """tau of every rule equals the oracle's rule applied to the oracle's fp32 scores of the
+    reservoir keys; a decode step with that tau then meets the parity rule."""
+    G.say(f"threshold rules dtype={dtype} grouping={grouping} n={n}")
+    seed, R = 77, 256
+    cid = 2 if dtype == "bf16" else 1
+    c = W.make_cache(cid, n=n, n_kv_heads=2, batch=2)
+    q = W.make_queries(cid, n_q_heads=8, batch=2)
+    gr = G.L.LVR_GROUP_TREE if grouping == "tree" else G.L.LVR_GROUP_CONTIGUOUS
+    with G.Index(c.K, c.V, dtype, 8, grouping=gr, reservoir_size=R, seed=seed) as ix:
+        res = _check_reservoir(oracle, ix, seed, R)
+        m = min(n, R)
+        for mode, param in (("sample-max", 0), ("sample-mean-max", 0), ("sample-gap", 0), ("sample-topk", 1),
+                            ("sample-topk", 8), ("sample-topk", 1000), ("budget", 0.02), ("budget", 0.3),
+                            ("budget", 1.0)):
+            tau = ix.threshold(q, mode, param)
+            for b in range(ix.batch):
+                for h in range(ix.hq):
+                    g = h // ix.G
+                    s = oracle.scores_f32(q[b, h], ix.K[b, g][res[b, g, :m]])
+                    want = oracle.threshold(s, mode, param)
+                    if mode == "sample-gap":
+                        # equal largest gaps (to rounding) may cut at either: accept any cut whose
+                        # gap is within rounding of the largest
+                        sd = np.sort(s.astype(np.float64))[::-1]
+                        gaps = sd[:-1] - sd[1:]
+                        ok = sd[:-1][gaps >= gaps.max() - 4e-6 * np.abs(sd).max()] if m > 1 else sd[:1]
+                        assert np.min(np.abs(ok - tau[b, h])) <= 2e-6 * max(1.0, np.abs(sd).max()), (mode, b, h)
+                    else:
+                        assert abs(tau[b, h] - want) <= 2e-6 * max(1.0, float(np.abs(s).max())), \
+                            (mode, param, b, h, tau[b, h], want)
+            if mode in ("sample-topk", "budget", "sample-mean-max"):
+                idx, cnt, out = ix.query(q, tau, fused=True)
+                G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=f"{mode}/{param}")
+
+
+def test_threshold_needs_a_reservoir(G):
+    c = W.make_cache(2, n=512, n_kv_heads=2)
+    q = W.make_queries(2, n_q_heads=8)
+    with G.Index(c.K, c.V, "bf16", 8) as ix:
+        with pytest.raises(G.L.LouverError):
+            ix.threshold(q, "sample-max")
+    with G.Index(c.K, c.V, "bf16", 8, reservoir_size=16, seed=1) as ix:
+        with pytest.raises(G.L.LouverError):
+            ix.threshold(q, "budget", 0.0)
+        with pytest.raises(G.L.LouverError):
+            ix.threshold(q, "sample-topk", 0.0)
