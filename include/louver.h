@@ -57,7 +57,15 @@ enum lvr_flags {
     /* Run the bound test and the exact check as two kernel launches (survivor list through
      * HBM) instead of the fused single launch.  Same results; lets the two stages be timed
      * apart.  fp32 caches always run this way. */
-    LVR_SEPARATE_KERNELS = 2u
+    LVR_SEPARATE_KERNELS = 2u,
+    /* Two-stream update (App. "GPU Update").  When an lvr_append fills the buffer, the B buffered
+     * keys are grouped on a stream the library owns, into index slots beyond the published group
+     * count, while calls on the caller's stream keep answering queries with those keys still in
+     * the buffer (scanned exactly, so results do not change).  The new groups are published by
+     * the next lvr_append, lvr_build or lvr_publish: the caller's stream waits for the side
+     * stream's event, then the published count advances.  All calls on one index must be
+     * ordered on one stream. */
+    LVR_CONCURRENT_UPDATE = 4u
 };
 
 enum lvr_error {
@@ -105,7 +113,7 @@ typedef struct lvr_stats {
     int64_t bytes_keys;       /* candidate key bytes read by the exact filter                    */
     int64_t bytes_attention;  /* K and V bytes gathered by the sparse attention                  */
     int32_t overflow;         /* 1 if some retrieved set exceeded cap since the last call here   */
-    int32_t reserved;
+    int32_t update_pending;   /* 1 while groups prepared by a concurrent update await lvr_publish */
 } lvr_stats;
 
 /* Allocate an index (arena for `capacity` keys per sequence and KV head, plus work space) on
@@ -129,6 +137,11 @@ int lvr_build(lvr_index *ix, const void *K_dev, const void *V_dev, int64_t n,
  * New keys join the buffer; whenever the buffer holds B keys they are grouped and their
  * balls appended to the index. */
 int lvr_append(lvr_index *ix, const void *k_new_dev, const void *v_new_dev, int64_t m, void *stream);
+
+/* Phase 2 of the two-stream update (App. "GPU Update"): make `stream` wait for the side stream's
+ * update-done event and publish the prepared groups to later queries.  No-op when nothing is
+ * pending (always, without LVR_CONCURRENT_UPDATE). */
+int lvr_publish(lvr_index *ix, void *stream);
 
 /* Range query (Problem 1; Sec. 4.2): bound test of every ball against the halfspace
  * (Eq. (2), summed over subspaces as in "Query 2"), then the exact dot product on the keys

@@ -18,6 +18,7 @@ LVR_GROUP_CONTIGUOUS, LVR_GROUP_TREE = 0, 1
 LVR_ENCLOSE_BALL, LVR_ENCLOSE_AABB = 0, 1
 LVR_ATTEND_BUFFER_DENSE = 1
 LVR_SEPARATE_KERNELS = 2
+LVR_CONCURRENT_UPDATE = 4
 LVR_OK, LVR_E_INVALID, LVR_E_UNSUPPORTED, LVR_E_CAPACITY = 0, -1, -2, -3
 LVR_E_OVERFLOW, LVR_E_HIP, LVR_E_NOMEM, LVR_E_STATE = -4, -5, -6, -7
 
@@ -37,11 +38,11 @@ class lvr_stats(C.Structure):
         ("n_keys", C.c_int64), ("n_indexed", C.c_int64), ("groups_scored", C.c_int64),
         ("groups_surviving", C.c_int64), ("keys_scanned", C.c_int64), ("keys_emitted", C.c_int64),
         ("bytes_index", C.c_int64), ("bytes_keys", C.c_int64), ("bytes_attention", C.c_int64),
-        ("overflow", C.c_int32), ("reserved", C.c_int32),
+        ("overflow", C.c_int32), ("update_pending", C.c_int32),
     ]
 
     def as_dict(self):
-        return {k: int(getattr(self, k)) for k, _ in self._fields_ if k != "reserved"}
+        return {k: int(getattr(self, k)) for k, _ in self._fields_}
 
 
 class lvr_profile(C.Structure):
@@ -55,7 +56,7 @@ EXPORTS = [
     "lvr_create", "lvr_destroy", "lvr_arena_bytes", "lvr_build", "lvr_append", "lvr_query",
     "lvr_sparse_attention", "lvr_decode_step", "lvr_dense_attention", "lvr_get_stats",
     "lvr_export_index", "lvr_length", "lvr_strerror", "lvr_last_hip_error",
-    "lvr_profile_enable", "lvr_profile_read", "lvr_threshold", "lvr_export_reservoir",
+    "lvr_profile_enable", "lvr_profile_read", "lvr_threshold", "lvr_export_reservoir", "lvr_publish",
 ]
 
 _lib = None
@@ -95,6 +96,7 @@ def lib():
     L.lvr_length.argtypes = [vp, C.POINTER(i64), C.POINTER(i64)]
     L.lvr_profile_enable.argtypes = [vp, C.c_int]
     L.lvr_profile_read.argtypes = [vp, C.POINTER(lvr_profile)]
+    L.lvr_publish.argtypes = [vp, vp]
     L.lvr_threshold.argtypes = [vp, vp, C.c_int, C.c_float, vp, vp]
     L.lvr_export_reservoir.argtypes = [vp, vp]
     L.lvr_strerror.argtypes = [C.c_int]
@@ -110,11 +112,40 @@ def _check(code: int, where: str):
 
 
 def _stream(stream=None):
+    if type(stream) is C.c_void_p:      # already marshalled (stream_arg)
+        return stream
     s = torch.cuda.current_stream() if stream is None else stream
     return C.c_void_p(s.cuda_stream)
 
 
-def _dev(t: torch.Tensor, dtype=None, name="tensor"):
+def stream_arg(stream=None) -> C.c_void_p:
+    """The stream argument marshalled once, for callers that issue many calls on one stream."""
+    return _stream(stream)
+
+
+class DeviceArg:
+    """A device tensor checked and marshalled once (tensor_arg); the tensor is kept alive."""
+    __slots__ = ("tensor", "ptr", "dtype", "shape")
+
+    def __init__(self, t: torch.Tensor):
+        if not t.is_cuda:
+            raise ValueError("tensor must be a device tensor")
+        if not t.is_contiguous():
+            raise ValueError("tensor must be contiguous")
+        self.tensor, self.ptr, self.dtype, self.shape = t, C.c_void_p(t.data_ptr()), t.dtype, tuple(t.shape)
+
+
+def tensor_arg(t: torch.Tensor) -> DeviceArg:
+    """Check and marshal a device tensor once; every entry point accepts the result in place
+    of the tensor (saves the per-call checks in tight decode loops)."""
+    return DeviceArg(t)
+
+
+def _dev(t, dtype=None, name="tensor"):
+    if type(t) is DeviceArg:
+        if dtype is not None and t.dtype != dtype:
+            raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+        return t.ptr
     if not t.is_cuda:
         raise ValueError(f"{name} must be a device tensor")
     if dtype is not None and t.dtype != dtype:
@@ -224,6 +255,10 @@ def lvr_export_reservoir(h, cfg: lvr_config):
     res = np.full((cfg.batch, cfg.n_kv_heads, max(cfg.reservoir_size, 1)), -1, dtype=np.int32)
     _check(lib().lvr_export_reservoir(h, res.ctypes.data_as(C.c_void_p)), "lvr_export_reservoir")
     return res
+
+
+def lvr_publish(h, stream=None) -> None:
+    _check(lib().lvr_publish(h, _stream(stream)), "lvr_publish")
 
 
 def lvr_length(h):

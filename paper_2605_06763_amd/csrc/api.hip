@@ -100,6 +100,30 @@ void free_all(lvr_index *ix) {
                     ix->tree_axis, ix->tree_partial, ix->tree_temp, ix->chunk_K, ix->chunk_V, ix->reservoir};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
+    if (ix->ev_fork) (void)hipEventDestroy(ix->ev_fork);
+    if (ix->ev_done) (void)hipEventDestroy(ix->ev_done);
+    if (ix->side) (void)hipStreamDestroy(ix->side);
+    delete ix->pend_perm;
+}
+
+// Phase 2 of the two-stream update (App. "GPU Update"): `st` waits for the side stream, then
+// the prepared groups become visible to the launches that follow.
+int publish_pending(lvr_index *ix, hipStream_t st) {
+    if (!ix->pending) return LVR_OK;
+    const int64_t B = ix->cfg.buffer_size;
+    const int r = ix->cfg.group_size;
+    LVR_HIP(hipStreamWaitEvent(st, ix->ev_done, 0));
+    if (ix->cfg.grouping == LVR_GROUP_TREE) {
+        // the chunk's order was computed on the side stream from a staged copy; moving the rows
+        // and forming their bounds happens here, where no query can be reading them
+        const int64_t cs[3] = {(int64_t)ix->cfg.n_kv_heads * B * LVR_D, B * LVR_D, LVR_D};
+        LVR_HIP(lvr_tree_gather(ix, ix->chunk_K, cs, ix->chunk_V, cs, ix->pend_perm, B, ix->pend_row0, st));
+        const int64_t g0 = ix->pend_row0 / r;
+        LVR_HIP(lvr_launch_build_groups(ix, g0, g0 + B / r, st));
+    }
+    ix->n_indexed = ix->pend_row0 + B;
+    ix->pending = 0;
+    return LVR_OK;
 }
 
 // Optional event pair around one kernel launch.
@@ -187,6 +211,15 @@ int lvr_create(const lvr_config *cfg, lvr_index **out) {
         e = hipMalloc((void **)&ix->reservoir, rb);
         if (e == hipSuccess) e = hipMemset(ix->reservoir, 0xff, rb);
     }
+    if (e == hipSuccess && (cfg->flags & LVR_CONCURRENT_UPDATE)) {
+        e = hipStreamCreateWithFlags(&ix->side, hipStreamNonBlocking);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&ix->ev_fork, hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&ix->ev_done, hipEventDisableTiming);
+        if (e == hipSuccess) {
+            ix->pend_perm = new (std::nothrow) lvr_tree_perm();
+            if (!ix->pend_perm) e = hipErrorOutOfMemory;
+        }
+    }
     if (e == hipSuccess) e = hipMemset(ix->counters, 0, s.counters);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
@@ -222,6 +255,10 @@ int lvr_build(lvr_index *ix, const void *K, const void *V, int64_t n, const int6
         for (int i = 0; i < 3; ++i)
             if (ks[i] < 0 || vs[i] < 0 || ks[i] % per16 || vs[i] % per16) return LVR_E_INVALID;
         if (ks[2] < LVR_D || vs[2] < LVR_D) return LVR_E_INVALID;
+    }
+    if (ix->pending) {   // an unpublished update belongs to the content being discarded
+        LVR_HIP(hipStreamWaitEvent(st, ix->ev_done, 0));
+        ix->pending = 0;
     }
     ix->built = 0;
     ix->n_total = 0;
@@ -264,6 +301,10 @@ int lvr_append(lvr_index *ix, const void *k_new, const void *v_new, int64_t m, v
     if (ix->n_total + m > ix->cfg.capacity) return LVR_E_CAPACITY;
     if (!aligned16(k_new) || !aligned16(v_new)) return LVR_E_INVALID;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    {
+        int rc = publish_pending(ix, st);
+        if (rc != LVR_OK) return rc;
+    }
     const int64_t strides[3] = {(int64_t)ix->cfg.n_kv_heads * m * LVR_D, m * LVR_D, LVR_D};
     {
         Timed t(ix, LVR_K_COPY, st);
@@ -276,7 +317,31 @@ int lvr_append(lvr_index *ix, const void *k_new, const void *v_new, int64_t m, v
     const int64_t B = ix->cfg.buffer_size;
     const int r = ix->cfg.group_size;
     const int64_t full = (ix->n_total - ix->n_indexed) / B;
-    if (full > 0) {
+    if (full == 1 && (ix->cfg.flags & LVR_CONCURRENT_UPDATE)) {
+        // Phase 1 on the side stream: it starts once the rows copied above are in the arena and
+        // writes only index slots (and staging) that no query launched before the publish reads
+        const int64_t g0 = ix->n_indexed / r;
+        LVR_HIP(hipEventRecord(ix->ev_fork, st));
+        LVR_HIP(hipStreamWaitEvent(ix->side, ix->ev_fork, 0));
+        if (ix->cfg.grouping == LVR_GROUP_TREE) {
+            const size_t row_bytes = LVR_D * ix->elt;
+            const int64_t cs[3] = {(int64_t)ix->cfg.n_kv_heads * B * LVR_D, B * LVR_D, LVR_D};
+            LVR_HIP(hipMemcpy2DAsync(ix->chunk_K, B * row_bytes, static_cast<char *>(ix->K) + ix->n_indexed * row_bytes,
+                                     ix->cap_rows * row_bytes, B * row_bytes, lvr_n_bh(ix), hipMemcpyDeviceToDevice,
+                                     ix->side));
+            LVR_HIP(hipMemcpy2DAsync(ix->chunk_V, B * row_bytes, static_cast<char *>(ix->V) + ix->n_indexed * row_bytes,
+                                     ix->cap_rows * row_bytes, B * row_bytes, lvr_n_bh(ix), hipMemcpyDeviceToDevice,
+                                     ix->side));
+            hipError_t e = lvr_tree_order(ix, ix->chunk_K, cs, B, ix->side, ix->pend_perm);
+            if (e == hipErrorInvalidValue) return LVR_E_UNSUPPORTED;
+            LVR_HIP(e);
+        } else {
+            LVR_HIP(lvr_launch_build_groups(ix, g0, g0 + B / r, ix->side));
+        }
+        LVR_HIP(hipEventRecord(ix->ev_done, ix->side));
+        ix->pend_row0 = ix->n_indexed;
+        ix->pending = 1;
+    } else if (full > 0) {
         const int64_t g0 = ix->n_indexed / r, g1 = g0 + full * (B / r);
         Timed t(ix, LVR_K_BUILD, st);
         if (ix->cfg.grouping == LVR_GROUP_TREE) {
@@ -301,6 +366,12 @@ int lvr_append(lvr_index *ix, const void *k_new, const void *v_new, int64_t m, v
         ix->n_indexed += full * B;
     }
     return LVR_OK;
+}
+
+int lvr_publish(lvr_index *ix, void *stream) {
+    if (!ix) return LVR_E_INVALID;
+    if (!ix->built) return LVR_E_STATE;
+    return publish_pending(ix, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"
@@ -329,6 +400,7 @@ int enqueue_query(lvr_index *ix, const float *q, const float *tau, int32_t *out_
         LVR_HIP(lvr_launch_filter(ix, q, tau, out_idx, cap, st));
     }
     ix->last_buffer_rows = ix->n_total - ix->n_indexed;
+    ix->last_indexed = ix->n_indexed;
     return LVR_OK;
 }
 
@@ -456,7 +528,8 @@ int lvr_get_stats(lvr_index *ix, lvr_stats *out) {
     const int64_t row_bytes = (int64_t)LVR_D * (int64_t)ix->elt;
     out->n_keys = ix->n_total;
     out->n_indexed = ix->n_indexed;
-    out->groups_scored = (ix->n_indexed / r) * n_bh;
+    out->groups_scored = (ix->last_indexed / r) * n_bh;
+    out->update_pending = ix->pending;
     out->groups_surviving = surv;
     out->keys_scanned = surv * r + ix->last_buffer_rows * n_bh;
     out->keys_emitted = emitted;

@@ -57,6 +57,14 @@ struct lvr_index {
     float *part_ml;        // [batch][H_q][Pmax][2]
     float *part_o;         // [batch][H_q][Pmax][d]
     int64_t last_buffer_rows; // buffer rows scanned by the last query (host copy for stats)
+    int64_t last_indexed;     // indexed rows the last query saw
+    // concurrent update (LVR_CONCURRENT_UPDATE): a full buffer is grouped on `side` while the
+    // caller's stream keeps answering queries that still see those keys as buffer keys
+    hipStream_t side;
+    hipEvent_t ev_fork, ev_done;
+    int pending;              // a chunk's groups are being prepared / wait to be published
+    int64_t pend_row0;        // first arena row of that chunk
+    struct lvr_tree_perm *pend_perm;   // TREE grouping: the chunk's order, gathered at publish time
     // optional per-kernel timing (lvr_profile_enable): pairs of events around every launch
     int prof_on;
     int prof_used;            // events handed out so far
@@ -128,6 +136,16 @@ hipError_t lvr_launch_reservoir_update(lvr_index *ix, int64_t pos0, int64_t coun
 hipError_t lvr_launch_threshold(lvr_index *ix, const float *q, int mode, float param, float *tau_out, hipStream_t st);
 // tree grouping (tree.hip)
 size_t lvr_tree_sort_temp_bytes(int64_t total_keys);
+// order of the rows after the tree grouping: sorted keys whose low pos_bits give the source row
+struct lvr_tree_perm {
+    uint64_t *keys;
+    int64_t np;
+    int pos_bits;
+};
+hipError_t lvr_tree_order(lvr_index *ix, const void *Ksrc, const int64_t ks[3], int64_t n_real, hipStream_t st,
+                          lvr_tree_perm *perm);
+hipError_t lvr_tree_gather(lvr_index *ix, const void *Ksrc, const int64_t ks[3], const void *Vsrc, const int64_t vs[3],
+                           const lvr_tree_perm *perm, int64_t n_real, int64_t row0, hipStream_t st);
 hipError_t lvr_tree_group(lvr_index *ix, const void *Ksrc, const int64_t ks[3], const void *Vsrc, const int64_t vs[3],
                           int64_t n_real, int64_t row0, hipStream_t st);
 

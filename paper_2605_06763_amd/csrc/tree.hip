@@ -26,11 +26,6 @@ namespace {
 
 constexpr int PIECE = 1024;   // rows per partial-statistics piece for nodes larger than this
 
-__device__ __forceinline__ float elem_as_float(const void *row, int c, int elt) {
-    if (elt == 2) return __uint_as_float((uint32_t)static_cast<const uint16_t *>(row)[c] << 16);
-    return static_cast<const float *>(row)[c];
-}
-
 struct TreeSrc {
     const char *K;             // source key rows
     int64_t sb, sh, st;        // element strides (batch, head, token)
@@ -248,8 +243,9 @@ size_t lvr_tree_sort_temp_bytes(int64_t total_keys) {
 // Orders n_real = groups*r keys (positions 0..n_real-1 of the given source rows) by the tree and
 // writes them, regrouped, to arena rows row0 .. row0+n_real-1 together with the position maps.
 // Returns hipErrorInvalidValue if the sort key would not fit in 64 bits.
-hipError_t lvr_tree_group(lvr_index *ix, const void *Ksrc, const int64_t ks[3], const void *Vsrc, const int64_t vs[3],
-                          int64_t n_real, int64_t row0, hipStream_t st) {
+hipError_t lvr_tree_order(lvr_index *ix, const void *Ksrc, const int64_t ks[3], int64_t n_real, hipStream_t st,
+                          lvr_tree_perm *perm) {
+    perm->keys = nullptr;
     if (n_real <= 0) return hipSuccess;
     const int r = ix->cfg.group_size;
     const int n_bh = lvr_n_bh(ix);
@@ -265,7 +261,6 @@ hipError_t lvr_tree_group(lvr_index *ix, const void *Ksrc, const int64_t ks[3], 
     if ((int64_t)n_bh * np > ix->tree_cap_keys) return hipErrorInvalidValue;
 
     TreeSrc ksrc{static_cast<const char *>(Ksrc), ks[0], ks[1], ks[2], (int)ix->elt, ix->cfg.n_kv_heads};
-    TreeSrc vsrc{static_cast<const char *>(Vsrc), vs[0], vs[1], vs[2], (int)ix->elt, ix->cfg.n_kv_heads};
     uint64_t *cur = ix->tree_keys_a, *alt = ix->tree_keys_b;
     hipLaunchKernelGGL(tree_init_kernel, dim3((unsigned)((np + 255) / 256), (unsigned)n_bh), dim3(256), 0, st, cur, np);
     for (int L = 0; L < levels; ++L) {
@@ -291,10 +286,30 @@ hipError_t lvr_tree_group(lvr_index *ix, const void *Ksrc, const int64_t ks[3], 
         cur = alt;
         alt = t;
     }
+    perm->keys = cur;
+    perm->np = np;
+    perm->pos_bits = pos_bits;
+    return hipGetLastError();
+}
+
+hipError_t lvr_tree_gather(lvr_index *ix, const void *Ksrc, const int64_t ks[3], const void *Vsrc, const int64_t vs[3],
+                           const lvr_tree_perm *perm, int64_t n_real, int64_t row0, hipStream_t st) {
+    if (n_real <= 0 || !perm->keys) return hipSuccess;
+    const int n_bh = lvr_n_bh(ix);
+    TreeSrc ksrc{static_cast<const char *>(Ksrc), ks[0], ks[1], ks[2], (int)ix->elt, ix->cfg.n_kv_heads};
+    TreeSrc vsrc{static_cast<const char *>(Vsrc), vs[0], vs[1], vs[2], (int)ix->elt, ix->cfg.n_kv_heads};
     const int row_bytes = (int)(LVR_D * ix->elt);
     const int64_t total = n_real * (row_bytes / 16);
     hipLaunchKernelGGL(tree_gather_kernel, dim3((unsigned)((total + 255) / 256), (unsigned)n_bh, 2), dim3(256), 0, st,
-                       ksrc, vsrc, cur, static_cast<char *>(ix->K), static_cast<char *>(ix->V), ix->slot_pos,
-                       ix->pos_slot, np, n_real, pos_bits, ix->cap_rows, row0, row_bytes);
+                       ksrc, vsrc, perm->keys, static_cast<char *>(ix->K), static_cast<char *>(ix->V), ix->slot_pos,
+                       ix->pos_slot, perm->np, n_real, perm->pos_bits, ix->cap_rows, row0, row_bytes);
     return hipGetLastError();
+}
+
+hipError_t lvr_tree_group(lvr_index *ix, const void *Ksrc, const int64_t ks[3], const void *Vsrc, const int64_t vs[3],
+                          int64_t n_real, int64_t row0, hipStream_t st) {
+    lvr_tree_perm perm;
+    hipError_t e = lvr_tree_order(ix, Ksrc, ks, n_real, st, &perm);
+    if (e != hipSuccess) return e;
+    return lvr_tree_gather(ix, Ksrc, ks, Vsrc, vs, &perm, n_real, row0, st);
 }

@@ -653,3 +653,86 @@ def test_threshold_needs_a_reservoir(G):
             ix.threshold(q, "budget", 0.0)
         with pytest.raises(G.L.LouverError):
             ix.threshold(q, "sample-topk", 0.0)
+
+
+# ---------------------------------------------------------------------------------------------
+# Two-stream update (App. "GPU Update"): groups prepared on a side stream, published later
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("grouping", ["contiguous", "tree"])
+def test_concurrent_update_half_published_state(G, oracle, grouping):
+    """Between the append that fills the buffer and the publish, queries still see the old group
+    count and scan the full buffer exactly, so their result is the oracle's; after the publish
+    the index equals, bit for bit, the one a single-stream index builds from the same stream."""
+    L = G.L
+    n0, steps, B = 203, 150, 32
+    gr = L.LVR_GROUP_TREE if grouping == "tree" else L.LVR_GROUP_CONTIGUOUS
+    cache = _small_cache(5, n0)
+    k_new, v_new = W.make_append_stream(5, steps, cache)
+    qs = W.drift_queries(5, steps, n_q_heads=8)
+    G.say(f"concurrent update grouping={grouping}")
+    with G.Index(cache.K, cache.V, "bf16", 8, capacity=n0 + steps, buffer_size=B, grouping=gr,
+                 flags=L.LVR_CONCURRENT_UPDATE) as ix, \
+         G.Index(cache.K, cache.V, "bf16", 8, capacity=n0 + steps, buffer_size=B, grouping=gr) as ref:
+        windows = 0
+        for t in range(steps):
+            ix.append(k_new[t][:, :, None, :], v_new[t][:, :, None, :])
+            ref.append(k_new[t][:, :, None, :], v_new[t][:, :, None, :])
+            n, n_indexed = L.lvr_length(ix.h)
+            n_ref, n_indexed_ref = L.lvr_length(ref.h)
+            assert n == n_ref == n0 + t + 1
+            pending = n_indexed != n_indexed_ref
+            if pending:
+                # the window: the chunk's groups exist (or are being formed) but are not visible
+                windows += 1
+                assert n_indexed_ref - n_indexed == B and n - n_indexed >= B
+                tau = G.oracle_taus(oracle, ix, qs[t], frac=0.05)
+                for fused in (True, False):
+                    idx, cnt, out = ix.query(qs[t], tau, fused=fused)
+                    G.check_step(oracle, ix, qs[t], tau, idx, cnt, out, tag=f"window t={t}")
+                st = ix.stats()
+                assert st["update_pending"] == 1 and st["n_indexed"] == n_indexed
+                assert st["keys_scanned"] >= (n - n_indexed) * ix.batch * ix.hkv
+                if windows % 2 == 0:
+                    L.lvr_publish(ix.h)                  # explicit phase 2; otherwise the next append does it
+                    assert L.lvr_length(ix.h)[1] == n_indexed_ref
+                    idx, cnt, out = ix.query(qs[t], tau)
+                    G.check_step(oracle, ix, qs[t], tau, idx, cnt, out, tag=f"published t={t}")
+                    assert ix.stats()["update_pending"] == 0
+            elif t % 11 == 0:
+                tau = G.oracle_taus(oracle, ix, qs[t], frac=0.05)
+                idx, cnt, out = ix.query(qs[t], tau)
+                G.check_step(oracle, ix, qs[t], tau, idx, cnt, out, tag=f"t={t}")
+        assert windows >= 4
+        L.lvr_publish(ix.h)
+        a, b = ix.export(), ref.export()
+        for name, x, y in zip(("centres", "radii", "slot_pos", "keys"), a, b):
+            assert np.array_equal(np.asarray(x), np.asarray(y)), name
+        # a publish with nothing pending, and on an index without the flag, is a no-op
+        L.lvr_publish(ix.h)
+        L.lvr_publish(ref.h)
+
+
+def test_concurrent_update_bulk_append_and_rebuild(G, oracle):
+    """Several chunks in one append take the single-stream path; a rebuild discards a pending update."""
+    L = G.L
+    n0, B = 100, 32
+    cache = _small_cache(5, n0 + 200)
+    q = W.make_queries(5, n_q_heads=8)
+    K0, V0 = cache.K[:, :, :n0], cache.V[:, :, :n0]
+    with G.Index(K0, V0, "bf16", 8, capacity=n0 + 200, buffer_size=B, flags=L.LVR_CONCURRENT_UPDATE) as ix:
+        ix.append(cache.K[:, :, n0:n0 + 40], cache.V[:, :, n0:n0 + 40])          # fills one chunk: pending
+        assert ix.stats()["update_pending"] == 1
+        ix.append(cache.K[:, :, n0 + 40:n0 + 170], cache.V[:, :, n0 + 40:n0 + 170])   # publishes, then 4 chunks at once
+        n, n_indexed = L.lvr_length(ix.h)
+        assert n == n0 + 170 and n - n_indexed < B + 4
+        tau = G.oracle_taus(oracle, ix, q, frac=0.05)
+        idx, cnt, out = ix.query(q, tau)
+        G.check_step(oracle, ix, q, tau, idx, cnt, out, tag="bulk")
+        ix.append(cache.K[:, :, n0 + 170:n0 + 200], cache.V[:, :, n0 + 170:n0 + 200])
+        # rebuild from the prompt alone while an update may be pending
+        L.lvr_build(ix.h, ix.Kd, ix.Vd)
+        ix.K, ix.V = K0.copy(), V0.copy()
+        assert L.lvr_length(ix.h) == (n0, n0 // 4 * 4)
+        tau = G.oracle_taus(oracle, ix, q, frac=0.05)
+        idx, cnt, out = ix.query(q, tau)
+        G.check_step(oracle, ix, q, tau, idx, cnt, out, tag="rebuilt")
