@@ -156,6 +156,18 @@ int lvr_publish(lvr_index *ix, void *stream);
 int lvr_query(lvr_index *ix, const float *q_dev, const float *tau_dev, int32_t *out_idx_dev,
               int32_t *out_count_dev, int64_t cap, void *stream);
 
+/* "Query 1" (Sec. 4.2, Eq. "ball gate" per subspace; Alg. 3): per-subspace thresholds.
+ *   tau_s_dev [batch][n_q_heads][S] fp32: tau_s is a lower bound on <pi_s q, pi_s k> for every
+ *             key the caller regards as relevant; a group is a candidate for a head iff in EVERY
+ *             subspace its ball bound reaches that subspace's threshold
+ *   tau_dev   [batch][n_q_heads]: the exact check on candidates, as in lvr_query
+ * Every key with <q,k> >= tau whose subspace products all reach their tau_s is returned; keys
+ * with <q,k> >= tau that miss some tau_s may or may not be (they are outside Query 1's promise).
+ * Buffer keys are checked against tau only.  Balls on bf16 caches with S <= 4, fused launch
+ * form; other configurations return LVR_E_UNSUPPORTED. */
+int lvr_query1(lvr_index *ix, const float *q_dev, const float *tau_s_dev, const float *tau_dev, int32_t *out_idx_dev,
+               int32_t *out_count_dev, int64_t cap, void *stream);
+
 /* Attention over given index lists (Sec. 2 "Sparse Attention"; App. "GPU Sparse Attention
  * Kernel": P splits with partial (m, l, o), then a combine pass).  Softmax is normalised over
  * the listed keys only.  idx_dev / count_dev as produced by lvr_query (count is clamped to

@@ -56,7 +56,7 @@ EXPORTS = [
     "lvr_create", "lvr_destroy", "lvr_arena_bytes", "lvr_build", "lvr_append", "lvr_query",
     "lvr_sparse_attention", "lvr_decode_step", "lvr_dense_attention", "lvr_get_stats",
     "lvr_export_index", "lvr_length", "lvr_strerror", "lvr_last_hip_error",
-    "lvr_profile_enable", "lvr_profile_read", "lvr_threshold", "lvr_export_reservoir", "lvr_publish",
+    "lvr_profile_enable", "lvr_profile_read", "lvr_threshold", "lvr_export_reservoir", "lvr_publish", "lvr_query1",
 ]
 
 _lib = None
@@ -97,6 +97,7 @@ def lib():
     L.lvr_profile_enable.argtypes = [vp, C.c_int]
     L.lvr_profile_read.argtypes = [vp, C.POINTER(lvr_profile)]
     L.lvr_publish.argtypes = [vp, vp]
+    L.lvr_query1.argtypes = [vp, vp, vp, vp, vp, vp, i64, vp]
     L.lvr_threshold.argtypes = [vp, vp, C.c_int, C.c_float, vp, vp]
     L.lvr_export_reservoir.argtypes = [vp, vp]
     L.lvr_strerror.argtypes = [C.c_int]
@@ -199,6 +200,13 @@ def lvr_query(h, q, tau, out_idx, out_count, stream=None) -> None:
     _check(lib().lvr_query(h, _dev(q, torch.float32, "q"), _dev(tau, torch.float32, "tau"),
                            _dev(out_idx, torch.int32, "out_idx"), _dev(out_count, torch.int32, "out_count"),
                            cap, _stream(stream)), "lvr_query")
+
+
+def lvr_query1(h, q, tau_s, tau, out_idx, out_count, stream=None) -> None:
+    cap = out_idx.shape[-1]
+    _check(lib().lvr_query1(h, _dev(q, torch.float32, "q"), _dev(tau_s, torch.float32, "tau_s"),
+                            _dev(tau, torch.float32, "tau"), _dev(out_idx, torch.int32, "out_idx"),
+                            _dev(out_count, torch.int32, "out_count"), cap, _stream(stream)), "lvr_query1")
 
 
 def lvr_sparse_attention(h, q, idx, count, out, stream=None) -> None:

@@ -379,7 +379,8 @@ int lvr_publish(lvr_index *ix, void *stream) {
 namespace {
 
 // bound test + exact filter; leaves the set sizes in the internal per-head counters
-int enqueue_query(lvr_index *ix, const float *q, const float *tau, int32_t *out_idx, int64_t cap, hipStream_t st) {
+int enqueue_query(lvr_index *ix, const float *q, const float *tau, int32_t *out_idx, int64_t cap, hipStream_t st,
+                  const float *tau_s = nullptr) {
     const bool fused = ix->cfg.kv_dtype == LVR_BF16 && !(ix->cfg.flags & LVR_SEPARATE_KERNELS);
     if (ix->counters_dirty) {   // an earlier query never published its counts: start from zero again
         Timed t(ix, LVR_K_RESET, st);
@@ -388,7 +389,7 @@ int enqueue_query(lvr_index *ix, const float *q, const float *tau, int32_t *out_
     ix->counters_dirty = 1;
     if (fused) {
         Timed t(ix, LVR_K_FILTER, st);
-        LVR_HIP(lvr_launch_query_fused(ix, q, tau, out_idx, cap, st));
+        LVR_HIP(lvr_launch_query_fused(ix, q, tau, tau_s, out_idx, cap, st));
     } else {
         if (ix->n_indexed > 0) {
             Timed t(ix, LVR_K_PRUNE, st);
@@ -414,6 +415,23 @@ int lvr_query(lvr_index *ix, const float *q, const float *tau, int32_t *out_idx,
     if (!ix->built) return LVR_E_STATE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     int rc = enqueue_query(ix, q, tau, out_idx, cap, st);
+    if (rc != LVR_OK) return rc;
+    {
+        Timed t(ix, LVR_K_RESET, st);
+        LVR_HIP(lvr_launch_publish_counts(ix, out_count, st));
+    }
+    ix->counters_dirty = 0;
+    return LVR_OK;
+}
+
+int lvr_query1(lvr_index *ix, const float *q, const float *tau_s, const float *tau, int32_t *out_idx,
+               int32_t *out_count, int64_t cap, void *stream) {
+    if (!ix || !q || !tau_s || !tau || !out_count || cap < 0 || (cap > 0 && !out_idx)) return LVR_E_INVALID;
+    if (!ix->built) return LVR_E_STATE;
+    if (ix->cfg.kv_dtype != LVR_BF16 || (ix->cfg.flags & LVR_SEPARATE_KERNELS) || ix->box || ix->cfg.n_subspaces > 4)
+        return LVR_E_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int rc = enqueue_query(ix, q, tau, out_idx, cap, st, tau_s);
     if (rc != LVR_OK) return rc;
     {
         Timed t(ix, LVR_K_RESET, st);

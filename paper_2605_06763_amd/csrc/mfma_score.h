@@ -107,6 +107,24 @@ __device__ __forceinline__ lvr_f32x4 lvr_score_tile(const uint4 (&a)[4], const l
     return s;
 }
 
+// Partial score over coordinates kk0*32 .. kk1*32-1 only (one coordinate block of "Query 1").
+template <int KK0, int KK1>
+__device__ __forceinline__ lvr_f32x4 lvr_score_tile_block(const uint4 (&a)[4], const lvr_bf16x8 (&bq)[4]) {
+    lvr_f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = KK0; kk < KK1; ++kk)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lvr_bf16x8, a[kk]), bq[kk], acc, 0, 0, 0);
+    lvr_f32x4 s;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float v = acc[j];
+        float t = v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x114, 0xf, 0xf, true));
+        t += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x118, 0xf, 0xf, true));
+        s[j] = t;
+    }
+    return s;
+}
+
 // Two chains into one accumulator:  D = A1 . B1 + A2 . B2  (box bound: upper corners against the
 // positive part of q, lower corners against the negative part; exact check of a row against
 // q = q+ + q-: the same A twice).

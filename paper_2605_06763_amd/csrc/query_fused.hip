@@ -1,7 +1,8 @@
 // Fused range-query kernel for bf16 caches: bound test and exact check in one launch.
 //
 // A workgroup owns a segment of consecutive groups of one (sequence, KV head):
-//   phase A  (Sec. 4.2 "Query 2" bound, Eq. (2) per coordinate block, summed): every wave
+//   phase A  (Sec. 4.2 "Query 2" bound, Eq. (2) per coordinate block, summed; or "Query 1":
+//            Eq. (2) per coordinate block against that block's own threshold): every wave
 //            scores its tiles of 16 centres on the matrix cores, adds the radius terms and
 //            keeps a bit per group; the four waves compact the surviving group ids into LDS
 //            (ballot + prefix sum, no global traffic).
@@ -15,6 +16,8 @@
 // The per-head counters must be zero when the kernel starts; the kernels that publish the
 // counts (publish_counts_kernel, combine_kernel) clear them for the next query.
 #include <stdlib.h>
+
+#include <type_traits>
 
 #include "emitter.h"
 #include "mfma_score.h"
@@ -30,15 +33,18 @@ struct FusedArgs {
     const int32_t *slot_pos;
     const float *q;
     const float *tau;
+    const float *tau_s;      // Query 1: [batch][H_q][S] per-block thresholds; NULL: Query 2
     int32_t *seg_count;      // survivors per segment, for statistics only
     lvr_emit_target emit;
     int64_t n_groups, max_groups, max_segs, cap_rows, n_indexed, n_total;
     int log2r, n_q_heads, n_kv_heads, G, buffer_dense, n_segs, tiles_per_wave;
 };
 
-template <int HB, int S, int UA, int ENC>   // UA = centre tiles per phase-A trip; ENC = 1: boxes instead of balls
+// UA = centre tiles per phase-A trip; ENC = 1: boxes instead of balls; Q1 = 1: per-block thresholds (S <= 4)
+template <int HB, int S, int UA, int ENC, int Q1 = 0>
 __global__ void __launch_bounds__(256)
 query_fused_kernel(const FusedArgs a) {
+    static_assert(!Q1 || (S <= 4 && !ENC), "Query 1 needs blocks that are whole MFMA steps");
     __shared__ uint4 s_bq[HB][4][64];
     __shared__ uint4 s_bq2[ENC ? HB : 1][4][64];
     __shared__ float s_qn[HB * 4][16];
@@ -121,6 +127,14 @@ query_fused_kernel(const FusedArgs a) {
         rep[hb] = n >= 8 && n < 12 && h < a.G;
         taue[hb] = rep[hb] ? lvr_effective_tau(a.tau[hq0 + h]) : INFINITY;
     }
+    float taus[HB][Q1 ? S : 1];
+    if constexpr (Q1) {
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+            for (int s = 0; s < S; ++s)
+                taus[hb][s] = rep[hb] ? lvr_effective_tau(a.tau_s[(hq0 + hb * 4 + n - 8) * S + s]) : INFINITY;
+    }
 
     int64_t rows;          // key rows phase B has to check
     int64_t buf_row0 = 0;
@@ -141,6 +155,30 @@ query_fused_kernel(const FusedArgs a) {
                 uint32_t alive4 = 0;
 #pragma unroll
                 for (int hb = 0; hb < HB; ++hb) {
+                    if constexpr (Q1) {
+                        // a group survives for a head iff every block's bound reaches that block's threshold
+                        bool okb[4] = {true, true, true, true};
+                        auto block = [&](auto s_c) {
+                            constexpr int s = decltype(s_c)::value;
+                            constexpr int KPS = 4 / S;
+                            const lvr_f32x4 sc = lvr_score_tile_block<s * KPS, (s + 1) * KPS>(av[u], bq[hb]);
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) okb[j] = okb[j] && (sc[j] + rad[u][j][s] * qn[hb][s] >= taus[hb][s]);
+                        };
+                        block(std::integral_constant<int, 0>{});
+                        if constexpr (S >= 2) block(std::integral_constant<int, 1>{});
+                        if constexpr (S >= 4) {
+                            block(std::integral_constant<int, 2>{});
+                            block(std::integral_constant<int, 3>{});
+                        }
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const bool ok = rep[hb] && okb[j] && (g_row + 4 * kq + j) < a.n_groups &&
+                                            (it + u) < a.tiles_per_wave;
+                            alive4 |= ok ? (1u << j) : 0u;
+                        }
+                        continue;
+                    }
                     lvr_f32x4 sc;
                     if constexpr (ENC) sc = lvr_score_tile2(av[u], bq[hb], av2[u], bq2[hb]);
                     else sc = lvr_score_tile(av[u], bq[hb]);
@@ -270,10 +308,12 @@ void launch_s(dim3 grid, hipStream_t st, const FusedArgs &a, int S) {
 
 }  // namespace
 
-hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *tau, int32_t *out_idx, int64_t cap,
-                                  hipStream_t st) {
+hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *tau, const float *tau_s,
+                                  int32_t *out_idx, int64_t cap, hipStream_t st) {
     if (ix->cfg.kv_dtype != LVR_BF16) return hipErrorInvalidValue;
+    if (tau_s && (ix->box || ix->cfg.n_subspaces > 4)) return hipErrorInvalidValue;
     FusedArgs a;
+    a.tau_s = tau_s;
     a.centres = ix->centres;
     a.radii = ix->radii;
     a.K = ix->K;
@@ -318,6 +358,19 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
     // one centre tile per trip (fewer registers, five waves per SIMD) for the small segments of short
     // contexts, two per trip for long ones: measured crossover between 32k and 128k keys
     const bool one = tpw == 1;
+    if (tau_s) {   // Query 1: per-block thresholds
+        const int S = ix->cfg.n_subspaces;
+        if (ix->G <= 4) {
+            if (S == 1) hipLaunchKernelGGL((query_fused_kernel<1, 1, 1, 0, 1>), grid, dim3(256), 0, st, a);
+            else if (S == 2) hipLaunchKernelGGL((query_fused_kernel<1, 2, 1, 0, 1>), grid, dim3(256), 0, st, a);
+            else hipLaunchKernelGGL((query_fused_kernel<1, 4, 1, 0, 1>), grid, dim3(256), 0, st, a);
+        } else {
+            if (S == 1) hipLaunchKernelGGL((query_fused_kernel<2, 1, 1, 0, 1>), grid, dim3(256), 0, st, a);
+            else if (S == 2) hipLaunchKernelGGL((query_fused_kernel<2, 2, 1, 0, 1>), grid, dim3(256), 0, st, a);
+            else hipLaunchKernelGGL((query_fused_kernel<2, 4, 1, 0, 1>), grid, dim3(256), 0, st, a);
+        }
+        return hipGetLastError();
+    }
     if (ix->box) {   // boxes: one allowance per group, one tile (two rows per group) per trip
         if (ix->G <= 4) hipLaunchKernelGGL((query_fused_kernel<1, 1, 1, 1>), grid, dim3(256), 0, st, a);
         else hipLaunchKernelGGL((query_fused_kernel<2, 1, 1, 1>), grid, dim3(256), 0, st, a);

@@ -161,3 +161,18 @@ def oracle_taus(oracle, ix: Index, q, k_count=None, frac=None):
             k = k_count if k_count is not None else int(math.ceil(frac * s.shape[0]))
             tau[b, h] = W.tau_for_count(s, k)
     return tau
+
+
+def query1(ix: Index, q: np.ndarray, tau_s: np.ndarray, tau: np.ndarray, cap=None):
+    """lvr_query1 followed by lvr_sparse_attention; tau_s [batch][hq][S]."""
+    cap = ix.n if cap is None else cap
+    qd = torch.from_numpy(np.ascontiguousarray(q, dtype=np.float32)).cuda()
+    td = torch.from_numpy(np.ascontiguousarray(tau, dtype=np.float32)).cuda()
+    tsd = torch.from_numpy(np.ascontiguousarray(tau_s, dtype=np.float32)).cuda()
+    idx = torch.full((ix.batch, ix.hq, max(cap, 1)), -7, dtype=torch.int32, device="cuda")
+    cnt = torch.full((ix.batch, ix.hq), -7, dtype=torch.int32, device="cuda")
+    out = torch.full((ix.batch, ix.hq, ix.d), float("nan"), dtype=torch.float32, device="cuda")
+    L.lvr_query1(ix.h, qd, tsd, td, idx, cnt)
+    L.lvr_sparse_attention(ix.h, qd, idx, cnt, out)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), cnt.cpu().numpy(), out.cpu().numpy()

@@ -736,3 +736,100 @@ def test_concurrent_update_bulk_append_and_rebuild(G, oracle):
         tau = G.oracle_taus(oracle, ix, q, frac=0.05)
         idx, cnt, out = ix.query(q, tau)
         G.check_step(oracle, ix, q, tau, idx, cnt, out, tag="rebuilt")
+
+
+# ---------------------------------------------------------------------------------------------
+# Query 1 (Sec. 4.2, Alg. 3): per-subspace thresholds
+# ---------------------------------------------------------------------------------------------
+def _exported_bounds(G, oracle, ix, q, r):
+    """Eq. (2) per block, evaluated by the oracle (fp64) on the index as the library stores it:
+    f [hq][S][groups] for sequence 0 (one KV head per G query heads)."""
+    centres, radii, _, _ = ix.export()
+    out = []
+    for h in range(ix.hq):
+        g = h // ix.G
+        c = W.bf16_bits_to_f32(centres[0, g]).reshape(-1, 128).astype(np.float64)
+        out.append(oracle.ball_bounds(q[0, h], c, radii[0, g].astype(np.float64)))
+    return np.stack(out)
+
+
+@pytest.mark.parametrize("S,keys,hq", [(1, "local", 4), (2, "local", 4), (4, "local", 4), (1, "workload", 4),
+                                       (2, "workload", 4), (4, "workload", 4), (2, "local", 8), (4, "local", 2),
+                                       (4, "workload", 1)])
+def test_query1_per_subspace_thresholds(G, oracle, S, keys, hq):
+    """Safe thresholds (tau_s = tau minus the largest bounds of the other blocks) must give
+    Problem 1's set; arbitrary thresholds must give a set between Alg. 3's candidates (oracle's
+    Query 1 on the exported index, thresholds nudged by rounding) filtered at tau, and every key
+    the promise covers (all block products reach their thresholds) must be present."""
+    n, r = 4096 + 37, 4
+    cache = W.make_local_cache(2, n=n) if keys == "local" else W.make_cache(2, n=n)
+    K, V = cache.K[:, :1], cache.V[:, :1]
+    q = W.make_queries(2, n_q_heads=hq)
+    G.say(f"query1 S={S} keys={keys} heads={hq}")
+    with G.Index(K, V, "bf16", hq, group_size=r, n_subspaces=S) as ix:
+        n_groups = n // r
+        f = _exported_bounds(G, oracle, ix, q, r)                      # [hq][S][groups]
+        label = np.tile(np.arange(n_groups * r, dtype=np.int32) // r, (S, 1))
+        ds = S and 128 // S
+        Kd = K[0, 0].astype(np.float64)
+        tau = G.oracle_taus(oracle, ix, q, frac=0.02)
+        # (1) provably safe thresholds
+        tau_s = np.empty((1, hq, S), dtype=np.float32)
+        for h in range(hq):
+            top = f[h].max(axis=1)
+            for s in range(S):
+                tau_s[0, h, s] = np.float32(tau[0, h] - (top.sum() - top[s]) - 1e-3)
+        idx, cnt, out = G.query1(ix, q, tau_s, tau)
+        G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=f"query1 safe S={S}")
+        st_safe = ix.stats()
+        # (2) thresholds that cut: per block the median of that block's bounds
+        for quant in (0.5, 0.9):
+            for h in range(hq):
+                tau_s[0, h] = np.quantile(f[h], quant, axis=1).astype(np.float32)
+            idx, cnt, out = G.query1(ix, q, tau_s, tau)
+            st = ix.stats()
+            alive_any_lo = np.zeros(n_groups, dtype=bool)
+            alive_any_hi = np.zeros(n_groups, dtype=bool)
+            for h in range(hq):
+                s_f32 = oracle.scores_f32(q[0, h], K[0, 0])
+                te = tau_s[0, h].astype(np.float64)
+                te = te - 0.5e-4 * np.abs(te)
+                slack = 1e-5 * np.abs(te) + 1e-3
+                strict = oracle.query1_filter(f[h], label, te + slack)          # certainly candidates
+                loose = oracle.query1_filter(f[h], label, te - slack)           # possibly candidates
+                alive_any_lo |= strict.reshape(n_groups, r)[:, 0]
+                alive_any_hi |= loose.reshape(n_groups, r)[:, 0]
+                got = np.zeros(n, dtype=bool)
+                got[idx[0, h, :cnt[0, h]]] = True
+                assert cnt[0, h] == got.sum()
+                band = 1e-4 * abs(float(tau[0, h]))
+                tail = np.arange(n) >= n_groups * r                            # buffer keys: tau only
+                # zero false negatives inside Alg. 3's candidate set
+                must = (s_f32 >= tau[0, h]) & (np.concatenate([strict, np.ones(n - n_groups * r, bool)]) | tail)
+                assert not (must & ~got).any(), (S, quant, h)
+                # nothing below the threshold band
+                assert not (got & (s_f32 < tau[0, h] - band)).any()
+                # the promise of Query 1: relevant keys whose block products all reach tau_s
+                blocks = (Kd * q[0, h].astype(np.float64)).reshape(n, S, ds).sum(-1)   # [n][S]
+                relevant = (s_f32 >= tau[0, h]) & (blocks >= tau_s[0, h][None, :] + 1e-3).all(1)
+                assert not (relevant & ~got).any()
+            assert alive_any_lo.sum() <= st["groups_surviving"] <= alive_any_hi.sum(), \
+                (S, quant, alive_any_lo.sum(), st["groups_surviving"], alive_any_hi.sum())
+            G.say(f"  quantile {quant}: {st['groups_surviving']} of {st['groups_scored']} groups are candidates "
+                  f"(safe thresholds: {st_safe['groups_surviving']})")
+            assert st["groups_surviving"] < st["groups_scored"]
+
+
+def test_query1_unsupported_configurations(G):
+    L = G.L
+    cache = _small_cache(2, 512)
+    q = torch.zeros((1, 8, 128), device="cuda")
+    tau = torch.zeros((1, 8), device="cuda")
+    idx = torch.zeros((1, 8, 16), dtype=torch.int32, device="cuda")
+    cnt = torch.zeros((1, 8), dtype=torch.int32, device="cuda")
+    for kw in (dict(n_subspaces=8), dict(enclosing=L.LVR_ENCLOSE_AABB), dict(flags=L.LVR_SEPARATE_KERNELS)):
+        with G.Index(cache.K, cache.V, "bf16", 8, **kw) as ix:
+            S = kw.get("n_subspaces", 4)
+            with pytest.raises(L.LouverError) as e:
+                L.lvr_query1(ix.h, q, torch.zeros((1, 8, S), device="cuda"), tau, idx, cnt)
+            assert e.value.code == L.LVR_E_UNSUPPORTED
