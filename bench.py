@@ -67,6 +67,10 @@ def main():
                          "not one of the five workloads")
     ap.add_argument("--concurrent-update", action="store_true",
                     help="group full buffers on a side stream (two-stream update); matters for --config 5")
+    ap.add_argument("--offload", action="store_true",
+                    help="offloaded mode: K and V in pinned host memory, only the index in HBM")
+    ap.add_argument("--separate", action="store_true",
+                    help="bound test and exact check as two launches (times the index search apart)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle sample")
     args = ap.parse_args()
@@ -118,7 +122,9 @@ def main():
                         group_size=args.group_size, n_subspaces=args.subspaces, buffer_size=256, capacity=capacity,
                         enclosing=L.LVR_ENCLOSE_AABB if args.enclosing == "aabb" else L.LVR_ENCLOSE_BALL,
                         grouping=L.LVR_GROUP_TREE if args.grouping == "tree" else L.LVR_GROUP_CONTIGUOUS,
-                        flags=L.LVR_CONCURRENT_UPDATE if args.concurrent_update else 0)
+                        flags=(L.LVR_CONCURRENT_UPDATE if args.concurrent_update else 0)
+                        | (L.LVR_KV_IN_HOST_MEMORY if args.offload else 0)
+                        | (L.LVR_SEPARATE_KERNELS if args.separate else 0))
     h = L.lvr_create(cfg)
     torch.cuda.synchronize()
     tb = time.time()
@@ -235,16 +241,18 @@ def main():
     #   groups * (d*2 + S*4) bytes of centres and radii  +  keys_scanned * d*2 bytes of key rows
     n_bh = B * Hkv
     filt = kern.get("filter", dict(avg_us=float("nan")))
+    if args.separate and "prune" in kern:
+        filt = dict(avg_us=filt["avg_us"] + kern["prune"]["avg_us"])
     query_bytes = st["bytes_index"] + st["bytes_keys"]
     achieved = query_bytes / (filt["avg_us"] * 1e-6) / 1e9
     step_bytes = st["bytes_index"] + st["bytes_keys"] + st["bytes_attention"]
-    roofline = dict(bound="hbm", kernel="query_fused_kernel", achieved=round(achieved, 1), peak=HBM_PEAK_GBS,
+    roofline = dict(bound="hbm", kernel="prune_mfma_kernel+filter_mfma_kernel" if args.separate else "query_fused_kernel", achieved=round(achieved, 1), peak=HBM_PEAK_GBS,
                     unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
                     bytes_per_launch=int(query_bytes), avg_launch_us=round(filt["avg_us"], 2))
     # HBM bytes per launch measured offline with rocprofv3 --pmc (profiles/), when this workload was profiled
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
     if (os.path.exists(tpath) and args.group_size == 4 and args.subspaces == 4 and args.keys == "workload"
-            and args.enclosing == "ball"):
+            and args.enclosing == "ball" and not args.offload and not args.separate and args.grouping == "contiguous"):
         for line in open(tpath):
             f = line.split()
             if len(f) == 3 and f[0] == f"config{cid}" and f[1] == "query_fused_kernel":
@@ -269,7 +277,9 @@ def main():
                    "head_dim": d, "context": int(n_now), "kv_storage": "bf16", "group_size": args.group_size,
                    "subspaces": args.subspaces, "grouping": args.grouping, "enclosing": args.enclosing,
                    "step": "append+query+attention" if appending else "query+attention",
-                   "update": "two-stream" if args.concurrent_update else "single-stream"},
+                   "update": "two-stream" if args.concurrent_update else "single-stream",
+                   "kv_memory": "host (pinned, read in place)" if args.offload else "hbm",
+                   "device_bytes": int(L.lvr_arena_bytes(cfg)), "host_bytes": int(L.lvr_host_bytes(cfg))},
         "roofline": roofline,
         "step_bytes": {"index": int(st["bytes_index"]), "keys": int(st["bytes_keys"]),
                        "attention": int(st["bytes_attention"]), "total": int(step_bytes),

@@ -65,7 +65,13 @@ enum lvr_flags {
      * the next lvr_append, lvr_build or lvr_publish: the caller's stream waits for the side
      * stream's event, then the published count advances.  All calls on one index must be
      * ordered on one stream. */
-    LVR_CONCURRENT_UPDATE = 4u
+    LVR_CONCURRENT_UPDATE = 4u,
+    /* Offloaded mode (Sec. 5 "KV Cache Offloading"): the K and V arena lives in pinned host
+     * memory that the GPU reads in place; only the index (centres or boxes, radii) and the
+     * work space stay in device memory.  The bound test runs on the GPU over the index; only
+     * the rows of surviving groups, and later the retrieved rows, cross the host link.  Every
+     * entry point works unchanged; lvr_arena_bytes then excludes the K and V arena. */
+    LVR_KV_IN_HOST_MEMORY = 8u
 };
 
 enum lvr_error {
@@ -123,6 +129,8 @@ int lvr_destroy(lvr_index *ix);
 
 /* Device bytes lvr_create would allocate for this configuration (0 if it is invalid). */
 size_t lvr_arena_bytes(const lvr_config *cfg_host);
+/* Pinned host bytes lvr_create would allocate (non-zero only with LVR_KV_IN_HOST_MEMORY). */
+size_t lvr_host_bytes(const lvr_config *cfg_host);
 
 /* Index construction (Sec. 4.1, Alg. 1; grouping per lvr_config.grouping; Eq. (1) balls).
  * K_dev, V_dev: [batch][n_kv_heads][n][head_dim] of kv_dtype, addressed with ELEMENT strides

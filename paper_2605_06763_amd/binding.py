@@ -19,6 +19,7 @@ LVR_ENCLOSE_BALL, LVR_ENCLOSE_AABB = 0, 1
 LVR_ATTEND_BUFFER_DENSE = 1
 LVR_SEPARATE_KERNELS = 2
 LVR_CONCURRENT_UPDATE = 4
+LVR_KV_IN_HOST_MEMORY = 8
 LVR_OK, LVR_E_INVALID, LVR_E_UNSUPPORTED, LVR_E_CAPACITY = 0, -1, -2, -3
 LVR_E_OVERFLOW, LVR_E_HIP, LVR_E_NOMEM, LVR_E_STATE = -4, -5, -6, -7
 
@@ -56,7 +57,7 @@ EXPORTS = [
     "lvr_create", "lvr_destroy", "lvr_arena_bytes", "lvr_build", "lvr_append", "lvr_query",
     "lvr_sparse_attention", "lvr_decode_step", "lvr_dense_attention", "lvr_get_stats",
     "lvr_export_index", "lvr_length", "lvr_strerror", "lvr_last_hip_error",
-    "lvr_profile_enable", "lvr_profile_read", "lvr_threshold", "lvr_export_reservoir", "lvr_publish", "lvr_query1",
+    "lvr_profile_enable", "lvr_profile_read", "lvr_threshold", "lvr_export_reservoir", "lvr_publish", "lvr_query1", "lvr_host_bytes",
 ]
 
 _lib = None
@@ -97,6 +98,8 @@ def lib():
     L.lvr_profile_enable.argtypes = [vp, C.c_int]
     L.lvr_profile_read.argtypes = [vp, C.POINTER(lvr_profile)]
     L.lvr_publish.argtypes = [vp, vp]
+    L.lvr_host_bytes.argtypes = [C.POINTER(lvr_config)]
+    L.lvr_host_bytes.restype = C.c_size_t
     L.lvr_query1.argtypes = [vp, vp, vp, vp, vp, vp, i64, vp]
     L.lvr_threshold.argtypes = [vp, vp, C.c_int, C.c_float, vp, vp]
     L.lvr_export_reservoir.argtypes = [vp, vp]
@@ -165,6 +168,10 @@ def make_config(*, batch, n_q_heads, n_kv_heads, head_dim=128, kv_dtype=LVR_BF16
 
 def lvr_arena_bytes(cfg: lvr_config) -> int:
     return int(lib().lvr_arena_bytes(C.byref(cfg)))
+
+
+def lvr_host_bytes(cfg: lvr_config) -> int:
+    return int(lib().lvr_host_bytes(C.byref(cfg)))
 
 
 def lvr_create(cfg: lvr_config) -> C.c_void_p:

@@ -75,7 +75,8 @@ Sizes sizes_of(const lvr_config *c) {
     s.counters = al(lvr_counter_ints((int)n_bh, (int)n_bhq, s.max_groups) * sizeof(int32_t));
     s.part_ml = al((size_t)n_bhq * s.Pmax * 2 * sizeof(float));
     s.part_o = al((size_t)n_bhq * s.Pmax * LVR_D * sizeof(float));
-    s.total = 2 * s.kv + s.centres + s.radii + s.list + s.counters + s.part_ml + s.part_o;
+    const bool kv_on_host = (c->flags & LVR_KV_IN_HOST_MEMORY) != 0;
+    s.total = (kv_on_host ? 0 : 2 * s.kv) + s.centres + s.radii + s.list + s.counters + s.part_ml + s.part_o;
     s.tree_keys = 0;
     s.maps = s.tree_keybytes = s.tree_axis = s.tree_partial = s.tree_temp = s.chunk = 0;
     if (c->grouping == LVR_GROUP_TREE) {
@@ -95,6 +96,11 @@ Sizes sizes_of(const lvr_config *c) {
 }
 
 void free_all(lvr_index *ix) {
+    if (ix->K_host || ix->V_host) {   // K and V alias pinned host memory
+        if (ix->K_host) (void)hipHostFree(ix->K_host);
+        if (ix->V_host) (void)hipHostFree(ix->V_host);
+        ix->K = ix->V = nullptr;
+    }
     void *ptrs[] = {ix->K, ix->V, ix->centres, ix->radii, ix->slot_pos, ix->pos_slot,
                     ix->surv_list, ix->counters, ix->part_ml, ix->part_o, ix->tree_keys_a, ix->tree_keys_b,
                     ix->tree_axis, ix->tree_partial, ix->tree_temp, ix->chunk_K, ix->chunk_V, ix->reservoir};
@@ -164,6 +170,11 @@ size_t lvr_arena_bytes(const lvr_config *cfg) {
     return sizes_of(cfg).total;
 }
 
+size_t lvr_host_bytes(const lvr_config *cfg) {
+    if (check_config(cfg) != LVR_OK || !(cfg->flags & LVR_KV_IN_HOST_MEMORY)) return 0;
+    return 2 * sizes_of(cfg).kv;
+}
+
 int lvr_create(const lvr_config *cfg, lvr_index **out) {
     if (!out) return LVR_E_INVALID;
     int rc = check_config(cfg);
@@ -184,13 +195,21 @@ int lvr_create(const lvr_config *cfg, lvr_index **out) {
     ix->elt = cfg->kv_dtype == LVR_BF16 ? 2 : 4;
     ix->sigma = cfg->scale > 0.f ? cfg->scale : 1.0f / sqrtf((float)cfg->head_dim);
     hipError_t e = hipGetDevice(&ix->device);
+    const bool kv_on_host = (cfg->flags & LVR_KV_IN_HOST_MEMORY) != 0;
+    if (kv_on_host) {
+        // pinned, GPU-mapped host memory: kernels read (and the build/append copies write) it in place
+        if (e == hipSuccess) e = hipHostMalloc(&ix->K_host, s.kv, hipHostMallocMapped);
+        if (e == hipSuccess) e = hipHostMalloc(&ix->V_host, s.kv, hipHostMallocMapped);
+        if (e == hipSuccess) e = hipHostGetDevicePointer(&ix->K, ix->K_host, 0);
+        if (e == hipSuccess) e = hipHostGetDevicePointer(&ix->V, ix->V_host, 0);
+    }
     struct { void **p; size_t bytes; } allocs[] = {
-        {&ix->K, s.kv}, {&ix->V, s.kv}, {&ix->centres, s.centres}, {(void **)&ix->radii, s.radii},
+        {&ix->K, kv_on_host ? 0 : s.kv}, {&ix->V, kv_on_host ? 0 : s.kv}, {&ix->centres, s.centres}, {(void **)&ix->radii, s.radii},
         {(void **)&ix->surv_list, s.list}, {(void **)&ix->counters, s.counters},
         {(void **)&ix->part_ml, s.part_ml}, {(void **)&ix->part_o, s.part_o}};
     for (auto &a : allocs) {
         if (e != hipSuccess) break;
-        e = hipMalloc(a.p, a.bytes);
+        if (a.bytes) e = hipMalloc(a.p, a.bytes);
     }
     if (e == hipSuccess && cfg->grouping == LVR_GROUP_TREE) {
         ix->tree_cap_keys = s.tree_keys;
@@ -327,10 +346,10 @@ int lvr_append(lvr_index *ix, const void *k_new, const void *v_new, int64_t m, v
             const size_t row_bytes = LVR_D * ix->elt;
             const int64_t cs[3] = {(int64_t)ix->cfg.n_kv_heads * B * LVR_D, B * LVR_D, LVR_D};
             LVR_HIP(hipMemcpy2DAsync(ix->chunk_K, B * row_bytes, static_cast<char *>(ix->K) + ix->n_indexed * row_bytes,
-                                     ix->cap_rows * row_bytes, B * row_bytes, lvr_n_bh(ix), hipMemcpyDeviceToDevice,
+                                     ix->cap_rows * row_bytes, B * row_bytes, lvr_n_bh(ix), hipMemcpyDefault,
                                      ix->side));
             LVR_HIP(hipMemcpy2DAsync(ix->chunk_V, B * row_bytes, static_cast<char *>(ix->V) + ix->n_indexed * row_bytes,
-                                     ix->cap_rows * row_bytes, B * row_bytes, lvr_n_bh(ix), hipMemcpyDeviceToDevice,
+                                     ix->cap_rows * row_bytes, B * row_bytes, lvr_n_bh(ix), hipMemcpyDefault,
                                      ix->side));
             hipError_t e = lvr_tree_order(ix, ix->chunk_K, cs, B, ix->side, ix->pend_perm);
             if (e == hipErrorInvalidValue) return LVR_E_UNSUPPORTED;
@@ -353,10 +372,10 @@ int lvr_append(lvr_index *ix, const void *k_new, const void *v_new, int64_t m, v
                 const int64_t row0 = ix->n_indexed + c * B;
                 LVR_HIP(hipMemcpy2DAsync(ix->chunk_K, B * row_bytes, static_cast<char *>(ix->K) + row0 * row_bytes,
                                          ix->cap_rows * row_bytes, B * row_bytes, lvr_n_bh(ix),
-                                         hipMemcpyDeviceToDevice, st));
+                                         hipMemcpyDefault, st));
                 LVR_HIP(hipMemcpy2DAsync(ix->chunk_V, B * row_bytes, static_cast<char *>(ix->V) + row0 * row_bytes,
                                          ix->cap_rows * row_bytes, B * row_bytes, lvr_n_bh(ix),
-                                         hipMemcpyDeviceToDevice, st));
+                                         hipMemcpyDefault, st));
                 hipError_t e = lvr_tree_group(ix, ix->chunk_K, cs, ix->chunk_V, cs, B, row0, st);
                 if (e == hipErrorInvalidValue) return LVR_E_UNSUPPORTED;
                 LVR_HIP(e);
@@ -582,7 +601,7 @@ int lvr_export_index(lvr_index *ix, void *centres, float *radii, int32_t *slot_p
         if (keys && n > 0)
             LVR_HIP(hipMemcpy(static_cast<char *>(keys) + (size_t)bh * n * row_bytes,
                               static_cast<char *>(ix->K) + (size_t)bh * ix->cap_rows * row_bytes, (size_t)n * row_bytes,
-                              hipMemcpyDeviceToHost));
+                              hipMemcpyDefault));
         if (slot_pos && n > 0) {
             if (ix->slot_pos) {
                 LVR_HIP(hipMemcpy(slot_pos + (size_t)bh * n, ix->slot_pos + (size_t)bh * ix->cap_rows,

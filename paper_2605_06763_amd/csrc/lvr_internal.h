@@ -33,8 +33,9 @@ struct lvr_index {
     float sigma;
     size_t elt;            // bytes per K/V element
     // arena (device)
-    void *K;               // [batch][H_kv][cap_rows][d]
+    void *K;               // [batch][H_kv][cap_rows][d]  (device address; host-resident in offloaded mode)
     void *V;
+    void *K_host, *V_host; // offloaded mode: the pinned host allocations behind K and V, else NULL
     void *centres;         // [batch][H_kv][max_groups][d]  (boxes: [..][max_groups][2][d], upper then lower corner)
     float *radii;          // [batch][H_kv][max_groups][S_store]
     int32_t *slot_pos;     // [batch][H_kv][cap_rows] token position of arena row (TREE grouping), else NULL

@@ -833,3 +833,46 @@ def test_query1_unsupported_configurations(G):
             with pytest.raises(L.LouverError) as e:
                 L.lvr_query1(ix.h, q, torch.zeros((1, 8, S), device="cuda"), tau, idx, cnt)
             assert e.value.code == L.LVR_E_UNSUPPORTED
+
+
+# ---------------------------------------------------------------------------------------------
+# Offloaded mode (Sec. 5 "KV Cache Offloading"): K and V in pinned host memory, index on the GPU
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("grouping,flags", [("contiguous", 0), ("contiguous", 2), ("tree", 0), ("contiguous", 4)])
+def test_offloaded_kv_same_results(G, oracle, grouping, flags):
+    """With the K/V arena in host memory every entry point gives the results of the resident
+    arena: sets and attention against the oracle, exported index bit-equal, appends included;
+    device memory then holds the index and work space only."""
+    L = G.L
+    n0, extra, B = 3000 + 3, 150, 64
+    gr = L.LVR_GROUP_TREE if grouping == "tree" else L.LVR_GROUP_CONTIGUOUS
+    cache = W.make_local_cache(2, n=n0 + extra)
+    K, V = cache.K[:, :2], cache.V[:, :2]
+    q = W.make_queries(2, n_q_heads=8)
+    G.say(f"offloaded grouping={grouping} flags={flags}")
+    kw = dict(capacity=n0 + extra, buffer_size=B, grouping=gr)
+    with G.Index(K[:, :, :n0], V[:, :, :n0], "bf16", 8, flags=flags | L.LVR_KV_IN_HOST_MEMORY, **kw) as ix, \
+         G.Index(K[:, :, :n0], V[:, :, :n0], "bf16", 8, flags=flags, **kw) as ref:
+        kv_bytes = 2 * 2 * ((n0 + extra + 63) // 64 * 64) * 128 * 2
+        assert L.lvr_host_bytes(ix.cfg) == kv_bytes and L.lvr_host_bytes(ref.cfg) == 0
+        assert L.lvr_arena_bytes(ref.cfg) - L.lvr_arena_bytes(ix.cfg) == kv_bytes
+        for step in range(3):
+            for frac in (0.01, 0.2):
+                tau = G.oracle_taus(oracle, ix, q, frac=frac)
+                for fused in (True, False):
+                    idx, cnt, out = ix.query(q, tau, fused=fused)
+                    G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=f"offloaded step={step} frac={frac}")
+                st, st_ref = ix.stats(), None
+                ref.query(q, tau)
+                st_ref = ref.stats()
+                assert st["groups_surviving"] == st_ref["groups_surviving"]
+            got = ix.dense(q)
+            want = oracle.dense_attention(ix.K, ix.V, q, ix.sigma, 8)
+            assert (np.abs(got - want).max(axis=-1) / np.abs(want).max(axis=-1)).max() <= G.ATTN_TOL
+            lo, hi = n0 + step * 50, n0 + (step + 1) * 50
+            ix.append(K[:, :, lo:hi], V[:, :, lo:hi])
+            ref.append(K[:, :, lo:hi], V[:, :, lo:hi])
+        L.lvr_publish(ix.h)
+        L.lvr_publish(ref.h)
+        for name, x, y in zip(("centres", "radii", "slot_pos", "keys"), ix.export(), ref.export()):
+            assert np.array_equal(np.asarray(x), np.asarray(y)), name
