@@ -71,6 +71,8 @@ def main():
                     help="offloaded mode: K and V in pinned host memory, only the index in HBM")
     ap.add_argument("--separate", action="store_true",
                     help="bound test and exact check as two launches (times the index search apart)")
+    ap.add_argument("--rotate", type=int, default=4,
+                    help="replicas of the index cycled through by the cache-cold pass (1 = skip that pass)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle sample")
     args = ap.parse_args()
@@ -198,6 +200,46 @@ def main():
         log("[bench] WARNING: a retrieved set exceeded cap; lists were truncated")
     n_now = st["n_keys"]
 
+    # ---- distribution over steps: one event after every step of another pass over the same K steps
+    # (each figure includes the event's own cost, about 1 us; the mean above does not) ----
+    step_dist = None
+    if not appending:
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(K_steps + 1)]
+        torch.cuda.synchronize()
+        evs[0].record()
+        for t in range(K_steps):
+            one_step(W_steps + t)
+            evs[t + 1].record()
+        torch.cuda.synchronize()
+        per = np.array([evs[t].elapsed_time(evs[t + 1]) * 1e3 for t in range(K_steps)])
+        step_dist = {"p10": round(float(np.percentile(per, 10)), 2), "median": round(float(np.median(per)), 2),
+                     "p90": round(float(np.percentile(per, 90)), 2), "max": round(float(per.max()), 2)}
+
+    # ---- cache-cold protocol: the same steps over `rotate` replicas of the index in turn, so that a
+    # step never finds the previous step's lines of its replica in the 256 MB memory-side cache ----
+    cold = None
+    if not appending and args.rotate > 1:
+        reps = [h]
+        for _ in range(args.rotate - 1):
+            hr = L.lvr_create(cfg)
+            L.lvr_build(hr, Kd, Vd)
+            reps.append(hr)
+        def run_rot(n_steps, first):
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            ev0.record()
+            for t in range(first, first + n_steps):
+                L.lvr_decode_step(reps[t % len(reps)], q_args[t % n_distinct], tau_args[t % n_distinct], out_a, idx_a,
+                                  cnt_a, st_arg)
+            ev1.record()
+            torch.cuda.synchronize()
+            return ev0.elapsed_time(ev1)
+        run_rot(max(W_steps, len(reps)), 0)
+        cold_ms = run_rot(K_steps, W_steps) / K_steps
+        for hr in reps[1:]:
+            L.lvr_destroy(hr)
+        cold = {"replicas": len(reps), "us_per_step": round(cold_ms * 1e3, 2)}
+
     # ---- per-kernel time with HIP events on the launch stream (same K steps again) ----
     L.lvr_profile_enable(h, 8 * K_steps + 64)
     first = total_steps if appending else W_steps
@@ -294,6 +336,8 @@ def main():
                            "GBs": round(dense_bytes / (dense_ms * 1e-3) / 1e9, 1),
                            "frac_of_peak": round(dense_bytes / (dense_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                            "speedup_of_sparse_path": round(dense_ms / ms_per_step, 3)},
+        "step_us_distribution": step_dist,
+        "cache_cold": cold,
         "device_copy_GBs": round(copy_gbs, 1),
         "build_ms": round(build_ms, 3),
     }
