@@ -48,6 +48,12 @@ sparse_attention_kernel(const void *__restrict__ K, const void *__restrict__ V, 
     const int bh = b * n_kv_heads + h / G;
     const int lane = threadIdx.x & 63, sub = lane >> 4, li = lane & 15;
 
+    const int32_t *my_idx = idx + hq * cap;
+    // The split geometry depends on the count, and the positions on the geometry: two dependent
+    // loads before the first gather.  The common geometry (16 entries per split) is assumed for a
+    // speculative load of the positions that goes out together with the count.
+    const int64_t e_spec = (int64_t)p * 16 + lane;
+    const int32_t pos_spec = (lane < 16 && e_spec < cap) ? my_idx[e_spec] : -1;
     int64_t cnt = count[hq * count_stride];
     if (cnt > cap) cnt = cap;
     if (cnt < 0) cnt = 0;
@@ -65,7 +71,6 @@ sparse_attention_kernel(const void *__restrict__ K, const void *__restrict__ V, 
     }
     const char *Kb = static_cast<const char *>(K) + (int64_t)bh * cap_rows * LVR_D * sizeof(KT);
     const char *Vb = static_cast<const char *>(V) + (int64_t)bh * cap_rows * LVR_D * sizeof(KT);
-    const int32_t *my_idx = idx + hq * cap;
     const int32_t *pslot = pos_slot ? pos_slot + (int64_t)bh * cap_rows : nullptr;
 
     float m = -INFINITY, l = 0.f, acc[8];
@@ -75,7 +80,7 @@ sparse_attention_kernel(const void *__restrict__ K, const void *__restrict__ V, 
         int64_t e = c0 + lane;
         int myslot = -1;
         if (e < end) {
-            const int64_t pos = my_idx[e];
+            const int64_t pos = (L == 16) ? (int64_t)pos_spec : (int64_t)my_idx[e];
             if (pos >= 0 && pos < n_total) myslot = pslot ? pslot[pos] : (int)pos;
         }
         const int chunk = (int)((end - c0 < 64) ? end - c0 : 64);
@@ -270,6 +275,19 @@ combine_kernel(const float *__restrict__ part_ml, const float *__restrict__ part
     __shared__ float s_num[4][LVR_D];
     const int64_t hq = blockIdx.x;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int c = t & (LVR_D - 1), sl = t >> 7;
+    const float *po = part_o + hq * P * LVR_D + c;
+    // up to 16 partials per thread (all of them for P <= 64) and the (m, l) pairs are requested
+    // first, together with the count, so that nothing waits for a second trip to memory; what
+    // lies beyond the partials in use is stale and is masked once the count has arrived
+    float pv[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int p = sl + 4 * i;
+        pv[i] = (p < P) ? po[(int64_t)p * LVR_D] : 0.f;
+    }
+    const float m_raw = (t < P) ? part_ml[(hq * P + t) * 2] : -INFINITY;
+    const float l_raw = (t < P) ? part_ml[(hq * P + t) * 2 + 1] : 0.f;
     int used = P;
     if (count) {
         int64_t cnt = count[hq * count_stride];
@@ -282,17 +300,8 @@ combine_kernel(const float *__restrict__ part_ml, const float *__restrict__ part
         if (cnt < 0) cnt = 0;
         split_length(cnt, P, &used);
     }
-    const int c = t & (LVR_D - 1), sl = t >> 7;
-    const float *po = part_o + hq * P * LVR_D + c;
-    // up to 8 partials per thread are fetched before anything depends on them
-    float pv[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int p = sl + 4 * i;
-        pv[i] = (p < used) ? po[(int64_t)p * LVR_D] : 0.f;
-    }
-    const float m = (t < used) ? part_ml[(hq * P + t) * 2] : -INFINITY;
-    const float l = (t < used) ? part_ml[(hq * P + t) * 2 + 1] : 0.f;
+    const float m = (t < used) ? m_raw : -INFINITY;
+    const float l = (t < used) ? l_raw : 0.f;
     float mx = m;
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
@@ -314,12 +323,12 @@ combine_kernel(const float *__restrict__ part_ml, const float *__restrict__ part
     for (int w = 0; w < 8; ++w) den += s_red[w];
     float num = 0.f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < 16; ++i) {
         const int p = sl + 4 * i;
         num += (p < used) ? s_w[p] * pv[i] : 0.f;
     }
 #pragma unroll 4
-    for (int p = sl + 32; p < used; p += 4) num += s_w[p] * po[(int64_t)p * LVR_D];
+    for (int p = sl + 64; p < used; p += 4) num += s_w[p] * po[(int64_t)p * LVR_D];
     s_num[sl][c] = num;
     __syncthreads();
     if (t < LVR_D) {
