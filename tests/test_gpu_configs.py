@@ -121,3 +121,41 @@ def test_config5_long_output_decode(G, oracle):
         G.say("config5", dict(checked_steps=len(check_at), retrieved=total_retrieved, attn_err=worst), st)
     finally:
         L.lvr_destroy(h)
+
+
+def test_config2_library_thresholds_query1_and_offload(G, oracle):
+    """Full-size config 2 through the rows beyond the core path: tau chosen by the library's
+    budget rule over its reservoir (equal to the oracle's rule on the oracle's sample) and used
+    for a decode step; Query 1 with safe per-subspace thresholds; the same step with the K/V
+    arena in host memory."""
+    L = G.L
+    seed, R = 20260506, 256
+    cache = W.make_cache(2)
+    q = W.make_queries(2)
+    with G.Index(cache.K, cache.V, "bf16", 32, reservoir_size=R, seed=seed) as ix:
+        res = ix.reservoir()
+        for g in range(8):
+            assert np.array_equal(res[0, g], oracle.reservoir(seed, g, ix.n, R))
+        for mode, param in (("budget", 0.02), ("sample-topk", 3), ("sample-max", 0)):
+            tau = ix.threshold(q, mode, param)
+            for h in range(32):
+                s = oracle.scores_f32(q[0, h], ix.K[0, h // 4][res[0, h // 4]])
+                assert abs(tau[0, h] - oracle.threshold(s, mode, param)) <= 2e-6 * max(1.0, float(np.abs(s).max()))
+            idx, cnt, out = ix.query(q, tau, cap=8192, fused=True)
+            r = G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=f"config2 {mode}")
+            G.say(f"config2 tau by {mode}({param}): retrieved per head {cnt.mean():.1f}", r)
+        # Query 1 with thresholds that cannot lose a qualifying key
+        centres, radii, _, _ = ix.export()
+        tau = G.oracle_taus(oracle, ix, q, frac=0.01)
+        tau_s = np.empty((1, 32, 4), dtype=np.float32)
+        for h in range(32):
+            c = W.bf16_bits_to_f32(centres[0, h // 4]).reshape(-1, 128).astype(np.float64)
+            top = oracle.ball_bounds(q[0, h], c, radii[0, h // 4].astype(np.float64)).max(axis=1)
+            tau_s[0, h] = (tau[0, h] - (top.sum() - top) - 1e-3).astype(np.float32)
+        idx, cnt, out = G.query1(ix, q, tau_s, tau, cap=2048)
+        G.check_step(oracle, ix, q, tau, idx, cnt, out, tag="config2 query1")
+    with G.Index(cache.K, cache.V, "bf16", 32, flags=L.LVR_KV_IN_HOST_MEMORY) as ix:
+        assert L.lvr_host_bytes(ix.cfg) == 2 * 8 * 32768 * 128 * 2
+        tau = G.oracle_taus(oracle, ix, q, frac=0.01)
+        idx, cnt, out = ix.query(q, tau, cap=2048, fused=True)
+        G.check_step(oracle, ix, q, tau, idx, cnt, out, tag="config2 offloaded")
