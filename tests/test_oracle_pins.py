@@ -586,3 +586,33 @@ def test_threshold_rules_closed_forms(oracle):
         t = oracle.threshold(x, "budget", a)
         assert (x >= t).sum() == math.ceil(a * 256)
     assert oracle.threshold(np.zeros(0, np.float32), "sample-max") == -np.inf
+
+
+def test_threshold_rules_against_the_papers_table(oracle):
+    """The appendix table of mean thresholds (tests/golden/threshold_oracle_table.txt) fixes how the
+    rank-based rules relate: with a reservoir of 256, budget(alpha) read as the ceil(alpha*256)-th
+    largest score puts budget(5 %) = 13th largest below topk(10) and above budget(10 %) = 26th, which
+    is the order of the printed means; and sample-mean-max read as (max + mean)/2 is half the
+    sample-max when the mean score is near zero (31.3 against 62.0 / 2)."""
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "threshold_oracle_table.txt")) if l.strip() and l[0] != "#"]
+    table = {(r[0], float(r[1])): float(r[2]) for r in rows}
+    rank_of = {("sample-max", 0.0): 1, ("sample-topk", 2.0): 2, ("sample-topk", 5.0): 5, ("sample-topk", 10.0): 10,
+               ("budget", 0.05): math.ceil(0.05 * 256), ("budget", 0.10): math.ceil(0.10 * 256),
+               ("budget", 0.15): math.ceil(0.15 * 256)}
+    by_rank = sorted(rank_of, key=lambda k: rank_of[k])
+    means = [table[k] for k in by_rank]
+    assert means == sorted(means, reverse=True), "printed means must fall as the rank the rule reads grows"
+    # the oracle's rules read exactly those ranks of a sample, whatever the sample
+    g = np.random.default_rng(5)
+    for _ in range(20):
+        s = (g.standard_normal(256) * g.uniform(1, 20) + g.uniform(-5, 5)).astype(np.float32)
+        srt = np.sort(s)[::-1]
+        for (mode, param), rank in rank_of.items():
+            assert oracle.threshold(s, mode, param) == srt[rank - 1], (mode, param)
+        gap = oracle.threshold(s, "sample-gap")
+        assert srt[-1] < gap <= srt[0]
+    # (max + mean) / 2: the table's mean-max is half its sample-max up to the (small) mean score
+    implied_mean = 2 * table[("sample-mean-max", 0.0)] - table[("sample-max", 0.0)]
+    assert abs(implied_mean) < 0.25 * table[("budget", 0.15)]
+    # sample-gap's printed mean lies between topk(2) and topk(5): the largest gap sits in the top few
+    assert table[("sample-topk", 5.0)] < table[("sample-gap", 0.0)] < table[("sample-topk", 2.0)]
