@@ -62,8 +62,10 @@ enum lvr_flags {
      * keys are grouped on a stream the library owns, into index slots beyond the published group
      * count, while calls on the caller's stream keep answering queries with those keys still in
      * the buffer (scanned exactly, so results do not change).  The new groups are published by
-     * the next lvr_append, lvr_build or lvr_publish: the caller's stream waits for the side
-     * stream's event, then the published count advances.  All calls on one index must be
+     * lvr_publish, or by a later lvr_append: the first one that finds the side stream finished
+     * (a host-side poll; it never blocks), at the latest the one that fills the next chunk.  To
+     * publish, the caller's stream waits for the side stream's event, then the published count
+     * advances.  All calls on one index must be
      * ordered on one stream. */
     LVR_CONCURRENT_UPDATE = 4u,
     /* Offloaded mode (Sec. 5 "KV Cache Offloading"): the K and V arena lives in pinned host

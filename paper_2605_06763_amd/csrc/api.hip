@@ -114,10 +114,20 @@ void free_all(lvr_index *ix) {
 
 // Phase 2 of the two-stream update (App. "GPU Update"): `st` waits for the side stream, then
 // the prepared groups become visible to the launches that follow.
-int publish_pending(lvr_index *ix, hipStream_t st) {
+// force = false: publish only if the side stream has already finished (a host-side poll that never
+// blocks), so a slow update stays hidden behind as many decode steps as it needs.
+int publish_pending(lvr_index *ix, hipStream_t st, bool force) {
     if (!ix->pending) return LVR_OK;
     const int64_t B = ix->cfg.buffer_size;
     const int r = ix->cfg.group_size;
+    if (!force) {
+        const hipError_t qe = hipEventQuery(ix->ev_done);
+        if (qe == hipErrorNotReady) {
+            (void)hipGetLastError();   // "not ready" is an answer, not a failure to be reported later
+            return LVR_OK;
+        }
+        LVR_HIP(qe);
+    }
     LVR_HIP(hipStreamWaitEvent(st, ix->ev_done, 0));
     if (ix->cfg.grouping == LVR_GROUP_TREE) {
         // the chunk's order was computed on the side stream from a staged copy; moving the rows
@@ -231,8 +241,7 @@ int lvr_create(const lvr_config *cfg, lvr_index **out) {
         if (e == hipSuccess) e = hipMemset(ix->reservoir, 0xff, rb);
     }
     if (e == hipSuccess && (cfg->flags & LVR_CONCURRENT_UPDATE)) {
-        e = hipStreamCreateWithFlags(&ix->side, hipStreamNonBlocking);
-        if (e == hipSuccess) e = hipEventCreateWithFlags(&ix->ev_fork, hipEventDisableTiming);
+        e = hipEventCreateWithFlags(&ix->ev_fork, hipEventDisableTiming);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&ix->ev_done, hipEventDisableTiming);
         if (e == hipSuccess) {
             ix->pend_perm = new (std::nothrow) lvr_tree_perm();
@@ -321,7 +330,11 @@ int lvr_append(lvr_index *ix, const void *k_new, const void *v_new, int64_t m, v
     if (!aligned16(k_new) || !aligned16(v_new)) return LVR_E_INVALID;
     hipStream_t st = static_cast<hipStream_t>(stream);
     {
-        int rc = publish_pending(ix, st);
+        // groups prepared earlier become visible as soon as they are ready; they must be before
+        // the next chunk is formed
+        const int64_t unpublished = ix->pending ? ix->cfg.buffer_size : 0;
+        const bool next_chunk_fills = ix->n_total + m - ix->n_indexed - unpublished >= ix->cfg.buffer_size;
+        int rc = publish_pending(ix, st, next_chunk_fills);
         if (rc != LVR_OK) return rc;
     }
     const int64_t strides[3] = {(int64_t)ix->cfg.n_kv_heads * m * LVR_D, m * LVR_D, LVR_D};
@@ -335,11 +348,12 @@ int lvr_append(lvr_index *ix, const void *k_new, const void *v_new, int64_t m, v
     // every full buffer of B keys becomes B/r new groups at the tail of the index
     const int64_t B = ix->cfg.buffer_size;
     const int r = ix->cfg.group_size;
-    const int64_t full = (ix->n_total - ix->n_indexed) / B;
+    const int64_t full = ix->pending ? 0 : (ix->n_total - ix->n_indexed) / B;   // pending: its B keys are spoken for, fewer than B more
     if (full == 1 && (ix->cfg.flags & LVR_CONCURRENT_UPDATE)) {
         // Phase 1 on the side stream: it starts once the rows copied above are in the arena and
         // writes only index slots (and staging) that no query launched before the publish reads
         const int64_t g0 = ix->n_indexed / r;
+        if (!ix->side) LVR_HIP(hipStreamCreateWithFlags(&ix->side, hipStreamNonBlocking));   // made at first use
         LVR_HIP(hipEventRecord(ix->ev_fork, st));
         LVR_HIP(hipStreamWaitEvent(ix->side, ix->ev_fork, 0));
         if (ix->cfg.grouping == LVR_GROUP_TREE) {
@@ -390,7 +404,7 @@ int lvr_append(lvr_index *ix, const void *k_new, const void *v_new, int64_t m, v
 int lvr_publish(lvr_index *ix, void *stream) {
     if (!ix) return LVR_E_INVALID;
     if (!ix->built) return LVR_E_STATE;
-    return publish_pending(ix, static_cast<hipStream_t>(stream));
+    return publish_pending(ix, static_cast<hipStream_t>(stream), true);
 }
 
 }  // extern "C"

@@ -225,6 +225,136 @@ __global__ void tree_gather_kernel(TreeSrc ksrc, TreeSrc vsrc, const uint64_t *_
     }
 }
 
+// Small inputs (a buffer chunk of B keys, np <= TREE_WG_MAX padded entries): the whole tree in ONE
+// launch, one 256-thread workgroup per (sequence, KV head).  Same steps as the level-synchronous
+// kernels above (same statistics in the same order, same keys), with the order kept in LDS and a
+// bitonic sort in place of the device-wide radix sort; keys are unique, so any sort gives the
+// same order.  The node index inside the key is local to the (sequence, KV head).
+constexpr int TREE_WG_MAX = 1024;
+
+__global__ void __launch_bounds__(256)
+tree_small_kernel(TreeSrc src, uint64_t *__restrict__ keys_out, int np, int64_t n_real, int levels, int pos_bits,
+                  int coord_bits) {
+    __shared__ uint64_t s_keys[TREE_WG_MAX];
+    __shared__ int32_t s_axis[TREE_WG_MAX / 2];
+    __shared__ double s_part[4][256];   // per run: 128 sums, 128 sums of squares
+    __shared__ int s_cnt[4];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int bh = blockIdx.x;
+    for (int i = t; i < np; i += 256) s_keys[i] = (uint64_t)i;
+    __syncthreads();
+    for (int L = 0; L < levels; ++L) {
+        const int n_nodes = 1 << L;
+        const int m = np >> L;
+        // 1. split axis of every node.  The entries of the level are dealt to the four waves in
+        // runs of `run` consecutive entries (a whole node, or a quarter of a big one); each wave
+        // sums its run relative to the node's first key, eight rows in flight at a time, and the
+        // runs of a node are added in order.
+        {
+            const int run = (m >= 4 * 8) ? ((n_nodes >= 4) ? m : m / (4 / n_nodes)) : m;   // entries per run
+            const int runs_per_node = m / run;
+            const int n_runs = n_nodes * runs_per_node;
+            for (int rix = wave; rix < n_runs; rix += 4) {
+                const int node = rix / runs_per_node;
+                const uint64_t *kk = s_keys + node * m;
+                const int i_begin = (rix % runs_per_node) * run;
+                const int64_t ppos = key_pos(kk[0], pos_bits);   // padding sorts last: entry 0 is real unless all are padding
+                float p0 = 0.f, p1 = 0.f;
+                if (ppos < n_real) lane_pair(src.row(bh, ppos), lane, src.elt, p0, p1);
+                double s0 = 0., s1 = 0., q0 = 0., q1 = 0.;
+                int cnt = 0;
+                for (int i0 = i_begin; i0 < i_begin + run; i0 += 8) {
+                    float x0[8], x1[8];
+                    bool real[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int64_t pos = (i0 + u < i_begin + run) ? key_pos(kk[i0 + u], pos_bits) : n_real;
+                        real[u] = pos < n_real;
+                        lane_pair(src.row(bh, real[u] ? pos : (ppos < n_real ? ppos : 0)), lane, src.elt, x0[u], x1[u]);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const double d0 = real[u] ? (double)x0[u] - (double)p0 : 0.;
+                        const double d1 = real[u] ? (double)x1[u] - (double)p1 : 0.;
+                        s0 += d0; s1 += d1; q0 += d0 * d0; q1 += d1 * d1;
+                        cnt += real[u] ? 1 : 0;
+                    }
+                }
+                double *o = s_part[rix & 3];
+                o[2 * lane] = s0; o[2 * lane + 1] = s1;
+                o[128 + 2 * lane] = q0; o[128 + 2 * lane + 1] = q1;
+                if (lane == 0) s_cnt[rix & 3] = cnt;
+                if (runs_per_node == 1) {
+                    const double inv = cnt > 0 ? 1.0 / (double)cnt : 0.;
+                    const double v0 = (q0 - s0 * s0 * inv) * inv, v1 = (q1 - s1 * s1 * inv) * inv;
+                    const int arg = wave_argmax(v0, v1, lane);
+                    if (lane == 0) s_axis[node] = arg;
+                }
+            }
+            if (runs_per_node > 1) {   // 1 or 2 nodes, each summed by 4 or 2 waves: add the runs in order
+                __syncthreads();
+                if (wave < n_nodes) {
+                    double s0 = 0., s1 = 0., q0 = 0., q1 = 0.;
+                    int cnt = 0;
+                    for (int k = 0; k < runs_per_node; ++k) {
+                        const double *o = s_part[wave * runs_per_node + k];
+                        s0 += o[2 * lane]; s1 += o[2 * lane + 1];
+                        q0 += o[128 + 2 * lane]; q1 += o[128 + 2 * lane + 1];
+                        cnt += s_cnt[wave * runs_per_node + k];
+                    }
+                    const double inv = cnt > 0 ? 1.0 / (double)cnt : 0.;
+                    const double v0 = (q0 - s0 * s0 * inv) * inv, v1 = (q1 - s1 * s1 * inv) * inv;
+                    const int arg = wave_argmax(v0, v1, lane);
+                    if (lane == 0) s_axis[wave] = arg;
+                }
+            }
+        }
+        __syncthreads();
+        // 2. keys [ node | coordinate code | position ]
+        for (int i = t; i < np; i += 256) {
+            const int64_t pos = key_pos(s_keys[i], pos_bits);
+            const int node = i / m;
+            uint64_t code;
+            if (pos >= n_real) {
+                code = (1ull << coord_bits) - 1ull;
+            } else {
+                const int c = s_axis[node];
+                const char *row = src.row(bh, pos);
+                if (src.elt == 2) {
+                    uint32_t u = static_cast<const uint16_t *>(static_cast<const void *>(row))[c];
+                    if (u == 0x8000u) u = 0;
+                    code = (u & 0x8000u) ? (~u & 0xffffu) : (u | 0x8000u);
+                } else {
+                    uint32_t u = __float_as_uint(static_cast<const float *>(static_cast<const void *>(row))[c]);
+                    if (u == 0x80000000u) u = 0;
+                    code = (u & 0x80000000u) ? (uint64_t)(~u) : (uint64_t)(u | 0x80000000u);
+                }
+            }
+            s_keys[i] = ((uint64_t)node << (coord_bits + pos_bits)) | (code << pos_bits) | (uint64_t)pos;
+        }
+        __syncthreads();
+        // 3. ascending bitonic sort inside every node (nodes are aligned runs of m = 2^x entries and
+        // the node index leads the key, so sorting the runs sorts the array)
+        for (int k = 2; k <= m; k <<= 1) {
+            for (int j = k >> 1; j > 0; j >>= 1) {
+                for (int i = t; i < np; i += 256) {
+                    const int partner = i ^ j;
+                    if (partner > i) {
+                        const uint64_t a = s_keys[i], b = s_keys[partner];
+                        const bool up = k == m || (i & k) == 0;   // the last merge of every node ascends
+                        if (up ? (a > b) : (a < b)) {
+                            s_keys[i] = b;
+                            s_keys[partner] = a;
+                        }
+                    }
+                }
+                __syncthreads();
+            }
+        }
+    }
+    for (int i = t; i < np; i += 256) keys_out[(int64_t)bh * np + i] = s_keys[i];
+}
+
 int bits_for(int64_t v) {   // bits needed to hold values 0 .. v-1
     int b = 0;
     while (((int64_t)1 << b) < v) ++b;
@@ -262,6 +392,15 @@ hipError_t lvr_tree_order(lvr_index *ix, const void *Ksrc, const int64_t ks[3], 
 
     TreeSrc ksrc{static_cast<const char *>(Ksrc), ks[0], ks[1], ks[2], (int)ix->elt, ix->cfg.n_kv_heads};
     uint64_t *cur = ix->tree_keys_a, *alt = ix->tree_keys_b;
+    if (np <= TREE_WG_MAX && pos_bits + coord_bits + levels <= 64) {
+        // small input (a buffer chunk): the whole tree in one launch
+        hipLaunchKernelGGL(tree_small_kernel, dim3((unsigned)n_bh), dim3(256), 0, st, ksrc, cur, (int)np, n_real, levels,
+                           pos_bits, coord_bits);
+        perm->keys = cur;
+        perm->np = np;
+        perm->pos_bits = pos_bits;
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(tree_init_kernel, dim3((unsigned)((np + 255) / 256), (unsigned)n_bh), dim3(256), 0, st, cur, np);
     for (int L = 0; L < levels; ++L) {
         const int64_t n_nodes = (int64_t)1 << L;
