@@ -71,6 +71,8 @@ def main():
                     help="offloaded mode: K and V in pinned host memory, only the index in HBM")
     ap.add_argument("--separate", action="store_true",
                     help="bound test and exact check as two launches (times the index search apart)")
+    ap.add_argument("--attn-splits", type=int, default=0,
+                    help="lvr_config.attn_splits: 0 = default (64 splits + combine launch), -1 = one workgroup per head, one launch")
     ap.add_argument("--rotate", type=int, default=4,
                     help="replicas of the index cycled through by the cache-cold pass (1 = skip that pass)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -124,6 +126,7 @@ def main():
                         group_size=args.group_size, n_subspaces=args.subspaces, buffer_size=256, capacity=capacity,
                         enclosing=L.LVR_ENCLOSE_AABB if args.enclosing == "aabb" else L.LVR_ENCLOSE_BALL,
                         grouping=L.LVR_GROUP_TREE if args.grouping == "tree" else L.LVR_GROUP_CONTIGUOUS,
+                        attn_splits=args.attn_splits,
                         flags=(L.LVR_CONCURRENT_UPDATE if args.concurrent_update else 0)
                         | (L.LVR_KV_IN_HOST_MEMORY if args.offload else 0)
                         | (L.LVR_SEPARATE_KERNELS if args.separate else 0))
@@ -317,7 +320,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"config{cid}:{c['name']}" + (" [supplementary: keys with positional locality]" if args.keys == "local" else ""), "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
                    "head_dim": d, "context": int(n_now), "kv_storage": "bf16", "group_size": args.group_size,
-                   "subspaces": args.subspaces, "grouping": args.grouping, "enclosing": args.enclosing,
+                   "subspaces": args.subspaces, "attn_splits": args.attn_splits, "grouping": args.grouping, "enclosing": args.enclosing,
                    "step": "append+query+attention" if appending else "query+attention",
                    "update": "two-stream" if args.concurrent_update else "single-stream",
                    "kv_memory": "host (pinned, read in place)" if args.offload else "hbm",

@@ -102,8 +102,9 @@ typedef struct lvr_config {
     int64_t capacity;    /* max keys per (sequence, KV head): the arena is sized once (App. "GPU Update") */
     float scale;         /* sigma; 0 means 1/sqrt(head_dim)  (Sec. 2, "Attention")               */
     int32_t attn_splits; /* P > 0: up to P partial-softmax splits per head, then a combine launch;
-                          * 0: default (64);  -1: one workgroup per head, 16 splits merged in LDS,
-                          * single launch (slower when there are few heads)                    */
+                          * -1: one workgroup per head, 16 splits merged in LDS, a single launch;
+                          * 0: chosen per call: the single launch for batches of 128 heads or more
+                          *    and for contexts up to 65536 keys, else 64 splits + combine      */
     int32_t reservoir_size; /* R <= 256 past keys kept per (sequence, KV head) by reservoir sampling for
                              * lvr_threshold (appendix "Threshold Oracle Comparison"); 0 = none         */
     uint64_t seed;          /* seed of the counter-based generator behind the reservoir              */

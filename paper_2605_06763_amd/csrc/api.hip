@@ -169,6 +169,16 @@ void prof_free(lvr_index *ix) {
     ix->prof_cap = ix->prof_used = ix->prof_on = 0;
 }
 
+// Sparse attention as one launch (a workgroup per head merges its splits in LDS) or as partials plus
+// a combine launch.  One launch wins whenever there are many heads in the batch or few keys per head;
+// with one sequence's 32 heads and several hundred retrieved keys each, 32 workgroups cannot gather
+// fast enough and the two-launch form wins (measured crossover: between 32k and 128k keys of context
+// at 0.5-1 % retrieved).  The set sizes are not known on the host, so the context length stands in.
+inline bool one_launch_attention(const lvr_index *ix) {
+    if (ix->attn_one_launch >= 0) return ix->attn_one_launch != 0;
+    return lvr_n_bhq(ix) >= 128 || ix->n_total <= 65536;
+}
+
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 }  // namespace
@@ -201,7 +211,7 @@ int lvr_create(const lvr_config *cfg, lvr_index **out) {
     ix->max_groups = s.max_groups;
     ix->P = s.P;
     ix->P_dense = s.P_dense;
-    ix->attn_one_launch = cfg->attn_splits < 0;
+    ix->attn_one_launch = cfg->attn_splits < 0 ? 1 : (cfg->attn_splits == 0 ? -1 : 0);   // -1: chosen per call
     ix->elt = cfg->kv_dtype == LVR_BF16 ? 2 : 4;
     ix->sigma = cfg->scale > 0.f ? cfg->scale : 1.0f / sqrtf((float)cfg->head_dim);
     hipError_t e = hipGetDevice(&ix->device);
@@ -479,7 +489,7 @@ int lvr_sparse_attention(lvr_index *ix, const float *q, const int32_t *idx, cons
     if (!ix || !q || !count || !out || cap < 0 || (cap > 0 && !idx)) return LVR_E_INVALID;
     if (!ix->built) return LVR_E_STATE;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (ix->attn_one_launch) {
+    if (one_launch_attention(ix)) {
         Timed t(ix, LVR_K_ATTN_PARTIAL, st);
         LVR_HIP(lvr_launch_sparse_attention_wg(ix, q, idx, count, 1, cap, out, nullptr, st));
         return LVR_OK;
@@ -502,7 +512,7 @@ int lvr_decode_step(lvr_index *ix, const float *q, const float *tau, float *out,
     hipStream_t st = static_cast<hipStream_t>(stream);
     int rc = enqueue_query(ix, q, tau, out_idx, cap, st);
     if (rc != LVR_OK) return rc;
-    if (ix->attn_one_launch) {   // reads the set sizes from the internal counters and hands them to the caller
+    if (one_launch_attention(ix)) {   // reads the set sizes from the internal counters and hands them to the caller
         Timed t(ix, LVR_K_ATTN_PARTIAL, st);
         LVR_HIP(lvr_launch_sparse_attention_wg(ix, q, out_idx, lvr_head_count(ix), LVR_CNT_STRIDE, cap, out, out_count, st));
         ix->counters_dirty = 0;
