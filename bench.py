@@ -3,8 +3,8 @@
 
 One step = one pass of the per-step hot path over one batch of synthetic input: range query
 (bound pruning + exact filter) followed by sparse attention over the retrieved keys, through
-the C ABI (lvr_decode_step).  For the append workload (config 5) a step also appends the
-step's new key/value first.  Inputs (K, V, all queries, all thresholds) are resident in HBM
+the C ABI (lvr_decode_step).  For the append workload (config 5) a step first appends the
+step's new key/value (lvr_append_decode_step: both in one call).  Inputs (K, V, all queries, all thresholds) are resident in HBM
 before the timed region starts.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config {2,3,4,5}]
@@ -179,8 +179,9 @@ def main():
 
     def one_step(t):
         if appending:
-            L.lvr_append(h, k_args[t], v_args[t], st_arg)
-            L.lvr_decode_step(h, q_args[t % n_distinct], tau_args[t], out_a, idx_a, cnt_a, st_arg)
+            # the step's token joins the cache, then the query is answered: one call
+            L.lvr_append_decode_step(h, k_args[t], v_args[t], q_args[t % n_distinct], tau_args[t], out_a, idx_a, cnt_a,
+                                     st_arg)
         else:
             L.lvr_decode_step(h, q_args[t % n_distinct], tau_args[t % n_distinct], out_a, idx_a, cnt_a, st_arg)
 

@@ -191,6 +191,15 @@ int lvr_sparse_attention(lvr_index *ix, const float *q_dev, const int32_t *idx_d
 int lvr_decode_step(lvr_index *ix, const float *q_dev, const float *tau_dev, float *out_dev,
                     int32_t *out_idx_dev, int32_t *out_count_dev, int64_t cap, void *stream);
 
+/* lvr_append of m tokens followed by lvr_decode_step, as one call (Sec. 4.3 followed by Sec. 4.2:
+ * the token generated by the previous step joins the cache, then the next query is answered).
+ * Same results as the two calls.  When the append only has to store rows (no buffer chunk becomes
+ * full, contiguous grouping, no reservoir) the store rides in the query launch, which saves a
+ * launch per decode step; otherwise the two calls run one after the other. */
+int lvr_append_decode_step(lvr_index *ix, const void *k_new_dev, const void *v_new_dev, int64_t m, const float *q_dev,
+                           const float *tau_dev, float *out_dev, int32_t *out_idx_dev, int32_t *out_count_dev,
+                           int64_t cap, void *stream);
+
 /* Built-in threshold selection (appendix "Threshold Oracle Comparison"): tau per query head from
  * the dot products of q with the reservoir of past keys of its KV head.
  *   SAMPLE_MAX       largest reservoir score

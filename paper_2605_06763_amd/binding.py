@@ -57,7 +57,7 @@ EXPORTS = [
     "lvr_create", "lvr_destroy", "lvr_arena_bytes", "lvr_build", "lvr_append", "lvr_query",
     "lvr_sparse_attention", "lvr_decode_step", "lvr_dense_attention", "lvr_get_stats",
     "lvr_export_index", "lvr_length", "lvr_strerror", "lvr_last_hip_error",
-    "lvr_profile_enable", "lvr_profile_read", "lvr_threshold", "lvr_export_reservoir", "lvr_publish", "lvr_query1", "lvr_host_bytes",
+    "lvr_profile_enable", "lvr_profile_read", "lvr_threshold", "lvr_export_reservoir", "lvr_publish", "lvr_query1", "lvr_append_decode_step", "lvr_host_bytes",
 ]
 
 _lib = None
@@ -98,6 +98,7 @@ def lib():
     L.lvr_profile_enable.argtypes = [vp, C.c_int]
     L.lvr_profile_read.argtypes = [vp, C.POINTER(lvr_profile)]
     L.lvr_publish.argtypes = [vp, vp]
+    L.lvr_append_decode_step.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp, i64, vp]
     L.lvr_host_bytes.argtypes = [C.POINTER(lvr_config)]
     L.lvr_host_bytes.restype = C.c_size_t
     L.lvr_query1.argtypes = [vp, vp, vp, vp, vp, vp, i64, vp]
@@ -229,6 +230,15 @@ def lvr_decode_step(h, q, tau, out, out_idx, out_count, stream=None) -> None:
                                  _dev(out, torch.float32, "out"), _dev(out_idx, torch.int32, "out_idx"),
                                  _dev(out_count, torch.int32, "out_count"), cap, _stream(stream)),
            "lvr_decode_step")
+
+
+def lvr_append_decode_step(h, k_new, v_new, q, tau, out, out_idx, out_count, stream=None) -> None:
+    cap = out_idx.shape[-1]
+    _check(lib().lvr_append_decode_step(h, _dev(k_new, name="k_new"), _dev(v_new, name="v_new"), k_new.shape[2],
+                                        _dev(q, torch.float32, "q"), _dev(tau, torch.float32, "tau"),
+                                        _dev(out, torch.float32, "out"), _dev(out_idx, torch.int32, "out_idx"),
+                                        _dev(out_count, torch.int32, "out_count"), cap, _stream(stream)),
+           "lvr_append_decode_step")
 
 
 def lvr_dense_attention(h, q, out, stream=None) -> None:

@@ -423,7 +423,8 @@ namespace {
 
 // bound test + exact filter; leaves the set sizes in the internal per-head counters
 int enqueue_query(lvr_index *ix, const float *q, const float *tau, int32_t *out_idx, int64_t cap, hipStream_t st,
-                  const float *tau_s = nullptr) {
+                  const float *tau_s = nullptr, const void *k_new = nullptr, const void *v_new = nullptr,
+                  int64_t m_new = 0) {
     const bool fused = ix->cfg.kv_dtype == LVR_BF16 && !(ix->cfg.flags & LVR_SEPARATE_KERNELS);
     if (ix->counters_dirty) {   // an earlier query never published its counts: start from zero again
         Timed t(ix, LVR_K_RESET, st);
@@ -432,7 +433,8 @@ int enqueue_query(lvr_index *ix, const float *q, const float *tau, int32_t *out_
     ix->counters_dirty = 1;
     if (fused) {
         Timed t(ix, LVR_K_FILTER, st);
-        LVR_HIP(lvr_launch_query_fused(ix, q, tau, tau_s, out_idx, cap, st));
+        LVR_HIP(lvr_launch_query_fused(ix, q, tau, tau_s, out_idx, cap, st, k_new, v_new, m_new));
+        ix->n_total += m_new;
     } else {
         if (ix->n_indexed > 0) {
             Timed t(ix, LVR_K_PRUNE, st);
@@ -445,6 +447,29 @@ int enqueue_query(lvr_index *ix, const float *q, const float *tau, int32_t *out_
     }
     ix->last_buffer_rows = ix->n_total - ix->n_indexed;
     ix->last_indexed = ix->n_indexed;
+    return LVR_OK;
+}
+
+// query + attention; with k_new the query launch also appends m_new rows (see lvr_append_decode_step)
+int decode_step_impl(lvr_index *ix, const float *q, const float *tau, float *out, int32_t *out_idx, int32_t *out_count,
+                     int64_t cap, hipStream_t st, const void *k_new, const void *v_new, int64_t m_new) {
+    int rc = enqueue_query(ix, q, tau, out_idx, cap, st, nullptr, k_new, v_new, m_new);
+    if (rc != LVR_OK) return rc;
+    if (one_launch_attention(ix)) {   // reads the set sizes from the internal counters and hands them to the caller
+        Timed t(ix, LVR_K_ATTN_PARTIAL, st);
+        LVR_HIP(lvr_launch_sparse_attention_wg(ix, q, out_idx, lvr_head_count(ix), LVR_CNT_STRIDE, cap, out, out_count, st));
+        ix->counters_dirty = 0;
+        return LVR_OK;
+    }
+    {   // the attention reads the set sizes straight from the internal counters ...
+        Timed t(ix, LVR_K_ATTN_PARTIAL, st);
+        LVR_HIP(lvr_launch_sparse_partial(ix, q, out_idx, lvr_head_count(ix), LVR_CNT_STRIDE, cap, st));
+    }
+    {   // ... and the combine pass hands them to the caller
+        Timed t(ix, LVR_K_ATTN_COMBINE, st);
+        LVR_HIP(lvr_launch_combine(ix, out, ix->P, lvr_head_count(ix), LVR_CNT_STRIDE, cap, out_count, st));
+    }
+    ix->counters_dirty = 0;
     return LVR_OK;
 }
 
@@ -509,25 +534,29 @@ int lvr_decode_step(lvr_index *ix, const float *q, const float *tau, float *out,
                     int64_t cap, void *stream) {
     if (!ix || !q || !tau || !out || !out_count || cap < 0 || (cap > 0 && !out_idx)) return LVR_E_INVALID;
     if (!ix->built) return LVR_E_STATE;
+    return decode_step_impl(ix, q, tau, out, out_idx, out_count, cap, static_cast<hipStream_t>(stream), nullptr, nullptr, 0);
+}
+
+int lvr_append_decode_step(lvr_index *ix, const void *k_new, const void *v_new, int64_t m, const float *q,
+                           const float *tau, float *out, int32_t *out_idx, int32_t *out_count, int64_t cap,
+                           void *stream) {
+    if (!ix || !q || !tau || !out || !out_count || cap < 0 || (cap > 0 && !out_idx)) return LVR_E_INVALID;
+    if (m < 0 || (m > 0 && (!k_new || !v_new))) return LVR_E_INVALID;
+    if (!ix->built) return LVR_E_STATE;
+    if (ix->n_total + m > ix->cfg.capacity) return LVR_E_CAPACITY;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    int rc = enqueue_query(ix, q, tau, out_idx, cap, st);
-    if (rc != LVR_OK) return rc;
-    if (one_launch_attention(ix)) {   // reads the set sizes from the internal counters and hands them to the caller
-        Timed t(ix, LVR_K_ATTN_PARTIAL, st);
-        LVR_HIP(lvr_launch_sparse_attention_wg(ix, q, out_idx, lvr_head_count(ix), LVR_CNT_STRIDE, cap, out, out_count, st));
-        ix->counters_dirty = 0;
-        return LVR_OK;
+    // The copy rides in the query launch when that launch has a buffer workgroup to do it and the
+    // append needs nothing else (no chunk becomes full, no position maps, no reservoir, no update in
+    // flight); otherwise the two calls run one after the other.
+    const bool rides = m > 0 && m <= 64 && ix->cfg.kv_dtype == LVR_BF16 && !(ix->cfg.flags & LVR_SEPARATE_KERNELS) &&
+                       !ix->slot_pos && !ix->reservoir && !ix->pending && aligned16(k_new) && aligned16(v_new) &&
+                       ix->n_total + m - ix->n_indexed < ix->cfg.buffer_size;
+    if (!rides) {
+        int rc = lvr_append(ix, k_new, v_new, m, stream);
+        if (rc != LVR_OK) return rc;
+        return decode_step_impl(ix, q, tau, out, out_idx, out_count, cap, st, nullptr, nullptr, 0);
     }
-    {   // the attention reads the set sizes straight from the internal counters ...
-        Timed t(ix, LVR_K_ATTN_PARTIAL, st);
-        LVR_HIP(lvr_launch_sparse_partial(ix, q, out_idx, lvr_head_count(ix), LVR_CNT_STRIDE, cap, st));
-    }
-    {   // ... and the combine pass hands them to the caller
-        Timed t(ix, LVR_K_ATTN_COMBINE, st);
-        LVR_HIP(lvr_launch_combine(ix, out, ix->P, lvr_head_count(ix), LVR_CNT_STRIDE, cap, out_count, st));
-    }
-    ix->counters_dirty = 0;
-    return LVR_OK;
+    return decode_step_impl(ix, q, tau, out, out_idx, out_count, cap, st, k_new, v_new, m);
 }
 
 int lvr_threshold(lvr_index *ix, const float *q, int mode, float param, float *tau_out, void *stream) {

@@ -113,8 +113,9 @@ hipError_t lvr_launch_prune(lvr_index *ix, const float *q, const float *tau, hip
 hipError_t lvr_launch_filter(lvr_index *ix, const float *q, const float *tau, int32_t *out_idx, int64_t cap,
                              hipStream_t st);
 // bf16 caches: bound test + exact check in one launch (per-head counters must be zero on entry)
-hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *tau, const float *tau_s, int32_t *out_idx, int64_t cap,
-                                  hipStream_t st);
+hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *tau, const float *tau_s, int32_t *out_idx,
+                                  int64_t cap, hipStream_t st, const void *k_new = nullptr, const void *v_new = nullptr,
+                                  int64_t m_new = 0);
 // internal per-head counters -> caller's array and the statistics copy; clears the counters
 hipError_t lvr_launch_publish_counts(lvr_index *ix, int32_t *out_count, hipStream_t st);
 // partial softmax per (head, split); count is read with the given stride (1 = caller's array)

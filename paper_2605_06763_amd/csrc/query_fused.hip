@@ -34,6 +34,9 @@ struct FusedArgs {
     const float *q;
     const float *tau;
     const float *tau_s;      // Query 1: [batch][H_q][S] per-block thresholds; NULL: Query 2
+    const void *k_new, *v_new;   // rows appended by this launch ([batch][H_kv][m_new][d]), or NULL
+    void *V;
+    int m_new;               // n_total already counts them
     int32_t *seg_count;      // survivors per segment, for statistics only
     lvr_emit_target emit;
     int64_t n_groups, max_groups, max_segs, cap_rows, n_indexed, n_total;
@@ -243,6 +246,22 @@ query_fused_kernel(const FusedArgs a) {
     } else {
         rows = a.n_total - a.n_indexed;
         buf_row0 = a.n_indexed;
+        if (a.m_new > 0) {
+            // append fused into the step (Sec. 4.3): this workgroup owns the buffer of its (sequence, KV
+            // head), so it stores the new K and V rows at the arena tail before it scans the buffer;
+            // the attention launch that follows finds the V rows in place
+            const int64_t pieces = (int64_t)a.m_new * 16;   // 16-byte pieces per matrix
+            const uint4 *ks = static_cast<const uint4 *>(a.k_new) + (int64_t)bh * pieces;
+            const uint4 *vs = static_cast<const uint4 *>(a.v_new) + (int64_t)bh * pieces;
+            const int64_t row0 = (int64_t)bh * a.cap_rows + (a.n_total - a.m_new);
+            uint4 *kd = static_cast<uint4 *>(const_cast<void *>(a.K)) + row0 * 16;
+            uint4 *vd = static_cast<uint4 *>(a.V) + row0 * 16;
+            for (int64_t i = threadIdx.x; i < 2 * pieces; i += 256) {
+                if (i < pieces) kd[i] = ks[i];
+                else vd[i - pieces] = vs[i - pieces];
+            }
+            __syncthreads();
+        }
     }
 
     // ---------------- phase B: exact check of the surviving rows ----------------
@@ -309,11 +328,16 @@ void launch_s(dim3 grid, hipStream_t st, const FusedArgs &a, int S) {
 }  // namespace
 
 hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *tau, const float *tau_s,
-                                  int32_t *out_idx, int64_t cap, hipStream_t st) {
+                                  int32_t *out_idx, int64_t cap, hipStream_t st, const void *k_new, const void *v_new,
+                                  int64_t m_new) {
     if (ix->cfg.kv_dtype != LVR_BF16) return hipErrorInvalidValue;
     if (tau_s && (ix->box || ix->cfg.n_subspaces > 4)) return hipErrorInvalidValue;
     FusedArgs a;
     a.tau_s = tau_s;
+    a.k_new = k_new;
+    a.v_new = v_new;
+    a.V = ix->V;
+    a.m_new = (int)m_new;
     a.centres = ix->centres;
     a.radii = ix->radii;
     a.K = ix->K;
@@ -330,7 +354,7 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
     a.max_segs = lvr_max_segs(ix->max_groups);
     a.cap_rows = ix->cap_rows;
     a.n_indexed = ix->n_indexed;
-    a.n_total = ix->n_total;
+    a.n_total = ix->n_total + m_new;
     a.log2r = 0;
     while ((1 << a.log2r) < ix->cfg.group_size) ++a.log2r;
     a.n_q_heads = ix->cfg.n_q_heads;
@@ -350,7 +374,7 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
     a.tiles_per_wave = tpw;
     const int seg_groups = tpw * 64;
     a.n_segs = (int)((a.n_groups + seg_groups - 1) / seg_groups);
-    const int has_buffer = ix->n_total > ix->n_indexed ? 1 : 0;
+    const int has_buffer = a.n_total > ix->n_indexed ? 1 : 0;
     ix->seg_groups = seg_groups;
     ix->n_segs = a.n_segs;
     if (a.n_segs + has_buffer == 0) return hipSuccess;

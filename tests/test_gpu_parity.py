@@ -876,3 +876,54 @@ def test_offloaded_kv_same_results(G, oracle, grouping, flags):
         L.lvr_publish(ref.h)
         for name, x, y in zip(("centres", "radii", "slot_pos", "keys"), ix.export(), ref.export()):
             assert np.array_equal(np.asarray(x), np.asarray(y)), name
+
+
+# ---------------------------------------------------------------------------------------------
+# Append + decode step in one call (the store of the new rows rides in the query launch)
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("variant", ["plain", "tree", "reservoir", "buffer_dense", "m3"])
+def test_append_decode_step_equals_the_two_calls(G, oracle, variant):
+    L = G.L
+    n0, steps, B = 203, 120, 32
+    m = 3 if variant == "m3" else 1
+    kw = dict(capacity=n0 + steps * m, buffer_size=B)
+    if variant == "tree":
+        kw["grouping"] = L.LVR_GROUP_TREE
+    if variant == "reservoir":
+        kw.update(reservoir_size=64, seed=9)
+    if variant == "buffer_dense":
+        kw["flags"] = L.LVR_ATTEND_BUFFER_DENSE
+    cache = _small_cache(5, n0)
+    k_new, v_new = W.make_append_stream(5, steps * m, cache)          # [T][batch][hkv][d]
+    qs = W.drift_queries(5, steps, n_q_heads=8)
+    G.say(f"append+decode variant={variant}")
+    with G.Index(cache.K, cache.V, "bf16", 8, **kw) as ix, G.Index(cache.K, cache.V, "bf16", 8, **kw) as ref:
+        cap = n0 + steps * m
+        out = torch.zeros((1, 8, 128), device="cuda")
+        idx = torch.zeros((1, 8, cap), dtype=torch.int32, device="cuda")
+        cnt = torch.zeros((1, 8), dtype=torch.int32, device="cuda")
+        for t in range(steps):
+            kk = np.ascontiguousarray(k_new[t * m:(t + 1) * m].transpose(1, 2, 0, 3))
+            vv = np.ascontiguousarray(v_new[t * m:(t + 1) * m].transpose(1, 2, 0, 3))
+            ref.append(kk, vv)
+            ix.K, ix.V = ref.K, ref.V                                   # host copies for the oracle
+            tau = G.oracle_taus(oracle, ref, qs[t], frac=0.05)
+            qd = torch.from_numpy(qs[t]).cuda()
+            td = torch.from_numpy(tau).cuda()
+            L.lvr_append_decode_step(ix.h, G.to_device(kk, "bf16"), G.to_device(vv, "bf16"), qd, td, out, idx, cnt)
+            torch.cuda.synchronize()
+            assert L.lvr_length(ix.h) == L.lvr_length(ref.h)
+            gi, gc, go = idx.cpu().numpy(), cnt.cpu().numpy(), out.cpu().numpy()
+            ri, rc, ro = ref.query(qs[t], tau, cap=cap, fused=True)
+            assert np.array_equal(gc, rc)
+            for h in range(8):
+                assert set(gi[0, h, :gc[0, h]].tolist()) == set(ri[0, h, :rc[0, h]].tolist()), (t, h)
+            assert np.abs(go - ro).max() <= 1e-5 * max(1.0, np.abs(ro).max())
+            if t % 13 == 0 or t == steps - 1:
+                n_indexed = L.lvr_length(ix.h)[1]
+                G.check_step(oracle, ix, qs[t], tau, gi, gc, go, tag=f"append+decode {variant} t={t}",
+                             extra_from=(n_indexed if variant == "buffer_dense" else -1))
+        for name, x, y in zip(("centres", "radii", "slot_pos", "keys"), ix.export(), ref.export()):
+            assert np.array_equal(np.asarray(x), np.asarray(y)), name
+        if variant == "reservoir":
+            assert np.array_equal(ix.reservoir(), ref.reservoir())
