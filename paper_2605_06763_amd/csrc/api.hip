@@ -50,7 +50,7 @@ int check_config(const lvr_config *c) {
 struct Sizes {
     int64_t cap_rows, max_groups;
     int P, P_dense, Pmax;
-    size_t kv, centres, radii, list, counters, part_ml, part_o, total;
+    size_t kv, centres, radii, list, counters, part_ml, part_o, scores, total;
     // tree grouping only
     int64_t tree_keys;
     size_t maps, tree_keybytes, tree_axis, tree_partial, tree_temp, chunk;
@@ -75,8 +75,10 @@ Sizes sizes_of(const lvr_config *c) {
     s.counters = al(lvr_counter_ints((int)n_bh, (int)n_bhq, s.max_groups) * sizeof(int32_t));
     s.part_ml = al((size_t)n_bhq * s.Pmax * 2 * sizeof(float));
     s.part_o = al((size_t)n_bhq * s.Pmax * LVR_D * sizeof(float));
+    const bool fused_path = c->kv_dtype == LVR_BF16 && !(c->flags & LVR_SEPARATE_KERNELS);
+    s.scores = fused_path ? al((size_t)n_bhq * s.cap_rows * sizeof(float)) : 0;
     const bool kv_on_host = (c->flags & LVR_KV_IN_HOST_MEMORY) != 0;
-    s.total = (kv_on_host ? 0 : 2 * s.kv) + s.centres + s.radii + s.list + s.counters + s.part_ml + s.part_o;
+    s.total = s.scores + (kv_on_host ? 0 : 2 * s.kv) + s.centres + s.radii + s.list + s.counters + s.part_ml + s.part_o;
     s.tree_keys = 0;
     s.maps = s.tree_keybytes = s.tree_axis = s.tree_partial = s.tree_temp = s.chunk = 0;
     if (c->grouping == LVR_GROUP_TREE) {
@@ -103,7 +105,7 @@ void free_all(lvr_index *ix) {
     }
     void *ptrs[] = {ix->K, ix->V, ix->centres, ix->radii, ix->slot_pos, ix->pos_slot,
                     ix->surv_list, ix->counters, ix->part_ml, ix->part_o, ix->tree_keys_a, ix->tree_keys_b,
-                    ix->tree_axis, ix->tree_partial, ix->tree_temp, ix->chunk_K, ix->chunk_V, ix->reservoir};
+                    ix->tree_axis, ix->tree_partial, ix->tree_temp, ix->chunk_K, ix->chunk_V, ix->reservoir, ix->scores};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     if (ix->ev_fork) (void)hipEventDestroy(ix->ev_fork);
@@ -226,7 +228,7 @@ int lvr_create(const lvr_config *cfg, lvr_index **out) {
     struct { void **p; size_t bytes; } allocs[] = {
         {&ix->K, kv_on_host ? 0 : s.kv}, {&ix->V, kv_on_host ? 0 : s.kv}, {&ix->centres, s.centres}, {(void **)&ix->radii, s.radii},
         {(void **)&ix->surv_list, s.list}, {(void **)&ix->counters, s.counters},
-        {(void **)&ix->part_ml, s.part_ml}, {(void **)&ix->part_o, s.part_o}};
+        {(void **)&ix->part_ml, s.part_ml}, {(void **)&ix->part_o, s.part_o}, {(void **)&ix->scores, s.scores}};
     for (auto &a : allocs) {
         if (e != hipSuccess) break;
         if (a.bytes) e = hipMalloc(a.p, a.bytes);
@@ -455,15 +457,24 @@ int decode_step_impl(lvr_index *ix, const float *q, const float *tau, float *out
                      int64_t cap, hipStream_t st, const void *k_new, const void *v_new, int64_t m_new) {
     int rc = enqueue_query(ix, q, tau, out_idx, cap, st, nullptr, k_new, v_new, m_new);
     if (rc != LVR_OK) return rc;
+    // The fused query kernel leaves the raw score of every emitted key beside its position; an
+    // attention that uses it gathers V rows only.  That halves the attention's traffic, but the query
+    // launch that FOLLOWS such an attention was measured ~3 us slower at 128k keys (it no longer finds
+    // the retrieved K rows' pages and lines touched just before it), which is more than the
+    // partials-plus-combine form gains; so the scores are used by the one-launch form and whenever
+    // K and V sit behind the host link.
+    const bool fused = ix->cfg.kv_dtype == LVR_BF16 && !(ix->cfg.flags & LVR_SEPARATE_KERNELS);
+    const bool use_scores = fused && (one_launch_attention(ix) || (ix->cfg.flags & LVR_KV_IN_HOST_MEMORY));
+    const float *carried = use_scores ? ix->scores : nullptr;
     if (one_launch_attention(ix)) {   // reads the set sizes from the internal counters and hands them to the caller
         Timed t(ix, LVR_K_ATTN_PARTIAL, st);
-        LVR_HIP(lvr_launch_sparse_attention_wg(ix, q, out_idx, lvr_head_count(ix), LVR_CNT_STRIDE, cap, out, out_count, st));
+        LVR_HIP(lvr_launch_sparse_attention_wg(ix, q, out_idx, carried, lvr_head_count(ix), LVR_CNT_STRIDE, cap, out, out_count, st));
         ix->counters_dirty = 0;
         return LVR_OK;
     }
     {   // the attention reads the set sizes straight from the internal counters ...
         Timed t(ix, LVR_K_ATTN_PARTIAL, st);
-        LVR_HIP(lvr_launch_sparse_partial(ix, q, out_idx, lvr_head_count(ix), LVR_CNT_STRIDE, cap, st));
+        LVR_HIP(lvr_launch_sparse_partial(ix, q, out_idx, carried, lvr_head_count(ix), LVR_CNT_STRIDE, cap, st));
     }
     {   // ... and the combine pass hands them to the caller
         Timed t(ix, LVR_K_ATTN_COMBINE, st);
@@ -516,12 +527,12 @@ int lvr_sparse_attention(lvr_index *ix, const float *q, const int32_t *idx, cons
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (one_launch_attention(ix)) {
         Timed t(ix, LVR_K_ATTN_PARTIAL, st);
-        LVR_HIP(lvr_launch_sparse_attention_wg(ix, q, idx, count, 1, cap, out, nullptr, st));
+        LVR_HIP(lvr_launch_sparse_attention_wg(ix, q, idx, nullptr, count, 1, cap, out, nullptr, st));
         return LVR_OK;
     }
     {
         Timed t(ix, LVR_K_ATTN_PARTIAL, st);
-        LVR_HIP(lvr_launch_sparse_partial(ix, q, idx, count, 1, cap, st));
+        LVR_HIP(lvr_launch_sparse_partial(ix, q, idx, nullptr, count, 1, cap, st));
     }
     {
         Timed t(ix, LVR_K_ATTN_COMBINE, st);

@@ -35,10 +35,13 @@ __device__ __forceinline__ int64_t split_length(int64_t cnt, int P_max, int *use
 // partials are merged by combine_kernel in a launch of its own: making them visible to a
 // "last wave" inside this launch would take a device-scope fence per wave, which costs more
 // on this multi-die part than the extra launch does.
-template <typename KT>
+// CARRY: the raw scores of the listed keys are given (written by the query kernel that made the
+// list), so only V rows are gathered.
+template <typename KT, bool CARRY>
 __global__ void __launch_bounds__(64)
 sparse_attention_kernel(const void *__restrict__ K, const void *__restrict__ V, const int32_t *__restrict__ pos_slot,
                         const float *__restrict__ q, const int32_t *__restrict__ idx,
+                        const float *__restrict__ scores, int64_t score_stride,
                         const int32_t *__restrict__ count, int count_stride, int64_t cap,
                         float *__restrict__ part_ml, float *__restrict__ part_o, int64_t cap_rows, int64_t n_total,
                         int P, int n_q_heads, int n_kv_heads, int G, float qscale) {
@@ -54,6 +57,9 @@ sparse_attention_kernel(const void *__restrict__ K, const void *__restrict__ V, 
     // speculative load of the positions that goes out together with the count.
     const int64_t e_spec = (int64_t)p * 16 + lane;
     const int32_t pos_spec = (lane < 16 && e_spec < cap) ? my_idx[e_spec] : -1;
+    const float *my_sc = CARRY ? scores + hq * score_stride : nullptr;
+    float sc_spec = 0.f;
+    if constexpr (CARRY) sc_spec = (lane < 16 && e_spec < cap && e_spec < score_stride) ? my_sc[e_spec] : 0.f;
     int64_t cnt = count[hq * count_stride];
     if (cnt > cap) cnt = cap;
     if (cnt < 0) cnt = 0;
@@ -79,31 +85,41 @@ sparse_attention_kernel(const void *__restrict__ K, const void *__restrict__ V, 
         // positions of up to 64 entries, validated and mapped to arena rows once
         int64_t e = c0 + lane;
         int myslot = -1;
+        float myscore = 0.f;
         if (e < end) {
             const int64_t pos = (L == 16) ? (int64_t)pos_spec : (int64_t)my_idx[e];
+            if constexpr (CARRY) myscore = ((L == 16) ? sc_spec : my_sc[e]) * qscale;
             if (pos >= 0 && pos < n_total) myslot = pslot ? pslot[pos] : (int)pos;
         }
         const int chunk = (int)((end - c0 < 64) ? end - c0 : 64);
         for (int b0 = 0; b0 < chunk; b0 += 16) {
-            lvr_raw8<KT> kr[4], vr[4];
+            lvr_raw8<KT> kr[CARRY ? 1 : 4], vr[4];
             int slot[4];
+            float given[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 slot[i] = __shfl(myslot, (b0 + i * 4 + sub) & 63, 64);
+                if constexpr (CARRY) given[i] = __shfl(myscore, (b0 + i * 4 + sub) & 63, 64);
                 if (b0 + i * 4 + sub >= chunk) slot[i] = -1;
                 const int64_t sl = slot[i] < 0 ? 0 : slot[i];
-                lvr_load_raw(Kb, sl, li, kr[i]);
+                if constexpr (!CARRY) lvr_load_raw(Kb, sl, li, kr[i]);
                 lvr_load_raw(Vb, sl, li, vr[i]);
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                float kx[8], vx[8];
-                lvr_unpack(kr[i], kx);
+                float vx[8];
                 lvr_unpack(vr[i], vx);
-                float d = 0.f;
+                float s;
+                if constexpr (CARRY) {
+                    s = given[i];
+                } else {
+                    float kx[8];
+                    lvr_unpack(kr[i], kx);
+                    float d = 0.f;
 #pragma unroll
-                for (int c = 0; c < 8; ++c) d += qv[c] * kx[c];
-                float s = lvr_row16_sum(d);
+                    for (int c = 0; c < 8; ++c) d += qv[c] * kx[c];
+                    s = lvr_row16_sum(d);
+                }
                 s = (slot[i] >= 0) ? s : -INFINITY;
                 const float m_new = fmaxf(m, s);
                 const float alpha = exp2_safe(m, m_new);
@@ -145,11 +161,12 @@ sparse_attention_kernel(const void *__restrict__ K, const void *__restrict__ V, 
 // then the 16 partial triples are merged through LDS, so no partials travel through HBM and no
 // combine launch follows.  Thread 0 also publishes (and clears) the head's internal counter
 // when asked to.
-template <typename KT>
+template <typename KT, bool CARRY>
 __global__ void __launch_bounds__(1024)
 sparse_attention_wg_kernel(const void *__restrict__ K, const void *__restrict__ V,
                            const int32_t *__restrict__ pos_slot, const float *__restrict__ q,
-                           const int32_t *__restrict__ idx, const int32_t *__restrict__ count, int count_stride,
+                           const int32_t *__restrict__ idx, const float *__restrict__ scores, int64_t score_stride,
+                           const int32_t *__restrict__ count, int count_stride,
                            int64_t cap, float *__restrict__ out, int64_t cap_rows, int64_t n_total, int n_q_heads,
                            int n_kv_heads, int G, float qscale, int32_t *__restrict__ head_count,
                            int32_t *__restrict__ head_stat, int32_t *__restrict__ publish_count) {
@@ -185,31 +202,41 @@ sparse_attention_wg_kernel(const void *__restrict__ K, const void *__restrict__ 
     for (int64_t c0 = start; c0 < end; c0 += 64) {          // uniform over the wave
         int64_t e = c0 + lane;
         int myslot = -1;
+        float myscore = 0.f;
         if (e < end) {
             const int64_t pos = my_idx[e];
+            if constexpr (CARRY) myscore = (e < score_stride ? scores[hq * score_stride + e] : 0.f) * qscale;
             if (pos >= 0 && pos < n_total) myslot = pslot ? pslot[pos] : (int)pos;
         }
         const int chunk = (int)((end - c0 < 64) ? end - c0 : 64);
         for (int b0 = 0; b0 < chunk; b0 += 16) {
-            lvr_raw8<KT> kr[4], vr[4];
+            lvr_raw8<KT> kr[CARRY ? 1 : 4], vr[4];
             int slot[4];
+            float given[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 slot[i] = __shfl(myslot, (b0 + i * 4 + sub) & 63, 64);
+                if constexpr (CARRY) given[i] = __shfl(myscore, (b0 + i * 4 + sub) & 63, 64);
                 if (b0 + i * 4 + sub >= chunk) slot[i] = -1;
                 const int64_t sl = slot[i] < 0 ? 0 : slot[i];
-                lvr_load_raw(Kb, sl, li, kr[i]);
+                if constexpr (!CARRY) lvr_load_raw(Kb, sl, li, kr[i]);
                 lvr_load_raw(Vb, sl, li, vr[i]);
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                float kx[8], vx[8];
-                lvr_unpack(kr[i], kx);
+                float vx[8];
                 lvr_unpack(vr[i], vx);
-                float d = 0.f;
+                float s;
+                if constexpr (CARRY) {
+                    s = given[i];
+                } else {
+                    float kx[8];
+                    lvr_unpack(kr[i], kx);
+                    float d = 0.f;
 #pragma unroll
-                for (int c = 0; c < 8; ++c) d += qv[c] * kx[c];
-                float s = lvr_row16_sum(d);
+                    for (int c = 0; c < 8; ++c) d += qv[c] * kx[c];
+                    s = lvr_row16_sum(d);
+                }
                 s = (slot[i] >= 0) ? s : -INFINITY;
                 const float m_new = fmaxf(m, s);
                 const float alpha = exp2_safe(m, m_new);
@@ -598,38 +625,45 @@ hipError_t launch_dense_t(lvr_index *ix, const float *q, float *out, int P, hipS
 
 }  // namespace
 
-hipError_t lvr_launch_sparse_attention_wg(lvr_index *ix, const float *q, const int32_t *idx, const int32_t *count,
-                                          int count_stride, int64_t cap, float *out, int32_t *publish_count,
-                                          hipStream_t st) {
+hipError_t lvr_launch_sparse_attention_wg(lvr_index *ix, const float *q, const int32_t *idx, const float *scores,
+                                          const int32_t *count, int count_stride, int64_t cap, float *out,
+                                          int32_t *publish_count, hipStream_t st) {
     const int n_bhq = lvr_n_bhq(ix);
     const float qscale = ix->sigma * LOG2E;
-    if (ix->cfg.kv_dtype == LVR_BF16)
-        hipLaunchKernelGGL(sparse_attention_wg_kernel<lvr_bf16_t>, dim3((unsigned)n_bhq), dim3(1024), 0, st, ix->K, ix->V,
-                           ix->pos_slot, q, idx, count, count_stride, cap, out, ix->cap_rows, ix->n_total,
-                           ix->cfg.n_q_heads, ix->cfg.n_kv_heads, ix->G, qscale, lvr_head_count(ix), lvr_head_stat(ix),
-                           publish_count);
-    else
-        hipLaunchKernelGGL(sparse_attention_wg_kernel<lvr_f32_t>, dim3((unsigned)n_bhq), dim3(1024), 0, st, ix->K, ix->V,
-                           ix->pos_slot, q, idx, count, count_stride, cap, out, ix->cap_rows, ix->n_total,
-                           ix->cfg.n_q_heads, ix->cfg.n_kv_heads, ix->G, qscale, lvr_head_count(ix), lvr_head_stat(ix),
-                           publish_count);
+#define LVR_WG_LAUNCH(KT, CARRY)                                                                                         \
+    hipLaunchKernelGGL((sparse_attention_wg_kernel<KT, CARRY>), dim3((unsigned)n_bhq), dim3(1024), 0, st, ix->K, ix->V,  \
+                       ix->pos_slot, q, idx, scores, ix->cap_rows, count, count_stride, cap, out, ix->cap_rows,          \
+                       ix->n_total, ix->cfg.n_q_heads, ix->cfg.n_kv_heads, ix->G, qscale, lvr_head_count(ix),            \
+                       lvr_head_stat(ix), publish_count)
+    if (ix->cfg.kv_dtype == LVR_BF16) {
+        if (scores) LVR_WG_LAUNCH(lvr_bf16_t, true);
+        else LVR_WG_LAUNCH(lvr_bf16_t, false);
+    } else {
+        if (scores) LVR_WG_LAUNCH(lvr_f32_t, true);
+        else LVR_WG_LAUNCH(lvr_f32_t, false);
+    }
+#undef LVR_WG_LAUNCH
     return hipGetLastError();
 }
 
-hipError_t lvr_launch_sparse_partial(lvr_index *ix, const float *q, const int32_t *idx, const int32_t *count,
-                                     int count_stride, int64_t cap, hipStream_t st) {
+hipError_t lvr_launch_sparse_partial(lvr_index *ix, const float *q, const int32_t *idx, const float *scores,
+                                     const int32_t *count, int count_stride, int64_t cap, hipStream_t st) {
     const int n_bhq = lvr_n_bhq(ix);
     const int P = ix->P;
     dim3 grid((unsigned)P, (unsigned)n_bhq);
     const float qscale = ix->sigma * LOG2E;
-    if (ix->cfg.kv_dtype == LVR_BF16)
-        hipLaunchKernelGGL(sparse_attention_kernel<lvr_bf16_t>, grid, dim3(64), 0, st, ix->K, ix->V, ix->pos_slot, q,
-                           idx, count, count_stride, cap, ix->part_ml, ix->part_o, ix->cap_rows, ix->n_total, P,
-                           ix->cfg.n_q_heads, ix->cfg.n_kv_heads, ix->G, qscale);
-    else
-        hipLaunchKernelGGL(sparse_attention_kernel<lvr_f32_t>, grid, dim3(64), 0, st, ix->K, ix->V, ix->pos_slot, q,
-                           idx, count, count_stride, cap, ix->part_ml, ix->part_o, ix->cap_rows, ix->n_total, P,
-                           ix->cfg.n_q_heads, ix->cfg.n_kv_heads, ix->G, qscale);
+#define LVR_PART_LAUNCH(KT, CARRY)                                                                                       \
+    hipLaunchKernelGGL((sparse_attention_kernel<KT, CARRY>), grid, dim3(64), 0, st, ix->K, ix->V, ix->pos_slot, q, idx,  \
+                       scores, ix->cap_rows, count, count_stride, cap, ix->part_ml, ix->part_o, ix->cap_rows,            \
+                       ix->n_total, P, ix->cfg.n_q_heads, ix->cfg.n_kv_heads, ix->G, qscale)
+    if (ix->cfg.kv_dtype == LVR_BF16) {
+        if (scores) LVR_PART_LAUNCH(lvr_bf16_t, true);
+        else LVR_PART_LAUNCH(lvr_bf16_t, false);
+    } else {
+        if (scores) LVR_PART_LAUNCH(lvr_f32_t, true);
+        else LVR_PART_LAUNCH(lvr_f32_t, false);
+    }
+#undef LVR_PART_LAUNCH
     return hipGetLastError();
 }
 

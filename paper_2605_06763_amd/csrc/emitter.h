@@ -15,13 +15,18 @@ struct lvr_emit_target {
     int32_t *head_count;     // padded, LVR_CNT_STRIDE ints apart
     int32_t *overflow;
     int64_t cap;
+    float *out_score;        // [n_bhq][score_stride] raw scores of the emitted keys (emitters that carry them), or NULL
+    int64_t score_stride;
 };
 
 // The lanes with (lane % 16) in [rep_base, rep_base+NH) report head (lane % 16) - rep_base; the
 // four lanes (one per quarter of the wave) that report the same head keep identical counts.
-template <int NH>
+// CARRY: the raw score of every queued key travels with it, so that the attention that follows
+// needs neither the key row nor the dot product again.
+template <int NH, bool CARRY = false>
 struct lvr_emitter {
     int32_t (*q)[LVR_QCAP];   // LDS, [NH][LVR_QCAP], private to the wave
+    float (*qs)[LVR_QCAP];    // LDS, scores of the queued keys (CARRY only)
     int count;                // queued entries of my head (0 on lanes that report nothing)
     int rep_base;
     int64_t hq_base;          // flat index of head 0
@@ -43,6 +48,9 @@ struct lvr_emitter {
                 if (p < a.cap) {
                     const int32_t row = q[h][lane];
                     a.out_idx[(hq_base + h) * a.cap + p] = spos ? spos[row] : row;
+                    if constexpr (CARRY) {
+                        if (p < a.score_stride) a.out_score[(hq_base + h) * a.score_stride + p] = qs[h][lane];
+                    }
                 } else
                     *a.overflow = 1;
             }
@@ -53,14 +61,16 @@ struct lvr_emitter {
 
     // pred: this lane's (row, head) qualifies; the row's arena slot is held by lane `src_lane`.
     __device__ __forceinline__ void push(const lvr_emit_target &a, int lane, bool reporting, bool pred, int my_slot,
-                                         int src_lane, const int32_t *spos) {
+                                         int src_lane, const int32_t *spos, float score = 0.f) {
         const uint64_t any = __ballot(pred);
         if (!any) return;   // wave-uniform
         const int slot = __shfl(my_slot, src_lane, 64);
         const uint64_t mh = reporting ? (any & (0x0001000100010001ull << (lane & 15))) : 0ull;
         if (pred) {
             const int hl = (lane & 15) - rep_base;
-            q[hl][count + __popcll(mh & ((1ull << lane) - 1ull))] = slot;
+            const int at = count + __popcll(mh & ((1ull << lane) - 1ull));
+            q[hl][at] = slot;
+            if constexpr (CARRY) qs[hl][at] = score;
         }
         count += __popcll(mh);
         if (__ballot(count > LVR_QCAP - 4)) flush(a, lane, reporting, spos);

@@ -237,6 +237,8 @@ hipError_t lvr_launch_filter(lvr_index *ix, const float *q, const float *tau, in
     a.emit.head_count = lvr_head_count(ix);
     a.emit.overflow = lvr_overflow_flag(ix);
     a.emit.cap = cap;
+    a.emit.out_score = nullptr;
+    a.emit.score_stride = 0;
     a.cap_rows = ix->cap_rows;
     a.max_groups = ix->max_groups;
     a.max_segs = lvr_max_segs(ix->max_groups);

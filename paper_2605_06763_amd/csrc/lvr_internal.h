@@ -55,6 +55,7 @@ struct lvr_index {
     int seg_groups;        // groups per segment used by the last bound test
     int n_segs;            // segments per (sequence, KV head) filled by the last bound test (0: none)
     int counters_dirty;    // a query was started but its counts were never published (a launch failed)
+    float *scores;         // [batch][H_q][cap_rows] raw scores of the keys the fused query emitted, or NULL
     float *part_ml;        // [batch][H_q][Pmax][2]
     float *part_o;         // [batch][H_q][Pmax][d]
     int64_t last_buffer_rows; // buffer rows scanned by the last query (host copy for stats)
@@ -119,12 +120,13 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
 // internal per-head counters -> caller's array and the statistics copy; clears the counters
 hipError_t lvr_launch_publish_counts(lvr_index *ix, int32_t *out_count, hipStream_t st);
 // partial softmax per (head, split); count is read with the given stride (1 = caller's array)
-hipError_t lvr_launch_sparse_partial(lvr_index *ix, const float *q, const int32_t *idx, const int32_t *count,
-                                     int count_stride, int64_t cap, hipStream_t st);
+// scores: raw <q,k> of the listed keys, [n_bhq][cap_rows] (then no key row is read), or NULL
+hipError_t lvr_launch_sparse_partial(lvr_index *ix, const float *q, const int32_t *idx, const float *scores,
+                                     const int32_t *count, int count_stride, int64_t cap, hipStream_t st);
 // whole sparse attention of a head in one workgroup (16 splits merged through LDS), one launch
-hipError_t lvr_launch_sparse_attention_wg(lvr_index *ix, const float *q, const int32_t *idx, const int32_t *count,
-                                          int count_stride, int64_t cap, float *out, int32_t *publish_count,
-                                          hipStream_t st);
+hipError_t lvr_launch_sparse_attention_wg(lvr_index *ix, const float *q, const int32_t *idx, const float *scores,
+                                          const int32_t *count, int count_stride, int64_t cap, float *out,
+                                          int32_t *publish_count, hipStream_t st);
 hipError_t lvr_launch_dense_partial(lvr_index *ix, const float *q, hipStream_t st);
 // merge the partials of every head.  count == NULL: all P (dense baseline); otherwise as many as the
 // sparse split geometry uses for that count.  publish_count != NULL: also hands the internal

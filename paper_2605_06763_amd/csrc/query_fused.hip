@@ -48,7 +48,14 @@ template <int HB, int S, int UA, int ENC, int Q1 = 0>
 __global__ void __launch_bounds__(256)
 query_fused_kernel(const FusedArgs a) {
     static_assert(!Q1 || (S <= 4 && !ENC), "Query 1 needs blocks that are whole MFMA steps");
-    __shared__ uint4 s_bq[HB][4][64];
+    // the staging area of the query operand is dead once every wave holds its fragments; the score
+    // queues of the emitters live in the same bytes afterwards (LDS per workgroup decides how many
+    // workgroups a CU holds: 4 KB more costs one of four)
+    __shared__ union {
+        uint4 bq[HB][4][64];
+        float qscore[4][HB][4][LVR_QCAP];
+    } s_u;
+    static_assert(sizeof(s_u.bq) == sizeof(s_u.qscore), "aliasing assumes equal sizes");
     __shared__ uint4 s_bq2[ENC ? HB : 1][4][64];
     __shared__ float s_qn[HB * 4][16];
     __shared__ int32_t s_queue[4][HB][4][LVR_QCAP];
@@ -120,7 +127,7 @@ query_fused_kernel(const FusedArgs a) {
     // B operands: q itself for balls; for boxes its positive part (meets the upper corners) and its
     // negative part (meets the lower corners); q = q+ + q- serves the exact check of phase B
     lvr_bf16x8 bq[HB][4], bq2[ENC ? HB : 1][4];
-    lvr_build_q_frags_wg<HB>(a.q + hq0 * LVR_D, a.G, 1.0f, s_bq, bq, ENC ? 1 : 0);   // syncs
+    lvr_build_q_frags_wg<HB>(a.q + hq0 * LVR_D, a.G, 1.0f, s_u.bq, bq, ENC ? 1 : 0);   // syncs
     if constexpr (ENC) lvr_build_q_frags_wg<HB>(a.q + hq0 * LVR_D, a.G, 1.0f, s_bq2, bq2, -1);
     float taue[HB];
     bool rep[HB];
@@ -260,15 +267,18 @@ query_fused_kernel(const FusedArgs a) {
                 if (i < pieces) kd[i] = ks[i];
                 else vd[i - pieces] = vs[i - pieces];
             }
-            __syncthreads();
         }
+        // the new rows are in place for every wave of this workgroup, and no wave still reads the
+        // operand staging area that the score queues are about to reuse
+        __syncthreads();
     }
 
     // ---------------- phase B: exact check of the surviving rows ----------------
-    lvr_emitter<4> em[HB];
+    lvr_emitter<4, true> em[HB];
 #pragma unroll
     for (int hb = 0; hb < HB; ++hb) {
         em[hb].q = s_queue[wave][hb];
+        em[hb].qs = s_u.qscore[wave][hb];
         em[hb].count = 0;
         em[hb].rep_base = 8;
         em[hb].hq_base = hq0 + hb * 4;
@@ -304,7 +314,7 @@ query_fused_kernel(const FusedArgs a) {
                     const int trow = 4 * kq + j;
                     const bool pred = trow < nvalid[u] && rep[hb] &&
                                       (s[j] >= taue[hb] || (buffer_wg && a.buffer_dense));
-                    em[hb].push(a.emit, lane, rep[hb], pred, slot[u], trow, spos);
+                    em[hb].push(a.emit, lane, rep[hb], pred, slot[u], trow, spos, s[j]);
                 }
             }
         }
@@ -349,6 +359,8 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
     a.emit.head_count = lvr_head_count(ix);
     a.emit.overflow = lvr_overflow_flag(ix);
     a.emit.cap = cap;
+    a.emit.out_score = ix->scores;
+    a.emit.score_stride = ix->cap_rows;
     a.n_groups = ix->n_indexed / ix->cfg.group_size;
     a.max_groups = ix->max_groups;
     a.max_segs = lvr_max_segs(ix->max_groups);
