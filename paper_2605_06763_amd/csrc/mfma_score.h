@@ -125,6 +125,111 @@ __device__ __forceinline__ lvr_f32x4 lvr_score_tile_block(const uint4 (&a)[4], c
     return s;
 }
 
+// The radius term of the bound, sum_s rho_s * |pi_s q|, as one more MFMA step.
+// k-slot of the step: k = part' * S + s for k < 3S (S <= 8), zero beyond.
+//   A[i = row][k]      = part' of rho_{row,s}   (three bf16 terms that add up to rho exactly;
+//                        rho >= 0, so truncation gives them: top 8 bits, next 8, last 8)
+//   B[k][n = (p, h)]   = part p of |pi_s q_h|   (the same three-term split as q itself)
+// Summed over k this is (rho_hi + rho_mid + rho_lo) * |pi_s q|_p per subspace, and the three
+// columns p of a head are added up with those of the centre product.
+template <int S>
+__device__ __forceinline__ lvr_bf16x8 lvr_radius_a_frag(const float (&rho)[S]) {
+    static_assert(3 * S <= 32, "the radius terms must fit one MFMA step");
+    const int kq = (threadIdx.x & 63) >> 4;
+    uint32_t part[3][S];
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+        const uint32_t u0 = __float_as_uint(rho[s]) & 0xffff0000u;
+        const float r1 = rho[s] - __uint_as_float(u0);
+        const uint32_t u1 = __float_as_uint(r1) & 0xffff0000u;
+        const float r2 = r1 - __uint_as_float(u1);
+        part[0][s] = u0 >> 16;
+        part[1][s] = u1 >> 16;
+        part[2][s] = __float_as_uint(r2) >> 16;
+    }
+    uint32_t w[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        uint32_t v = 0;
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            const int k = 8 * q4 + j;   // compile-time
+            if (k < 3 * S) v = (kq == q4) ? part[k / S][k % S] : v;
+        }
+        w[j] = v;
+    }
+    uint4 packed = make_uint4(w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16));
+    return __builtin_bit_cast(lvr_bf16x8, packed);
+}
+
+// qn_group: [heads][16] floats, |pi_s q_h| for s < S (already rounded up); head block hb.
+template <int S>
+__device__ __forceinline__ lvr_bf16x8 lvr_radius_b_frag(const float (*qn_group)[16], int G, int hb) {
+    const int lane = threadIdx.x & 63;
+    const int n = lane & 15, kq = lane >> 4;
+    const int p = n >> 2, h = hb * 4 + (n & 3);
+    const bool live = p < 3 && h < G;
+    uint32_t val[S];
+#pragma unroll
+    for (int s = 0; s < S; ++s) val[s] = live ? lvr_split_part(qn_group[live ? h : 0][s], p) : 0u;
+    uint32_t w[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        uint32_t v = 0;
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            const int k = 8 * q4 + j;
+            if (k < 3 * S) v = (kq == q4) ? val[k % S] : v;
+        }
+        w[j] = v;
+    }
+    uint4 packed = make_uint4(w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16));
+    return __builtin_bit_cast(lvr_bf16x8, packed);
+}
+
+// Bound of a tile of 16 balls: centre product plus the radius step.
+__device__ __forceinline__ lvr_f32x4 lvr_bound_tile(const uint4 (&a)[4], const lvr_bf16x8 (&bq)[4], lvr_bf16x8 ra,
+                                                    lvr_bf16x8 rb) {
+    lvr_f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lvr_bf16x8, a[kk]), bq[kk], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ra, rb, acc, 0, 0, 0);
+    lvr_f32x4 s;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float v = acc[j];
+        float t = v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x114, 0xf, 0xf, true));
+        t += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x118, 0xf, 0xf, true));
+        s[j] = t;
+    }
+    return s;
+}
+
+// Bound of a tile of 16 boxes: upper corners against q+, lower corners against q-, plus the
+// allowance step.
+__device__ __forceinline__ lvr_f32x4 lvr_bound_tile2(const uint4 (&a1)[4], const lvr_bf16x8 (&b1)[4],
+                                                     const uint4 (&a2)[4], const lvr_bf16x8 (&b2)[4], lvr_bf16x8 ra,
+                                                     lvr_bf16x8 rb) {
+    lvr_f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lvr_bf16x8, a1[kk]), b1[kk], acc, 0, 0, 0);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lvr_bf16x8, a2[kk]), b2[kk], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ra, rb, acc, 0, 0, 0);
+    lvr_f32x4 s;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float v = acc[j];
+        float t = v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x114, 0xf, 0xf, true));
+        t += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x118, 0xf, 0xf, true));
+        s[j] = t;
+    }
+    return s;
+}
+
 // Two chains into one accumulator:  D = A1 . B1 + A2 . B2  (box bound: upper corners against the
 // positive part of q, lower corners against the negative part; exact check of a row against
 // q = q+ + q-: the same A twice).

@@ -76,8 +76,13 @@ query_fused_kernel(const FusedArgs a) {
     const float *Rb = a.radii + (int64_t)bh * a.max_groups * S;
     const int64_t n_tiles = (a.n_groups + 15) >> 4;
     const int64_t tile0 = ((int64_t)blockIdx.x * 4 + wave) * a.tiles_per_wave;
-    uint4 av[UA][4], av2[UA][4];
-    float rad[UA][4][SP];
+    // RM: the radius term rides on the matrix cores as a fifth step (S <= 4, one threshold per head);
+    // a lane then needs only its own row's radii.  Otherwise the lanes that hold the scores fetch
+    // the radii of their four rows and add the terms on the vector ALU.
+    constexpr bool RM = !Q1 && S <= 4;
+    uint4 av[UA][4], av2[ENC ? UA : 1][4];
+    float rad[RM ? 1 : UA][4][SP];
+    float rrow[RM ? UA : 1][SP];
     auto issueA = [&](int it) {
 #pragma unroll
         for (int u = 0; u < UA; ++u) {
@@ -90,7 +95,16 @@ query_fused_kernel(const FusedArgs a) {
             } else {
                 lvr_load_a_frags(Cb, g, av[u]);
             }
-            if constexpr (S <= 4) {
+            if constexpr (RM) {
+                const float *rp = Rb + g * S;
+                if constexpr (S == 4) {
+                    const float4 r = *reinterpret_cast<const float4 *>(rp);
+                    rrow[u][0] = r.x; rrow[u][1] = r.y; rrow[u][2] = r.z; rrow[u][3] = r.w;
+                } else {
+#pragma unroll
+                    for (int s = 0; s < S; ++s) rrow[u][s] = rp[s];
+                }
+            } else if constexpr (S <= 4) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     int64_t gj = g0 + 4 * kq + j;
@@ -129,6 +143,13 @@ query_fused_kernel(const FusedArgs a) {
     lvr_bf16x8 bq[HB][4], bq2[ENC ? HB : 1][4];
     lvr_build_q_frags_wg<HB>(a.q + hq0 * LVR_D, a.G, 1.0f, s_u.bq, bq, ENC ? 1 : 0);   // syncs
     if constexpr (ENC) lvr_build_q_frags_wg<HB>(a.q + hq0 * LVR_D, a.G, 1.0f, s_bq2, bq2, -1);
+    lvr_bf16x8 rbq[RM ? HB : 1];
+    if constexpr (RM) {
+        if (!buffer_wg) {
+#pragma unroll
+            for (int hb = 0; hb < HB; ++hb) rbq[hb] = lvr_radius_b_frag<S>(s_qn, a.G, hb);
+        }
+    }
     float taue[HB];
     bool rep[HB];
 #pragma unroll
@@ -190,12 +211,20 @@ query_fused_kernel(const FusedArgs a) {
                         continue;
                     }
                     lvr_f32x4 sc;
-                    if constexpr (ENC) sc = lvr_score_tile2(av[u], bq[hb], av2[u], bq2[hb]);
-                    else sc = lvr_score_tile(av[u], bq[hb]);
+                    if constexpr (RM) {
+                        const lvr_bf16x8 ra = lvr_radius_a_frag<S>(rrow[u]);
+                        if constexpr (ENC) sc = lvr_bound_tile2(av[u], bq[hb], av2[u], bq2[hb], ra, rbq[hb]);
+                        else sc = lvr_bound_tile(av[u], bq[hb], ra, rbq[hb]);
+                    } else {
+                        if constexpr (ENC) sc = lvr_score_tile2(av[u], bq[hb], av2[u], bq2[hb]);
+                        else sc = lvr_score_tile(av[u], bq[hb]);
+                    }
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         float ub = sc[j];
-                        if constexpr (S <= 4) {
+                        if constexpr (RM) {
+                            // the radius terms are already in the sum
+                        } else if constexpr (S <= 4) {
 #pragma unroll
                             for (int s = 0; s < S; ++s) ub += rad[u][j][s] * qn[hb][s];
                         } else {
@@ -391,8 +420,8 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
     ix->n_segs = a.n_segs;
     if (a.n_segs + has_buffer == 0) return hipSuccess;
     dim3 grid((unsigned)(a.n_segs + has_buffer), (unsigned)n_bh);
-    // one centre tile per trip (fewer registers, five waves per SIMD) for the small segments of short
-    // contexts, two per trip for long ones: measured crossover between 32k and 128k keys
+    // one centre tile per trip for the small segments of short contexts, two per trip for long ones
+    // (measured crossover between 32k and 128k keys); four per trip costs a wave per SIMD and 12 us
     const bool one = tpw == 1;
     if (tau_s) {   // Query 1: per-block thresholds
         const int S = ix->cfg.n_subspaces;
