@@ -74,3 +74,18 @@ def test_product_path_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".h")):
                 src = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in src.lower().replace("threshold oracle", ""), f
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/louver.h is the C ABI: it must compile as C99 (and as C++) on its own, with no
+    HIP or torch types in any signature."""
+    import subprocess
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "louver.h"\nint main(void) { lvr_config c; lvr_stats s; (void)c; (void)s; '
+                   'return lvr_strerror(0) == 0; }\n')
+    inc = os.path.join(ROOT, "include")
+    for cmd in (["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror"], ["g++", "-std=c++17", "-x", "c++", "-Wall", "-Werror"]):
+        r = subprocess.run(cmd + ["-I", inc, "-c", str(src), "-o", str(tmp_path / "o.o")], capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
+    text = re.sub(r"/\*.*?\*/", "", open(os.path.join(inc, "louver.h")).read(), flags=re.S)   # declarations only
+    assert "hipStream_t" not in text and "torch" not in text and "at::" not in text and "#include <hip" not in text
