@@ -62,6 +62,9 @@ def main():
     ap.add_argument("--subspaces", type=int, default=4)
     ap.add_argument("--enclosing", choices=["ball", "aabb"], default="ball")
     ap.add_argument("--grouping", choices=["contiguous", "tree"], default="contiguous")
+    ap.add_argument("--centres", choices=["auto", "bf16", "fp8"], default="auto",
+                    help="storage of the centres: the cache's bf16, or 8-bit e4m3 codes (half the index read); "
+                         "auto = the library's default (8-bit where supported)")
     ap.add_argument("--keys", choices=["workload", "local"], default="workload",
                     help="'local': supplementary cache whose keys have positional locality (the pruned regime); "
                          "not one of the five workloads")
@@ -127,6 +130,7 @@ def main():
                         enclosing=L.LVR_ENCLOSE_AABB if args.enclosing == "aabb" else L.LVR_ENCLOSE_BALL,
                         grouping=L.LVR_GROUP_TREE if args.grouping == "tree" else L.LVR_GROUP_CONTIGUOUS,
                         attn_splits=args.attn_splits,
+                        index_dtype={"auto": L.LVR_INDEX_AUTO, "bf16": L.LVR_INDEX_SAME, "fp8": L.LVR_INDEX_FP8}[args.centres],
                         flags=(L.LVR_CONCURRENT_UPDATE if args.concurrent_update else 0)
                         | (L.LVR_KV_IN_HOST_MEMORY if args.offload else 0)
                         | (L.LVR_SEPARATE_KERNELS if args.separate else 0))
@@ -282,9 +286,11 @@ def main():
     copy_gbs = 10 * 2 * src.numel() / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
     del src, dst
 
+    index_bytes_per_group = st["bytes_index"] // max(st["groups_scored"], 1)
     # ---- algorithmic bytes of the dominant kernel ----
     # fused range-query kernel (bound test + exact check): per (sequence, KV head)
-    #   groups * (d*2 + S*4) bytes of centres and radii  +  keys_scanned * d*2 bytes of key rows
+    #   groups * (d*c + S*4) bytes of centres (c = 1 byte per coordinate as e4m3 codes, 2 as bf16) and radii
+    #   +  keys_scanned * d*2 bytes of key rows
     n_bh = B * Hkv
     filt = kern.get("filter", dict(avg_us=float("nan")))
     if args.separate and "prune" in kern:
@@ -298,7 +304,7 @@ def main():
     # HBM bytes per launch measured offline with rocprofv3 --pmc (profiles/), when this workload was profiled
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
     if (os.path.exists(tpath) and args.group_size == 4 and args.subspaces == 4 and args.keys == "workload"
-            and args.enclosing == "ball" and not args.offload and not args.separate and args.grouping == "contiguous"):
+            and args.enclosing == "ball" and args.centres == "auto" and not args.offload and not args.separate and args.grouping == "contiguous"):
         for line in open(tpath):
             f = line.split()
             if len(f) == 3 and f[0] == f"config{cid}" and f[1] == "query_fused_kernel":
@@ -321,7 +327,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"config{cid}:{c['name']}" + (" [supplementary: keys with positional locality]" if args.keys == "local" else ""), "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
                    "head_dim": d, "context": int(n_now), "kv_storage": "bf16", "group_size": args.group_size,
-                   "subspaces": args.subspaces, "attn_splits": args.attn_splits, "grouping": args.grouping, "enclosing": args.enclosing,
+                   "subspaces": args.subspaces, "attn_splits": args.attn_splits, "grouping": args.grouping,
+                   "centres": ("fp8" if index_bytes_per_group == 128 + 4 * args.subspaces else "bf16"), "enclosing": args.enclosing,
                    "step": "append+query+attention" if appending else "query+attention",
                    "update": "two-stream" if args.concurrent_update else "single-stream",
                    "kv_memory": "host (pinned, read in place)" if args.offload else "hbm",

@@ -49,6 +49,16 @@ enum lvr_grouping { LVR_GROUP_CONTIGUOUS = 0, LVR_GROUP_TREE = 1 };
  *         n_subspaces is ignored. */
 enum lvr_enclosing { LVR_ENCLOSE_BALL = 0, LVR_ENCLOSE_AABB = 1 };
 
+/* Storage of the centres (Sec. 4.1; the paper does not fix their precision).  Whatever the
+ * format, every radius is measured against the centre AS STORED, so a ball always encloses its
+ * members and no qualifying key can be lost; a coarser centre only makes the balls larger.
+ *   SAME: the cache's own format (bf16 or fp32), 2 or 4 bytes per coordinate.
+ *   FP8:  OCP e4m3 codes (1 sign, 4 exponent, 3 mantissa bits), 1 byte per coordinate: the index
+ *         read of a query halves.  bf16 caches, ball enclosure, n_subspaces <= 4, fused query
+ *         kernel (LVR_E_UNSUPPORTED otherwise).
+ *   AUTO: FP8 where it is supported, else SAME. */
+enum lvr_index_dtype { LVR_INDEX_AUTO = 0, LVR_INDEX_SAME = 1, LVR_INDEX_FP8 = 2 };
+
 enum lvr_flags {
     /* Keys not yet in the index (the buffer of Sec. 4.3 "Dynamic Updates") are retrieved
      * whatever their score, as in Alg. 3 / Alg. 4's  K[L*] ∪ B.  Default (flag clear): they are
@@ -108,6 +118,8 @@ typedef struct lvr_config {
     int32_t reservoir_size; /* R <= 256 past keys kept per (sequence, KV head) by reservoir sampling for
                              * lvr_threshold (appendix "Threshold Oracle Comparison"); 0 = none         */
     uint64_t seed;          /* seed of the counter-based generator behind the reservoir              */
+    int32_t index_dtype;    /* lvr_index_dtype: storage of the centres                               */
+    int32_t reserved;      /* must be 0                                                             */
 } lvr_config;
 
 /* Counters of the most recent lvr_query / lvr_decode_step, summed over batch and heads. */

@@ -20,6 +20,7 @@ LVR_ATTEND_BUFFER_DENSE = 1
 LVR_SEPARATE_KERNELS = 2
 LVR_CONCURRENT_UPDATE = 4
 LVR_KV_IN_HOST_MEMORY = 8
+LVR_INDEX_AUTO, LVR_INDEX_SAME, LVR_INDEX_FP8 = 0, 1, 2
 LVR_OK, LVR_E_INVALID, LVR_E_UNSUPPORTED, LVR_E_CAPACITY = 0, -1, -2, -3
 LVR_E_OVERFLOW, LVR_E_HIP, LVR_E_NOMEM, LVR_E_STATE = -4, -5, -6, -7
 
@@ -30,7 +31,7 @@ class lvr_config(C.Structure):
         ("kv_dtype", C.c_int32), ("group_size", C.c_int32), ("n_subspaces", C.c_int32),
         ("buffer_size", C.c_int32), ("grouping", C.c_int32), ("enclosing", C.c_int32), ("flags", C.c_uint32),
         ("capacity", C.c_int64), ("scale", C.c_float), ("attn_splits", C.c_int32),
-        ("reservoir_size", C.c_int32), ("seed", C.c_uint64),
+        ("reservoir_size", C.c_int32), ("seed", C.c_uint64), ("index_dtype", C.c_int32), ("reserved", C.c_int32),
     ]
 
 
@@ -162,9 +163,9 @@ def _dev(t, dtype=None, name="tensor"):
 
 def make_config(*, batch, n_q_heads, n_kv_heads, head_dim=128, kv_dtype=LVR_BF16, group_size=4,
                 n_subspaces=4, buffer_size=256, grouping=LVR_GROUP_CONTIGUOUS, enclosing=LVR_ENCLOSE_BALL, flags=0, capacity,
-                scale=0.0, attn_splits=0, reservoir_size=0, seed=0) -> lvr_config:
+                scale=0.0, attn_splits=0, reservoir_size=0, seed=0, index_dtype=0) -> lvr_config:
     return lvr_config(batch, n_q_heads, n_kv_heads, head_dim, kv_dtype, group_size, n_subspaces,
-                      buffer_size, grouping, enclosing, flags, capacity, scale, attn_splits, reservoir_size, seed)
+                      buffer_size, grouping, enclosing, flags, capacity, scale, attn_splits, reservoir_size, seed, index_dtype, 0)
 
 
 def lvr_arena_bytes(cfg: lvr_config) -> int:

@@ -25,6 +25,15 @@ inline int hip_fail(hipError_t e) {
 
 inline bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 
+inline bool fp8_centres_supported(const lvr_config *c) {
+    return c->kv_dtype == LVR_BF16 && c->enclosing == LVR_ENCLOSE_BALL && !(c->flags & LVR_SEPARATE_KERNELS) &&
+           c->n_subspaces <= 4;
+}
+
+inline bool fp8_centres(const lvr_config *c) {
+    return c->index_dtype == LVR_INDEX_FP8 || (c->index_dtype == LVR_INDEX_AUTO && fp8_centres_supported(c));
+}
+
 int check_config(const lvr_config *c) {
     if (!c) return LVR_E_INVALID;
     if (c->batch <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->capacity <= 0) return LVR_E_INVALID;
@@ -44,6 +53,10 @@ int check_config(const lvr_config *c) {
     if (c->reservoir_size < 0 || c->reservoir_size > 256) return LVR_E_INVALID;
     if (c->enclosing == LVR_ENCLOSE_AABB && (c->kv_dtype != LVR_BF16 || (c->flags & LVR_SEPARATE_KERNELS)))
         return LVR_E_UNSUPPORTED;
+    if (c->index_dtype != LVR_INDEX_AUTO && c->index_dtype != LVR_INDEX_SAME && c->index_dtype != LVR_INDEX_FP8)
+        return LVR_E_INVALID;
+    if (c->reserved != 0) return LVR_E_INVALID;
+    if (c->index_dtype == LVR_INDEX_FP8 && !fp8_centres_supported(c)) return LVR_E_UNSUPPORTED;
     return LVR_OK;
 }
 
@@ -69,7 +82,8 @@ Sizes sizes_of(const lvr_config *c) {
     auto al = [](size_t b) { return (b + 255) / 256 * 256; };
     s.kv = al((size_t)n_bh * s.cap_rows * LVR_D * elt);
     const bool box = c->enclosing == LVR_ENCLOSE_AABB;
-    s.centres = al((size_t)n_bh * s.max_groups * LVR_D * elt * (box ? 2 : 1));
+    const size_t c_elt = fp8_centres(c) ? 1 : elt;
+    s.centres = al((size_t)n_bh * s.max_groups * LVR_D * c_elt * (box ? 2 : 1));
     s.radii = al((size_t)n_bh * s.max_groups * (box ? 1 : c->n_subspaces) * sizeof(float));
     s.list = al((size_t)n_bh * s.max_groups * sizeof(int32_t));
     s.counters = al(lvr_counter_ints((int)n_bh, (int)n_bhq, s.max_groups) * sizeof(int32_t));
@@ -209,6 +223,7 @@ int lvr_create(const lvr_config *cfg, lvr_index **out) {
     ix->G = cfg->n_q_heads / cfg->n_kv_heads;
     ix->box = cfg->enclosing == LVR_ENCLOSE_AABB;
     ix->S_store = ix->box ? 1 : cfg->n_subspaces;
+    ix->cf8 = fp8_centres(cfg);
     ix->cap_rows = s.cap_rows;
     ix->max_groups = s.max_groups;
     ix->P = s.P;
@@ -634,7 +649,7 @@ int lvr_get_stats(lvr_index *ix, lvr_stats *out) {
     out->groups_surviving = surv;
     out->keys_scanned = surv * r + ix->last_buffer_rows * n_bh;
     out->keys_emitted = emitted;
-    out->bytes_index = out->groups_scored * (row_bytes * (ix->box ? 2 : 1) + (int64_t)ix->S_store * 4);
+    out->bytes_index = out->groups_scored * ((ix->cf8 ? (int64_t)LVR_D : row_bytes * (ix->box ? 2 : 1)) + (int64_t)ix->S_store * 4);
     out->bytes_keys = out->keys_scanned * row_bytes;
     out->bytes_attention = emitted * 2 * row_bytes;
     out->overflow = overflow;
@@ -655,7 +670,30 @@ int lvr_export_index(lvr_index *ix, void *centres, float *radii, int32_t *slot_p
     const size_t row_bytes = LVR_D * ix->elt;
     const size_t crow = row_bytes * (ix->box ? 2 : 1);   // bytes of one group's enclosure rows
     for (int bh = 0; bh < n_bh; ++bh) {
-        if (centres && ng > 0)
+        if (centres && ng > 0 && ix->cf8) {
+            // e4m3 codes in matrix-operand order -> bf16 bit patterns in coordinate order (exact)
+            uint8_t *codes = static_cast<uint8_t *>(malloc((size_t)ng * LVR_D));
+            if (!codes) return LVR_E_NOMEM;
+            hipError_t e = hipMemcpy(codes, static_cast<char *>(ix->centres) + (size_t)bh * ix->max_groups * LVR_D,
+                                     (size_t)ng * LVR_D, hipMemcpyDeviceToHost);
+            if (e != hipSuccess) {
+                free(codes);
+                return hip_fail(e);
+            }
+            uint16_t *dst = static_cast<uint16_t *>(centres) + (size_t)bh * ng * LVR_D;
+            for (int64_t g = 0; g < ng; ++g)
+                for (int c = 0; c < LVR_D; ++c) {
+                    const int kk = c / 32, kq = (c % 32) / 8, j = c % 8;
+                    const uint8_t code = codes[g * LVR_D + kq * 32 + kk * 8 + j];
+                    const int sgn = code >> 7, ex = (code >> 3) & 15, m = code & 7;
+                    const float v = ex == 0 ? ldexpf((float)m / 8.f, -6) : ldexpf(1.f + (float)m / 8.f, ex - 7);
+                    uint32_t bits;
+                    const float sv = sgn ? -v : v;
+                    memcpy(&bits, &sv, 4);
+                    dst[g * LVR_D + c] = (uint16_t)(bits >> 16);   // 4 significant bits: exact in bf16
+                }
+            free(codes);
+        } else if (centres && ng > 0)
             LVR_HIP(hipMemcpy(static_cast<char *>(centres) + (size_t)bh * ng * crow,
                               static_cast<char *>(ix->centres) + (size_t)bh * ix->max_groups * crow,
                               (size_t)ng * crow, hipMemcpyDeviceToHost));

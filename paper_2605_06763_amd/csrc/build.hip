@@ -42,7 +42,25 @@ __device__ __forceinline__ float seg_sum(float v, int lanes_per_sub) {
     return v;
 }
 
-template <typename KT>
+// fp32 -> OCP e4m3 code (1 sign, 4 exponent bits of bias 7, 3 mantissa bits; subnormals below 2^-6),
+// round to nearest even, magnitudes above the largest finite value (448) saturate to it.
+__device__ __forceinline__ uint32_t f32_to_e4m3(float x) {
+    const uint32_t sign = (__float_as_uint(x) >> 24) & 0x80u;
+    float a = fabsf(x);
+    if (!(a < 448.f)) a = 448.f;
+    if (a < 0x1p-6f) return sign | (uint32_t)(int)rintf(a * 512.f);   // 0..8; 8 is the smallest normal
+    uint32_t u = __float_as_uint(a);
+    u += 0x7ffffu + ((u >> 20) & 1u);
+    uint32_t code = (((u >> 23) - 120u) << 3) | ((u >> 20) & 7u);
+    if (code > 0x7eu) code = 0x7eu;
+    return sign | code;
+}
+
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float lvr_f32x2;
+
+// CF8: the centre is stored as 128 e4m3 codes in the order the matrix-core operand wants them
+// (byte kq*32 + kk*8 + j holds coordinate kk*32 + kq*8 + j); only for bf16 caches.
+template <typename KT, bool CF8 = false>
 __global__ void __launch_bounds__(256)
 build_groups_kernel(const void *__restrict__ K, void *__restrict__ centres, float *__restrict__ radii,
                     int64_t cap_rows, int64_t max_groups, int64_t g0, int64_t g1, int r, int S) {
@@ -65,8 +83,20 @@ build_groups_kernel(const void *__restrict__ K, void *__restrict__ centres, floa
 #pragma unroll
     for (int e = 0; e < 8; ++e) c[e] *= inv;
 
-    char *Cb = static_cast<char *>(centres) + ((int64_t)bh * max_groups + g) * LVR_D * sizeof(KT);
-    if constexpr (std::is_same<KT, lvr_bf16_t>::value) {
+    char *Cb = static_cast<char *>(centres) + ((int64_t)bh * max_groups + g) * LVR_D * (CF8 ? 1 : sizeof(KT));
+    if constexpr (CF8) {
+        uint32_t code[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) code[e] = f32_to_e4m3(c[e]);
+        const uint32_t w0 = code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24);
+        const uint32_t w1 = code[4] | (code[5] << 8) | (code[6] << 16) | (code[7] << 24);
+        // from here on: the centre as stored (decoded by the same instruction the query kernel uses)
+        const lvr_f32x2 d0 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w0, false), d1 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w0, true);
+        const lvr_f32x2 d2 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w1, false), d3 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w1, true);
+        c[0] = d0[0]; c[1] = d0[1]; c[2] = d1[0]; c[3] = d1[1];
+        c[4] = d2[0]; c[5] = d2[1]; c[6] = d3[0]; c[7] = d3[1];
+        if (valid) *reinterpret_cast<uint2 *>(Cb + (li & 3) * 32 + (li >> 2) * 8) = make_uint2(w0, w1);
+    } else if constexpr (std::is_same<KT, lvr_bf16_t>::value) {
         uint32_t b[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -194,7 +224,10 @@ hipError_t lvr_launch_build_groups(lvr_index *ix, int64_t g0, int64_t g1, hipStr
                            ix->max_groups, g0, g1, ix->cfg.group_size);
         return hipGetLastError();
     }
-    if (ix->cfg.kv_dtype == LVR_BF16)
+    if (ix->cf8)
+        hipLaunchKernelGGL((build_groups_kernel<lvr_bf16_t, true>), grid, dim3(256), 0, st, ix->K, ix->centres, ix->radii,
+                           ix->cap_rows, ix->max_groups, g0, g1, ix->cfg.group_size, ix->cfg.n_subspaces);
+    else if (ix->cfg.kv_dtype == LVR_BF16)
         hipLaunchKernelGGL(build_groups_kernel<lvr_bf16_t>, grid, dim3(256), 0, st, ix->K, ix->centres, ix->radii,
                            ix->cap_rows, ix->max_groups, g0, g1, ix->cfg.group_size, ix->cfg.n_subspaces);
     else

@@ -22,6 +22,7 @@ struct lvr_index {
     int G;                 // query heads per KV head
     int box;               // 1: groups are enclosed by axis-aligned boxes (two rows per group in `centres`)
     int S_store;           // floats per group in `radii` (S for balls, 1 for boxes)
+    int cf8;               // 1: centres are stored as e4m3 codes, 128 bytes per group, in matrix-operand order
     int64_t cap_rows;      // arena rows per (sequence, KV head), multiple of 64
     int64_t max_groups;    // cap_rows / r
     int64_t n_total;       // keys held

@@ -88,6 +88,30 @@ __device__ __forceinline__ void lvr_load_a_frags(const char *__restrict__ base, 
     for (int kk = 0; kk < 4; ++kk) a[kk] = p[kk * 4];
 }
 
+// Centres stored as e4m3 codes in operand order: a lane's 32 bytes of a row are its four pieces of
+// 8 coordinates (kk = 0..3).  Two 16-byte loads instead of four ...
+__device__ __forceinline__ void lvr_load_a_codes(const char *__restrict__ base, int64_t row, uint4 (&raw)[2]) {
+    const int kq = (threadIdx.x & 63) >> 4;
+    const uint4 *p = reinterpret_cast<const uint4 *>(base + row * LVR_D + kq * 32);
+    raw[0] = p[0];
+    raw[1] = p[1];
+}
+
+// ... and one conversion instruction per two codes (exact: an e4m3 value has 4 significant bits)
+// turns them into the bf16 operand pieces.
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 lvr_bf16x2;
+__device__ __forceinline__ void lvr_codes_to_a_frags(const uint4 (&raw)[2], uint4 (&a)[4]) {
+    const uint32_t w[8] = {raw[0].x, raw[0].y, raw[0].z, raw[0].w, raw[1].x, raw[1].y, raw[1].z, raw[1].w};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        const uint32_t d0 = w[2 * kk], d1 = w[2 * kk + 1];
+        a[kk].x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)d0, 1.0f, false));
+        a[kk].y = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)d0, 1.0f, true));
+        a[kk].z = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)d1, 1.0f, false));
+        a[kk].w = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)d1, 1.0f, true));
+    }
+}
+
 // D = A . B over the 128 coordinates, then the three query parts are added up.
 // Result valid in lanes with (lane % 16) in [8, 12): score of head hb*4 + lane%16 - 8 for rows
 // 4*(lane/16) + j, j = 0..3.

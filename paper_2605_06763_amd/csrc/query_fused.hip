@@ -43,11 +43,13 @@ struct FusedArgs {
     int log2r, n_q_heads, n_kv_heads, G, buffer_dense, n_segs, tiles_per_wave;
 };
 
-// UA = centre tiles per phase-A trip; ENC = 1: boxes instead of balls; Q1 = 1: per-block thresholds (S <= 4)
-template <int HB, int S, int UA, int ENC, int Q1 = 0>
+// UA = centre tiles per phase-A trip; ENC = 1: boxes instead of balls; Q1 = 1: per-block thresholds (S <= 4);
+// CF8 = 1: centres stored as e4m3 codes (balls, S <= 4)
+template <int HB, int S, int UA, int ENC, int Q1 = 0, int CF8 = 0>
 __global__ void __launch_bounds__(256)
 query_fused_kernel(const FusedArgs a) {
     static_assert(!Q1 || (S <= 4 && !ENC), "Query 1 needs blocks that are whole MFMA steps");
+    static_assert(!CF8 || (S <= 4 && !ENC), "8-bit centres: balls, at most four coordinate blocks");
     // the staging area of the query operand is dead once every wave holds its fragments; the score
     // queues of the emitters live in the same bytes afterwards (LDS per workgroup decides how many
     // workgroups a CU holds: 4 KB more costs one of four)
@@ -72,7 +74,7 @@ query_fused_kernel(const FusedArgs a) {
     // in flight before the prologue builds the query operand ----
     constexpr int SP = (S <= 4) ? S : 1;      // radii are fetched ahead only when they are few
     // balls: one row per group (the centre); boxes: two rows per group (upper corner, lower corner)
-    const char *Cb = static_cast<const char *>(a.centres) + (int64_t)bh * a.max_groups * LVR_D * 2 * (ENC ? 2 : 1);
+    const char *Cb = static_cast<const char *>(a.centres) + (int64_t)bh * a.max_groups * LVR_D * (CF8 ? 1 : 2) * (ENC ? 2 : 1);
     const float *Rb = a.radii + (int64_t)bh * a.max_groups * S;
     const int64_t n_tiles = (a.n_groups + 15) >> 4;
     const int64_t tile0 = ((int64_t)blockIdx.x * 4 + wave) * a.tiles_per_wave;
@@ -80,7 +82,7 @@ query_fused_kernel(const FusedArgs a) {
     // a lane then needs only its own row's radii.  Otherwise the lanes that hold the scores fetch
     // the radii of their four rows and add the terms on the vector ALU.
     constexpr bool RM = !Q1 && S <= 4;
-    uint4 av[UA][4], av2[ENC ? UA : 1][4];
+    uint4 av[UA][CF8 ? 2 : 4], av2[ENC ? UA : 1][4];
     float rad[RM ? 1 : UA][4][SP];
     float rrow[RM ? UA : 1][SP];
     auto issueA = [&](int it) {
@@ -92,6 +94,8 @@ query_fused_kernel(const FusedArgs a) {
             if constexpr (ENC) {
                 lvr_load_a_frags(Cb, 2 * g, av[u]);
                 lvr_load_a_frags(Cb, 2 * g + 1, av2[u]);
+            } else if constexpr (CF8) {
+                lvr_load_a_codes(Cb, g, av[u]);
             } else {
                 lvr_load_a_frags(Cb, g, av[u]);
             }
@@ -184,6 +188,13 @@ query_fused_kernel(const FusedArgs a) {
             for (int u = 0; u < UA; ++u) {
                 const int64_t g_row = (tile0 + it + u) * 16;
                 uint32_t alive4 = 0;
+                uint4 ac[4];   // the tile's operand pieces (decoded from the 8-bit codes if that is how they are stored)
+                if constexpr (CF8) {
+                    lvr_codes_to_a_frags(av[u], ac);
+                } else {
+#pragma unroll
+                    for (int kk = 0; kk < 4; ++kk) ac[kk] = av[u][kk];
+                }
 #pragma unroll
                 for (int hb = 0; hb < HB; ++hb) {
                     if constexpr (Q1) {
@@ -192,7 +203,7 @@ query_fused_kernel(const FusedArgs a) {
                         auto block = [&](auto s_c) {
                             constexpr int s = decltype(s_c)::value;
                             constexpr int KPS = 4 / S;
-                            const lvr_f32x4 sc = lvr_score_tile_block<s * KPS, (s + 1) * KPS>(av[u], bq[hb]);
+                            const lvr_f32x4 sc = lvr_score_tile_block<s * KPS, (s + 1) * KPS>(ac, bq[hb]);
 #pragma unroll
                             for (int j = 0; j < 4; ++j) okb[j] = okb[j] && (sc[j] + rad[u][j][s] * qn[hb][s] >= taus[hb][s]);
                         };
@@ -213,11 +224,11 @@ query_fused_kernel(const FusedArgs a) {
                     lvr_f32x4 sc;
                     if constexpr (RM) {
                         const lvr_bf16x8 ra = lvr_radius_a_frag<S>(rrow[u]);
-                        if constexpr (ENC) sc = lvr_bound_tile2(av[u], bq[hb], av2[u], bq2[hb], ra, rbq[hb]);
-                        else sc = lvr_bound_tile(av[u], bq[hb], ra, rbq[hb]);
+                        if constexpr (ENC) sc = lvr_bound_tile2(ac, bq[hb], av2[u], bq2[hb], ra, rbq[hb]);
+                        else sc = lvr_bound_tile(ac, bq[hb], ra, rbq[hb]);
                     } else {
-                        if constexpr (ENC) sc = lvr_score_tile2(av[u], bq[hb], av2[u], bq2[hb]);
-                        else sc = lvr_score_tile(av[u], bq[hb]);
+                        if constexpr (ENC) sc = lvr_score_tile2(ac, bq[hb], av2[u], bq2[hb]);
+                        else sc = lvr_score_tile(ac, bq[hb]);
                     }
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
@@ -425,15 +436,38 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
     const bool one = tpw == 1;
     if (tau_s) {   // Query 1: per-block thresholds
         const int S = ix->cfg.n_subspaces;
+#define LVR_Q1_LAUNCH(HB, CF8)                                                                                  \
+    do {                                                                                                        \
+        if (S == 1) hipLaunchKernelGGL((query_fused_kernel<HB, 1, 1, 0, 1, CF8>), grid, dim3(256), 0, st, a);   \
+        else if (S == 2) hipLaunchKernelGGL((query_fused_kernel<HB, 2, 1, 0, 1, CF8>), grid, dim3(256), 0, st, a); \
+        else hipLaunchKernelGGL((query_fused_kernel<HB, 4, 1, 0, 1, CF8>), grid, dim3(256), 0, st, a);          \
+    } while (0)
         if (ix->G <= 4) {
-            if (S == 1) hipLaunchKernelGGL((query_fused_kernel<1, 1, 1, 0, 1>), grid, dim3(256), 0, st, a);
-            else if (S == 2) hipLaunchKernelGGL((query_fused_kernel<1, 2, 1, 0, 1>), grid, dim3(256), 0, st, a);
-            else hipLaunchKernelGGL((query_fused_kernel<1, 4, 1, 0, 1>), grid, dim3(256), 0, st, a);
+            if (ix->cf8) LVR_Q1_LAUNCH(1, 1);
+            else LVR_Q1_LAUNCH(1, 0);
         } else {
-            if (S == 1) hipLaunchKernelGGL((query_fused_kernel<2, 1, 1, 0, 1>), grid, dim3(256), 0, st, a);
-            else if (S == 2) hipLaunchKernelGGL((query_fused_kernel<2, 2, 1, 0, 1>), grid, dim3(256), 0, st, a);
-            else hipLaunchKernelGGL((query_fused_kernel<2, 4, 1, 0, 1>), grid, dim3(256), 0, st, a);
+            if (ix->cf8) LVR_Q1_LAUNCH(2, 1);
+            else LVR_Q1_LAUNCH(2, 0);
         }
+#undef LVR_Q1_LAUNCH
+        return hipGetLastError();
+    }
+    if (ix->cf8) {   // 8-bit centres
+        const int S = ix->cfg.n_subspaces;
+#define LVR_F8_LAUNCH(HB, UA)                                                                                 \
+    do {                                                                                                      \
+        if (S == 1) hipLaunchKernelGGL((query_fused_kernel<HB, 1, UA, 0, 0, 1>), grid, dim3(256), 0, st, a);  \
+        else if (S == 2) hipLaunchKernelGGL((query_fused_kernel<HB, 2, UA, 0, 0, 1>), grid, dim3(256), 0, st, a); \
+        else hipLaunchKernelGGL((query_fused_kernel<HB, 4, UA, 0, 0, 1>), grid, dim3(256), 0, st, a);         \
+    } while (0)
+        if (ix->G <= 4) {
+            if (one) LVR_F8_LAUNCH(1, 1);
+            else LVR_F8_LAUNCH(1, 2);
+        } else {
+            if (one) LVR_F8_LAUNCH(2, 1);
+            else LVR_F8_LAUNCH(2, 2);
+        }
+#undef LVR_F8_LAUNCH
         return hipGetLastError();
     }
     if (ix->box) {   // boxes: one allowance per group, one tile (two rows per group) per trip

@@ -228,7 +228,7 @@ def test_index_balls_enclose_members(G, oracle):
     cache = _small_cache(2, n)
     for dtype, Kc in (("bf16", cache.K), ("f32", W.make_cache(1, n=n).K)):
         hkv = Kc.shape[1]
-        with G.Index(Kc, Kc, dtype, hkv, group_size=r, n_subspaces=S) as ix:
+        with G.Index(Kc, Kc, dtype, hkv, group_size=r, n_subspaces=S, index_dtype=G.L.LVR_INDEX_SAME) as ix:
             centres, radii, slot_pos, keys = ix.export()
             for h in range(hkv):
                 c = W.bf16_bits_to_f32(centres[0, h]).reshape(n // r, 128) if dtype == "bf16" else centres[0, h]
@@ -756,7 +756,8 @@ def _exported_bounds(G, oracle, ix, q, r):
 @pytest.mark.parametrize("S,keys,hq", [(1, "local", 4), (2, "local", 4), (4, "local", 4), (1, "workload", 4),
                                        (2, "workload", 4), (4, "workload", 4), (2, "local", 8), (4, "local", 2),
                                        (4, "workload", 1)])
-def test_query1_per_subspace_thresholds(G, oracle, S, keys, hq):
+@pytest.mark.parametrize("centres", ["fp8", "same"])
+def test_query1_per_subspace_thresholds(G, oracle, S, keys, hq, centres):
     """Safe thresholds (tau_s = tau minus the largest bounds of the other blocks) must give
     Problem 1's set; arbitrary thresholds must give a set between Alg. 3's candidates (oracle's
     Query 1 on the exported index, thresholds nudged by rounding) filtered at tau, and every key
@@ -765,8 +766,9 @@ def test_query1_per_subspace_thresholds(G, oracle, S, keys, hq):
     cache = W.make_local_cache(2, n=n) if keys == "local" else W.make_cache(2, n=n)
     K, V = cache.K[:, :1], cache.V[:, :1]
     q = W.make_queries(2, n_q_heads=hq)
-    G.say(f"query1 S={S} keys={keys} heads={hq}")
-    with G.Index(K, V, "bf16", hq, group_size=r, n_subspaces=S) as ix:
+    G.say(f"query1 S={S} keys={keys} heads={hq} centres={centres}")
+    idt = G.L.LVR_INDEX_FP8 if centres == "fp8" else G.L.LVR_INDEX_SAME
+    with G.Index(K, V, "bf16", hq, group_size=r, n_subspaces=S, index_dtype=idt) as ix:
         n_groups = n // r
         f = _exported_bounds(G, oracle, ix, q, r)                      # [hq][S][groups]
         label = np.tile(np.arange(n_groups * r, dtype=np.int32) // r, (S, 1))
@@ -927,3 +929,145 @@ def test_append_decode_step_equals_the_two_calls(G, oracle, variant):
             assert np.array_equal(np.asarray(x), np.asarray(y)), name
         if variant == "reservoir":
             assert np.array_equal(ix.reservoir(), ref.reservoir())
+
+
+# ---------------------------------------------------------------------------------------------
+# Centres stored as 8-bit e4m3 codes (LVR_INDEX_FP8)
+# ---------------------------------------------------------------------------------------------
+def _e4m3_values():
+    v = []
+    for code in range(127):                      # 0x7f is the NaN code
+        e, m = code >> 3, code & 7
+        v.append((m / 8.0) * 2.0 ** -6 if e == 0 else (1 + m / 8.0) * 2.0 ** (e - 7))
+    return np.array(sorted(set(v + [-x for x in v])))
+
+
+@pytest.mark.parametrize("S", [1, 2, 4])
+def test_fp8_centres_enclose_members(G, oracle, S):
+    """Exported 8-bit index: every stored centre coordinate is an e4m3 value and the nearest one
+    to the group mean (ties aside), the balls enclose their members measured against the centres
+    AS STORED, and are not looser than the documented widening."""
+    n, r = 2048, 4
+    cache = _small_cache(2, n)
+    Kc = cache.K
+    with G.Index(Kc, Kc, "bf16", 2, group_size=r, n_subspaces=S, index_dtype=G.L.LVR_INDEX_FP8) as ix:
+        centres, radii, slot_pos, keys = ix.export()
+        grid = _e4m3_values()
+        for h in range(2):
+            c = W.bf16_bits_to_f32(centres[0, h]).reshape(n // r, 128).astype(np.float64)
+            assert np.isin(c, grid).all(), "a stored centre coordinate is not an e4m3 value"
+            label = (np.arange(n) // r).astype(np.int32)
+            mean, _ = oracle.ball_index(Kc[0, h], label, n // r, S)
+            mean = np.clip(mean, -448, 448)
+            # nearest grid value: no other e4m3 value is closer to the mean (up to the fp32 error of the mean)
+            pos = np.searchsorted(grid, mean)
+            lo = grid[np.clip(pos - 1, 0, grid.size - 1)]
+            hi = grid[np.clip(pos, 0, grid.size - 1)]
+            best = np.minimum(np.abs(mean - lo), np.abs(mean - hi))
+            assert np.all(np.abs(c - mean) <= best + 1e-6 * np.abs(mean) + 1e-12)
+            need = oracle.ball_radii_for_centres(Kc[0, h], label, c, S)
+            assert np.all(radii[0, h] >= need), "a member lies outside its ball"
+            cn = np.stack([np.linalg.norm(c[:, a:b], axis=1)
+                           for a, b in (oracle.subspace_range(128, S, s) for s in range(S))], axis=1)
+            assert np.all(radii[0, h] <= need * (1 + 2.0 ** -11) + cn * 2.0 ** -11 + 1e-30)
+            assert np.array_equal(keys[0, h], W.f32_to_bf16_bits(Kc[0, h]).reshape(n, 128))
+
+
+@pytest.mark.parametrize("n,r,S,hq,grouping", [(1000, 4, 4, 8, "contiguous"), (2051, 4, 4, 16, "contiguous"),
+                                               (777, 8, 2, 4, "tree"), (4096, 2, 1, 8, "contiguous"), (3, 4, 4, 8, "contiguous")])
+def test_fp8_centres_queries(G, oracle, n, r, S, hq, grouping):
+    L = G.L
+    cache = _small_cache(2, n)
+    q = W.make_queries(2, n_q_heads=hq)
+    gr = L.LVR_GROUP_TREE if grouping == "tree" else L.LVR_GROUP_CONTIGUOUS
+    G.say(f"fp8 centres n={n} r={r} S={S} hq={hq} {grouping}")
+    with G.Index(cache.K, cache.V, "bf16", hq, group_size=r, n_subspaces=S, grouping=gr,
+                 index_dtype=L.LVR_INDEX_FP8) as ix:
+        for frac in (0.01, 0.2):
+            tau = G.oracle_taus(oracle, ix, q, frac=frac)
+            for fused in (True, False):
+                idx, cnt, out = ix.query(q, tau, fused=fused)
+                G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=f"fp8 n={n} frac={frac}")
+        st = ix.stats()
+        assert st["bytes_index"] == st["groups_scored"] * (128 + 4 * S)
+
+
+@pytest.mark.parametrize("S", [1, 4])
+def test_fp8_centres_surviving_groups_and_pruning(G, oracle, S):
+    """On keys with positional locality: the groups kept equal those whose Eq. (2) bound on the
+    exported 8-bit index reaches tau; coarser centres keep somewhat more groups than bf16 centres,
+    never fewer qualifying keys."""
+    n, r = 8192, 4
+    cache = W.make_local_cache(2, n=n)
+    K, V = cache.K[:, :1], cache.V[:, :1]
+    q = W.make_queries(2, n_q_heads=4)
+    with G.Index(K, V, "bf16", 4, group_size=r, n_subspaces=S, index_dtype=G.L.LVR_INDEX_FP8) as ix, \
+         G.Index(K, V, "bf16", 4, group_size=r, n_subspaces=S, index_dtype=G.L.LVR_INDEX_SAME) as ref:
+        centres, radii, _, _ = ix.export()
+        c = W.bf16_bits_to_f32(centres[0, 0]).reshape(n // r, 128).astype(np.float64)
+        for frac in (0.002, 0.02):
+            t = G.oracle_taus(oracle, ix, q, frac=frac)
+            idx, cnt, out = ix.query(q, t)
+            G.check_step(oracle, ix, q, t, idx, cnt, out, tag=f"fp8 local frac={frac}")
+            st = ix.stats()
+            ref.query(q, t)
+            st_ref = ref.stats()
+            ub = np.stack([oracle.ball_bounds(q[0, h], c, radii[0, 0].astype(np.float64)).sum(0) for h in range(4)])
+            te = t[0] - 0.5e-4 * np.abs(t[0])
+            lo = int(np.any(ub >= te[:, None] * (1 + 1e-5) + 1e-3, axis=0).sum())
+            hi = int(np.any(ub >= te[:, None] * (1 - 1e-5) - 1e-3, axis=0).sum())
+            assert lo <= st["groups_surviving"] <= hi, (frac, lo, st["groups_surviving"], hi)
+            G.say(f"  S={S} frac={frac}: surviving with 8-bit centres {st['groups_surviving']}, with bf16 centres "
+                  f"{st_ref['groups_surviving']} of {st['groups_scored']}")
+            assert st["groups_surviving"] < 0.5 * st["groups_scored"]
+            assert st["bytes_index"] < 0.6 * st_ref["bytes_index"]
+
+
+def test_fp8_centres_surface_keys_saturation_and_append(G, oracle):
+    """Keys exactly on ball surfaces, coordinates beyond the e4m3 range (the centre saturates, the
+    radius takes up the difference), appends across flushes: nothing is ever lost."""
+    L = G.L
+    g = np.random.default_rng(12)
+    n, r = 512, 4
+    qdir = np.zeros(128, dtype=np.float32)
+    qdir[[3, 40, 77, 120]] = [1.0, -1.0, 1.0, 1.0]
+    K = np.zeros((1, 1, n, 128), dtype=np.float32)
+    for gi in range(n // r):
+        centre = W.round_to_bf16(g.integers(-8, 9, size=128).astype(np.float32))
+        if gi % 7 == 0:
+            centre[5] = 1000.0          # beyond 448
+            centre[99] = -3000.0
+        step = float(g.integers(1, 5)) * 0.5
+        K[0, 0, gi * r + 0] = centre + step * qdir
+        K[0, 0, gi * r + 1] = centre - step * qdir
+        K[0, 0, gi * r + 2] = centre
+        K[0, 0, gi * r + 3] = centre
+    K = W.round_to_bf16(K)
+    V = W.round_to_bf16(g.standard_normal((1, 1, n, 128)).astype(np.float32))
+    q = (qdir * 3.0)[None, None, :]
+    for S in (1, 4):
+        with G.Index(K[:, :, :300], V[:, :, :300], "bf16", 1, n_subspaces=S, capacity=n, buffer_size=32,
+                     index_dtype=L.LVR_INDEX_FP8) as ix:
+            ix.append(K[:, :, 300:], V[:, :, 300:])
+            s = oracle.scores_f32(q[0, 0], K[0, 0])
+            for tau in np.unique(s)[-6:]:
+                t = np.full((1, 1), tau, dtype=np.float32)
+                idx, cnt, out = ix.query(q, t)
+                G.check_step(oracle, ix, q, t, idx, cnt, out, tag=f"fp8 surface S={S} tau={tau}")
+
+
+def test_fp8_centres_unsupported_configurations(G):
+    L = G.L
+    ok = dict(batch=1, n_q_heads=8, n_kv_heads=2, capacity=1024, index_dtype=L.LVR_INDEX_FP8)
+    assert L.lvr_arena_bytes(L.make_config(**ok)) > 0
+    for bad in (dict(ok, kv_dtype=L.LVR_F32), dict(ok, enclosing=L.LVR_ENCLOSE_AABB), dict(ok, n_subspaces=8),
+                dict(ok, flags=L.LVR_SEPARATE_KERNELS), dict(ok, index_dtype=3)):
+        assert L.lvr_arena_bytes(L.make_config(**bad)) == 0
+    # AUTO falls back to the cache's own format where 8-bit centres are not supported
+    for kw in (dict(n_subspaces=8), dict(flags=L.LVR_SEPARATE_KERNELS), dict(enclosing=L.LVR_ENCLOSE_AABB)):
+        cfg_auto = L.make_config(batch=1, n_q_heads=8, n_kv_heads=2, capacity=1024, **kw)
+        cfg_same = L.make_config(batch=1, n_q_heads=8, n_kv_heads=2, capacity=1024, index_dtype=L.LVR_INDEX_SAME, **kw)
+        assert L.lvr_arena_bytes(cfg_auto) == L.lvr_arena_bytes(cfg_same) > 0
+    cfg_auto = L.make_config(batch=1, n_q_heads=8, n_kv_heads=2, capacity=1024)
+    cfg_same = L.make_config(batch=1, n_q_heads=8, n_kv_heads=2, capacity=1024, index_dtype=L.LVR_INDEX_SAME)
+    assert L.lvr_arena_bytes(cfg_same) - L.lvr_arena_bytes(cfg_auto) == 2 * (1024 // 4) * 128
