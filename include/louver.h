@@ -56,7 +56,7 @@ enum lvr_enclosing { LVR_ENCLOSE_BALL = 0, LVR_ENCLOSE_AABB = 1 };
  *   FP8:  OCP e4m3 codes (1 sign, 4 exponent, 3 mantissa bits), 1 byte per coordinate: the index
  *         read of a query halves.  bf16 caches, ball enclosure, n_subspaces <= 4, fused query
  *         kernel (LVR_E_UNSUPPORTED otherwise).
- *   AUTO: FP8 where it is supported, else SAME. */
+ *   AUTO: FP8 where it is supported and K/V are in device memory, else SAME. */
 enum lvr_index_dtype { LVR_INDEX_AUTO = 0, LVR_INDEX_SAME = 1, LVR_INDEX_FP8 = 2 };
 
 enum lvr_flags {

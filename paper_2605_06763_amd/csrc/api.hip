@@ -30,8 +30,12 @@ inline bool fp8_centres_supported(const lvr_config *c) {
            c->n_subspaces <= 4;
 }
 
+// AUTO: 8-bit centres halve the index read, at the price of somewhat larger balls.  That pays when the
+// surviving key rows come from HBM; behind the host link a key row costs a hundred times more than an
+// index byte, so the tighter centres in the cache's own format are kept there.
 inline bool fp8_centres(const lvr_config *c) {
-    return c->index_dtype == LVR_INDEX_FP8 || (c->index_dtype == LVR_INDEX_AUTO && fp8_centres_supported(c));
+    return c->index_dtype == LVR_INDEX_FP8 ||
+           (c->index_dtype == LVR_INDEX_AUTO && fp8_centres_supported(c) && !(c->flags & LVR_KV_IN_HOST_MEMORY));
 }
 
 int check_config(const lvr_config *c) {
