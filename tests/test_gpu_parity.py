@@ -852,7 +852,7 @@ def test_offloaded_kv_same_results(G, oracle, grouping, flags):
     K, V = cache.K[:, :2], cache.V[:, :2]
     q = W.make_queries(2, n_q_heads=8)
     G.say(f"offloaded grouping={grouping} flags={flags}")
-    kw = dict(capacity=n0 + extra, buffer_size=B, grouping=gr)
+    kw = dict(capacity=n0 + extra, buffer_size=B, grouping=gr, index_dtype=L.LVR_INDEX_SAME)
     with G.Index(K[:, :, :n0], V[:, :, :n0], "bf16", 8, flags=flags | L.LVR_KV_IN_HOST_MEMORY, **kw) as ix, \
          G.Index(K[:, :, :n0], V[:, :, :n0], "bf16", 8, flags=flags, **kw) as ref:
         kv_bytes = 2 * 2 * ((n0 + extra + 63) // 64 * 64) * 128 * 2
@@ -878,6 +878,13 @@ def test_offloaded_kv_same_results(G, oracle, grouping, flags):
         L.lvr_publish(ref.h)
         for name, x, y in zip(("centres", "radii", "slot_pos", "keys"), ix.export(), ref.export()):
             assert np.array_equal(np.asarray(x), np.asarray(y)), name
+    # the default centre format: 8-bit in device memory, the cache's own behind the host link
+    auto_dev = L.make_config(batch=1, n_q_heads=8, n_kv_heads=2, capacity=1024)
+    auto_host = L.make_config(batch=1, n_q_heads=8, n_kv_heads=2, capacity=1024, flags=L.LVR_KV_IN_HOST_MEMORY)
+    same_host = L.make_config(batch=1, n_q_heads=8, n_kv_heads=2, capacity=1024, flags=L.LVR_KV_IN_HOST_MEMORY,
+                              index_dtype=L.LVR_INDEX_SAME)
+    assert L.lvr_arena_bytes(auto_host) == L.lvr_arena_bytes(same_host)
+    assert L.lvr_arena_bytes(auto_dev) - 2 * L.lvr_host_bytes(auto_host) // 2 == L.lvr_arena_bytes(auto_host) - 2 * (1024 // 4) * 128
 
 
 # ---------------------------------------------------------------------------------------------
