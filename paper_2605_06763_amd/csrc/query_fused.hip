@@ -254,14 +254,16 @@ query_fused_kernel(const FusedArgs a) {
                         alive4 |= ok ? (1u << j) : 0u;
                     }
                 }
-                uint32_t mask16 = 0;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint64_t bal = __ballot((alive4 >> j) & 1u);
-#pragma unroll
-                    for (int qd = 0; qd < 4; ++qd)
-                        mask16 |= ((bal >> (16 * qd)) & 0xffffull) ? (1u << (4 * qd + j)) : 0u;
-                }
+                // "some head keeps the group": OR over the four lanes of a quarter that hold the heads' bits
+                // (lanes 8..11 of each row of 16; the other lanes hold zero), then the four quarters' nibbles
+                // are read off lane 11 of each row into one 16-bit mask (bit 4*kq + j = group 4*kq + j of the tile)
+                uint32_t v = alive4;
+                v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, true);   // row_shr:1
+                v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, true);   // row_shr:2
+                const uint32_t mask16 = (uint32_t)__builtin_amdgcn_readlane((int)v, 11) |
+                                        ((uint32_t)__builtin_amdgcn_readlane((int)v, 27) << 4) |
+                                        ((uint32_t)__builtin_amdgcn_readlane((int)v, 43) << 8) |
+                                        ((uint32_t)__builtin_amdgcn_readlane((int)v, 59) << 12);
                 if (lane == it + u) mybits = mask16;
             }
         }
