@@ -88,7 +88,7 @@ Sizes sizes_of(const lvr_config *c) {
     const bool box = c->enclosing == LVR_ENCLOSE_AABB;
     const size_t c_elt = fp8_centres(c) ? 1 : elt;
     s.centres = al((size_t)n_bh * s.max_groups * LVR_D * c_elt * (box ? 2 : 1));
-    s.radii = al((size_t)n_bh * s.max_groups * (box ? 1 : c->n_subspaces) * sizeof(float));
+    s.radii = al((size_t)n_bh * s.max_groups * (box ? 1 : (fp8_centres(c) ? 4 : c->n_subspaces)) * sizeof(float));
     s.list = al((size_t)n_bh * s.max_groups * sizeof(int32_t));
     s.counters = al(lvr_counter_ints((int)n_bh, (int)n_bhq, s.max_groups) * sizeof(int32_t));
     s.part_ml = al((size_t)n_bhq * s.Pmax * 2 * sizeof(float));
@@ -226,8 +226,8 @@ int lvr_create(const lvr_config *cfg, lvr_index **out) {
     const Sizes s = sizes_of(cfg);
     ix->G = cfg->n_q_heads / cfg->n_kv_heads;
     ix->box = cfg->enclosing == LVR_ENCLOSE_AABB;
-    ix->S_store = ix->box ? 1 : cfg->n_subspaces;
     ix->cf8 = fp8_centres(cfg);
+    ix->S_store = ix->box ? 1 : (ix->cf8 ? 4 : cfg->n_subspaces);   // 8-bit centres: 16 bytes of pre-split radii per group
     ix->cap_rows = s.cap_rows;
     ix->max_groups = s.max_groups;
     ix->P = s.P;
@@ -701,7 +701,26 @@ int lvr_export_index(lvr_index *ix, void *centres, float *radii, int32_t *slot_p
             LVR_HIP(hipMemcpy(static_cast<char *>(centres) + (size_t)bh * ng * crow,
                               static_cast<char *>(ix->centres) + (size_t)bh * ix->max_groups * crow,
                               (size_t)ng * crow, hipMemcpyDeviceToHost));
-        if (radii && ng > 0)
+        if (radii && ng > 0 && ix->cf8) {
+            // pre-split radii (eight bf16 per group, slot k = part*S' + s) -> one float per subspace
+            const int Ss = ix->cfg.n_subspaces;
+            uint16_t *blk = static_cast<uint16_t *>(malloc((size_t)ng * 16));
+            if (!blk) return LVR_E_NOMEM;
+            hipError_t e = hipMemcpy(blk, ix->radii + (size_t)bh * ix->max_groups * 4, (size_t)ng * 16, hipMemcpyDeviceToHost);
+            if (e != hipSuccess) {
+                free(blk);
+                return hip_fail(e);
+            }
+            for (int64_t g = 0; g < ng; ++g)
+                for (int sidx = 0; sidx < Ss; ++sidx) {
+                    const uint32_t hi = (uint32_t)blk[g * 8 + sidx] << 16, mid = (uint32_t)blk[g * 8 + Ss + sidx] << 16;
+                    float fh, fm;
+                    memcpy(&fh, &hi, 4);
+                    memcpy(&fm, &mid, 4);
+                    radii[((size_t)bh * ng + g) * Ss + sidx] = fh + fm;
+                }
+            free(blk);
+        } else if (radii && ng > 0)
             LVR_HIP(hipMemcpy(radii + (size_t)bh * ng * S, ix->radii + (size_t)bh * ix->max_groups * S,
                               (size_t)ng * S * sizeof(float), hipMemcpyDeviceToHost));
         if (keys && n > 0)

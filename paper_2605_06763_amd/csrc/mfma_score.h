@@ -187,7 +187,8 @@ __device__ __forceinline__ lvr_bf16x8 lvr_radius_a_frag(const float (&rho)[S]) {
 }
 
 // qn_group: [heads][16] floats, |pi_s q_h| for s < S (already rounded up); head block hb.
-template <int S>
+// NP = bf16 terms per radius on the A side (3: split on the fly; 2: stored pre-split).
+template <int S, int NP = 3>
 __device__ __forceinline__ lvr_bf16x8 lvr_radius_b_frag(const float (*qn_group)[16], int G, int hb) {
     const int lane = threadIdx.x & 63;
     const int n = lane & 15, kq = lane >> 4;
@@ -203,12 +204,24 @@ __device__ __forceinline__ lvr_bf16x8 lvr_radius_b_frag(const float (*qn_group)[
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
             const int k = 8 * q4 + j;
-            if (k < 3 * S) v = (kq == q4) ? val[k % S] : v;
+            if (k < NP * S) v = (kq == q4) ? val[k % S] : v;
         }
         w[j] = v;
     }
     uint4 packed = make_uint4(w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16));
     return __builtin_bit_cast(lvr_bf16x8, packed);
+}
+
+// Radii stored pre-split (eight bf16 per group, slot k = part*S + s, two parts): the block IS the
+// operand piece of the lanes with kq = 0; the other lanes contribute zeros.
+__device__ __forceinline__ lvr_bf16x8 lvr_radius_a_stored(const uint4 &block) {
+    const bool first = ((threadIdx.x & 63) >> 4) == 0;
+    uint4 r;
+    r.x = first ? block.x : 0u;
+    r.y = first ? block.y : 0u;
+    r.z = first ? block.z : 0u;
+    r.w = first ? block.w : 0u;
+    return __builtin_bit_cast(lvr_bf16x8, r);
 }
 
 // Bound of a tile of 16 balls: centre product plus the radius step.

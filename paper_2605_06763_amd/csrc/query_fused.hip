@@ -75,7 +75,7 @@ query_fused_kernel(const FusedArgs a) {
     constexpr int SP = (S <= 4) ? S : 1;      // radii are fetched ahead only when they are few
     // balls: one row per group (the centre); boxes: two rows per group (upper corner, lower corner)
     const char *Cb = static_cast<const char *>(a.centres) + (int64_t)bh * a.max_groups * LVR_D * (CF8 ? 1 : 2) * (ENC ? 2 : 1);
-    const float *Rb = a.radii + (int64_t)bh * a.max_groups * S;
+    const float *Rb = a.radii + (int64_t)bh * a.max_groups * (CF8 ? 4 : S);   // 8-bit centres: 16 bytes of pre-split radii per group
     const int64_t n_tiles = (a.n_groups + 15) >> 4;
     const int64_t tile0 = ((int64_t)blockIdx.x * 4 + wave) * a.tiles_per_wave;
     // RM: the radius term rides on the matrix cores as a fifth step (S <= 4, one threshold per head);
@@ -84,7 +84,8 @@ query_fused_kernel(const FusedArgs a) {
     constexpr bool RM = !Q1 && S <= 4;
     uint4 av[UA][CF8 ? 2 : 4], av2[ENC ? UA : 1][4];
     float rad[RM ? 1 : UA][4][SP];
-    float rrow[RM ? UA : 1][SP];
+    float rrow[(RM && !CF8) ? UA : 1][SP];
+    uint4 rblk[(RM && CF8) ? UA : 1];
     auto issueA = [&](int it) {
 #pragma unroll
         for (int u = 0; u < UA; ++u) {
@@ -99,7 +100,9 @@ query_fused_kernel(const FusedArgs a) {
             } else {
                 lvr_load_a_frags(Cb, g, av[u]);
             }
-            if constexpr (RM) {
+            if constexpr (RM && CF8) {
+                rblk[u] = reinterpret_cast<const uint4 *>(Rb)[g];
+            } else if constexpr (RM) {
                 const float *rp = Rb + g * S;
                 if constexpr (S == 4) {
                     const float4 r = *reinterpret_cast<const float4 *>(rp);
@@ -114,7 +117,16 @@ query_fused_kernel(const FusedArgs a) {
                     int64_t gj = g0 + 4 * kq + j;
                     if (gj >= a.n_groups) gj = a.n_groups - 1;
                     const float *rp = Rb + gj * S;
-                    if constexpr (S == 4) {
+                    if constexpr (CF8) {   // pre-split radii: rho_s = slot s + slot S+s (exact in fp32)
+                        const uint4 blk = reinterpret_cast<const uint4 *>(Rb)[gj];
+                        const uint32_t w[4] = {blk.x, blk.y, blk.z, blk.w};
+#pragma unroll
+                        for (int s = 0; s < S; ++s) {
+                            const uint32_t hi = (w[s / 2] >> (16 * (s & 1))) << 16;
+                            const uint32_t mid = (w[(S + s) / 2] >> (16 * ((S + s) & 1))) << 16;
+                            rad[u][j][s] = __uint_as_float(hi) + __uint_as_float(mid);
+                        }
+                    } else if constexpr (S == 4) {
                         const float4 r = *reinterpret_cast<const float4 *>(rp);
                         rad[u][j][0] = r.x; rad[u][j][1] = r.y; rad[u][j][2] = r.z; rad[u][j][3] = r.w;
                     } else {
@@ -151,7 +163,7 @@ query_fused_kernel(const FusedArgs a) {
     if constexpr (RM) {
         if (!buffer_wg) {
 #pragma unroll
-            for (int hb = 0; hb < HB; ++hb) rbq[hb] = lvr_radius_b_frag<S>(s_qn, a.G, hb);
+            for (int hb = 0; hb < HB; ++hb) rbq[hb] = lvr_radius_b_frag<S, CF8 ? 2 : 3>(s_qn, a.G, hb);
         }
     }
     float taue[HB];
@@ -215,15 +227,15 @@ query_fused_kernel(const FusedArgs a) {
                         }
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
-                            const bool ok = rep[hb] && okb[j] && (g_row + 4 * kq + j) < a.n_groups &&
-                                            (it + u) < a.tiles_per_wave;
-                            alive4 |= ok ? (1u << j) : 0u;
+                            alive4 |= okb[j] ? (1u << j) : 0u;   // lanes that report no head compare against +inf
                         }
                         continue;
                     }
                     lvr_f32x4 sc;
                     if constexpr (RM) {
-                        const lvr_bf16x8 ra = lvr_radius_a_frag<S>(rrow[u]);
+                        lvr_bf16x8 ra;
+                        if constexpr (CF8) ra = lvr_radius_a_stored(rblk[u]);
+                        else ra = lvr_radius_a_frag<S>(rrow[u]);
                         if constexpr (ENC) sc = lvr_bound_tile2(ac, bq[hb], av2[u], bq2[hb], ra, rbq[hb]);
                         else sc = lvr_bound_tile(ac, bq[hb], ra, rbq[hb]);
                     } else {
@@ -249,9 +261,7 @@ query_fused_kernel(const FusedArgs a) {
                                       r.w * qn[hb][4 * s4 + 3];
                             }
                         }
-                        const bool ok = rep[hb] && ub >= taue[hb] && (g_row + 4 * kq + j) < a.n_groups &&
-                                        (it + u) < a.tiles_per_wave;
-                        alive4 |= ok ? (1u << j) : 0u;
+                        alive4 |= (ub >= taue[hb]) ? (1u << j) : 0u;   // lanes that report no head compare against +inf
                     }
                 }
                 // "some head keeps the group": OR over the four lanes of a quarter that hold the heads' bits
@@ -264,7 +274,11 @@ query_fused_kernel(const FusedArgs a) {
                                         ((uint32_t)__builtin_amdgcn_readlane((int)v, 27) << 4) |
                                         ((uint32_t)__builtin_amdgcn_readlane((int)v, 43) << 8) |
                                         ((uint32_t)__builtin_amdgcn_readlane((int)v, 59) << 12);
-                if (lane == it + u) mybits = mask16;
+                // groups past the end of the index, tiles past the wave's share: a wave-uniform mask
+                const int64_t left = a.n_groups - g_row;
+                const uint32_t valid16 = (it + u) >= a.tiles_per_wave || left <= 0 ? 0u
+                                         : (left >= 16 ? 0xffffu : ((1u << (int)left) - 1u));
+                if (lane == it + u) mybits = mask16 & valid16;
             }
         }
         // compaction of the four waves' masks into the LDS list
