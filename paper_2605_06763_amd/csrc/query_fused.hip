@@ -82,11 +82,20 @@ query_fused_kernel(const FusedArgs a) {
     // a lane then needs only its own row's radii.  Otherwise the lanes that hold the scores fetch
     // the radii of their four rows and add the terms on the vector ALU.
     constexpr bool RM = !Q1 && S <= 4;
-    uint4 av[UA][CF8 ? 2 : 4], av2[ENC ? UA : 1][4];
-    float rad[RM ? 1 : UA][4][SP];
-    float rrow[(RM && !CF8) ? UA : 1][SP];
-    uint4 rblk[(RM && CF8) ? UA : 1];
-    auto issueA = [&](int it) {
+    // operands of one trip (UA tiles of 16 groups) as they arrive from HBM
+    struct Trip {
+        uint4 av[UA][CF8 ? 2 : 4], av2[ENC ? UA : 1][4];
+        float rad[RM ? 1 : UA][4][SP];
+        float rrow[(RM && !CF8) ? UA : 1][SP];
+        uint4 rblk[(RM && CF8) ? UA : 1];
+    };
+    // 8-bit centres leave room for two trips in registers: the next trip's loads are issued before
+    // the current trip is scored, so the memory pipe does not drain between trips
+    constexpr bool DB = CF8 && !Q1;
+    Trip t0, t1;
+    auto issueA = [&](Trip &T, int it) {
+        auto &av = T.av; auto &av2 = T.av2; auto &rad = T.rad; auto &rrow = T.rrow; auto &rblk = T.rblk;
+        (void)av2; (void)rad; (void)rrow; (void)rblk;
 #pragma unroll
         for (int u = 0; u < UA; ++u) {
             const int64_t g0 = (tile0 + it + u) * 16;
@@ -138,7 +147,7 @@ query_fused_kernel(const FusedArgs a) {
         }
     };
     const bool phaseA = !buffer_wg && tile0 < n_tiles && a.n_groups > 0;   // wave-uniform
-    if (phaseA) issueA(0);
+    if (phaseA) issueA(t0, 0);
 
     // ---- prologue: subspace norms of q (phase A only) and the B operand of q ----
     if (!buffer_wg && (int)threadIdx.x < HB * 64) {
@@ -193,9 +202,9 @@ query_fused_kernel(const FusedArgs a) {
 #pragma unroll
             for (int s = 0; s < S; ++s) qn[hb][s] = rep[hb] ? s_qn[hb * 4 + n - 8][s] : 0.f;
         uint32_t mybits = 0;   // lane `it` keeps the 16-bit survivor mask of the wave's tile `it`
-        for (int it = 0; it < a.tiles_per_wave; it += UA) {
-            if (tile0 + it >= n_tiles) break;   // wave-uniform
-            if (it > 0) issueA(it);
+        auto scoreA = [&](Trip &T, int it) {
+            auto &av = T.av; auto &av2 = T.av2; auto &rad = T.rad; auto &rrow = T.rrow; auto &rblk = T.rblk;
+            (void)av2; (void)rad; (void)rrow; (void)rblk;
 #pragma unroll
             for (int u = 0; u < UA; ++u) {
                 const int64_t g_row = (tile0 + it + u) * 16;
@@ -279,6 +288,24 @@ query_fused_kernel(const FusedArgs a) {
                 const uint32_t valid16 = (it + u) >= a.tiles_per_wave || left <= 0 ? 0u
                                          : (left >= 16 ? 0xffffu : ((1u << (int)left) - 1u));
                 if (lane == it + u) mybits = mask16 & valid16;
+            }
+        };
+        auto more = [&](int it) { return it < a.tiles_per_wave && tile0 + it < n_tiles; };   // wave-uniform
+        if constexpr (DB) {
+            for (int it = 0; more(it); it += 2 * UA) {
+                const bool m1 = more(it + UA);
+                if (m1) issueA(t1, it + UA);
+                scoreA(t0, it);
+                if (!m1) break;
+                const bool m2 = more(it + 2 * UA);
+                if (m2) issueA(t0, it + 2 * UA);
+                scoreA(t1, it + UA);
+                if (!m2) break;
+            }
+        } else {
+            for (int it = 0; more(it); it += UA) {
+                if (it > 0) issueA(t0, it);
+                scoreA(t0, it);
             }
         }
         // compaction of the four waves' masks into the LDS list
