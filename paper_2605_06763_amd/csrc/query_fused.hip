@@ -148,6 +148,13 @@ query_fused_kernel(const FusedArgs a) {
     };
     const bool phaseA = !buffer_wg && tile0 < n_tiles && a.n_groups > 0;   // wave-uniform
     if (phaseA) issueA(t0, 0);
+    // the thresholds too are asked for before the prologue's barrier; they are needed last
+    float tau_raw[HB];
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) {
+        const int h = hb * 4 + n - 8;
+        tau_raw[hb] = (n >= 8 && n < 12 && h < a.G) ? a.tau[hq0 + h] : INFINITY;
+    }
 
     // ---- prologue: subspace norms of q (phase A only) and the B operand of q ----
     if (!buffer_wg && (int)threadIdx.x < HB * 64) {
@@ -181,7 +188,7 @@ query_fused_kernel(const FusedArgs a) {
     for (int hb = 0; hb < HB; ++hb) {
         const int h = hb * 4 + n - 8;
         rep[hb] = n >= 8 && n < 12 && h < a.G;
-        taue[hb] = rep[hb] ? lvr_effective_tau(a.tau[hq0 + h]) : INFINITY;
+        taue[hb] = rep[hb] ? lvr_effective_tau(tau_raw[hb]) : INFINITY;
     }
     float taus[HB][Q1 ? S : 1];
     if constexpr (Q1) {
