@@ -157,12 +157,18 @@ def main():
         for t in range(T_all):
             s = scores_on_gpu(Kfull[:, :, :n0 + t + 1], q_all[t % n_distinct], G)
             tau_all[t] = s.amax(-1) - c["tau_below_max"]
+            if t % 512 == 511:
+                torch.cuda.synchronize()
+                log(f"[bench] thresholds placed for {t + 1} of {T_all} steps")
         del Kfull
     else:
         kq = int(math.ceil(c["qualify_frac"] * n0))
         tau_all = torch.empty((n_distinct, B, Hq), dtype=torch.float32, device=dev)
         for t in range(n_distinct):
             tau_all[t] = kth_midpoint_tau(scores_on_gpu(Kd, q_all[t], G), kq)
+            if t % 32 == 31:
+                torch.cuda.synchronize()
+                log(f"[bench] thresholds placed for {t + 1} of {n_distinct} queries")
     cap = 4096 if not appending else 8192
     out = torch.zeros((B, Hq, d), dtype=torch.float32, device=dev)
     idx = torch.zeros((B, Hq, cap), dtype=torch.int32, device=dev)
