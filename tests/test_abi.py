@@ -89,3 +89,13 @@ def test_header_is_plain_c(tmp_path):
         assert r.returncode == 0, r.stderr
     text = re.sub(r"/\*.*?\*/", "", open(os.path.join(inc, "louver.h")).read(), flags=re.S)   # declarations only
     assert "hipStream_t" not in text and "torch" not in text and "at::" not in text and "#include <hip" not in text
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; any other --gpus value ends with a message and a non-zero status
+    before anything touches a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
