@@ -191,3 +191,44 @@ def test_config3_threshold_rules_are_stable_over_the_drifting_query(G, oracle):
         G.say(f"  budget(5 %): retrieved share {100 * share:.2f} %")
         assert 0.02 < share < 0.10
         G.check_step(oracle, ix, qs[0], tau, idx, cnt, out, heads=[0, 13, 31], tag="config3 budget(5%)")
+
+
+def test_four_million_keys_per_head(G, oracle):
+    """Largest size exercised: 4 194 304 keys on each of 8 KV heads (a 16 GiB K/V arena, byte offsets
+    far beyond 2^32).  Data is made on the device from a seeded torch generator; the heads of the
+    LAST KV head (the largest offsets) are checked against the oracle on the host copy of its keys."""
+    L = G.L
+    n, hkv, hq, d = 1 << 22, 8, 32, 128
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(20260506)
+    Kd = torch.randn((1, hkv, n, d), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    Vd = torch.randn((1, hkv, n, d), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    q = W.make_queries(3)                                     # [1][32][128], bf16-representable
+    cfg = L.make_config(batch=1, n_q_heads=hq, n_kv_heads=hkv, capacity=n)
+    h = L.lvr_create(cfg)
+    try:
+        L.lvr_build(h, Kd, Vd)
+        g = hkv - 1
+        K_last = Kd[0, g].float().cpu().numpy()
+        V_last = Vd[0, g].float().cpu().numpy()
+        heads = list(range(4 * g, 4 * g + 4))
+        tau = np.full((1, hq), np.inf, dtype=np.float32)      # other heads: nothing qualifies
+        for hh in heads:
+            tau[0, hh] = W.tau_for_count(oracle.scores_f32(q[0, hh], K_last), 500)
+        qd, td = torch.from_numpy(q).cuda(), torch.from_numpy(tau).cuda()
+        out = torch.zeros((1, hq, d), device="cuda")
+        idx = torch.zeros((1, hq, 1024), dtype=torch.int32, device="cuda")
+        cnt = torch.zeros((1, hq), dtype=torch.int32, device="cuda")
+        L.lvr_decode_step(h, qd, td, out, idx, cnt)
+        torch.cuda.synchronize()
+        gi, gc, go = idx.cpu().numpy(), cnt.cpu().numpy(), out.cpu().numpy()
+        assert (gc[0, :4 * g] == 0).all() and np.abs(go[0, :4 * g]).max() == 0.0
+        for hh in heads:
+            r = G.check_head(oracle, q[0, hh], K_last, V_last, tau[0, hh], gi[0, hh], int(gc[0, hh]), go[0, hh],
+                             1.0 / math.sqrt(d), where=f"4M keys head {hh}")
+            assert 500 <= r["size"] <= 510
+            G.say(f"4M keys, head {hh}:", r)
+        st = L.lvr_get_stats(h)
+        assert st["n_keys"] == n and st["n_indexed"] == n and st["groups_scored"] == hkv * n // 4
+    finally:
+        L.lvr_destroy(h)
