@@ -1,5 +1,5 @@
 """The five workloads at their full sizes, in the launch configuration bench.py times
-(r = 4, S = 4, contiguous grouping, fused query kernel, 32 attention splits), checked against
+(r = 4, S = 4, contiguous grouping, 8-bit centres, fused query kernel, default attention form), checked against
 the CPU oracle: every head of every sampled step by the band rule for the retrieved sets and
 against the oracle's attention on the same lists."""
 import math
