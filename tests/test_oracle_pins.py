@@ -573,6 +573,9 @@ def test_threshold_rules_closed_forms(oracle):
     # sorted: 10 9.5 9 | 3 2.5 2 1 0.5  -> largest gap between 9 and 3: tau = 9, three keys qualify
     assert oracle.threshold(s, "sample-gap") == 9.0
     assert (s >= oracle.threshold(s, "sample-gap")).sum() == 3
+    # equal largest gaps: the first one from the top is the cut (sorted 10 | 7 | 4 3: gaps 3, 3, 1)
+    assert oracle.threshold(np.array([4.0, 10.0, 3.0, 7.0], dtype=np.float32), "sample-gap") == 10.0
+    assert oracle.threshold(np.array([5.0], dtype=np.float32), "sample-gap") == 5.0
     for k in (1, 2, 5, 8):
         assert oracle.threshold(s, "sample-topk", k) == np.sort(s)[::-1][k - 1]
     assert oracle.threshold(s, "sample-topk", 100) == 0.5
