@@ -1079,3 +1079,60 @@ def test_fp8_centres_unsupported_configurations(G):
     cfg_auto = L.make_config(batch=1, n_q_heads=8, n_kv_heads=2, capacity=1024)
     cfg_same = L.make_config(batch=1, n_q_heads=8, n_kv_heads=2, capacity=1024, index_dtype=L.LVR_INDEX_SAME)
     assert L.lvr_arena_bytes(cfg_same) - L.lvr_arena_bytes(cfg_auto) == 2 * (1024 // 4) * 128
+
+
+# ---------------------------------------------------------------------------------------------
+# Seeded sweep over combinations of the options
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("case", range(160))
+def test_option_combinations(G, oracle, case):
+    """Group size, subspaces, heads per KV head, grouping, enclosure, centre format, launch form, buffer
+    size and cache size drawn from a seeded generator; every combination the library accepts must give
+    the oracle's sets and attention, before and after appends."""
+    L = G.L
+    g = np.random.default_rng(1000 + case)
+    r = int(g.choice([1, 2, 4, 8, 16]))
+    S = int(g.choice([1, 2, 4, 8, 16]))
+    hkv = int(g.choice([1, 2, 3]))
+    Gq = int(g.choice([1, 2, 4, 8]))
+    hq = hkv * Gq
+    batch = int(g.choice([1, 2]))
+    grouping = int(g.choice([L.LVR_GROUP_CONTIGUOUS, L.LVR_GROUP_TREE]))
+    enclosing = int(g.choice([L.LVR_ENCLOSE_BALL, L.LVR_ENCLOSE_BALL, L.LVR_ENCLOSE_AABB]))
+    index_dtype = int(g.choice([L.LVR_INDEX_AUTO, L.LVR_INDEX_SAME, L.LVR_INDEX_FP8]))
+    flags = int(g.choice([0, 0, L.LVR_SEPARATE_KERNELS, L.LVR_ATTEND_BUFFER_DENSE, L.LVR_CONCURRENT_UPDATE]))
+    attn = int(g.choice([0, -1, 3, 64]))
+    B = 16 * int(g.choice([1, 2, 4])) * (r if r > 1 else 1)
+    n0 = int(g.integers(0, 3000))
+    extra = int(g.integers(0, 3 * B))
+    wl = 1 if case % 5 == 4 else 2          # workload 1 is fp32 with iid keys, workload 2 bf16 with channel scales
+    dtype = W.CONFIGS[wl]["dtype"]
+    cfg = L.make_config(batch=batch, n_q_heads=hq, n_kv_heads=hkv, group_size=r, n_subspaces=S, buffer_size=B,
+                        kv_dtype=(L.LVR_F32 if dtype == "f32" else L.LVR_BF16),
+                        grouping=grouping, enclosing=enclosing, flags=flags, capacity=max(n0 + extra, 1),
+                        attn_splits=attn, index_dtype=index_dtype)
+    desc = f"case {case}: {dtype} r={r} S={S} hq={hq} hkv={hkv} batch={batch} grouping={grouping} enclosing={enclosing} " \
+           f"centres={index_dtype} flags={flags} attn={attn} B={B} n0={n0} extra={extra}"
+    G.say(desc)
+    if L.lvr_arena_bytes(cfg) == 0:
+        pytest.skip("combination not supported: " + desc)
+    cache = W.make_local_cache(wl, n=n0 + extra, n_kv_heads=hkv, batch=batch) if case % 2 else \
+        W.make_cache(wl, n=n0 + extra, n_kv_heads=hkv, batch=batch)
+    q = W.make_queries(wl, n_q_heads=hq, batch=batch, step=case)
+    with G.Index(cache.K[:, :, :n0], cache.V[:, :, :n0], dtype, hq, capacity=max(n0 + extra, 1), group_size=r,
+                 n_subspaces=S, buffer_size=B, flags=flags, grouping=grouping, enclosing=enclosing, attn_splits=attn,
+                 index_dtype=index_dtype) as ix:
+        steps = [n0] + ([n0 + extra // 2, n0 + extra] if extra else [])
+        have = n0
+        for upto in steps:
+            if upto > have:
+                ix.append(cache.K[:, :, have:upto], cache.V[:, :, have:upto])
+                have = upto
+            if have == 0:
+                continue
+            n_indexed = L.lvr_length(ix.h)[1]
+            for frac in (0.02, 0.3):
+                tau = G.oracle_taus(oracle, ix, q, frac=frac)
+                idx, cnt, out = ix.query(q, tau, fused=bool(case & 4))
+                G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=desc,
+                             extra_from=(n_indexed if flags & L.LVR_ATTEND_BUFFER_DENSE else -1))

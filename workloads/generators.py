@@ -128,14 +128,17 @@ def make_cache(config_id: int, *, n: int | None = None, batch: int | None = None
 
 
 def make_local_cache(config_id: int, *, block: int = 64, spread: float = 3.0, noise: float = 0.05,
-                     n: int | None = None) -> KVCache:
+                     n: int | None = None, batch: int | None = None,
+                     n_kv_heads: int | None = None) -> KVCache:
     """Supplementary workload (not one of the five): keys with positional locality.  Every run of
     `block` consecutive tokens shares a mean drawn from N(0, spread^2) per coordinate and adds
     N(0, noise^2) of its own, so neighbouring keys are close in key space and groups of consecutive
     keys have tight bounding balls.  Values as in the base workload.  Same shapes as config_id."""
     c = CONFIGS[config_id]
     n = c["n"] if n is None else int(n)
-    batch, hkv, d = c["batch"], c["n_kv_heads"], c["head_dim"]
+    batch = c["batch"] if batch is None else int(batch)
+    hkv = c["n_kv_heads"] if n_kv_heads is None else int(n_kv_heads)
+    d = c["head_dim"]
     nb = (n + block - 1) // block
     K = np.empty((batch, hkv, n, d), dtype=np.float32)
     V = np.empty((batch, hkv, n, d), dtype=np.float32)
