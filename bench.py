@@ -141,6 +141,7 @@ def main():
     torch.cuda.synchronize()
     build_ms = (time.time() - tb) * 1e3
 
+    set_turnover = None
     # thresholds (inputs): per step and head, so that the configured share of keys qualifies
     if appending:
         T_all = total_steps + K_steps                       # timed pass, then the profiled pass
@@ -164,11 +165,21 @@ def main():
     else:
         kq = int(math.ceil(c["qualify_frac"] * n0))
         tau_all = torch.empty((n_distinct, B, Hq), dtype=torch.float32, device=dev)
+        prev, turn = None, []
         for t in range(n_distinct):
-            tau_all[t] = kth_midpoint_tau(scores_on_gpu(Kd, q_all[t], G), kq)
+            sc = scores_on_gpu(Kd, q_all[t], G)
+            tau_all[t] = kth_midpoint_tau(sc, kq)
+            if cid == 3:                                    # drifting queries: how much of the set is new each step
+                cur = sc >= tau_all[t].unsqueeze(-1)
+                if prev is not None:
+                    turn.append((cur & ~prev).sum(-1).float().div(kq).mean())
+                prev = cur
             if t % 32 == 31:
                 torch.cuda.synchronize()
                 log(f"[bench] thresholds placed for {t + 1} of {n_distinct} queries")
+        if turn:
+            set_turnover = float(torch.stack(turn).mean())
+        del prev
     cap = 4096 if not appending else 8192
     out = torch.zeros((B, Hq, d), dtype=torch.float32, device=dev)
     idx = torch.zeros((B, Hq, cap), dtype=torch.int32, device=dev)
@@ -344,6 +355,7 @@ def main():
                        "attention": int(st["bytes_attention"]), "total": int(step_bytes),
                        "step_GBs": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
                        "step_frac_of_peak": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+        "set_turnover_per_step": None if set_turnover is None else round(set_turnover, 4),
         "f_scan": round(st["keys_scanned"] / max(n_bh * st["n_keys"], 1), 4),
         "groups_surviving_frac": round(st["groups_surviving"] / max(st["groups_scored"], 1), 4),
         "retrieved_per_head": round(st["keys_emitted"] / (B * Hq), 1),
