@@ -8,6 +8,9 @@
  *   - Every pointer named *_dev is DEVICE memory on the GPU that was current at lvr_create;
  *     every pointer named *_host is HOST memory.  The caller owns all buffers it passes in;
  *     the library owns the index arena (its own copy of K and V, centres, radii, work lists).
+ *     That GPU must be the current device in every later call on the index (LVR_E_STATE
+ *     otherwise).  fp32 and int32 arrays must be 4-byte aligned, K and V rows 16-byte aligned
+ *     (LVR_E_INVALID otherwise; the pointers themselves are not dereferenced on the host).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All device work
  *     of a call is enqueued on that stream and the hot-path calls never synchronise with the
  *     host; results are valid once the stream reaches the end of the call's work.
@@ -88,13 +91,14 @@ enum lvr_flags {
 
 enum lvr_error {
     LVR_OK = 0,
-    LVR_E_INVALID = -1,     /* bad argument (NULL, negative size, unsupported shape)          */
+    LVR_E_INVALID = -1,     /* bad argument (NULL, misaligned, negative size, unknown flag)   */
     LVR_E_UNSUPPORTED = -2, /* valid request this build has no kernel for                      */
     LVR_E_CAPACITY = -3,    /* more keys than lvr_config.capacity                               */
     LVR_E_OVERFLOW = -4,    /* a retrieved set was larger than the caller's `cap` (sticky)      */
     LVR_E_HIP = -5,         /* a HIP runtime call failed; see lvr_last_hip_error                */
     LVR_E_NOMEM = -6,
-    LVR_E_STATE = -7        /* call order wrong (e.g. query before build)                       */
+    LVR_E_STATE = -7        /* call order wrong (e.g. query before build), or the current device
+                             * is not the one the index was created on                        */
 };
 
 typedef struct lvr_config {

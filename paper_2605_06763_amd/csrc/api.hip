@@ -60,6 +60,8 @@ int check_config(const lvr_config *c) {
     if (c->index_dtype != LVR_INDEX_AUTO && c->index_dtype != LVR_INDEX_SAME && c->index_dtype != LVR_INDEX_FP8)
         return LVR_E_INVALID;
     if (c->reserved != 0) return LVR_E_INVALID;
+    if (c->flags & ~(uint32_t)(LVR_ATTEND_BUFFER_DENSE | LVR_SEPARATE_KERNELS | LVR_CONCURRENT_UPDATE | LVR_KV_IN_HOST_MEMORY))
+        return LVR_E_INVALID;
     if (c->index_dtype == LVR_INDEX_FP8 && !fp8_centres_supported(c)) return LVR_E_UNSUPPORTED;
     return LVR_OK;
 }
@@ -200,6 +202,14 @@ inline bool one_launch_attention(const lvr_index *ix) {
 }
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
+
+// The arena belongs to the device that was current in lvr_create; a launch from another device
+// would hand that device's kernels pointers it cannot read.
+inline bool on_home_device(const lvr_index *ix) {
+    int d = -1;
+    return hipGetDevice(&d) == hipSuccess && d == ix->device;
+}
 
 }  // namespace
 
@@ -307,6 +317,7 @@ int lvr_build(lvr_index *ix, const void *K, const void *V, int64_t n, const int6
               void *stream) {
     if (!ix || n < 0 || (n > 0 && (!K || !V || !ks || !vs))) return LVR_E_INVALID;
     if (n > ix->cfg.capacity) return LVR_E_CAPACITY;
+    if (!on_home_device(ix)) return LVR_E_STATE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int64_t per16 = 16 / (int64_t)ix->elt;
     if (n > 0) {
@@ -356,6 +367,7 @@ int lvr_build(lvr_index *ix, const void *K, const void *V, int64_t n, const int6
 int lvr_append(lvr_index *ix, const void *k_new, const void *v_new, int64_t m, void *stream) {
     if (!ix || m < 0 || (m > 0 && (!k_new || !v_new))) return LVR_E_INVALID;
     if (!ix->built) return LVR_E_STATE;
+    if (!on_home_device(ix)) return LVR_E_STATE;
     if (m == 0) return LVR_OK;
     if (ix->n_total + m > ix->cfg.capacity) return LVR_E_CAPACITY;
     if (!aligned16(k_new) || !aligned16(v_new)) return LVR_E_INVALID;
@@ -435,6 +447,7 @@ int lvr_append(lvr_index *ix, const void *k_new, const void *v_new, int64_t m, v
 int lvr_publish(lvr_index *ix, void *stream) {
     if (!ix) return LVR_E_INVALID;
     if (!ix->built) return LVR_E_STATE;
+    if (!on_home_device(ix)) return LVR_E_STATE;
     return publish_pending(ix, static_cast<hipStream_t>(stream), true);
 }
 
@@ -511,6 +524,8 @@ int lvr_query(lvr_index *ix, const float *q, const float *tau, int32_t *out_idx,
               void *stream) {
     if (!ix || !q || !tau || !out_count || cap < 0 || (cap > 0 && !out_idx)) return LVR_E_INVALID;
     if (!ix->built) return LVR_E_STATE;
+    if (!on_home_device(ix)) return LVR_E_STATE;
+    if (!aligned4(q) || !aligned4(tau) || !aligned4(out_idx) || !aligned4(out_count)) return LVR_E_INVALID;
     hipStream_t st = static_cast<hipStream_t>(stream);
     int rc = enqueue_query(ix, q, tau, out_idx, cap, st);
     if (rc != LVR_OK) return rc;
@@ -526,6 +541,8 @@ int lvr_query1(lvr_index *ix, const float *q, const float *tau_s, const float *t
                int32_t *out_count, int64_t cap, void *stream) {
     if (!ix || !q || !tau_s || !tau || !out_count || cap < 0 || (cap > 0 && !out_idx)) return LVR_E_INVALID;
     if (!ix->built) return LVR_E_STATE;
+    if (!on_home_device(ix)) return LVR_E_STATE;
+    if (!aligned4(q) || !aligned4(tau) || !aligned4(tau_s) || !aligned4(out_idx) || !aligned4(out_count)) return LVR_E_INVALID;
     if (ix->cfg.kv_dtype != LVR_BF16 || (ix->cfg.flags & LVR_SEPARATE_KERNELS) || ix->box || ix->cfg.n_subspaces > 4)
         return LVR_E_UNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -543,6 +560,8 @@ int lvr_sparse_attention(lvr_index *ix, const float *q, const int32_t *idx, cons
                          float *out, void *stream) {
     if (!ix || !q || !count || !out || cap < 0 || (cap > 0 && !idx)) return LVR_E_INVALID;
     if (!ix->built) return LVR_E_STATE;
+    if (!on_home_device(ix)) return LVR_E_STATE;
+    if (!aligned4(q) || !aligned4(idx) || !aligned4(count) || !aligned4(out)) return LVR_E_INVALID;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (one_launch_attention(ix)) {
         Timed t(ix, LVR_K_ATTN_PARTIAL, st);
@@ -564,6 +583,8 @@ int lvr_decode_step(lvr_index *ix, const float *q, const float *tau, float *out,
                     int64_t cap, void *stream) {
     if (!ix || !q || !tau || !out || !out_count || cap < 0 || (cap > 0 && !out_idx)) return LVR_E_INVALID;
     if (!ix->built) return LVR_E_STATE;
+    if (!on_home_device(ix)) return LVR_E_STATE;
+    if (!aligned4(q) || !aligned4(tau) || !aligned4(out) || !aligned4(out_idx) || !aligned4(out_count)) return LVR_E_INVALID;
     return decode_step_impl(ix, q, tau, out, out_idx, out_count, cap, static_cast<hipStream_t>(stream), nullptr, nullptr, 0);
 }
 
@@ -573,6 +594,8 @@ int lvr_append_decode_step(lvr_index *ix, const void *k_new, const void *v_new, 
     if (!ix || !q || !tau || !out || !out_count || cap < 0 || (cap > 0 && !out_idx)) return LVR_E_INVALID;
     if (m < 0 || (m > 0 && (!k_new || !v_new))) return LVR_E_INVALID;
     if (!ix->built) return LVR_E_STATE;
+    if (!on_home_device(ix)) return LVR_E_STATE;
+    if (!aligned4(q) || !aligned4(tau) || !aligned4(out) || !aligned4(out_idx) || !aligned4(out_count)) return LVR_E_INVALID;
     if (ix->n_total + m > ix->cfg.capacity) return LVR_E_CAPACITY;
     hipStream_t st = static_cast<hipStream_t>(stream);
     // The copy rides in the query launch when that launch has a buffer workgroup to do it and the
@@ -593,7 +616,8 @@ int lvr_threshold(lvr_index *ix, const float *q, int mode, float param, float *t
     if (!ix || !q || !tau_out || mode < LVR_TAU_SAMPLE_MAX || mode > LVR_TAU_BUDGET) return LVR_E_INVALID;
     if (mode == LVR_TAU_BUDGET && !(param > 0.f && param <= 1.f)) return LVR_E_INVALID;
     if (mode == LVR_TAU_SAMPLE_TOPK && param < 1.f) return LVR_E_INVALID;
-    if (!ix->built || !ix->reservoir) return LVR_E_STATE;
+    if (!ix->built || !ix->reservoir || !on_home_device(ix)) return LVR_E_STATE;
+    if (!aligned4(q) || !aligned4(tau_out)) return LVR_E_INVALID;
     LVR_HIP(lvr_launch_threshold(ix, q, mode, param, tau_out, static_cast<hipStream_t>(stream)));
     return LVR_OK;
 }
@@ -610,6 +634,8 @@ int lvr_export_reservoir(lvr_index *ix, int32_t *positions) {
 int lvr_dense_attention(lvr_index *ix, const float *q, float *out, void *stream) {
     if (!ix || !q || !out) return LVR_E_INVALID;
     if (!ix->built) return LVR_E_STATE;
+    if (!on_home_device(ix)) return LVR_E_STATE;
+    if (!aligned4(q) || !aligned4(out)) return LVR_E_INVALID;
     hipStream_t st = static_cast<hipStream_t>(stream);
     {
         Timed t(ix, LVR_K_DENSE_PARTIAL, st);

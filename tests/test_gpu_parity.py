@@ -1,6 +1,7 @@
 """GPU parity tests at sizes the oracle finishes in seconds: every entry point goes through the
 C ABI (ctypes binding) and is compared element by element with the CPU oracle."""
 import math
+import ctypes as C
 
 import numpy as np
 import pytest
@@ -1136,3 +1137,34 @@ def test_option_combinations(G, oracle, case):
                 idx, cnt, out = ix.query(q, tau, fused=bool(case & 4))
                 G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=desc,
                              extra_from=(n_indexed if flags & L.LVR_ATTEND_BUFFER_DENSE else -1))
+
+
+def test_misaligned_pointers_are_refused_on_the_host(G):
+    """A pointer that the kernels could not read with their load widths comes back as LVR_E_INVALID
+    from the host-side check; nothing is launched and the index stays usable."""
+    L = G.L
+    cache = W.make_cache(2, n=512, n_kv_heads=2)
+    q = W.make_queries(2, n_q_heads=8)
+    with G.Index(cache.K, cache.V, "bf16", 8, capacity=600) as ix:
+        raw = torch.zeros(8 * 128 * 4 + 16, dtype=torch.uint8, device="cuda")
+        base = raw.data_ptr()
+        assert base % 16 == 0
+        good = torch.from_numpy(q.astype(np.float32)).cuda()
+        tau = torch.zeros((1, 8), dtype=torch.float32, device="cuda")
+        out = torch.zeros((1, 8, 128), dtype=torch.float32, device="cuda")
+        idx = torch.zeros((1, 8, 512), dtype=torch.int32, device="cuda")
+        cnt = torch.zeros((1, 8), dtype=torch.int32, device="cuda")
+        lib = L.lib()
+        P = C.c_void_p
+        bad_q = P(base + 2)
+        assert lib.lvr_decode_step(ix.h, bad_q, P(tau.data_ptr()), P(out.data_ptr()), P(idx.data_ptr()),
+                                   P(cnt.data_ptr()), 512, None) == L.LVR_E_INVALID
+        assert lib.lvr_query(ix.h, P(good.data_ptr()), P(tau.data_ptr() + 1), P(idx.data_ptr()), P(cnt.data_ptr()), 512,
+                             None) == L.LVR_E_INVALID
+        assert lib.lvr_dense_attention(ix.h, P(good.data_ptr()), P(out.data_ptr() + 3), None) == L.LVR_E_INVALID
+        # one appended row whose address is a multiple of 2 but not of 16
+        assert lib.lvr_append(ix.h, P(base + 2), P(base), 1, None) == L.LVR_E_INVALID
+        assert L.lvr_length(ix.h)[0] == 512
+        tau_np = np.full((1, 8), -np.inf, dtype=np.float32)
+        idx2, cnt2, _ = ix.query(q, tau_np)
+        assert (cnt2 == 512).all()
