@@ -54,6 +54,8 @@ def _load():
     lib.lvo_aabb_bounds.argtypes = [vp, i32, vp, vp, i64, vp]
     lib.lvo_query1_filter.argtypes = [vp, vp, i32, i64, i64, vp, vp]
     lib.lvo_ta_filter.argtypes = [vp, vp, i32, i64, i64, f64, vp]
+    lib.lvo_safe_subspace_thresholds.argtypes = [vp, i32, i64, f64, vp]
+    lib.lvo_safe_subspace_thresholds.restype = None
     lib.lvo_hash32.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64]
     lib.lvo_hash32.restype = C.c_uint32
     lib.lvo_reservoir.argtypes = [C.c_uint64, C.c_uint64, i64, i32, vp]
@@ -225,6 +227,16 @@ def query1_filter(f, label, tau_s):
     alive = np.zeros(n, dtype=np.uint8)
     _load().lvo_query1_filter(_p(f), _p(label), S, n_groups, n, _p(tau_s), _p(alive))
     return alive.astype(bool)
+
+
+def safe_subspace_thresholds(f, tau: float):
+    """Thresholds tau_s [S] valid for every key with <q,k> >= tau: tau minus the largest ball
+    bounds of the other subspaces (f [S][n_groups])."""
+    f = np.ascontiguousarray(f, dtype=np.float64)
+    S, n_groups = f.shape
+    out = np.empty(S, dtype=np.float64)
+    _load().lvo_safe_subspace_thresholds(_p(f), S, n_groups, float(tau), _p(out))
+    return out
 
 
 def ta_filter(f, label, tau):

@@ -326,6 +326,29 @@ void lvo_query1_filter(const double *f, const int32_t *label, int S, int64_t n_g
     }
 }
 
+/* Per-subspace thresholds that are valid for EVERY key with <q,k> >= tau (Sec. 4.2: Query 1 is
+ * correct when tau_s is a lower bound on the subspace term of every relevant key).  The dot
+ * product is the sum of its subspace terms and the term of subspace t never exceeds the largest
+ * ball bound M_t = max_i f[t][i], hence a key with <q,k> >= tau has term_s >= tau - sum_{t != s} M_t.
+ * f: [S][n_groups]; no groups: nothing can be pruned, tau_s = -inf. */
+void lvo_safe_subspace_thresholds(const double *f, int S, int64_t n_groups, double tau, double *tau_s) {
+    for (int s = 0; s < S; ++s) {
+        if (n_groups <= 0) {
+            tau_s[s] = -INFINITY;
+            continue;
+        }
+        double others = 0.0;
+        for (int t = 0; t < S; ++t) {
+            if (t == s) continue;
+            double m = f[(int64_t)t * n_groups];
+            for (int64_t i = 1; i < n_groups; ++i)
+                if (f[(int64_t)t * n_groups + i] > m) m = f[(int64_t)t * n_groups + i];
+            others += m;
+        }
+        tau_s[s] = tau - others;
+    }
+}
+
 /* ---------------------------------------------------------------- Alg. 4: TA filter */
 
 typedef struct {

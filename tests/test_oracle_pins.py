@@ -533,6 +533,41 @@ def test_query1_filter_with_valid_thresholds_keeps_every_relevant_key(oracle):
     assert oracle.query1_filter(f1, lab1, np.array([3.0])).tolist() == [True, True, True]
 
 
+def test_safe_subspace_thresholds(oracle):
+    """tau_s = tau - (largest bounds of the OTHER subspaces): hand-computed table; one subspace
+    gives tau itself; on random keys with one grouping per subspace the thresholds lose no key
+    with <q,k> >= tau, and they are the largest with that guarantee: when one key attains the
+    largest bound in every other subspace exactly, its own subspace term equals tau_s."""
+    f = np.array([[5.0, 3.0], [2.0, 7.0], [1.0, 1.0]])
+    assert oracle.safe_subspace_thresholds(f, 10.0).tolist() == [2.0, 4.0, -2.0]
+    assert oracle.safe_subspace_thresholds(np.array([[4.0, 9.0, -1.0]]), 6.5).tolist() == [6.5]
+    assert np.all(np.isneginf(oracle.safe_subspace_thresholds(np.zeros((3, 0)), 1.0)))
+    # negative bounds subtract as they are (no clamping at zero)
+    assert oracle.safe_subspace_thresholds(np.array([[-2.0, -3.0], [1.0, 0.5]]), 0.0).tolist() == [-1.0, 2.0]
+    g = np.random.default_rng(23)
+    n, d, S, r = 96, 12, 3, 4
+    for trial in range(4):
+        K = (g.standard_normal((n, d)) * g.uniform(0.3, 3, size=d)).astype(np.float32)
+        q = g.standard_normal(d).astype(np.float32)
+        label = np.stack([(g.permutation(n) // r) for _ in range(S)]).astype(np.int32)
+        f = np.zeros((S, n // r))
+        for s in range(S):
+            lo_, hi_ = oracle.subspace_range(d, S, s)
+            Ks = np.zeros_like(K)
+            Ks[:, lo_:hi_] = K[:, lo_:hi_]
+            c, rad = oracle.ball_index(Ks, label[s], n // r, S)
+            f[s] = oracle.ball_bounds(q, c, rad)[s]
+        score = oracle.scores_f64(q, K)
+        for tau in np.quantile(score, [0.99, 0.9, 0.3]):
+            tau_s = oracle.safe_subspace_thresholds(f, tau)
+            assert np.all(oracle.query1_filter(f, label, tau_s)[score >= tau])
+    # tightness: groups of one key (bound = the key's own term), a key that is the maximiser of
+    # subspaces 1 and 2 and sits exactly at tau has term_0 == tau_0
+    terms = np.array([[1.0, 4.0, 2.0], [6.0, 0.0, 1.0], [3.0, 1.0, 0.0]])   # [S][keys]
+    tau = terms[:, 0].sum()                                                   # key 0: 1 + 6 + 3
+    assert oracle.safe_subspace_thresholds(terms, tau)[0] == terms[0, 0]
+
+
 # ------------------------------------------------------------------ threshold oracles and reservoir
 def test_hash_reference_values(oracle):
     """splitmix64 finaliser: the published generator seeded with 0 produces 0xE220A8397B1DCDAF
