@@ -195,6 +195,18 @@ int lvr_query(lvr_index *ix, const float *q_dev, const float *tau_dev, int32_t *
 int lvr_query1(lvr_index *ix, const float *q_dev, const float *tau_s_dev, const float *tau_dev, int32_t *out_idx_dev,
                int32_t *out_count_dev, int64_t cap, void *stream);
 
+/* Per-subspace thresholds for lvr_query1 derived from tau alone (Sec. 4.2: Query 1 is correct
+ * when tau_s is a lower bound on the subspace term of every relevant key).  For every query
+ * head, tau_s = tau - (sum over the OTHER subspaces of the largest ball bound, Eq. (2), among the
+ * indexed groups): every key with <q,k> >= tau then reaches tau_s in every subspace, so
+ * lvr_query1 with these thresholds returns Problem 1's set.  One pass over the index.
+ *   q_dev [batch][n_q_heads][head_dim], tau_dev [batch][n_q_heads] (-INFINITY gives -INFINITY),
+ *   tau_s_out_dev [batch][n_q_heads][S]; all -INFINITY while no group is indexed.
+ * Same configurations as lvr_query1 (LVR_E_UNSUPPORTED otherwise).  Uses the work space of the
+ * attention entry points: order it with them on one stream. */
+int lvr_subspace_thresholds(lvr_index *ix, const float *q_dev, const float *tau_dev, float *tau_s_out_dev,
+                            void *stream);
+
 /* Attention over given index lists (Sec. 2 "Sparse Attention"; App. "GPU Sparse Attention
  * Kernel": P splits with partial (m, l, o), then a combine pass).  Softmax is normalised over
  * the listed keys only.  idx_dev / count_dev as produced by lvr_query (count is clamped to

@@ -59,6 +59,7 @@ EXPORTS = [
     "lvr_sparse_attention", "lvr_decode_step", "lvr_dense_attention", "lvr_get_stats",
     "lvr_export_index", "lvr_length", "lvr_strerror", "lvr_last_hip_error",
     "lvr_profile_enable", "lvr_profile_read", "lvr_threshold", "lvr_export_reservoir", "lvr_publish", "lvr_query1", "lvr_append_decode_step", "lvr_host_bytes",
+    "lvr_subspace_thresholds",
 ]
 
 _lib = None
@@ -103,6 +104,7 @@ def lib():
     L.lvr_host_bytes.argtypes = [C.POINTER(lvr_config)]
     L.lvr_host_bytes.restype = C.c_size_t
     L.lvr_query1.argtypes = [vp, vp, vp, vp, vp, vp, i64, vp]
+    L.lvr_subspace_thresholds.argtypes = [vp, vp, vp, vp, vp]
     L.lvr_threshold.argtypes = [vp, vp, C.c_int, C.c_float, vp, vp]
     L.lvr_export_reservoir.argtypes = [vp, vp]
     L.lvr_strerror.argtypes = [C.c_int]
@@ -216,6 +218,12 @@ def lvr_query1(h, q, tau_s, tau, out_idx, out_count, stream=None) -> None:
     _check(lib().lvr_query1(h, _dev(q, torch.float32, "q"), _dev(tau_s, torch.float32, "tau_s"),
                             _dev(tau, torch.float32, "tau"), _dev(out_idx, torch.int32, "out_idx"),
                             _dev(out_count, torch.int32, "out_count"), cap, _stream(stream)), "lvr_query1")
+
+
+def lvr_subspace_thresholds(h, q, tau, tau_s_out, stream=None) -> None:
+    _check(lib().lvr_subspace_thresholds(h, _dev(q, torch.float32, "q"), _dev(tau, torch.float32, "tau"),
+                                         _dev(tau_s_out, torch.float32, "tau_s_out"), _stream(stream)),
+           "lvr_subspace_thresholds")
 
 
 def lvr_sparse_attention(h, q, idx, count, out, stream=None) -> None:

@@ -556,6 +556,16 @@ int lvr_query1(lvr_index *ix, const float *q, const float *tau_s, const float *t
     return LVR_OK;
 }
 
+int lvr_subspace_thresholds(lvr_index *ix, const float *q, const float *tau, float *tau_s_out, void *stream) {
+    if (!ix || !q || !tau || !tau_s_out) return LVR_E_INVALID;
+    if (!ix->built || !on_home_device(ix)) return LVR_E_STATE;
+    if (!aligned4(q) || !aligned4(tau) || !aligned4(tau_s_out)) return LVR_E_INVALID;
+    if (ix->cfg.kv_dtype != LVR_BF16 || (ix->cfg.flags & LVR_SEPARATE_KERNELS) || ix->box || ix->cfg.n_subspaces > 4)
+        return LVR_E_UNSUPPORTED;
+    LVR_HIP(lvr_launch_safe_tau_s(ix, q, tau, tau_s_out, static_cast<hipStream_t>(stream)));
+    return LVR_OK;
+}
+
 int lvr_sparse_attention(lvr_index *ix, const float *q, const int32_t *idx, const int32_t *count, int64_t cap,
                          float *out, void *stream) {
     if (!ix || !q || !count || !out || cap < 0 || (cap > 0 && !idx)) return LVR_E_INVALID;

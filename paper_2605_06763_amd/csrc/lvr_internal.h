@@ -138,6 +138,7 @@ int lvr_dense_splits(const lvr_index *ix);
 // reservoir of past keys and threshold selection (threshold.hip)
 hipError_t lvr_launch_reservoir_reset(lvr_index *ix, hipStream_t st);
 hipError_t lvr_launch_reservoir_update(lvr_index *ix, int64_t pos0, int64_t count, hipStream_t st);
+hipError_t lvr_launch_safe_tau_s(lvr_index *ix, const float *q, const float *tau, float *tau_s, hipStream_t st);
 hipError_t lvr_launch_threshold(lvr_index *ix, const float *q, int mode, float param, float *tau_out, hipStream_t st);
 // tree grouping (tree.hip)
 size_t lvr_tree_sort_temp_bytes(int64_t total_keys);

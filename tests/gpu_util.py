@@ -164,6 +164,16 @@ def oracle_taus(oracle, ix: Index, q, k_count=None, frac=None):
     return tau
 
 
+def subspace_thresholds(ix: Index, q: np.ndarray, tau: np.ndarray) -> np.ndarray:
+    """lvr_subspace_thresholds -> [batch][hq][S] fp32."""
+    qd = torch.from_numpy(np.ascontiguousarray(q, dtype=np.float32)).cuda()
+    td = torch.from_numpy(np.ascontiguousarray(tau, dtype=np.float32)).cuda()
+    out = torch.full((ix.batch, ix.hq, ix.cfg.n_subspaces), float("nan"), dtype=torch.float32, device="cuda")
+    L.lvr_subspace_thresholds(ix.h, qd, td, out)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
 def query1(ix: Index, q: np.ndarray, tau_s: np.ndarray, tau: np.ndarray, cap=None):
     """lvr_query1 followed by lvr_sparse_attention; tau_s [batch][hq][S]."""
     cap = ix.n if cap is None else cap

@@ -154,6 +154,11 @@ def test_config2_library_thresholds_query1_and_offload(G, oracle):
             tau_s[0, h] = (tau[0, h] - (top.sum() - top) - 1e-3).astype(np.float32)
         idx, cnt, out = G.query1(ix, q, tau_s, tau, cap=2048)
         G.check_step(oracle, ix, q, tau, idx, cnt, out, tag="config2 query1")
+        # the same thresholds derived by the library from tau alone
+        lib_tau_s = G.subspace_thresholds(ix, q, tau)
+        assert np.all(np.abs(lib_tau_s - (tau_s + 1e-3)) <= 2e-5 * (np.abs(tau)[..., None] + np.abs(tau_s - tau[..., None]) + 1))
+        idx, cnt, out = G.query1(ix, q, lib_tau_s, tau, cap=2048)
+        G.check_step(oracle, ix, q, tau, idx, cnt, out, tag="config2 query1, library thresholds")
     with G.Index(cache.K, cache.V, "bf16", 32, flags=L.LVR_KV_IN_HOST_MEMORY) as ix:
         assert L.lvr_host_bytes(ix.cfg) == 2 * 8 * 32768 * 128 * 2
         tau = G.oracle_taus(oracle, ix, q, frac=0.01)

@@ -785,6 +785,17 @@ def test_query1_per_subspace_thresholds(G, oracle, S, keys, hq, centres):
         idx, cnt, out = G.query1(ix, q, tau_s, tau)
         G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=f"query1 safe S={S}")
         st_safe = ix.stats()
+        # (1b) the library derives the same thresholds from tau alone: equal to the oracle's on the
+        # exported index up to fp32 rounding of the bounds, never above them by more than that, and
+        # Query 1 with them returns Problem 1's set
+        lib_tau_s = G.subspace_thresholds(ix, q, tau)
+        for h in range(hq):
+            want = oracle.safe_subspace_thresholds(f[h], float(tau[0, h]))
+            scale = abs(float(tau[0, h])) + np.abs(f[h]).max(axis=1).sum()
+            assert np.all(np.abs(lib_tau_s[0, h] - want) <= 2e-5 * scale), (h, lib_tau_s[0, h], want)
+        idx, cnt, out = G.query1(ix, q, lib_tau_s, tau)
+        G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=f"query1 library thresholds S={S}")
+        assert ix.stats()["groups_surviving"] <= st_safe["groups_surviving"] * 1.05 + 8
         # (2) thresholds that cut: per block the median of that block's bounds
         for quant in (0.5, 0.9):
             for h in range(hq):
@@ -1172,3 +1183,31 @@ def test_misaligned_pointers_are_refused_on_the_host(G):
         tau_np = np.full((1, 8), -np.inf, dtype=np.float32)
         idx2, cnt2, _ = ix.query(q, tau_np)
         assert (cnt2 == 512).all()
+
+
+def test_subspace_thresholds_edge_cases(G, oracle):
+    """No indexed group: every threshold is -inf (nothing can be pruned) and Query 1 still returns
+    the buffer's qualifying keys; tau = -inf stays -inf; appended groups are taken into account;
+    boxes and S > 4 have no such entry point."""
+    L = G.L
+    cache = W.make_cache(2, n=300, n_kv_heads=2)
+    q = W.make_queries(2, n_q_heads=8)
+    with G.Index(cache.K[:, :, :3], cache.V[:, :, :3], "bf16", 8, capacity=300, buffer_size=32) as ix:
+        tau = np.zeros((1, 8), dtype=np.float32)
+        ts = G.subspace_thresholds(ix, q, tau)
+        assert np.all(np.isneginf(ts))
+        idx, cnt, out = G.query1(ix, q, ts, tau)
+        G.check_step(oracle, ix, q, tau, idx, cnt, out, tag="query1 without groups")
+        ix.append(cache.K[:, :, 3:], cache.V[:, :, 3:])
+        tau = G.oracle_taus(oracle, ix, q, frac=0.05)
+        tau[0, 3] = -np.inf
+        ts = G.subspace_thresholds(ix, q, tau)
+        assert np.all(np.isneginf(ts[0, 3])) and np.all(np.isfinite(np.delete(ts[0], 3, axis=0)))
+        idx, cnt, out = G.query1(ix, q, ts, tau)
+        G.check_step(oracle, ix, q, tau, idx, cnt, out, tag="query1 after append")
+        assert cnt[0, 3] == 300
+    for kw in (dict(n_subspaces=8), dict(enclosing=L.LVR_ENCLOSE_AABB)):
+        with G.Index(cache.K, cache.V, "bf16", 8, **kw) as ix:
+            with pytest.raises(L.LouverError) as e:
+                G.subspace_thresholds(ix, q, np.zeros((1, 8), dtype=np.float32))
+            assert e.value.code == L.LVR_E_UNSUPPORTED
