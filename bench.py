@@ -381,7 +381,7 @@ def main():
         nb = 1 if B > 1 else B
         done, cpu_s, recall_num, recall_den, spurious, worst = 0, 0.0, 0, 0, 0, 0.0
         sample_steps = []
-        while cpu_s < args.cpu_seconds and done < n_distinct:
+        while cpu_s < args.cpu_seconds and done < 8 * n_distinct:   # wraps around the distinct steps if they are few
             t = (done * 37) % n_distinct
             tc = time.time()
             sets, counts, o_ref = oracle.decode_step(K_bits[:nb], V_bits[:nb], q_np[t][:nb], tau_np[t][:nb], sigma, Hq, cap=cap)
