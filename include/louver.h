@@ -215,7 +215,10 @@ int lvr_subspace_thresholds(lvr_index *ix, const float *q_dev, const float *tau_
 int lvr_sparse_attention(lvr_index *ix, const float *q_dev, const int32_t *idx_dev,
                          const int32_t *count_dev, int64_t cap, float *out_dev, void *stream);
 
-/* lvr_query followed by lvr_sparse_attention on its result, in one call. */
+/* lvr_query followed by lvr_sparse_attention on its result, in one call (Alg. 3 / Alg. 4 end to
+ * end: retrieve, then attend).  Launches kernels only: no allocation, no host synchronisation,
+ * no memset, so the call may be recorded while `stream` is under HIP graph capture; a recorded
+ * step stays valid until the next lvr_build / lvr_append / lvr_publish on the index. */
 int lvr_decode_step(lvr_index *ix, const float *q_dev, const float *tau_dev, float *out_dev,
                     int32_t *out_idx_dev, int32_t *out_count_dev, int64_t cap, void *stream);
 

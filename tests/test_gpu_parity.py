@@ -1211,3 +1211,42 @@ def test_subspace_thresholds_edge_cases(G, oracle):
             with pytest.raises(L.LouverError) as e:
                 G.subspace_thresholds(ix, q, np.zeros((1, 8), dtype=np.float32))
             assert e.value.code == L.LVR_E_UNSUPPORTED
+
+
+def test_decode_step_under_graph_capture(G, oracle):
+    """lvr_decode_step allocates nothing and never synchronises, so a caller can capture it in a HIP
+    graph: every replay (with eager calls and synchronisations in between, fresh q and tau written
+    into the captured buffers) must equal the eager call on the same inputs, and the oracle."""
+    L = G.L
+    cache = W.make_cache(2, n=8192 + 77, n_kv_heads=2)
+    steps = 6
+    qs = W.drift_queries(3, steps, n_q_heads=8)
+    with G.Index(cache.K, cache.V, "bf16", 8) as ix:
+        taus = [G.oracle_taus(oracle, ix, qs[t], frac=0.01) for t in range(steps)]
+        q_in = torch.zeros((1, 8, 128), dtype=torch.float32, device="cuda")
+        tau_in = torch.zeros((1, 8), dtype=torch.float32, device="cuda")
+        out = torch.zeros((1, 8, 128), dtype=torch.float32, device="cuda")
+        idx = torch.zeros((1, 8, 1024), dtype=torch.int32, device="cuda")
+        cnt = torch.zeros((1, 8), dtype=torch.int32, device="cuda")
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):                      # one eager call on the capture stream first
+            L.lvr_decode_step(ix.h, q_in, tau_in, out, idx, cnt, stream=side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            L.lvr_decode_step(ix.h, q_in, tau_in, out, idx, cnt, stream=torch.cuda.current_stream())
+        for t in range(steps):
+            # eager result on the same inputs
+            i_e, c_e, o_e = ix.query(qs[t], taus[t], cap=1024, fused=True)
+            q_in.copy_(torch.from_numpy(qs[t]))
+            tau_in.copy_(torch.from_numpy(taus[t]))
+            graph.replay()
+            torch.cuda.synchronize()
+            c_g, o_g, i_g = cnt.cpu().numpy(), out.cpu().numpy(), idx.cpu().numpy()
+            assert np.array_equal(c_g, c_e), t
+            for h in range(8):
+                assert set(i_g[0, h, :c_g[0, h]].tolist()) == set(i_e[0, h, :c_e[0, h]].tolist()), (t, h)
+            np.testing.assert_allclose(o_g, o_e, rtol=1e-5, atol=1e-6)
+            G.check_step(oracle, ix, qs[t], taus[t], i_g, c_g, o_g, tag=f"graph replay {t}")
+        del graph
