@@ -149,6 +149,29 @@ __device__ __forceinline__ lvr_f32x4 lvr_score_tile_block(const uint4 (&a)[4], c
     return s;
 }
 
+// Partial score over a coordinate block that is a FRACTION of one MFMA step: coordinates
+// KK*32 + KQ0*8 .. KK*32 + KQ1*8 - 1.  A lane's B fragment holds the eight query coordinates
+// KK*32 + kq*8 .. +7 of its column, so zeroing the fragment on the lanes whose kq lies outside
+// [KQ0, KQ1) leaves exactly the block's products in the sum.
+template <int KK, int KQ0, int KQ1>
+__device__ __forceinline__ lvr_f32x4 lvr_score_tile_subblock(const uint4 (&a)[4], const lvr_bf16x8 (&bq)[4], int kq) {
+    const bool in = kq >= KQ0 && kq < KQ1;
+    const uint4 full = __builtin_bit_cast(uint4, bq[KK]);
+    const uint4 masked = make_uint4(in ? full.x : 0u, in ? full.y : 0u, in ? full.z : 0u, in ? full.w : 0u);
+    lvr_f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lvr_bf16x8, a[KK]), __builtin_bit_cast(lvr_bf16x8, masked),
+                                                  acc, 0, 0, 0);
+    lvr_f32x4 s;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float v = acc[j];
+        float t = v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x114, 0xf, 0xf, true));
+        t += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x118, 0xf, 0xf, true));
+        s[j] = t;
+    }
+    return s;
+}
+
 // The radius term of the bound, sum_s rho_s * |pi_s q|, as one more MFMA step.
 // k-slot of the step: k = part' * S + s for k < 3S (S <= 8), zero beyond.
 //   A[i = row][k]      = part' of rho_{row,s}   (three bf16 terms that add up to rho exactly;

@@ -125,14 +125,14 @@ void launch_max(lvr_index *ix, const float *q, float *part, int NB, int64_t n_gr
 
 }  // namespace
 
-// Callers guarantee: bf16 cache, ball enclosure, S <= 4.  The per-workgroup maxima go through the
+// Callers guarantee: bf16 cache, ball enclosure (8-bit centres only with S <= 4).  The per-workgroup maxima go through the
 // attention's partial-output buffer (at least 512 floats per query head), which no launch in flight
 // on the same stream still needs once this one runs.
 hipError_t lvr_launch_safe_tau_s(lvr_index *ix, const float *q, const float *tau, float *tau_s, hipStream_t st) {
     const int S = ix->cfg.n_subspaces, G = ix->G;
     const int64_t n_groups = ix->n_indexed / ix->cfg.group_size;
     int64_t nb = (n_groups + 15) / 16;
-    if (nb > 128) nb = 128;          // NB * G * S floats per KV head must fit G * 512
+    if (nb > 512 / S) nb = 512 / S;  // NB * G * S floats per KV head must fit G * 512
     const int NB = (int)nb;
     if (NB > 0) {
         switch (G) {

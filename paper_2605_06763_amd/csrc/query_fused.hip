@@ -48,7 +48,8 @@ struct FusedArgs {
 template <int HB, int S, int UA, int ENC, int Q1 = 0, int CF8 = 0>
 __global__ void __launch_bounds__(256)
 query_fused_kernel(const FusedArgs a) {
-    static_assert(!Q1 || (S <= 4 && !ENC), "Query 1 needs blocks that are whole MFMA steps");
+    static_assert(!Q1 || !ENC, "Query 1 is built for balls");
+    static_assert(!Q1 || S <= 4 || !CF8, "8-bit centres: at most four coordinate blocks");
     static_assert(!CF8 || (S <= 4 && !ENC), "8-bit centres: balls, at most four coordinate blocks");
     // the staging area of the query operand is dead once every wave holds its fragments; the score
     // queues of the emitters live in the same bytes afterwards (LDS per workgroup decides how many
@@ -228,18 +229,65 @@ query_fused_kernel(const FusedArgs a) {
                     if constexpr (Q1) {
                         // a group survives for a head iff every block's bound reaches that block's threshold
                         bool okb[4] = {true, true, true, true};
-                        auto block = [&](auto s_c) {
-                            constexpr int s = decltype(s_c)::value;
-                            constexpr int KPS = 4 / S;
-                            const lvr_f32x4 sc = lvr_score_tile_block<s * KPS, (s + 1) * KPS>(ac, bq[hb]);
+                        if constexpr (S <= 4) {
+                            auto block = [&](auto s_c) {
+                                constexpr int s = decltype(s_c)::value;
+                                constexpr int KPS = 4 / S;
+                                const lvr_f32x4 sc = lvr_score_tile_block<s * KPS, (s + 1) * KPS>(ac, bq[hb]);
 #pragma unroll
-                            for (int j = 0; j < 4; ++j) okb[j] = okb[j] && (sc[j] + rad[u][j][s] * qn[hb][s] >= taus[hb][s]);
-                        };
-                        block(std::integral_constant<int, 0>{});
-                        if constexpr (S >= 2) block(std::integral_constant<int, 1>{});
-                        if constexpr (S >= 4) {
-                            block(std::integral_constant<int, 2>{});
-                            block(std::integral_constant<int, 3>{});
+                                for (int j = 0; j < 4; ++j) okb[j] = okb[j] && (sc[j] + rad[u][j][s] * qn[hb][s] >= taus[hb][s]);
+                            };
+                            block(std::integral_constant<int, 0>{});
+                            if constexpr (S >= 2) block(std::integral_constant<int, 1>{});
+                            if constexpr (S >= 4) {
+                                block(std::integral_constant<int, 2>{});
+                                block(std::integral_constant<int, 3>{});
+                            }
+                        } else {
+                            // a block is a half (S = 8) or a quarter (S = 16) of a 32-coordinate step: the step is
+                            // issued once per block with the query operand masked to the block's lanes
+                            constexpr int BPS = S / 4;      // blocks per step
+                            constexpr int QPB = 4 / BPS;    // operand quarters per block
+                            const float *rp[4];
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                int64_t gj = g_row + 4 * kq + j;
+                                if (gj >= a.n_groups) gj = a.n_groups - 1;
+                                rp[j] = Rb + gj * S;
+                            }
+                            auto step = [&](auto kk_c) {
+                                constexpr int kk = decltype(kk_c)::value;
+                                float4 r4[4][BPS / 4 ? BPS / 4 : 1];
+                                float r2[4][2];
+                                (void)r4; (void)r2;
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) {
+                                    if constexpr (BPS == 4) r4[j][0] = *reinterpret_cast<const float4 *>(rp[j] + kk * 4);
+                                    else { const float2 t2 = *reinterpret_cast<const float2 *>(rp[j] + kk * 2); r2[j][0] = t2.x; r2[j][1] = t2.y; }
+                                }
+                                auto sub = [&](auto t_c) {
+                                    constexpr int t = decltype(t_c)::value;
+                                    constexpr int s = kk * BPS + t;
+                                    const lvr_f32x4 sc = lvr_score_tile_subblock<kk, t * QPB, (t + 1) * QPB>(ac, bq[hb], kq);
+#pragma unroll
+                                    for (int j = 0; j < 4; ++j) {
+                                        float rho;
+                                        if constexpr (BPS == 4) rho = t == 0 ? r4[j][0].x : (t == 1 ? r4[j][0].y : (t == 2 ? r4[j][0].z : r4[j][0].w));
+                                        else rho = r2[j][t];
+                                        okb[j] = okb[j] && (sc[j] + rho * qn[hb][s] >= taus[hb][s]);
+                                    }
+                                };
+                                sub(std::integral_constant<int, 0>{});
+                                sub(std::integral_constant<int, 1>{});
+                                if constexpr (BPS == 4) {
+                                    sub(std::integral_constant<int, 2>{});
+                                    sub(std::integral_constant<int, 3>{});
+                                }
+                            };
+                            step(std::integral_constant<int, 0>{});
+                            step(std::integral_constant<int, 1>{});
+                            step(std::integral_constant<int, 2>{});
+                            step(std::integral_constant<int, 3>{});
                         }
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
@@ -431,7 +479,7 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
                                   int32_t *out_idx, int64_t cap, hipStream_t st, const void *k_new, const void *v_new,
                                   int64_t m_new) {
     if (ix->cfg.kv_dtype != LVR_BF16) return hipErrorInvalidValue;
-    if (tau_s && (ix->box || ix->cfg.n_subspaces > 4)) return hipErrorInvalidValue;
+    if (tau_s && (ix->box || (ix->cf8 && ix->cfg.n_subspaces > 4))) return hipErrorInvalidValue;
     FusedArgs a;
     a.tau_s = tau_s;
     a.k_new = k_new;
@@ -490,7 +538,11 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
     do {                                                                                                        \
         if (S == 1) hipLaunchKernelGGL((query_fused_kernel<HB, 1, 1, 0, 1, CF8>), grid, dim3(256), 0, st, a);   \
         else if (S == 2) hipLaunchKernelGGL((query_fused_kernel<HB, 2, 1, 0, 1, CF8>), grid, dim3(256), 0, st, a); \
-        else hipLaunchKernelGGL((query_fused_kernel<HB, 4, 1, 0, 1, CF8>), grid, dim3(256), 0, st, a);          \
+        else if (S == 4) hipLaunchKernelGGL((query_fused_kernel<HB, 4, 1, 0, 1, CF8>), grid, dim3(256), 0, st, a); \
+        else if constexpr (!CF8) {                                                                              \
+            if (S == 8) hipLaunchKernelGGL((query_fused_kernel<HB, 8, 1, 0, 1, 0>), grid, dim3(256), 0, st, a); \
+            else hipLaunchKernelGGL((query_fused_kernel<HB, 16, 1, 0, 1, 0>), grid, dim3(256), 0, st, a);       \
+        }                                                                                                       \
     } while (0)
         if (ix->G <= 4) {
             if (ix->cf8) LVR_Q1_LAUNCH(1, 1);

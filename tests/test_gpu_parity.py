@@ -754,10 +754,13 @@ def _exported_bounds(G, oracle, ix, q, r):
     return np.stack(out)
 
 
-@pytest.mark.parametrize("S,keys,hq", [(1, "local", 4), (2, "local", 4), (4, "local", 4), (1, "workload", 4),
-                                       (2, "workload", 4), (4, "workload", 4), (2, "local", 8), (4, "local", 2),
-                                       (4, "workload", 1)])
-@pytest.mark.parametrize("centres", ["fp8", "same"])
+_Q1_CASES = [(1, "local", 4), (2, "local", 4), (4, "local", 4), (1, "workload", 4), (2, "workload", 4), (4, "workload", 4),
+             (2, "local", 8), (4, "local", 2), (4, "workload", 1), (8, "local", 4), (16, "local", 4), (8, "workload", 8),
+             (16, "workload", 8), (16, "local", 1), (8, "workload", 2)]
+
+
+# 8-bit centres are built for at most four coordinate blocks
+@pytest.mark.parametrize("S,keys,hq,centres", [c + (f,) for c in _Q1_CASES for f in ("fp8", "same") if f == "same" or c[0] <= 4])
 def test_query1_per_subspace_thresholds(G, oracle, S, keys, hq, centres):
     """Safe thresholds (tau_s = tau minus the largest bounds of the other blocks) must give
     Problem 1's set; arbitrary thresholds must give a set between Alg. 3's candidates (oracle's
@@ -841,7 +844,7 @@ def test_query1_unsupported_configurations(G):
     tau = torch.zeros((1, 8), device="cuda")
     idx = torch.zeros((1, 8, 16), dtype=torch.int32, device="cuda")
     cnt = torch.zeros((1, 8), dtype=torch.int32, device="cuda")
-    for kw in (dict(n_subspaces=8), dict(enclosing=L.LVR_ENCLOSE_AABB), dict(flags=L.LVR_SEPARATE_KERNELS)):
+    for kw in (dict(enclosing=L.LVR_ENCLOSE_AABB), dict(flags=L.LVR_SEPARATE_KERNELS)):
         with G.Index(cache.K, cache.V, "bf16", 8, **kw) as ix:
             S = kw.get("n_subspaces", 4)
             with pytest.raises(L.LouverError) as e:
@@ -1188,7 +1191,7 @@ def test_misaligned_pointers_are_refused_on_the_host(G):
 def test_subspace_thresholds_edge_cases(G, oracle):
     """No indexed group: every threshold is -inf (nothing can be pruned) and Query 1 still returns
     the buffer's qualifying keys; tau = -inf stays -inf; appended groups are taken into account;
-    boxes and S > 4 have no such entry point."""
+    boxes and the two-launch form have no such entry point."""
     L = G.L
     cache = W.make_cache(2, n=300, n_kv_heads=2)
     q = W.make_queries(2, n_q_heads=8)
@@ -1206,7 +1209,7 @@ def test_subspace_thresholds_edge_cases(G, oracle):
         idx, cnt, out = G.query1(ix, q, ts, tau)
         G.check_step(oracle, ix, q, tau, idx, cnt, out, tag="query1 after append")
         assert cnt[0, 3] == 300
-    for kw in (dict(n_subspaces=8), dict(enclosing=L.LVR_ENCLOSE_AABB)):
+    for kw in (dict(flags=L.LVR_SEPARATE_KERNELS), dict(enclosing=L.LVR_ENCLOSE_AABB)):
         with G.Index(cache.K, cache.V, "bf16", 8, **kw) as ix:
             with pytest.raises(L.LouverError) as e:
                 G.subspace_thresholds(ix, q, np.zeros((1, 8), dtype=np.float32))
