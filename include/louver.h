@@ -57,9 +57,10 @@ enum lvr_enclosing { LVR_ENCLOSE_BALL = 0, LVR_ENCLOSE_AABB = 1 };
  * members and no qualifying key can be lost; a coarser centre only makes the balls larger.
  *   SAME: the cache's own format (bf16 or fp32), 2 or 4 bytes per coordinate.
  *   FP8:  OCP e4m3 codes (1 sign, 4 exponent, 3 mantissa bits), 1 byte per coordinate: the index
- *         read of a query halves.  bf16 caches, ball enclosure, n_subspaces <= 4, fused query
- *         kernel (LVR_E_UNSUPPORTED otherwise).
- *   AUTO: FP8 where it is supported and K/V are in device memory, else SAME. */
+ *         read of a query halves.  Box corners are rounded outwards (upper corner up, lower corner
+ *         down), so the stored box contains the exact one.  bf16 caches and the fused query kernel;
+ *         balls with n_subspaces <= 4, or boxes (LVR_E_UNSUPPORTED otherwise).
+ *   AUTO: FP8 for balls where it is supported and K/V are in device memory, else SAME. */
 enum lvr_index_dtype { LVR_INDEX_AUTO = 0, LVR_INDEX_SAME = 1, LVR_INDEX_FP8 = 2 };
 
 enum lvr_flags {

@@ -26,8 +26,8 @@ inline int hip_fail(hipError_t e) {
 inline bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 
 inline bool fp8_centres_supported(const lvr_config *c) {
-    return c->kv_dtype == LVR_BF16 && c->enclosing == LVR_ENCLOSE_BALL && !(c->flags & LVR_SEPARATE_KERNELS) &&
-           c->n_subspaces <= 4;
+    if (c->kv_dtype != LVR_BF16 || (c->flags & LVR_SEPARATE_KERNELS)) return false;
+    return c->enclosing == LVR_ENCLOSE_AABB || c->n_subspaces <= 4;   // boxes do not look at n_subspaces
 }
 
 // AUTO: 8-bit centres halve the index read, at the price of somewhat larger balls.  That pays when the
@@ -35,7 +35,8 @@ inline bool fp8_centres_supported(const lvr_config *c) {
 // index byte, so the tighter centres in the cache's own format are kept there.
 inline bool fp8_centres(const lvr_config *c) {
     return c->index_dtype == LVR_INDEX_FP8 ||
-           (c->index_dtype == LVR_INDEX_AUTO && fp8_centres_supported(c) && !(c->flags & LVR_KV_IN_HOST_MEMORY));
+           (c->index_dtype == LVR_INDEX_AUTO && fp8_centres_supported(c) && c->enclosing == LVR_ENCLOSE_BALL &&
+            !(c->flags & LVR_KV_IN_HOST_MEMORY));
 }
 
 int check_config(const lvr_config *c) {
@@ -90,7 +91,7 @@ Sizes sizes_of(const lvr_config *c) {
     const bool box = c->enclosing == LVR_ENCLOSE_AABB;
     const size_t c_elt = fp8_centres(c) ? 1 : elt;
     s.centres = al((size_t)n_bh * s.max_groups * LVR_D * c_elt * (box ? 2 : 1));
-    s.radii = al((size_t)n_bh * s.max_groups * (box ? 1 : (fp8_centres(c) ? 4 : c->n_subspaces)) * sizeof(float));
+    s.radii = al((size_t)n_bh * s.max_groups * (box ? 1 : (fp8_centres(c) ? 4 : c->n_subspaces)) * sizeof(float));   // boxes: one allowance
     s.list = al((size_t)n_bh * s.max_groups * sizeof(int32_t));
     s.counters = al(lvr_counter_ints((int)n_bh, (int)n_bhq, s.max_groups) * sizeof(int32_t));
     s.part_ml = al((size_t)n_bhq * s.Pmax * 2 * sizeof(float));
@@ -687,7 +688,7 @@ int lvr_get_stats(lvr_index *ix, lvr_stats *out) {
     out->groups_surviving = surv;
     out->keys_scanned = surv * r + ix->last_buffer_rows * n_bh;
     out->keys_emitted = emitted;
-    out->bytes_index = out->groups_scored * ((ix->cf8 ? (int64_t)LVR_D : row_bytes * (ix->box ? 2 : 1)) + (int64_t)ix->S_store * 4);
+    out->bytes_index = out->groups_scored * ((ix->cf8 ? (int64_t)LVR_D : row_bytes) * (ix->box ? 2 : 1) + (int64_t)ix->S_store * 4);
     out->bytes_keys = out->keys_scanned * row_bytes;
     out->bytes_attention = emitted * 2 * row_bytes;
     out->overflow = overflow;
@@ -709,17 +710,19 @@ int lvr_export_index(lvr_index *ix, void *centres, float *radii, int32_t *slot_p
     const size_t crow = row_bytes * (ix->box ? 2 : 1);   // bytes of one group's enclosure rows
     for (int bh = 0; bh < n_bh; ++bh) {
         if (centres && ng > 0 && ix->cf8) {
-            // e4m3 codes in matrix-operand order -> bf16 bit patterns in coordinate order (exact)
-            uint8_t *codes = static_cast<uint8_t *>(malloc((size_t)ng * LVR_D));
+            // e4m3 codes in matrix-operand order -> bf16 bit patterns in coordinate order (exact);
+            // one row of codes per ball, two (upper, lower corner) per box
+            const int64_t nr = ng * (ix->box ? 2 : 1), max_rows = ix->max_groups * (ix->box ? 2 : 1);
+            uint8_t *codes = static_cast<uint8_t *>(malloc((size_t)nr * LVR_D));
             if (!codes) return LVR_E_NOMEM;
-            hipError_t e = hipMemcpy(codes, static_cast<char *>(ix->centres) + (size_t)bh * ix->max_groups * LVR_D,
-                                     (size_t)ng * LVR_D, hipMemcpyDeviceToHost);
+            hipError_t e = hipMemcpy(codes, static_cast<char *>(ix->centres) + (size_t)bh * max_rows * LVR_D,
+                                     (size_t)nr * LVR_D, hipMemcpyDeviceToHost);
             if (e != hipSuccess) {
                 free(codes);
                 return hip_fail(e);
             }
-            uint16_t *dst = static_cast<uint16_t *>(centres) + (size_t)bh * ng * LVR_D;
-            for (int64_t g = 0; g < ng; ++g)
+            uint16_t *dst = static_cast<uint16_t *>(centres) + (size_t)bh * nr * LVR_D;
+            for (int64_t g = 0; g < nr; ++g)
                 for (int c = 0; c < LVR_D; ++c) {
                     const int kk = c / 32, kq = (c % 32) / 8, j = c % 8;
                     const uint8_t code = codes[g * LVR_D + kq * 32 + kk * 8 + j];
@@ -735,7 +738,7 @@ int lvr_export_index(lvr_index *ix, void *centres, float *radii, int32_t *slot_p
             LVR_HIP(hipMemcpy(static_cast<char *>(centres) + (size_t)bh * ng * crow,
                               static_cast<char *>(ix->centres) + (size_t)bh * ix->max_groups * crow,
                               (size_t)ng * crow, hipMemcpyDeviceToHost));
-        if (radii && ng > 0 && ix->cf8) {
+        if (radii && ng > 0 && ix->cf8 && !ix->box) {
             // pre-split radii (eight bf16 per group, slot k = part*S' + s) -> one float per subspace
             const int Ss = ix->cfg.n_subspaces;
             uint16_t *blk = static_cast<uint16_t *>(malloc((size_t)ng * 16));

@@ -58,6 +58,31 @@ __device__ __forceinline__ uint32_t f32_to_e4m3(float x) {
 
 typedef __attribute__((__vector_size__(2 * sizeof(float)))) float lvr_f32x2;
 
+// Value of one e4m3 code (never the NaN code: the encoder above does not produce it).
+__device__ __forceinline__ float e4m3_value(uint32_t code) {
+    const lvr_f32x2 d = __builtin_amdgcn_cvt_pk_f32_fp8((int)(code & 0xffu), false);
+    return d[0];
+}
+
+// fp32 -> e4m3 code rounded towards +inf (up = true) or -inf (up = false): the nearest code, moved one
+// step in the wanted direction when it fell on the wrong side.  Codes are sign-magnitude, so a step
+// up is magnitude + 1 for positive and magnitude - 1 for negative values, with -0 -> smallest positive.
+// At the ends (+-448) the code stays; the caller accounts for what it cannot enclose.
+__device__ __forceinline__ uint32_t f32_to_e4m3_directed(float x, bool up) {
+    uint32_t c = f32_to_e4m3(x);
+    const float d = e4m3_value(c);
+    const uint32_t mag = c & 0x7fu;
+    const bool neg = (c & 0x80u) != 0;
+    if (up && d < x) {
+        if (neg) c = mag == 0 ? 0x01u : (0x80u | (mag - 1u));
+        else if (mag < 0x7eu) c = mag + 1u;
+    } else if (!up && d > x) {
+        if (!neg) c = mag == 0 ? 0x81u : (mag - 1u);
+        else if (mag < 0x7eu) c = 0x80u | (mag + 1u);
+    }
+    return c;
+}
+
 // CF8: the centre is stored as 128 e4m3 codes in the order the matrix-core operand wants them
 // (byte kq*32 + kk*8 + j holds coordinate kk*32 + kq*8 + j); only for bf16 caches.
 template <typename KT, bool CF8 = false>
@@ -169,6 +194,11 @@ build_groups_kernel(const void *__restrict__ K, void *__restrict__ centres, floa
 // rounding allowance for the bound  sum_c (q+_c hi_c + q-_c lo_c)  evaluated in fp32 over 256
 // terms: 2^-15 * |a|_2 with a_c = max(|lo_c|, |hi_c|); times |q|_2 it exceeds the rounding error
 // by Cauchy-Schwarz, so a computed bound never falls below a member's exact score.
+// CF8: the corners are stored as e4m3 codes in matrix-operand order, the upper corner rounded up and
+// the lower corner rounded down, so the stored box contains the exact one.  A member beyond +-448
+// cannot be enclosed by a code; what sticks out (e_c per coordinate) is added to the allowance as
+// |e|_2, which times |q|_2 exceeds sum_c |q_c| e_c.
+template <bool CF8>
 __global__ void __launch_bounds__(256)
 build_boxes_kernel(const void *__restrict__ K, void *__restrict__ corners, float *__restrict__ allowance,
                    int64_t cap_rows, int64_t max_groups, int64_t g0, int64_t g1, int r) {
@@ -194,6 +224,35 @@ build_boxes_kernel(const void *__restrict__ K, void *__restrict__ corners, float
         }
     }
     float a2 = 0.f;
+    if constexpr (CF8) {
+        uint32_t ch[8], cl[8];
+        float e2 = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            ch[e] = f32_to_e4m3_directed(hi[e], true);
+            cl[e] = f32_to_e4m3_directed(lo[e], false);
+            const float hd = e4m3_value(ch[e]), ld = e4m3_value(cl[e]);
+            const float out = fmaxf(fmaxf(hi[e] - hd, ld - lo[e]), 0.f);   // non-zero only beyond +-448
+            e2 += out * out;
+            const float a = fmaxf(fabsf(ld), fabsf(hd));
+            a2 += a * a;
+        }
+        a2 = seg_sum(a2, 16);
+        e2 = seg_sum(e2, 16);
+        if (valid) {
+            char *dst = static_cast<char *>(corners) + ((int64_t)bh * max_groups + g) * 2 * LVR_D;
+            const int at = (li & 3) * 32 + (li >> 2) * 8;
+            *reinterpret_cast<uint2 *>(dst + at) = make_uint2(ch[0] | (ch[1] << 8) | (ch[2] << 16) | (ch[3] << 24),
+                                                              ch[4] | (ch[5] << 8) | (ch[6] << 16) | (ch[7] << 24));
+            *reinterpret_cast<uint2 *>(dst + LVR_D + at) = make_uint2(cl[0] | (cl[1] << 8) | (cl[2] << 16) | (cl[3] << 24),
+                                                                      cl[4] | (cl[5] << 8) | (cl[6] << 16) | (cl[7] << 24));
+            if (li == 0) {
+                float al = sqrtf(a2) * 0x1p-15f + sqrtf(e2) * (1.0f + 0x1p-20f);
+                allowance[(int64_t)bh * max_groups + g] = __uint_as_float(__float_as_uint(al) + 1u);
+            }
+        }
+        return;
+    }
     uint32_t bh_[8], bl_[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -246,8 +305,12 @@ hipError_t lvr_launch_build_groups(lvr_index *ix, int64_t g0, int64_t g1, hipStr
     if (g1 <= g0) return hipSuccess;
     dim3 grid((unsigned)((g1 - g0 + 15) / 16), (unsigned)lvr_n_bh(ix));
     if (ix->box) {
-        hipLaunchKernelGGL(build_boxes_kernel, grid, dim3(256), 0, st, ix->K, ix->centres, ix->radii, ix->cap_rows,
-                           ix->max_groups, g0, g1, ix->cfg.group_size);
+        if (ix->cf8)
+            hipLaunchKernelGGL(build_boxes_kernel<true>, grid, dim3(256), 0, st, ix->K, ix->centres, ix->radii, ix->cap_rows,
+                               ix->max_groups, g0, g1, ix->cfg.group_size);
+        else
+            hipLaunchKernelGGL(build_boxes_kernel<false>, grid, dim3(256), 0, st, ix->K, ix->centres, ix->radii, ix->cap_rows,
+                               ix->max_groups, g0, g1, ix->cfg.group_size);
         return hipGetLastError();
     }
     if (ix->cf8)

@@ -44,13 +44,15 @@ struct FusedArgs {
 };
 
 // UA = centre tiles per phase-A trip; ENC = 1: boxes instead of balls; Q1 = 1: per-block thresholds (S <= 4);
-// CF8 = 1: centres stored as e4m3 codes (balls, S <= 4)
+// CF8 = 1: centres (balls, S <= 4) or box corners stored as e4m3 codes
 template <int HB, int S, int UA, int ENC, int Q1 = 0, int CF8 = 0>
 __global__ void __launch_bounds__(256)
 query_fused_kernel(const FusedArgs a) {
     static_assert(!Q1 || !ENC, "Query 1 is built for balls");
     static_assert(!Q1 || S <= 4 || !CF8, "8-bit centres: at most four coordinate blocks");
-    static_assert(!CF8 || (S <= 4 && !ENC), "8-bit centres: balls, at most four coordinate blocks");
+    static_assert(!CF8 || S <= 4, "8-bit centres: at most four coordinate blocks");
+    // RP: the radii of 8-bit balls come pre-split for the matrix cores; boxes keep one fp32 allowance per group
+    constexpr bool RP = CF8 && !ENC;
     // the staging area of the query operand is dead once every wave holds its fragments; the score
     // queues of the emitters live in the same bytes afterwards (LDS per workgroup decides how many
     // workgroups a CU holds: 4 KB more costs one of four)
@@ -76,7 +78,7 @@ query_fused_kernel(const FusedArgs a) {
     constexpr int SP = (S <= 4) ? S : 1;      // radii are fetched ahead only when they are few
     // balls: one row per group (the centre); boxes: two rows per group (upper corner, lower corner)
     const char *Cb = static_cast<const char *>(a.centres) + (int64_t)bh * a.max_groups * LVR_D * (CF8 ? 1 : 2) * (ENC ? 2 : 1);
-    const float *Rb = a.radii + (int64_t)bh * a.max_groups * (CF8 ? 4 : S);   // 8-bit centres: 16 bytes of pre-split radii per group
+    const float *Rb = a.radii + (int64_t)bh * a.max_groups * (RP ? 4 : S);   // 8-bit centres: 16 bytes of pre-split radii per group
     const int64_t n_tiles = (a.n_groups + 15) >> 4;
     const int64_t tile0 = ((int64_t)blockIdx.x * 4 + wave) * a.tiles_per_wave;
     // RM: the radius term rides on the matrix cores as a fifth step (S <= 4, one threshold per head);
@@ -85,10 +87,10 @@ query_fused_kernel(const FusedArgs a) {
     constexpr bool RM = !Q1 && S <= 4;
     // operands of one trip (UA tiles of 16 groups) as they arrive from HBM
     struct Trip {
-        uint4 av[UA][CF8 ? 2 : 4], av2[ENC ? UA : 1][4];
+        uint4 av[UA][CF8 ? 2 : 4], av2[ENC ? UA : 1][CF8 ? 2 : 4];
         float rad[RM ? 1 : UA][4][SP];
-        float rrow[(RM && !CF8) ? UA : 1][SP];
-        uint4 rblk[(RM && CF8) ? UA : 1];
+        float rrow[(RM && !RP) ? UA : 1][SP];
+        uint4 rblk[(RM && RP) ? UA : 1];
     };
     // 8-bit centres leave room for two trips in registers: the next trip's loads are issued before
     // the current trip is scored, so the memory pipe does not drain between trips
@@ -102,7 +104,10 @@ query_fused_kernel(const FusedArgs a) {
             const int64_t g0 = (tile0 + it + u) * 16;
             int64_t g = g0 + n;
             if (g >= a.n_groups) g = a.n_groups - 1;
-            if constexpr (ENC) {
+            if constexpr (ENC && CF8) {
+                lvr_load_a_codes(Cb, 2 * g, av[u]);
+                lvr_load_a_codes(Cb, 2 * g + 1, av2[u]);
+            } else if constexpr (ENC) {
                 lvr_load_a_frags(Cb, 2 * g, av[u]);
                 lvr_load_a_frags(Cb, 2 * g + 1, av2[u]);
             } else if constexpr (CF8) {
@@ -110,7 +115,7 @@ query_fused_kernel(const FusedArgs a) {
             } else {
                 lvr_load_a_frags(Cb, g, av[u]);
             }
-            if constexpr (RM && CF8) {
+            if constexpr (RM && RP) {
                 rblk[u] = reinterpret_cast<const uint4 *>(Rb)[g];
             } else if constexpr (RM) {
                 const float *rp = Rb + g * S;
@@ -127,7 +132,7 @@ query_fused_kernel(const FusedArgs a) {
                     int64_t gj = g0 + 4 * kq + j;
                     if (gj >= a.n_groups) gj = a.n_groups - 1;
                     const float *rp = Rb + gj * S;
-                    if constexpr (CF8) {   // pre-split radii: rho_s = slot s + slot S+s (exact in fp32)
+                    if constexpr (RP) {   // pre-split radii: rho_s = slot s + slot S+s (exact in fp32)
                         const uint4 blk = reinterpret_cast<const uint4 *>(Rb)[gj];
                         const uint32_t w[4] = {blk.x, blk.y, blk.z, blk.w};
 #pragma unroll
@@ -180,7 +185,7 @@ query_fused_kernel(const FusedArgs a) {
     if constexpr (RM) {
         if (!buffer_wg) {
 #pragma unroll
-            for (int hb = 0; hb < HB; ++hb) rbq[hb] = lvr_radius_b_frag<S, CF8 ? 2 : 3>(s_qn, a.G, hb);
+            for (int hb = 0; hb < HB; ++hb) rbq[hb] = lvr_radius_b_frag<S, RP ? 2 : 3>(s_qn, a.G, hb);
         }
     }
     float taue[HB];
@@ -218,11 +223,17 @@ query_fused_kernel(const FusedArgs a) {
                 const int64_t g_row = (tile0 + it + u) * 16;
                 uint32_t alive4 = 0;
                 uint4 ac[4];   // the tile's operand pieces (decoded from the 8-bit codes if that is how they are stored)
+                uint4 ac2[ENC ? 4 : 1];   // boxes: the lower corners
+                (void)ac2;
                 if constexpr (CF8) {
                     lvr_codes_to_a_frags(av[u], ac);
+                    if constexpr (ENC) lvr_codes_to_a_frags(av2[u], ac2);
                 } else {
 #pragma unroll
-                    for (int kk = 0; kk < 4; ++kk) ac[kk] = av[u][kk];
+                    for (int kk = 0; kk < 4; ++kk) {
+                        ac[kk] = av[u][kk];
+                        if constexpr (ENC) ac2[kk] = av2[u][kk];
+                    }
                 }
 #pragma unroll
                 for (int hb = 0; hb < HB; ++hb) {
@@ -298,12 +309,12 @@ query_fused_kernel(const FusedArgs a) {
                     lvr_f32x4 sc;
                     if constexpr (RM) {
                         lvr_bf16x8 ra;
-                        if constexpr (CF8) ra = lvr_radius_a_stored(rblk[u]);
+                        if constexpr (RP) ra = lvr_radius_a_stored(rblk[u]);
                         else ra = lvr_radius_a_frag<S>(rrow[u]);
-                        if constexpr (ENC) sc = lvr_bound_tile2(ac, bq[hb], av2[u], bq2[hb], ra, rbq[hb]);
+                        if constexpr (ENC) sc = lvr_bound_tile2(ac, bq[hb], ac2, bq2[hb], ra, rbq[hb]);
                         else sc = lvr_bound_tile(ac, bq[hb], ra, rbq[hb]);
                     } else {
-                        if constexpr (ENC) sc = lvr_score_tile2(ac, bq[hb], av2[u], bq2[hb]);
+                        if constexpr (ENC) sc = lvr_score_tile2(ac, bq[hb], ac2, bq2[hb]);
                         else sc = lvr_score_tile(ac, bq[hb]);
                     }
 #pragma unroll
@@ -552,6 +563,11 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
             else LVR_Q1_LAUNCH(2, 0);
         }
 #undef LVR_Q1_LAUNCH
+        return hipGetLastError();
+    }
+    if (ix->box && ix->cf8) {   // boxes with 8-bit corners
+        if (ix->G <= 4) hipLaunchKernelGGL((query_fused_kernel<1, 1, 1, 1, 0, 1>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((query_fused_kernel<2, 1, 1, 1, 0, 1>), grid, dim3(256), 0, st, a);
         return hipGetLastError();
     }
     if (ix->cf8) {   // 8-bit centres

@@ -487,26 +487,49 @@ def test_everything_qualifies_large(G, oracle):
 
 
 # ------------------------------------------------------------------ box enclosure (Def. 1, AABB)
+def _e4m3_values():
+    """All finite e4m3 values (OCP: bias 7, subnormals below 2^-6, largest 448), ascending."""
+    v = []
+    for code in range(0x7f):
+        ex, m = code >> 3, code & 7
+        v.append(m / 8.0 * 2.0 ** -6 if ex == 0 else (1 + m / 8.0) * 2.0 ** (ex - 7))
+    v = np.array(v)
+    return np.concatenate([-v[:0:-1], v])
+
+
+@pytest.mark.parametrize("centres", ["same", "fp8"])
 @pytest.mark.parametrize("r,hq,hkv", [(4, 8, 2), (2, 4, 1), (16, 16, 2), (1, 2, 2)])
-def test_box_enclosure_index_and_queries(G, oracle, r, hq, hkv):
+def test_box_enclosure_index_and_queries(G, oracle, r, hq, hkv, centres):
     """Boxes instead of balls: the stored corners are exactly the per-coordinate extremes of each
-    group, the number of surviving groups matches the oracle's box bound, and query + attention
+    group (bf16 corners) or the nearest e4m3 values outside them (8-bit corners), the number of
+    surviving groups matches the oracle's box bound on the stored corners, and query + attention
     equal the oracle's."""
     import paper_2605_06763_amd as L
     n = 1100
     cache = _small_cache(2, n, hkv=hkv)
     q = W.make_queries(2, n_q_heads=hq)
     Gq = hq // hkv
-    with G.Index(cache.K, cache.V, "bf16", hq, group_size=r, enclosing=L.LVR_ENCLOSE_AABB, buffer_size=64) as ix:
+    idt = L.LVR_INDEX_FP8 if centres == "fp8" else L.LVR_INDEX_SAME
+    with G.Index(cache.K, cache.V, "bf16", hq, group_size=r, enclosing=L.LVR_ENCLOSE_AABB, buffer_size=64,
+                 index_dtype=idt) as ix:
         corners, allow, slot_pos, keys = ix.export()
         n_idx = n // r * r
         label = (np.arange(n_idx) // r).astype(np.int32)
+        stored = []
         for h in range(hkv):
             lo, hi = oracle.aabb_index(cache.K[0, h, :n_idx], label, n_idx // r)
             got_hi = W.bf16_bits_to_f32(corners[0, h, :, 0]).reshape(-1, 128)
             got_lo = W.bf16_bits_to_f32(corners[0, h, :, 1]).reshape(-1, 128)
-            assert np.array_equal(got_hi, hi.astype(np.float32)) and np.array_equal(got_lo, lo.astype(np.float32))
-            a = np.maximum(np.abs(lo), np.abs(hi))
+            stored.append((got_lo.astype(np.float64), got_hi.astype(np.float64)))
+            if centres == "same":
+                assert np.array_equal(got_hi, hi.astype(np.float32)) and np.array_equal(got_lo, lo.astype(np.float32))
+            else:
+                vals = _e4m3_values()
+                want_hi = vals[np.minimum(np.searchsorted(vals, hi, side="left"), len(vals) - 1)]     # smallest value >= hi
+                want_lo = vals[np.maximum(np.searchsorted(vals, lo, side="right") - 1, 0)]             # largest value <= lo
+                assert np.array_equal(got_hi, want_hi.astype(np.float32)) and np.array_equal(got_lo, want_lo.astype(np.float32))
+                assert np.all(got_hi >= hi) and np.all(got_lo <= lo)                                   # these keys stay inside +-448
+            a = np.maximum(np.abs(got_lo), np.abs(got_hi))
             # the allowance must exceed the fp32 error bound 2^-16 |a| of the 256-term bound (it is twice that)
             assert np.all(allow[0, h, :, 0] >= 2.0 ** -15 * np.linalg.norm(a, axis=1) * (1 - 1e-5))
             assert np.all(allow[0, h, :, 0] <= 2.0 ** -14 * np.linalg.norm(a, axis=1) + 1e-30)
@@ -515,11 +538,11 @@ def test_box_enclosure_index_and_queries(G, oracle, r, hq, hkv):
             for boost in (1.0, 2.5):
                 t = (tau * boost).astype(np.float32) if frac < 0.1 else tau
                 idx, cnt, out = ix.query(q, t, fused=True)
-                G.check_step(oracle, ix, q, t, idx, cnt, out, tag=f"box r={r} frac={frac} boost={boost}")
+                G.check_step(oracle, ix, q, t, idx, cnt, out, tag=f"box r={r} frac={frac} boost={boost} {centres}")
                 st = ix.stats()
                 lo_cnt = hi_cnt = 0
                 for h in range(hkv):
-                    lo, hi = oracle.aabb_index(cache.K[0, h, :n_idx], label, n_idx // r)
+                    lo, hi = stored[h]
                     # the kernel adds its rounding allowance (stored per group) times |q| to the box bound
                     ub = np.stack([oracle.aabb_bounds(q[0, h * Gq + g], lo, hi)
                                    + allow[0, h, :, 0].astype(np.float64) * np.linalg.norm(q[0, h * Gq + g].astype(np.float64))
@@ -531,15 +554,55 @@ def test_box_enclosure_index_and_queries(G, oracle, r, hq, hkv):
                 assert lo_cnt <= st["groups_surviving"] <= hi_cnt, (lo_cnt, st["groups_surviving"], hi_cnt)
 
 
+def test_box_8bit_corners_beyond_the_code_range(G, oracle):
+    """Members beyond +-448 cannot be enclosed by an e4m3 corner: the corner saturates and what sticks
+    out goes into the group's allowance, so no qualifying key is lost; tiny and zero coordinates round
+    outwards to the smallest codes."""
+    import paper_2605_06763_amd as L
+    n, r = 512, 4
+    cache = _small_cache(2, n, hkv=1)
+    K = cache.K.copy()
+    g = np.random.default_rng(5)
+    K[0, 0, 8:12, 3] = [500.0, 1000.0, -30.0, 2.0]          # upper corner beyond the range
+    K[0, 0, 16:20, 7] = [-600.0, -449.0, 5.0, 0.0]          # lower corner beyond the range
+    K[0, 0, 24:28, :] = 0.0                                  # a group of zeros
+    K[0, 0, 32:36, 5] = [1e-5, -1e-5, 0.0, 2e-6]            # below the smallest code
+    K = W.round_to_bf16(K)
+    q = W.make_queries(2, n_q_heads=4)
+    with G.Index(K, cache.V, "bf16", 4, group_size=r, enclosing=L.LVR_ENCLOSE_AABB, index_dtype=L.LVR_INDEX_FP8) as ix:
+        corners, allow, _, _ = ix.export()
+        hi = W.bf16_bits_to_f32(corners[0, 0, :, 0]).reshape(-1, 128).astype(np.float64)
+        lo = W.bf16_bits_to_f32(corners[0, 0, :, 1]).reshape(-1, 128).astype(np.float64)
+        Kg = K[0, 0].reshape(n // r, r, 128).astype(np.float64)
+        out_hi = np.maximum(Kg.max(axis=1) - hi, 0)
+        out_lo = np.maximum(lo - Kg.min(axis=1), 0)
+        sticks = np.linalg.norm(np.maximum(out_hi, out_lo), axis=1)
+        assert sticks[2] > 500 and sticks[4] > 150 and np.count_nonzero(sticks) == 2
+        assert hi[2, 3] == 448.0 and lo[4, 7] == -448.0
+        assert np.all(allow[0, 0, :, 0] >= sticks)
+        assert np.all(hi[6] == 0) and np.all(lo[6] == 0)
+        assert hi[8, 5] == 2.0 ** -9 and lo[8, 5] == -2.0 ** -9
+        # every member's score stays below its group's bound: exact scores against stored corners + allowance
+        for h in range(4):
+            ub = oracle.aabb_bounds(q[0, h], lo, hi) + allow[0, 0, :, 0].astype(np.float64) * np.linalg.norm(q[0, h].astype(np.float64))
+            sc = oracle.scores_f64(q[0, h], K[0, 0]).reshape(n // r, r)
+            assert np.all(sc.max(axis=1) <= ub)
+        for frac in (0.01, 0.2):
+            tau = G.oracle_taus(oracle, ix, q, frac=frac)
+            idx, cnt, out = ix.query(q, tau, fused=True)
+            G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=f"box fp8 range frac={frac}")
+
+
 def test_box_enclosure_with_tree_grouping_and_append(G, oracle):
     import paper_2605_06763_amd as L
     n0, steps, B = 200, 40, 32
     cache = _small_cache(5, n0)
     k_new, v_new = W.make_append_stream(5, steps, cache)
     qs = W.drift_queries(5, steps, n_q_heads=8)
-    for grouping in (L.LVR_GROUP_CONTIGUOUS, L.LVR_GROUP_TREE):
+    for grouping, idt in ((L.LVR_GROUP_CONTIGUOUS, L.LVR_INDEX_SAME), (L.LVR_GROUP_TREE, L.LVR_INDEX_SAME),
+                          (L.LVR_GROUP_CONTIGUOUS, L.LVR_INDEX_FP8), (L.LVR_GROUP_TREE, L.LVR_INDEX_FP8)):
         with G.Index(cache.K, cache.V, "bf16", 8, capacity=n0 + steps, buffer_size=B, grouping=grouping,
-                     enclosing=L.LVR_ENCLOSE_AABB) as ix:
+                     enclosing=L.LVR_ENCLOSE_AABB, index_dtype=idt) as ix:
             for t in range(steps):
                 ix.append(k_new[t][:, :, None, :], v_new[t][:, :, None, :])
                 if t % 13 == 0 or t == steps - 1:
@@ -554,15 +617,16 @@ def test_box_versus_ball_pruning_on_local_keys(G, oracle):
     K, V = cache.K[:, :2], cache.V[:, :2]
     q = W.make_queries(2, n_q_heads=8)
     surv = {}
-    for name, enc in (("ball", L.LVR_ENCLOSE_BALL), ("box", L.LVR_ENCLOSE_AABB)):
-        with G.Index(K, V, "bf16", 8, enclosing=enc) as ix:
+    for name, enc, idt in (("ball", L.LVR_ENCLOSE_BALL, L.LVR_INDEX_SAME), ("box", L.LVR_ENCLOSE_AABB, L.LVR_INDEX_SAME),
+                           ("ball8", L.LVR_ENCLOSE_BALL, L.LVR_INDEX_FP8), ("box8", L.LVR_ENCLOSE_AABB, L.LVR_INDEX_FP8)):
+        with G.Index(K, V, "bf16", 8, enclosing=enc, index_dtype=idt) as ix:
             tau = G.oracle_taus(oracle, ix, q, frac=0.02)
             idx, cnt, out = ix.query(q, tau, fused=True)
             G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=name)
             st = ix.stats()
             surv[name] = st["groups_surviving"] / st["groups_scored"]
     G.say("surviving fraction on keys with positional locality:", surv)
-    assert surv["ball"] < 0.25 and surv["box"] < 0.25
+    assert surv["ball"] < 0.25 and surv["box"] < 0.25 and surv["box8"] < 0.3 and surv["box"] <= surv["box8"]
 
 
 def test_box_enclosure_unsupported_combinations():
@@ -1083,7 +1147,8 @@ def test_fp8_centres_unsupported_configurations(G):
     L = G.L
     ok = dict(batch=1, n_q_heads=8, n_kv_heads=2, capacity=1024, index_dtype=L.LVR_INDEX_FP8)
     assert L.lvr_arena_bytes(L.make_config(**ok)) > 0
-    for bad in (dict(ok, kv_dtype=L.LVR_F32), dict(ok, enclosing=L.LVR_ENCLOSE_AABB), dict(ok, n_subspaces=8),
+    assert L.lvr_arena_bytes(L.make_config(**dict(ok, enclosing=L.LVR_ENCLOSE_AABB, n_subspaces=16))) > 0
+    for bad in (dict(ok, kv_dtype=L.LVR_F32), dict(ok, n_subspaces=8),
                 dict(ok, flags=L.LVR_SEPARATE_KERNELS), dict(ok, index_dtype=3)):
         assert L.lvr_arena_bytes(L.make_config(**bad)) == 0
     # AUTO falls back to the cache's own format where 8-bit centres are not supported
