@@ -345,7 +345,7 @@ def main():
         "config": {"workload": f"config{cid}:{c['name']}" + (" [supplementary: keys with positional locality]" if args.keys == "local" else ""), "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
                    "head_dim": d, "context": int(n_now), "kv_storage": "bf16", "group_size": args.group_size,
                    "subspaces": args.subspaces, "attn_splits": args.attn_splits, "grouping": args.grouping,
-                   "centres": ("fp8" if index_bytes_per_group < 256 else "bf16"), "enclosing": args.enclosing,
+                   "centres": ("fp8" if index_bytes_per_group < (512 if args.enclosing == "aabb" else 256) else "bf16"), "enclosing": args.enclosing,
                    "step": "append+query+attention" if appending else "query+attention",
                    "update": "two-stream" if args.concurrent_update else "single-stream",
                    "kv_memory": "host (pinned, read in place)" if args.offload else "hbm",
