@@ -1318,3 +1318,80 @@ def test_decode_step_under_graph_capture(G, oracle):
             np.testing.assert_allclose(o_g, o_e, rtol=1e-5, atol=1e-6)
             G.check_step(oracle, ix, qs[t], taus[t], i_g, c_g, o_g, tag=f"graph replay {t}")
         del graph
+
+
+# ---------------------------------------------------------------------------------------------
+# Seeded random sequences of calls on one index
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("case", range(24))
+def test_random_call_sequences(G, oracle, case):
+    """A seeded random walk through the entry points on one index (appends of random length, the
+    one-call append + step, explicit publishes, rebuilds, queries in both launch forms, Query 1 with the
+    library's thresholds, dense attention, the reservoir): after every step the state and every result
+    equal the oracle's on the keys held so far."""
+    L = G.L
+    g = np.random.default_rng(7000 + case)
+    hkv, Gq = int(g.choice([1, 2])), int(g.choice([1, 4, 8]))
+    hq = hkv * Gq
+    r = int(g.choice([1, 4, 8]))
+    S = int(g.choice([1, 4]))
+    B = int(g.choice([16, 32, 64])) * (r if r > 4 else 1)
+    grouping = int(g.choice([L.LVR_GROUP_CONTIGUOUS, L.LVR_GROUP_CONTIGUOUS, L.LVR_GROUP_TREE]))
+    flags = int(g.choice([0, 0, L.LVR_CONCURRENT_UPDATE, L.LVR_SEPARATE_KERNELS]))
+    idt = int(g.choice([L.LVR_INDEX_AUTO, L.LVR_INDEX_SAME]))
+    R = int(g.choice([0, 64]))
+    cap = 1500
+    pool = W.make_local_cache(2, n=cap, n_kv_heads=hkv) if case % 2 else W.make_cache(2, n=cap, n_kv_heads=hkv)
+    n0 = int(g.integers(0, 400))
+    desc = f"sequence {case}: hq={hq} hkv={hkv} r={r} S={S} B={B} grouping={grouping} flags={flags} centres={idt} R={R} n0={n0}"
+    G.say(desc)
+    with G.Index(pool.K[:, :, :n0], pool.V[:, :, :n0], "bf16", hq, capacity=cap, group_size=r, n_subspaces=S,
+                 buffer_size=B, grouping=grouping, flags=flags, index_dtype=idt, reservoir_size=R, seed=case) as ix:
+        have = n0
+        fused_ok = not (flags & L.LVR_SEPARATE_KERNELS)
+        for step in range(14):
+            op = g.choice(["append", "append", "append_step", "query", "query", "query1", "dense", "publish", "rebuild"])
+            q = W.make_queries(2, n_q_heads=hq, step=100 * case + step)
+            tag = f"{desc} step {step} {op} n={have}"
+            if op == "append" and have < cap:
+                m = int(min(g.choice([1, 1, 3, B - 1, B, 2 * B + 5]), cap - have))
+                ix.append(pool.K[:, :, have:have + m], pool.V[:, :, have:have + m])
+                have += m
+            elif op == "append_step" and have < cap:
+                m = int(min(g.choice([1, 1, 2, 70]), cap - have))
+                kk, vv = pool.K[:, :, have:have + m], pool.V[:, :, have:have + m]
+                ix.K = np.concatenate([ix.K, kk], axis=2)
+                ix.V = np.concatenate([ix.V, vv], axis=2)
+                have += m
+                tau = G.oracle_taus(oracle, ix, q, frac=0.05)
+                qd, td = torch.from_numpy(q).cuda(), torch.from_numpy(tau).cuda()
+                out = torch.full((1, hq, 128), float("nan"), device="cuda")
+                idx = torch.full((1, hq, cap), -7, dtype=torch.int32, device="cuda")
+                cnt = torch.full((1, hq), -7, dtype=torch.int32, device="cuda")
+                L.lvr_append_decode_step(ix.h, G.to_device(kk, "bf16"), G.to_device(vv, "bf16"), qd, td, out, idx, cnt)
+                torch.cuda.synchronize()
+                G.check_step(oracle, ix, q, tau, idx.cpu().numpy(), cnt.cpu().numpy(), out.cpu().numpy(), tag=tag)
+            elif op == "query" and have > 0:
+                tau = G.oracle_taus(oracle, ix, q, frac=float(g.choice([0.01, 0.2, 1.0])))
+                idx, cnt, out = ix.query(q, tau, fused=bool(g.integers(0, 2)))
+                G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=tag)
+            elif op == "query1" and have > 0 and fused_ok:
+                tau = G.oracle_taus(oracle, ix, q, frac=0.03)
+                idx, cnt, out = G.query1(ix, q, G.subspace_thresholds(ix, q, tau), tau)
+                G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=tag)
+            elif op == "dense" and have > 0:
+                ref = oracle.dense_attention(ix.K, ix.V, q, ix.sigma, hq)
+                got = ix.dense(q)
+                assert (np.abs(got - ref).max(axis=-1) / np.abs(ref).max(axis=-1)).max() <= G.ATTN_TOL, tag
+            elif op == "publish":
+                L.lvr_publish(ix.h)
+                assert ix.stats(raise_on_overflow=False)["update_pending"] == 0, tag
+            elif op == "rebuild":
+                have = int(g.integers(0, 300))
+                ix.K, ix.V = pool.K[:, :, :have].copy(), pool.V[:, :, :have].copy()
+                L.lvr_build(ix.h, G.to_device(ix.K, "bf16"), G.to_device(ix.V, "bf16"))
+            n, n_indexed = L.lvr_length(ix.h)
+            assert n == have == ix.K.shape[2], tag
+            assert n_indexed % r == 0 and 0 <= n - n_indexed < 2 * B + r, (tag, n, n_indexed)
+            if R:
+                _check_reservoir(oracle, ix, case, R)
