@@ -54,8 +54,7 @@ query_fused_kernel(const FusedArgs a) {
     // RP: the radii of 8-bit balls come pre-split for the matrix cores; boxes keep one fp32 allowance per group
     constexpr bool RP = CF8 && !ENC;
     // the staging area of the query operand is dead once every wave holds its fragments; the score
-    // queues of the emitters live in the same bytes afterwards (LDS per workgroup decides how many
-    // workgroups a CU holds: 4 KB more costs one of four)
+    // queues of the emitters live in the same bytes afterwards
     __shared__ union {
         uint4 bq[HB][4][64];
         float qscore[4][HB][4][LVR_QCAP];
