@@ -60,6 +60,12 @@ query_fused_kernel(const FusedArgs a) {
         float qscore[4][HB][4][LVR_QCAP];
     } s_u;
     static_assert(sizeof(s_u.bq) == sizeof(s_u.qscore), "aliasing assumes equal sizes");
+    // BL: with eight heads per KV head the query operand (two head blocks, 32 registers) stays in LDS
+    // and a lane fetches its pieces right before the matrix instructions that use them; that brings
+    // the kernel back under the register budget of four waves per SIMD.  The staging area then keeps
+    // its content, so the score queues get bytes of their own.
+    constexpr bool BL = HB == 2 && !ENC && !Q1;
+    __shared__ float s_qs2[BL ? 4 : 1][BL ? HB : 1][4][BL ? LVR_QCAP : 1];
     __shared__ uint4 s_bq2[ENC ? HB : 1][4][64];
     __shared__ float s_qn[HB * 4][16];
     __shared__ int32_t s_queue[4][HB][4][LVR_QCAP];
@@ -180,6 +186,15 @@ query_fused_kernel(const FusedArgs a) {
     lvr_bf16x8 bq[HB][4], bq2[ENC ? HB : 1][4];
     lvr_build_q_frags_wg<HB>(a.q + hq0 * LVR_D, a.G, 1.0f, s_u.bq, bq, ENC ? 1 : 0);   // syncs
     if constexpr (ENC) lvr_build_q_frags_wg<HB>(a.q + hq0 * LVR_D, a.G, 1.0f, s_bq2, bq2, -1);
+    // BL: the pieces of head block hb, fetched anew at every use (the index register comes out of an
+    // opaque instruction so that the loads are not hoisted out of the loops and kept in registers)
+    auto fetch_bq = [&](int hb, lvr_bf16x8 (&b)[4]) {
+        int z;
+        asm volatile("v_mov_b32 %0, 0" : "=v"(z));
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) b[kk] = __builtin_bit_cast(lvr_bf16x8, s_u.bq[hb][kk][lane + z]);
+    };
+    (void)fetch_bq;
     lvr_bf16x8 rbq[RM ? HB : 1];
     if constexpr (RM) {
         if (!buffer_wg) {
@@ -311,10 +326,18 @@ query_fused_kernel(const FusedArgs a) {
                         if constexpr (RP) ra = lvr_radius_a_stored(rblk[u]);
                         else ra = lvr_radius_a_frag<S>(rrow[u]);
                         if constexpr (ENC) sc = lvr_bound_tile2(ac, bq[hb], ac2, bq2[hb], ra, rbq[hb]);
-                        else sc = lvr_bound_tile(ac, bq[hb], ra, rbq[hb]);
+                        else if constexpr (BL) {
+                            lvr_bf16x8 b[4];
+                            fetch_bq(hb, b);
+                            sc = lvr_bound_tile(ac, b, ra, rbq[hb]);
+                        } else sc = lvr_bound_tile(ac, bq[hb], ra, rbq[hb]);
                     } else {
                         if constexpr (ENC) sc = lvr_score_tile2(ac, bq[hb], ac2, bq2[hb]);
-                        else sc = lvr_score_tile(ac, bq[hb]);
+                        else if constexpr (BL) {
+                            lvr_bf16x8 b[4];
+                            fetch_bq(hb, b);
+                            sc = lvr_score_tile(ac, b);
+                        } else sc = lvr_score_tile(ac, bq[hb]);
                     }
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
@@ -426,7 +449,8 @@ query_fused_kernel(const FusedArgs a) {
 #pragma unroll
     for (int hb = 0; hb < HB; ++hb) {
         em[hb].q = s_queue[wave][hb];
-        em[hb].qs = s_u.qscore[wave][hb];
+        if constexpr (BL) em[hb].qs = s_qs2[wave][hb];
+        else em[hb].qs = s_u.qscore[wave][hb];
         em[hb].count = 0;
         em[hb].rep_base = 8;
         em[hb].hq_base = hq0 + hb * 4;
@@ -456,7 +480,11 @@ query_fused_kernel(const FusedArgs a) {
             for (int hb = 0; hb < HB; ++hb) {
                 lvr_f32x4 s;
                 if constexpr (ENC) s = lvr_score_tile2(av[u], bq[hb], av[u], bq2[hb]);
-                else s = lvr_score_tile(av[u], bq[hb]);
+                else if constexpr (BL) {
+                    lvr_bf16x8 b[4];
+                    fetch_bq(hb, b);
+                    s = lvr_score_tile(av[u], b);
+                } else s = lvr_score_tile(av[u], bq[hb]);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int trow = 4 * kq + j;
