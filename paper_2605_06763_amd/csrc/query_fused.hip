@@ -64,7 +64,7 @@ query_fused_kernel(const FusedArgs a) {
     // and a lane fetches its pieces right before the matrix instructions that use them; that brings
     // the kernel back under the register budget of four waves per SIMD.  The staging area then keeps
     // its content, so the score queues get bytes of their own.
-    constexpr bool BL = HB == 2 && !ENC && !Q1;
+    constexpr bool BL = HB == 2 && !Q1;
     __shared__ float s_qs2[BL ? 4 : 1][BL ? HB : 1][4][BL ? LVR_QCAP : 1];
     __shared__ uint4 s_bq2[ENC ? HB : 1][4][64];
     __shared__ float s_qn[HB * 4][16];
@@ -194,7 +194,14 @@ query_fused_kernel(const FusedArgs a) {
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) b[kk] = __builtin_bit_cast(lvr_bf16x8, s_u.bq[hb][kk][lane + z]);
     };
+    auto fetch_bq2 = [&](int hb, lvr_bf16x8 (&b)[4]) {   // boxes: the negative part of q
+        int z;
+        asm volatile("v_mov_b32 %0, 0" : "=v"(z));
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) b[kk] = __builtin_bit_cast(lvr_bf16x8, s_bq2[ENC ? hb : 0][kk][lane + z]);
+    };
     (void)fetch_bq;
+    (void)fetch_bq2;
     lvr_bf16x8 rbq[RM ? HB : 1];
     if constexpr (RM) {
         if (!buffer_wg) {
@@ -325,14 +332,24 @@ query_fused_kernel(const FusedArgs a) {
                         lvr_bf16x8 ra;
                         if constexpr (RP) ra = lvr_radius_a_stored(rblk[u]);
                         else ra = lvr_radius_a_frag<S>(rrow[u]);
-                        if constexpr (ENC) sc = lvr_bound_tile2(ac, bq[hb], ac2, bq2[hb], ra, rbq[hb]);
+                        if constexpr (ENC && BL) {
+                            lvr_bf16x8 b[4], b2[4];
+                            fetch_bq(hb, b);
+                            fetch_bq2(hb, b2);
+                            sc = lvr_bound_tile2(ac, b, ac2, b2, ra, rbq[hb]);
+                        } else if constexpr (ENC) sc = lvr_bound_tile2(ac, bq[hb], ac2, bq2[hb], ra, rbq[hb]);
                         else if constexpr (BL) {
                             lvr_bf16x8 b[4];
                             fetch_bq(hb, b);
                             sc = lvr_bound_tile(ac, b, ra, rbq[hb]);
                         } else sc = lvr_bound_tile(ac, bq[hb], ra, rbq[hb]);
                     } else {
-                        if constexpr (ENC) sc = lvr_score_tile2(ac, bq[hb], ac2, bq2[hb]);
+                        if constexpr (ENC && BL) {
+                            lvr_bf16x8 b[4], b2[4];
+                            fetch_bq(hb, b);
+                            fetch_bq2(hb, b2);
+                            sc = lvr_score_tile2(ac, b, ac2, b2);
+                        } else if constexpr (ENC) sc = lvr_score_tile2(ac, bq[hb], ac2, bq2[hb]);
                         else if constexpr (BL) {
                             lvr_bf16x8 b[4];
                             fetch_bq(hb, b);
@@ -479,7 +496,12 @@ query_fused_kernel(const FusedArgs a) {
 #pragma unroll
             for (int hb = 0; hb < HB; ++hb) {
                 lvr_f32x4 s;
-                if constexpr (ENC) s = lvr_score_tile2(av[u], bq[hb], av[u], bq2[hb]);
+                if constexpr (ENC && BL) {
+                    lvr_bf16x8 b[4], b2[4];
+                    fetch_bq(hb, b);
+                    fetch_bq2(hb, b2);
+                    s = lvr_score_tile2(av[u], b, av[u], b2);
+                } else if constexpr (ENC) s = lvr_score_tile2(av[u], bq[hb], av[u], bq2[hb]);
                 else if constexpr (BL) {
                     lvr_bf16x8 b[4];
                     fetch_bq(hb, b);
