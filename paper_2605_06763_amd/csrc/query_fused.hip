@@ -476,45 +476,67 @@ query_fused_kernel(const FusedArgs a) {
     const int32_t *spos = a.slot_pos ? a.slot_pos + (int64_t)bh * a.cap_rows : nullptr;
     const int rmask = (1 << a.log2r) - 1;
     const int64_t tiles = (rows + 15) >> 4;
-    for (int64_t t0 = wave; t0 < tiles; t0 += 8) {
-        int slot[2], nvalid[2];
-        uint4 av[2][4];
+    // This wave checks tiles wave, wave + 4, wave + 8, ...: m of them, two at a time in two register sets.
+    // Rotated form: as soon as a set has been scored the wave's next tile but one is requested into it, so
+    // loads stay outstanding while the other set is scored.  Past the end the request repeats the wave's
+    // last tile (a cache hit, never scored): every trip issues the same loads and the waits stay exact.
+    const int64_t m = tiles > wave ? (tiles - wave + 3) >> 2 : 0;
+    int slot[2], nvalid[2];
+    uint4 av[2][4];
+    auto request = [&](auto u_c, int64_t k) {
+        constexpr int u = decltype(u_c)::value;
+        const int64_t t = wave + 4 * (k < m ? k : m - 1);
+        int64_t rowidx = t * 16 + n;
+        const int64_t left = rows - t * 16;
+        nvalid[u] = k >= m ? 0 : (left < 16 ? (int)left : 16);
+        if (rowidx >= rows) rowidx = 0;
+        slot[u] = buffer_wg ? (int)(buf_row0 + rowidx)
+                            : (int)(((int64_t)s_list[rowidx >> a.log2r] << a.log2r) + (rowidx & rmask));
+        lvr_load_a_frags(Kb, slot[u], av[u]);
+    };
+    auto check = [&](auto u_c) {
+        constexpr int u = decltype(u_c)::value;
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int64_t t = t0 + 4 * u;
-            int64_t rowidx = t * 16 + n;
-            const int64_t left = rows - t * 16;
-            nvalid[u] = left <= 0 ? 0 : (left < 16 ? (int)left : 16);
-            if (rowidx >= rows) rowidx = 0;
-            slot[u] = buffer_wg ? (int)(buf_row0 + rowidx)
-                                : (int)(((int64_t)s_list[rowidx >> a.log2r] << a.log2r) + (rowidx & rmask));
-            lvr_load_a_frags(Kb, slot[u], av[u]);
-        }
+        for (int hb = 0; hb < HB; ++hb) {
+            lvr_f32x4 s;
+            if constexpr (ENC && BL) {
+                lvr_bf16x8 b[4], b2[4];
+                fetch_bq(hb, b);
+                fetch_bq2(hb, b2);
+                s = lvr_score_tile2(av[u], b, av[u], b2);
+            } else if constexpr (ENC) s = lvr_score_tile2(av[u], bq[hb], av[u], bq2[hb]);
+            else if constexpr (BL) {
+                lvr_bf16x8 b[4];
+                fetch_bq(hb, b);
+                s = lvr_score_tile(av[u], b);
+            } else s = lvr_score_tile(av[u], bq[hb]);
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            if (nvalid[u] == 0) continue;   // wave-uniform
-#pragma unroll
-            for (int hb = 0; hb < HB; ++hb) {
-                lvr_f32x4 s;
-                if constexpr (ENC && BL) {
-                    lvr_bf16x8 b[4], b2[4];
-                    fetch_bq(hb, b);
-                    fetch_bq2(hb, b2);
-                    s = lvr_score_tile2(av[u], b, av[u], b2);
-                } else if constexpr (ENC) s = lvr_score_tile2(av[u], bq[hb], av[u], bq2[hb]);
-                else if constexpr (BL) {
-                    lvr_bf16x8 b[4];
-                    fetch_bq(hb, b);
-                    s = lvr_score_tile(av[u], b);
-                } else s = lvr_score_tile(av[u], bq[hb]);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int trow = 4 * kq + j;
-                    const bool pred = trow < nvalid[u] && rep[hb] &&
-                                      (s[j] >= taue[hb] || (buffer_wg && a.buffer_dense));
-                    em[hb].push(a.emit, lane, rep[hb], pred, slot[u], trow, spos, s[j]);
-                }
+            for (int j = 0; j < 4; ++j) {
+                const int trow = 4 * kq + j;
+                const bool pred = trow < nvalid[u] && rep[hb] &&
+                                  (s[j] >= taue[hb] || (buffer_wg && a.buffer_dense));
+                em[hb].push(a.emit, lane, rep[hb], pred, slot[u], trow, spos, s[j]);
             }
+        }
+    };
+    // The rotation pays where scoring a tile takes long against the memory latency (two head blocks:
+    // 62.2 -> 60.1 us per launch at 128k keys); with one head block the launch is at the streaming
+    // ceiling either way and the repeated requests of short segments cost more than they hide.
+    if (HB == 2 && m >= 4) {   // wave-uniform
+        request(std::integral_constant<int, 0>{}, 0);
+        request(std::integral_constant<int, 1>{}, 1);
+        for (int64_t k = 0; k < m; k += 2) {
+            check(std::integral_constant<int, 0>{});
+            request(std::integral_constant<int, 0>{}, k + 2);
+            if (nvalid[1] > 0) check(std::integral_constant<int, 1>{});   // wave-uniform
+            request(std::integral_constant<int, 1>{}, k + 3);
+        }
+    } else {
+        for (int64_t k = 0; k < m; k += 2) {   // both sets requested, then both scored
+            request(std::integral_constant<int, 0>{}, k);
+            request(std::integral_constant<int, 1>{}, k + 1);   // past the end: a repeat of the last tile, not scored
+            check(std::integral_constant<int, 0>{});
+            if (nvalid[1] > 0) check(std::integral_constant<int, 1>{});
         }
     }
 #pragma unroll
