@@ -39,7 +39,9 @@ struct lvr_emitter {
         if (reporting && (lane >> 4) == 0 && count > 0)
             base = atomicAdd(&a.head_count[(hq_base + hl) * LVR_CNT_STRIDE], count);
         __builtin_amdgcn_wave_barrier();
-#pragma unroll
+        // four heads: unrolled, the four gathers overlap; eight heads unrolled would keep all eight in
+        // registers at once (182 VGPRs in the query kernel), so they go two at a time
+#pragma unroll(NH <= 4 ? NH : 2)
         for (int h = 0; h < NH; ++h) {
             const int b_h = __shfl(base, rep_base + h, 64);
             const int c_h = __shfl(count, rep_base + h, 64);

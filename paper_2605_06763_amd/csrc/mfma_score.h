@@ -79,6 +79,124 @@ __device__ __forceinline__ void lvr_build_q_frags_wg(const float *__restrict__ q
         for (int kk = 0; kk < 4; ++kk) bq[hb][kk] = __builtin_bit_cast(lvr_bf16x8, s_bq[hb][kk][lane]);
 }
 
+// ---- eight heads per KV head in ONE operand ----
+// Column n = part * 8 + head: the two leading bf16 terms of eight heads fill all 16 columns of the
+// main operand; the third term (zero for every query with at most 16 significant bits, bf16 queries
+// among them) goes into columns 8..15 of a second operand that is contracted into the same
+// accumulator only when some head needs it.  After  d + row_shr:8(d)  the lanes with n in [8, 16)
+// hold the finished score of head n - 8.
+// third = false: the main operand; third = true: the operand of the third terms.
+// Returns true if this lane put a non-zero third term into its piece.
+__device__ __forceinline__ bool lvr_build_q_frag8_one(const float *__restrict__ q_group, int G, int kk, float scale,
+                                                      bool third, lvr_bf16x8 &out) {
+    const int lane = threadIdx.x & 63;
+    const int n = lane & 15, kq = lane >> 4;
+    const int h = n & 7;
+    const int part = third ? 2 : (n >> 3);
+    const bool live = h < G && (!third || n >= 8);
+    uint32_t w[8];
+    uint32_t any = 0;
+    const float *src = q_group + (int64_t)(live ? h : 0) * LVR_D + kk * 32 + kq * 8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        w[e] = live ? lvr_split_part(src[e] * scale, part) : 0u;
+        any |= w[e] & 0x7fffu;   // a signed zero contributes nothing either
+    }
+    uint4 packed = make_uint4(w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16));
+    out = __builtin_bit_cast(lvr_bf16x8, packed);
+    return third && any != 0;
+}
+
+// Both operands of a KV group of up to eight heads, built once per 256-thread workgroup into LDS
+// (s_bq[0] = main, s_bq[1] = third terms); wave w builds the pieces of coordinates w*32 .. w*32+31.
+// Contains a barrier: every thread of the workgroup must call it.  Returns whether the second
+// operand holds anything (the same answer in every thread).
+__device__ __forceinline__ bool lvr_build_q_frags8_wg(const float *__restrict__ q_group, int G, float scale,
+                                                      uint4 (&s_bq)[2][4][64]) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    lvr_bf16x8 f;
+    lvr_build_q_frag8_one(q_group, G, wave, scale, false, f);
+    s_bq[0][wave][lane] = __builtin_bit_cast(uint4, f);
+    const bool nz = lvr_build_q_frag8_one(q_group, G, wave, scale, true, f);
+    s_bq[1][wave][lane] = __builtin_bit_cast(uint4, f);
+    return __syncthreads_or(nz ? 1 : 0) != 0;
+}
+
+// Sum over the parts' columns for the eight-head layout.
+__device__ __forceinline__ lvr_f32x4 lvr_sum_parts8(const lvr_f32x4 &acc) {
+    lvr_f32x4 s;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float v = acc[j];
+        s[j] = v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x118, 0xf, 0xf, true));   // row_shr:8
+    }
+    return s;
+}
+
+// Scores of a tile for eight heads: result valid in lanes with (lane % 16) in [8, 16).
+__device__ __forceinline__ lvr_f32x4 lvr_score_tile8(const uint4 (&a)[4], const lvr_bf16x8 (&b)[4],
+                                                     const lvr_bf16x8 (&b3)[4], bool third) {
+    lvr_f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lvr_bf16x8, a[kk]), b[kk], acc, 0, 0, 0);
+    if (third) {   // wave-uniform
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lvr_bf16x8, a[kk]), b3[kk], acc, 0, 0, 0);
+    }
+    return lvr_sum_parts8(acc);
+}
+
+// Bound of a tile of 16 balls for eight heads: centre product plus the radius step.
+__device__ __forceinline__ lvr_f32x4 lvr_bound_tile8(const uint4 (&a)[4], const lvr_bf16x8 (&b)[4],
+                                                     const lvr_bf16x8 (&b3)[4], bool third, lvr_bf16x8 ra, lvr_bf16x8 rb) {
+    lvr_f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lvr_bf16x8, a[kk]), b[kk], acc, 0, 0, 0);
+    if (third) {   // wave-uniform
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lvr_bf16x8, a[kk]), b3[kk], acc, 0, 0, 0);
+    }
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ra, rb, acc, 0, 0, 0);
+    return lvr_sum_parts8(acc);
+}
+
+// Radius step, B side, eight heads: column n = part * 8 + head with TWO terms per norm, the leading
+// eight bits and the rest rounded UP to eight bits (the sum is at least the norm; a bound may be loose,
+// never tight).  k-slots as in lvr_radius_b_frag.  qn_group: [heads][16] floats, |pi_s q_h| >= 0.
+template <int S, int NP>
+__device__ __forceinline__ lvr_bf16x8 lvr_radius_b_frag8(const float (*qn_group)[16], int G) {
+    const int lane = threadIdx.x & 63;
+    const int n = lane & 15, kq = lane >> 4;
+    const int p = n >> 3, h = n & 7;
+    const bool live = h < G;
+    uint32_t val[S];
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+        const float x = qn_group[live ? h : 0][s];
+        const uint32_t hi = __float_as_uint(x) & 0xffff0000u;
+        uint32_t rest = __float_as_uint(x - __uint_as_float(hi));
+        if (rest & 0xffffu) rest = (rest & 0xffff0000u) + 0x10000u;
+        val[s] = live ? ((p == 0 ? hi : rest) >> 16) : 0u;
+    }
+    uint32_t w[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        uint32_t v = 0;
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            const int k = 8 * q4 + j;
+            if (k < NP * S) v = (kq == q4) ? val[k % S] : v;
+        }
+        w[j] = v;
+    }
+    uint4 packed = make_uint4(w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16));
+    return __builtin_bit_cast(lvr_bf16x8, packed);
+}
+
 // The four 16-byte pieces of the A operand for row `row` (lane's row = lane % 16):
 // coordinates kk*32 + 8*(lane/16) .. +7 for kk = 0..3.
 __device__ __forceinline__ void lvr_load_a_frags(const char *__restrict__ base, int64_t row, uint4 (&a)[4]) {

@@ -45,12 +45,16 @@ struct FusedArgs {
 
 // UA = centre tiles per phase-A trip; ENC = 1: boxes instead of balls; Q1 = 1: per-block thresholds (S <= 4);
 // CF8 = 1: centres (balls, S <= 4) or box corners stored as e4m3 codes
-template <int HB, int S, int UA, int ENC, int Q1 = 0, int CF8 = 0>
+// W = heads per head block: 4 (three exact bf16 terms of four heads in the 16 operand columns; HB blocks) or
+//     8 (two terms of eight heads fill the columns, the rarely non-zero third term has an operand of its own:
+//     one pass per tile for up to eight heads; balls with one threshold per head, HB = 1)
+template <int HB, int S, int UA, int ENC, int Q1 = 0, int CF8 = 0, int W = 4>
 __global__ void __launch_bounds__(256)
 query_fused_kernel(const FusedArgs a) {
     static_assert(!Q1 || !ENC, "Query 1 is built for balls");
     static_assert(!Q1 || S <= 4 || !CF8, "8-bit centres: at most four coordinate blocks");
     static_assert(!CF8 || S <= 4, "8-bit centres: at most four coordinate blocks");
+    static_assert(W == 4 || (W == 8 && HB == 1 && !ENC && !Q1), "the eight-head operand serves balls with one threshold per head");
     // RP: the radii of 8-bit balls come pre-split for the matrix cores; boxes keep one fp32 allowance per group
     constexpr bool RP = CF8 && !ENC;
     // the staging area of the query operand is dead once every wave holds its fragments; the score
@@ -60,15 +64,16 @@ query_fused_kernel(const FusedArgs a) {
         float qscore[4][HB][4][LVR_QCAP];
     } s_u;
     static_assert(sizeof(s_u.bq) == sizeof(s_u.qscore), "aliasing assumes equal sizes");
+    __shared__ uint4 s_bq8[W == 8 ? 2 : 1][4][64];   // W = 8: main operand and the operand of the third terms
     // BL: with eight heads per KV head the query operand (two head blocks, 32 registers) stays in LDS
     // and a lane fetches its pieces right before the matrix instructions that use them; that brings
     // the kernel back under the register budget of four waves per SIMD.  The staging area then keeps
     // its content, so the score queues get bytes of their own.
-    constexpr bool BL = HB == 2 && !Q1;
-    __shared__ float s_qs2[BL ? 4 : 1][BL ? HB : 1][4][BL ? LVR_QCAP : 1];
+    constexpr bool BL = (HB == 2 && !Q1) || W == 8;
+    __shared__ float s_qs2[BL ? 4 : 1][BL ? HB : 1][W][BL ? LVR_QCAP : 1];
     __shared__ uint4 s_bq2[ENC ? HB : 1][4][64];
-    __shared__ float s_qn[HB * 4][16];
-    __shared__ int32_t s_queue[4][HB][4][LVR_QCAP];
+    __shared__ float s_qn[HB * W][16];
+    __shared__ int32_t s_queue[4][HB][W][LVR_QCAP];
     __shared__ int32_t s_list[SEG_MAX_GROUPS];
     __shared__ int s_tot[4];
     const int bh = blockIdx.y;
@@ -163,12 +168,12 @@ query_fused_kernel(const FusedArgs a) {
     float tau_raw[HB];
 #pragma unroll
     for (int hb = 0; hb < HB; ++hb) {
-        const int h = hb * 4 + n - 8;
-        tau_raw[hb] = (n >= 8 && n < 12 && h < a.G) ? a.tau[hq0 + h] : INFINITY;
+        const int h = hb * W + n - 8;
+        tau_raw[hb] = (n >= 8 && n < 8 + W && h < a.G) ? a.tau[hq0 + h] : INFINITY;
     }
 
     // ---- prologue: subspace norms of q (phase A only) and the B operand of q ----
-    if (!buffer_wg && (int)threadIdx.x < HB * 64) {
+    if (!buffer_wg && (int)threadIdx.x < HB * W * 16) {
         const int h = threadIdx.x >> 4, li = threadIdx.x & 15;
         float ss = 0.f;
         if (h < a.G) {
@@ -184,7 +189,9 @@ query_fused_kernel(const FusedArgs a) {
     // B operands: q itself for balls; for boxes its positive part (meets the upper corners) and its
     // negative part (meets the lower corners); q = q+ + q- serves the exact check of phase B
     lvr_bf16x8 bq[HB][4], bq2[ENC ? HB : 1][4];
-    lvr_build_q_frags_wg<HB>(a.q + hq0 * LVR_D, a.G, 1.0f, s_u.bq, bq, ENC ? 1 : 0);   // syncs
+    bool third = false;   // W = 8: some head's query has more than 16 significant bits (the same in every thread)
+    if constexpr (W == 8) third = lvr_build_q_frags8_wg(a.q + hq0 * LVR_D, a.G, 1.0f, s_bq8);   // syncs
+    else lvr_build_q_frags_wg<HB>(a.q + hq0 * LVR_D, a.G, 1.0f, s_u.bq, bq, ENC ? 1 : 0);   // syncs
     if constexpr (ENC) lvr_build_q_frags_wg<HB>(a.q + hq0 * LVR_D, a.G, 1.0f, s_bq2, bq2, -1);
     // BL: the pieces of head block hb, fetched anew at every use (the index register comes out of an
     // opaque instruction so that the loads are not hoisted out of the loops and kept in registers)
@@ -200,21 +207,32 @@ query_fused_kernel(const FusedArgs a) {
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) b[kk] = __builtin_bit_cast(lvr_bf16x8, s_bq2[ENC ? hb : 0][kk][lane + z]);
     };
+    auto fetch_bq8 = [&](int which, lvr_bf16x8 (&b)[4]) {   // W = 8: 0 the main operand, 1 the third terms
+        int z;
+        asm volatile("v_mov_b32 %0, 0" : "=v"(z));
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) b[kk] = __builtin_bit_cast(lvr_bf16x8, s_bq8[W == 8 ? which : 0][kk][lane + z]);
+    };
     (void)fetch_bq;
     (void)fetch_bq2;
+    (void)fetch_bq8;
+    (void)third;
     lvr_bf16x8 rbq[RM ? HB : 1];
     if constexpr (RM) {
         if (!buffer_wg) {
 #pragma unroll
-            for (int hb = 0; hb < HB; ++hb) rbq[hb] = lvr_radius_b_frag<S, RP ? 2 : 3>(s_qn, a.G, hb);
+            for (int hb = 0; hb < HB; ++hb) {
+                if constexpr (W == 8) rbq[hb] = lvr_radius_b_frag8<S, RP ? 2 : 3>(s_qn, a.G);
+                else rbq[hb] = lvr_radius_b_frag<S, RP ? 2 : 3>(s_qn, a.G, hb);
+            }
         }
     }
     float taue[HB];
     bool rep[HB];
 #pragma unroll
     for (int hb = 0; hb < HB; ++hb) {
-        const int h = hb * 4 + n - 8;
-        rep[hb] = n >= 8 && n < 12 && h < a.G;
+        const int h = hb * W + n - 8;
+        rep[hb] = n >= 8 && n < 8 + W && h < a.G;
         taue[hb] = rep[hb] ? lvr_effective_tau(tau_raw[hb]) : INFINITY;
     }
     float taus[HB][Q1 ? S : 1];
@@ -234,7 +252,7 @@ query_fused_kernel(const FusedArgs a) {
 #pragma unroll
         for (int hb = 0; hb < HB; ++hb)
 #pragma unroll
-            for (int s = 0; s < S; ++s) qn[hb][s] = rep[hb] ? s_qn[hb * 4 + n - 8][s] : 0.f;
+            for (int s = 0; s < S; ++s) qn[hb][s] = rep[hb] ? s_qn[hb * W + n - 8][s] : 0.f;
         uint32_t mybits = 0;   // lane `it` keeps the 16-bit survivor mask of the wave's tile `it`
         auto scoreA = [&](Trip &T, int it) {
             auto &av = T.av; auto &av2 = T.av2; auto &rad = T.rad; auto &rrow = T.rrow; auto &rblk = T.rblk;
@@ -338,7 +356,12 @@ query_fused_kernel(const FusedArgs a) {
                             fetch_bq2(hb, b2);
                             sc = lvr_bound_tile2(ac, b, ac2, b2, ra, rbq[hb]);
                         } else if constexpr (ENC) sc = lvr_bound_tile2(ac, bq[hb], ac2, bq2[hb], ra, rbq[hb]);
-                        else if constexpr (BL) {
+                        else if constexpr (W == 8) {
+                            lvr_bf16x8 b[4], b3[4];
+                            fetch_bq8(0, b);
+                            if (third) fetch_bq8(1, b3);
+                            sc = lvr_bound_tile8(ac, b, b3, third, ra, rbq[hb]);
+                        } else if constexpr (BL) {
                             lvr_bf16x8 b[4];
                             fetch_bq(hb, b);
                             sc = lvr_bound_tile(ac, b, ra, rbq[hb]);
@@ -350,7 +373,12 @@ query_fused_kernel(const FusedArgs a) {
                             fetch_bq2(hb, b2);
                             sc = lvr_score_tile2(ac, b, ac2, b2);
                         } else if constexpr (ENC) sc = lvr_score_tile2(ac, bq[hb], ac2, bq2[hb]);
-                        else if constexpr (BL) {
+                        else if constexpr (W == 8) {
+                            lvr_bf16x8 b[4], b3[4];
+                            fetch_bq8(0, b);
+                            if (third) fetch_bq8(1, b3);
+                            sc = lvr_score_tile8(ac, b, b3, third);
+                        } else if constexpr (BL) {
                             lvr_bf16x8 b[4];
                             fetch_bq(hb, b);
                             sc = lvr_score_tile(ac, b);
@@ -384,10 +412,12 @@ query_fused_kernel(const FusedArgs a) {
                 uint32_t v = alive4;
                 v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, true);   // row_shr:1
                 v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, true);   // row_shr:2
-                const uint32_t mask16 = (uint32_t)__builtin_amdgcn_readlane((int)v, 11) |
-                                        ((uint32_t)__builtin_amdgcn_readlane((int)v, 27) << 4) |
-                                        ((uint32_t)__builtin_amdgcn_readlane((int)v, 43) << 8) |
-                                        ((uint32_t)__builtin_amdgcn_readlane((int)v, 59) << 12);
+                if constexpr (W == 8) v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, true);   // row_shr:4
+                constexpr int L0 = 7 + W;   // last lane of a row that holds a head's bits: 11 (four heads) or 15 (eight)
+                const uint32_t mask16 = (uint32_t)__builtin_amdgcn_readlane((int)v, L0) |
+                                        ((uint32_t)__builtin_amdgcn_readlane((int)v, L0 + 16) << 4) |
+                                        ((uint32_t)__builtin_amdgcn_readlane((int)v, L0 + 32) << 8) |
+                                        ((uint32_t)__builtin_amdgcn_readlane((int)v, L0 + 48) << 12);
                 // groups past the end of the index, tiles past the wave's share: a wave-uniform mask
                 const int64_t left = a.n_groups - g_row;
                 const uint32_t valid16 = (it + u) >= a.tiles_per_wave || left <= 0 ? 0u
@@ -462,7 +492,7 @@ query_fused_kernel(const FusedArgs a) {
     }
 
     // ---------------- phase B: exact check of the surviving rows ----------------
-    lvr_emitter<4, true> em[HB];
+    lvr_emitter<W, true> em[HB];
 #pragma unroll
     for (int hb = 0; hb < HB; ++hb) {
         em[hb].q = s_queue[wave][hb];
@@ -470,7 +500,7 @@ query_fused_kernel(const FusedArgs a) {
         else em[hb].qs = s_u.qscore[wave][hb];
         em[hb].count = 0;
         em[hb].rep_base = 8;
-        em[hb].hq_base = hq0 + hb * 4;
+        em[hb].hq_base = hq0 + hb * W;
     }
     const char *Kb = static_cast<const char *>(a.K) + (int64_t)bh * a.cap_rows * LVR_D * 2;
     const int32_t *spos = a.slot_pos ? a.slot_pos + (int64_t)bh * a.cap_rows : nullptr;
@@ -505,7 +535,12 @@ query_fused_kernel(const FusedArgs a) {
                 fetch_bq2(hb, b2);
                 s = lvr_score_tile2(av[u], b, av[u], b2);
             } else if constexpr (ENC) s = lvr_score_tile2(av[u], bq[hb], av[u], bq2[hb]);
-            else if constexpr (BL) {
+            else if constexpr (W == 8) {
+                lvr_bf16x8 b[4], b3[4];
+                fetch_bq8(0, b);
+                if (third) fetch_bq8(1, b3);
+                s = lvr_score_tile8(av[u], b, b3, third);
+            } else if constexpr (BL) {
                 lvr_bf16x8 b[4];
                 fetch_bq(hb, b);
                 s = lvr_score_tile(av[u], b);
@@ -522,7 +557,7 @@ query_fused_kernel(const FusedArgs a) {
     // The rotation pays where scoring a tile takes long against the memory latency (two head blocks:
     // 62.2 -> 60.1 us per launch at 128k keys); with one head block the launch is at the streaming
     // ceiling either way and the repeated requests of short segments cost more than they hide.
-    if (HB == 2 && m >= 4) {   // wave-uniform
+    if ((HB == 2 || W == 8) && m >= 4) {   // wave-uniform
         request(std::integral_constant<int, 0>{}, 0);
         request(std::integral_constant<int, 1>{}, 1);
         for (int64_t k = 0; k < m; k += 2) {
@@ -544,14 +579,14 @@ query_fused_kernel(const FusedArgs a) {
         if (__ballot(em[hb].count > 0)) em[hb].flush(a.emit, lane, rep[hb], spos);
 }
 
-template <int HB, int UA>
+template <int UA, int W>
 void launch_s(dim3 grid, hipStream_t st, const FusedArgs &a, int S) {
     switch (S) {
-        case 1: hipLaunchKernelGGL((query_fused_kernel<HB, 1, UA, 0>), grid, dim3(256), 0, st, a); break;
-        case 2: hipLaunchKernelGGL((query_fused_kernel<HB, 2, UA, 0>), grid, dim3(256), 0, st, a); break;
-        case 4: hipLaunchKernelGGL((query_fused_kernel<HB, 4, UA, 0>), grid, dim3(256), 0, st, a); break;
-        case 8: hipLaunchKernelGGL((query_fused_kernel<HB, 8, UA, 0>), grid, dim3(256), 0, st, a); break;
-        default: hipLaunchKernelGGL((query_fused_kernel<HB, 16, UA, 0>), grid, dim3(256), 0, st, a); break;
+        case 1: hipLaunchKernelGGL((query_fused_kernel<1, 1, UA, 0, 0, 0, W>), grid, dim3(256), 0, st, a); break;
+        case 2: hipLaunchKernelGGL((query_fused_kernel<1, 2, UA, 0, 0, 0, W>), grid, dim3(256), 0, st, a); break;
+        case 4: hipLaunchKernelGGL((query_fused_kernel<1, 4, UA, 0, 0, 0, W>), grid, dim3(256), 0, st, a); break;
+        case 8: hipLaunchKernelGGL((query_fused_kernel<1, 8, UA, 0, 0, 0, W>), grid, dim3(256), 0, st, a); break;
+        default: hipLaunchKernelGGL((query_fused_kernel<1, 16, UA, 0, 0, 0, W>), grid, dim3(256), 0, st, a); break;
     }
 }
 
@@ -643,18 +678,18 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
     }
     if (ix->cf8) {   // 8-bit centres
         const int S = ix->cfg.n_subspaces;
-#define LVR_F8_LAUNCH(HB, UA)                                                                                 \
+#define LVR_F8_LAUNCH(UA, W)                                                                                  \
     do {                                                                                                      \
-        if (S == 1) hipLaunchKernelGGL((query_fused_kernel<HB, 1, UA, 0, 0, 1>), grid, dim3(256), 0, st, a);  \
-        else if (S == 2) hipLaunchKernelGGL((query_fused_kernel<HB, 2, UA, 0, 0, 1>), grid, dim3(256), 0, st, a); \
-        else hipLaunchKernelGGL((query_fused_kernel<HB, 4, UA, 0, 0, 1>), grid, dim3(256), 0, st, a);         \
+        if (S == 1) hipLaunchKernelGGL((query_fused_kernel<1, 1, UA, 0, 0, 1, W>), grid, dim3(256), 0, st, a);  \
+        else if (S == 2) hipLaunchKernelGGL((query_fused_kernel<1, 2, UA, 0, 0, 1, W>), grid, dim3(256), 0, st, a); \
+        else hipLaunchKernelGGL((query_fused_kernel<1, 4, UA, 0, 0, 1, W>), grid, dim3(256), 0, st, a);         \
     } while (0)
         if (ix->G <= 4) {
-            if (one) LVR_F8_LAUNCH(1, 1);
-            else LVR_F8_LAUNCH(1, 2);
-        } else {
-            if (one) LVR_F8_LAUNCH(2, 1);
-            else LVR_F8_LAUNCH(2, 2);
+            if (one) LVR_F8_LAUNCH(1, 4);
+            else LVR_F8_LAUNCH(2, 4);
+        } else {   // up to eight heads in one operand
+            if (one) LVR_F8_LAUNCH(1, 8);
+            else LVR_F8_LAUNCH(2, 8);
         }
 #undef LVR_F8_LAUNCH
         return hipGetLastError();
@@ -665,11 +700,11 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
         return hipGetLastError();
     }
     if (ix->G <= 4) {
-        if (one) launch_s<1, 1>(grid, st, a, ix->cfg.n_subspaces);
-        else launch_s<1, 2>(grid, st, a, ix->cfg.n_subspaces);
-    } else {
-        if (one) launch_s<2, 1>(grid, st, a, ix->cfg.n_subspaces);
-        else launch_s<2, 2>(grid, st, a, ix->cfg.n_subspaces);
+        if (one) launch_s<1, 4>(grid, st, a, ix->cfg.n_subspaces);
+        else launch_s<2, 4>(grid, st, a, ix->cfg.n_subspaces);
+    } else {   // up to eight heads in one operand
+        if (one) launch_s<1, 8>(grid, st, a, ix->cfg.n_subspaces);
+        else launch_s<2, 8>(grid, st, a, ix->cfg.n_subspaces);
     }
     return hipGetLastError();
 }

@@ -1395,3 +1395,28 @@ def test_random_call_sequences(G, oracle, case):
             assert n_indexed % r == 0 and 0 <= n - n_indexed < 2 * B + r, (tag, n, n_indexed)
             if R:
                 _check_reservoir(oracle, ix, case, R)
+
+
+@pytest.mark.parametrize("hq,hkv", [(8, 1), (16, 2), (4, 1), (4, 2), (1, 1)])
+@pytest.mark.parametrize("kind", ["full", "mixed", "sixteen_bits"])
+def test_queries_with_full_fp32_precision(G, oracle, hq, hkv, kind):
+    """The scoring operand carries an fp32 query exactly (three bf16 terms; with more than four heads per
+    KV head the third term travels in an operand of its own that is skipped when every term is zero).
+    Queries with 24 significant bits, with 16, and a mix of exact-bf16 and full-precision heads must all
+    give the oracle's sets and attention, in both enclosure formats."""
+    L = G.L
+    n = 3000 + 5
+    cache = W.make_cache(2, n=n, n_kv_heads=hkv)
+    g = np.random.default_rng(99 + hq)
+    q = g.standard_normal((1, hq, 128)).astype(np.float32)                 # 24 significant bits
+    if kind == "sixteen_bits":
+        q = (q.view(np.uint32) & np.uint32(0xffffff00)).view(np.float32)   # hi + mid terms only
+    elif kind == "mixed":
+        q[:, ::2] = W.round_to_bf16(q[:, ::2])                             # every other head is bf16-exact
+    for idt in (L.LVR_INDEX_AUTO, L.LVR_INDEX_SAME):
+        for S in (4, 16):
+            with G.Index(cache.K, cache.V, "bf16", hq, n_subspaces=S, index_dtype=idt, buffer_size=64) as ix:
+                for frac in (0.01, 0.3):
+                    tau = G.oracle_taus(oracle, ix, q, frac=frac)
+                    idx, cnt, out = ix.query(q, tau, fused=True)
+                    G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=f"fp32 q {kind} hq={hq} S={S} centres={idt} frac={frac}")
