@@ -65,6 +65,9 @@ def main():
     ap.add_argument("--centres", choices=["auto", "bf16", "fp8"], default="auto",
                     help="storage of the centres: the cache's bf16, or 8-bit e4m3 codes (half the index read); "
                          "auto = the library's default (8-bit where supported)")
+    ap.add_argument("--q-heads", type=int, default=0,
+                    help="supplementary: query heads per sequence (8, 16, 32 or 64 over the workload's 8 KV heads; "
+                         "default: the workload's 32)")
     ap.add_argument("--keys", choices=["workload", "local"], default="workload",
                     help="'local': supplementary cache whose keys have positional locality (the pruned regime); "
                          "not one of the five workloads")
@@ -97,6 +100,9 @@ def main():
     cid = args.config
     c = W.CONFIGS[cid]
     B, Hq, Hkv, d, n0 = c["batch"], c["n_q_heads"], c["n_kv_heads"], c["head_dim"], c["n"]
+    if args.q_heads:
+        assert args.q_heads in (8, 16, 32, 64) and cid != 5, "--q-heads: 8, 16, 32 or 64, not with the append workload"
+        Hq = args.q_heads
     G = Hq // Hkv
     K_steps, W_steps = args.steps, args.warmup
     total_steps = K_steps + W_steps
@@ -115,13 +121,13 @@ def main():
     # distinct queries cycled through the timed steps
     if cid == 3:
         n_distinct = 256
-        q_np = W.drift_queries(3, n_distinct)                      # [T][B][Hq][d]
+        q_np = W.drift_queries(3, n_distinct, n_q_heads=Hq)        # [T][B][Hq][d]
     elif appending:
         n_distinct = total_steps
         q_np = W.drift_queries(5, n_distinct)
     else:
         n_distinct = 16
-        q_np = np.stack([W.make_queries(cid, step=t) for t in range(n_distinct)])
+        q_np = np.stack([W.make_queries(cid, step=t, n_q_heads=Hq) for t in range(n_distinct)])
     q_all = torch.from_numpy(q_np).to(dev)
 
     capacity = n0 + (total_steps + K_steps + 64 if appending else 0)
@@ -321,7 +327,8 @@ def main():
     # HBM bytes per launch measured offline with rocprofv3 --pmc (profiles/), when this workload was profiled
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
     if (os.path.exists(tpath) and args.group_size == 4 and args.subspaces == 4 and args.keys == "workload"
-            and args.enclosing == "ball" and args.centres == "auto" and not args.offload and not args.separate and args.grouping == "contiguous"):
+            and args.enclosing == "ball" and args.centres == "auto" and not args.offload and not args.separate and args.grouping == "contiguous"
+            and not args.q_heads):
         for line in open(tpath):
             f = line.split()
             if len(f) == 3 and f[0] == f"config{cid}" and f[1] == "query_fused_kernel":
@@ -342,7 +349,7 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"config{cid}:{c['name']}" + (" [supplementary: keys with positional locality]" if args.keys == "local" else ""), "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
+        "config": {"workload": f"config{cid}:{c['name']}" + (" [supplementary: keys with positional locality]" if args.keys == "local" else "") + (f" [supplementary: {Hq} query heads]" if args.q_heads else ""), "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
                    "head_dim": d, "context": int(n_now), "kv_storage": "bf16", "group_size": args.group_size,
                    "subspaces": args.subspaces, "attn_splits": args.attn_splits, "grouping": args.grouping,
                    "centres": ("fp8" if index_bytes_per_group < (512 if args.enclosing == "aabb" else 256) else "bf16"), "enclosing": args.enclosing,
