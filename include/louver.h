@@ -191,8 +191,9 @@ int lvr_query(lvr_index *ix, const float *q_dev, const float *tau_dev, int32_t *
  *   tau_dev   [batch][n_q_heads]: the exact check on candidates, as in lvr_query
  * Every key with <q,k> >= tau whose subspace products all reach their tau_s is returned; keys
  * with <q,k> >= tau that miss some tau_s may or may not be (they are outside Query 1's promise).
- * Buffer keys are checked against tau only.  Balls on bf16 caches, fused launch form; other
- * configurations return LVR_E_UNSUPPORTED. */
+ * Buffer keys are checked against tau only.  bf16 caches, fused launch form: balls with any
+ * n_subspaces; boxes with n_subspaces <= 4 blocks (per block the box bound of that block's
+ * coordinates plus the group's allowance); other configurations return LVR_E_UNSUPPORTED. */
 int lvr_query1(lvr_index *ix, const float *q_dev, const float *tau_s_dev, const float *tau_dev, int32_t *out_idx_dev,
                int32_t *out_count_dev, int64_t cap, void *stream);
 

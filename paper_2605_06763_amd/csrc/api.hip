@@ -544,7 +544,8 @@ int lvr_query1(lvr_index *ix, const float *q, const float *tau_s, const float *t
     if (!ix->built) return LVR_E_STATE;
     if (!on_home_device(ix)) return LVR_E_STATE;
     if (!aligned4(q) || !aligned4(tau) || !aligned4(tau_s) || !aligned4(out_idx) || !aligned4(out_count)) return LVR_E_INVALID;
-    if (ix->cfg.kv_dtype != LVR_BF16 || (ix->cfg.flags & LVR_SEPARATE_KERNELS) || ix->box) return LVR_E_UNSUPPORTED;
+    if (ix->cfg.kv_dtype != LVR_BF16 || (ix->cfg.flags & LVR_SEPARATE_KERNELS) || (ix->box && ix->cfg.n_subspaces > 4))
+        return LVR_E_UNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(stream);
     int rc = enqueue_query(ix, q, tau, out_idx, cap, st, tau_s);
     if (rc != LVR_OK) return rc;
@@ -560,7 +561,8 @@ int lvr_subspace_thresholds(lvr_index *ix, const float *q, const float *tau, flo
     if (!ix || !q || !tau || !tau_s_out) return LVR_E_INVALID;
     if (!ix->built || !on_home_device(ix)) return LVR_E_STATE;
     if (!aligned4(q) || !aligned4(tau) || !aligned4(tau_s_out)) return LVR_E_INVALID;
-    if (ix->cfg.kv_dtype != LVR_BF16 || (ix->cfg.flags & LVR_SEPARATE_KERNELS) || ix->box) return LVR_E_UNSUPPORTED;
+    if (ix->cfg.kv_dtype != LVR_BF16 || (ix->cfg.flags & LVR_SEPARATE_KERNELS) || (ix->box && ix->cfg.n_subspaces > 4))
+        return LVR_E_UNSUPPORTED;
     LVR_HIP(lvr_launch_safe_tau_s(ix, q, tau, tau_s_out, static_cast<hipStream_t>(stream)));
     return LVR_OK;
 }

@@ -41,7 +41,8 @@ struct lvr_emitter {
         __builtin_amdgcn_wave_barrier();
         // four heads: unrolled, the four gathers overlap; eight heads unrolled would keep all eight in
         // registers at once (182 VGPRs in the query kernel), so they go two at a time
-#pragma unroll(NH <= 4 ? NH : 2)
+        constexpr int kUnroll = NH <= 4 ? NH : 2;
+#pragma unroll kUnroll
         for (int h = 0; h < NH; ++h) {
             const int b_h = __shfl(base, rep_base + h, 64);
             const int c_h = __shfl(count, rep_base + h, 64);

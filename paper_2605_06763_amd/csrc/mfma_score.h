@@ -267,6 +267,28 @@ __device__ __forceinline__ lvr_f32x4 lvr_score_tile_block(const uint4 (&a)[4], c
     return s;
 }
 
+// The same for boxes: upper corners against the positive part of q, lower corners against the
+// negative part, both restricted to the block, in one accumulator.
+template <int KK0, int KK1>
+__device__ __forceinline__ lvr_f32x4 lvr_score_tile_block2(const uint4 (&a1)[4], const lvr_bf16x8 (&b1)[4],
+                                                           const uint4 (&a2)[4], const lvr_bf16x8 (&b2)[4]) {
+    lvr_f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = KK0; kk < KK1; ++kk) {
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lvr_bf16x8, a1[kk]), b1[kk], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lvr_bf16x8, a2[kk]), b2[kk], acc, 0, 0, 0);
+    }
+    lvr_f32x4 s;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float v = acc[j];
+        float t = v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x114, 0xf, 0xf, true));
+        t += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x118, 0xf, 0xf, true));
+        s[j] = t;
+    }
+    return s;
+}
+
 // Partial score over a coordinate block that is a FRACTION of one MFMA step: coordinates
 // KK*32 + KQ0*8 .. KK*32 + KQ1*8 - 1.  A lane's B fragment holds the eight query coordinates
 // KK*32 + kq*8 .. +7 of its column, so zeroing the fragment on the lanes whose kq lies outside

@@ -22,7 +22,9 @@ __device__ __forceinline__ float seg_sum16(float v, int lanes_per_sub) {
 // grid (NB, batch * n_kv_heads), 256 threads: 16 quarter waves, one group per quarter per trip.
 // Lane li of a quarter holds coordinates 8 li .. 8 li + 7, all inside subspace li / (16 / S).
 // part: [batch * n_kv_heads][NB][G][S] maxima of this workgroup's groups.
-template <int G, bool CF8>
+// BOX: two rows per group (upper corner, lower corner); the block's bound is sum_c max(q_c lo_c, q_c hi_c)
+// over the block's coordinates plus the group's allowance times the norm of the whole query.
+template <int G, bool CF8, bool BOX = false>
 __global__ void __launch_bounds__(256)
 subspace_max_kernel(const void *__restrict__ centres, const float *__restrict__ radii, const float *__restrict__ q,
                     float *__restrict__ part, int64_t max_groups, int64_t n_groups, int S, int n_kv_heads, int n_q_heads) {
@@ -41,36 +43,51 @@ subspace_max_kernel(const void *__restrict__ centres, const float *__restrict__ 
             n2 += qv[h][e] * qv[h][e];
         }
         // rounded up a little: the norm multiplies a non-negative radius in an upper bound
-        qn[h] = sqrtf(seg_sum16(n2, lanes_per_sub)) * (1.0f + 0x1p-20f);
+        qn[h] = sqrtf(seg_sum16(n2, BOX ? 16 : lanes_per_sub)) * (1.0f + 0x1p-20f);
         m[h] = -INFINITY;
     }
-    const char *Cb = static_cast<const char *>(centres) + (int64_t)bh * max_groups * LVR_D * (CF8 ? 1 : 2);
+    const char *Cb = static_cast<const char *>(centres) + (int64_t)bh * max_groups * LVR_D * (CF8 ? 1 : 2) * (BOX ? 2 : 1);
+    auto load_row = [&](int64_t row, float (&x)[8]) {
+        if constexpr (CF8) {
+            // 128 e4m3 codes per row in matrix-operand order: coordinates 8 li .. 8 li + 7 are the
+            // eight bytes at (li & 3) * 32 + (li >> 2) * 8
+            const uint2 w = *reinterpret_cast<const uint2 *>(Cb + row * LVR_D + (li & 3) * 32 + (li >> 2) * 8);
+            const f32x2 d0 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w.x, false), d1 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w.x, true);
+            const f32x2 d2 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w.y, false), d3 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w.y, true);
+            x[0] = d0[0]; x[1] = d0[1]; x[2] = d1[0]; x[3] = d1[1];
+            x[4] = d2[0]; x[5] = d2[1]; x[6] = d3[0]; x[7] = d3[1];
+        } else {
+            lvr_load8<lvr_bf16_t>(Cb, row, li, x);
+        }
+    };
     const int64_t trips = (n_groups + 16 * (int64_t)gridDim.x - 1) / (16 * (int64_t)gridDim.x);
     for (int64_t it = 0; it < trips; ++it) {        // the same trip count for every lane: the shuffles stay convergent
         int64_t g = (it * gridDim.x + blockIdx.x) * 16 + quarter;
         const bool valid = g < n_groups;
         if (!valid) g = 0;
-        float x[8], rho;
-        if constexpr (CF8) {
-            // 128 e4m3 codes per group in matrix-operand order: coordinates 8 li .. 8 li + 7 are the
-            // eight bytes at (li & 3) * 32 + (li >> 2) * 8
-            const uint2 w = *reinterpret_cast<const uint2 *>(Cb + g * LVR_D + (li & 3) * 32 + (li >> 2) * 8);
-            const f32x2 d0 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w.x, false), d1 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w.x, true);
-            const f32x2 d2 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w.y, false), d3 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w.y, true);
-            x[0] = d0[0]; x[1] = d0[1]; x[2] = d1[0]; x[3] = d1[1];
-            x[4] = d2[0]; x[5] = d2[1]; x[6] = d3[0]; x[7] = d3[1];
+        float x[8], x2[8], rho;
+        (void)x2;
+        if constexpr (BOX) {
+            load_row(2 * g, x);        // upper corner
+            load_row(2 * g + 1, x2);   // lower corner
+            rho = radii[(int64_t)bh * max_groups + g];
+        } else if constexpr (CF8) {
+            load_row(g, x);
             // radii as eight bf16 per group: slot s = top bits of rho_s, slot S + s = the rest rounded up
             const uint16_t *rb = reinterpret_cast<const uint16_t *>(radii) + ((int64_t)bh * max_groups + g) * 8;
             rho = __uint_as_float((uint32_t)rb[s_l] << 16) + __uint_as_float((uint32_t)rb[S + s_l] << 16);
         } else {
-            lvr_load8<lvr_bf16_t>(Cb, g, li, x);
+            load_row(g, x);
             rho = radii[((int64_t)bh * max_groups + g) * S + s_l];
         }
 #pragma unroll
         for (int h = 0; h < G; ++h) {
             float p = 0.f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) p += qv[h][e] * x[e];
+            for (int e = 0; e < 8; ++e) {
+                if constexpr (BOX) p += fmaxf(qv[h][e] * x[e], qv[h][e] * x2[e]);
+                else p += qv[h][e] * x[e];
+            }
             const float f = seg_sum16(p, lanes_per_sub) + rho * qn[h];
             if (valid) m[h] = fmaxf(m[h], f);
         }
@@ -115,7 +132,13 @@ __global__ void safe_tau_s_kernel(const float *__restrict__ part, const float *_
 template <int G>
 void launch_max(lvr_index *ix, const float *q, float *part, int NB, int64_t n_groups, hipStream_t st) {
     dim3 grid((unsigned)NB, (unsigned)lvr_n_bh(ix));
-    if (ix->cf8)
+    if (ix->box && ix->cf8)
+        hipLaunchKernelGGL((subspace_max_kernel<G, true, true>), grid, dim3(256), 0, st, ix->centres, ix->radii, q, part,
+                           ix->max_groups, n_groups, ix->cfg.n_subspaces, ix->cfg.n_kv_heads, ix->cfg.n_q_heads);
+    else if (ix->box)
+        hipLaunchKernelGGL((subspace_max_kernel<G, false, true>), grid, dim3(256), 0, st, ix->centres, ix->radii, q, part,
+                           ix->max_groups, n_groups, ix->cfg.n_subspaces, ix->cfg.n_kv_heads, ix->cfg.n_q_heads);
+    else if (ix->cf8)
         hipLaunchKernelGGL((subspace_max_kernel<G, true>), grid, dim3(256), 0, st, ix->centres, ix->radii, q, part,
                            ix->max_groups, n_groups, ix->cfg.n_subspaces, ix->cfg.n_kv_heads, ix->cfg.n_q_heads);
     else
@@ -125,7 +148,7 @@ void launch_max(lvr_index *ix, const float *q, float *part, int NB, int64_t n_gr
 
 }  // namespace
 
-// Callers guarantee: bf16 cache, ball enclosure (8-bit centres only with S <= 4).  The per-workgroup maxima go through the
+// Callers guarantee: bf16 cache; 8-bit index rows and boxes only with S <= 4.  The per-workgroup maxima go through the
 // attention's partial-output buffer (at least 512 floats per query head), which no launch in flight
 // on the same stream still needs once this one runs.
 hipError_t lvr_launch_safe_tau_s(lvr_index *ix, const float *q, const float *tau, float *tau_s, hipStream_t st) {

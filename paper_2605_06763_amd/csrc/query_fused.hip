@@ -51,7 +51,7 @@ struct FusedArgs {
 template <int HB, int S, int UA, int ENC, int Q1 = 0, int CF8 = 0, int W = 4>
 __global__ void __launch_bounds__(256)
 query_fused_kernel(const FusedArgs a) {
-    static_assert(!Q1 || !ENC, "Query 1 is built for balls");
+    static_assert(!(Q1 && ENC) || S <= 4, "Query 1 on boxes: blocks of whole MFMA steps");
     static_assert(!Q1 || S <= 4 || !CF8, "8-bit centres: at most four coordinate blocks");
     static_assert(!CF8 || S <= 4, "8-bit centres: at most four coordinate blocks");
     static_assert(W == 4 || (W == 8 && HB == 1 && !ENC && !Q1), "the eight-head operand serves balls with one threshold per head");
@@ -88,7 +88,7 @@ query_fused_kernel(const FusedArgs a) {
     constexpr int SP = (S <= 4) ? S : 1;      // radii are fetched ahead only when they are few
     // balls: one row per group (the centre); boxes: two rows per group (upper corner, lower corner)
     const char *Cb = static_cast<const char *>(a.centres) + (int64_t)bh * a.max_groups * LVR_D * (CF8 ? 1 : 2) * (ENC ? 2 : 1);
-    const float *Rb = a.radii + (int64_t)bh * a.max_groups * (RP ? 4 : S);   // 8-bit centres: 16 bytes of pre-split radii per group
+    const float *Rb = a.radii + (int64_t)bh * a.max_groups * (RP ? 4 : (ENC ? 1 : S));   // boxes: one allowance per group, whatever S   // 8-bit centres: 16 bytes of pre-split radii per group
     const int64_t n_tiles = (a.n_groups + 15) >> 4;
     const int64_t tile0 = ((int64_t)blockIdx.x * 4 + wave) * a.tiles_per_wave;
     // RM: the radius term rides on the matrix cores as a fifth step (S <= 4, one threshold per head);
@@ -141,8 +141,10 @@ query_fused_kernel(const FusedArgs a) {
                 for (int j = 0; j < 4; ++j) {
                     int64_t gj = g0 + 4 * kq + j;
                     if (gj >= a.n_groups) gj = a.n_groups - 1;
-                    const float *rp = Rb + gj * S;
-                    if constexpr (RP) {   // pre-split radii: rho_s = slot s + slot S+s (exact in fp32)
+                    const float *rp = Rb + gj * (ENC ? 1 : S);
+                    if constexpr (ENC) {   // the box's allowance; S only counts the blocks of Query 1
+                        rad[u][j][0] = rp[0];
+                    } else if constexpr (RP) {   // pre-split radii: rho_s = slot s + slot S+s (exact in fp32)
                         const uint4 blk = reinterpret_cast<const uint4 *>(Rb)[gj];
                         const uint32_t w[4] = {blk.x, blk.y, blk.z, blk.w};
 #pragma unroll
@@ -280,12 +282,23 @@ query_fused_kernel(const FusedArgs a) {
                         // a group survives for a head iff every block's bound reaches that block's threshold
                         bool okb[4] = {true, true, true, true};
                         if constexpr (S <= 4) {
+                            float qnw = 0.f;   // boxes: the allowance multiplies the norm of the whole query
+                            if constexpr (ENC) {
+#pragma unroll
+                                for (int s = 0; s < S; ++s) qnw += qn[hb][s] * qn[hb][s];
+                                qnw = sqrtf(qnw) * (1.0f + 0x1p-20f);
+                            }
                             auto block = [&](auto s_c) {
                                 constexpr int s = decltype(s_c)::value;
                                 constexpr int KPS = 4 / S;
-                                const lvr_f32x4 sc = lvr_score_tile_block<s * KPS, (s + 1) * KPS>(ac, bq[hb]);
+                                lvr_f32x4 sc;
+                                if constexpr (ENC) sc = lvr_score_tile_block2<s * KPS, (s + 1) * KPS>(ac, bq[hb], ac2, bq2[hb]);
+                                else sc = lvr_score_tile_block<s * KPS, (s + 1) * KPS>(ac, bq[hb]);
 #pragma unroll
-                                for (int j = 0; j < 4; ++j) okb[j] = okb[j] && (sc[j] + rad[u][j][s] * qn[hb][s] >= taus[hb][s]);
+                                for (int j = 0; j < 4; ++j) {
+                                    const float slack = ENC ? rad[u][j][0] * qnw : rad[u][j][s] * qn[hb][s];
+                                    okb[j] = okb[j] && (sc[j] + slack >= taus[hb][s]);
+                                }
                             };
                             block(std::integral_constant<int, 0>{});
                             if constexpr (S >= 2) block(std::integral_constant<int, 1>{});
@@ -596,7 +609,7 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
                                   int32_t *out_idx, int64_t cap, hipStream_t st, const void *k_new, const void *v_new,
                                   int64_t m_new) {
     if (ix->cfg.kv_dtype != LVR_BF16) return hipErrorInvalidValue;
-    if (tau_s && (ix->box || (ix->cf8 && ix->cfg.n_subspaces > 4))) return hipErrorInvalidValue;
+    if (tau_s && ((ix->box || ix->cf8) && ix->cfg.n_subspaces > 4)) return hipErrorInvalidValue;
     FusedArgs a;
     a.tau_s = tau_s;
     a.k_new = k_new;
@@ -649,6 +662,24 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
     // one centre tile per trip for the small segments of short contexts, two per trip for long ones
     // (measured crossover between 32k and 128k keys); four per trip costs a wave per SIMD and 12 us
     const bool one = tpw == 1;
+    if (tau_s && ix->box) {   // Query 1 on boxes: per-block box bounds, blocks of whole MFMA steps
+        const int S = ix->cfg.n_subspaces;
+#define LVR_Q1B_LAUNCH(HB, CF8)                                                                                 \
+    do {                                                                                                        \
+        if (S == 1) hipLaunchKernelGGL((query_fused_kernel<HB, 1, 1, 1, 1, CF8>), grid, dim3(256), 0, st, a);   \
+        else if (S == 2) hipLaunchKernelGGL((query_fused_kernel<HB, 2, 1, 1, 1, CF8>), grid, dim3(256), 0, st, a); \
+        else hipLaunchKernelGGL((query_fused_kernel<HB, 4, 1, 1, 1, CF8>), grid, dim3(256), 0, st, a);          \
+    } while (0)
+        if (ix->G <= 4) {
+            if (ix->cf8) LVR_Q1B_LAUNCH(1, 1);
+            else LVR_Q1B_LAUNCH(1, 0);
+        } else {
+            if (ix->cf8) LVR_Q1B_LAUNCH(2, 1);
+            else LVR_Q1B_LAUNCH(2, 0);
+        }
+#undef LVR_Q1B_LAUNCH
+        return hipGetLastError();
+    }
     if (tau_s) {   // Query 1: per-block thresholds
         const int S = ix->cfg.n_subspaces;
 #define LVR_Q1_LAUNCH(HB, CF8)                                                                                  \

@@ -908,7 +908,7 @@ def test_query1_unsupported_configurations(G):
     tau = torch.zeros((1, 8), device="cuda")
     idx = torch.zeros((1, 8, 16), dtype=torch.int32, device="cuda")
     cnt = torch.zeros((1, 8), dtype=torch.int32, device="cuda")
-    for kw in (dict(enclosing=L.LVR_ENCLOSE_AABB), dict(flags=L.LVR_SEPARATE_KERNELS)):
+    for kw in (dict(enclosing=L.LVR_ENCLOSE_AABB, n_subspaces=8), dict(flags=L.LVR_SEPARATE_KERNELS)):
         with G.Index(cache.K, cache.V, "bf16", 8, **kw) as ix:
             S = kw.get("n_subspaces", 4)
             with pytest.raises(L.LouverError) as e:
@@ -1256,7 +1256,7 @@ def test_misaligned_pointers_are_refused_on_the_host(G):
 def test_subspace_thresholds_edge_cases(G, oracle):
     """No indexed group: every threshold is -inf (nothing can be pruned) and Query 1 still returns
     the buffer's qualifying keys; tau = -inf stays -inf; appended groups are taken into account;
-    boxes and the two-launch form have no such entry point."""
+    boxes with more than four blocks and the two-launch form have no such entry point."""
     L = G.L
     cache = W.make_cache(2, n=300, n_kv_heads=2)
     q = W.make_queries(2, n_q_heads=8)
@@ -1274,7 +1274,7 @@ def test_subspace_thresholds_edge_cases(G, oracle):
         idx, cnt, out = G.query1(ix, q, ts, tau)
         G.check_step(oracle, ix, q, tau, idx, cnt, out, tag="query1 after append")
         assert cnt[0, 3] == 300
-    for kw in (dict(flags=L.LVR_SEPARATE_KERNELS), dict(enclosing=L.LVR_ENCLOSE_AABB)):
+    for kw in (dict(flags=L.LVR_SEPARATE_KERNELS), dict(enclosing=L.LVR_ENCLOSE_AABB, n_subspaces=16)):
         with G.Index(cache.K, cache.V, "bf16", 8, **kw) as ix:
             with pytest.raises(L.LouverError) as e:
                 G.subspace_thresholds(ix, q, np.zeros((1, 8), dtype=np.float32))
@@ -1420,3 +1420,74 @@ def test_queries_with_full_fp32_precision(G, oracle, hq, hkv, kind):
                     tau = G.oracle_taus(oracle, ix, q, frac=frac)
                     idx, cnt, out = ix.query(q, tau, fused=True)
                     G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=f"fp32 q {kind} hq={hq} S={S} centres={idt} frac={frac}")
+
+
+@pytest.mark.parametrize("centres", ["same", "fp8"])
+@pytest.mark.parametrize("S,keys,hq", [(1, "local", 4), (2, "local", 4), (4, "local", 4), (4, "workload", 4), (2, "workload", 8),
+                                       (4, "local", 8), (4, "workload", 1)])
+def test_query1_on_boxes(G, oracle, S, keys, hq, centres):
+    """Query 1 with box enclosures: a group is a candidate for a head iff in every coordinate block the box
+    bound of that block (upper corner against q+, lower corner against q-, plus the group's allowance times
+    |q|) reaches the block's threshold.  The library's thresholds equal the oracle's on the exported boxes
+    and give Problem 1's set; cutting thresholds keep every key the promise covers, and the number of
+    candidate groups matches the oracle's Alg. 3 on the same bounds."""
+    L = G.L
+    n, r = 4096 + 37, 4
+    cache = W.make_local_cache(2, n=n) if keys == "local" else W.make_cache(2, n=n)
+    K, V = cache.K[:, :1], cache.V[:, :1]
+    q = W.make_queries(2, n_q_heads=hq)
+    G.say(f"query1 on boxes S={S} keys={keys} heads={hq} corners={centres}")
+    idt = L.LVR_INDEX_FP8 if centres == "fp8" else L.LVR_INDEX_SAME
+    with G.Index(K, V, "bf16", hq, group_size=r, n_subspaces=S, enclosing=L.LVR_ENCLOSE_AABB, index_dtype=idt) as ix:
+        n_groups = n // r
+        corners, allow, _, _ = ix.export()
+        hi = W.bf16_bits_to_f32(corners[0, 0, :, 0]).reshape(-1, 128).astype(np.float64)
+        lo = W.bf16_bits_to_f32(corners[0, 0, :, 1]).reshape(-1, 128).astype(np.float64)
+        ds = 128 // S
+        f = np.empty((hq, S, n_groups))
+        for h in range(hq):
+            qn = np.linalg.norm(q[0, h].astype(np.float64))
+            for s_ in range(S):
+                qm = np.zeros(128, dtype=np.float32)
+                qm[s_ * ds:(s_ + 1) * ds] = q[0, h, s_ * ds:(s_ + 1) * ds]
+                f[h, s_] = oracle.aabb_bounds(qm, lo, hi) + allow[0, 0, :, 0].astype(np.float64) * qn
+        label = np.tile(np.arange(n_groups * r, dtype=np.int32) // r, (S, 1))
+        Kd = K[0, 0].astype(np.float64)
+        tau = G.oracle_taus(oracle, ix, q, frac=0.02)
+        lib_tau_s = G.subspace_thresholds(ix, q, tau)
+        for h in range(hq):
+            want = oracle.safe_subspace_thresholds(f[h], float(tau[0, h]))
+            scale = abs(float(tau[0, h])) + np.abs(f[h]).max(axis=1).sum()
+            assert np.all(np.abs(lib_tau_s[0, h] - want) <= 2e-5 * scale), (h, lib_tau_s[0, h], want)
+        idx, cnt, out = G.query1(ix, q, lib_tau_s, tau)
+        G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=f"query1 boxes, library thresholds S={S}")
+        tau_s = np.empty((1, hq, S), dtype=np.float32)
+        for quant in (0.5, 0.9):
+            for h in range(hq):
+                tau_s[0, h] = np.quantile(f[h], quant, axis=1).astype(np.float32)
+            idx, cnt, out = G.query1(ix, q, tau_s, tau)
+            st = ix.stats()
+            alive_lo = np.zeros(n_groups, dtype=bool)
+            alive_hi = np.zeros(n_groups, dtype=bool)
+            for h in range(hq):
+                s_f32 = oracle.scores_f32(q[0, h], K[0, 0])
+                te = tau_s[0, h].astype(np.float64)
+                te = te - 0.5e-4 * np.abs(te)
+                slack = 1e-5 * np.abs(te) + 1e-5 * np.abs(f[h]).max(axis=1) + 2e-3
+                strict = oracle.query1_filter(f[h], label, te + slack)
+                loose = oracle.query1_filter(f[h], label, te - slack)
+                alive_lo |= strict.reshape(n_groups, r)[:, 0]
+                alive_hi |= loose.reshape(n_groups, r)[:, 0]
+                got = np.zeros(n, dtype=bool)
+                got[idx[0, h, :cnt[0, h]]] = True
+                assert cnt[0, h] == got.sum()
+                band = 1e-4 * abs(float(tau[0, h]))
+                tail = np.arange(n) >= n_groups * r
+                must = (s_f32 >= tau[0, h]) & (np.concatenate([strict, np.ones(n - n_groups * r, bool)]) | tail)
+                assert not (must & ~got).any(), (S, quant, h)
+                assert not (got & (s_f32 < tau[0, h] - band)).any()
+                blocks = (Kd * q[0, h].astype(np.float64)).reshape(n, S, ds).sum(-1)
+                relevant = (s_f32 >= tau[0, h]) & (blocks >= tau_s[0, h][None, :] + 1e-3).all(1)
+                assert not (relevant & ~got).any()
+            assert alive_lo.sum() <= st["groups_surviving"] <= alive_hi.sum(), (S, quant, alive_lo.sum(), st["groups_surviving"], alive_hi.sum())
+            assert st["groups_surviving"] < st["groups_scored"]
