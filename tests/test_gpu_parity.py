@@ -1491,3 +1491,34 @@ def test_query1_on_boxes(G, oracle, S, keys, hq, centres):
                 assert not (relevant & ~got).any()
             assert alive_lo.sum() <= st["groups_surviving"] <= alive_hi.sum(), (S, quant, alive_lo.sum(), st["groups_surviving"], alive_hi.sum())
             assert st["groups_surviving"] < st["groups_scored"]
+
+
+def test_create_destroy_returns_all_memory(G):
+    """Device memory in use goes back to where it was after indices of every flavour have been created,
+    used and destroyed (arena, index, work space, position maps, reservoir, side stream and events,
+    profiling events)."""
+    L = G.L
+    cache = W.make_cache(2, n=2048, n_kv_heads=2)
+    q = W.make_queries(2, n_q_heads=8)
+    tau = np.zeros((1, 8), dtype=np.float32)
+    flavours = [dict(), dict(grouping=L.LVR_GROUP_TREE), dict(enclosing=L.LVR_ENCLOSE_AABB), dict(reservoir_size=256),
+                dict(flags=L.LVR_CONCURRENT_UPDATE, buffer_size=32), dict(flags=L.LVR_SEPARATE_KERNELS),
+                dict(flags=L.LVR_KV_IN_HOST_MEMORY), dict(index_dtype=L.LVR_INDEX_SAME, n_subspaces=16)]
+
+    def cycle():
+        for kw in flavours:
+            with G.Index(cache.K[:, :, :2000], cache.V[:, :, :2000], "bf16", 8, capacity=2048, **kw) as ix:
+                L.lvr_profile_enable(ix.h, 16)
+                ix.append(cache.K[:, :, 2000:2040], cache.V[:, :, 2000:2040])
+                ix.query(q, tau, fused=True)
+                L.lvr_profile_read(ix.h)
+    cycle()                                   # first use: the runtime's own pools reach their size
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    free0, _ = torch.cuda.mem_get_info()
+    for _ in range(5):
+        cycle()
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    free1, _ = torch.cuda.mem_get_info()
+    assert free0 - free1 < 8 << 20, (free0, free1)
