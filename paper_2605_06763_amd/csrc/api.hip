@@ -295,6 +295,7 @@ int lvr_create(const lvr_config *cfg, lvr_index **out) {
     if (e != hipSuccess) {
         free_all(ix);
         delete ix;
+        (void)hipGetLastError();   // the failure is reported here, not by whatever HIP call comes next
         if (e == hipErrorOutOfMemory) {
             g_last_hip_error = (int)e;
             return LVR_E_NOMEM;

@@ -1522,3 +1522,23 @@ def test_create_destroy_returns_all_memory(G):
     torch.cuda.empty_cache()
     free1, _ = torch.cuda.mem_get_info()
     assert free0 - free1 < 8 << 20, (free0, free1)
+
+
+def test_create_beyond_device_memory_fails_cleanly(G):
+    """An arena that cannot fit (about a terabyte here) comes back as LVR_E_NOMEM with nothing
+    left allocated, and the library keeps working."""
+    L = G.L
+    torch.cuda.synchronize()
+    free0, total = torch.cuda.mem_get_info()
+    cfg = L.make_config(batch=8, n_q_heads=32, n_kv_heads=8, capacity=1 << 26)     # 2 * 64 * 2^26 * 256 B = 2 TiB
+    assert L.lvr_arena_bytes(cfg) > total
+    h = C.c_void_p()
+    rc = L.lib().lvr_create(C.byref(cfg), C.byref(h))
+    assert rc == L.LVR_E_NOMEM and not h.value, rc
+    torch.cuda.synchronize()
+    free1, _ = torch.cuda.mem_get_info()
+    assert free0 - free1 < 8 << 20
+    cache = W.make_cache(2, n=256, n_kv_heads=2)
+    with G.Index(cache.K, cache.V, "bf16", 8) as ix:
+        idx, cnt, _ = ix.query(W.make_queries(2, n_q_heads=8), np.full((1, 8), -np.inf, dtype=np.float32))
+        assert (cnt == 256).all()
