@@ -351,12 +351,15 @@ int lvr_build(lvr_index *ix, const void *K, const void *V, int64_t n, const int6
             LVR_HIP(lvr_launch_iota_rows(ix, n_tree, n - n_tree, st));
         }
     } else if (n > 0) {
+        // contiguous groups: V and the ungrouped tail of K are copied here, the grouped key rows by the
+        // build kernel below, which reads them from the caller's K anyway
         Timed t(ix, LVR_K_COPY, st);
-        LVR_HIP(lvr_launch_copy_kv(ix, K, ks, V, vs, 0, n, st));
+        LVR_HIP(lvr_launch_copy_kv(ix, K, ks, V, vs, 0, n, st, n_groups * r));
     }
     {
         Timed t(ix, LVR_K_BUILD, st);
-        LVR_HIP(lvr_launch_build_groups(ix, 0, n_groups, st));
+        const bool fused_copy = n > 0 && ix->cfg.grouping != LVR_GROUP_TREE;
+        LVR_HIP(lvr_launch_build_groups(ix, 0, n_groups, st, fused_copy ? K : nullptr, fused_copy ? ks : nullptr));
     }
     LVR_HIP(lvr_launch_reservoir_reset(ix, st));
     LVR_HIP(lvr_launch_reservoir_update(ix, 0, n, st));

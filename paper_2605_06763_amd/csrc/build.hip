@@ -20,6 +20,16 @@ struct CopySide {
     const char *src;
     char *dst;
     int64_t sb, sh, st;
+    int64_t first;   // rows below this one are left alone (someone else writes them)
+};
+
+// Where a build kernel takes the member rows from: the arena (base == NULL), or the caller's K with
+// its element strides, in which case the kernel also writes the rows into the arena (the copy of K
+// and the pass over the groups are then one read of K instead of two).
+struct BuildSrc {
+    const char *base;
+    int64_t sb, sh, st;
+    int n_kv_heads;
 };
 
 __global__ void copy_rows_kernel(CopySide k, CopySide v, int n_kv_heads, int64_t cap_rows, int64_t dst_row0,
@@ -31,6 +41,7 @@ __global__ void copy_rows_kernel(CopySide k, CopySide v, int n_kv_heads, int64_t
     int bh = blockIdx.y;
     int b = bh / n_kv_heads, h = bh % n_kv_heads;
     int64_t row = i / chunks;
+    if (row < c.first) return;
     int ch = (int)(i % chunks);
     const uint4 *s = reinterpret_cast<const uint4 *>(c.src + (b * c.sb + h * c.sh + row * c.st) * elt) + ch;
     uint4 *d = reinterpret_cast<uint4 *>(c.dst + ((int64_t)bh * cap_rows + dst_row0 + row) * row_bytes) + ch;
@@ -87,20 +98,27 @@ __device__ __forceinline__ uint32_t f32_to_e4m3_directed(float x, bool up) {
 // (byte kq*32 + kk*8 + j holds coordinate kk*32 + kq*8 + j); only for bf16 caches.
 template <typename KT, bool CF8 = false>
 __global__ void __launch_bounds__(256)
-build_groups_kernel(const void *__restrict__ K, void *__restrict__ centres, float *__restrict__ radii,
-                    int64_t cap_rows, int64_t max_groups, int64_t g0, int64_t g1, int r, int S) {
+build_groups_kernel(void *__restrict__ K, void *__restrict__ centres, float *__restrict__ radii,
+                    int64_t cap_rows, int64_t max_groups, int64_t g0, int64_t g1, int r, int S, const BuildSrc src) {
     const int bh = blockIdx.y;
     const int li = threadIdx.x & 15;
     int64_t g = g0 + (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
     const bool valid = g < g1;
     if (!valid) g = g0;   // keep every lane busy so the shuffles below see defined data
-    const char *Kb = static_cast<const char *>(K) + (int64_t)bh * cap_rows * LVR_D * sizeof(KT);
+    char *Kb = static_cast<char *>(K) + (int64_t)bh * cap_rows * LVR_D * sizeof(KT);
+    const bool from_src = src.base != nullptr;   // uniform
+    const char *Sb = from_src ? src.base + ((int64_t)(bh / src.n_kv_heads) * src.sb + (int64_t)(bh % src.n_kv_heads) * src.sh) * (int64_t)sizeof(KT)
+                              : Kb;
+    const int64_t row_stride = from_src ? src.st * (int64_t)sizeof(KT) : (int64_t)LVR_D * (int64_t)sizeof(KT);
 
     float c[8];
     lvr_zero8(c);
     for (int m = 0; m < r; ++m) {          // members in ascending row order
         float x[8];
-        lvr_load8<KT>(Kb, g * r + m, li, x);
+        lvr_raw8<KT> raw;
+        lvr_load_raw(Sb + (g * r + m) * row_stride, 0, li, raw);
+        if (from_src && valid) lvr_store_raw(Kb, g * r + m, li, raw);   // the arena's copy of the row
+        lvr_unpack(raw, x);
 #pragma unroll
         for (int e = 0; e < 8; ++e) c[e] += x[e];
     }
@@ -147,7 +165,7 @@ build_groups_kernel(const void *__restrict__ K, void *__restrict__ centres, floa
     float max_d2 = 0.f;
     for (int m = 0; m < r; ++m) {
         float x[8];
-        lvr_load8<KT>(Kb, g * r + m, li, x);
+        lvr_load8<KT>(Sb + (g * r + m) * row_stride, 0, li, x);
         float d2 = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -200,14 +218,17 @@ build_groups_kernel(const void *__restrict__ K, void *__restrict__ centres, floa
 // |e|_2, which times |q|_2 exceeds sum_c |q_c| e_c.
 template <bool CF8>
 __global__ void __launch_bounds__(256)
-build_boxes_kernel(const void *__restrict__ K, void *__restrict__ corners, float *__restrict__ allowance,
-                   int64_t cap_rows, int64_t max_groups, int64_t g0, int64_t g1, int r) {
+build_boxes_kernel(void *__restrict__ K, void *__restrict__ corners, float *__restrict__ allowance,
+                   int64_t cap_rows, int64_t max_groups, int64_t g0, int64_t g1, int r, const BuildSrc src) {
     const int bh = blockIdx.y;
     const int li = threadIdx.x & 15;
     int64_t g = g0 + (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
     const bool valid = g < g1;
     if (!valid) g = g0;
-    const char *Kb = static_cast<const char *>(K) + (int64_t)bh * cap_rows * LVR_D * 2;
+    char *Kb = static_cast<char *>(K) + (int64_t)bh * cap_rows * LVR_D * 2;
+    const bool from_src = src.base != nullptr;   // uniform
+    const char *Sb = from_src ? src.base + ((int64_t)(bh / src.n_kv_heads) * src.sb + (int64_t)(bh % src.n_kv_heads) * src.sh) * 2 : Kb;
+    const int64_t row_stride = from_src ? src.st * 2 : (int64_t)LVR_D * 2;
     float lo[8], hi[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -216,7 +237,10 @@ build_boxes_kernel(const void *__restrict__ K, void *__restrict__ corners, float
     }
     for (int m = 0; m < r; ++m) {
         float x[8];
-        lvr_load8<lvr_bf16_t>(Kb, g * r + m, li, x);
+        lvr_raw8<lvr_bf16_t> raw;
+        lvr_load_raw(Sb + (g * r + m) * row_stride, 0, li, raw);
+        if (from_src && valid) lvr_store_raw(Kb, g * r + m, li, raw);   // the arena's copy of the row
+        lvr_unpack(raw, x);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             lo[e] = fminf(lo[e], x[e]);
@@ -289,39 +313,43 @@ __global__ void iota_rows_kernel(int32_t *slot_pos, int32_t *pos_slot, int64_t c
 }  // namespace
 
 hipError_t lvr_launch_copy_kv(lvr_index *ix, const void *K, const int64_t ks[3], const void *V, const int64_t vs[3],
-                              int64_t dst_row0, int64_t rows, hipStream_t st) {
+                              int64_t dst_row0, int64_t rows, hipStream_t st, int64_t k_first) {
     if (rows <= 0) return hipSuccess;
     const int row_bytes = (int)(LVR_D * ix->elt);
     const int64_t total = rows * (row_bytes / 16);
     dim3 grid((unsigned)((total + 255) / 256), (unsigned)lvr_n_bh(ix), 2);
-    CopySide k{static_cast<const char *>(K), static_cast<char *>(ix->K), ks[0], ks[1], ks[2]};
-    CopySide v{static_cast<const char *>(V), static_cast<char *>(ix->V), vs[0], vs[1], vs[2]};
+    // k_first > 0: the leading key rows are written by the build kernel that reads them from the caller's K
+    CopySide k{static_cast<const char *>(K), static_cast<char *>(ix->K), ks[0], ks[1], ks[2], k_first};
+    CopySide v{static_cast<const char *>(V), static_cast<char *>(ix->V), vs[0], vs[1], vs[2], 0};
     hipLaunchKernelGGL(copy_rows_kernel, grid, dim3(256), 0, st, k, v, ix->cfg.n_kv_heads, ix->cap_rows, dst_row0, rows,
                        row_bytes, (int)ix->elt);
     return hipGetLastError();
 }
 
-hipError_t lvr_launch_build_groups(lvr_index *ix, int64_t g0, int64_t g1, hipStream_t st) {
+hipError_t lvr_launch_build_groups(lvr_index *ix, int64_t g0, int64_t g1, hipStream_t st, const void *K_src,
+                                   const int64_t *ks) {
     if (g1 <= g0) return hipSuccess;
     dim3 grid((unsigned)((g1 - g0 + 15) / 16), (unsigned)lvr_n_bh(ix));
+    // K_src: the groups' rows come from the caller's K (element strides ks) and are copied into the arena on the way
+    BuildSrc src{static_cast<const char *>(K_src), K_src ? ks[0] : 0, K_src ? ks[1] : 0, K_src ? ks[2] : 0, ix->cfg.n_kv_heads};
     if (ix->box) {
         if (ix->cf8)
             hipLaunchKernelGGL(build_boxes_kernel<true>, grid, dim3(256), 0, st, ix->K, ix->centres, ix->radii, ix->cap_rows,
-                               ix->max_groups, g0, g1, ix->cfg.group_size);
+                               ix->max_groups, g0, g1, ix->cfg.group_size, src);
         else
             hipLaunchKernelGGL(build_boxes_kernel<false>, grid, dim3(256), 0, st, ix->K, ix->centres, ix->radii, ix->cap_rows,
-                               ix->max_groups, g0, g1, ix->cfg.group_size);
+                               ix->max_groups, g0, g1, ix->cfg.group_size, src);
         return hipGetLastError();
     }
     if (ix->cf8)
         hipLaunchKernelGGL((build_groups_kernel<lvr_bf16_t, true>), grid, dim3(256), 0, st, ix->K, ix->centres, ix->radii,
-                           ix->cap_rows, ix->max_groups, g0, g1, ix->cfg.group_size, ix->cfg.n_subspaces);
+                           ix->cap_rows, ix->max_groups, g0, g1, ix->cfg.group_size, ix->cfg.n_subspaces, src);
     else if (ix->cfg.kv_dtype == LVR_BF16)
         hipLaunchKernelGGL(build_groups_kernel<lvr_bf16_t>, grid, dim3(256), 0, st, ix->K, ix->centres, ix->radii,
-                           ix->cap_rows, ix->max_groups, g0, g1, ix->cfg.group_size, ix->cfg.n_subspaces);
+                           ix->cap_rows, ix->max_groups, g0, g1, ix->cfg.group_size, ix->cfg.n_subspaces, src);
     else
         hipLaunchKernelGGL(build_groups_kernel<lvr_f32_t>, grid, dim3(256), 0, st, ix->K, ix->centres, ix->radii,
-                           ix->cap_rows, ix->max_groups, g0, g1, ix->cfg.group_size, ix->cfg.n_subspaces);
+                           ix->cap_rows, ix->max_groups, g0, g1, ix->cfg.group_size, ix->cfg.n_subspaces, src);
     return hipGetLastError();
 }
 

@@ -104,8 +104,9 @@ static inline size_t lvr_counter_ints(int n_bh, int n_bhq, int64_t max_groups) {
 // ---- launchers (each returns a hipError_t from hipGetLastError after the launch) ----
 // copies `rows` key rows and value rows into the arena starting at arena row dst_row0 (one launch)
 hipError_t lvr_launch_copy_kv(lvr_index *ix, const void *K, const int64_t ks[3], const void *V, const int64_t vs[3],
-                              int64_t dst_row0, int64_t rows, hipStream_t st);
-hipError_t lvr_launch_build_groups(lvr_index *ix, int64_t g0, int64_t g1, hipStream_t st);
+                              int64_t dst_row0, int64_t rows, hipStream_t st, int64_t k_first = 0);
+hipError_t lvr_launch_build_groups(lvr_index *ix, int64_t g0, int64_t g1, hipStream_t st, const void *K_src = nullptr,
+                                   const int64_t *ks = nullptr);
 hipError_t lvr_launch_iota_rows(lvr_index *ix, int64_t row0, int64_t rows, hipStream_t st);
 // clears the per-head counters (used when there is no index to prune)
 hipError_t lvr_launch_reset(lvr_index *ix, hipStream_t st);
@@ -206,6 +207,14 @@ __device__ __forceinline__ void lvr_load_raw(const void *base, int64_t row, int 
     const float4 *p = reinterpret_cast<const float4 *>(static_cast<const float *>(base) + row * LVR_D) + 2 * li;
     r.a = p[0];
     r.b = p[1];
+}
+__device__ __forceinline__ void lvr_store_raw(void *base, int64_t row, int li, const lvr_raw8<lvr_bf16_t> &r) {
+    reinterpret_cast<uint4 *>(static_cast<uint16_t *>(base) + row * LVR_D)[li] = r.a;
+}
+__device__ __forceinline__ void lvr_store_raw(void *base, int64_t row, int li, const lvr_raw8<lvr_f32_t> &r) {
+    float4 *p = reinterpret_cast<float4 *>(static_cast<float *>(base) + row * LVR_D) + 2 * li;
+    p[0] = r.a;
+    p[1] = r.b;
 }
 __device__ __forceinline__ void lvr_unpack(const lvr_raw8<lvr_bf16_t> &r, float (&x)[8]) {
     x[0] = lvr_bf16_lo(r.a.x); x[1] = lvr_bf16_hi(r.a.x);
