@@ -113,14 +113,33 @@ build_groups_kernel(void *__restrict__ K, void *__restrict__ centres, float *__r
 
     float c[8];
     lvr_zero8(c);
-    for (int m = 0; m < r; ++m) {          // members in ascending row order
-        float x[8];
-        lvr_raw8<KT> raw;
-        lvr_load_raw(Sb + (g * r + m) * row_stride, 0, li, raw);
-        if (from_src && valid) lvr_store_raw(Kb, g * r + m, li, raw);   // the arena's copy of the row
-        lvr_unpack(raw, x);
+    // groups of up to four rows stay in registers between the two passes over the members
+    lvr_raw8<KT> keep[4];
+    const bool kept = r <= 4;   // uniform
+    if (kept) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) c[e] += x[e];
+        for (int m = 0; m < 4; ++m)
+            if (m < r) lvr_load_raw(Sb + (g * r + m) * row_stride, 0, li, keep[m]);
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {       // members in ascending row order
+            if (m < r) {
+                float x[8];
+                if (from_src && valid) lvr_store_raw(Kb, g * r + m, li, keep[m]);   // the arena's copy of the row
+                lvr_unpack(keep[m], x);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) c[e] += x[e];
+            }
+        }
+    } else {
+        for (int m = 0; m < r; ++m) {
+            float x[8];
+            lvr_raw8<KT> raw;
+            lvr_load_raw(Sb + (g * r + m) * row_stride, 0, li, raw);
+            if (from_src && valid) lvr_store_raw(Kb, g * r + m, li, raw);
+            lvr_unpack(raw, x);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) c[e] += x[e];
+        }
     }
     const float inv = 1.0f / (float)r;
 #pragma unroll
@@ -163,9 +182,7 @@ build_groups_kernel(void *__restrict__ K, void *__restrict__ centres, float *__r
     cn2 = seg_sum(cn2, lanes_per_sub);
 
     float max_d2 = 0.f;
-    for (int m = 0; m < r; ++m) {
-        float x[8];
-        lvr_load8<KT>(Sb + (g * r + m) * row_stride, 0, li, x);
+    auto distance = [&](const float (&x)[8]) {
         float d2 = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -174,6 +191,22 @@ build_groups_kernel(void *__restrict__ K, void *__restrict__ centres, float *__r
         }
         d2 = seg_sum(d2, lanes_per_sub);
         max_d2 = fmaxf(max_d2, d2);
+    };
+    if (kept) {
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            if (m < r) {            // uniform: every lane takes part in the reduction
+                float x[8];
+                lvr_unpack(keep[m], x);
+                distance(x);
+            }
+        }
+    } else {
+        for (int m = 0; m < r; ++m) {
+            float x[8];
+            lvr_load8<KT>(Sb + (g * r + m) * row_stride, 0, li, x);
+            distance(x);
+        }
     }
     float rho = sqrtf(max_d2) * (1.0f + 0x1p-12f) + sqrtf(cn2) * 0x1p-12f;
     rho = __uint_as_float(__float_as_uint(rho) + 1u);    // one ulp up (rho >= 0)
