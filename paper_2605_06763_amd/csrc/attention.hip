@@ -166,9 +166,9 @@ __global__ void __launch_bounds__(1024)
 sparse_attention_wg_kernel(const void *__restrict__ K, const void *__restrict__ V,
                            const int32_t *__restrict__ pos_slot, const float *__restrict__ q,
                            const int32_t *__restrict__ idx, const float *__restrict__ scores, int64_t score_stride,
-                           const int32_t *__restrict__ count, int count_stride,
+                           const int32_t *count, int count_stride,   // may alias head_count: not restrict
                            int64_t cap, float *__restrict__ out, int64_t cap_rows, int64_t n_total, int n_q_heads,
-                           int n_kv_heads, int G, float qscale, int32_t *__restrict__ head_count,
+                           int n_kv_heads, int G, float qscale, int32_t *head_count,
                            int32_t *__restrict__ head_stat, int32_t *__restrict__ publish_count) {
     constexpr int NW = 16;
     __shared__ float s_m[NW], s_l[NW];
@@ -293,9 +293,12 @@ sparse_attention_wg_kernel(const void *__restrict__ K, const void *__restrict__ 
 // attention's split geometry; without one all P are merged (dense baseline).
 constexpr int COMBINE_MAX_P = 256;
 
+// `count` and `head_count` may be the same array (the decode step hands the internal counters to
+// both), so neither is declared restrict, every thread reads the count BEFORE the kernel's first
+// barrier and the counter is cleared only AFTER it.
 __global__ void __launch_bounds__(512)
 combine_kernel(const float *__restrict__ part_ml, const float *__restrict__ part_o, float *__restrict__ out, int P,
-               const int32_t *__restrict__ count, int count_stride, int64_t cap, int32_t *__restrict__ head_count,
+               const int32_t *count, int count_stride, int64_t cap, int32_t *head_count,
                int32_t *__restrict__ head_stat, int32_t *__restrict__ publish_count) {
     __shared__ float s_w[COMBINE_MAX_P];
     __shared__ float s_red[8];
@@ -316,13 +319,10 @@ combine_kernel(const float *__restrict__ part_ml, const float *__restrict__ part
     const float m_raw = (t < P) ? part_ml[(hq * P + t) * 2] : -INFINITY;
     const float l_raw = (t < P) ? part_ml[(hq * P + t) * 2 + 1] : 0.f;
     int used = P;
+    int32_t true_cnt = 0;
     if (count) {
         int64_t cnt = count[hq * count_stride];
-        if (publish_count && t == 0) {
-            publish_count[hq] = (int32_t)cnt;
-            head_stat[hq] = (int32_t)cnt;
-            head_count[hq * LVR_CNT_STRIDE] = 0;
-        }
+        true_cnt = (int32_t)cnt;
         if (cnt > cap) cnt = cap;
         if (cnt < 0) cnt = 0;
         split_length(cnt, P, &used);
@@ -334,6 +334,13 @@ combine_kernel(const float *__restrict__ part_ml, const float *__restrict__ part
     for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
     if (lane == 0) s_red[wave] = mx;
     __syncthreads();
+    // every thread's read of the count has completed (its value fed the shuffle above), so the
+    // counter can be handed over and cleared for the next query
+    if (count && publish_count && t == 0) {
+        publish_count[hq] = true_cnt;
+        head_stat[hq] = true_cnt;
+        head_count[hq * LVR_CNT_STRIDE] = 0;
+    }
     float M = s_red[0];
 #pragma unroll
     for (int w = 1; w < 8; ++w) M = fmaxf(M, s_red[w]);
