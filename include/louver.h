@@ -217,6 +217,25 @@ int lvr_subspace_thresholds(lvr_index *ix, const float *q_dev, const float *tau_
 int lvr_sparse_attention(lvr_index *ix, const float *q_dev, const int32_t *idx_dev,
                          const int32_t *count_dev, int64_t cap, float *out_dev, void *stream);
 
+/* lvr_sparse_attention for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  No lvr_index is needed and
+ * nothing is allocated or freed, by this call or by anything it uses: K_dev and V_dev are the
+ * caller's own cache, contiguous [batch][n_kv_heads][n][128] of kv_dtype (rows 16-byte aligned),
+ * positions in idx_dev are row numbers 0 .. n-1, and the split pass keeps its partial (m, l, o)
+ * triples in a static device array inside the library (8.1 MiB per GPU, held until the process
+ * ends) whose per-device address is looked up on the first call on that device.
+ * Same kernels and same results as lvr_sparse_attention with attn_splits = 64 (64 splits per
+ * head, then the combine pass).  scale = 0 means 1/sqrt(128).
+ * Limits: batch * n_q_heads <= 256 and n <= 2^30, else LVR_E_CAPACITY.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ * streams, two threads) race on it and must be ordered by the caller.  The array keeps the last
+ * call's partials; none of it has to start at zero, since a call reads only what its own split
+ * pass has just written. */
+int lvr_sparse_attention_static(const void *K_dev, const void *V_dev, int64_t n, int32_t kv_dtype, int32_t batch,
+                                int32_t n_q_heads, int32_t n_kv_heads, float scale, const float *q_dev,
+                                const int32_t *idx_dev, const int32_t *count_dev, int64_t cap, float *out_dev,
+                                void *stream);
+
 /* lvr_query followed by lvr_sparse_attention on its result, in one call (Alg. 3 / Alg. 4 end to
  * end: retrieve, then attend).  Launches kernels only: no allocation, no host synchronisation,
  * no memset, so the call may be recorded while `stream` is under HIP graph capture; a recorded

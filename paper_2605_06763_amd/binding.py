@@ -59,7 +59,7 @@ EXPORTS = [
     "lvr_sparse_attention", "lvr_decode_step", "lvr_dense_attention", "lvr_get_stats",
     "lvr_export_index", "lvr_length", "lvr_strerror", "lvr_last_hip_error",
     "lvr_profile_enable", "lvr_profile_read", "lvr_threshold", "lvr_export_reservoir", "lvr_publish", "lvr_query1", "lvr_append_decode_step", "lvr_host_bytes",
-    "lvr_subspace_thresholds",
+    "lvr_subspace_thresholds", "lvr_sparse_attention_static",
 ]
 
 _lib = None
@@ -105,6 +105,8 @@ def lib():
     L.lvr_host_bytes.restype = C.c_size_t
     L.lvr_query1.argtypes = [vp, vp, vp, vp, vp, vp, i64, vp]
     L.lvr_subspace_thresholds.argtypes = [vp, vp, vp, vp, vp]
+    L.lvr_sparse_attention_static.argtypes = [vp, vp, i64, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_float,
+                                              vp, vp, vp, i64, vp, vp]
     L.lvr_threshold.argtypes = [vp, vp, C.c_int, C.c_float, vp, vp]
     L.lvr_export_reservoir.argtypes = [vp, vp]
     L.lvr_strerror.argtypes = [C.c_int]
@@ -231,6 +233,21 @@ def lvr_sparse_attention(h, q, idx, count, out, stream=None) -> None:
     _check(lib().lvr_sparse_attention(h, _dev(q, torch.float32, "q"), _dev(idx, torch.int32, "idx"),
                                       _dev(count, torch.int32, "count"), cap, _dev(out, torch.float32, "out"),
                                       _stream(stream)), "lvr_sparse_attention")
+
+
+def lvr_sparse_attention_static(K, V, q, idx, count, out, scale=0.0, stream=None) -> None:
+    """K, V: contiguous device tensors [batch][n_kv_heads][n][128] (bf16 or fp32); no index object."""
+    if K.dim() != 4 or V.shape != K.shape or K.dtype != V.dtype:
+        raise ValueError("K and V must be [batch][n_kv_heads][n][head_dim] of one dtype")
+    if K.dtype not in (torch.bfloat16, torch.float32):
+        raise ValueError("K and V must be bf16 or fp32")
+    cap = idx.shape[-1]
+    _check(lib().lvr_sparse_attention_static(_dev(K, name="K"), _dev(V, name="V"), K.shape[2],
+                                             LVR_BF16 if K.dtype == torch.bfloat16 else LVR_F32, K.shape[0],
+                                             q.shape[1], K.shape[1], float(scale), _dev(q, torch.float32, "q"),
+                                             _dev(idx, torch.int32, "idx"), _dev(count, torch.int32, "count"), cap,
+                                             _dev(out, torch.float32, "out"), _stream(stream)),
+           "lvr_sparse_attention_static")
 
 
 def lvr_decode_step(h, q, tau, out, out_idx, out_count, stream=None) -> None:
