@@ -124,7 +124,9 @@ typedef struct lvr_config {
                              * lvr_threshold (appendix "Threshold Oracle Comparison"); 0 = none         */
     uint64_t seed;          /* seed of the counter-based generator behind the reservoir              */
     int32_t index_dtype;    /* lvr_index_dtype: storage of the centres                               */
-    int32_t reserved;      /* must be 0                                                             */
+    int32_t query_workgroups; /* workgroups a range-query launch aims at (its segment size follows from it);
+                               * 0 = the default, 1024 (four per compute unit); a tuning knob, results do not
+                               * depend on it                                                        */
 } lvr_config;
 
 /* Counters of the most recent lvr_query / lvr_decode_step, summed over batch and heads. */
@@ -310,6 +312,22 @@ enum lvr_kernel {
 };
 int lvr_profile_enable(lvr_index *ix, int max_launches); /* 0 turns timing off and frees the pool */
 int lvr_profile_read(lvr_index *ix, lvr_profile *out_host);
+
+/* Measurement aid: the exact filter without the index (Sec. 4.2: what the bound test of Eq. (2)
+ * buys is the difference to this).  enabled = 0: lvr_query / lvr_decode_step /
+ * lvr_append_decode_step skip the bound test and give every indexed key the exact dot product,
+ * reading no centre and no radius; enabled = 1 (the state after lvr_create) restores the test.
+ * Results are the same either way (Problem 1's set).  lvr_query1 ignores the setting.  bf16
+ * caches in the fused launch form; LVR_E_UNSUPPORTED otherwise.  Takes effect from the next call. */
+int lvr_set_bound_test(lvr_index *ix, int enabled);
+
+/* Measurement aid: one launch of a kernel that only READS `bytes` bytes (rounded down to a
+ * multiple of 16) from src_dev, 16 bytes per lane, eight consecutive KiB per wave in flight, and
+ * writes nothing (sink_dev, 4 bytes of device memory, is there so that the loads cannot be
+ * dropped).  workgroups = launch size (0 = 4096).  Timed by the caller, it gives the
+ * streaming-read rate this GPU reaches in practice, the ceiling the HBM-bound kernels of
+ * Sec. 4.2 are read against beside the published peak. */
+int lvr_stream_read(const void *src_dev, int64_t bytes, uint32_t *sink_dev, int32_t workgroups, void *stream);
 
 /* n = keys held per (sequence, KV head); n_indexed = keys inside groups. */
 int lvr_length(const lvr_index *ix, int64_t *n_host, int64_t *n_indexed_host);

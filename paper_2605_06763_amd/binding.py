@@ -31,7 +31,7 @@ class lvr_config(C.Structure):
         ("kv_dtype", C.c_int32), ("group_size", C.c_int32), ("n_subspaces", C.c_int32),
         ("buffer_size", C.c_int32), ("grouping", C.c_int32), ("enclosing", C.c_int32), ("flags", C.c_uint32),
         ("capacity", C.c_int64), ("scale", C.c_float), ("attn_splits", C.c_int32),
-        ("reservoir_size", C.c_int32), ("seed", C.c_uint64), ("index_dtype", C.c_int32), ("reserved", C.c_int32),
+        ("reservoir_size", C.c_int32), ("seed", C.c_uint64), ("index_dtype", C.c_int32), ("query_workgroups", C.c_int32),
     ]
 
 
@@ -60,6 +60,7 @@ EXPORTS = [
     "lvr_export_index", "lvr_length", "lvr_strerror", "lvr_last_hip_error",
     "lvr_profile_enable", "lvr_profile_read", "lvr_threshold", "lvr_export_reservoir", "lvr_publish", "lvr_query1", "lvr_append_decode_step", "lvr_host_bytes",
     "lvr_subspace_thresholds", "lvr_sparse_attention_static",
+    "lvr_set_bound_test", "lvr_stream_read",
 ]
 
 _lib = None
@@ -107,6 +108,8 @@ def lib():
     L.lvr_subspace_thresholds.argtypes = [vp, vp, vp, vp, vp]
     L.lvr_sparse_attention_static.argtypes = [vp, vp, i64, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_float,
                                               vp, vp, vp, i64, vp, vp]
+    L.lvr_set_bound_test.argtypes = [vp, C.c_int]
+    L.lvr_stream_read.argtypes = [vp, i64, vp, C.c_int32, vp]
     L.lvr_threshold.argtypes = [vp, vp, C.c_int, C.c_float, vp, vp]
     L.lvr_export_reservoir.argtypes = [vp, vp]
     L.lvr_strerror.argtypes = [C.c_int]
@@ -167,9 +170,9 @@ def _dev(t, dtype=None, name="tensor"):
 
 def make_config(*, batch, n_q_heads, n_kv_heads, head_dim=128, kv_dtype=LVR_BF16, group_size=4,
                 n_subspaces=4, buffer_size=256, grouping=LVR_GROUP_CONTIGUOUS, enclosing=LVR_ENCLOSE_BALL, flags=0, capacity,
-                scale=0.0, attn_splits=0, reservoir_size=0, seed=0, index_dtype=0) -> lvr_config:
+                scale=0.0, attn_splits=0, reservoir_size=0, seed=0, index_dtype=0, query_workgroups=0) -> lvr_config:
     return lvr_config(batch, n_q_heads, n_kv_heads, head_dim, kv_dtype, group_size, n_subspaces,
-                      buffer_size, grouping, enclosing, flags, capacity, scale, attn_splits, reservoir_size, seed, index_dtype, 0)
+                      buffer_size, grouping, enclosing, flags, capacity, scale, attn_splits, reservoir_size, seed, index_dtype, query_workgroups)
 
 
 def lvr_arena_bytes(cfg: lvr_config) -> int:
@@ -310,6 +313,17 @@ def lvr_export_reservoir(h, cfg: lvr_config):
 
 def lvr_publish(h, stream=None) -> None:
     _check(lib().lvr_publish(h, _stream(stream)), "lvr_publish")
+
+
+def lvr_set_bound_test(h, enabled: bool) -> None:
+    _check(lib().lvr_set_bound_test(h, 1 if enabled else 0), "lvr_set_bound_test")
+
+
+def lvr_stream_read(src, sink, workgroups=0, stream=None) -> None:
+    """One read-only pass over the bytes of `src` (any contiguous device tensor); sink: int32 tensor of >= 1 element."""
+    t = src.tensor if type(src) is DeviceArg else src
+    _check(lib().lvr_stream_read(_dev(src, name="src"), t.numel() * t.element_size(), _dev(sink, torch.int32, "sink"),
+                                 int(workgroups), _stream(stream)), "lvr_stream_read")
 
 
 def lvr_length(h):

@@ -60,7 +60,7 @@ int check_config(const lvr_config *c) {
         return LVR_E_UNSUPPORTED;
     if (c->index_dtype != LVR_INDEX_AUTO && c->index_dtype != LVR_INDEX_SAME && c->index_dtype != LVR_INDEX_FP8)
         return LVR_E_INVALID;
-    if (c->reserved != 0) return LVR_E_INVALID;
+    if (c->query_workgroups < 0 || c->query_workgroups > (1 << 20)) return LVR_E_INVALID;
     if (c->flags & ~(uint32_t)(LVR_ATTEND_BUFFER_DENSE | LVR_SEPARATE_KERNELS | LVR_CONCURRENT_UPDATE | LVR_KV_IN_HOST_MEMORY))
         return LVR_E_INVALID;
     if (c->index_dtype == LVR_INDEX_FP8 && !fp8_centres_supported(c)) return LVR_E_UNSUPPORTED;
@@ -486,6 +486,7 @@ int enqueue_query(lvr_index *ix, const float *q, const float *tau, int32_t *out_
     }
     ix->last_buffer_rows = ix->n_total - ix->n_indexed;
     ix->last_indexed = ix->n_indexed;
+    ix->last_skipped = fused && ix->skip_bounds && !tau_s;
     return LVR_OK;
 }
 
@@ -689,7 +690,7 @@ int lvr_get_stats(lvr_index *ix, lvr_stats *out) {
     const int64_t row_bytes = (int64_t)LVR_D * (int64_t)ix->elt;
     out->n_keys = ix->n_total;
     out->n_indexed = ix->n_indexed;
-    out->groups_scored = (ix->last_indexed / r) * n_bh;
+    out->groups_scored = ix->last_skipped ? 0 : (ix->last_indexed / r) * n_bh;   // no bound was evaluated when the test was off
     out->update_pending = ix->pending;
     out->groups_surviving = surv;
     out->keys_scanned = surv * r + ix->last_buffer_rows * n_bh;
@@ -818,6 +819,13 @@ int lvr_profile_read(lvr_index *ix, lvr_profile *out) {
         out->launches[k] += 1;
     }
     ix->prof_used = 0;
+    return LVR_OK;
+}
+
+int lvr_set_bound_test(lvr_index *ix, int enabled) {
+    if (!ix) return LVR_E_INVALID;
+    if (!enabled && (ix->cfg.kv_dtype != LVR_BF16 || (ix->cfg.flags & LVR_SEPARATE_KERNELS))) return LVR_E_UNSUPPORTED;
+    ix->skip_bounds = enabled ? 0 : 1;
     return LVR_OK;
 }
 

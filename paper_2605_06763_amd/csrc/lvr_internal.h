@@ -56,11 +56,13 @@ struct lvr_index {
     int seg_groups;        // groups per segment used by the last bound test
     int n_segs;            // segments per (sequence, KV head) filled by the last bound test (0: none)
     int counters_dirty;    // a query was started but its counts were never published (a launch failed)
+    int skip_bounds;       // lvr_set_bound_test(ix, 0): queries run the exact filter alone over every indexed key
     float *scores;         // [batch][H_q][cap_rows] raw scores of the keys the fused query emitted, or NULL
     float *part_ml;        // [batch][H_q][Pmax][2]
     float *part_o;         // [batch][H_q][Pmax][d]
     int64_t last_buffer_rows; // buffer rows scanned by the last query (host copy for stats)
     int64_t last_indexed;     // indexed rows the last query saw
+    int last_skipped;         // the last query ran with the bound test off
     // concurrent update (LVR_CONCURRENT_UPDATE): a full buffer is grouped on `side` while the
     // caller's stream keeps answering queries that still see those keys as buffer keys
     hipStream_t side;

@@ -15,8 +15,6 @@
 // once per segment instead of twice, and removes one kernel tail from the step.
 // The per-head counters must be zero when the kernel starts; the kernels that publish the
 // counts (publish_counts_kernel, combine_kernel) clear them for the next query.
-#include <stdlib.h>
-
 #include <type_traits>
 
 #include "emitter.h"
@@ -41,6 +39,7 @@ struct FusedArgs {
     lvr_emit_target emit;
     int64_t n_groups, max_groups, max_segs, cap_rows, n_indexed, n_total;
     int log2r, n_q_heads, n_kv_heads, G, buffer_dense, n_segs, tiles_per_wave;
+    int skip_bounds;         // 1: no bound test, every group of the segment goes to the exact check
 };
 
 // UA = centre tiles per phase-A trip; ENC = 1: boxes instead of balls; Q1 = 1: per-block thresholds (S <= 4);
@@ -164,7 +163,7 @@ query_fused_kernel(const FusedArgs a) {
             }
         }
     };
-    const bool phaseA = !buffer_wg && tile0 < n_tiles && a.n_groups > 0;   // wave-uniform
+    const bool phaseA = !buffer_wg && !a.skip_bounds && tile0 < n_tiles && a.n_groups > 0;   // wave-uniform
     if (phaseA) issueA(t0, 0);
     // the thresholds too are asked for before the prologue's barrier; they are needed last
     float tau_raw[HB];
@@ -248,7 +247,19 @@ query_fused_kernel(const FusedArgs a) {
 
     int64_t rows;          // key rows phase B has to check
     int64_t buf_row0 = 0;
-    if (!buffer_wg) {
+    const bool direct = buffer_wg || a.skip_bounds;   // phase B walks a run of consecutive rows, not a survivor list
+    if (!buffer_wg && a.skip_bounds) {
+        // the exact filter alone: the segment's groups all count as survivors
+        const int64_t seg_groups = (int64_t)a.tiles_per_wave * 64;
+        const int64_t g0 = (int64_t)blockIdx.x * seg_groups;
+        int64_t total = a.n_groups - g0;
+        if (total > seg_groups) total = seg_groups;
+        if (total < 0) total = 0;
+        if (threadIdx.x == 0) a.seg_count[(int64_t)bh * a.max_segs + blockIdx.x] = (int32_t)total;
+        rows = total << a.log2r;
+        buf_row0 = g0 << a.log2r;
+        __syncthreads();   // no wave still reads the operand staging area that the score queues reuse
+    } else if (!buffer_wg) {
         // ---------------- phase A: bound test over this segment's centres ----------------
         float qn[HB][S];
 #pragma unroll
@@ -533,8 +544,8 @@ query_fused_kernel(const FusedArgs a) {
         const int64_t left = rows - t * 16;
         nvalid[u] = k >= m ? 0 : (left < 16 ? (int)left : 16);
         if (rowidx >= rows) rowidx = 0;
-        slot[u] = buffer_wg ? (int)(buf_row0 + rowidx)
-                            : (int)(((int64_t)s_list[rowidx >> a.log2r] << a.log2r) + (rowidx & rmask));
+        slot[u] = direct ? (int)(buf_row0 + rowidx)
+                         : (int)(((int64_t)s_list[rowidx >> a.log2r] << a.log2r) + (rowidx & rmask));
         lvr_load_a_frags(Kb, slot[u], av[u]);
     };
     auto check = [&](auto u_c) {
@@ -641,13 +652,10 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
     a.n_kv_heads = ix->cfg.n_kv_heads;
     a.G = ix->G;
     a.buffer_dense = (ix->cfg.flags & LVR_ATTEND_BUFFER_DENSE) ? 1 : 0;
+    a.skip_bounds = (ix->skip_bounds && !tau_s) ? 1 : 0;
     const int n_bh = lvr_n_bh(ix);
     // segment = 4 waves x tiles_per_wave tiles x 16 groups; aim at a fixed number of workgroups per launch
-    static const int64_t target_wgs = [] {
-        const char *e = getenv("LVR_SEG_TARGET_WGS");
-        const long v = e ? atol(e) : 0;
-        return (int64_t)(v > 0 ? v : 1024);
-    }();
+    const int64_t target_wgs = ix->cfg.query_workgroups > 0 ? ix->cfg.query_workgroups : 1024;
     const int64_t want = a.n_groups * n_bh / target_wgs;
     int tpw = 1;
     while (tpw < 16 && (int64_t)tpw * 64 < want) tpw *= 2;

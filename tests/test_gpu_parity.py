@@ -321,6 +321,55 @@ def test_pruning_happens_on_clustered_keys(G, oracle, separate):
         assert st["keys_scanned"] == st["groups_surviving"] * 4
 
 
+@pytest.mark.parametrize("n,r,grouping", [(8192, 4, "contiguous"), (2051, 4, "contiguous"), (1000, 1, "contiguous"),
+                                          (1500, 8, "tree"), (40, 16, "contiguous")])
+def test_bound_test_switched_off(G, oracle, n, r, grouping):
+    """lvr_set_bound_test(0): the exact filter alone.  Same sets and attention as with the bound
+    test on; no group is scored, every held key gets the exact dot product; switching the test
+    back on restores the pruning.  Also across an append that stays in the buffer."""
+    import paper_2605_06763_amd as L
+    g = np.random.default_rng(5)
+    hkv, hq = 2, 8
+    base = np.repeat(g.standard_normal((1, hkv, (n + 63) // 64, 128)).astype(np.float32) * 3.0, 64, axis=2)[:, :, :n]
+    K = W.round_to_bf16(base + 0.05 * g.standard_normal((1, hkv, n, 128)).astype(np.float32))
+    V = W.round_to_bf16(g.standard_normal((1, hkv, n, 128)).astype(np.float32))
+    q = W.make_queries(2, n_q_heads=hq)
+    with G.Index(K, V, "bf16", hq, group_size=r, capacity=n + 8,
+                 grouping=L.LVR_GROUP_TREE if grouping == "tree" else L.LVR_GROUP_CONTIGUOUS) as ix:
+        tau = G.oracle_taus(oracle, ix, q, frac=0.02)
+        idx, cnt, out = ix.query(q, tau, fused=True)
+        G.check_step(oracle, ix, q, tau, idx, cnt, out, tag="bounds on")
+        on = ix.stats()
+        L.lvr_set_bound_test(ix.h, False)
+        for fused in (True, False):
+            idx2, cnt2, out2 = ix.query(q, tau, fused=fused)
+            G.check_step(oracle, ix, q, tau, idx2, cnt2, out2, tag=f"bounds off fused={fused}")
+            off = ix.stats()
+            assert off["groups_scored"] == 0 and off["bytes_index"] == 0
+            assert off["keys_scanned"] == hkv * n, (off, n)
+            assert off["keys_emitted"] == on["keys_emitted"]
+            for h in range(hq):
+                assert set(idx[0, h, :cnt[0, h]].tolist()) == set(idx2[0, h, :cnt2[0, h]].tolist())
+        ix.append(K[:, :, :3].copy(), V[:, :, :3].copy())
+        tau = G.oracle_taus(oracle, ix, q, frac=0.02)
+        idx3, cnt3, out3 = ix.query(q, tau, fused=True)
+        G.check_step(oracle, ix, q, tau, idx3, cnt3, out3, tag="bounds off, after append")
+        assert ix.stats()["keys_scanned"] == hkv * (n + 3)
+        L.lvr_set_bound_test(ix.h, True)
+        idx4, cnt4, out4 = ix.query(q, tau, fused=True)
+        G.check_step(oracle, ix, q, tau, idx4, cnt4, out4, tag="bounds on again")
+        again = ix.stats()
+        assert again["groups_scored"] == on["groups_scored"]
+        if n >= 1000 and r > 1:
+            assert again["groups_surviving"] < 0.5 * again["groups_scored"]
+    # the two-launch form and fp32 caches have no such switch
+    with G.Index(K[:, :, :64], V[:, :, :64], "bf16", hq, flags=L.LVR_SEPARATE_KERNELS) as ix:
+        with pytest.raises(L.LouverError) as e:
+            L.lvr_set_bound_test(ix.h, False)
+        assert e.value.code == L.LVR_E_UNSUPPORTED
+        L.lvr_set_bound_test(ix.h, True)
+
+
 # ------------------------------------------------------------------ append
 @pytest.mark.parametrize("flags", [0, 1, 2, 3])
 def test_append_matches_oracle_on_grown_cache(G, oracle, flags):

@@ -61,6 +61,15 @@ def round_to_bf16(x: np.ndarray) -> np.ndarray:
     return bf16_bits_to_f32(f32_to_bf16_bits(x)).reshape(np.shape(x))
 
 
+def _bits_of_exact(x: np.ndarray) -> np.ndarray:
+    """bf16 bit patterns of an fp32 array whose values are already bf16-representable: the upper
+    halves of the words (checked: the lower halves must be zero)."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    if np.bitwise_and(u, np.uint32(0xFFFF)).any():      # not exact after all: round
+        return f32_to_bf16_bits(x).reshape(x.shape)
+    return (u >> np.uint32(16)).astype(np.uint16).reshape(x.shape)
+
+
 # --------------------------------------------------------------------------- caches
 @dataclass
 class KVCache:
@@ -77,11 +86,11 @@ class KVCache:
 
     def K_bits(self) -> np.ndarray:
         assert self.dtype == "bf16"
-        return f32_to_bf16_bits(self.K).reshape(self.K.shape)
+        return _bits_of_exact(self.K)
 
     def V_bits(self) -> np.ndarray:
         assert self.dtype == "bf16"
-        return f32_to_bf16_bits(self.V).reshape(self.V.shape)
+        return _bits_of_exact(self.V)
 
 
 def _channel_scales(config_id: int, seq: int, n_kv_heads: int, d: int) -> np.ndarray:
@@ -116,13 +125,20 @@ def make_cache(config_id: int, *, n: int | None = None, batch: int | None = None
     K = np.empty((batch, hkv, n, d), dtype=np.float32)
     V = np.empty((batch, hkv, n, d), dtype=np.float32)
     scales = np.empty((batch, hkv, d), dtype=np.float32) if c["dist"] == "channel" else None
-    for b in range(batch):
+    def one(b):
         sc = None
         if scales is not None:
             sc = _channel_scales(config_id, b, hkv, d)
             scales[b] = sc
         K[b] = _draw_rows(config_id, STREAM_K, b, (hkv, n, d), c["dist"], sc, c["dtype"])
         V[b] = _draw_rows(config_id, STREAM_V, b, (hkv, n, d), "iid", None, c["dtype"])
+    # every sequence has streams of its own, so the sequences can be drawn side by side
+    if batch > 1:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=min(batch, 8)) as pool:
+            list(pool.map(one, range(batch)))
+    else:
+        one(0)
     return KVCache(K=K, V=V, dtype=c["dtype"], channel_scale=scales,
                    meta=dict(config=config_id, name=c["name"]))
 
