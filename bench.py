@@ -138,7 +138,8 @@ def measure(cid, args, *, group_size, steps, warmup, full, cpu_seconds, legs=Tru
         return L.make_config(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, kv_dtype=L.LVR_BF16,
                              group_size=r, n_subspaces=args.subspaces, buffer_size=256, capacity=capacity,
                              enclosing=L.LVR_ENCLOSE_AABB if args.enclosing == "aabb" else L.LVR_ENCLOSE_BALL,
-                             grouping=L.LVR_GROUP_TREE if args.grouping == "tree" else L.LVR_GROUP_CONTIGUOUS,
+                             grouping={"contiguous": L.LVR_GROUP_CONTIGUOUS, "tree": L.LVR_GROUP_TREE,
+                                       "subspace": L.LVR_GROUP_SUBSPACE_TREE}[args.grouping],
                              attn_splits=args.attn_splits, query_workgroups=args.query_workgroups,
                              index_dtype={"auto": L.LVR_INDEX_AUTO, "bf16": L.LVR_INDEX_SAME, "fp8": L.LVR_INDEX_FP8}[args.centres],
                              flags=(L.LVR_CONCURRENT_UPDATE if args.concurrent_update else 0)
@@ -275,7 +276,7 @@ def measure(cid, args, *, group_size, steps, warmup, full, cpu_seconds, legs=Tru
 
     # ---- the exact filter alone on the same arena: no bound test, every held key scored ----
     exact_only = None
-    if legs and not args.separate:
+    if legs and not args.separate and args.grouping != "subspace":
         L.lvr_set_bound_test(h, False)
         if not appending:
             timed(one_step, max(W_steps // 2, 4), 0)
@@ -304,12 +305,14 @@ def measure(cid, args, *, group_size, steps, warmup, full, cpu_seconds, legs=Tru
     #   +  keys_scanned * d*2 bytes of key rows
     n_bh = B * Hkv
     filt = kern.get("filter", dict(avg_us=float("nan")))
-    if args.separate and "prune" in kern:
+    two_launches = args.separate or args.grouping == "subspace"
+    if two_launches and "prune" in kern:
         filt = dict(avg_us=filt["avg_us"] + kern["prune"]["avg_us"])
     query_bytes = st["bytes_index"] + st["bytes_keys"]
     achieved = query_bytes / (filt["avg_us"] * 1e-6) / 1e9
     step_bytes = st["bytes_index"] + st["bytes_keys"] + st["bytes_attention"]
-    kernel_name = "prune_mfma_kernel+filter_mfma_kernel" if args.separate else "query_fused_kernel"
+    kernel_name = ("subspace_bounds_kernel+label_filter_kernel" if args.grouping == "subspace"
+                   else "prune_mfma_kernel+filter_mfma_kernel" if args.separate else "query_fused_kernel")
     roofline = dict(bound="hbm", kernel=kernel_name, achieved=round(achieved, 1), peak=HBM_PEAK_GBS,
                     unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None, traffic_source=None,
                     bytes_per_launch=int(query_bytes), avg_launch_us=round(filt["avg_us"], 2))
@@ -463,7 +466,8 @@ def main():
                     help="r; 1 = every key its own group (centre = the key in 8 bits, radius = its rounding error)")
     ap.add_argument("--subspaces", type=int, default=4)
     ap.add_argument("--enclosing", choices=["ball", "aabb"], default="ball")
-    ap.add_argument("--grouping", choices=["contiguous", "tree"], default="contiguous")
+    ap.add_argument("--grouping", choices=["contiguous", "tree", "subspace"], default="contiguous",
+                    help="'subspace': one tree grouping per subspace with per-key labels (the paper's own layout)")
     ap.add_argument("--centres", choices=["auto", "bf16", "fp8"], default="auto",
                     help="storage of the centres: the cache's bf16, or 8-bit e4m3 codes (half the index read); "
                          "auto = the library's default (8-bit where supported)")

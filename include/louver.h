@@ -42,8 +42,16 @@ enum lvr_dtype { LVR_BF16 = 0, LVR_F32 = 1 };
  * the query result does not depend on the choice, only the pruning power does).
  *   CONTIGUOUS: r consecutive token positions form a group (the appendix's best performer).
  *   TREE:       recursive median split on the coordinate axis of largest variance (Alg. 2),
- *               one tree over the full key shared by all subspaces; rows are stored regrouped. */
-enum lvr_grouping { LVR_GROUP_CONTIGUOUS = 0, LVR_GROUP_TREE = 1 };
+ *               one tree over the full key shared by all subspaces; rows are stored regrouped.
+ *   SUBSPACE_TREE: the paper's own layout (Sec. 4.1, Alg. 1): Alg. 2 is run once per subspace on that
+ *               subspace's coordinates, so every subspace has a grouping of its own and a key carries one
+ *               16-bit label per subspace; rows stay in arrival order.  A key is a candidate iff the
+ *               bounds of its S groups add up to tau ("Query 2"'s bound, evaluated per key; a subset of
+ *               what Alg. 4's depth scan keeps).  bf16 caches, balls with centres in the cache's format,
+ *               at most four query heads per KV head, at most 65536 groups per (sequence, KV head),
+ *               fused launch form, single-stream update, K and V in device memory; lvr_query1,
+ *               lvr_subspace_thresholds and lvr_set_bound_test are not available (LVR_E_UNSUPPORTED). */
+enum lvr_grouping { LVR_GROUP_CONTIGUOUS = 0, LVR_GROUP_TREE = 1, LVR_GROUP_SUBSPACE_TREE = 2 };
 
 /* Shape that encloses a group (appendix "Ablation on Index Design", Def. 1).
  *   BALL: centre + one radius per coordinate block (Sec. 4.1, Eq. (1)); bound of Eq. (2) per block, summed.
@@ -294,6 +302,11 @@ int lvr_get_stats(lvr_index *ix, lvr_stats *out_host);
  *   keys_host     [batch][n_kv_heads][n][head_dim] of kv_dtype, arena row order */
 int lvr_export_index(lvr_index *ix, void *centres_host, float *radii_host, int32_t *slot_pos_host,
                      void *keys_host);
+
+/* Synchronises the device and copies the per-subspace group labels of a LVR_GROUP_SUBSPACE_TREE index to
+ * host memory: labels_host [batch][n_kv_heads][n_subspaces][n_indexed] int32, the group of key j in
+ * subspace s (Sec. 4.1: "n assignment labels" per subspace).  LVR_E_STATE for other groupings. */
+int lvr_export_labels(lvr_index *ix, int32_t *labels_host);
 
 /* Per-kernel GPU time, for measurement (App. "Kernel Implementation Details" names the stages).
  * While enabled, every kernel launch of every call is bracketed by a pair of HIP events on the

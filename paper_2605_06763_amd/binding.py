@@ -14,7 +14,7 @@ import torch
 from .build import LIB_PATH
 
 LVR_BF16, LVR_F32 = 0, 1
-LVR_GROUP_CONTIGUOUS, LVR_GROUP_TREE = 0, 1
+LVR_GROUP_CONTIGUOUS, LVR_GROUP_TREE, LVR_GROUP_SUBSPACE_TREE = 0, 1, 2
 LVR_ENCLOSE_BALL, LVR_ENCLOSE_AABB = 0, 1
 LVR_ATTEND_BUFFER_DENSE = 1
 LVR_SEPARATE_KERNELS = 2
@@ -60,7 +60,7 @@ EXPORTS = [
     "lvr_export_index", "lvr_length", "lvr_strerror", "lvr_last_hip_error",
     "lvr_profile_enable", "lvr_profile_read", "lvr_threshold", "lvr_export_reservoir", "lvr_publish", "lvr_query1", "lvr_append_decode_step", "lvr_host_bytes",
     "lvr_subspace_thresholds", "lvr_sparse_attention_static",
-    "lvr_set_bound_test", "lvr_stream_read",
+    "lvr_set_bound_test", "lvr_stream_read", "lvr_export_labels",
 ]
 
 _lib = None
@@ -109,6 +109,7 @@ def lib():
     L.lvr_sparse_attention_static.argtypes = [vp, vp, i64, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_float,
                                               vp, vp, vp, i64, vp, vp]
     L.lvr_set_bound_test.argtypes = [vp, C.c_int]
+    L.lvr_export_labels.argtypes = [vp, vp]
     L.lvr_stream_read.argtypes = [vp, i64, vp, C.c_int32, vp]
     L.lvr_threshold.argtypes = [vp, vp, C.c_int, C.c_float, vp, vp]
     L.lvr_export_reservoir.argtypes = [vp, vp]
@@ -313,6 +314,15 @@ def lvr_export_reservoir(h, cfg: lvr_config):
 
 def lvr_publish(h, stream=None) -> None:
     _check(lib().lvr_publish(h, _stream(stream)), "lvr_publish")
+
+
+def lvr_export_labels(h, cfg: lvr_config):
+    """Per-subspace group labels [batch][n_kv_heads][S][n_indexed] int32 (LVR_GROUP_SUBSPACE_TREE only)."""
+    import numpy as np
+    _, ni = lvr_length(h)
+    lab = np.zeros((cfg.batch, cfg.n_kv_heads, cfg.n_subspaces, ni), dtype=np.int32)
+    _check(lib().lvr_export_labels(h, lab.ctypes.data_as(C.c_void_p)), "lvr_export_labels")
+    return lab
 
 
 def lvr_set_bound_test(h, enabled: bool) -> None:

@@ -27,6 +27,7 @@ inline bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 
 inline bool fp8_centres_supported(const lvr_config *c) {
     if (c->kv_dtype != LVR_BF16 || (c->flags & LVR_SEPARATE_KERNELS)) return false;
+    if (c->grouping == LVR_GROUP_SUBSPACE_TREE) return false;   // that layout keeps its centres in the cache's format
     return c->enclosing == LVR_ENCLOSE_AABB || c->n_subspaces <= 4;   // boxes do not look at n_subspaces
 }
 
@@ -44,7 +45,8 @@ int check_config(const lvr_config *c) {
     if (c->batch <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->capacity <= 0) return LVR_E_INVALID;
     if (c->n_q_heads % c->n_kv_heads != 0) return LVR_E_INVALID;
     if (c->kv_dtype != LVR_BF16 && c->kv_dtype != LVR_F32) return LVR_E_INVALID;
-    if (c->grouping != LVR_GROUP_CONTIGUOUS && c->grouping != LVR_GROUP_TREE) return LVR_E_INVALID;
+    if (c->grouping != LVR_GROUP_CONTIGUOUS && c->grouping != LVR_GROUP_TREE && c->grouping != LVR_GROUP_SUBSPACE_TREE)
+        return LVR_E_INVALID;
     if (c->scale < 0.f || c->attn_splits < -1) return LVR_E_INVALID;
     if (c->head_dim != LVR_D) return LVR_E_UNSUPPORTED;
     const int G = c->n_q_heads / c->n_kv_heads;
@@ -64,6 +66,12 @@ int check_config(const lvr_config *c) {
     if (c->flags & ~(uint32_t)(LVR_ATTEND_BUFFER_DENSE | LVR_SEPARATE_KERNELS | LVR_CONCURRENT_UPDATE | LVR_KV_IN_HOST_MEMORY))
         return LVR_E_INVALID;
     if (c->index_dtype == LVR_INDEX_FP8 && !fp8_centres_supported(c)) return LVR_E_UNSUPPORTED;
+    if (c->grouping == LVR_GROUP_SUBSPACE_TREE) {
+        // one grouping per coordinate block: labels are 16 bits, one launch form, one head block
+        if (c->kv_dtype != LVR_BF16 || c->enclosing != LVR_ENCLOSE_BALL || G > 4) return LVR_E_UNSUPPORTED;
+        if (c->flags & (LVR_SEPARATE_KERNELS | LVR_CONCURRENT_UPDATE | LVR_KV_IN_HOST_MEMORY)) return LVR_E_UNSUPPORTED;
+        if ((c->capacity + 63) / 64 * 64 / c->group_size > 65536) return LVR_E_UNSUPPORTED;
+    }
     return LVR_OK;
 }
 
@@ -74,6 +82,8 @@ struct Sizes {
     // tree grouping only
     int64_t tree_keys;
     size_t maps, tree_keybytes, tree_axis, tree_partial, tree_temp, chunk;
+    // one grouping per coordinate block only
+    size_t labels, f_table;
 };
 
 Sizes sizes_of(const lvr_config *c) {
@@ -102,18 +112,25 @@ Sizes sizes_of(const lvr_config *c) {
     s.total = s.scores + (kv_on_host ? 0 : 2 * s.kv) + s.centres + s.radii + s.list + s.counters + s.part_ml + s.part_o;
     s.tree_keys = 0;
     s.maps = s.tree_keybytes = s.tree_axis = s.tree_partial = s.tree_temp = s.chunk = 0;
-    if (c->grouping == LVR_GROUP_TREE) {
+    s.labels = s.f_table = 0;
+    const bool per_subspace = c->grouping == LVR_GROUP_SUBSPACE_TREE;
+    if (c->grouping == LVR_GROUP_TREE || per_subspace) {
         int64_t gp = 1;
         while (gp < s.max_groups) gp <<= 1;
         const int64_t np = gp * c->group_size;
         s.tree_keys = n_bh * np;
-        s.maps = al((size_t)n_bh * s.cap_rows * sizeof(int32_t));
+        s.maps = per_subspace ? 0 : al((size_t)n_bh * s.cap_rows * sizeof(int32_t));   // rows stay in arrival order there
         s.tree_keybytes = al((size_t)s.tree_keys * sizeof(uint64_t));
         s.tree_axis = al((size_t)n_bh * gp * sizeof(int32_t));
         s.tree_partial = al((size_t)n_bh * (np / 1024 + 1) * 258 * sizeof(double));
         s.tree_temp = 0;   // asked from the sort library at create time
-        s.chunk = al((size_t)n_bh * c->buffer_size * LVR_D * elt);
+        s.chunk = per_subspace ? 0 : al((size_t)n_bh * c->buffer_size * LVR_D * elt);
         s.total += 2 * s.maps + 2 * s.tree_keybytes + s.tree_axis + s.tree_partial + 2 * s.chunk;
+    }
+    if (per_subspace) {
+        s.labels = al((size_t)n_bh * s.cap_rows * c->n_subspaces * sizeof(uint16_t));
+        s.f_table = al((size_t)n_bh * s.max_groups * c->n_subspaces * 4 * sizeof(float));
+        s.total += s.labels + s.f_table;
     }
     return s;
 }
@@ -126,7 +143,8 @@ void free_all(lvr_index *ix) {
     }
     void *ptrs[] = {ix->K, ix->V, ix->centres, ix->radii, ix->slot_pos, ix->pos_slot,
                     ix->surv_list, ix->counters, ix->part_ml, ix->part_o, ix->tree_keys_a, ix->tree_keys_b,
-                    ix->tree_axis, ix->tree_partial, ix->tree_temp, ix->chunk_K, ix->chunk_V, ix->reservoir, ix->scores};
+                    ix->tree_axis, ix->tree_partial, ix->tree_temp, ix->chunk_K, ix->chunk_V, ix->reservoir, ix->scores,
+                    ix->labels, ix->f_table};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     if (ix->ev_fork) (void)hipEventDestroy(ix->ev_fork);
@@ -202,6 +220,25 @@ inline bool one_launch_attention(const lvr_index *ix) {
     return lvr_n_bhq(ix) >= 128 || ix->n_total <= 65536;
 }
 
+// One grouping per coordinate block: groups [g0, g0 + ng) are formed from arena rows g0*r .. (g0+ng)*r - 1
+// (a whole build, or one buffer chunk).  Per block: the tree order over the block's coordinates
+// (Alg. 2), then the block's centres, radii and the members' labels.
+int build_subspace_groups(lvr_index *ix, int64_t g0, int64_t ng, hipStream_t st) {
+    if (ng <= 0) return LVR_OK;
+    const int r = ix->cfg.group_size, S = ix->cfg.n_subspaces;
+    const int64_t row0 = g0 * r;
+    const char *src = static_cast<const char *>(ix->K) + row0 * LVR_D * (int64_t)ix->elt;
+    const int64_t as[3] = {(int64_t)ix->cfg.n_kv_heads * ix->cap_rows * LVR_D, ix->cap_rows * LVR_D, LVR_D};
+    for (int sb = 0; sb < S; ++sb) {
+        lvr_tree_perm perm;
+        hipError_t e = lvr_tree_order(ix, src, as, ng * r, st, &perm, sb * (LVR_D / S), (sb + 1) * (LVR_D / S));
+        if (e == hipErrorInvalidValue) return LVR_E_UNSUPPORTED;   // sort key wider than 64 bits
+        LVR_HIP(e);
+        LVR_HIP(lvr_launch_subspace_groups(ix, &perm, sb, row0, g0, ng, st));
+    }
+    return LVR_OK;
+}
+
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
 
@@ -263,7 +300,12 @@ int lvr_create(const lvr_config *cfg, lvr_index **out) {
         if (e != hipSuccess) break;
         if (a.bytes) e = hipMalloc(a.p, a.bytes);
     }
-    if (e == hipSuccess && cfg->grouping == LVR_GROUP_TREE) {
+    ix->per_subspace = cfg->grouping == LVR_GROUP_SUBSPACE_TREE;
+    if (e == hipSuccess && ix->per_subspace) {
+        e = hipMalloc((void **)&ix->labels, s.labels);
+        if (e == hipSuccess) e = hipMalloc((void **)&ix->f_table, s.f_table);
+    }
+    if (e == hipSuccess && (cfg->grouping == LVR_GROUP_TREE || ix->per_subspace)) {
         ix->tree_cap_keys = s.tree_keys;
         ix->tree_temp_bytes = lvr_tree_sort_temp_bytes(s.tree_keys);
         struct { void **p; size_t bytes; } tallocs[] = {
@@ -274,7 +316,7 @@ int lvr_create(const lvr_config *cfg, lvr_index **out) {
             {&ix->chunk_V, s.chunk}};
         for (auto &a : tallocs) {
             if (e != hipSuccess) break;
-            e = hipMalloc(a.p, a.bytes);
+            if (a.bytes) e = hipMalloc(a.p, a.bytes);
         }
     }
     if (e == hipSuccess && cfg->reservoir_size > 0) {
@@ -337,7 +379,17 @@ int lvr_build(lvr_index *ix, const void *K, const void *V, int64_t n, const int6
     ix->n_indexed = 0;
     const int r = ix->cfg.group_size;
     const int64_t n_groups = n / r;
-    if (n > 0 && ix->cfg.grouping == LVR_GROUP_TREE) {
+    if (n > 0 && ix->per_subspace) {
+        // rows stay in arrival order; every coordinate block gets the tree order of its own coordinates,
+        // and from it the block's balls and the keys' labels (Alg. 1: one BalancedPCATree call per subspace)
+        {
+            Timed t(ix, LVR_K_COPY, st);
+            LVR_HIP(lvr_launch_copy_kv(ix, K, ks, V, vs, 0, n, st));
+        }
+        Timed t(ix, LVR_K_BUILD, st);
+        int rc = build_subspace_groups(ix, 0, n_groups, st);
+        if (rc != LVR_OK) return rc;
+    } else if (n > 0 && ix->cfg.grouping == LVR_GROUP_TREE) {
         // rows of the n_groups*r leading keys go into the arena in tree order; the tail stays in arrival order
         Timed t(ix, LVR_K_COPY, st);
         const int64_t n_tree = n_groups * r;
@@ -356,7 +408,7 @@ int lvr_build(lvr_index *ix, const void *K, const void *V, int64_t n, const int6
         Timed t(ix, LVR_K_COPY, st);
         LVR_HIP(lvr_launch_copy_kv(ix, K, ks, V, vs, 0, n, st, n_groups * r));
     }
-    {
+    if (!ix->per_subspace) {
         Timed t(ix, LVR_K_BUILD, st);
         const bool fused_copy = n > 0 && ix->cfg.grouping != LVR_GROUP_TREE;
         LVR_HIP(lvr_launch_build_groups(ix, 0, n_groups, st, fused_copy ? K : nullptr, fused_copy ? ks : nullptr));
@@ -422,6 +474,14 @@ int lvr_append(lvr_index *ix, const void *k_new, const void *v_new, int64_t m, v
         LVR_HIP(hipEventRecord(ix->ev_done, ix->side));
         ix->pend_row0 = ix->n_indexed;
         ix->pending = 1;
+    } else if (full > 0 && ix->per_subspace) {
+        // every chunk of B buffered keys is grouped on its own, block by block (Sec. 4.3)
+        Timed t(ix, LVR_K_BUILD, st);
+        for (int64_t c = 0; c < full; ++c) {
+            int rc = build_subspace_groups(ix, ix->n_indexed / r, B / r, st);
+            if (rc != LVR_OK) return rc;
+            ix->n_indexed += B;
+        }
     } else if (full > 0) {
         const int64_t g0 = ix->n_indexed / r, g1 = g0 + full * (B / r);
         Timed t(ix, LVR_K_BUILD, st);
@@ -470,7 +530,14 @@ int enqueue_query(lvr_index *ix, const float *q, const float *tau, int32_t *out_
         LVR_HIP(lvr_launch_reset(ix, st));
     }
     ix->counters_dirty = 1;
-    if (fused) {
+    if (ix->per_subspace) {
+        if (ix->n_indexed > 0) {
+            Timed t(ix, LVR_K_PRUNE, st);
+            LVR_HIP(lvr_launch_subspace_bounds(ix, q, st));
+        }
+        Timed t(ix, LVR_K_FILTER, st);
+        LVR_HIP(lvr_launch_label_filter(ix, q, tau, out_idx, cap, st));
+    } else if (fused) {
         Timed t(ix, LVR_K_FILTER, st);
         LVR_HIP(lvr_launch_query_fused(ix, q, tau, tau_s, out_idx, cap, st, k_new, v_new, m_new));
         ix->n_total += m_new;
@@ -549,7 +616,8 @@ int lvr_query1(lvr_index *ix, const float *q, const float *tau_s, const float *t
     if (!ix->built) return LVR_E_STATE;
     if (!on_home_device(ix)) return LVR_E_STATE;
     if (!aligned4(q) || !aligned4(tau) || !aligned4(tau_s) || !aligned4(out_idx) || !aligned4(out_count)) return LVR_E_INVALID;
-    if (ix->cfg.kv_dtype != LVR_BF16 || (ix->cfg.flags & LVR_SEPARATE_KERNELS) || (ix->box && ix->cfg.n_subspaces > 4))
+    if (ix->cfg.kv_dtype != LVR_BF16 || (ix->cfg.flags & LVR_SEPARATE_KERNELS) || (ix->box && ix->cfg.n_subspaces > 4) ||
+        ix->per_subspace)
         return LVR_E_UNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(stream);
     int rc = enqueue_query(ix, q, tau, out_idx, cap, st, tau_s);
@@ -566,7 +634,8 @@ int lvr_subspace_thresholds(lvr_index *ix, const float *q, const float *tau, flo
     if (!ix || !q || !tau || !tau_s_out) return LVR_E_INVALID;
     if (!ix->built || !on_home_device(ix)) return LVR_E_STATE;
     if (!aligned4(q) || !aligned4(tau) || !aligned4(tau_s_out)) return LVR_E_INVALID;
-    if (ix->cfg.kv_dtype != LVR_BF16 || (ix->cfg.flags & LVR_SEPARATE_KERNELS) || (ix->box && ix->cfg.n_subspaces > 4))
+    if (ix->cfg.kv_dtype != LVR_BF16 || (ix->cfg.flags & LVR_SEPARATE_KERNELS) || (ix->box && ix->cfg.n_subspaces > 4) ||
+        ix->per_subspace)
         return LVR_E_UNSUPPORTED;
     LVR_HIP(lvr_launch_safe_tau_s(ix, q, tau, tau_s_out, static_cast<hipStream_t>(stream)));
     return LVR_OK;
@@ -618,7 +687,7 @@ int lvr_append_decode_step(lvr_index *ix, const void *k_new, const void *v_new, 
     // append needs nothing else (no chunk becomes full, no position maps, no reservoir, no update in
     // flight); otherwise the two calls run one after the other.
     const bool rides = m > 0 && m <= 64 && ix->cfg.kv_dtype == LVR_BF16 && !(ix->cfg.flags & LVR_SEPARATE_KERNELS) &&
-                       !ix->slot_pos && !ix->reservoir && !ix->pending && aligned16(k_new) && aligned16(v_new) &&
+                       !ix->slot_pos && !ix->reservoir && !ix->pending && !ix->per_subspace && aligned16(k_new) && aligned16(v_new) &&
                        ix->n_total + m - ix->n_indexed < ix->cfg.buffer_size;
     if (!rides) {
         int rc = lvr_append(ix, k_new, v_new, m, stream);
@@ -692,10 +761,12 @@ int lvr_get_stats(lvr_index *ix, lvr_stats *out) {
     out->n_indexed = ix->n_indexed;
     out->groups_scored = ix->last_skipped ? 0 : (ix->last_indexed / r) * n_bh;   // no bound was evaluated when the test was off
     out->update_pending = ix->pending;
-    out->groups_surviving = surv;
-    out->keys_scanned = surv * r + ix->last_buffer_rows * n_bh;
+    out->groups_surviving = surv;   // one grouping per block: the candidate KEYS (a key has S groups, none of which is "its" group)
+    out->keys_scanned = (ix->per_subspace ? surv : surv * r) + ix->last_buffer_rows * n_bh;
     out->keys_emitted = emitted;
     out->bytes_index = out->groups_scored * ((ix->cf8 ? (int64_t)LVR_D : row_bytes) * (ix->box ? 2 : 1) + (int64_t)ix->S_store * 4);
+    if (ix->per_subspace)   // plus the labels of every indexed key; the block-bound table is work space, not index
+        out->bytes_index += ix->last_indexed * n_bh * (int64_t)ix->cfg.n_subspaces * 2;
     out->bytes_keys = out->keys_scanned * row_bytes;
     out->bytes_attention = emitted * 2 * row_bytes;
     out->overflow = overflow;
@@ -783,6 +854,29 @@ int lvr_export_index(lvr_index *ix, void *centres, float *radii, int32_t *slot_p
     return LVR_OK;
 }
 
+int lvr_export_labels(lvr_index *ix, int32_t *labels_host) {
+    if (!ix || !labels_host) return LVR_E_INVALID;
+    if (!ix->built || !ix->per_subspace) return LVR_E_STATE;
+    LVR_HIP(hipDeviceSynchronize());
+    const int n_bh = lvr_n_bh(ix), S = ix->cfg.n_subspaces;
+    const int64_t ni = ix->n_indexed;
+    if (ni == 0) return LVR_OK;
+    uint16_t *tmp = static_cast<uint16_t *>(malloc((size_t)ni * S * sizeof(uint16_t)));
+    if (!tmp) return LVR_E_NOMEM;
+    for (int bh = 0; bh < n_bh; ++bh) {
+        hipError_t e = hipMemcpy(tmp, ix->labels + (size_t)bh * ix->cap_rows * S, (size_t)ni * S * sizeof(uint16_t),
+                                 hipMemcpyDeviceToHost);
+        if (e != hipSuccess) {
+            free(tmp);
+            return hip_fail(e);
+        }
+        for (int sb = 0; sb < S; ++sb)
+            for (int64_t j = 0; j < ni; ++j) labels_host[((size_t)bh * S + sb) * ni + j] = tmp[j * S + sb];
+    }
+    free(tmp);
+    return LVR_OK;
+}
+
 int lvr_profile_enable(lvr_index *ix, int max_launches) {
     if (!ix || max_launches < 0 || max_launches > (1 << 20)) return LVR_E_INVALID;
     LVR_HIP(hipDeviceSynchronize());
@@ -824,7 +918,8 @@ int lvr_profile_read(lvr_index *ix, lvr_profile *out) {
 
 int lvr_set_bound_test(lvr_index *ix, int enabled) {
     if (!ix) return LVR_E_INVALID;
-    if (!enabled && (ix->cfg.kv_dtype != LVR_BF16 || (ix->cfg.flags & LVR_SEPARATE_KERNELS))) return LVR_E_UNSUPPORTED;
+    if (!enabled && (ix->cfg.kv_dtype != LVR_BF16 || (ix->cfg.flags & LVR_SEPARATE_KERNELS) || ix->per_subspace))
+        return LVR_E_UNSUPPORTED;
     ix->skip_bounds = enabled ? 0 : 1;
     return LVR_OK;
 }

@@ -42,6 +42,11 @@ struct lvr_index {
     int32_t *slot_pos;     // [batch][H_kv][cap_rows] token position of arena row (TREE grouping), else NULL
     int32_t *pos_slot;     // inverse map, or NULL
     int32_t *reservoir;    // [batch][H_kv][R] token positions kept by reservoir sampling (-1 = unused), or NULL
+    // one grouping per coordinate block (LVR_GROUP_SUBSPACE_TREE): per key its group in every block, and the
+    // per-query table of block bounds that the labels point into
+    uint16_t *labels;      // [batch][H_kv][cap_rows][S]
+    float *f_table;        // [batch][H_kv][max_groups][S][4]
+    int per_subspace;      // 1: that layout
     // work space of the tree grouping (TREE grouping only)
     uint64_t *tree_keys_a, *tree_keys_b;   // [n_bh * padded entries] sort keys, ping-pong
     int32_t *tree_axis;                    // [n_bh * nodes] split axis per node of the current level
@@ -143,6 +148,12 @@ hipError_t lvr_launch_reservoir_reset(lvr_index *ix, hipStream_t st);
 hipError_t lvr_launch_reservoir_update(lvr_index *ix, int64_t pos0, int64_t count, hipStream_t st);
 hipError_t lvr_launch_safe_tau_s(lvr_index *ix, const float *q, const float *tau, float *tau_s, hipStream_t st);
 hipError_t lvr_launch_threshold(lvr_index *ix, const float *q, int mode, float param, float *tau_out, hipStream_t st);
+// one grouping per coordinate block (subspace_layout.hip)
+hipError_t lvr_launch_subspace_groups(lvr_index *ix, const struct lvr_tree_perm *perm, int s, int64_t row0, int64_t g_base,
+                                      int64_t n_new_groups, hipStream_t st);
+hipError_t lvr_launch_subspace_bounds(lvr_index *ix, const float *q, hipStream_t st);
+hipError_t lvr_launch_label_filter(lvr_index *ix, const float *q, const float *tau, int32_t *out_idx, int64_t cap,
+                                   hipStream_t st);
 // tree grouping (tree.hip)
 size_t lvr_tree_sort_temp_bytes(int64_t total_keys);
 // order of the rows after the tree grouping: sorted keys whose low pos_bits give the source row
@@ -151,8 +162,9 @@ struct lvr_tree_perm {
     int64_t np;
     int pos_bits;
 };
+// c_lo, c_hi: the split axis of every node is chosen among coordinates [c_lo, c_hi) only
 hipError_t lvr_tree_order(lvr_index *ix, const void *Ksrc, const int64_t ks[3], int64_t n_real, hipStream_t st,
-                          lvr_tree_perm *perm);
+                          lvr_tree_perm *perm, int c_lo = 0, int c_hi = LVR_D);
 hipError_t lvr_tree_gather(lvr_index *ix, const void *Ksrc, const int64_t ks[3], const void *Vsrc, const int64_t vs[3],
                            const lvr_tree_perm *perm, int64_t n_real, int64_t row0, hipStream_t st);
 hipError_t lvr_tree_group(lvr_index *ix, const void *Ksrc, const int64_t ks[3], const void *Vsrc, const int64_t vs[3],

@@ -58,7 +58,10 @@ __device__ __forceinline__ void lane_pair(const char *row, int lane, int elt, fl
 }
 
 // argmax over 128 channel variances held as (v0, v1) per lane; lowest channel wins ties
-__device__ __forceinline__ int wave_argmax(double v0, double v1, int lane) {
+// [c_lo, c_hi): the coordinates that may be chosen (a tree over one coordinate block looks at that block only)
+__device__ __forceinline__ int wave_argmax(double v0, double v1, int lane, int c_lo, int c_hi) {
+    if (2 * lane < c_lo || 2 * lane >= c_hi) v0 = -1.0;           // variances are >= 0
+    if (2 * lane + 1 < c_lo || 2 * lane + 1 >= c_hi) v1 = -1.0;
     double best = v0;
     int arg = 2 * lane;
     if (v1 > best) { best = v1; arg = 2 * lane + 1; }
@@ -75,7 +78,7 @@ __device__ __forceinline__ int wave_argmax(double v0, double v1, int lane) {
 // real key (the variance does not depend on the shift; the shift removes the cancellation).
 __global__ void __launch_bounds__(256)
 tree_stats_small_kernel(TreeSrc src, const uint64_t *__restrict__ keys, int32_t *__restrict__ axis, int64_t np,
-                        int64_t n_real, int64_t m, int pos_bits, int64_t n_nodes) {
+                        int64_t n_real, int64_t m, int pos_bits, int64_t n_nodes, int c_lo, int c_hi) {
     const int lane = threadIdx.x & 63;
     const int64_t node = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int bh = blockIdx.y;
@@ -96,7 +99,7 @@ tree_stats_small_kernel(TreeSrc src, const uint64_t *__restrict__ keys, int32_t 
     }
     const double inv = cnt > 0 ? 1.0 / (double)cnt : 0.;
     const double v0 = (q0 - s0 * s0 * inv) * inv, v1 = (q1 - s1 * s1 * inv) * inv;
-    const int arg = wave_argmax(v0, v1, lane);
+    const int arg = wave_argmax(v0, v1, lane, c_lo, c_hi);
     if (lane == 0) axis[(int64_t)bh * n_nodes + node] = arg;
 }
 
@@ -144,7 +147,7 @@ tree_stats_piece_kernel(TreeSrc src, const uint64_t *__restrict__ keys, double *
 
 __global__ void __launch_bounds__(128)
 tree_stats_merge_kernel(const double *__restrict__ partial, int32_t *__restrict__ axis, int64_t np, int64_t m,
-                        int64_t n_nodes) {
+                        int64_t n_nodes, int c_lo, int c_hi) {
     __shared__ double sv[128];
     __shared__ int sa[128];
     const int bh = blockIdx.y, t = threadIdx.x;
@@ -158,7 +161,7 @@ tree_stats_merge_kernel(const double *__restrict__ partial, int32_t *__restrict_
         cnt += pp[p * 258 + 256];
     }
     const double var = cnt > 0 ? (q - s * s / cnt) / cnt : 0.0;
-    sv[t] = var;
+    sv[t] = (t >= c_lo && t < c_hi) ? var : -1.0;   // coordinates outside the block are never chosen
     sa[t] = t;
     __syncthreads();
     for (int off = 64; off >= 1; off >>= 1) {
@@ -234,7 +237,7 @@ constexpr int TREE_WG_MAX = 1024;
 
 __global__ void __launch_bounds__(256)
 tree_small_kernel(TreeSrc src, uint64_t *__restrict__ keys_out, int np, int64_t n_real, int levels, int pos_bits,
-                  int coord_bits) {
+                  int coord_bits, int c_lo, int c_hi) {
     __shared__ uint64_t s_keys[TREE_WG_MAX];
     __shared__ int32_t s_axis[TREE_WG_MAX / 2];
     __shared__ double s_part[4][256];   // per run: 128 sums, 128 sums of squares
@@ -287,7 +290,7 @@ tree_small_kernel(TreeSrc src, uint64_t *__restrict__ keys_out, int np, int64_t 
                 if (runs_per_node == 1) {
                     const double inv = cnt > 0 ? 1.0 / (double)cnt : 0.;
                     const double v0 = (q0 - s0 * s0 * inv) * inv, v1 = (q1 - s1 * s1 * inv) * inv;
-                    const int arg = wave_argmax(v0, v1, lane);
+                    const int arg = wave_argmax(v0, v1, lane, c_lo, c_hi);
                     if (lane == 0) s_axis[node] = arg;
                 }
             }
@@ -304,7 +307,7 @@ tree_small_kernel(TreeSrc src, uint64_t *__restrict__ keys_out, int np, int64_t 
                     }
                     const double inv = cnt > 0 ? 1.0 / (double)cnt : 0.;
                     const double v0 = (q0 - s0 * s0 * inv) * inv, v1 = (q1 - s1 * s1 * inv) * inv;
-                    const int arg = wave_argmax(v0, v1, lane);
+                    const int arg = wave_argmax(v0, v1, lane, c_lo, c_hi);
                     if (lane == 0) s_axis[wave] = arg;
                 }
             }
@@ -374,7 +377,7 @@ size_t lvr_tree_sort_temp_bytes(int64_t total_keys) {
 // writes them, regrouped, to arena rows row0 .. row0+n_real-1 together with the position maps.
 // Returns hipErrorInvalidValue if the sort key would not fit in 64 bits.
 hipError_t lvr_tree_order(lvr_index *ix, const void *Ksrc, const int64_t ks[3], int64_t n_real, hipStream_t st,
-                          lvr_tree_perm *perm) {
+                          lvr_tree_perm *perm, int c_lo, int c_hi) {
     perm->keys = nullptr;
     if (n_real <= 0) return hipSuccess;
     const int r = ix->cfg.group_size;
@@ -395,7 +398,7 @@ hipError_t lvr_tree_order(lvr_index *ix, const void *Ksrc, const int64_t ks[3], 
     if (np <= TREE_WG_MAX && pos_bits + coord_bits + levels <= 64) {
         // small input (a buffer chunk): the whole tree in one launch
         hipLaunchKernelGGL(tree_small_kernel, dim3((unsigned)n_bh), dim3(256), 0, st, ksrc, cur, (int)np, n_real, levels,
-                           pos_bits, coord_bits);
+                           pos_bits, coord_bits, c_lo, c_hi);
         perm->keys = cur;
         perm->np = np;
         perm->pos_bits = pos_bits;
@@ -407,12 +410,12 @@ hipError_t lvr_tree_order(lvr_index *ix, const void *Ksrc, const int64_t ks[3], 
         const int64_t m = np >> L;                      // entries per node at this level (>= 2r)
         if (m <= PIECE) {
             hipLaunchKernelGGL(tree_stats_small_kernel, dim3((unsigned)((n_nodes + 3) / 4), (unsigned)n_bh), dim3(256), 0,
-                               st, ksrc, cur, ix->tree_axis, np, n_real, m, pos_bits, n_nodes);
+                               st, ksrc, cur, ix->tree_axis, np, n_real, m, pos_bits, n_nodes, c_lo, c_hi);
         } else {
             hipLaunchKernelGGL(tree_stats_piece_kernel, dim3((unsigned)(np / PIECE), (unsigned)n_bh), dim3(256), 0, st,
                                ksrc, cur, ix->tree_partial, np, n_real, m, pos_bits);
             hipLaunchKernelGGL(tree_stats_merge_kernel, dim3((unsigned)n_nodes, (unsigned)n_bh), dim3(128), 0, st,
-                               ix->tree_partial, ix->tree_axis, np, m, n_nodes);
+                               ix->tree_partial, ix->tree_axis, np, m, n_nodes, c_lo, c_hi);
         }
         hipLaunchKernelGGL(tree_keys_kernel, dim3((unsigned)((np + 255) / 256), (unsigned)n_bh), dim3(256), 0, st, ksrc,
                            cur, ix->tree_axis, np, n_real, m, pos_bits, coord_bits, n_nodes);

@@ -1,7 +1,9 @@
-"""The five workloads at their full sizes, in the launch configuration bench.py times
-(r = 4, S = 4, contiguous grouping, 8-bit centres, fused query kernel, default attention form), checked against
-the CPU oracle: every head of every sampled step by the band rule for the retrieved sets and
-against the oracle's attention on the same lists."""
+"""The five workloads at their full sizes, checked against the CPU oracle: every head of every
+sampled step by the band rule for the retrieved sets and against the oracle's attention on the
+same lists.  Three index settings each: the launch configuration bench.py times by default (r = 1:
+every key its own group, 8-bit centres, contiguous, fused query kernel, default attention form), the
+paper's printed r = 4 / S = 4 with one shared grouping, and the paper's own layout (one tree
+grouping per subspace, r = 4, S = 16, labels per key)."""
 import math
 
 import numpy as np
@@ -20,27 +22,38 @@ def G():
     return gpu_util
 
 
-def test_config2_llama_layer_32k(G, oracle):
+def _settings():
+    import paper_2605_06763_amd as L
+    return {"r1": dict(group_size=1), "r4": dict(group_size=4),
+            "per_subspace_r4_S16": dict(group_size=4, n_subspaces=16, grouping=L.LVR_GROUP_SUBSPACE_TREE)}
+
+
+SETTINGS = ["r1", "r4", "per_subspace_r4_S16"]
+
+
+@pytest.mark.parametrize("setting", SETTINGS)
+def test_config2_llama_layer_32k(G, oracle, setting):
     """32 query / 8 KV heads, d=128, 32768 keys, bf16, channel-scaled keys, tau at the 99th percentile."""
     cache = W.make_cache(2)
     q = W.make_queries(2)
-    with G.Index(cache.K, cache.V, "bf16", 32) as ix:
+    with G.Index(cache.K, cache.V, "bf16", 32, **_settings()[setting]) as ix:
         tau = G.oracle_taus(oracle, ix, q, frac=0.01)
         idx, cnt, out = ix.query(q, tau, cap=2048, fused=True)
         r = G.check_step(oracle, ix, q, tau, idx, cnt, out, tag="config2")
         st = ix.stats()
         assert st["keys_emitted"] == int(cnt.sum()) and 328 * 32 <= st["keys_emitted"] <= 330 * 32 + 64
-        G.say("config2", r, st)
+        G.say("config2", setting, r, st)
         ref = oracle.dense_attention(ix.K, ix.V, q, ix.sigma, 32)
         assert (np.abs(ix.dense(q) - ref).max(axis=-1) / np.abs(ref).max(axis=-1)).max() <= G.ATTN_TOL
 
 
-def test_config3_128k_drifting_query(G, oracle):
+@pytest.mark.parametrize("setting", SETTINGS)
+def test_config3_128k_drifting_query(G, oracle, setting):
     """131072 keys, 0.5 % qualify, query drifting over 256 steps; three of the steps are checked
     in full, and the retrieved sets must change from step to step."""
     cache = W.make_cache(3)
     qs = W.drift_queries(3, 256)
-    with G.Index(cache.K, cache.V, "bf16", 32) as ix:
+    with G.Index(cache.K, cache.V, "bf16", 32, **_settings()[setting]) as ix:
         prev = None
         for t in (0, 1, 255):
             tau = G.oracle_taus(oracle, ix, qs[t], k_count=656)
@@ -54,25 +67,27 @@ def test_config3_128k_drifting_query(G, oracle):
                 assert turnover > 0.05
             prev = sets
             G.say(f"config3 t={t}", r)
-        G.say("config3", ix.stats())
+        G.say("config3", setting, ix.stats())
 
 
-def test_config4_batch16(G, oracle):
+@pytest.mark.parametrize("setting", SETTINGS)
+def test_config4_batch16(G, oracle, setting):
     """16 independent 32k caches, one batched step, tau at the 98th percentile per (sequence, head)."""
     cache = W.make_cache(4)
     q = W.make_queries(4)
-    with G.Index(cache.K, cache.V, "bf16", 32) as ix:
+    with G.Index(cache.K, cache.V, "bf16", 32, **_settings()[setting]) as ix:
         tau = G.oracle_taus(oracle, ix, q, frac=0.02)
         idx, cnt, out = ix.query(q, tau, cap=2048, fused=True)
         r = G.check_step(oracle, ix, q, tau, idx, cnt, out, tag="config4")
         st = ix.stats()
         assert st["keys_emitted"] == int(cnt.sum())
-        G.say("config4", r, st)
+        G.say("config4", setting, r, st)
         # sequences are independent: swapping the queries of two sequences changes their results
         assert not np.array_equal(idx[0, 0, :16], idx[1, 0, :16])
 
 
-def test_config5_long_output_decode(G, oracle):
+@pytest.mark.parametrize("setting", SETTINGS)
+def test_config5_long_output_decode(G, oracle, setting):
     """Prompt of 16384 keys, then 4096 decode steps, each appending one key/value per KV head and
     issuing query + attention with tau = (max score so far) - 8 per head.  Every step runs on the
     GPU; the oracle checks a sample of steps in full, including the ones around buffer flushes."""
@@ -85,7 +100,8 @@ def test_config5_long_output_decode(G, oracle):
     V_all = np.concatenate([cache.V, v_new.transpose(1, 2, 0, 3)], axis=2)
     Kd_all, Vd_all = G.to_device(K_all, "bf16"), G.to_device(V_all, "bf16")
     q_dev = torch.from_numpy(qs).cuda()
-    cfg = L.make_config(batch=1, n_q_heads=hq, n_kv_heads=hkv, capacity=n0 + steps, buffer_size=B)
+    cfg = L.make_config(batch=1, n_q_heads=hq, n_kv_heads=hkv, capacity=n0 + steps, buffer_size=B, **_settings()[setting])
+    r_grp = cfg.group_size
     h = L.lvr_create(cfg)
     sigma = 1.0 / math.sqrt(d)
     cap = 8192
@@ -106,7 +122,7 @@ def test_config5_long_output_decode(G, oracle):
             if t in check_at:
                 torch.cuda.synchronize()
                 n, n_indexed = L.lvr_length(h)
-                assert n == n_t and n_indexed % 4 == 0 and 0 <= n - n_indexed < B
+                assert n == n_t and n_indexed % r_grp == 0 and 0 <= n - n_indexed < B
                 assert n_indexed == n0 + ((t + 1) // B) * B
                 i_np, c_np, o_np, tau_np = idx.cpu().numpy(), cnt.cpu().numpy(), out.cpu().numpy(), tau.cpu().numpy()
                 for hh in range(hq):
@@ -118,7 +134,7 @@ def test_config5_long_output_decode(G, oracle):
                     assert r["size"] >= 1          # the maximum itself always qualifies
                 G.say(f"config5 t={t}: n={n_t} indexed={n_indexed} mean set size {c_np.mean():.1f}")
         st = L.lvr_get_stats(h)
-        G.say("config5", dict(checked_steps=len(check_at), retrieved=total_retrieved, attn_err=worst), st)
+        G.say("config5", setting, dict(checked_steps=len(check_at), retrieved=total_retrieved, attn_err=worst), st)
     finally:
         L.lvr_destroy(h)
 
