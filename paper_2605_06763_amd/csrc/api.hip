@@ -101,7 +101,7 @@ Sizes sizes_of(const lvr_config *c) {
     const bool box = c->enclosing == LVR_ENCLOSE_AABB;
     const size_t c_elt = fp8_centres(c) ? 1 : elt;
     s.centres = al((size_t)n_bh * s.max_groups * LVR_D * c_elt * (box ? 2 : 1));
-    s.radii = al((size_t)n_bh * s.max_groups * (box ? 1 : (fp8_centres(c) ? 4 : c->n_subspaces)) * sizeof(float));   // boxes: one allowance
+    s.radii = al((size_t)n_bh * s.max_groups * (box ? 1 : (fp8_centres(c) ? 2 : c->n_subspaces)) * sizeof(float));   // boxes: one allowance; 8-bit balls: four bf16
     s.list = al((size_t)n_bh * s.max_groups * sizeof(int32_t));
     s.counters = al(lvr_counter_ints((int)n_bh, (int)n_bhq, s.max_groups) * sizeof(int32_t));
     s.part_ml = al((size_t)n_bhq * s.Pmax * 2 * sizeof(float));
@@ -275,7 +275,7 @@ int lvr_create(const lvr_config *cfg, lvr_index **out) {
     ix->G = cfg->n_q_heads / cfg->n_kv_heads;
     ix->box = cfg->enclosing == LVR_ENCLOSE_AABB;
     ix->cf8 = fp8_centres(cfg);
-    ix->S_store = ix->box ? 1 : (ix->cf8 ? 4 : cfg->n_subspaces);   // 8-bit centres: 16 bytes of pre-split radii per group
+    ix->S_store = ix->box ? 1 : (ix->cf8 ? 2 : cfg->n_subspaces);   // 8-bit centres: 8 bytes of radii per group (four bf16)
     ix->cap_rows = s.cap_rows;
     ix->max_groups = s.max_groups;
     ix->P = s.P;
@@ -569,7 +569,11 @@ int decode_step_impl(lvr_index *ix, const float *q, const float *tau, float *out
     // partials-plus-combine form gains; so the scores are used by the one-launch form and whenever
     // K and V sit behind the host link.
     const bool fused = ix->cfg.kv_dtype == LVR_BF16 && !(ix->cfg.flags & LVR_SEPARATE_KERNELS);
-    const bool use_scores = fused && (one_launch_attention(ix) || (ix->cfg.flags & LVR_KV_IN_HOST_MEMORY));
+    // With one key per group the query launch reads few key rows itself (the survivors of the 8-bit
+    // test), so it has nothing to gain from rows the attention touched: the scores are used there too
+    // (measured at 128k keys: attention 0.9 us shorter, the query launch unchanged).
+    const bool use_scores = fused && (one_launch_attention(ix) || (ix->cfg.flags & LVR_KV_IN_HOST_MEMORY) ||
+                                      ix->cfg.group_size == 1);
     const float *carried = use_scores ? ix->scores : nullptr;
     if (one_launch_attention(ix)) {   // reads the set sizes from the internal counters and hands them to the caller
         Timed t(ix, LVR_K_ATTN_PARTIAL, st);
@@ -817,22 +821,21 @@ int lvr_export_index(lvr_index *ix, void *centres, float *radii, int32_t *slot_p
                               static_cast<char *>(ix->centres) + (size_t)bh * ix->max_groups * crow,
                               (size_t)ng * crow, hipMemcpyDeviceToHost));
         if (radii && ng > 0 && ix->cf8 && !ix->box) {
-            // pre-split radii (eight bf16 per group, slot k = part*S' + s) -> one float per subspace
+            // four bf16 per group (slot s = rho_s) -> one float per subspace
             const int Ss = ix->cfg.n_subspaces;
-            uint16_t *blk = static_cast<uint16_t *>(malloc((size_t)ng * 16));
+            uint16_t *blk = static_cast<uint16_t *>(malloc((size_t)ng * 8));
             if (!blk) return LVR_E_NOMEM;
-            hipError_t e = hipMemcpy(blk, ix->radii + (size_t)bh * ix->max_groups * 4, (size_t)ng * 16, hipMemcpyDeviceToHost);
+            hipError_t e = hipMemcpy(blk, ix->radii + (size_t)bh * ix->max_groups * 2, (size_t)ng * 8, hipMemcpyDeviceToHost);
             if (e != hipSuccess) {
                 free(blk);
                 return hip_fail(e);
             }
             for (int64_t g = 0; g < ng; ++g)
                 for (int sidx = 0; sidx < Ss; ++sidx) {
-                    const uint32_t hi = (uint32_t)blk[g * 8 + sidx] << 16, mid = (uint32_t)blk[g * 8 + Ss + sidx] << 16;
-                    float fh, fm;
+                    const uint32_t hi = (uint32_t)blk[g * 4 + sidx] << 16;
+                    float fh;
                     memcpy(&fh, &hi, 4);
-                    memcpy(&fm, &mid, 4);
-                    radii[((size_t)bh * ng + g) * Ss + sidx] = fh + fm;
+                    radii[((size_t)bh * ng + g) * Ss + sidx] = fh;
                 }
             free(blk);
         } else if (radii && ng > 0)

@@ -211,29 +211,24 @@ build_groups_kernel(void *__restrict__ K, void *__restrict__ centres, float *__r
     float rho = sqrtf(max_d2) * (1.0f + 0x1p-12f) + sqrtf(cn2) * 0x1p-12f;
     rho = __uint_as_float(__float_as_uint(rho) + 1u);    // one ulp up (rho >= 0)
     if constexpr (CF8) {
-        // The radii go out in the form the query's radius step reads them: eight bf16 per group,
-        // slot k = part*S + s for k < 2S, part 0 = the top eight bits of rho_s, part 1 = the rest
-        // rounded UP to eight bits (so part 0 + part 1 >= rho_s, looser by at most 2^-16 rho_s).
-        uint32_t slot[8];
+        // The radii go out in the form the query's radius step reads them: four bf16 per group (8 bytes),
+        // slot s = rho_s rounded UP to bf16's eight significant bits (looser by at most 2^-7 rho_s, never
+        // tighter), slots S..3 zero.
+        uint32_t slot[4];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) slot[k] = 0;
+        for (int k = 0; k < 4; ++k) slot[k] = 0;
         const int lane = threadIdx.x & 63, base = lane & ~15;
         for (int sidx = 0; sidx < S; ++sidx) {   // S <= 4
             const float rs = __shfl(rho, base + sidx * lanes_per_sub, 64);
-            const uint32_t hi = __float_as_uint(rs) & 0xffff0000u;
-            const float rest = rs - __uint_as_float(hi);
-            uint32_t mid = __float_as_uint(rest);
-            if (mid & 0xffffu) mid = (mid & 0xffff0000u) + 0x10000u;
+            uint32_t up = __float_as_uint(rs);
+            if (up & 0xffffu) up = (up & 0xffff0000u) + 0x10000u;
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                if (k == sidx) slot[k] = hi >> 16;
-                if (k == S + sidx) slot[k] = mid >> 16;
-            }
+            for (int k = 0; k < 4; ++k)
+                if (k == sidx) slot[k] = up >> 16;
         }
         if (valid && li == 0)
-            reinterpret_cast<uint4 *>(radii)[(int64_t)bh * max_groups + g] =
-                make_uint4(slot[0] | (slot[1] << 16), slot[2] | (slot[3] << 16), slot[4] | (slot[5] << 16),
-                           slot[6] | (slot[7] << 16));
+            reinterpret_cast<uint2 *>(radii)[(int64_t)bh * max_groups + g] =
+                make_uint2(slot[0] | (slot[1] << 16), slot[2] | (slot[3] << 16));
     } else {
         if (valid && (li % lanes_per_sub) == 0) radii[((int64_t)bh * max_groups + g) * S + li / lanes_per_sub] = rho;
     }

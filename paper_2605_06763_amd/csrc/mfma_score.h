@@ -350,7 +350,7 @@ __device__ __forceinline__ lvr_bf16x8 lvr_radius_a_frag(const float (&rho)[S]) {
 }
 
 // qn_group: [heads][16] floats, |pi_s q_h| for s < S (already rounded up); head block hb.
-// NP = bf16 terms per radius on the A side (3: split on the fly; 2: stored pre-split).
+// NP = bf16 terms per radius on the A side (3: split on the fly; 1: stored as one bf16 rounded up).
 template <int S, int NP = 3>
 __device__ __forceinline__ lvr_bf16x8 lvr_radius_b_frag(const float (*qn_group)[16], int G, int hb) {
     const int lane = threadIdx.x & 63;
@@ -375,15 +375,15 @@ __device__ __forceinline__ lvr_bf16x8 lvr_radius_b_frag(const float (*qn_group)[
     return __builtin_bit_cast(lvr_bf16x8, packed);
 }
 
-// Radii stored pre-split (eight bf16 per group, slot k = part*S + s, two parts): the block IS the
-// operand piece of the lanes with kq = 0; the other lanes contribute zeros.
-__device__ __forceinline__ lvr_bf16x8 lvr_radius_a_stored(const uint4 &block) {
+// Radii stored as four bf16 per group (slot s = rho_s rounded up, one part): the block IS the first
+// half of the operand piece of the lanes with kq = 0 (k-slots 0..3); everything else is zero.
+__device__ __forceinline__ lvr_bf16x8 lvr_radius_a_stored(const uint2 &block) {
     const bool first = ((threadIdx.x & 63) >> 4) == 0;
     uint4 r;
     r.x = first ? block.x : 0u;
     r.y = first ? block.y : 0u;
-    r.z = first ? block.z : 0u;
-    r.w = first ? block.w : 0u;
+    r.z = 0u;
+    r.w = 0u;
     return __builtin_bit_cast(lvr_bf16x8, r);
 }
 

@@ -73,9 +73,9 @@ subspace_max_kernel(const void *__restrict__ centres, const float *__restrict__ 
             rho = radii[(int64_t)bh * max_groups + g];
         } else if constexpr (CF8) {
             load_row(g, x);
-            // radii as eight bf16 per group: slot s = top bits of rho_s, slot S + s = the rest rounded up
-            const uint16_t *rb = reinterpret_cast<const uint16_t *>(radii) + ((int64_t)bh * max_groups + g) * 8;
-            rho = __uint_as_float((uint32_t)rb[s_l] << 16) + __uint_as_float((uint32_t)rb[S + s_l] << 16);
+            // radii as four bf16 per group: slot s = rho_s
+            const uint16_t *rb = reinterpret_cast<const uint16_t *>(radii) + ((int64_t)bh * max_groups + g) * 4;
+            rho = __uint_as_float((uint32_t)rb[s_l] << 16);
         } else {
             load_row(g, x);
             rho = radii[((int64_t)bh * max_groups + g) * S + s_l];

@@ -54,7 +54,7 @@ query_fused_kernel(const FusedArgs a) {
     static_assert(!Q1 || S <= 4 || !CF8, "8-bit centres: at most four coordinate blocks");
     static_assert(!CF8 || S <= 4, "8-bit centres: at most four coordinate blocks");
     static_assert(W == 4 || (W == 8 && HB == 1 && !ENC && !Q1), "the eight-head operand serves balls with one threshold per head");
-    // RP: the radii of 8-bit balls come pre-split for the matrix cores; boxes keep one fp32 allowance per group
+    // RP: the radii of 8-bit balls are stored as bf16 in the radius step's operand form; boxes keep one fp32 allowance per group
     constexpr bool RP = CF8 && !ENC;
     // the staging area of the query operand is dead once every wave holds its fragments; the score
     // queues of the emitters live in the same bytes afterwards
@@ -87,7 +87,7 @@ query_fused_kernel(const FusedArgs a) {
     constexpr int SP = (S <= 4) ? S : 1;      // radii are fetched ahead only when they are few
     // balls: one row per group (the centre); boxes: two rows per group (upper corner, lower corner)
     const char *Cb = static_cast<const char *>(a.centres) + (int64_t)bh * a.max_groups * LVR_D * (CF8 ? 1 : 2) * (ENC ? 2 : 1);
-    const float *Rb = a.radii + (int64_t)bh * a.max_groups * (RP ? 4 : (ENC ? 1 : S));   // boxes: one allowance per group, whatever S   // 8-bit centres: 16 bytes of pre-split radii per group
+    const float *Rb = a.radii + (int64_t)bh * a.max_groups * (RP ? 2 : (ENC ? 1 : S));   // boxes: one allowance per group, whatever S; 8-bit centres: 8 bytes of radii per group (four bf16)
     const int64_t n_tiles = (a.n_groups + 15) >> 4;
     const int64_t tile0 = ((int64_t)blockIdx.x * 4 + wave) * a.tiles_per_wave;
     // RM: the radius term rides on the matrix cores as a fifth step (S <= 4, one threshold per head);
@@ -99,7 +99,7 @@ query_fused_kernel(const FusedArgs a) {
         uint4 av[UA][CF8 ? 2 : 4], av2[ENC ? UA : 1][CF8 ? 2 : 4];
         float rad[RM ? 1 : UA][4][SP];
         float rrow[(RM && !RP) ? UA : 1][SP];
-        uint4 rblk[(RM && RP) ? UA : 1];
+        uint2 rblk[(RM && RP) ? UA : 1];
     };
     // 8-bit centres leave room for two trips in registers: the next trip's loads are issued before
     // the current trip is scored, so the memory pipe does not drain between trips
@@ -125,7 +125,7 @@ query_fused_kernel(const FusedArgs a) {
                 lvr_load_a_frags(Cb, g, av[u]);
             }
             if constexpr (RM && RP) {
-                rblk[u] = reinterpret_cast<const uint4 *>(Rb)[g];
+                rblk[u] = reinterpret_cast<const uint2 *>(Rb)[g];
             } else if constexpr (RM) {
                 const float *rp = Rb + g * S;
                 if constexpr (S == 4) {
@@ -143,15 +143,11 @@ query_fused_kernel(const FusedArgs a) {
                     const float *rp = Rb + gj * (ENC ? 1 : S);
                     if constexpr (ENC) {   // the box's allowance; S only counts the blocks of Query 1
                         rad[u][j][0] = rp[0];
-                    } else if constexpr (RP) {   // pre-split radii: rho_s = slot s + slot S+s (exact in fp32)
-                        const uint4 blk = reinterpret_cast<const uint4 *>(Rb)[gj];
-                        const uint32_t w[4] = {blk.x, blk.y, blk.z, blk.w};
+                    } else if constexpr (RP) {   // four bf16 per group: slot s = rho_s
+                        const uint2 blk = reinterpret_cast<const uint2 *>(Rb)[gj];
+                        const uint32_t w[2] = {blk.x, blk.y};
 #pragma unroll
-                        for (int s = 0; s < S; ++s) {
-                            const uint32_t hi = (w[s / 2] >> (16 * (s & 1))) << 16;
-                            const uint32_t mid = (w[(S + s) / 2] >> (16 * ((S + s) & 1))) << 16;
-                            rad[u][j][s] = __uint_as_float(hi) + __uint_as_float(mid);
-                        }
+                        for (int s = 0; s < S; ++s) rad[u][j][s] = __uint_as_float((w[s / 2] >> (16 * (s & 1))) << 16);
                     } else if constexpr (S == 4) {
                         const float4 r = *reinterpret_cast<const float4 *>(rp);
                         rad[u][j][0] = r.x; rad[u][j][1] = r.y; rad[u][j][2] = r.z; rad[u][j][3] = r.w;
@@ -223,8 +219,8 @@ query_fused_kernel(const FusedArgs a) {
         if (!buffer_wg) {
 #pragma unroll
             for (int hb = 0; hb < HB; ++hb) {
-                if constexpr (W == 8) rbq[hb] = lvr_radius_b_frag8<S, RP ? 2 : 3>(s_qn, a.G);
-                else rbq[hb] = lvr_radius_b_frag<S, RP ? 2 : 3>(s_qn, a.G, hb);
+                if constexpr (W == 8) rbq[hb] = lvr_radius_b_frag8<S, RP ? 1 : 3>(s_qn, a.G);
+                else rbq[hb] = lvr_radius_b_frag<S, RP ? 1 : 3>(s_qn, a.G, hb);
             }
         }
     }
