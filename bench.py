@@ -175,13 +175,15 @@ def measure(cid, args, *, group_size, steps, warmup, full, cpu_seconds, legs=Tru
                 log(f"[bench] thresholds placed for {t + 1} of {T_all} steps")
         del Kfull
     else:
-        kq = int(math.ceil(c["qualify_frac"] * n0))
+        frac = c["qualify_frac"] if args.qualify_frac is None else args.qualify_frac
+        kq = int(math.ceil(frac * n0))
         tau_all = torch.empty((n_distinct, B, Hq), dtype=torch.float32, device=dev)
         prev, turn = None, []
         for t in range(n_distinct):
             sc = scores_on_gpu(Kd, q_all[t], G)
-            tau_all[t] = kth_midpoint_tau(sc, kq)
-            if cid == 3:                                    # drifting queries: how much of the set is new each step
+            # --qualify-frac 0: thresholds that no key reaches (the bound phase alone: no survivors, no hits)
+            tau_all[t] = kth_midpoint_tau(sc, kq) if kq > 0 else sc.amax(-1) * 1.5 + 1.0
+            if cid == 3 and kq > 0:                         # drifting queries: how much of the set is new each step
                 cur = sc >= tau_all[t].unsqueeze(-1)
                 if prev is not None:
                     turn.append((cur & ~prev).sum(-1).float().div(kq).mean())
@@ -319,7 +321,7 @@ def measure(cid, args, *, group_size, steps, warmup, full, cpu_seconds, legs=Tru
     # HBM bytes per launch measured OFFLINE with rocprofv3 --pmc on this same command (the counters cannot
     # be read from inside the run); only the default options of a workload have a figure
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
-    default_opts = (args.subspaces == 4 and args.keys == "workload" and args.query_workgroups == 0
+    default_opts = (args.subspaces == 4 and args.keys == "workload" and args.query_workgroups == 0 and args.qualify_frac is None
                     and args.enclosing == "ball" and args.centres == "auto" and not args.offload and not args.separate
                     and args.grouping == "contiguous" and not args.q_heads)
     if os.path.exists(tpath) and default_opts:
@@ -488,6 +490,9 @@ def main():
                     help="replicas of the index cycled through by the cache-cold pass (1 = skip that pass)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle sample")
+    ap.add_argument("--qualify-frac", type=float, default=None,
+                    help="share of the keys that qualifies per head (default: the workload's); 0 = thresholds that nothing "
+                         "reaches, which times the bound phase alone; not for the append workload")
     ap.add_argument("--query-workgroups", type=int, default=0,
                     help="lvr_config.query_workgroups: workgroups a range-query launch aims at (0 = the library's default)")
     ap.add_argument("--only", action="store_true", help="measure --config alone (no block for the other workloads)")
@@ -528,7 +533,8 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"config{cid}:{r['name']}" + (" [supplementary: keys with positional locality]" if args.keys == "local" else "") + (f" [supplementary: {Hq} query heads]" if args.q_heads else ""), "batch": B, "n_q_heads": Hq, "n_kv_heads": r["Hkv"],
+        "config": {"workload": f"config{cid}:{r['name']}" + (" [supplementary: keys with positional locality]" if args.keys == "local" else "") + (f" [supplementary: {Hq} query heads]" if args.q_heads else "")
+                               + (f" [supplementary: {args.qualify_frac} of the keys qualify]" if args.qualify_frac is not None else ""), "batch": B, "n_q_heads": Hq, "n_kv_heads": r["Hkv"],
                    "head_dim": r["d"], "context": r["n_now"], "kv_storage": "bf16", "group_size": args.group_size,
                    "subspaces": args.subspaces, "attn_splits": args.attn_splits, "grouping": args.grouping,
                    "centres": "fp8" if fp8 else "bf16", "enclosing": args.enclosing,

@@ -173,7 +173,10 @@ int lvr_build(lvr_index *ix, const void *K_dev, const void *V_dev, int64_t n,
 /* Dynamic update (Sec. 4.3; App. "GPU Update", single-stream form): m new tokens per
  * (sequence, KV head), k_new_dev / v_new_dev: [batch][n_kv_heads][m][head_dim] contiguous.
  * New keys join the buffer; whenever the buffer holds B keys they are grouped and their
- * balls appended to the index. */
+ * balls appended to the index.
+ * A call that returns LVR_E_INVALID, LVR_E_STATE, LVR_E_CAPACITY or LVR_E_UNSUPPORTED has stored
+ * nothing (every such check precedes the first store).  After LVR_E_HIP the rows may or may not
+ * have been stored: rebuild the index with lvr_build rather than repeating the append. */
 int lvr_append(lvr_index *ix, const void *k_new_dev, const void *v_new_dev, int64_t m, void *stream);
 
 /* Phase 2 of the two-stream update (App. "GPU Update"): make `stream` wait for the side stream's
@@ -189,7 +192,12 @@ int lvr_publish(lvr_index *ix, void *stream);
  *   out_idx_dev   [batch][n_q_heads][cap] int32 positions, order within a head unspecified
  *   out_count_dev [batch][n_q_heads] int32, the TRUE set size even when it exceeds cap
  * A key is emitted iff its fp32 score >= tau - 0.5e-4*|tau| (the comparison leans towards
- * inclusion so that rounding-order differences never lose a key).  If a set exceeds cap the
+ * inclusion so that rounding-order differences never lose a key).  The slack is relative to
+ * |tau|: at tau = 0 it vanishes and the decision is the sign of the kernel's own fp32 score (bf16
+ * products are exact, accumulation is fp32 in matrix-core order), which can differ from another
+ * summation order by a few units of 2^-24 * sum_c |q_c k_c|; every key whose exact score exceeds
+ * tau by more than head_dim * 2^-23 * sum_c |q_c k_c| is returned whatever tau is, and integer-valued
+ * data (exact sums) is decided exactly.  If a set exceeds cap the
  * list is truncated and a sticky overflow flag is raised (reported by lvr_get_stats). */
 int lvr_query(lvr_index *ix, const float *q_dev, const float *tau_dev, int32_t *out_idx_dev,
               int32_t *out_count_dev, int64_t cap, void *stream);

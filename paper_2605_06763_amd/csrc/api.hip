@@ -429,6 +429,14 @@ int lvr_append(lvr_index *ix, const void *k_new, const void *v_new, int64_t m, v
     if (ix->n_total + m > ix->cfg.capacity) return LVR_E_CAPACITY;
     if (!aligned16(k_new) || !aligned16(v_new)) return LVR_E_INVALID;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    // Everything that can refuse the call is settled before a row is stored, so a call that returns
+    // LVR_E_UNSUPPORTED has changed nothing and may be repeated differently: whether a chunk can be
+    // grouped by the tree (the width of its sort key), and the side stream of the two-stream update.
+    if ((ix->cfg.grouping == LVR_GROUP_TREE || ix->per_subspace) &&
+        ix->n_total + m - ix->n_indexed >= ix->cfg.buffer_size && !lvr_tree_feasible(ix, ix->cfg.buffer_size))
+        return LVR_E_UNSUPPORTED;
+    if ((ix->cfg.flags & LVR_CONCURRENT_UPDATE) && !ix->side)
+        LVR_HIP(hipStreamCreateWithFlags(&ix->side, hipStreamNonBlocking));
     {
         // groups prepared earlier become visible as soon as they are ready; they must be before
         // the next chunk is formed
@@ -453,7 +461,6 @@ int lvr_append(lvr_index *ix, const void *k_new, const void *v_new, int64_t m, v
         // Phase 1 on the side stream: it starts once the rows copied above are in the arena and
         // writes only index slots (and staging) that no query launched before the publish reads
         const int64_t g0 = ix->n_indexed / r;
-        if (!ix->side) LVR_HIP(hipStreamCreateWithFlags(&ix->side, hipStreamNonBlocking));   // made at first use
         LVR_HIP(hipEventRecord(ix->ev_fork, st));
         LVR_HIP(hipStreamWaitEvent(ix->side, ix->ev_fork, 0));
         if (ix->cfg.grouping == LVR_GROUP_TREE) {

@@ -162,6 +162,7 @@ struct lvr_tree_perm {
     int64_t np;
     int pos_bits;
 };
+bool lvr_tree_feasible(const lvr_index *ix, int64_t n_real);
 // c_lo, c_hi: the split axis of every node is chosen among coordinates [c_lo, c_hi) only
 hipError_t lvr_tree_order(lvr_index *ix, const void *Ksrc, const int64_t ks[3], int64_t n_real, hipStream_t st,
                           lvr_tree_perm *perm, int c_lo = 0, int c_hi = LVR_D);

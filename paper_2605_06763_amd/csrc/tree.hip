@@ -373,6 +373,23 @@ size_t lvr_tree_sort_temp_bytes(int64_t total_keys) {
     return bytes;
 }
 
+// Whether lvr_tree_order can handle n_real keys per (sequence, KV head): the sort key
+// [node | coordinate | position] has to fit 64 bits and the work space the padded entries.
+bool lvr_tree_feasible(const lvr_index *ix, int64_t n_real) {
+    if (n_real <= 0) return true;
+    const int r = ix->cfg.group_size;
+    const int n_bh = lvr_n_bh(ix);
+    int64_t groups = n_real / r, gp = 1;
+    while (gp < groups) gp <<= 1;
+    const int64_t np = gp * r;
+    const int pos_bits = bits_for(np);
+    const int coord_bits = ix->elt == 2 ? 16 : 32;
+    int levels = 0;
+    while (((int64_t)1 << levels) < gp) ++levels;
+    const int node_bits = bits_for((int64_t)n_bh << (levels > 0 ? levels - 1 : 0));
+    return pos_bits + coord_bits + node_bits <= 64 && (int64_t)n_bh * np <= ix->tree_cap_keys;
+}
+
 // Orders n_real = groups*r keys (positions 0..n_real-1 of the given source rows) by the tree and
 // writes them, regrouped, to arena rows row0 .. row0+n_real-1 together with the position maps.
 // Returns hipErrorInvalidValue if the sort key would not fit in 64 bits.

@@ -95,6 +95,43 @@ def test_tau_extremes(G, oracle):
         assert np.abs(out[0, 5] - ref[0, 5]).max() / np.abs(ref[0, 5]).max() <= G.ATTN_TOL
 
 
+@pytest.mark.parametrize("r", [1, 4])
+def test_tau_zero_and_tiny(G, oracle, r):
+    """tau = 0 ("every key with a non-negative product") and |tau| tiny: the relative slack of the
+    comparison vanishes there, so the promise is the absolute one of the header.  Integer-valued
+    data (every sum exact) is decided exactly, zeros included; on real-valued data every key whose
+    exact score clears tau by more than d * 2^-23 * sum|q_c k_c| comes back and nothing that far below does."""
+    g = np.random.default_rng(77)
+    n, hq, hkv = 3000, 8, 2
+    Ki = g.integers(-3, 4, size=(1, hkv, n, 128)).astype(np.float32)
+    Vi = W.round_to_bf16(g.standard_normal((1, hkv, n, 128)).astype(np.float32))
+    qi = g.integers(-2, 3, size=(1, hq, 128)).astype(np.float32)
+    with G.Index(Ki, Vi, "bf16", hq, group_size=r) as ix:
+        for t in (0.0, 1.0, -1.0):
+            tau = np.full((1, hq), t, dtype=np.float32)
+            idx, cnt, out = ix.query(qi, tau, fused=True)
+            for h in range(hq):
+                s = oracle.scores_f64(qi[0, h], Ki[0, h // 4])
+                want = set(np.nonzero(s >= t - 0.5e-4 * abs(t))[0].tolist())    # exact scores: exactly the kernel's rule
+                assert set(idx[0, h, :cnt[0, h]].tolist()) == want, (t, h)
+                assert (s == 0).sum() > 0                                        # the tie at zero is really there
+    cache = _small_cache(2, n)
+    q = W.make_queries(2, n_q_heads=hq)
+    with G.Index(cache.K, cache.V, "bf16", hq, group_size=r) as ix:
+        for t in (0.0, 1e-6, -1e-6):
+            tau = np.full((1, hq), t, dtype=np.float32)
+            idx, cnt, out = ix.query(q, tau, fused=True)
+            for h in range(hq):
+                Kh = cache.K[0, h // 4].astype(np.float64)
+                s = Kh @ q[0, h].astype(np.float64)
+                slack = 128 * 2.0 ** -23 * (np.abs(Kh) @ np.abs(q[0, h].astype(np.float64)))
+                got = np.zeros(n, dtype=bool)
+                got[idx[0, h, :cnt[0, h]]] = True
+                assert not np.any((s >= t + slack) & ~got), (t, h, "a key clearly above tau is missing")
+                assert not np.any((s <= t - slack) & got), (t, h, "a key clearly below tau came back")
+                assert abs(int(got.sum()) - int((s >= t).sum())) <= 2
+
+
 def test_empty_index(G, oracle):
     cache = _small_cache(2, 0)
     q = W.make_queries(2, n_q_heads=8)
