@@ -496,6 +496,9 @@ def main():
     ap.add_argument("--query-workgroups", type=int, default=0,
                     help="lvr_config.query_workgroups: workgroups a range-query launch aims at (0 = the library's default)")
     ap.add_argument("--only", action="store_true", help="measure --config alone (no block for the other workloads)")
+    ap.add_argument("--no-legs", action="store_true",
+                    help="skip the exact-filter-only pass and the r = 4 pass (they launch the same kernel as the timed steps; "
+                         "a profile of the run then shows the timed steps' launches alone)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the hot path is a single-GPU kernel pipeline; "
@@ -513,7 +516,8 @@ def main():
     if cid == 5 and steps == 256 and not any(a.startswith("--steps") for a in sys.argv[1:]):
         steps = 1024                     # the append workload: a longer run, the cache grows as it goes
     cpu_s = 0.0 if args.no_cpu_baseline else args.cpu_seconds
-    r = measure(cid, args, group_size=args.group_size, steps=steps, warmup=args.warmup, full=True, cpu_seconds=cpu_s)
+    r = measure(cid, args, group_size=args.group_size, steps=steps, warmup=args.warmup, full=True, cpu_seconds=cpu_s,
+                legs=not args.no_legs)
     ms_per_step = r["ms_per_step"]
     B, Hq = r["B"], r["Hq"]
     appending = cid == 5
