@@ -18,6 +18,8 @@
 //      the CPU reference uses) and the sort needs no values;
 //   3. a device-wide radix sort of the keys (rocPRIM: a plain library sort).
 // After the last level the low bits of the sorted keys are the slot -> position map.
+// Only the levels whose nodes exceed 1024 entries go through steps 1-3; the levels below are finished
+// by tree_small_kernel in one launch, a workgroup per node with the node's order in LDS.
 #include <rocprim/device/device_radix_sort.hpp>
 
 #include "lvr_internal.h"
@@ -228,23 +230,27 @@ __global__ void tree_gather_kernel(TreeSrc ksrc, TreeSrc vsrc, const uint64_t *_
     }
 }
 
-// Small inputs (a buffer chunk of B keys, np <= TREE_WG_MAX padded entries): the whole tree in ONE
-// launch, one 256-thread workgroup per (sequence, KV head).  Same steps as the level-synchronous
-// kernels above (same statistics in the same order, same keys), with the order kept in LDS and a
-// bitonic sort in place of the device-wide radix sort; keys are unique, so any sort gives the
-// same order.  The node index inside the key is local to the (sequence, KV head).
+// Subtrees of at most TREE_WG_MAX padded entries: ALL their remaining levels in ONE launch, one
+// 256-thread workgroup per subtree.  Either the whole tree of a small input (a buffer chunk of B
+// keys: keys_in == NULL, one workgroup per (sequence, KV head)), or every node of the level at which
+// the level-synchronous kernels above have brought the nodes down to TREE_WG_MAX entries (keys_in =
+// the order so far; the node's entries are np consecutive ones).  Same steps as the level-synchronous
+// kernels (same statistics in the same order, same keys), with the order kept in LDS and a bitonic
+// sort in place of the device-wide radix sort; keys are unique, so any sort gives the same order.
+// The node index inside the key is local to the subtree (only the position bits are read later).
 constexpr int TREE_WG_MAX = 1024;
 
 __global__ void __launch_bounds__(256)
-tree_small_kernel(TreeSrc src, uint64_t *__restrict__ keys_out, int np, int64_t n_real, int levels, int pos_bits,
-                  int coord_bits, int c_lo, int c_hi) {
+tree_small_kernel(TreeSrc src, const uint64_t *__restrict__ keys_in, uint64_t *__restrict__ keys_out, int64_t np_total,
+                  int np, int64_t n_real, int levels, int pos_bits, int coord_bits, int c_lo, int c_hi) {
     __shared__ uint64_t s_keys[TREE_WG_MAX];
     __shared__ int32_t s_axis[TREE_WG_MAX / 2];
     __shared__ double s_part[4][256];   // per run: 128 sums, 128 sums of squares
     __shared__ int s_cnt[4];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const int bh = blockIdx.x;
-    for (int i = t; i < np; i += 256) s_keys[i] = (uint64_t)i;
+    const int bh = blockIdx.y;
+    const int64_t base = (int64_t)bh * np_total + (int64_t)blockIdx.x * np;   // this subtree's entries
+    for (int i = t; i < np; i += 256) s_keys[i] = keys_in ? (uint64_t)key_pos(keys_in[base + i], pos_bits) : (uint64_t)i;
     __syncthreads();
     for (int L = 0; L < levels; ++L) {
         const int n_nodes = 1 << L;
@@ -355,7 +361,7 @@ tree_small_kernel(TreeSrc src, uint64_t *__restrict__ keys_out, int np, int64_t 
             }
         }
     }
-    for (int i = t; i < np; i += 256) keys_out[(int64_t)bh * np + i] = s_keys[i];
+    for (int i = t; i < np; i += 256) keys_out[base + i] = s_keys[i];
 }
 
 int bits_for(int64_t v) {   // bits needed to hold values 0 .. v-1
@@ -414,15 +420,23 @@ hipError_t lvr_tree_order(lvr_index *ix, const void *Ksrc, const int64_t ks[3], 
     uint64_t *cur = ix->tree_keys_a, *alt = ix->tree_keys_b;
     if (np <= TREE_WG_MAX && pos_bits + coord_bits + levels <= 64) {
         // small input (a buffer chunk): the whole tree in one launch
-        hipLaunchKernelGGL(tree_small_kernel, dim3((unsigned)n_bh), dim3(256), 0, st, ksrc, cur, (int)np, n_real, levels,
-                           pos_bits, coord_bits, c_lo, c_hi);
+        hipLaunchKernelGGL(tree_small_kernel, dim3(1, (unsigned)n_bh), dim3(256), 0, st, ksrc, (const uint64_t *)nullptr, cur, np,
+                           (int)np, n_real, levels, pos_bits, coord_bits, c_lo, c_hi);
         perm->keys = cur;
         perm->np = np;
         perm->pos_bits = pos_bits;
         return hipGetLastError();
     }
+    // the upper levels one by one (device-wide sort per level) until a node has at most TREE_WG_MAX
+    // entries; all the levels below that in one launch, a workgroup per node, sorted in LDS
+    int top_levels = levels;
+    for (int L = 0; L < levels; ++L)
+        if ((np >> L) <= TREE_WG_MAX && pos_bits + coord_bits + (levels - L) <= 64) {
+            top_levels = L;
+            break;
+        }
     hipLaunchKernelGGL(tree_init_kernel, dim3((unsigned)((np + 255) / 256), (unsigned)n_bh), dim3(256), 0, st, cur, np);
-    for (int L = 0; L < levels; ++L) {
+    for (int L = 0; L < top_levels; ++L) {
         const int64_t n_nodes = (int64_t)1 << L;
         const int64_t m = np >> L;                      // entries per node at this level (>= 2r)
         if (m <= PIECE) {
@@ -444,6 +458,12 @@ hipError_t lvr_tree_order(lvr_index *ix, const void *Ksrc, const int64_t ks[3], 
         uint64_t *t = cur;
         cur = alt;
         alt = t;
+    }
+    if (top_levels < levels) {
+        const int64_t m0 = np >> top_levels;   // entries of a node at that level
+        hipLaunchKernelGGL(tree_small_kernel, dim3((unsigned)(np / m0), (unsigned)n_bh), dim3(256), 0, st, ksrc,
+                           (const uint64_t *)cur, alt, np, (int)m0, n_real, levels - top_levels, pos_bits, coord_bits, c_lo, c_hi);
+        cur = alt;
     }
     perm->keys = cur;
     perm->np = np;

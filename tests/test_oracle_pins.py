@@ -654,3 +654,24 @@ def test_threshold_rules_against_the_papers_table(oracle):
     assert abs(implied_mean) < 0.25 * table[("budget", 0.15)]
     # sample-gap's printed mean lies between topk(2) and topk(5): the largest gap sits in the top few
     assert table[("sample-topk", 5.0)] < table[("sample-gap", 0.0)] < table[("sample-topk", 2.0)]
+
+
+def test_pruning_power_report_runs_on_the_oracle_alone(oracle, capsys):
+    """oracle/pruning_power.py (the source of the pruning table in the design doc) on a small cache: its
+    own check (no summed bound below a key's score) holds, the depth scan's live set contains the
+    summed-bound set, and a grouping per subspace with small subspaces keeps fewer keys than one
+    shared grouping, which keeps (nearly) all of these keys."""
+    from oracle import pruning_power as pp
+    pp.run(2, 2048, [4], [4, 16], n_queries=2)
+    lines = [l for l in capsys.readouterr().out.splitlines() if l.startswith("config 2")]
+    assert len(lines) == 6
+    got = {}
+    for l in lines:
+        name = "per" if "per subspace" in l else ("shared" if "shared tree" in l else "contiguous")
+        S = int(l.split("S=")[1].split()[0])
+        keep_sum = float(l.split("summed bounds keep")[1].split()[0])
+        keep_ta = float(l.split("depth scan keeps")[1].split()[0])
+        assert keep_sum <= keep_ta + 1e-12
+        got[(name, S)] = keep_sum
+    assert got[("contiguous", 4)] > 0.99 and got[("shared", 16)] > 0.99
+    assert got[("per", 16)] < got[("per", 4)] <= 1.0 and got[("per", 16)] < 0.9
