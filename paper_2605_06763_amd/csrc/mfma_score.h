@@ -59,6 +59,55 @@ __device__ __forceinline__ void lvr_build_q_frag_one(const float *__restrict__ q
     out = __builtin_bit_cast(lvr_bf16x8, packed);
 }
 
+// The same in two steps, so that the loads of q can be put in flight ahead of other loads
+// (vector memory loads return in order: whatever is requested first is usable first).
+__device__ __forceinline__ void lvr_q_frag_load(const float *__restrict__ q_group, int G, int hb, int kk, float (&raw)[8]) {
+    const int lane = threadIdx.x & 63;
+    const int n = lane & 15, kq = lane >> 4;
+    const int part = n >> 2, h = hb * 4 + (n & 3);
+    const bool live = part < 3 && h < G;
+    const float *src = q_group + (int64_t)(live ? h : 0) * LVR_D + kk * 32 + kq * 8;
+    const float4 a = *reinterpret_cast<const float4 *>(src), b = *reinterpret_cast<const float4 *>(src + 4);
+    raw[0] = a.x; raw[1] = a.y; raw[2] = a.z; raw[3] = a.w;
+    raw[4] = b.x; raw[5] = b.y; raw[6] = b.z; raw[7] = b.w;
+}
+
+__device__ __forceinline__ void lvr_q_frag_make(const float (&raw)[8], int G, int hb, float scale, lvr_bf16x8 &out, int sign = 0) {
+    const int lane = threadIdx.x & 63;
+    const int n = lane & 15;
+    const int part = n >> 2, h = hb * 4 + (n & 3);
+    const bool live = part < 3 && h < G;
+    uint32_t w[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        float x = live ? raw[e] * scale : 0.f;
+        if (sign > 0) x = fmaxf(x, 0.f);
+        if (sign < 0) x = fminf(x, 0.f);
+        w[e] = live ? lvr_split_part(x, part) : 0u;
+    }
+    uint4 packed = make_uint4(w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16));
+    out = __builtin_bit_cast(lvr_bf16x8, packed);
+}
+
+// The exchange step of lvr_build_q_frags_wg for fragments made from values loaded earlier.
+// Contains a __syncthreads(): every thread of the workgroup must call it.
+template <int HB>
+__device__ __forceinline__ void lvr_exchange_q_frags_wg(const float (&raw)[HB][8], int G, float scale, uint4 (&s_bq)[HB][4][64],
+                                                        lvr_bf16x8 (&bq)[HB][4], int sign = 0) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) {
+        lvr_bf16x8 f;
+        lvr_q_frag_make(raw[hb], G, hb, scale, f, sign);
+        s_bq[hb][wave][lane] = __builtin_bit_cast(uint4, f);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) bq[hb][kk] = __builtin_bit_cast(lvr_bf16x8, s_bq[hb][kk][lane]);
+}
+
 // All B fragments of a KV group, built once per 256-thread workgroup: wave w builds the
 // fragment of coordinates w*32 .. w*32+31 for every head block, the four waves exchange them
 // through LDS.  Contains a __syncthreads(): every thread of the workgroup must call it.

@@ -160,23 +160,41 @@ query_fused_kernel(const FusedArgs a) {
         }
     };
     const bool phaseA = !buffer_wg && !a.skip_bounds && tile0 < n_tiles && a.n_groups > 0;   // wave-uniform
-    if (phaseA) issueA(t0, 0);
-    // the thresholds too are asked for before the prologue's barrier; they are needed last
+    // Order of the first requests.  Vector memory loads return in order, so what the prologue needs (q for the
+    // operand and the norms, the thresholds: a few KB that sit in the caches) is requested FIRST and the first
+    // trip of centres right behind it: the prologue's arithmetic and its barrier then run while the centres
+    // are still on their way, instead of waiting behind them.
+    float qraw[W == 4 ? HB : 1][8];   // this lane's share of q for the operand pieces it builds
+    float qnv[8];                     // and for the norms
+    (void)qraw;
+    if constexpr (W == 4) {
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb) lvr_q_frag_load(a.q + hq0 * LVR_D, a.G, hb, wave, qraw[hb]);
+    }
+    const bool norm_thread = !buffer_wg && (int)threadIdx.x < HB * W * 16 && (int)(threadIdx.x >> 4) < a.G;
+    {
+        const float *qh = a.q + (hq0 + (norm_thread ? (threadIdx.x >> 4) : 0)) * LVR_D + (threadIdx.x & 15) * 8;
+        const float4 x = *reinterpret_cast<const float4 *>(qh), y = *reinterpret_cast<const float4 *>(qh + 4);
+        qnv[0] = x.x; qnv[1] = x.y; qnv[2] = x.z; qnv[3] = x.w;
+        qnv[4] = y.x; qnv[5] = y.y; qnv[6] = y.z; qnv[7] = y.w;
+    }
     float tau_raw[HB];
 #pragma unroll
     for (int hb = 0; hb < HB; ++hb) {
         const int h = hb * W + n - 8;
         tau_raw[hb] = (n >= 8 && n < 8 + W && h < a.G) ? a.tau[hq0 + h] : INFINITY;
     }
+    __builtin_amdgcn_sched_barrier(0);
+    if (phaseA) issueA(t0, 0);
+    __builtin_amdgcn_sched_barrier(0);
 
     // ---- prologue: subspace norms of q (phase A only) and the B operand of q ----
     if (!buffer_wg && (int)threadIdx.x < HB * W * 16) {
         const int h = threadIdx.x >> 4, li = threadIdx.x & 15;
         float ss = 0.f;
         if (h < a.G) {
-            const float *qh = a.q + (hq0 + h) * LVR_D + li * 8;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) ss += qh[e] * qh[e];
+            for (int e = 0; e < 8; ++e) ss += qnv[e] * qnv[e];
         }
         constexpr int lanes_per_sub = 16 / S;
 #pragma unroll
@@ -188,8 +206,8 @@ query_fused_kernel(const FusedArgs a) {
     lvr_bf16x8 bq[HB][4], bq2[ENC ? HB : 1][4];
     bool third = false;   // W = 8: some head's query has more than 16 significant bits (the same in every thread)
     if constexpr (W == 8) third = lvr_build_q_frags8_wg(a.q + hq0 * LVR_D, a.G, 1.0f, s_bq8);   // syncs
-    else lvr_build_q_frags_wg<HB>(a.q + hq0 * LVR_D, a.G, 1.0f, s_u.bq, bq, ENC ? 1 : 0);   // syncs
-    if constexpr (ENC) lvr_build_q_frags_wg<HB>(a.q + hq0 * LVR_D, a.G, 1.0f, s_bq2, bq2, -1);
+    else lvr_exchange_q_frags_wg<HB>(qraw, a.G, 1.0f, s_u.bq, bq, ENC ? 1 : 0);   // syncs
+    if constexpr (ENC) lvr_exchange_q_frags_wg<HB>(qraw, a.G, 1.0f, s_bq2, bq2, -1);
     // BL: the pieces of head block hb, fetched anew at every use (the index register comes out of an
     // opaque instruction so that the loads are not hoisted out of the loops and kept in registers)
     auto fetch_bq = [&](int hb, lvr_bf16x8 (&b)[4]) {
