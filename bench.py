@@ -141,7 +141,7 @@ def measure(cid, args, *, group_size, steps, warmup, full, cpu_seconds, legs=Tru
                              grouping={"contiguous": L.LVR_GROUP_CONTIGUOUS, "tree": L.LVR_GROUP_TREE,
                                        "subspace": L.LVR_GROUP_SUBSPACE_TREE}[args.grouping],
                              attn_splits=args.attn_splits, query_workgroups=args.query_workgroups,
-                             index_dtype={"auto": L.LVR_INDEX_AUTO, "bf16": L.LVR_INDEX_SAME, "fp8": L.LVR_INDEX_FP8}[args.centres],
+                             index_dtype={"auto": L.LVR_INDEX_AUTO, "bf16": L.LVR_INDEX_SAME, "fp8": L.LVR_INDEX_FP8, "fp6": L.LVR_INDEX_FP6}[args.centres],
                              flags=(L.LVR_CONCURRENT_UPDATE if args.concurrent_update else 0)
                              | (L.LVR_KV_IN_HOST_MEMORY if args.offload else 0)
                              | (L.LVR_SEPARATE_KERNELS if args.separate else 0))
@@ -470,7 +470,7 @@ def main():
     ap.add_argument("--enclosing", choices=["ball", "aabb"], default="ball")
     ap.add_argument("--grouping", choices=["contiguous", "tree", "subspace"], default="contiguous",
                     help="'subspace': one tree grouping per subspace with per-key labels (the paper's own layout)")
-    ap.add_argument("--centres", choices=["auto", "bf16", "fp8"], default="auto",
+    ap.add_argument("--centres", choices=["auto", "bf16", "fp8", "fp6"], default="auto",
                     help="storage of the centres: the cache's bf16, or 8-bit e4m3 codes (half the index read); "
                          "auto = the library's default (8-bit where supported)")
     ap.add_argument("--q-heads", type=int, default=0,
@@ -541,7 +541,7 @@ def main():
                                + (f" [supplementary: {args.qualify_frac} of the keys qualify]" if args.qualify_frac is not None else ""), "batch": B, "n_q_heads": Hq, "n_kv_heads": r["Hkv"],
                    "head_dim": r["d"], "context": r["n_now"], "kv_storage": "bf16", "group_size": args.group_size,
                    "subspaces": args.subspaces, "attn_splits": args.attn_splits, "grouping": args.grouping,
-                   "centres": "fp8" if fp8 else "bf16", "enclosing": args.enclosing,
+                   "centres": "fp6" if args.centres == "fp6" else ("fp8" if fp8 else "bf16"), "enclosing": args.enclosing,
                    "index_bytes_per_key": r["index_bytes_per_key"],
                    "step": "append+query+attention" if appending else "query+attention",
                    "update": "two-stream" if args.concurrent_update else "single-stream",

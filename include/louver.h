@@ -68,8 +68,15 @@ enum lvr_enclosing { LVR_ENCLOSE_BALL = 0, LVR_ENCLOSE_AABB = 1 };
  *         read of a query halves.  Box corners are rounded outwards (upper corner up, lower corner
  *         down), so the stored box contains the exact one.  bf16 caches and the fused query kernel;
  *         balls with n_subspaces <= 4, or boxes (LVR_E_UNSUPPORTED otherwise).
+ *   FP6:  6-bit codes with a shared power-of-two scale per 32 coordinates (the OCP microscaling
+ *         element format e2m3: 1 sign, 2 exponent, 3 mantissa bits; scale = an 8-bit exponent), 96 bytes
+ *         of codes and 12 bytes of radii and scales per group: a fifth less index than FP8 for balls
+ *         about 1.6 times as large.  The 32 coordinates that share a scale are the ones one lane of the
+ *         query kernel holds (coordinates 32 kk + 8 b + e, kk = 0..3, e = 0..7, for scale block b), so a
+ *         lane decodes its share of a centre with one conversion instruction.  Balls with
+ *         n_subspaces <= 4, bf16 caches, the fused query kernel (LVR_E_UNSUPPORTED otherwise).
  *   AUTO: FP8 for balls where it is supported and K/V are in device memory, else SAME. */
-enum lvr_index_dtype { LVR_INDEX_AUTO = 0, LVR_INDEX_SAME = 1, LVR_INDEX_FP8 = 2 };
+enum lvr_index_dtype { LVR_INDEX_AUTO = 0, LVR_INDEX_SAME = 1, LVR_INDEX_FP8 = 2, LVR_INDEX_FP6 = 3 };
 
 enum lvr_flags {
     /* Keys not yet in the index (the buffer of Sec. 4.3 "Dynamic Updates") are retrieved

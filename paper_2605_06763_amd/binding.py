@@ -20,7 +20,7 @@ LVR_ATTEND_BUFFER_DENSE = 1
 LVR_SEPARATE_KERNELS = 2
 LVR_CONCURRENT_UPDATE = 4
 LVR_KV_IN_HOST_MEMORY = 8
-LVR_INDEX_AUTO, LVR_INDEX_SAME, LVR_INDEX_FP8 = 0, 1, 2
+LVR_INDEX_AUTO, LVR_INDEX_SAME, LVR_INDEX_FP8, LVR_INDEX_FP6 = 0, 1, 2, 3
 LVR_OK, LVR_E_INVALID, LVR_E_UNSUPPORTED, LVR_E_CAPACITY = 0, -1, -2, -3
 LVR_E_OVERFLOW, LVR_E_HIP, LVR_E_NOMEM, LVR_E_STATE = -4, -5, -6, -7
 

@@ -34,6 +34,13 @@ inline bool fp8_centres_supported(const lvr_config *c) {
 // AUTO: 8-bit centres halve the index read, at the price of somewhat larger balls.  That pays when the
 // surviving key rows come from HBM; behind the host link a key row costs a hundred times more than an
 // index byte, so the tighter centres in the cache's own format are kept there.
+// 6-bit centres: balls only (a box corner has to be rounded outwards per coordinate, which a shared scale makes
+// coarse); asked for explicitly, never chosen by AUTO.
+inline bool fp6_centres_supported(const lvr_config *c) {
+    return fp8_centres_supported(c) && c->enclosing == LVR_ENCLOSE_BALL && c->n_subspaces <= 4;
+}
+inline bool fp6_centres(const lvr_config *c) { return c->index_dtype == LVR_INDEX_FP6; }
+
 inline bool fp8_centres(const lvr_config *c) {
     return c->index_dtype == LVR_INDEX_FP8 ||
            (c->index_dtype == LVR_INDEX_AUTO && fp8_centres_supported(c) && c->enclosing == LVR_ENCLOSE_BALL &&
@@ -60,12 +67,14 @@ int check_config(const lvr_config *c) {
     if (c->reservoir_size < 0 || c->reservoir_size > 256) return LVR_E_INVALID;
     if (c->enclosing == LVR_ENCLOSE_AABB && (c->kv_dtype != LVR_BF16 || (c->flags & LVR_SEPARATE_KERNELS)))
         return LVR_E_UNSUPPORTED;
-    if (c->index_dtype != LVR_INDEX_AUTO && c->index_dtype != LVR_INDEX_SAME && c->index_dtype != LVR_INDEX_FP8)
+    if (c->index_dtype != LVR_INDEX_AUTO && c->index_dtype != LVR_INDEX_SAME && c->index_dtype != LVR_INDEX_FP8 &&
+        c->index_dtype != LVR_INDEX_FP6)
         return LVR_E_INVALID;
     if (c->query_workgroups < 0 || c->query_workgroups > (1 << 20)) return LVR_E_INVALID;
     if (c->flags & ~(uint32_t)(LVR_ATTEND_BUFFER_DENSE | LVR_SEPARATE_KERNELS | LVR_CONCURRENT_UPDATE | LVR_KV_IN_HOST_MEMORY))
         return LVR_E_INVALID;
     if (c->index_dtype == LVR_INDEX_FP8 && !fp8_centres_supported(c)) return LVR_E_UNSUPPORTED;
+    if (c->index_dtype == LVR_INDEX_FP6 && !fp6_centres_supported(c)) return LVR_E_UNSUPPORTED;
     if (c->grouping == LVR_GROUP_SUBSPACE_TREE) {
         // one grouping per coordinate block: labels are 16 bits, one launch form, one head block
         if (c->kv_dtype != LVR_BF16 || c->enclosing != LVR_ENCLOSE_BALL || G > 4) return LVR_E_UNSUPPORTED;
@@ -99,9 +108,10 @@ Sizes sizes_of(const lvr_config *c) {
     auto al = [](size_t b) { return (b + 255) / 256 * 256; };
     s.kv = al((size_t)n_bh * s.cap_rows * LVR_D * elt);
     const bool box = c->enclosing == LVR_ENCLOSE_AABB;
-    const size_t c_elt = fp8_centres(c) ? 1 : elt;
-    s.centres = al((size_t)n_bh * s.max_groups * LVR_D * c_elt * (box ? 2 : 1));
-    s.radii = al((size_t)n_bh * s.max_groups * (box ? 1 : (fp8_centres(c) ? 2 : c->n_subspaces)) * sizeof(float));   // boxes: one allowance; 8-bit balls: four bf16
+    const size_t c_row = fp6_centres(c) ? LVR_D * 3 / 4 : (fp8_centres(c) ? LVR_D : LVR_D * elt);
+    s.centres = al((size_t)n_bh * s.max_groups * c_row * (box ? 2 : 1));
+    // boxes: one allowance; 8-bit balls: four bf16; 6-bit balls: four bf16 and four scale bytes
+    s.radii = al((size_t)n_bh * s.max_groups * (box ? 1 : (fp6_centres(c) ? 3 : (fp8_centres(c) ? 2 : c->n_subspaces))) * sizeof(float));
     s.list = al((size_t)n_bh * s.max_groups * sizeof(int32_t));
     s.counters = al(lvr_counter_ints((int)n_bh, (int)n_bhq, s.max_groups) * sizeof(int32_t));
     s.part_ml = al((size_t)n_bhq * s.Pmax * 2 * sizeof(float));
@@ -275,7 +285,10 @@ int lvr_create(const lvr_config *cfg, lvr_index **out) {
     ix->G = cfg->n_q_heads / cfg->n_kv_heads;
     ix->box = cfg->enclosing == LVR_ENCLOSE_AABB;
     ix->cf8 = fp8_centres(cfg);
-    ix->S_store = ix->box ? 1 : (ix->cf8 ? 2 : cfg->n_subspaces);   // 8-bit centres: 8 bytes of radii per group (four bf16)
+    ix->cf6 = fp6_centres(cfg);
+    // 8-bit centres: 8 bytes of radii per group (four bf16); 6-bit centres: the same and four scale bytes
+    ix->S_store = ix->box ? 1 : (ix->cf6 ? 3 : (ix->cf8 ? 2 : cfg->n_subspaces));
+    ix->centre_bytes = ix->cf6 ? LVR_D * 3 / 4 : (ix->cf8 ? LVR_D : LVR_D * (cfg->kv_dtype == LVR_BF16 ? 2 : 4));
     ix->cap_rows = s.cap_rows;
     ix->max_groups = s.max_groups;
     ix->P = s.P;
@@ -775,7 +788,7 @@ int lvr_get_stats(lvr_index *ix, lvr_stats *out) {
     out->groups_surviving = surv;   // one grouping per block: the candidate KEYS (a key has S groups, none of which is "its" group)
     out->keys_scanned = (ix->per_subspace ? surv : surv * r) + ix->last_buffer_rows * n_bh;
     out->keys_emitted = emitted;
-    out->bytes_index = out->groups_scored * ((ix->cf8 ? (int64_t)LVR_D : row_bytes) * (ix->box ? 2 : 1) + (int64_t)ix->S_store * 4);
+    out->bytes_index = out->groups_scored * ((int64_t)ix->centre_bytes * (ix->box ? 2 : 1) + (int64_t)ix->S_store * 4);
     if (ix->per_subspace)   // plus the labels of every indexed key; the block-bound table is work space, not index
         out->bytes_index += ix->last_indexed * n_bh * (int64_t)ix->cfg.n_subspaces * 2;
     out->bytes_keys = out->keys_scanned * row_bytes;
@@ -798,7 +811,47 @@ int lvr_export_index(lvr_index *ix, void *centres, float *radii, int32_t *slot_p
     const size_t row_bytes = LVR_D * ix->elt;
     const size_t crow = row_bytes * (ix->box ? 2 : 1);   // bytes of one group's enclosure rows
     for (int bh = 0; bh < n_bh; ++bh) {
-        if (centres && ng > 0 && ix->cf8) {
+        if (centres && ng > 0 && ix->cf6) {
+            // e2m3 codes (6 bits, matrix-operand order) times the scale of their block -> bf16 bit patterns in
+            // coordinate order (exact: 4 significant bits).  Lane piece b of a row is its bytes 24 b .. 24 b + 23:
+            // 32 codes, code 8 kk + e = coordinate 32 kk + 8 b + e; the scale of piece b is byte b of the third
+            // word of the group's 12-byte record in `radii`.
+            const int cb = ix->centre_bytes;
+            uint8_t *codes = static_cast<uint8_t *>(malloc((size_t)ng * cb));
+            uint32_t *rec = static_cast<uint32_t *>(malloc((size_t)ng * 12));
+            if (!codes || !rec) {
+                free(codes);
+                free(rec);
+                return LVR_E_NOMEM;
+            }
+            hipError_t e = hipMemcpy(codes, static_cast<char *>(ix->centres) + (size_t)bh * ix->max_groups * cb, (size_t)ng * cb,
+                                     hipMemcpyDeviceToHost);
+            if (e == hipSuccess)
+                e = hipMemcpy(rec, ix->radii + (size_t)bh * ix->max_groups * 3, (size_t)ng * 12, hipMemcpyDeviceToHost);
+            if (e != hipSuccess) {
+                free(codes);
+                free(rec);
+                return hip_fail(e);
+            }
+            uint16_t *dst = static_cast<uint16_t *>(centres) + (size_t)bh * ng * LVR_D;
+            for (int64_t g = 0; g < ng; ++g)
+                for (int c = 0; c < LVR_D; ++c) {
+                    const int kk = c / 32, b = (c % 32) / 8, j = c % 8;
+                    const int bit = 6 * (8 * kk + j);
+                    const uint8_t *piece = codes + g * cb + 24 * b;
+                    const uint32_t two = (uint32_t)piece[bit >> 3] | ((uint32_t)piece[(bit >> 3) + 1 < 24 ? (bit >> 3) + 1 : 23] << 8);
+                    const uint32_t code = (two >> (bit & 7)) & 63u;
+                    const int sgn = code >> 5, ex = (code >> 3) & 3, m = code & 7;
+                    const int E = (int)((rec[g * 3 + 2] >> (8 * b)) & 0xffu) - 127;
+                    const float v = ldexpf(ex == 0 ? (float)m / 8.f : ldexpf(1.f + (float)m / 8.f, ex - 1), E);
+                    uint32_t bits;
+                    const float sv = sgn ? -v : v;
+                    memcpy(&bits, &sv, 4);
+                    dst[g * LVR_D + c] = (uint16_t)(bits >> 16);
+                }
+            free(codes);
+            free(rec);
+        } else if (centres && ng > 0 && ix->cf8) {
             // e4m3 codes in matrix-operand order -> bf16 bit patterns in coordinate order (exact);
             // one row of codes per ball, two (upper, lower corner) per box
             const int64_t nr = ng * (ix->box ? 2 : 1), max_rows = ix->max_groups * (ix->box ? 2 : 1);
@@ -827,19 +880,21 @@ int lvr_export_index(lvr_index *ix, void *centres, float *radii, int32_t *slot_p
             LVR_HIP(hipMemcpy(static_cast<char *>(centres) + (size_t)bh * ng * crow,
                               static_cast<char *>(ix->centres) + (size_t)bh * ix->max_groups * crow,
                               (size_t)ng * crow, hipMemcpyDeviceToHost));
-        if (radii && ng > 0 && ix->cf8 && !ix->box) {
-            // four bf16 per group (slot s = rho_s) -> one float per subspace
+        if (radii && ng > 0 && (ix->cf8 || ix->cf6) && !ix->box) {
+            // four bf16 per group (slot s = rho_s) -> one float per subspace; records of 8 bytes (8-bit centres)
+            // or 12 bytes (6-bit centres: the scale bytes follow the radii)
             const int Ss = ix->cfg.n_subspaces;
-            uint16_t *blk = static_cast<uint16_t *>(malloc((size_t)ng * 8));
+            const int rec16 = ix->S_store * 2;   // record length in 16-bit units
+            uint16_t *blk = static_cast<uint16_t *>(malloc((size_t)ng * rec16 * 2));
             if (!blk) return LVR_E_NOMEM;
-            hipError_t e = hipMemcpy(blk, ix->radii + (size_t)bh * ix->max_groups * 2, (size_t)ng * 8, hipMemcpyDeviceToHost);
+            hipError_t e = hipMemcpy(blk, ix->radii + (size_t)bh * ix->max_groups * ix->S_store, (size_t)ng * rec16 * 2, hipMemcpyDeviceToHost);
             if (e != hipSuccess) {
                 free(blk);
                 return hip_fail(e);
             }
             for (int64_t g = 0; g < ng; ++g)
                 for (int sidx = 0; sidx < Ss; ++sidx) {
-                    const uint32_t hi = (uint32_t)blk[g * 4 + sidx] << 16;
+                    const uint32_t hi = (uint32_t)blk[g * rec16 + sidx] << 16;
                     float fh;
                     memcpy(&fh, &hi, 4);
                     radii[((size_t)bh * ng + g) * Ss + sidx] = fh;

@@ -94,9 +94,28 @@ __device__ __forceinline__ uint32_t f32_to_e4m3_directed(float x, bool up) {
     return c;
 }
 
-// CF8: the centre is stored as 128 e4m3 codes in the order the matrix-core operand wants them
+// fp32 -> e2m3 code (1 sign, 2 exponent bits of bias 1, 3 mantissa bits: magnitudes 0, 1/8, ..., 15/8, 2, 2.25, ...,
+// 3.75, 4, 4.5, ..., 7.5) of x * inv_scale, round to nearest (ties to the even code), saturating at 7.5.
+__device__ __forceinline__ uint32_t f32_to_e2m3(float x, float inv_scale) {
+    const uint32_t sign = (__float_as_uint(x) >> 26) & 0x20u;
+    const float a = fabsf(x) * inv_scale;
+    uint32_t code;
+    if (a < 2.f) code = (uint32_t)(int)rintf(a * 8.f);                       // 0..16 (16 = the first code of the next binade)
+    else if (a < 4.f) code = 16u + (uint32_t)(int)rintf((a - 2.f) * 4.f);    // 16..24
+    else code = 24u + (uint32_t)(int)rintf((fminf(a, 7.5f) - 4.f) * 2.f);    // 24..31
+    return sign | code;
+}
+
+typedef __attribute__((__vector_size__(6 * sizeof(uint32_t)))) uint32_t lvr_u32x6;
+typedef __attribute__((__vector_size__(32 * sizeof(float)))) float lvr_f32x32;
+
+// CF = 1: the centre is stored as 128 e4m3 codes in the order the matrix-core operand wants them
 // (byte kq*32 + kk*8 + j holds coordinate kk*32 + kq*8 + j); only for bf16 caches.
-template <typename KT, bool CF8 = false>
+// CF = 2: as 128 e2m3 codes of 6 bits in the same order (bits 6 (kk*8 + j) .. of the 24 bytes at kq*24), times
+// one power-of-two scale per kq: the 32 coordinates of a scale block are the ones a lane of the query
+// kernel holds.  The scale is the smallest power of two that brings the block's largest magnitude to
+// at most 7.5; its biased exponent byte goes into the group's record in `radii` (byte kq of the third word).
+template <typename KT, int CF = 0>
 __global__ void __launch_bounds__(256)
 build_groups_kernel(void *__restrict__ K, void *__restrict__ centres, float *__restrict__ radii,
                     int64_t cap_rows, int64_t max_groups, int64_t g0, int64_t g1, int r, int S, const BuildSrc src) {
@@ -145,8 +164,43 @@ build_groups_kernel(void *__restrict__ K, void *__restrict__ centres, float *__r
 #pragma unroll
     for (int e = 0; e < 8; ++e) c[e] *= inv;
 
-    char *Cb = static_cast<char *>(centres) + ((int64_t)bh * max_groups + g) * LVR_D * (CF8 ? 1 : sizeof(KT));
-    if constexpr (CF8) {
+    constexpr bool CF8 = CF == 1;
+    char *Cb = static_cast<char *>(centres) + ((int64_t)bh * max_groups + g) * (CF == 2 ? LVR_D * 3 / 4 : LVR_D * (CF8 ? 1 : sizeof(KT)));
+    uint32_t scale_bytes = 0;   // CF = 2: the four blocks' exponent bytes (the same in all 16 lanes of the group)
+    (void)scale_bytes;
+    if constexpr (CF == 2) {
+        float amax = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(c[e]));
+        amax = fmaxf(amax, __shfl_xor(amax, 4, 64));    // the lanes of a block: same li & 3
+        amax = fmaxf(amax, __shfl_xor(amax, 8, 64));
+        // smallest E with amax <= 7.5 * 2^E; held to [-100, 120] so that scale, its inverse and every decoded
+        // value are normal numbers (a block beyond that saturates or rounds to zero; the radius measures it)
+        int p;
+        const float f = frexpf(amax, &p);   // amax = f * 2^p, f in [0.5, 1)
+        int E = (amax > 0.f) ? (f <= 0.9375f ? p - 3 : p - 2) : -100;
+        E = E < -100 ? -100 : (E > 120 ? 120 : E);
+        const float scale = __uint_as_float((uint32_t)(E + 127) << 23), inv_scale = __uint_as_float((uint32_t)(127 - E) << 23);
+        uint32_t code[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) code[e] = f32_to_e2m3(c[e], inv_scale);
+        const uint32_t lo = code[0] | (code[1] << 6) | (code[2] << 12) | (code[3] << 18) | (code[4] << 24) | (code[5] << 30);
+        const uint32_t hi = (code[5] >> 2) | (code[6] << 4) | (code[7] << 10);   // 16 bits
+        // from here on: the centre as stored (decoded by the conversion the query kernel uses, in its fp32 form)
+        const lvr_u32x6 src = {lo, hi, 0u, 0u, 0u, 0u};
+        const lvr_f32x32 dec = __builtin_amdgcn_cvt_scalef32_pk32_f32_fp6(src, scale);
+        c[0] = dec[0]; c[1] = dec[1]; c[2] = dec[2]; c[3] = dec[3];
+        c[4] = dec[4]; c[5] = dec[5]; c[6] = dec[6]; c[7] = dec[7];
+        if (valid) {
+            uint16_t *dst = reinterpret_cast<uint16_t *>(Cb + (li & 3) * 24 + (li >> 2) * 6);
+            dst[0] = (uint16_t)lo;
+            dst[1] = (uint16_t)(lo >> 16);
+            dst[2] = (uint16_t)hi;
+        }
+        const int lane = threadIdx.x & 63, base = lane & ~15;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) scale_bytes |= (uint32_t)(__shfl(E, base + b, 64) + 127) << (8 * b);
+    } else if constexpr (CF8) {
         uint32_t code[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) code[e] = f32_to_e4m3(c[e]);
@@ -210,7 +264,7 @@ build_groups_kernel(void *__restrict__ K, void *__restrict__ centres, float *__r
     }
     float rho = sqrtf(max_d2) * (1.0f + 0x1p-12f) + sqrtf(cn2) * 0x1p-12f;
     rho = __uint_as_float(__float_as_uint(rho) + 1u);    // one ulp up (rho >= 0)
-    if constexpr (CF8) {
+    if constexpr (CF != 0) {
         // The radii go out in the form the query's radius step reads them: four bf16 per group (8 bytes),
         // slot s = rho_s rounded UP to bf16's eight significant bits (looser by at most 2^-7 rho_s, never
         // tighter), slots S..3 zero.
@@ -226,7 +280,14 @@ build_groups_kernel(void *__restrict__ K, void *__restrict__ centres, float *__r
             for (int k = 0; k < 4; ++k)
                 if (k == sidx) slot[k] = up >> 16;
         }
-        if (valid && li == 0)
+        if constexpr (CF == 2) {   // 12-byte record: the radii, then the scale bytes
+            if (valid && li == 0) {
+                uint32_t *rec = reinterpret_cast<uint32_t *>(radii) + ((int64_t)bh * max_groups + g) * 3;
+                rec[0] = slot[0] | (slot[1] << 16);
+                rec[1] = slot[2] | (slot[3] << 16);
+                rec[2] = scale_bytes;
+            }
+        } else if (valid && li == 0)
             reinterpret_cast<uint2 *>(radii)[(int64_t)bh * max_groups + g] =
                 make_uint2(slot[0] | (slot[1] << 16), slot[2] | (slot[3] << 16));
     } else {
@@ -369,8 +430,11 @@ hipError_t lvr_launch_build_groups(lvr_index *ix, int64_t g0, int64_t g1, hipStr
                                ix->max_groups, g0, g1, ix->cfg.group_size, src);
         return hipGetLastError();
     }
-    if (ix->cf8)
-        hipLaunchKernelGGL((build_groups_kernel<lvr_bf16_t, true>), grid, dim3(256), 0, st, ix->K, ix->centres, ix->radii,
+    if (ix->cf6)
+        hipLaunchKernelGGL((build_groups_kernel<lvr_bf16_t, 2>), grid, dim3(256), 0, st, ix->K, ix->centres, ix->radii,
+                           ix->cap_rows, ix->max_groups, g0, g1, ix->cfg.group_size, ix->cfg.n_subspaces, src);
+    else if (ix->cf8)
+        hipLaunchKernelGGL((build_groups_kernel<lvr_bf16_t, 1>), grid, dim3(256), 0, st, ix->K, ix->centres, ix->radii,
                            ix->cap_rows, ix->max_groups, g0, g1, ix->cfg.group_size, ix->cfg.n_subspaces, src);
     else if (ix->cfg.kv_dtype == LVR_BF16)
         hipLaunchKernelGGL(build_groups_kernel<lvr_bf16_t>, grid, dim3(256), 0, st, ix->K, ix->centres, ix->radii,

@@ -23,6 +23,9 @@ struct lvr_index {
     int box;               // 1: groups are enclosed by axis-aligned boxes (two rows per group in `centres`)
     int S_store;           // floats per group in `radii` (S for balls, 1 for boxes)
     int cf8;               // 1: centres are stored as e4m3 codes, 128 bytes per group, in matrix-operand order
+    int cf6;               // 1: centres are stored as e2m3 codes with a scale per 32 coordinates, 96 bytes per group,
+                           //    in matrix-operand order; `radii` holds 12 bytes per group (four bf16 radii, four scale bytes)
+    int centre_bytes;      // bytes of one enclosure row in `centres` (256 / 512 in the cache's format, 128, 96)
     int64_t cap_rows;      // arena rows per (sequence, KV head), multiple of 64
     int64_t max_groups;    // cap_rows / r
     int64_t n_total;       // keys held

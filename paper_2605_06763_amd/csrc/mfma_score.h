@@ -279,6 +279,31 @@ __device__ __forceinline__ void lvr_codes_to_a_frags(const uint4 (&raw)[2], uint
     }
 }
 
+// Centres stored as e2m3 codes (6 bits) in operand order with one power-of-two scale per lane piece:
+// a lane's 24 bytes of a row are its 32 codes (code 8 kk + e = coordinate 32 kk + 8 kq + e).  The
+// rows are 96 bytes long, so a piece starts on an 8-byte boundary.
+struct alignas(8) lvr_codes6 {
+    uint32_t w[6];
+};
+__device__ __forceinline__ void lvr_load_a_codes6(const char *__restrict__ base, int64_t row, lvr_codes6 &raw) {
+    const int kq = (threadIdx.x & 63) >> 4;
+    raw = *reinterpret_cast<const lvr_codes6 *>(base + row * (LVR_D * 3 / 4) + kq * 24);
+}
+
+// One conversion instruction turns the 32 codes into the four bf16 operand pieces (exact: a code has 4
+// significant bits); `scales` holds the exponent bytes of the row's four pieces, this lane uses byte kq.
+typedef __attribute__((__vector_size__(6 * sizeof(uint32_t)))) uint32_t lvr_u32x6;
+typedef __attribute__((__vector_size__(32 * sizeof(__bf16)))) __bf16 lvr_bf16x32;
+typedef __attribute__((__vector_size__(16 * sizeof(uint32_t)))) uint32_t lvr_u32x16;
+__device__ __forceinline__ void lvr_codes6_to_a_frags(const lvr_codes6 &raw, uint32_t scales, uint4 (&a)[4]) {
+    const int kq = (threadIdx.x & 63) >> 4;
+    const float scale = __uint_as_float(((scales >> (8 * kq)) & 0xffu) << 23);
+    const lvr_u32x6 src = {raw.w[0], raw.w[1], raw.w[2], raw.w[3], raw.w[4], raw.w[5]};
+    const lvr_u32x16 d = __builtin_bit_cast(lvr_u32x16, __builtin_amdgcn_cvt_scalef32_pk32_bf16_fp6(src, scale));
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) a[kk] = make_uint4(d[4 * kk], d[4 * kk + 1], d[4 * kk + 2], d[4 * kk + 3]);
+}
+
 // D = A . B over the 128 coordinates, then the three query parts are added up.
 // Result valid in lanes with (lane % 16) in [8, 12): score of head hb*4 + lane%16 - 8 for rows
 // 4*(lane/16) + j, j = 0..3.

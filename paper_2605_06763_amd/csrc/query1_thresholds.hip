@@ -24,7 +24,8 @@ __device__ __forceinline__ float seg_sum16(float v, int lanes_per_sub) {
 // part: [batch * n_kv_heads][NB][G][S] maxima of this workgroup's groups.
 // BOX: two rows per group (upper corner, lower corner); the block's bound is sum_c max(q_c lo_c, q_c hi_c)
 // over the block's coordinates plus the group's allowance times the norm of the whole query.
-template <int G, bool CF8, bool BOX = false>
+// CF: 0 centres in the cache's format, 1 e4m3 codes, 2 e2m3 codes with a scale per lane piece (balls only)
+template <int G, int CF, bool BOX = false>
 __global__ void __launch_bounds__(256)
 subspace_max_kernel(const void *__restrict__ centres, const float *__restrict__ radii, const float *__restrict__ q,
                     float *__restrict__ part, int64_t max_groups, int64_t n_groups, int S, int n_kv_heads, int n_q_heads) {
@@ -46,9 +47,25 @@ subspace_max_kernel(const void *__restrict__ centres, const float *__restrict__ 
         qn[h] = sqrtf(seg_sum16(n2, BOX ? 16 : lanes_per_sub)) * (1.0f + 0x1p-20f);
         m[h] = -INFINITY;
     }
-    const char *Cb = static_cast<const char *>(centres) + (int64_t)bh * max_groups * LVR_D * (CF8 ? 1 : 2) * (BOX ? 2 : 1);
+    constexpr bool CF8 = CF == 1;
+    const char *Cb = static_cast<const char *>(centres) + (int64_t)bh * max_groups * (CF == 2 ? LVR_D * 3 / 4 : LVR_D * (CF8 ? 1 : 2)) * (BOX ? 2 : 1);
     auto load_row = [&](int64_t row, float (&x)[8]) {
-        if constexpr (CF8) {
+        if constexpr (CF == 2) {
+            // 96 bytes per row: coordinates 8 li .. 8 li + 7 are the 48 bits at (li & 3) * 24 + (li >> 2) * 6, six
+            // bits per code; their scale is byte li & 3 of the third word of the group's record in `radii`
+            const uint16_t *p = reinterpret_cast<const uint16_t *>(Cb + row * (LVR_D * 3 / 4) + (li & 3) * 24 + (li >> 2) * 6);
+            const uint64_t bits = (uint64_t)p[0] | ((uint64_t)p[1] << 16) | ((uint64_t)p[2] << 32);
+            const uint32_t sb = (reinterpret_cast<const uint32_t *>(radii)[((int64_t)bh * max_groups + row) * 3 + 2] >> (8 * (li & 3))) & 0xffu;
+            const float scale = __uint_as_float(sb << 23);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t code = (uint32_t)(bits >> (6 * e)) & 63u;
+                const uint32_t ex = (code >> 3) & 3u, m = code & 7u;
+                // magnitudes m/8 (ex = 0) or (1 + m/8) 2^(ex-1): all exact in fp32, and so is the product with the scale
+                const float mag = ex == 0 ? (float)m * 0.125f : (1.0f + (float)m * 0.125f) * (float)(1u << (ex - 1));
+                x[e] = (code & 32u) ? -mag * scale : mag * scale;
+            }
+        } else if constexpr (CF8) {
             // 128 e4m3 codes per row in matrix-operand order: coordinates 8 li .. 8 li + 7 are the
             // eight bytes at (li & 3) * 32 + (li >> 2) * 8
             const uint2 w = *reinterpret_cast<const uint2 *>(Cb + row * LVR_D + (li & 3) * 32 + (li >> 2) * 8);
@@ -71,10 +88,10 @@ subspace_max_kernel(const void *__restrict__ centres, const float *__restrict__ 
             load_row(2 * g, x);        // upper corner
             load_row(2 * g + 1, x2);   // lower corner
             rho = radii[(int64_t)bh * max_groups + g];
-        } else if constexpr (CF8) {
+        } else if constexpr (CF != 0) {
             load_row(g, x);
-            // radii as four bf16 per group: slot s = rho_s
-            const uint16_t *rb = reinterpret_cast<const uint16_t *>(radii) + ((int64_t)bh * max_groups + g) * 4;
+            // radii as four bf16 per group: slot s = rho_s (records of 8 bytes, or 12 with the scale bytes of 6-bit centres)
+            const uint16_t *rb = reinterpret_cast<const uint16_t *>(radii) + ((int64_t)bh * max_groups + g) * (CF == 2 ? 6 : 4);
             rho = __uint_as_float((uint32_t)rb[s_l] << 16);
         } else {
             load_row(g, x);
@@ -132,17 +149,20 @@ __global__ void safe_tau_s_kernel(const float *__restrict__ part, const float *_
 template <int G>
 void launch_max(lvr_index *ix, const float *q, float *part, int NB, int64_t n_groups, hipStream_t st) {
     dim3 grid((unsigned)NB, (unsigned)lvr_n_bh(ix));
-    if (ix->box && ix->cf8)
-        hipLaunchKernelGGL((subspace_max_kernel<G, true, true>), grid, dim3(256), 0, st, ix->centres, ix->radii, q, part,
+    if (ix->cf6)
+        hipLaunchKernelGGL((subspace_max_kernel<G, 2>), grid, dim3(256), 0, st, ix->centres, ix->radii, q, part,
+                           ix->max_groups, n_groups, ix->cfg.n_subspaces, ix->cfg.n_kv_heads, ix->cfg.n_q_heads);
+    else if (ix->box && ix->cf8)
+        hipLaunchKernelGGL((subspace_max_kernel<G, 1, true>), grid, dim3(256), 0, st, ix->centres, ix->radii, q, part,
                            ix->max_groups, n_groups, ix->cfg.n_subspaces, ix->cfg.n_kv_heads, ix->cfg.n_q_heads);
     else if (ix->box)
-        hipLaunchKernelGGL((subspace_max_kernel<G, false, true>), grid, dim3(256), 0, st, ix->centres, ix->radii, q, part,
+        hipLaunchKernelGGL((subspace_max_kernel<G, 0, true>), grid, dim3(256), 0, st, ix->centres, ix->radii, q, part,
                            ix->max_groups, n_groups, ix->cfg.n_subspaces, ix->cfg.n_kv_heads, ix->cfg.n_q_heads);
     else if (ix->cf8)
-        hipLaunchKernelGGL((subspace_max_kernel<G, true>), grid, dim3(256), 0, st, ix->centres, ix->radii, q, part,
+        hipLaunchKernelGGL((subspace_max_kernel<G, 1>), grid, dim3(256), 0, st, ix->centres, ix->radii, q, part,
                            ix->max_groups, n_groups, ix->cfg.n_subspaces, ix->cfg.n_kv_heads, ix->cfg.n_q_heads);
     else
-        hipLaunchKernelGGL((subspace_max_kernel<G, false>), grid, dim3(256), 0, st, ix->centres, ix->radii, q, part,
+        hipLaunchKernelGGL((subspace_max_kernel<G, 0>), grid, dim3(256), 0, st, ix->centres, ix->radii, q, part,
                            ix->max_groups, n_groups, ix->cfg.n_subspaces, ix->cfg.n_kv_heads, ix->cfg.n_q_heads);
 }
 

@@ -43,7 +43,8 @@ struct FusedArgs {
 };
 
 // UA = centre tiles per phase-A trip; ENC = 1: boxes instead of balls; Q1 = 1: per-block thresholds (S <= 4);
-// CF8 = 1: centres (balls, S <= 4) or box corners stored as e4m3 codes
+// CF8 = 1: centres (balls, S <= 4) or box corners stored as e4m3 codes; CF8 = 2: centres of balls (S <= 4) stored as
+//     e2m3 codes with a power-of-two scale per lane piece (96 bytes per group, 12-byte records of radii and scales)
 // W = heads per head block: 4 (three exact bf16 terms of four heads in the 16 operand columns; HB blocks) or
 //     8 (two terms of eight heads fill the columns, the rarely non-zero third term has an operand of its own:
 //     one pass per tile for up to eight heads; balls with one threshold per head, HB = 1)
@@ -53,6 +54,8 @@ query_fused_kernel(const FusedArgs a) {
     static_assert(!(Q1 && ENC) || S <= 4, "Query 1 on boxes: blocks of whole MFMA steps");
     static_assert(!Q1 || S <= 4 || !CF8, "8-bit centres: at most four coordinate blocks");
     static_assert(!CF8 || S <= 4, "8-bit centres: at most four coordinate blocks");
+    static_assert(CF8 != 2 || !ENC, "6-bit codes: balls only");
+    constexpr bool C6 = CF8 == 2;
     static_assert(W == 4 || (W == 8 && HB == 1 && !ENC && !Q1), "the eight-head operand serves balls with one threshold per head");
     // RP: the radii of 8-bit balls are stored as bf16 in the radius step's operand form; boxes keep one fp32 allowance per group
     constexpr bool RP = CF8 && !ENC;
@@ -86,8 +89,11 @@ query_fused_kernel(const FusedArgs a) {
     // in flight before the prologue builds the query operand ----
     constexpr int SP = (S <= 4) ? S : 1;      // radii are fetched ahead only when they are few
     // balls: one row per group (the centre); boxes: two rows per group (upper corner, lower corner)
-    const char *Cb = static_cast<const char *>(a.centres) + (int64_t)bh * a.max_groups * LVR_D * (CF8 ? 1 : 2) * (ENC ? 2 : 1);
-    const float *Rb = a.radii + (int64_t)bh * a.max_groups * (RP ? 2 : (ENC ? 1 : S));   // boxes: one allowance per group, whatever S; 8-bit centres: 8 bytes of radii per group (four bf16)
+    const char *Cb = static_cast<const char *>(a.centres) + (int64_t)bh * a.max_groups * (C6 ? LVR_D * 3 / 4 : LVR_D * (CF8 ? 1 : 2)) * (ENC ? 2 : 1);
+    // boxes: one allowance per group, whatever S; 8-bit centres: 8 bytes of radii per group (four bf16); 6-bit centres:
+    // 12 bytes (the radii, then the four scale bytes)
+    constexpr int RW = C6 ? 3 : (RP ? 2 : (ENC ? 1 : S));   // 32-bit words per group in the radii array
+    const float *Rb = a.radii + (int64_t)bh * a.max_groups * RW;
     const int64_t n_tiles = (a.n_groups + 15) >> 4;
     const int64_t tile0 = ((int64_t)blockIdx.x * 4 + wave) * a.tiles_per_wave;
     // RM: the radius term rides on the matrix cores as a fifth step (S <= 4, one threshold per head);
@@ -96,7 +102,9 @@ query_fused_kernel(const FusedArgs a) {
     constexpr bool RM = !Q1 && S <= 4;
     // operands of one trip (UA tiles of 16 groups) as they arrive from HBM
     struct Trip {
-        uint4 av[UA][CF8 ? 2 : 4], av2[ENC ? UA : 1][CF8 ? 2 : 4];
+        uint4 av[C6 ? 1 : UA][CF8 ? 2 : 4], av2[ENC ? UA : 1][CF8 ? 2 : 4];
+        lvr_codes6 c6[C6 ? UA : 1];
+        uint32_t sc[C6 ? UA : 1];   // 6-bit centres: the exponent bytes of the row's four pieces
         float rad[RM ? 1 : UA][4][SP];
         float rrow[(RM && !RP) ? UA : 1][SP];
         uint2 rblk[(RM && RP) ? UA : 1];
@@ -107,13 +115,17 @@ query_fused_kernel(const FusedArgs a) {
     Trip t0, t1;
     auto issueA = [&](Trip &T, int it) {
         auto &av = T.av; auto &av2 = T.av2; auto &rad = T.rad; auto &rrow = T.rrow; auto &rblk = T.rblk;
-        (void)av2; (void)rad; (void)rrow; (void)rblk;
+        auto &c6 = T.c6; auto &sc = T.sc;
+        (void)av; (void)av2; (void)rad; (void)rrow; (void)rblk; (void)c6; (void)sc;
 #pragma unroll
         for (int u = 0; u < UA; ++u) {
             const int64_t g0 = (tile0 + it + u) * 16;
             int64_t g = g0 + n;
             if (g >= a.n_groups) g = a.n_groups - 1;
-            if constexpr (ENC && CF8) {
+            if constexpr (C6) {
+                lvr_load_a_codes6(Cb, g, c6[u]);
+                sc[u] = reinterpret_cast<const uint32_t *>(Rb)[g * 3 + 2];
+            } else if constexpr (ENC && CF8) {
                 lvr_load_a_codes(Cb, 2 * g, av[u]);
                 lvr_load_a_codes(Cb, 2 * g + 1, av2[u]);
             } else if constexpr (ENC) {
@@ -125,7 +137,10 @@ query_fused_kernel(const FusedArgs a) {
                 lvr_load_a_frags(Cb, g, av[u]);
             }
             if constexpr (RM && RP) {
-                rblk[u] = reinterpret_cast<const uint2 *>(Rb)[g];
+                if constexpr (C6) {
+                    const uint32_t *rec = reinterpret_cast<const uint32_t *>(Rb) + g * 3;
+                    rblk[u] = make_uint2(rec[0], rec[1]);
+                } else rblk[u] = reinterpret_cast<const uint2 *>(Rb)[g];
             } else if constexpr (RM) {
                 const float *rp = Rb + g * S;
                 if constexpr (S == 4) {
@@ -144,8 +159,8 @@ query_fused_kernel(const FusedArgs a) {
                     if constexpr (ENC) {   // the box's allowance; S only counts the blocks of Query 1
                         rad[u][j][0] = rp[0];
                     } else if constexpr (RP) {   // four bf16 per group: slot s = rho_s
-                        const uint2 blk = reinterpret_cast<const uint2 *>(Rb)[gj];
-                        const uint32_t w[2] = {blk.x, blk.y};
+                        const uint32_t *rec = reinterpret_cast<const uint32_t *>(Rb) + gj * RW;
+                        const uint32_t w[2] = {rec[0], rec[1]};
 #pragma unroll
                         for (int s = 0; s < S; ++s) rad[u][j][s] = __uint_as_float((w[s / 2] >> (16 * (s & 1))) << 16);
                     } else if constexpr (S == 4) {
@@ -283,7 +298,8 @@ query_fused_kernel(const FusedArgs a) {
         uint32_t mybits = 0;   // lane `it` keeps the 16-bit survivor mask of the wave's tile `it`
         auto scoreA = [&](Trip &T, int it) {
             auto &av = T.av; auto &av2 = T.av2; auto &rad = T.rad; auto &rrow = T.rrow; auto &rblk = T.rblk;
-            (void)av2; (void)rad; (void)rrow; (void)rblk;
+            auto &c6 = T.c6; auto &sc = T.sc;
+            (void)av; (void)av2; (void)rad; (void)rrow; (void)rblk; (void)c6; (void)sc;
 #pragma unroll
             for (int u = 0; u < UA; ++u) {
                 const int64_t g_row = (tile0 + it + u) * 16;
@@ -291,7 +307,9 @@ query_fused_kernel(const FusedArgs a) {
                 uint4 ac[4];   // the tile's operand pieces (decoded from the 8-bit codes if that is how they are stored)
                 uint4 ac2[ENC ? 4 : 1];   // boxes: the lower corners
                 (void)ac2;
-                if constexpr (CF8) {
+                if constexpr (C6) {
+                    lvr_codes6_to_a_frags(c6[u], sc[u], ac);
+                } else if constexpr (CF8) {
                     lvr_codes_to_a_frags(av[u], ac);
                     if constexpr (ENC) lvr_codes_to_a_frags(av2[u], ac2);
                 } else {
@@ -634,7 +652,7 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
                                   int32_t *out_idx, int64_t cap, hipStream_t st, const void *k_new, const void *v_new,
                                   int64_t m_new) {
     if (ix->cfg.kv_dtype != LVR_BF16) return hipErrorInvalidValue;
-    if (tau_s && ((ix->box || ix->cf8) && ix->cfg.n_subspaces > 4)) return hipErrorInvalidValue;
+    if (tau_s && ((ix->box || ix->cf8 || ix->cf6) && ix->cfg.n_subspaces > 4)) return hipErrorInvalidValue;
     FusedArgs a;
     a.tau_s = tau_s;
     a.k_new = k_new;
@@ -715,10 +733,12 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
         }                                                                                                       \
     } while (0)
         if (ix->G <= 4) {
-            if (ix->cf8) LVR_Q1_LAUNCH(1, 1);
+            if (ix->cf6) LVR_Q1_LAUNCH(1, 2);
+            else if (ix->cf8) LVR_Q1_LAUNCH(1, 1);
             else LVR_Q1_LAUNCH(1, 0);
         } else {
-            if (ix->cf8) LVR_Q1_LAUNCH(2, 1);
+            if (ix->cf6) LVR_Q1_LAUNCH(2, 2);
+            else if (ix->cf8) LVR_Q1_LAUNCH(2, 1);
             else LVR_Q1_LAUNCH(2, 0);
         }
 #undef LVR_Q1_LAUNCH
@@ -729,21 +749,27 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
         else hipLaunchKernelGGL((query_fused_kernel<2, 1, 1, 1, 0, 1>), grid, dim3(256), 0, st, a);
         return hipGetLastError();
     }
-    if (ix->cf8) {   // 8-bit centres
+    if (ix->cf8 || ix->cf6) {   // 8-bit or 6-bit centres
         const int S = ix->cfg.n_subspaces;
-#define LVR_F8_LAUNCH(UA, W)                                                                                  \
+#define LVR_F8_LAUNCH(UA, W, CF)                                                                               \
     do {                                                                                                      \
-        if (S == 1) hipLaunchKernelGGL((query_fused_kernel<1, 1, UA, 0, 0, 1, W>), grid, dim3(256), 0, st, a);  \
-        else if (S == 2) hipLaunchKernelGGL((query_fused_kernel<1, 2, UA, 0, 0, 1, W>), grid, dim3(256), 0, st, a); \
-        else hipLaunchKernelGGL((query_fused_kernel<1, 4, UA, 0, 0, 1, W>), grid, dim3(256), 0, st, a);         \
+        if (S == 1) hipLaunchKernelGGL((query_fused_kernel<1, 1, UA, 0, 0, CF, W>), grid, dim3(256), 0, st, a);  \
+        else if (S == 2) hipLaunchKernelGGL((query_fused_kernel<1, 2, UA, 0, 0, CF, W>), grid, dim3(256), 0, st, a); \
+        else hipLaunchKernelGGL((query_fused_kernel<1, 4, UA, 0, 0, CF, W>), grid, dim3(256), 0, st, a);         \
+    } while (0)
+#define LVR_F86_LAUNCH(UA, W)            \
+    do {                                 \
+        if (ix->cf6) LVR_F8_LAUNCH(UA, W, 2); \
+        else LVR_F8_LAUNCH(UA, W, 1);    \
     } while (0)
         if (ix->G <= 4) {
-            if (one) LVR_F8_LAUNCH(1, 4);
-            else LVR_F8_LAUNCH(2, 4);
+            if (one) LVR_F86_LAUNCH(1, 4);
+            else LVR_F86_LAUNCH(2, 4);
         } else {   // up to eight heads in one operand
-            if (one) LVR_F8_LAUNCH(1, 8);
-            else LVR_F8_LAUNCH(2, 8);
+            if (one) LVR_F86_LAUNCH(1, 8);
+            else LVR_F86_LAUNCH(2, 8);
         }
+#undef LVR_F86_LAUNCH
 #undef LVR_F8_LAUNCH
         return hipGetLastError();
     }

@@ -56,7 +56,7 @@ def test_bad_configs_are_rejected_on_the_host(L):
     for bad in (dict(ok, head_dim=64), dict(ok, n_q_heads=30), dict(ok, group_size=3), dict(ok, n_subspaces=32),
                 dict(ok, buffer_size=100), dict(ok, capacity=0), dict(ok, n_q_heads=24, n_kv_heads=8),
                 dict(ok, kv_dtype=7), dict(ok, reservoir_size=257), dict(ok, reservoir_size=-1), dict(ok, flags=16),
-                dict(ok, flags=1 << 31), dict(ok, index_dtype=3)):
+                dict(ok, flags=1 << 31), dict(ok, index_dtype=4)):
         cfg = L.make_config(**bad)
         assert L.lvr_arena_bytes(cfg) == 0
         h = C.c_void_p()

@@ -24,11 +24,11 @@ def G():
 
 def _settings():
     import paper_2605_06763_amd as L
-    return {"r1": dict(group_size=1), "r4": dict(group_size=4),
+    return {"r1": dict(group_size=1), "r4": dict(group_size=4), "r1_fp6": dict(group_size=1, index_dtype=L.LVR_INDEX_FP6),
             "per_subspace_r4_S16": dict(group_size=4, n_subspaces=16, grouping=L.LVR_GROUP_SUBSPACE_TREE)}
 
 
-SETTINGS = ["r1", "r4", "per_subspace_r4_S16"]
+SETTINGS = ["r1", "r4", "per_subspace_r4_S16", "r1_fp6"]
 
 
 @pytest.mark.parametrize("setting", SETTINGS)

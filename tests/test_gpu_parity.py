@@ -910,7 +910,7 @@ _Q1_CASES = [(1, "local", 4), (2, "local", 4), (4, "local", 4), (1, "workload", 
 
 
 # 8-bit centres are built for at most four coordinate blocks
-@pytest.mark.parametrize("S,keys,hq,centres", [c + (f,) for c in _Q1_CASES for f in ("fp8", "same") if f == "same" or c[0] <= 4])
+@pytest.mark.parametrize("S,keys,hq,centres", [c + (f,) for c in _Q1_CASES for f in ("fp8", "fp6", "same") if f == "same" or c[0] <= 4])
 def test_query1_per_subspace_thresholds(G, oracle, S, keys, hq, centres):
     """Safe thresholds (tau_s = tau minus the largest bounds of the other blocks) must give
     Problem 1's set; arbitrary thresholds must give a set between Alg. 3's candidates (oracle's
@@ -921,7 +921,7 @@ def test_query1_per_subspace_thresholds(G, oracle, S, keys, hq, centres):
     K, V = cache.K[:, :1], cache.V[:, :1]
     q = W.make_queries(2, n_q_heads=hq)
     G.say(f"query1 S={S} keys={keys} heads={hq} centres={centres}")
-    idt = G.L.LVR_INDEX_FP8 if centres == "fp8" else G.L.LVR_INDEX_SAME
+    idt = {"fp8": G.L.LVR_INDEX_FP8, "fp6": G.L.LVR_INDEX_FP6, "same": G.L.LVR_INDEX_SAME}[centres]
     with G.Index(K, V, "bf16", hq, group_size=r, n_subspaces=S, index_dtype=idt) as ix:
         n_groups = n // r
         f = _exported_bounds(G, oracle, ix, q, r)                      # [hq][S][groups]
@@ -1237,7 +1237,7 @@ def test_fp8_centres_unsupported_configurations(G):
     assert L.lvr_arena_bytes(L.make_config(**ok)) > 0
     assert L.lvr_arena_bytes(L.make_config(**dict(ok, enclosing=L.LVR_ENCLOSE_AABB, n_subspaces=16))) > 0
     for bad in (dict(ok, kv_dtype=L.LVR_F32), dict(ok, n_subspaces=8),
-                dict(ok, flags=L.LVR_SEPARATE_KERNELS), dict(ok, index_dtype=3)):
+                dict(ok, flags=L.LVR_SEPARATE_KERNELS), dict(ok, index_dtype=4)):
         assert L.lvr_arena_bytes(L.make_config(**bad)) == 0
     # AUTO falls back to the cache's own format where 8-bit centres are not supported
     for kw in (dict(n_subspaces=8), dict(flags=L.LVR_SEPARATE_KERNELS), dict(enclosing=L.LVR_ENCLOSE_AABB)):
@@ -1247,6 +1247,161 @@ def test_fp8_centres_unsupported_configurations(G):
     cfg_auto = L.make_config(batch=1, n_q_heads=8, n_kv_heads=2, capacity=1024)
     cfg_same = L.make_config(batch=1, n_q_heads=8, n_kv_heads=2, capacity=1024, index_dtype=L.LVR_INDEX_SAME)
     assert L.lvr_arena_bytes(cfg_same) - L.lvr_arena_bytes(cfg_auto) == 2 * (1024 // 4) * (128 + 8)
+
+
+# ---------------------------------------------------------------------------------------------
+# Centres stored as 6-bit e2m3 codes with a power-of-two scale per 32 coordinates (LVR_INDEX_FP6)
+# ---------------------------------------------------------------------------------------------
+_E2M3 = np.array(sorted({s * v for s in (-1.0, 1.0)
+                         for v in [m / 8.0 for m in range(8)] + [(1 + m / 8.0) * 2.0 ** (e - 1) for e in (1, 2, 3) for m in range(8)]}))
+
+
+def _scale_blocks(x):
+    """[..., 128] -> [..., 4, 32]: block b holds coordinates 32 kk + 8 b + e (kk = 0..3, e = 0..7)."""
+    return np.moveaxis(x.reshape(x.shape[:-1] + (4, 4, 8)), -2, -3).reshape(x.shape[:-1] + (4, 32))
+
+
+@pytest.mark.parametrize("S", [1, 2, 4])
+@pytest.mark.parametrize("r", [1, 4])
+def test_fp6_centres_enclose_members(G, oracle, S, r):
+    """Exported 6-bit index: within every block of 32 coordinates that share a scale the stored centre is an
+    e2m3 value times the smallest power of two that covers the block's largest mean, and the nearest such value;
+    the balls enclose their members measured against the centres AS STORED and are not looser than the documented
+    widening."""
+    n = 2048
+    cache = _small_cache(2, n)
+    Kc = cache.K
+    with G.Index(Kc, Kc, "bf16", 2, group_size=r, n_subspaces=S, index_dtype=G.L.LVR_INDEX_FP6) as ix:
+        centres, radii, slot_pos, keys = ix.export()
+        st_bytes = G.L.lvr_arena_bytes(G.L.make_config(batch=1, n_q_heads=2, n_kv_heads=2, capacity=n, group_size=r,
+                                                       n_subspaces=S, index_dtype=G.L.LVR_INDEX_FP6))
+        assert st_bytes > 0
+        for h in range(2):
+            c = W.bf16_bits_to_f32(centres[0, h]).reshape(n // r, 128).astype(np.float64)
+            label = (np.arange(n) // r).astype(np.int32)
+            mean, _ = oracle.ball_index(Kc[0, h], label, n // r, S)
+            mb, cb = _scale_blocks(mean), _scale_blocks(c)
+            amax = np.abs(mb).max(axis=-1)
+            E = np.ceil(np.log2(np.maximum(amax, 1e-300) / 7.5))
+            # a block whose largest mean sits within rounding of 7.5 * 2^E may have gone either way: leave it out
+            frac = amax / (7.5 * 2.0 ** E)
+            sure = (frac < 1 - 1e-5) & (frac > 0.5 + 1e-5)
+            assert sure.mean() > 0.99
+            scaled = cb / 2.0 ** E[..., None]
+            assert np.isin(scaled[sure], _E2M3).all(), "a stored centre coordinate is not an e2m3 value times its block's scale"
+            # nearest: no other value of the block's grid is closer to the mean (up to the fp32 error of the mean)
+            target = mb / 2.0 ** E[..., None]
+            pos = np.searchsorted(_E2M3, target)
+            lo = _E2M3[np.clip(pos - 1, 0, _E2M3.size - 1)]
+            hi = _E2M3[np.clip(pos, 0, _E2M3.size - 1)]
+            best = np.minimum(np.abs(target - lo), np.abs(target - hi))
+            assert np.all((np.abs(scaled - target) <= best + 1e-5)[sure])
+            need = oracle.ball_radii_for_centres(Kc[0, h], label, c, S)
+            assert np.all(radii[0, h] >= need), "a member lies outside its ball"
+            cn = np.stack([np.linalg.norm(c[:, a:b], axis=1)
+                           for a, b in (oracle.subspace_range(128, S, s) for s in range(S))], axis=1)
+            assert np.all(radii[0, h] <= (need * (1 + 2.0 ** -11) + cn * 2.0 ** -11) * (1 + 2.0 ** -7) + 1e-30)
+            assert np.array_equal(keys[0, h], W.f32_to_bf16_bits(Kc[0, h]).reshape(n, 128))
+
+
+@pytest.mark.parametrize("n,r,S,hq,grouping", [(1000, 4, 4, 8, "contiguous"), (2051, 1, 4, 16, "contiguous"), (5000, 1, 4, 8, "contiguous"),
+                                               (777, 8, 2, 4, "tree"), (4096, 2, 1, 8, "contiguous"), (3, 4, 4, 8, "contiguous"),
+                                               (3001, 1, 2, 2, "tree"), (70000, 1, 4, 4, "contiguous")])
+def test_fp6_centres_queries(G, oracle, n, r, S, hq, grouping):
+    L = G.L
+    cache = _small_cache(2, n)
+    q = W.make_queries(2, n_q_heads=hq)
+    gr = L.LVR_GROUP_TREE if grouping == "tree" else L.LVR_GROUP_CONTIGUOUS
+    G.say(f"fp6 centres n={n} r={r} S={S} hq={hq} {grouping}")
+    with G.Index(cache.K, cache.V, "bf16", hq, group_size=r, n_subspaces=S, grouping=gr,
+                 index_dtype=L.LVR_INDEX_FP6) as ix:
+        for frac in (0.01, 0.2):
+            tau = G.oracle_taus(oracle, ix, q, frac=frac)
+            for fused in (True, False):
+                idx, cnt, out = ix.query(q, tau, fused=fused)
+                G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=f"fp6 n={n} frac={frac}")
+        st = ix.stats()
+        assert st["bytes_index"] == st["groups_scored"] * (96 + 12)     # codes + four bf16 radii + four scale bytes
+
+
+@pytest.mark.parametrize("S", [1, 4])
+def test_fp6_centres_surviving_groups_and_pruning(G, oracle, S):
+    """On keys with positional locality: the groups kept equal those whose Eq. (2) bound on the exported 6-bit
+    index reaches tau; the index is under half the bytes of bf16 centres and still prunes."""
+    n, r = 8192, 4
+    cache = W.make_local_cache(2, n=n)
+    K, V = cache.K[:, :1], cache.V[:, :1]
+    q = W.make_queries(2, n_q_heads=4)
+    with G.Index(K, V, "bf16", 4, group_size=r, n_subspaces=S, index_dtype=G.L.LVR_INDEX_FP6) as ix, \
+         G.Index(K, V, "bf16", 4, group_size=r, n_subspaces=S, index_dtype=G.L.LVR_INDEX_SAME) as ref:
+        centres, radii, _, _ = ix.export()
+        c = W.bf16_bits_to_f32(centres[0, 0]).reshape(n // r, 128).astype(np.float64)
+        for frac in (0.002, 0.02):
+            t = G.oracle_taus(oracle, ix, q, frac=frac)
+            idx, cnt, out = ix.query(q, t)
+            G.check_step(oracle, ix, q, t, idx, cnt, out, tag=f"fp6 local frac={frac}")
+            st = ix.stats()
+            ref.query(q, t)
+            st_ref = ref.stats()
+            ub = np.stack([oracle.ball_bounds(q[0, h], c, radii[0, 0].astype(np.float64)).sum(0) for h in range(4)])
+            te = t[0] - 0.5e-4 * np.abs(t[0])
+            lo = int(np.any(ub >= te[:, None] * (1 + 1e-5) + 1e-3, axis=0).sum())
+            hi = int(np.any(ub >= te[:, None] * (1 - 1e-5) - 1e-3, axis=0).sum())
+            assert lo <= st["groups_surviving"] <= hi, (frac, lo, st["groups_surviving"], hi)
+            G.say(f"  S={S} frac={frac}: surviving with 6-bit centres {st['groups_surviving']}, with bf16 centres "
+                  f"{st_ref['groups_surviving']} of {st['groups_scored']}")
+            assert st["groups_surviving"] < 0.6 * st["groups_scored"]
+            assert st["bytes_index"] < 0.45 * st_ref["bytes_index"]
+
+
+def test_fp6_centres_surface_keys_wide_range_and_append(G, oracle):
+    """Keys exactly on ball surfaces, blocks whose largest coordinate dwarfs the others (they round to zero under
+    the shared scale; the radius takes up the difference), all-zero groups, appends across flushes: nothing is
+    ever lost."""
+    L = G.L
+    g = np.random.default_rng(13)
+    n, r = 512, 4
+    qdir = np.zeros(128, dtype=np.float32)
+    qdir[[3, 40, 77, 120]] = [1.0, -1.0, 1.0, 1.0]
+    K = np.zeros((1, 1, n, 128), dtype=np.float32)
+    for gi in range(n // r):
+        centre = W.round_to_bf16(g.integers(-8, 9, size=128).astype(np.float32))
+        if gi % 7 == 0:
+            centre[5] = 1000.0
+            centre[99] = -3.0e6
+        if gi % 11 == 0:
+            centre[:] = 0.0
+        if gi % 13 == 0:
+            centre *= 2.0 ** -30
+        step = float(g.integers(1, 5)) * 0.5 * (2.0 ** -30 if gi % 13 == 0 else 1.0)
+        K[0, 0, gi * r + 0] = centre + step * qdir
+        K[0, 0, gi * r + 1] = centre - step * qdir
+        K[0, 0, gi * r + 2] = centre
+        K[0, 0, gi * r + 3] = centre
+    K = W.round_to_bf16(K)
+    V = W.round_to_bf16(g.standard_normal((1, 1, n, 128)).astype(np.float32))
+    q = (qdir * 3.0)[None, None, :]
+    for S, rr in ((1, 4), (4, 4), (4, 1)):
+        with G.Index(K[:, :, :300], V[:, :, :300], "bf16", 1, group_size=rr, n_subspaces=S, capacity=n, buffer_size=32,
+                     index_dtype=L.LVR_INDEX_FP6) as ix:
+            ix.append(K[:, :, 300:], V[:, :, 300:])
+            s = oracle.scores_f32(q[0, 0], K[0, 0])
+            for tau in np.unique(s)[-6:]:
+                t = np.full((1, 1), tau, dtype=np.float32)
+                idx, cnt, out = ix.query(q, t)
+                G.check_step(oracle, ix, q, t, idx, cnt, out, tag=f"fp6 surface S={S} r={rr} tau={tau}")
+
+
+def test_fp6_centres_unsupported_configurations(G):
+    L = G.L
+    ok = dict(batch=1, n_q_heads=8, n_kv_heads=2, capacity=1024, index_dtype=L.LVR_INDEX_FP6)
+    assert L.lvr_arena_bytes(L.make_config(**ok)) > 0
+    for bad in (dict(ok, kv_dtype=L.LVR_F32), dict(ok, n_subspaces=8), dict(ok, flags=L.LVR_SEPARATE_KERNELS),
+                dict(ok, enclosing=L.LVR_ENCLOSE_AABB), dict(ok, grouping=L.LVR_GROUP_SUBSPACE_TREE, n_q_heads=2, n_kv_heads=2)):
+        assert L.lvr_arena_bytes(L.make_config(**bad)) == 0
+    cfg_same = L.make_config(batch=1, n_q_heads=8, n_kv_heads=2, capacity=1024, index_dtype=L.LVR_INDEX_SAME)
+    # bf16 centres: 256 + 16 bytes per group of four keys; 6-bit: 96 + 12
+    assert L.lvr_arena_bytes(cfg_same) - L.lvr_arena_bytes(L.make_config(**ok)) == 2 * (1024 // 4) * (256 + 16 - 96 - 12)
 
 
 # ---------------------------------------------------------------------------------------------
@@ -1273,6 +1428,8 @@ def test_option_combinations(G, oracle, case):
     B = 16 * int(g.choice([1, 2, 4])) * (r if r > 1 else 1)
     n0 = int(g.integers(0, 3000))
     extra = int(g.integers(0, 3 * B))
+    if index_dtype == L.LVR_INDEX_FP8 and case % 2 == 0:
+        index_dtype = L.LVR_INDEX_FP6       # every other explicit 8-bit case asks for 6-bit centres instead
     wl = 1 if case % 5 == 4 else 2          # workload 1 is fp32 with iid keys, workload 2 bf16 with channel scales
     dtype = W.CONFIGS[wl]["dtype"]
     cfg = L.make_config(batch=batch, n_q_heads=hq, n_kv_heads=hkv, group_size=r, n_subspaces=S, buffer_size=B,
