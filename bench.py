@@ -134,14 +134,14 @@ def measure(cid, args, *, group_size, steps, warmup, full, cpu_seconds, legs=Tru
 
     capacity = n0 + (T_all + 64 if appending else 0)
 
-    def make_cfg(r):
+    def make_cfg(r, centres=None):
         return L.make_config(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, kv_dtype=L.LVR_BF16,
                              group_size=r, n_subspaces=args.subspaces, buffer_size=256, capacity=capacity,
                              enclosing=L.LVR_ENCLOSE_AABB if args.enclosing == "aabb" else L.LVR_ENCLOSE_BALL,
                              grouping={"contiguous": L.LVR_GROUP_CONTIGUOUS, "tree": L.LVR_GROUP_TREE,
                                        "subspace": L.LVR_GROUP_SUBSPACE_TREE}[args.grouping],
                              attn_splits=args.attn_splits, query_workgroups=args.query_workgroups,
-                             index_dtype={"auto": L.LVR_INDEX_AUTO, "bf16": L.LVR_INDEX_SAME, "fp8": L.LVR_INDEX_FP8, "fp6": L.LVR_INDEX_FP6}[args.centres],
+                             index_dtype={"auto": L.LVR_INDEX_AUTO, "bf16": L.LVR_INDEX_SAME, "fp8": L.LVR_INDEX_FP8, "fp6": L.LVR_INDEX_FP6}[centres or args.centres],
                              flags=(L.LVR_CONCURRENT_UPDATE if args.concurrent_update else 0)
                              | (L.LVR_KV_IN_HOST_MEMORY if args.offload else 0)
                              | (L.LVR_SEPARATE_KERNELS if args.separate else 0))
@@ -374,6 +374,19 @@ def measure(cid, args, *, group_size, steps, warmup, full, cpu_seconds, legs=Tru
                                    "step_frac_of_peak": round(b4 / (ms4 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         L.lvr_destroy(h4)
 
+    # ---- the same keys with 8-bit centres, when the library's choice was 6 bits ----
+    if full and not appending and legs and args.centres == "auto" and res["index_bytes_per_group"] == 108:
+        h8 = L.lvr_create(make_cfg(group_size, "fp8"))
+        L.lvr_build(h8, Kd, Vd)
+        step8 = step_on(h8)
+        timed(step8, W_steps, 0)
+        ms8 = timed(step8, K_steps, W_steps) / K_steps
+        st8 = L.lvr_get_stats(h8, raise_on_overflow=False)
+        res["centres_fp8"] = {"us_per_step": round(ms8 * 1e3, 2),
+                              "f_scan": round(st8["keys_scanned"] / max(n_bh * st8["n_keys"], 1), 4),
+                              "index_bytes_per_key": round(st8["bytes_index"] / max(n_bh * st8["n_indexed"], 1), 1)}
+        L.lvr_destroy(h8)
+
     # ---- CPU oracle on a bounded sample of the same workload (also checks recall) ----
     if cpu_seconds > 0:
         import oracle
@@ -471,8 +484,8 @@ def main():
     ap.add_argument("--grouping", choices=["contiguous", "tree", "subspace"], default="contiguous",
                     help="'subspace': one tree grouping per subspace with per-key labels (the paper's own layout)")
     ap.add_argument("--centres", choices=["auto", "bf16", "fp8", "fp6"], default="auto",
-                    help="storage of the centres: the cache's bf16, or 8-bit e4m3 codes (half the index read); "
-                         "auto = the library's default (8-bit where supported)")
+                    help="storage of the centres: the cache's bf16, 8-bit e4m3 codes, or 6-bit e2m3 codes with a scale per 32 "
+                         "coordinates; auto = the library's default (6-bit for single-key groups, else 8-bit, where supported)")
     ap.add_argument("--q-heads", type=int, default=0,
                     help="supplementary: query heads per sequence (8, 16, 32 or 64 over the workload's 8 KV heads; "
                          "default: the workload's 32)")
@@ -541,7 +554,7 @@ def main():
                                + (f" [supplementary: {args.qualify_frac} of the keys qualify]" if args.qualify_frac is not None else ""), "batch": B, "n_q_heads": Hq, "n_kv_heads": r["Hkv"],
                    "head_dim": r["d"], "context": r["n_now"], "kv_storage": "bf16", "group_size": args.group_size,
                    "subspaces": args.subspaces, "attn_splits": args.attn_splits, "grouping": args.grouping,
-                   "centres": "fp6" if args.centres == "fp6" else ("fp8" if fp8 else "bf16"), "enclosing": args.enclosing,
+                   "centres": "fp6" if r["index_bytes_per_group"] == 108 else ("fp8" if fp8 else "bf16"), "enclosing": args.enclosing,
                    "index_bytes_per_key": r["index_bytes_per_key"],
                    "step": "append+query+attention" if appending else "query+attention",
                    "update": "two-stream" if args.concurrent_update else "single-stream",
@@ -549,7 +562,7 @@ def main():
                    "device_bytes": int(L.lvr_arena_bytes(r["cfg"])), "host_bytes": int(L.lvr_host_bytes(r["cfg"]))},
     }
     for k in ("roofline", "step_bytes", "set_turnover_per_step", "f_scan", "groups_surviving_frac", "retrieved_per_head",
-              "kernels_us", "profiled_us_per_step", "exact_filter_only", "dense_baseline", "paper_setting_r4",
+              "kernels_us", "profiled_us_per_step", "exact_filter_only", "dense_baseline", "paper_setting_r4", "centres_fp8",
               "step_us_distribution", "cache_cold", "build_ms", "cpu_baseline", "recall", "borderline_extra_keys",
               "max_attention_rel_err"):
         if k in r:
