@@ -38,6 +38,12 @@ struct lvr_emitter {
         int base = 0;
         if (reporting && (lane >> 4) == 0 && count > 0)
             base = atomicAdd(&a.head_count[(hq_base + hl) * LVR_CNT_STRIDE], count);
+        write_out(a, lane, spos, base);
+    }
+
+    // The queued entries go to positions base .. base + count - 1 of their head's list; `base` is read from the
+    // lanes of the first quarter that report a head (the caller has reserved the range).
+    __device__ __forceinline__ void write_out(const lvr_emit_target &a, int lane, const int32_t *spos, int base) {
         __builtin_amdgcn_wave_barrier();
         // four heads: unrolled, the four gathers overlap; eight heads unrolled would keep all eight in
         // registers at once (182 VGPRs in the query kernel), so they go two at a time

@@ -78,6 +78,7 @@ query_fused_kernel(const FusedArgs a) {
     __shared__ int32_t s_queue[4][HB][W][LVR_QCAP];
     __shared__ int32_t s_list[SEG_MAX_GROUPS];
     __shared__ int s_tot[4];
+    __shared__ int s_wcnt[4][HB * W], s_wbase[HB * W];
     const int bh = blockIdx.y;
     const int b = bh / a.n_kv_heads, kvh = bh % a.n_kv_heads;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -630,9 +631,36 @@ query_fused_kernel(const FusedArgs a) {
             if (nvalid[1] > 0) check(std::integral_constant<int, 1>{});
         }
     }
+    // Last flush, once per workgroup instead of once per wave: the four waves add up what they still hold, ONE lane
+    // per head reserves the workgroup's range in the head's list, and every wave writes behind the waves before
+    // it.  Atomics on one counter are served one after the other, and at the end of a launch every wave of the
+    // device arrives at the same few counters at once: a quarter of the atomics is a quarter of that queue.
+    // (Flushes of a full queue in mid-flight stay per wave; they are rare and spread over time.)
 #pragma unroll
     for (int hb = 0; hb < HB; ++hb)
-        if (__ballot(em[hb].count > 0)) em[hb].flush(a.emit, lane, rep[hb], spos);
+        if (rep[hb] && kq == 0) s_wcnt[wave][hb * W + n - 8] = em[hb].count;
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb) {
+            if (rep[hb] && kq == 0) {
+                const int h = hb * W + n - 8;
+                const int tot = s_wcnt[0][h] + s_wcnt[1][h] + s_wcnt[2][h] + s_wcnt[3][h];
+                s_wbase[h] = tot > 0 ? atomicAdd(&a.emit.head_count[(hq0 + h) * LVR_CNT_STRIDE], tot) : 0;
+            }
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) {
+        int base = 0;
+        if (rep[hb] && kq == 0) {
+            const int h = hb * W + n - 8;
+            base = s_wbase[h];
+            for (int w = 0; w < wave; ++w) base += s_wcnt[w][h];
+        }
+        if (__ballot(em[hb].count > 0)) em[hb].write_out(a.emit, lane, spos, base);
+    }
 }
 
 template <int UA, int W>
