@@ -22,7 +22,8 @@
 
 namespace {
 
-constexpr int SEG_MAX_GROUPS = 1024;   // 4 waves x 16 tiles x 16 groups
+constexpr int SEG_MAX_TILES = 32;                          // tiles per wave (at most 64: lane `it` of a wave keeps the mask of its tile `it`)
+constexpr int SEG_MAX_GROUPS = 4 * SEG_MAX_TILES * 16;     // 4 waves x 32 tiles x 16 groups; the survivor list holds 16-bit offsets into the segment
 
 struct FusedArgs {
     const void *centres;
@@ -76,7 +77,7 @@ query_fused_kernel(const FusedArgs a) {
     __shared__ uint4 s_bq2[ENC ? HB : 1][4][64];
     __shared__ float s_qn[HB * W][16];
     __shared__ int32_t s_queue[4][HB][W][LVR_QCAP];
-    __shared__ int32_t s_list[SEG_MAX_GROUPS];
+    __shared__ uint16_t s_list[SEG_MAX_GROUPS];   // surviving groups, as offsets from the segment's first group
     __shared__ int s_tot[4];
     __shared__ int s_wcnt[4][HB * W], s_wbase[HB * W];
     const int bh = blockIdx.y;
@@ -520,7 +521,7 @@ query_fused_kernel(const FusedArgs a) {
             int o = before + (incl - cnt);
 #pragma unroll
             for (int k = 0; k < 16; ++k)
-                if (mybits & (1u << k)) s_list[o++] = (int32_t)(tile0 * 16 + (int64_t)lane * 16 + k);
+                if (mybits & (1u << k)) s_list[o++] = (uint16_t)((wave * a.tiles_per_wave + lane) * 16 + k);
         }
         if (threadIdx.x == 0) a.seg_count[(int64_t)bh * a.max_segs + blockIdx.x] = total;
         __syncthreads();
@@ -562,6 +563,7 @@ query_fused_kernel(const FusedArgs a) {
     const char *Kb = static_cast<const char *>(a.K) + (int64_t)bh * a.cap_rows * LVR_D * 2;
     const int32_t *spos = a.slot_pos ? a.slot_pos + (int64_t)bh * a.cap_rows : nullptr;
     const int rmask = (1 << a.log2r) - 1;
+    const int64_t seg_g0 = (int64_t)blockIdx.x * a.tiles_per_wave * 64;   // first group of this workgroup's segment
     const int64_t tiles = (rows + 15) >> 4;
     // This wave checks tiles wave, wave + 4, wave + 8, ...: m of them, two at a time in two register sets.
     // Rotated form: as soon as a set has been scored the wave's next tile but one is requested into it, so
@@ -578,7 +580,7 @@ query_fused_kernel(const FusedArgs a) {
         nvalid[u] = k >= m ? 0 : (left < 16 ? (int)left : 16);
         if (rowidx >= rows) rowidx = 0;
         slot[u] = direct ? (int)(buf_row0 + rowidx)
-                         : (int)(((int64_t)s_list[rowidx >> a.log2r] << a.log2r) + (rowidx & rmask));
+                         : (int)(((seg_g0 + s_list[rowidx >> a.log2r]) << a.log2r) + (rowidx & rmask));
         lvr_load_a_frags(Kb, slot[u], av[u]);
     };
     auto check = [&](auto u_c) {
@@ -718,7 +720,7 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
     const int64_t target_wgs = ix->cfg.query_workgroups > 0 ? ix->cfg.query_workgroups : 1024;
     const int64_t want = a.n_groups * n_bh / target_wgs;
     int tpw = 1;
-    while (tpw < 16 && (int64_t)tpw * 64 < want) tpw *= 2;
+    while (tpw < SEG_MAX_TILES && (int64_t)tpw * 64 < want) tpw *= 2;
     a.tiles_per_wave = tpw;
     const int seg_groups = tpw * 64;
     a.n_segs = (int)((a.n_groups + seg_groups - 1) / seg_groups);
