@@ -75,8 +75,7 @@ enum lvr_enclosing { LVR_ENCLOSE_BALL = 0, LVR_ENCLOSE_AABB = 1 };
  *         query kernel holds (coordinates 32 kk + 8 b + e, kk = 0..3, e = 0..7, for scale block b), so a
  *         lane decodes its share of a centre with one conversion instruction.  Balls with
  *         n_subspaces <= 4, bf16 caches, the fused query kernel (LVR_E_UNSUPPORTED otherwise).
- *   AUTO: with K/V in device memory, FP6 for balls of a single key (group_size = 1) and FP8 for other balls,
- *         where supported; else SAME. */
+ *   AUTO: FP6 for balls where it is supported and K/V are in device memory, else SAME. */
 enum lvr_index_dtype { LVR_INDEX_AUTO = 0, LVR_INDEX_SAME = 1, LVR_INDEX_FP8 = 2, LVR_INDEX_FP6 = 3 };
 
 enum lvr_flags {

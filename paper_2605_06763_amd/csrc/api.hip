@@ -31,28 +31,23 @@ inline bool fp8_centres_supported(const lvr_config *c) {
     return c->enclosing == LVR_ENCLOSE_AABB || c->n_subspaces <= 4;   // boxes do not look at n_subspaces
 }
 
-// AUTO: 8-bit centres halve the index read, at the price of somewhat larger balls.  That pays when the
-// surviving key rows come from HBM; behind the host link a key row costs a hundred times more than an
-// index byte, so the tighter centres in the cache's own format are kept there.
 // 6-bit centres: balls only (a box corner has to be rounded outwards per coordinate, which a shared scale makes
-// coarse).  AUTO takes them when every key is its own group: the ball is then nothing but the coding error, the
-// index read is the whole bound phase, and 108 instead of 136 bytes per key outweighed the extra survivors on
-// every workload measured (128k keys: 36.9 against 39.9 us per step).  Groups of several keys keep 8 bits:
-// their index is a small part of the step and their radii are dominated by the members' spread.
+// coarse).  AUTO takes them wherever they are supported and K/V are in device memory: a fifth less index
+// outweighed the somewhat larger balls on every workload and group size measured (128k keys, one key per
+// group: 34.1 against 37.2 us per step; groups of four: 60.7 against 62.1 us, on keys with positional locality
+// 24.4 against 25.5 us).  Behind the host link a surviving key row costs a hundred times more than an index
+// byte, so the tighter centres in the cache's own format are kept there.
 inline bool fp6_centres_supported(const lvr_config *c) {
     return fp8_centres_supported(c) && c->enclosing == LVR_ENCLOSE_BALL && c->n_subspaces <= 4;
 }
 inline bool fp6_centres(const lvr_config *c) {
     return c->index_dtype == LVR_INDEX_FP6 ||
-           (c->index_dtype == LVR_INDEX_AUTO && c->group_size == 1 && fp6_centres_supported(c) &&
-            !(c->flags & LVR_KV_IN_HOST_MEMORY));
+           (c->index_dtype == LVR_INDEX_AUTO && fp6_centres_supported(c) && !(c->flags & LVR_KV_IN_HOST_MEMORY));
 }
 
-inline bool fp8_centres(const lvr_config *c) {
-    return c->index_dtype == LVR_INDEX_FP8 ||
-           (c->index_dtype == LVR_INDEX_AUTO && !fp6_centres(c) && fp8_centres_supported(c) && c->enclosing == LVR_ENCLOSE_BALL &&
-            !(c->flags & LVR_KV_IN_HOST_MEMORY));
-}
+// 8-bit centres: asked for explicitly (AUTO's coded format is the 6-bit one, which serves every
+// configuration of balls that this one serves).
+inline bool fp8_centres(const lvr_config *c) { return c->index_dtype == LVR_INDEX_FP8; }
 
 int check_config(const lvr_config *c) {
     if (!c) return LVR_E_INVALID;

@@ -1,9 +1,9 @@
 """The five workloads at their full sizes, checked against the CPU oracle: every head of every
 sampled step by the band rule for the retrieved sets and against the oracle's attention on the
-same lists.  Four index settings each: the launch configuration bench.py times by default (r = 1:
+same lists.  Five index settings each: the launch configuration bench.py times by default (r = 1:
 every key its own group, 6-bit centres, contiguous, fused query kernel, default attention form), the
 paper's printed r = 4 / S = 4 with one shared grouping, the paper's own layout (one tree
-grouping per subspace, r = 4, S = 16, labels per key), and r = 1 with 8-bit centres."""
+grouping per subspace, r = 4, S = 16, labels per key), and r = 1 and r = 4 with 8-bit centres."""
 import math
 
 import numpy as np
@@ -24,11 +24,11 @@ def G():
 
 def _settings():
     import paper_2605_06763_amd as L
-    return {"r1": dict(group_size=1), "r4": dict(group_size=4), "r1_fp8": dict(group_size=1, index_dtype=L.LVR_INDEX_FP8),
+    return {"r1": dict(group_size=1), "r4": dict(group_size=4), "r1_fp8": dict(group_size=1, index_dtype=L.LVR_INDEX_FP8), "r4_fp8": dict(group_size=4, index_dtype=L.LVR_INDEX_FP8),
             "per_subspace_r4_S16": dict(group_size=4, n_subspaces=16, grouping=L.LVR_GROUP_SUBSPACE_TREE)}
 
 
-SETTINGS = ["r1", "r4", "per_subspace_r4_S16", "r1_fp8"]
+SETTINGS = ["r1", "r4", "per_subspace_r4_S16", "r1_fp8", "r4_fp8"]
 
 
 @pytest.mark.parametrize("setting", SETTINGS)

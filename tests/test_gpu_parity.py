@@ -1043,13 +1043,13 @@ def test_offloaded_kv_same_results(G, oracle, grouping, flags):
         L.lvr_publish(ref.h)
         for name, x, y in zip(("centres", "radii", "slot_pos", "keys"), ix.export(), ref.export()):
             assert np.array_equal(np.asarray(x), np.asarray(y)), name
-    # the default centre format: 8-bit in device memory, the cache's own behind the host link
+    # the default centre format: 6-bit in device memory, the cache's own behind the host link
     auto_dev = L.make_config(batch=1, n_q_heads=8, n_kv_heads=2, capacity=1024)
     auto_host = L.make_config(batch=1, n_q_heads=8, n_kv_heads=2, capacity=1024, flags=L.LVR_KV_IN_HOST_MEMORY)
     same_host = L.make_config(batch=1, n_q_heads=8, n_kv_heads=2, capacity=1024, flags=L.LVR_KV_IN_HOST_MEMORY,
                               index_dtype=L.LVR_INDEX_SAME)
     assert L.lvr_arena_bytes(auto_host) == L.lvr_arena_bytes(same_host)
-    assert L.lvr_arena_bytes(auto_dev) - 2 * L.lvr_host_bytes(auto_host) // 2 == L.lvr_arena_bytes(auto_host) - 2 * (1024 // 4) * (128 + 8)   # 8-bit centres: half the centre bytes, radii as four bf16 instead of four floats
+    assert L.lvr_arena_bytes(auto_dev) - 2 * L.lvr_host_bytes(auto_host) // 2 == L.lvr_arena_bytes(auto_host) - 2 * (1024 // 4) * (256 + 16 - 96 - 12)   # 6-bit centres: 96 bytes of codes, 12 of radii (four bf16) and scales, against 256 + four floats
 
 
 # ---------------------------------------------------------------------------------------------
@@ -1246,7 +1246,9 @@ def test_fp8_centres_unsupported_configurations(G):
         assert L.lvr_arena_bytes(cfg_auto) == L.lvr_arena_bytes(cfg_same) > 0
     cfg_auto = L.make_config(batch=1, n_q_heads=8, n_kv_heads=2, capacity=1024)
     cfg_same = L.make_config(batch=1, n_q_heads=8, n_kv_heads=2, capacity=1024, index_dtype=L.LVR_INDEX_SAME)
-    assert L.lvr_arena_bytes(cfg_same) - L.lvr_arena_bytes(cfg_auto) == 2 * (1024 // 4) * (128 + 8)
+    assert L.lvr_arena_bytes(cfg_same) - L.lvr_arena_bytes(cfg_auto) == 2 * (1024 // 4) * (256 + 16 - 96 - 12)   # AUTO: 6-bit centres
+    cfg_fp8 = L.make_config(**ok)
+    assert L.lvr_arena_bytes(cfg_same) - L.lvr_arena_bytes(cfg_fp8) == 2 * (1024 // 4) * (128 + 8)
 
 
 # ---------------------------------------------------------------------------------------------
