@@ -308,7 +308,8 @@ int lvr_get_stats(lvr_index *ix, lvr_stats *out_host);
 
 /* Synchronises the device and copies the index to host memory for inspection (tests check the
  * enclosure invariant on it).  Any pointer may be NULL to skip that part.
- *   centres_host  [batch][n_kv_heads][n_groups][head_dim] of kv_dtype
+ *   centres_host  [batch][n_kv_heads][n_groups][head_dim] of kv_dtype, in coordinate order whatever the
+ *                 storage format: coded centres (FP8, FP6) are decoded, which is exact in bf16
  *                 (AABB: [batch][n_kv_heads][n_groups][2][head_dim], upper corner then lower corner)
  *   radii_host    [batch][n_kv_heads][n_groups][n_subspaces] fp32
  *                 (AABB: [batch][n_kv_heads][n_groups][1], the rounding allowance of the bound)
