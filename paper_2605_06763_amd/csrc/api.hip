@@ -227,9 +227,11 @@ void prof_free(lvr_index *ix) {
 // with one sequence's 32 heads and several hundred retrieved keys each, 32 workgroups cannot gather
 // fast enough and the two-launch form wins (measured crossover: between 32k and 128k keys of context
 // at 0.5-1 % retrieved).  The set sizes are not known on the host, so the context length stands in.
-inline bool one_launch_attention(const lvr_index *ix) {
+inline bool one_launch_attention(const lvr_index *ix, bool carried = false) {
     if (ix->attn_one_launch >= 0) return ix->attn_one_launch != 0;
-    return lvr_n_bhq(ix) >= 128 || ix->n_total <= 65536;
+    // lists that carry their scores take the one-launch kernel with two dependent trips, which moves the
+    // crossover up (128k keys, 656 retrieved per head: 33.4 against 34.0 us per step)
+    return lvr_n_bhq(ix) >= 128 || ix->n_total <= (carried ? 131072 : 65536);
 }
 
 // One grouping per coordinate block: groups [g0, g0 + ng) are formed from arena rows g0*r .. (g0+ng)*r - 1
@@ -594,10 +596,11 @@ int decode_step_impl(lvr_index *ix, const float *q, const float *tau, float *out
     // With one key per group the query launch reads few key rows itself (the survivors of the 8-bit
     // test), so it has nothing to gain from rows the attention touched: the scores are used there too
     // (measured at 128k keys: attention 0.9 us shorter, the query launch unchanged).
-    const bool use_scores = fused && (one_launch_attention(ix) || (ix->cfg.flags & LVR_KV_IN_HOST_MEMORY) ||
-                                      ix->cfg.group_size == 1);
+    const bool scores_whatever_the_form = fused && ((ix->cfg.flags & LVR_KV_IN_HOST_MEMORY) || ix->cfg.group_size == 1);
+    const bool one_launch = one_launch_attention(ix, scores_whatever_the_form);
+    const bool use_scores = fused && (one_launch || scores_whatever_the_form);
     const float *carried = use_scores ? ix->scores : nullptr;
-    if (one_launch_attention(ix)) {   // reads the set sizes from the internal counters and hands them to the caller
+    if (one_launch) {   // reads the set sizes from the internal counters and hands them to the caller
         Timed t(ix, LVR_K_ATTN_PARTIAL, st);
         LVR_HIP(lvr_launch_sparse_attention_wg(ix, q, out_idx, carried, lvr_head_count(ix), LVR_CNT_STRIDE, cap, out, out_count, st));
         ix->counters_dirty = 0;

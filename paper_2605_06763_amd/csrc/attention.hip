@@ -286,6 +286,129 @@ sparse_attention_wg_kernel(const void *__restrict__ K, const void *__restrict__ 
     }
 }
 
+// The one-launch form for lists that carry their scores (the decode step on bf16 caches): the same 1024-thread
+// workgroup per head, with the dependent round trips to memory cut to two.
+//   trip 1  the count AND the positions and scores of the first 1024 list entries: which entries a lane asks for
+//           does not depend on the count (lane (quarter s, j) of wave w asks for entry j of batch w + 16 s, a batch
+//           being 16 consecutive entries), what lies beyond the count is dropped when it arrives;
+//   trip 2  the V rows of ALL the wave's batches (up to four: 16 rows per lane quarter in flight), then the
+//           softmax update over them.
+// sparse_attention_wg_kernel pays count -> positions -> one trip per batch: five in a row for 656 keys per head.
+// Lists longer than 1024 entries take further rounds of two trips each.
+template <typename KT>
+__global__ void __launch_bounds__(1024)
+sparse_attention_wg_carry_kernel(const void *__restrict__ V, const int32_t *__restrict__ pos_slot,
+                                 const int32_t *__restrict__ idx, const float *__restrict__ scores, int64_t score_stride,
+                                 const int32_t *count, int count_stride,   // may alias head_count: not restrict
+                                 int64_t cap, float *__restrict__ out, int64_t cap_rows, int64_t n_total, int n_q_heads,
+                                 int n_kv_heads, int G, float qscale, int32_t *head_count,
+                                 int32_t *__restrict__ head_stat, int32_t *__restrict__ publish_count) {
+    constexpr int NW = 16;
+    __shared__ float s_m[NW], s_l[NW];
+    __shared__ float s_o[NW][LVR_D];
+    const int64_t hq = blockIdx.x;
+    const int b = (int)(hq / n_q_heads), h = (int)(hq % n_q_heads);
+    const int bh = b * n_kv_heads + h / G;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, sub = lane >> 4, li = lane & 15;
+    const int32_t *my_idx = idx + hq * cap;
+    const float *my_sc = scores + hq * score_stride;
+    const char *Vb = static_cast<const char *>(V) + (int64_t)bh * cap_rows * LVR_D * sizeof(KT);
+    const int32_t *pslot = pos_slot ? pos_slot + (int64_t)bh * cap_rows : nullptr;
+
+    // trip 1
+    const int64_t e_rel = (int64_t)(wave + NW * sub) * 16 + li;   // this lane's entry within a round of 1024
+    int32_t pos = (e_rel < cap) ? my_idx[e_rel] : -1;
+    float sc = (e_rel < cap && e_rel < score_stride) ? my_sc[e_rel] : 0.f;
+    int64_t cnt = count[hq * count_stride];
+    const int32_t true_cnt = (int32_t)cnt;
+    if (cnt > cap) cnt = cap;
+    if (cnt < 0) cnt = 0;
+
+    float m = -INFINITY, l = 0.f, acc[8];
+    lvr_zero8(acc);
+    for (int64_t base = 0; base < cnt; base += NW * 64) {   // uniform over the workgroup
+        const int64_t e = base + e_rel;
+        if (base > 0) {
+            pos = (e < cnt) ? my_idx[e] : -1;
+            sc = (e < cnt && e < score_stride) ? my_sc[e] : 0.f;
+        }
+        int myslot = -1;
+        if (e < cnt && pos >= 0 && pos < n_total) myslot = pslot ? pslot[pos] : (int)pos;
+        const float myscore = sc * qscale;
+        // trip 2: batch bq of this wave is entries base + (wave + 16 bq) * 16 ..; row i * 4 + sub of it is held by lane 16 bq + i * 4 + sub
+        lvr_raw8<KT> vr[16];
+        bool have[4];
+#pragma unroll
+        for (int bq = 0; bq < 4; ++bq) {
+            have[bq] = base + (int64_t)(wave + NW * bq) * 16 < cnt;   // wave-uniform
+            if (have[bq]) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int sl = __shfl(myslot, 16 * bq + i * 4 + sub, 64);
+                    lvr_load_raw(Vb, sl < 0 ? 0 : sl, li, vr[bq * 4 + i]);
+                }
+            }
+        }
+#pragma unroll
+        for (int bq = 0; bq < 4; ++bq) {
+            if (have[bq]) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int sl = __shfl(myslot, 16 * bq + i * 4 + sub, 64);
+                    float s = __shfl(myscore, 16 * bq + i * 4 + sub, 64);
+                    s = (sl >= 0) ? s : -INFINITY;
+                    float vx[8];
+                    lvr_unpack(vr[bq * 4 + i], vx);
+                    const float m_new = fmaxf(m, s);
+                    const float alpha = exp2_safe(m, m_new);
+                    const float w = exp2_safe(s, m_new);
+                    l = l * alpha + w;
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) acc[c] = acc[c] * alpha + w * vx[c];
+                    m = m_new;
+                }
+            }
+        }
+    }
+    float m_all = fmaxf(m, __shfl_xor(m, 16, 64));
+    m_all = fmaxf(m_all, __shfl_xor(m_all, 32, 64));
+    const float scl = exp2_safe(m, m_all);
+    l *= scl;
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+        float a = acc[c] * scl;
+        a += __shfl_xor(a, 16, 64);
+        a += __shfl_xor(a, 32, 64);
+        if (sub == 0) s_o[wave][li * 8 + c] = a;
+    }
+    if (lane == 0) {
+        s_m[wave] = m_all;
+        s_l[wave] = l;
+    }
+    __syncthreads();
+    if (threadIdx.x < LVR_D) {
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) M = fmaxf(M, s_m[w]);
+        float num = 0.f, den = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float wt = exp2_safe(s_m[w], M);
+            den += wt * s_l[w];
+            num += wt * s_o[w][threadIdx.x];
+        }
+        out[hq * LVR_D + threadIdx.x] = (den > 0.f && M != -INFINITY) ? num / den : 0.f;
+    }
+    // every thread's read of the count lies before the barrier above, so the counter can be handed over and cleared
+    if (publish_count && threadIdx.x == 0) {
+        publish_count[hq] = true_cnt;
+        head_stat[hq] = true_cnt;
+        head_count[hq * LVR_CNT_STRIDE] = 0;
+    }
+}
+
 // Merge of the partial triples of one query head.  512 threads: thread (slice s, channel c) owns
 // every fourth partial of channel c; its values are requested first, then the weights
 // w_p = 2^(m_p - M) are computed into LDS, the slices are weighted, and the four slices are
@@ -643,7 +766,15 @@ hipError_t lvr_launch_sparse_attention_wg(lvr_index *ix, const float *q, const i
                        ix->n_total, ix->cfg.n_q_heads, ix->cfg.n_kv_heads, ix->G, qscale, lvr_head_count(ix),            \
                        lvr_head_stat(ix), publish_count)
     if (ix->cfg.kv_dtype == LVR_BF16) {
-        if (scores) LVR_WG_LAUNCH(lvr_bf16_t, true);
+        // With more heads than compute units the workgroups queue up behind each other and the lighter kernel wins
+        // (512 heads: 24.0 against 26.0 us); with one workgroup per unit the shorter chain of trips does (32 heads:
+        // 8.4 against 8.7 us at 328 keys per head, 10.5 against 10.9 us at 656).
+        if (scores && n_bhq > 256) LVR_WG_LAUNCH(lvr_bf16_t, true);
+        else if (scores)
+            hipLaunchKernelGGL((sparse_attention_wg_carry_kernel<lvr_bf16_t>), dim3((unsigned)n_bhq), dim3(1024), 0, st, ix->V,
+                               ix->pos_slot, idx, scores, ix->cap_rows, count, count_stride, cap, out, ix->cap_rows,
+                               ix->n_total, ix->cfg.n_q_heads, ix->cfg.n_kv_heads, ix->G, qscale, lvr_head_count(ix),
+                               lvr_head_stat(ix), publish_count);
         else LVR_WG_LAUNCH(lvr_bf16_t, false);
     } else {
         if (scores) LVR_WG_LAUNCH(lvr_f32_t, true);

@@ -44,22 +44,21 @@ struct FusedArgs {
 };
 
 // UA = centre tiles per phase-A trip; ENC = 1: boxes instead of balls; Q1 = 1: per-block thresholds (S <= 4);
-// CF8 = 1: centres (balls, S <= 4) or box corners stored as e4m3 codes; CF8 = 2: centres of balls (S <= 4) stored as
+// CF = 1: centres (balls, S <= 4) or box corners stored as e4m3 codes; CF = 2: centres of balls (S <= 4) stored as
 //     e2m3 codes with a power-of-two scale per lane piece (96 bytes per group, 12-byte records of radii and scales)
 // W = heads per head block: 4 (three exact bf16 terms of four heads in the 16 operand columns; HB blocks) or
 //     8 (two terms of eight heads fill the columns, the rarely non-zero third term has an operand of its own:
 //     one pass per tile for up to eight heads; balls with one threshold per head, HB = 1)
-template <int HB, int S, int UA, int ENC, int Q1 = 0, int CF8 = 0, int W = 4>
+template <int HB, int S, int UA, int ENC, int Q1 = 0, int CF = 0, int W = 4>
 __global__ void __launch_bounds__(256)
 query_fused_kernel(const FusedArgs a) {
     static_assert(!(Q1 && ENC) || S <= 4, "Query 1 on boxes: blocks of whole MFMA steps");
-    static_assert(!Q1 || S <= 4 || !CF8, "8-bit centres: at most four coordinate blocks");
-    static_assert(!CF8 || S <= 4, "8-bit centres: at most four coordinate blocks");
-    static_assert(CF8 != 2 || !ENC, "6-bit codes: balls only");
-    constexpr bool C6 = CF8 == 2;
+    static_assert(!CF || S <= 4, "coded centres: at most four coordinate blocks");
+    static_assert(CF != 2 || !ENC, "6-bit codes: balls only");
+    constexpr bool C6 = CF == 2;
     static_assert(W == 4 || (W == 8 && HB == 1 && !ENC && !Q1), "the eight-head operand serves balls with one threshold per head");
     // RP: the radii of 8-bit balls are stored as bf16 in the radius step's operand form; boxes keep one fp32 allowance per group
-    constexpr bool RP = CF8 && !ENC;
+    constexpr bool RP = CF && !ENC;
     // the staging area of the query operand is dead once every wave holds its fragments; the score
     // queues of the emitters live in the same bytes afterwards
     __shared__ union {
@@ -91,7 +90,7 @@ query_fused_kernel(const FusedArgs a) {
     // in flight before the prologue builds the query operand ----
     constexpr int SP = (S <= 4) ? S : 1;      // radii are fetched ahead only when they are few
     // balls: one row per group (the centre); boxes: two rows per group (upper corner, lower corner)
-    const char *Cb = static_cast<const char *>(a.centres) + (int64_t)bh * a.max_groups * (C6 ? LVR_D * 3 / 4 : LVR_D * (CF8 ? 1 : 2)) * (ENC ? 2 : 1);
+    const char *Cb = static_cast<const char *>(a.centres) + (int64_t)bh * a.max_groups * (C6 ? LVR_D * 3 / 4 : LVR_D * (CF ? 1 : 2)) * (ENC ? 2 : 1);
     // boxes: one allowance per group, whatever S; 8-bit centres: 8 bytes of radii per group (four bf16); 6-bit centres:
     // 12 bytes (the radii, then the four scale bytes)
     constexpr int RW = C6 ? 3 : (RP ? 2 : (ENC ? 1 : S));   // 32-bit words per group in the radii array
@@ -104,7 +103,7 @@ query_fused_kernel(const FusedArgs a) {
     constexpr bool RM = !Q1 && S <= 4;
     // operands of one trip (UA tiles of 16 groups) as they arrive from HBM
     struct Trip {
-        uint4 av[C6 ? 1 : UA][CF8 ? 2 : 4], av2[ENC ? UA : 1][CF8 ? 2 : 4];
+        uint4 av[C6 ? 1 : UA][CF ? 2 : 4], av2[ENC ? UA : 1][CF ? 2 : 4];
         lvr_codes6 c6[C6 ? UA : 1];
         uint32_t sc[C6 ? UA : 1];   // 6-bit centres: the exponent bytes of the row's four pieces
         float rad[RM ? 1 : UA][4][SP];
@@ -113,7 +112,7 @@ query_fused_kernel(const FusedArgs a) {
     };
     // 8-bit centres leave room for two trips in registers: the next trip's loads are issued before
     // the current trip is scored, so the memory pipe does not drain between trips
-    constexpr bool DB = CF8 && !Q1;
+    constexpr bool DB = CF && !Q1;
     Trip t0, t1;
     auto issueA = [&](Trip &T, int it) {
         auto &av = T.av; auto &av2 = T.av2; auto &rad = T.rad; auto &rrow = T.rrow; auto &rblk = T.rblk;
@@ -127,13 +126,13 @@ query_fused_kernel(const FusedArgs a) {
             if constexpr (C6) {
                 lvr_load_a_codes6(Cb, g, c6[u]);
                 sc[u] = reinterpret_cast<const uint32_t *>(Rb)[g * 3 + 2];
-            } else if constexpr (ENC && CF8) {
+            } else if constexpr (ENC && CF) {
                 lvr_load_a_codes(Cb, 2 * g, av[u]);
                 lvr_load_a_codes(Cb, 2 * g + 1, av2[u]);
             } else if constexpr (ENC) {
                 lvr_load_a_frags(Cb, 2 * g, av[u]);
                 lvr_load_a_frags(Cb, 2 * g + 1, av2[u]);
-            } else if constexpr (CF8) {
+            } else if constexpr (CF) {
                 lvr_load_a_codes(Cb, g, av[u]);
             } else {
                 lvr_load_a_frags(Cb, g, av[u]);
@@ -311,7 +310,7 @@ query_fused_kernel(const FusedArgs a) {
                 (void)ac2;
                 if constexpr (C6) {
                     lvr_codes6_to_a_frags(c6[u], sc[u], ac);
-                } else if constexpr (CF8) {
+                } else if constexpr (CF) {
                     lvr_codes_to_a_frags(av[u], ac);
                     if constexpr (ENC) lvr_codes_to_a_frags(av2[u], ac2);
                 } else {
@@ -734,11 +733,11 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
     const bool one = tpw == 1;
     if (tau_s && ix->box) {   // Query 1 on boxes: per-block box bounds, blocks of whole MFMA steps
         const int S = ix->cfg.n_subspaces;
-#define LVR_Q1B_LAUNCH(HB, CF8)                                                                                 \
+#define LVR_Q1B_LAUNCH(HB, CF)                                                                                 \
     do {                                                                                                        \
-        if (S == 1) hipLaunchKernelGGL((query_fused_kernel<HB, 1, 1, 1, 1, CF8>), grid, dim3(256), 0, st, a);   \
-        else if (S == 2) hipLaunchKernelGGL((query_fused_kernel<HB, 2, 1, 1, 1, CF8>), grid, dim3(256), 0, st, a); \
-        else hipLaunchKernelGGL((query_fused_kernel<HB, 4, 1, 1, 1, CF8>), grid, dim3(256), 0, st, a);          \
+        if (S == 1) hipLaunchKernelGGL((query_fused_kernel<HB, 1, 1, 1, 1, CF>), grid, dim3(256), 0, st, a);   \
+        else if (S == 2) hipLaunchKernelGGL((query_fused_kernel<HB, 2, 1, 1, 1, CF>), grid, dim3(256), 0, st, a); \
+        else hipLaunchKernelGGL((query_fused_kernel<HB, 4, 1, 1, 1, CF>), grid, dim3(256), 0, st, a);          \
     } while (0)
         if (ix->G <= 4) {
             if (ix->cf8) LVR_Q1B_LAUNCH(1, 1);
@@ -752,12 +751,12 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
     }
     if (tau_s) {   // Query 1: per-block thresholds
         const int S = ix->cfg.n_subspaces;
-#define LVR_Q1_LAUNCH(HB, CF8)                                                                                  \
+#define LVR_Q1_LAUNCH(HB, CF)                                                                                  \
     do {                                                                                                        \
-        if (S == 1) hipLaunchKernelGGL((query_fused_kernel<HB, 1, 1, 0, 1, CF8>), grid, dim3(256), 0, st, a);   \
-        else if (S == 2) hipLaunchKernelGGL((query_fused_kernel<HB, 2, 1, 0, 1, CF8>), grid, dim3(256), 0, st, a); \
-        else if (S == 4) hipLaunchKernelGGL((query_fused_kernel<HB, 4, 1, 0, 1, CF8>), grid, dim3(256), 0, st, a); \
-        else if constexpr (!CF8) {                                                                              \
+        if (S == 1) hipLaunchKernelGGL((query_fused_kernel<HB, 1, 1, 0, 1, CF>), grid, dim3(256), 0, st, a);   \
+        else if (S == 2) hipLaunchKernelGGL((query_fused_kernel<HB, 2, 1, 0, 1, CF>), grid, dim3(256), 0, st, a); \
+        else if (S == 4) hipLaunchKernelGGL((query_fused_kernel<HB, 4, 1, 0, 1, CF>), grid, dim3(256), 0, st, a); \
+        else if constexpr (!CF) {                                                                              \
             if (S == 8) hipLaunchKernelGGL((query_fused_kernel<HB, 8, 1, 0, 1, 0>), grid, dim3(256), 0, st, a); \
             else hipLaunchKernelGGL((query_fused_kernel<HB, 16, 1, 0, 1, 0>), grid, dim3(256), 0, st, a);       \
         }                                                                                                       \
@@ -781,26 +780,26 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
     }
     if (ix->cf8 || ix->cf6) {   // 8-bit or 6-bit centres
         const int S = ix->cfg.n_subspaces;
-#define LVR_F8_LAUNCH(UA, W, CF)                                                                               \
+#define LVR_CODED_LAUNCH(UA, W, CF)                                                                               \
     do {                                                                                                      \
         if (S == 1) hipLaunchKernelGGL((query_fused_kernel<1, 1, UA, 0, 0, CF, W>), grid, dim3(256), 0, st, a);  \
         else if (S == 2) hipLaunchKernelGGL((query_fused_kernel<1, 2, UA, 0, 0, CF, W>), grid, dim3(256), 0, st, a); \
         else hipLaunchKernelGGL((query_fused_kernel<1, 4, UA, 0, 0, CF, W>), grid, dim3(256), 0, st, a);         \
     } while (0)
-#define LVR_F86_LAUNCH(UA, W)            \
+#define LVR_CODED_ANY_LAUNCH(UA, W)            \
     do {                                 \
-        if (ix->cf6) LVR_F8_LAUNCH(UA, W, 2); \
-        else LVR_F8_LAUNCH(UA, W, 1);    \
+        if (ix->cf6) LVR_CODED_LAUNCH(UA, W, 2); \
+        else LVR_CODED_LAUNCH(UA, W, 1);    \
     } while (0)
         if (ix->G <= 4) {
-            if (one) LVR_F86_LAUNCH(1, 4);
-            else LVR_F86_LAUNCH(2, 4);
+            if (one) LVR_CODED_ANY_LAUNCH(1, 4);
+            else LVR_CODED_ANY_LAUNCH(2, 4);
         } else {   // up to eight heads in one operand
-            if (one) LVR_F86_LAUNCH(1, 8);
-            else LVR_F86_LAUNCH(2, 8);
+            if (one) LVR_CODED_ANY_LAUNCH(1, 8);
+            else LVR_CODED_ANY_LAUNCH(2, 8);
         }
-#undef LVR_F86_LAUNCH
-#undef LVR_F8_LAUNCH
+#undef LVR_CODED_ANY_LAUNCH
+#undef LVR_CODED_LAUNCH
         return hipGetLastError();
     }
     if (ix->box) {   // boxes: one allowance per group, one tile (two rows per group) per trip
