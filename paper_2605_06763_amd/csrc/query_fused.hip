@@ -483,8 +483,24 @@ query_fused_kernel(const FusedArgs a) {
             }
         };
         auto more = [&](int it) { return it < a.tiles_per_wave && tile0 + it < n_tiles; };   // wave-uniform
+        // Fair shares of a SIMD.  Its four resident waves belong to four workgroups, and at equal priority the
+        // arbiter serves the OLDEST first: measured with per-workgroup timestamps, the workgroups dispatched first
+        // finished this loop in 9.2 us and those dispatched last in 12.7 us (with the priorities set the other way
+        // round the order flips), so the launch waited for the youngest quarter.  Every wave therefore changes its
+        // priority with every pair of trips, starting from its workgroup's place in the dispatch order
+        // (workgroups 256 apart share a compute unit): each of the four is on top a quarter of the time.
+        const int prio_phase = (int)((blockIdx.y * gridDim.x + blockIdx.x) >> 8);
+        auto take_turn = [&](int turn) {
+            switch ((prio_phase + turn) & 3) {
+                case 0: __builtin_amdgcn_s_setprio(0); break;
+                case 1: __builtin_amdgcn_s_setprio(1); break;
+                case 2: __builtin_amdgcn_s_setprio(2); break;
+                default: __builtin_amdgcn_s_setprio(3); break;
+            }
+        };
         if constexpr (DB) {
             for (int it = 0; more(it); it += 2 * UA) {
+                take_turn(it / (2 * UA));
                 const bool m1 = more(it + UA);
                 if (m1) issueA(t1, it + UA);
                 scoreA(t0, it);
@@ -500,6 +516,7 @@ query_fused_kernel(const FusedArgs a) {
                 scoreA(t0, it);
             }
         }
+        if constexpr (DB) __builtin_amdgcn_s_setprio(0);
         // compaction of the four waves' masks into the LDS list
         const int cnt = __popc(mybits);
         int incl = cnt;
