@@ -275,6 +275,22 @@ query_fused_kernel(const FusedArgs a) {
                 taus[hb][s] = rep[hb] ? lvr_effective_tau(a.tau_s[(hq0 + hb * 4 + n - 8) * S + s]) : INFINITY;
     }
 
+    // Fair shares of a SIMD.  Its four resident waves belong to four workgroups, and at equal priority the
+    // arbiter serves the OLDEST first: measured with per-workgroup timestamps, the workgroups dispatched first
+    // finished the bound loop in 9.2 us and those dispatched last in 12.7 us (with the priorities set the other way
+    // round the order flips), so the launch waited for the youngest quarter.  Every wave therefore changes its
+    // priority with every pair of trips (bound phase) or of row tiles (key-row phase), starting from its workgroup's place in the dispatch order
+    // (workgroups 256 apart share a compute unit): each of the four is on top a quarter of the time.
+    const int prio_phase = (int)((blockIdx.y * gridDim.x + blockIdx.x) >> 8);
+    auto take_turn = [&](int turn) {
+        switch ((prio_phase + turn) & 3) {
+            case 0: __builtin_amdgcn_s_setprio(0); break;
+            case 1: __builtin_amdgcn_s_setprio(1); break;
+            case 2: __builtin_amdgcn_s_setprio(2); break;
+            default: __builtin_amdgcn_s_setprio(3); break;
+        }
+    };
+
     int64_t rows;          // key rows phase B has to check
     int64_t buf_row0 = 0;
     const bool direct = buffer_wg || a.skip_bounds;   // phase B walks a run of consecutive rows, not a survivor list
@@ -483,21 +499,6 @@ query_fused_kernel(const FusedArgs a) {
             }
         };
         auto more = [&](int it) { return it < a.tiles_per_wave && tile0 + it < n_tiles; };   // wave-uniform
-        // Fair shares of a SIMD.  Its four resident waves belong to four workgroups, and at equal priority the
-        // arbiter serves the OLDEST first: measured with per-workgroup timestamps, the workgroups dispatched first
-        // finished this loop in 9.2 us and those dispatched last in 12.7 us (with the priorities set the other way
-        // round the order flips), so the launch waited for the youngest quarter.  Every wave therefore changes its
-        // priority with every pair of trips, starting from its workgroup's place in the dispatch order
-        // (workgroups 256 apart share a compute unit): each of the four is on top a quarter of the time.
-        const int prio_phase = (int)((blockIdx.y * gridDim.x + blockIdx.x) >> 8);
-        auto take_turn = [&](int turn) {
-            switch ((prio_phase + turn) & 3) {
-                case 0: __builtin_amdgcn_s_setprio(0); break;
-                case 1: __builtin_amdgcn_s_setprio(1); break;
-                case 2: __builtin_amdgcn_s_setprio(2); break;
-                default: __builtin_amdgcn_s_setprio(3); break;
-            }
-        };
         if constexpr (DB) {
             for (int it = 0; more(it); it += 2 * UA) {
                 take_turn(it / (2 * UA));
@@ -636,6 +637,7 @@ query_fused_kernel(const FusedArgs a) {
         request(std::integral_constant<int, 0>{}, 0);
         request(std::integral_constant<int, 1>{}, 1);
         for (int64_t k = 0; k < m; k += 2) {
+            take_turn((int)(k >> 1));
             check(std::integral_constant<int, 0>{});
             request(std::integral_constant<int, 0>{}, k + 2);
             if (nvalid[1] > 0) check(std::integral_constant<int, 1>{});   // wave-uniform
@@ -643,12 +645,14 @@ query_fused_kernel(const FusedArgs a) {
         }
     } else {
         for (int64_t k = 0; k < m; k += 2) {   // both sets requested, then both scored
+            take_turn((int)(k >> 1));
             request(std::integral_constant<int, 0>{}, k);
             request(std::integral_constant<int, 1>{}, k + 1);   // past the end: a repeat of the last tile, not scored
             check(std::integral_constant<int, 0>{});
             if (nvalid[1] > 0) check(std::integral_constant<int, 1>{});
         }
     }
+    __builtin_amdgcn_s_setprio(0);
     // Last flush, once per workgroup instead of once per wave: the four waves add up what they still hold, ONE lane
     // per head reserves the workgroup's range in the head's list, and every wave writes behind the waves before
     // it.  Atomics on one counter are served one after the other, and at the end of a launch every wave of the
