@@ -49,8 +49,11 @@ struct FusedArgs {
 // W = heads per head block: 4 (three exact bf16 terms of four heads in the 16 operand columns; HB blocks) or
 //     8 (two terms of eight heads fill the columns, the rarely non-zero third term has an operand of its own:
 //     one pass per tile for up to eight heads; balls with one threshold per head, HB = 1)
+// Four waves per SIMD (four workgroups per compute unit) are asked for wherever the kernel fits 128 registers: one
+// head block of balls with at most four coordinate blocks, and the eight-head operand.  Left to itself the compiler
+// has filled 128 vector registers and then needed four accumulator registers more, which costs a quarter of the waves.
 template <int HB, int S, int UA, int ENC, int Q1 = 0, int CF = 0, int W = 4>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, ((HB == 1 && !ENC && S <= 4) || W == 8) ? 4 : 1)
 query_fused_kernel(const FusedArgs a) {
     static_assert(!(Q1 && ENC) || S <= 4, "Query 1 on boxes: blocks of whole MFMA steps");
     static_assert(!CF || S <= 4, "coded centres: at most four coordinate blocks");
@@ -75,6 +78,7 @@ query_fused_kernel(const FusedArgs a) {
     __shared__ float s_qs2[BL ? 4 : 1][BL ? HB : 1][W][BL ? LVR_QCAP : 1];
     __shared__ uint4 s_bq2[ENC ? HB : 1][4][64];
     __shared__ float s_qn[HB * W][16];
+    __shared__ float s_qpart[HB * 4][4];   // squared norm of q_h over the 32 coordinates of MFMA step kk (NQ only)
     __shared__ int32_t s_queue[4][HB][W][LVR_QCAP];
     __shared__ uint16_t s_list[SEG_MAX_GROUPS];   // surviving groups, as offsets from the segment's first group
     __shared__ int s_tot[4];
@@ -182,13 +186,18 @@ query_fused_kernel(const FusedArgs a) {
     // are still on their way, instead of waiting behind them.
     float qraw[W == 4 ? HB : 1][8];   // this lane's share of q for the operand pieces it builds
     float qnv[8];                     // and for the norms
-    (void)qraw;
+    (void)qraw; (void)qnv;
     if constexpr (W == 4) {
 #pragma unroll
         for (int hb = 0; hb < HB; ++hb) lvr_q_frag_load(a.q + hq0 * LVR_D, a.G, hb, wave, qraw[hb]);
     }
-    const bool norm_thread = !buffer_wg && (int)threadIdx.x < HB * W * 16 && (int)(threadIdx.x >> 4) < a.G;
-    {
+    // NQ: with at most four coordinate blocks every block is a whole number of MFMA steps, and wave kk has just asked
+    // for the 32 coordinates of step kk of every head: the norms come out of those values, and q is read once per
+    // workgroup instead of twice (a thousand workgroups ask for the same few lines at the same moment; measured
+    // with per-workgroup timestamps, the operand was ready 1.7 to 4.9 us after entry)
+    constexpr bool NQ = W == 4 && S <= 4;
+    const bool norm_thread = !NQ && !buffer_wg && (int)threadIdx.x < HB * W * 16 && (int)(threadIdx.x >> 4) < a.G;
+    if constexpr (!NQ) {
         const float *qh = a.q + (hq0 + (norm_thread ? (threadIdx.x >> 4) : 0)) * LVR_D + (threadIdx.x & 15) * 8;
         const float4 x = *reinterpret_cast<const float4 *>(qh), y = *reinterpret_cast<const float4 *>(qh + 4);
         qnv[0] = x.x; qnv[1] = x.y; qnv[2] = x.z; qnv[3] = x.w;
@@ -205,7 +214,19 @@ query_fused_kernel(const FusedArgs a) {
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- prologue: subspace norms of q (phase A only) and the B operand of q ----
-    if (!buffer_wg && (int)threadIdx.x < HB * W * 16) {
+    if constexpr (NQ) {
+        // the lanes that build the leading terms (columns 0..3) hold q itself: 8 values per lane, 32 per head over
+        // the four lane quarters
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb) {
+            float ss = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ss += qraw[hb][e] * qraw[hb][e];
+            ss += __shfl_xor(ss, 16, 64);
+            ss += __shfl_xor(ss, 32, 64);
+            if (lane < 4 && hb * 4 + lane < a.G) s_qpart[hb * 4 + lane][wave] = ss;
+        }
+    } else if (!buffer_wg && (int)threadIdx.x < HB * W * 16) {
         const int h = threadIdx.x >> 4, li = threadIdx.x & 15;
         float ss = 0.f;
         if (h < a.G) {
@@ -224,6 +245,19 @@ query_fused_kernel(const FusedArgs a) {
     if constexpr (W == 8) third = lvr_build_q_frags8_wg(a.q + hq0 * LVR_D, a.G, 1.0f, s_bq8);   // syncs
     else lvr_exchange_q_frags_wg<HB>(qraw, a.G, 1.0f, s_u.bq, bq, ENC ? 1 : 0);   // syncs
     if constexpr (ENC) lvr_exchange_q_frags_wg<HB>(qraw, a.G, 1.0f, s_bq2, bq2, -1);
+    if constexpr (NQ) {
+        // after the barrier of the exchange: every wave forms the block norms it is about to read and stores them
+        // (four waves store the same values; a wave's own stores precede its own loads)
+        if (lane < HB * 4 * S && lane / S < a.G) {
+            const int h = lane / S, sb = lane % S;
+            constexpr int SPB = 4 / S;   // steps per block
+            float ss = 0.f;
+#pragma unroll
+            for (int k = 0; k < SPB; ++k) ss += s_qpart[h][sb * SPB + k];
+            s_qn[h][sb] = sqrtf(ss) * (1.0f + 0x1p-20f);   // rounded up
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
     // BL: the pieces of head block hb, fetched anew at every use (the index register comes out of an
     // opaque instruction so that the loads are not hoisted out of the loops and kept in registers)
     auto fetch_bq = [&](int hb, lvr_bf16x8 (&b)[4]) {
