@@ -324,6 +324,7 @@ sparse_attention_wg_carry_kernel(const void *__restrict__ V, const int32_t *__re
     if (cnt > cap) cnt = cap;
     if (cnt < 0) cnt = 0;
 
+    // m and l are the same in all lanes of the wave; acc holds the partial sums of this lane quarter's rows
     float m = -INFINITY, l = 0.f, acc[8];
     lvr_zero8(acc);
     for (int64_t base = 0; base < cnt; base += NW * 64) {   // uniform over the workgroup
@@ -334,7 +335,6 @@ sparse_attention_wg_carry_kernel(const void *__restrict__ V, const int32_t *__re
         }
         int myslot = -1;
         if (e < cnt && pos >= 0 && pos < n_total) myslot = pslot ? pslot[pos] : (int)pos;
-        const float myscore = sc * qscale;
         // trip 2: batch bq of this wave is entries base + (wave + 16 bq) * 16 ..; row i * 4 + sub of it is held by lane 16 bq + i * 4 + sub
         lvr_raw8<KT> vr[16];
         bool have[4];
@@ -349,36 +349,41 @@ sparse_attention_wg_carry_kernel(const void *__restrict__ V, const int32_t *__re
                 }
             }
         }
+        if (!have[0]) continue;   // wave-uniform: none of this wave's batches holds an entry in this round
+        // The scores are here already, so the softmax weights of all 64 entries are formed while the rows travel:
+        // one maximum and one sum over the wave, one exponential per lane, instead of a chain of rescalings per row.
+        const float s_e = (myslot >= 0) ? sc * qscale : -INFINITY;
+        float mw = s_e;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) mw = fmaxf(mw, __shfl_xor(mw, off, 64));
+        const float m_new = fmaxf(m, mw);
+        const float w_e = exp2_safe(s_e, m_new);
+        float lw = w_e;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) lw += __shfl_xor(lw, off, 64);
+        const float alpha = exp2_safe(m, m_new);
+        l = l * alpha + lw;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[c] *= alpha;
+        m = m_new;
 #pragma unroll
         for (int bq = 0; bq < 4; ++bq) {
             if (have[bq]) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const int sl = __shfl(myslot, 16 * bq + i * 4 + sub, 64);
-                    float s = __shfl(myscore, 16 * bq + i * 4 + sub, 64);
-                    s = (sl >= 0) ? s : -INFINITY;
+                    const float w = __shfl(w_e, 16 * bq + i * 4 + sub, 64);   // 0 for a masked entry
                     float vx[8];
                     lvr_unpack(vr[bq * 4 + i], vx);
-                    const float m_new = fmaxf(m, s);
-                    const float alpha = exp2_safe(m, m_new);
-                    const float w = exp2_safe(s, m_new);
-                    l = l * alpha + w;
 #pragma unroll
-                    for (int c = 0; c < 8; ++c) acc[c] = acc[c] * alpha + w * vx[c];
-                    m = m_new;
+                    for (int c = 0; c < 8; ++c) acc[c] += w * vx[c];
                 }
             }
         }
     }
-    float m_all = fmaxf(m, __shfl_xor(m, 16, 64));
-    m_all = fmaxf(m_all, __shfl_xor(m_all, 32, 64));
-    const float scl = exp2_safe(m, m_all);
-    l *= scl;
-    l += __shfl_xor(l, 16, 64);
-    l += __shfl_xor(l, 32, 64);
+    const float m_all = m;
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
-        float a = acc[c] * scl;
+        float a = acc[c];
         a += __shfl_xor(a, 16, 64);
         a += __shfl_xor(a, 32, 64);
         if (sub == 0) s_o[wave][li * 8 + c] = a;
