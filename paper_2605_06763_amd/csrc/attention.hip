@@ -638,7 +638,17 @@ dense_mfma_kernel(const void *__restrict__ K, const void *__restrict__ V, const 
 #pragma unroll
     for (int h = 0; h < NH; ++h) lvr_zero8(acc[h]);
 
+    // the waves of the workgroups that share a compute unit take turns at the top priority (at equal priority the
+    // oldest wave is served first and the workgroups dispatched last finish last), as in the sparse path's query kernel
+    const int prio_phase = (int)((blockIdx.y * gridDim.x + blockIdx.x) >> 8);
+    int turn = 0;
     for (int64_t r0 = start + wave * 16; r0 < end; r0 += 64) {   // uniform over the wave
+        switch ((prio_phase + (turn++ >> 1)) & 3) {
+            case 0: __builtin_amdgcn_s_setprio(0); break;
+            case 1: __builtin_amdgcn_s_setprio(1); break;
+            case 2: __builtin_amdgcn_s_setprio(2); break;
+            default: __builtin_amdgcn_s_setprio(3); break;
+        }
         uint4 av[4];
         lvr_raw8<lvr_bf16_t> vr[4];
         {
@@ -697,6 +707,7 @@ dense_mfma_kernel(const void *__restrict__ K, const void *__restrict__ V, const 
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         __builtin_amdgcn_wave_barrier();
     }
+    __builtin_amdgcn_s_setprio(0);
     // per wave: add the four row subsets (same running maximum), collect l over the score lanes
 #pragma unroll
     for (int h = 0; h < NH; ++h) {
