@@ -1252,6 +1252,35 @@ def test_fp8_centres_unsupported_configurations(G):
 
 
 # ---------------------------------------------------------------------------------------------
+# One-launch attention over lists that carry their scores: set sizes around its batch and round boundaries
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("hkv,gq", [(2, 4), (1, 1), (3, 2)])
+def test_decode_step_set_sizes_around_batch_and_round_boundaries(G, oracle, hkv, gq):
+    """The decode step's attention takes entries in batches of 16 dealt to 16 waves and in rounds of 1024; every
+    head of one step gets a different set size around those boundaries (0, 1, 15, 16, 17, 255, 256, 257, 1023, 1024,
+    1025, 2047, 2049, 3000), with the list capacity at the context and just above the largest set."""
+    n = 6000
+    hq = hkv * gq
+    cache = _small_cache(2, n, hkv=hkv)
+    g = np.random.default_rng(31 + hq)
+    sizes = [0, 1, 15, 16, 17, 255, 256, 257, 1023, 1024, 1025, 2047, 2049, 3000]
+    for rep in range(2):
+        q = W.make_queries(2, n_q_heads=hq, step=rep)
+        with G.Index(cache.K, cache.V, "bf16", hq, group_size=1, buffer_size=64, capacity=n) as ix:
+            ks = [sizes[(h * 5 + rep * 3 + int(g.integers(0, 2))) % len(sizes)] for h in range(hq)]
+            tau = np.zeros((1, hq), dtype=np.float32)
+            for h in range(hq):
+                s = oracle.scores_f32(q[0, h], ix.K[0, h // ix.G])
+                tau[0, h] = W.tau_for_count(s, ks[h]) if ks[h] > 0 else np.float32(s.max() + 1.0)
+            for cap in (n, 3008):
+                G.say(f"set sizes {ks} cap {cap}")
+                idx, cnt, out = ix.query(q, tau, cap=cap, fused=True)
+                # the sizes asked for, plus at most the few keys inside the tolerance band just below a threshold
+                assert all(k <= int(c) <= k + 4 for k, c in zip(ks, cnt[0])), (ks, cnt[0].tolist())
+                G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=f"sizes hkv={hkv} gq={gq} cap={cap}")
+
+
+# ---------------------------------------------------------------------------------------------
 # Centres stored as 6-bit e2m3 codes with a power-of-two scale per 32 coordinates (LVR_INDEX_FP6)
 # ---------------------------------------------------------------------------------------------
 _E2M3 = np.array(sorted({s * v for s in (-1.0, 1.0)
