@@ -29,7 +29,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
-DEFAULT_GROUP_SIZE = 1  # chosen on measured step time over the five workloads (see DESIGN.md)
+DEFAULT_GROUP_SIZE = 1  # chosen on measured step time over the five workloads
 
 
 def log(*a):

@@ -11,7 +11,7 @@ axis-median tree over the full key shared by all subspaces, one tree per subspac
 
     python -m oracle.pruning_power <config id> <n keys> <r,r,...> [<S,S,...>]
 
-the design doc quotes its output for configs 2 and 3.
+The design notes quote its output for configs 2 and 3.
 """
 from __future__ import annotations
 

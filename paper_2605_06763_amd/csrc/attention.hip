@@ -349,7 +349,7 @@ sparse_attention_wg_carry_kernel(const void *__restrict__ V, const int32_t *__re
                 }
             }
         }
-        if (!have[0]) continue;   // wave-uniform: none of this wave's batches holds an entry in this round
+        if (!have[0]) continue;   // wave-uniform: none of this wave's batches holds an entry in this pass over 1024 entries
         // The scores are here already, so the softmax weights of all 64 entries are formed while the rows travel:
         // one maximum and one sum over the wave, one exponential per lane, instead of a chain of rescalings per row.
         const float s_e = (myslot >= 0) ? sc * qscale : -INFINITY;

@@ -657,7 +657,7 @@ def test_threshold_rules_against_the_papers_table(oracle):
 
 
 def test_pruning_power_report_runs_on_the_oracle_alone(oracle, capsys):
-    """oracle/pruning_power.py (the source of the pruning table in the design doc) on a small cache: its
+    """oracle/pruning_power.py (the source of the design notes' pruning table) on a small cache: its
     own check (no summed bound below a key's score) holds, the depth scan's live set contains the
     summed-bound set, and a grouping per subspace with small subspaces keeps fewer keys than one
     shared grouping, which keeps (nearly) all of these keys."""
