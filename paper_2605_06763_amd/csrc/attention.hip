@@ -414,6 +414,144 @@ sparse_attention_wg_carry_kernel(const void *__restrict__ V, const int32_t *__re
     }
 }
 
+// The same with SPLIT workgroups per head (SPLIT = 2), each responsible for one half of the channels: it reads one cache line of
+// every V row (eight lanes per row instead of sixteen) and writes 64 of the 128 outputs.  Both form the same
+// softmax weights from the carried scores, so nothing has to be merged between them; what one compute unit has to
+// pull through its 64 bytes per clock halves.  The two take a ticket once all their threads hold the count; the
+// one that draws the second ticket publishes the count and clears the head's counter when it ends.
+template <typename KT, int SPLIT>
+__global__ void __launch_bounds__(1024)
+sparse_attention_wg_carry_split_kernel(const void *__restrict__ V, const int32_t *__restrict__ pos_slot,
+                                 const int32_t *__restrict__ idx, const float *__restrict__ scores, int64_t score_stride,
+                                 const int32_t *count, int count_stride,   // may alias head_count: not restrict
+                                 int64_t cap, float *__restrict__ out, int64_t cap_rows, int64_t n_total, int n_q_heads,
+                                 int n_kv_heads, int G, float qscale, int32_t *head_count,
+                                 int32_t *__restrict__ head_stat, int32_t *__restrict__ publish_count,
+                                 int32_t *__restrict__ ticket) {
+    constexpr int NW = 16;
+    constexpr int LPR = 16 / SPLIT;          // lanes per row (16 bytes each)
+    constexpr int RPL = 64 / LPR;            // rows per load instruction of a wave
+    constexpr int NLOAD = 64 / RPL;          // load instructions that cover a wave's 64 entries
+    constexpr int CH = LVR_D / SPLIT;        // channels this workgroup is responsible for
+    __shared__ float s_m[NW], s_l[NW];
+    __shared__ float s_o[NW][CH];
+    const int64_t hq = blockIdx.x / SPLIT;
+    const int part = blockIdx.x % SPLIT;
+    const int b = (int)(hq / n_q_heads), h = (int)(hq % n_q_heads);
+    const int bh = b * n_kv_heads + h / G;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, sub = lane >> 4, li = lane & 15;
+    const int grp = lane / LPR, lp = lane % LPR;   // this lane's row within a load, its 16-byte piece of the row part
+    const int32_t *my_idx = idx + hq * cap;
+    const float *my_sc = scores + hq * score_stride;
+    const char *Vb = static_cast<const char *>(V) + (int64_t)bh * cap_rows * LVR_D * sizeof(KT);
+    const int32_t *pslot = pos_slot ? pos_slot + (int64_t)bh * cap_rows : nullptr;
+
+    // trip 1
+    const int64_t e_rel = (int64_t)(wave + NW * sub) * 16 + li;   // this lane's entry within a round of 1024
+    int32_t pos = (e_rel < cap) ? my_idx[e_rel] : -1;
+    float sc = (e_rel < cap && e_rel < score_stride) ? my_sc[e_rel] : 0.f;
+    int64_t cnt = count[hq * count_stride];
+    const int32_t true_cnt = (int32_t)cnt;
+    if (cnt > cap) cnt = cap;
+    if (cnt < 0) cnt = 0;
+    int drawn = 0;
+    if constexpr (SPLIT > 1) {
+        // the empty statement consumes the loaded value, so every thread waits for its copy of the count before the
+        // barrier; behind the barrier the workgroup may announce that it no longer needs the counter
+        asm volatile("" ::"v"(true_cnt));
+        __syncthreads();
+        if (threadIdx.x == 0) drawn = atomicAdd(&ticket[hq], 1);
+    }
+
+    // m and l are the same in all lanes of the wave; acc holds the partial sums of this lane group's rows
+    float m = -INFINITY, l = 0.f, acc[8];
+    lvr_zero8(acc);
+    for (int64_t base = 0; base < cnt; base += NW * 64) {   // uniform over the workgroup
+        const int64_t e = base + e_rel;
+        if (base > 0) {
+            pos = (e < cnt) ? my_idx[e] : -1;
+            sc = (e < cnt && e < score_stride) ? my_sc[e] : 0.f;
+        }
+        int myslot = -1;
+        if (e < cnt && pos >= 0 && pos < n_total) myslot = pslot ? pslot[pos] : (int)pos;
+        // trip 2: load j of the wave fetches the rows of the entries held by lanes j * RPL .. j * RPL + RPL - 1 (row
+        // grp of them is this lane's); those lanes belong to batch (j * RPL) / 16 of the wave, entries
+        // base + (wave + 16 bq) * 16 ..
+        lvr_raw8<KT> vr[NLOAD];
+        bool have[4];
+#pragma unroll
+        for (int bq = 0; bq < 4; ++bq) have[bq] = base + (int64_t)(wave + NW * bq) * 16 < cnt;   // wave-uniform
+#pragma unroll
+        for (int j = 0; j < NLOAD; ++j) {
+            if (have[(j * RPL) / 16]) {
+                const int sl = __shfl(myslot, j * RPL + grp, 64);
+                lvr_load_raw(Vb, sl < 0 ? 0 : sl, part * LPR + lp, vr[j]);
+            }
+        }
+        if (!have[0]) continue;   // wave-uniform: none of this wave's batches holds an entry in this pass over 1024 entries
+        // The scores are here already, so the softmax weights of all 64 entries are formed while the rows travel:
+        // one maximum and one sum over the wave, one exponential per lane, instead of a chain of rescalings per row.
+        const float s_e = (myslot >= 0) ? sc * qscale : -INFINITY;
+        float mw = s_e;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) mw = fmaxf(mw, __shfl_xor(mw, off, 64));
+        const float m_new = fmaxf(m, mw);
+        const float w_e = exp2_safe(s_e, m_new);
+        float lw = w_e;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) lw += __shfl_xor(lw, off, 64);
+        const float alpha = exp2_safe(m, m_new);
+        l = l * alpha + lw;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[c] *= alpha;
+        m = m_new;
+#pragma unroll
+        for (int j = 0; j < NLOAD; ++j) {
+            if (have[(j * RPL) / 16]) {
+                const float w = __shfl(w_e, j * RPL + grp, 64);   // 0 for a masked entry
+                float vx[8];
+                lvr_unpack(vr[j], vx);
+#pragma unroll
+                for (int c = 0; c < 8; ++c) acc[c] += w * vx[c];
+            }
+        }
+    }
+    const float m_all = m;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+        float a = acc[c];
+#pragma unroll
+        for (int off = LPR; off < 64; off <<= 1) a += __shfl_xor(a, off, 64);
+        if (grp == 0) s_o[wave][lp * 8 + c] = a;
+    }
+    if (lane == 0) {
+        s_m[wave] = m_all;
+        s_l[wave] = l;
+    }
+    __syncthreads();
+    if (threadIdx.x < CH) {
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) M = fmaxf(M, s_m[w]);
+        float num = 0.f, den = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float wt = exp2_safe(s_m[w], M);
+            den += wt * s_l[w];
+            num += wt * s_o[w][threadIdx.x];
+        }
+        out[hq * LVR_D + part * CH + threadIdx.x] = (den > 0.f && M != -INFINITY) ? num / den : 0.f;
+    }
+    // every thread's read of the count lies before a barrier above (in both workgroups of a split head once the
+    // second ticket has been drawn), so the counter can be handed over and cleared
+    if (publish_count && threadIdx.x == 0 && (SPLIT == 1 || drawn == SPLIT - 1)) {
+        publish_count[hq] = true_cnt;
+        head_stat[hq] = true_cnt;
+        head_count[hq * LVR_CNT_STRIDE] = 0;
+        if constexpr (SPLIT > 1) ticket[hq] = 0;
+    }
+}
+
 // Merge of the partial triples of one query head.  512 threads: thread (slice s, channel c) owns
 // every fourth partial of channel c; its values are requested first, then the weights
 // w_p = 2^(m_p - M) are computed into LDS, the slices are weighted, and the four slices are
@@ -785,7 +923,17 @@ hipError_t lvr_launch_sparse_attention_wg(lvr_index *ix, const float *q, const i
         // With more heads than compute units the workgroups queue up behind each other and the lighter kernel wins
         // (512 heads: 24.0 against 26.0 us); with one workgroup per unit the shorter chain of trips does (32 heads:
         // 8.4 against 8.7 us at 328 keys per head, 10.5 against 10.9 us at 656).
+        // Up to 128 heads two workgroups can share a head (one per half of the channels) and every workgroup still
+        // has a compute unit of its own.  That pays where a head's list is long (656 keys per head at 128k keys of
+        // context: 9.1 against 9.7 us); short lists lose more to the extra barrier and the ticket than they gain
+        // (3.6 keys per head: 7.6 against 6.9 us), and the list lengths are not known on the host, so the context
+        // length stands in as it does for the launch form.
         if (scores && n_bhq > 256) LVR_WG_LAUNCH(lvr_bf16_t, true);
+        else if (scores && n_bhq <= 128 && publish_count && ix->n_total > 65536)
+            hipLaunchKernelGGL((sparse_attention_wg_carry_split_kernel<lvr_bf16_t, 2>), dim3((unsigned)n_bhq * 2), dim3(1024), 0, st,
+                               ix->V, ix->pos_slot, idx, scores, ix->cap_rows, count, count_stride, cap, out, ix->cap_rows,
+                               ix->n_total, ix->cfg.n_q_heads, ix->cfg.n_kv_heads, ix->G, qscale, lvr_head_count(ix),
+                               lvr_head_stat(ix), publish_count, lvr_head_ticket(ix));
         else if (scores)
             hipLaunchKernelGGL((sparse_attention_wg_carry_kernel<lvr_bf16_t>), dim3((unsigned)n_bhq), dim3(1024), 0, st, ix->V,
                                ix->pos_slot, idx, scores, ix->cap_rows, count, count_stride, cap, out, ix->cap_rows,

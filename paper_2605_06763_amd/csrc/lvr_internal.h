@@ -108,7 +108,12 @@ static inline int32_t *lvr_head_stat(const lvr_index *ix) { return ix->counters 
 static inline int32_t *lvr_seg_count(const lvr_index *ix) { return ix->counters + ((size_t)lvr_n_bhq(ix) + 1) * LVR_CNT_STRIDE + (size_t)lvr_n_bhq(ix); }
 static inline int64_t lvr_max_segs(int64_t max_groups) { return max_groups / LVR_MIN_SEG_GROUPS + 2; }
 static inline size_t lvr_counter_ints(int n_bh, int n_bhq, int64_t max_groups) {
-    return ((size_t)n_bhq + 1) * LVR_CNT_STRIDE + (size_t)n_bhq + (size_t)n_bh * (size_t)lvr_max_segs(max_groups);
+    return ((size_t)n_bhq + 1) * LVR_CNT_STRIDE + (size_t)n_bhq + (size_t)n_bh * (size_t)lvr_max_segs(max_groups) + (size_t)n_bhq;
+}
+// per query head: tickets drawn by the workgroups that share the head in the attention launch (zero between launches)
+static inline int32_t *lvr_head_ticket(const lvr_index *ix) {
+    return ix->counters + ((size_t)lvr_n_bhq(ix) + 1) * LVR_CNT_STRIDE + (size_t)lvr_n_bhq(ix) +
+           (size_t)lvr_n_bh(ix) * (size_t)lvr_max_segs(ix->max_groups);
 }
 
 // ---- launchers (each returns a hipError_t from hipGetLastError after the launch) ----
