@@ -10,6 +10,7 @@ per query head.  Groupings: contiguous (r consecutive positions, the same in eve
 axis-median tree over the full key shared by all subspaces, one tree per subspace (Alg. 1 as printed).
 
     python -m oracle.pruning_power <config id> <n keys> <r,r,...> [<S,S,...>]
+    python -m oracle.pruning_power codings <config id> <n keys>       (groups of one key, coded centres)
 
 The design notes quote its output for configs 2 and 3.
 """
@@ -81,7 +82,81 @@ def run(cid, n, r_list, S_list, n_queries=3, kv_head=0):
                       f"depth scan keeps {np.mean(keep_ta):.4f}", flush=True)
 
 
+def _grid(exp_bits, man_bits, bias, top=None):
+    """Non-negative values of a small float format (subnormals included), ascending."""
+    v = {0.0}
+    for e in range(1 << exp_bits):
+        for m in range(1 << man_bits):
+            x = (m / (1 << man_bits)) * 2.0 ** (1 - bias) if e == 0 else (1 + m / (1 << man_bits)) * 2.0 ** (e - bias)
+            if top is None or x <= top:
+                v.add(x)
+    return np.array(sorted(v))
+
+
+E4M3 = _grid(4, 3, 7, top=448.0)     # one byte per coordinate
+E2M3 = _grid(2, 3, 1)                # six bits per coordinate, largest value 7.5
+
+
+def _nearest(a, grid):
+    i = np.searchsorted(grid, a).clip(1, len(grid) - 1)
+    lo, hi = grid[i - 1], grid[i]
+    return np.where(a - lo <= hi - a, lo, hi)
+
+
+def code_keys(K, coding):
+    """Every key rounded to a coded centre of its own (groups of one key): 'bf16' (the key itself), 'e4m3'
+    (one byte per coordinate), 'e2m3' (six bits per coordinate times one power-of-two scale per block of 32
+    coordinates; block b holds coordinates 32 kk + 8 b + e, kk = 0..3, e = 0..7: the smallest scale that brings
+    the block's largest magnitude to at most 7.5)."""
+    K = K.astype(np.float64)
+    if coding == "bf16":
+        return K.copy()
+    if coding == "e4m3":
+        return np.sign(K) * _nearest(np.minimum(np.abs(K), 448.0), E4M3)
+    n = K.shape[0]
+    B = np.moveaxis(K.reshape(n, 4, 4, 8), 2, 1).reshape(n, 4, 32)
+    amax = np.abs(B).max(-1, keepdims=True)
+    scale = 2.0 ** np.ceil(np.log2(np.maximum(amax, 1e-300) / 7.5))
+    C = np.sign(B) * _nearest(np.minimum(np.abs(B) / scale, 7.5), E2M3) * scale
+    return np.moveaxis(C.reshape(n, 4, 4, 8), 1, 2).reshape(n, 128)
+
+
+def coded_keep(cid, n, coding, S=4, n_queries=3, kv_head=0):
+    """Share of keys whose ball (coded centre, exact radius per coordinate block) reaches tau: per head and for
+    the four heads of a KV head together (a key row is read if any head keeps it); also the mean radius relative
+    to the key's norm.  Every bound is checked to lie above the key's score."""
+    c = W.CONFIGS[cid]
+    K = W.make_cache(cid, n=n, n_kv_heads=kv_head + 1).K[0, kv_head].astype(np.float64)
+    C = code_keys(K, coding)
+    ds = 128 // S
+    rad = np.stack([np.sqrt((((K - C)[:, s * ds:(s + 1) * ds]) ** 2).sum(1)) for s in range(S)])
+    frac = c.get("qualify_frac", 0.005)
+    per, union = [], []
+    drift = W.drift_queries(3, 256, n_q_heads=32) if cid == 3 else None   # config 3's queries drift, as in the bench
+    for t in range(n_queries):
+        Q = drift[(t * 85) % 256][0][:4] if drift is not None else W.make_queries(cid, n_q_heads=4, step=t)[0]
+        any_keep = np.zeros(n, dtype=bool)
+        for hq in range(4):
+            q = Q[hq].astype(np.float64)
+            sc = K @ q
+            tau = float(W.tau_for_fraction(sc.astype(np.float32), frac))
+            ub = C @ q + sum(rad[s] * np.linalg.norm(q[s * ds:(s + 1) * ds]) for s in range(S))
+            assert (ub >= sc - 1e-9 * np.abs(sc).max()).all(), "a bound below a key's score"
+            keep = ub >= tau
+            per.append(float(keep.mean()))
+            any_keep |= keep
+        union.append(float(any_keep.mean()))
+    rel = float(np.sqrt((rad ** 2).sum(0)).mean() / np.linalg.norm(K, axis=1).mean())
+    return dict(per_head=float(np.mean(per)), per_kv_head=float(np.mean(union)), relative_radius=rel)
+
+
 if __name__ == "__main__":
+    if sys.argv[1] == "codings":   # python -m oracle.pruning_power codings <config id> <n keys>
+        for coding in ("bf16", "e4m3", "e2m3"):
+            r = coded_keep(int(sys.argv[2]), int(sys.argv[3]), coding)
+            print(f"config {sys.argv[2]} n={sys.argv[3]} r=1 S=4 centres {coding:5s} keep per head {r['per_head']:.4f}  "
+                  f"per KV head {r['per_kv_head']:.4f}  radius / |k| {r['relative_radius']:.4f}", flush=True)
+        sys.exit(0)
     cid, n = int(sys.argv[1]), int(sys.argv[2])
     r_list = [int(x) for x in sys.argv[3].split(",")]
     S_list = [int(x) for x in sys.argv[4].split(",")] if len(sys.argv) > 4 else [4, 8, 16]

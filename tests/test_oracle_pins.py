@@ -675,3 +675,33 @@ def test_pruning_power_report_runs_on_the_oracle_alone(oracle, capsys):
         got[(name, S)] = keep_sum
     assert got[("contiguous", 4)] > 0.99 and got[("shared", 16)] > 0.99
     assert got[("per", 16)] < got[("per", 4)] <= 1.0 and got[("per", 16)] < 0.9
+
+
+def test_coded_single_key_balls_on_the_cpu():
+    """Groups of one key with coded centres (oracle/pruning_power.py, `codings`): the code grids are the formats'
+    (e4m3: 127 magnitudes up to 448 with eight steps per binade; e2m3: 32 magnitudes up to 7.5), every bound lies
+    above its key's score (asserted inside), the exact centre keeps exactly the qualifying share per head, and a
+    coarser code keeps more keys: bf16 < e4m3 < e2m3 with a scale per 32 coordinates, at radii of a few percent
+    of the key's norm."""
+    from oracle import pruning_power as pp
+    assert pp.E4M3.size == 127 and pp.E4M3[-1] == 448.0 and pp.E4M3[1] == 2.0 ** -9
+    assert np.array_equal(pp.E4M3[(pp.E4M3 >= 1) & (pp.E4M3 < 2)], 1 + np.arange(8) / 8)
+    assert pp.E2M3.size == 32 and pp.E2M3[-1] == 7.5
+    assert np.array_equal(pp.E2M3[:17], np.arange(17) / 8) and np.array_equal(pp.E2M3[16:25], 2 + np.arange(9) / 4)
+    # a key that is exactly representable is its own centre: radius 0 in that block
+    k = np.zeros((1, 128))
+    k[0, :8] = [0.125, -1.5, 3.75, 7.5, 0, 2.25, -6.5, 0.5]
+    assert np.array_equal(pp.code_keys(k, "e2m3"), k)
+    assert np.array_equal(pp.code_keys(k * 2.0 ** -20, "e2m3"), k * 2.0 ** -20)     # the scale follows the block
+    k2 = k.copy()
+    k2[0, 8] = 100.0                      # coordinate 8 is in another scale block (block 1): block 0 is untouched
+    c2 = pp.code_keys(k2, "e2m3")
+    assert np.array_equal(c2[0, :8], k[0, :8]) and c2[0, 8] == 96.0    # 100 / 16 = 6.25 -> 6.0 (ties to even code) * 16
+    k3 = k.copy()
+    k3[0, 32] = 100.0                     # coordinate 32 shares block 0's scale (16): 0.125 is lost, 7.5 becomes 8
+    c3 = pp.code_keys(k3, "e2m3")
+    assert c3[0, 0] == 0.0 and c3[0, 3] == 8.0 and c3[0, 32] == 96.0
+    r = {c: pp.coded_keep(2, 4096, c, n_queries=2) for c in ("bf16", "e4m3", "e2m3")}
+    assert r["bf16"]["relative_radius"] == 0.0 and abs(r["bf16"]["per_head"] - 0.01) < 1e-3
+    assert r["bf16"]["per_kv_head"] < r["e4m3"]["per_kv_head"] < r["e2m3"]["per_kv_head"] < 0.3
+    assert 0.015 < r["e4m3"]["relative_radius"] < r["e2m3"]["relative_radius"] < 0.06
