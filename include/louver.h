@@ -75,6 +75,12 @@ enum lvr_enclosing { LVR_ENCLOSE_BALL = 0, LVR_ENCLOSE_AABB = 1 };
  *         query kernel holds (coordinates 32 kk + 8 b + e, kk = 0..3, e = 0..7, for scale block b), so a
  *         lane decodes its share of a centre with one conversion instruction.  Balls with
  *         n_subspaces <= 4, bf16 caches, the fused query kernel (LVR_E_UNSUPPORTED otherwise).
+ *         With at most four query heads per KV head such an index lives in a rescaled space:
+ *         coordinate c of every key of a (sequence, KV head) is divided by 2^e_c (e_c in [-8, 8], taken
+ *         from the keys handed to lvr_build; zero before the first build), so that one large channel does
+ *         not drown the 31 that share its scale; the query kernels multiply q_c by 2^e_c, which leaves
+ *         every dot product as it was.  Centres, codes and radii are formed in that space, and the balls
+ *         enclose the rescaled keys (lvr_export_channel_scales hands out the exponents).
  *   AUTO: FP6 for balls where it is supported and K/V are in device memory, else SAME. */
 enum lvr_index_dtype { LVR_INDEX_AUTO = 0, LVR_INDEX_SAME = 1, LVR_INDEX_FP8 = 2, LVR_INDEX_FP6 = 3 };
 
@@ -318,6 +324,13 @@ int lvr_get_stats(lvr_index *ix, lvr_stats *out_host);
  *   keys_host     [batch][n_kv_heads][n][head_dim] of kv_dtype, arena row order */
 int lvr_export_index(lvr_index *ix, void *centres_host, float *radii_host, int32_t *slot_pos_host,
                      void *keys_host);
+
+/* The channel exponents e_c of a 6-bit index in a rescaled space (enum lvr_index_dtype, FP6):
+ * exp_host [batch][n_kv_heads][head_dim] signed bytes; all zero where the index is not rescaled.
+ * lvr_export_index returns the centres mapped back to the keys' own space (times 2^e_c) and the
+ * radii as they are stored, i.e. measured in the rescaled space: ball s of group g encloses
+ * pi_s(k_j / 2^e) within radii[g][s] of pi_s(centre_g / 2^e).  Synchronises the device. */
+int lvr_export_channel_scales(lvr_index *ix, int8_t *exp_host);
 
 /* Synchronises the device and copies the per-subspace group labels of a LVR_GROUP_SUBSPACE_TREE index to
  * host memory: labels_host [batch][n_kv_heads][n_subspaces][n_indexed] int32, the group of key j in

@@ -60,7 +60,7 @@ EXPORTS = [
     "lvr_export_index", "lvr_length", "lvr_strerror", "lvr_last_hip_error",
     "lvr_profile_enable", "lvr_profile_read", "lvr_threshold", "lvr_export_reservoir", "lvr_publish", "lvr_query1", "lvr_append_decode_step", "lvr_host_bytes",
     "lvr_subspace_thresholds", "lvr_sparse_attention_static",
-    "lvr_set_bound_test", "lvr_stream_read", "lvr_export_labels",
+    "lvr_set_bound_test", "lvr_stream_read", "lvr_export_labels", "lvr_export_channel_scales",
 ]
 
 _lib = None
@@ -110,6 +110,7 @@ def lib():
                                               vp, vp, vp, i64, vp, vp]
     L.lvr_set_bound_test.argtypes = [vp, C.c_int]
     L.lvr_export_labels.argtypes = [vp, vp]
+    L.lvr_export_channel_scales.argtypes = [vp, vp]
     L.lvr_stream_read.argtypes = [vp, i64, vp, C.c_int32, vp]
     L.lvr_threshold.argtypes = [vp, vp, C.c_int, C.c_float, vp, vp]
     L.lvr_export_reservoir.argtypes = [vp, vp]
@@ -314,6 +315,14 @@ def lvr_export_reservoir(h, cfg: lvr_config):
 
 def lvr_publish(h, stream=None) -> None:
     _check(lib().lvr_publish(h, _stream(stream)), "lvr_publish")
+
+
+def lvr_export_channel_scales(h, cfg: lvr_config):
+    """[batch][n_kv_heads][head_dim] int8: the channel exponents of a rescaled 6-bit index (zeros otherwise)."""
+    import numpy as np
+    e = np.zeros((cfg.batch, cfg.n_kv_heads, cfg.head_dim), dtype=np.int8)
+    _check(lib().lvr_export_channel_scales(h, e.ctypes.data_as(C.c_void_p)), "lvr_export_channel_scales")
+    return e
 
 
 def lvr_export_labels(h, cfg: lvr_config):

@@ -293,6 +293,10 @@ int lvr_create(const lvr_config *cfg, lvr_index **out) {
     // 8-bit centres: 8 bytes of radii per group (four bf16); 6-bit centres: the same and four scale bytes
     ix->S_store = ix->box ? 1 : (ix->cf6 ? 3 : (ix->cf8 ? 2 : cfg->n_subspaces));
     ix->centre_bytes = ix->cf6 ? LVR_D * 3 / 4 : (ix->cf8 ? LVR_D : LVR_D * (cfg->kv_dtype == LVR_BF16 ? 2 : 4));
+    // 6-bit centres share a scale among 32 coordinates, so one large channel would drown the others: the index is
+    // built in a space where every channel is divided by a power of two of its own (taken from the keys at lvr_build).
+    // The kernels that serve up to four heads per KV head carry the rescaled query beside the original one.
+    ix->chan_scaled = ix->cf6 && ix->G <= 4;
     ix->cap_rows = s.cap_rows;
     ix->max_groups = s.max_groups;
     ix->P = s.P;
@@ -350,6 +354,15 @@ int lvr_create(const lvr_config *cfg, lvr_index **out) {
         }
     }
     if (e == hipSuccess) e = hipMemset(ix->counters, 0, s.counters);
+    if (e == hipSuccess) {   // channel scaling starts as the identity: exponents 0 (the memset), factors 1
+        const size_t n_bh = (size_t)lvr_n_bh(ix);
+        float *ones = static_cast<float *>(malloc(LVR_D * sizeof(float)));
+        if (!ones) e = hipErrorOutOfMemory;
+        for (int c = 0; ones && c < LVR_D; ++c) ones[c] = 1.0f;
+        for (size_t i = 0; ones && i < n_bh && e == hipSuccess; ++i)
+            e = hipMemcpy(lvr_chan_exp(ix) + i * LVR_CHAN_STRIDE + LVR_D, ones, LVR_D * sizeof(float), hipMemcpyHostToDevice);
+        free(ones);
+    }
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         free_all(ix);
@@ -396,6 +409,7 @@ int lvr_build(lvr_index *ix, const void *K, const void *V, int64_t n, const int6
     ix->n_indexed = 0;
     const int r = ix->cfg.group_size;
     const int64_t n_groups = n / r;
+    LVR_HIP(lvr_launch_channel_scales(ix, K, ks, n, st));   // before any group is formed
     if (n > 0 && ix->per_subspace) {
         // rows stay in arrival order; every coordinate block gets the tree order of its own coordinates,
         // and from it the block's balls and the keys' labels (Alg. 1: one BalancedPCATree call per subspace)
@@ -822,6 +836,8 @@ int lvr_export_index(lvr_index *ix, void *centres, float *radii, int32_t *slot_p
             // 32 codes, code 8 kk + e = coordinate 32 kk + 8 b + e; the scale of piece b is byte b of the third
             // word of the group's 12-byte record in `radii`.
             const int cb = ix->centre_bytes;
+            int8_t chan[LVR_D];
+            LVR_HIP(hipMemcpy(chan, lvr_chan_exp(ix) + (size_t)bh * LVR_CHAN_STRIDE, LVR_D, hipMemcpyDeviceToHost));
             uint8_t *codes = static_cast<uint8_t *>(malloc((size_t)ng * cb));
             uint32_t *rec = static_cast<uint32_t *>(malloc((size_t)ng * 12));
             if (!codes || !rec) {
@@ -847,7 +863,7 @@ int lvr_export_index(lvr_index *ix, void *centres, float *radii, int32_t *slot_p
                     const uint32_t two = (uint32_t)piece[bit >> 3] | ((uint32_t)piece[(bit >> 3) + 1 < 24 ? (bit >> 3) + 1 : 23] << 8);
                     const uint32_t code = (two >> (bit & 7)) & 63u;
                     const int sgn = code >> 5, ex = (code >> 3) & 3, m = code & 7;
-                    const int E = (int)((rec[g * 3 + 2] >> (8 * b)) & 0xffu) - 127;
+                    const int E = (int)((rec[g * 3 + 2] >> (8 * b)) & 0xffu) - 127 + (int)chan[c];   // back to the keys' own space
                     const float v = ldexpf(ex == 0 ? (float)m / 8.f : ldexpf(1.f + (float)m / 8.f, ex - 1), E);
                     uint32_t bits;
                     const float sv = sgn ? -v : v;
@@ -921,6 +937,14 @@ int lvr_export_index(lvr_index *ix, void *centres, float *radii, int32_t *slot_p
             }
         }
     }
+    return LVR_OK;
+}
+
+int lvr_export_channel_scales(lvr_index *ix, int8_t *exp_host) {
+    if (!ix || !exp_host) return LVR_E_INVALID;
+    if (!ix->built) return LVR_E_STATE;
+    LVR_HIP(hipDeviceSynchronize());
+    LVR_HIP(hipMemcpy2D(exp_host, LVR_D, lvr_chan_exp(ix), LVR_CHAN_STRIDE, LVR_D, (size_t)lvr_n_bh(ix), hipMemcpyDeviceToHost));
     return LVR_OK;
 }
 

@@ -115,10 +115,15 @@ typedef __attribute__((__vector_size__(32 * sizeof(float)))) float lvr_f32x32;
 // one power-of-two scale per kq: the 32 coordinates of a scale block are the ones a lane of the query
 // kernel holds.  The scale is the smallest power of two that brings the block's largest magnitude to
 // at most 7.5; its biased exponent byte goes into the group's record in `radii` (byte kq of the third word).
+// chan_exp (CF = 2 only, may be NULL): 128 signed bytes at the start of every LVR_CHAN_STRIDE bytes, one set per
+// (sequence, KV head); the index then describes the keys
+// with coordinate c divided by 2^e_c: centre, codes and radii are all formed in that space (an exact rescaling: powers
+// of two), and the query multiplies q_c by 2^e_c, which leaves every dot product as it was.
 template <typename KT, int CF = 0>
 __global__ void __launch_bounds__(256)
 build_groups_kernel(void *__restrict__ K, void *__restrict__ centres, float *__restrict__ radii,
-                    int64_t cap_rows, int64_t max_groups, int64_t g0, int64_t g1, int r, int S, const BuildSrc src) {
+                    int64_t cap_rows, int64_t max_groups, int64_t g0, int64_t g1, int r, int S, const BuildSrc src,
+                    const int8_t *__restrict__ chan_exp = nullptr) {
     const int bh = blockIdx.y;
     const int li = threadIdx.x & 15;
     int64_t g = g0 + (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
@@ -163,6 +168,19 @@ build_groups_kernel(void *__restrict__ K, void *__restrict__ centres, float *__r
     const float inv = 1.0f / (float)r;
 #pragma unroll
     for (int e = 0; e < 8; ++e) c[e] *= inv;
+    float chs[8];   // 2^-e_c of this lane's eight coordinates
+#pragma unroll
+    for (int e = 0; e < 8; ++e) chs[e] = 1.0f;
+    if constexpr (CF == 2) {
+        if (chan_exp) {
+            const int8_t *ce = chan_exp + (int64_t)bh * LVR_CHAN_STRIDE + li * 8;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                chs[e] = __uint_as_float((uint32_t)(127 - (int)ce[e]) << 23);
+                c[e] *= chs[e];
+            }
+        }
+    }
 
     constexpr bool CF8 = CF == 1;
     char *Cb = static_cast<char *>(centres) + ((int64_t)bh * max_groups + g) * (CF == 2 ? LVR_D * 3 / 4 : LVR_D * (CF8 ? 1 : sizeof(KT)));
@@ -240,7 +258,7 @@ build_groups_kernel(void *__restrict__ K, void *__restrict__ centres, float *__r
         float d2 = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            float t = x[e] - c[e];
+            float t = x[e] * chs[e] - c[e];
             d2 += t * t;
         }
         d2 = seg_sum(d2, lanes_per_sub);
@@ -432,7 +450,8 @@ hipError_t lvr_launch_build_groups(lvr_index *ix, int64_t g0, int64_t g1, hipStr
     }
     if (ix->cf6)
         hipLaunchKernelGGL((build_groups_kernel<lvr_bf16_t, 2>), grid, dim3(256), 0, st, ix->K, ix->centres, ix->radii,
-                           ix->cap_rows, ix->max_groups, g0, g1, ix->cfg.group_size, ix->cfg.n_subspaces, src);
+                           ix->cap_rows, ix->max_groups, g0, g1, ix->cfg.group_size, ix->cfg.n_subspaces, src,
+                           ix->chan_scaled ? lvr_chan_exp(ix) : nullptr);
     else if (ix->cf8)
         hipLaunchKernelGGL((build_groups_kernel<lvr_bf16_t, 1>), grid, dim3(256), 0, st, ix->K, ix->centres, ix->radii,
                            ix->cap_rows, ix->max_groups, g0, g1, ix->cfg.group_size, ix->cfg.n_subspaces, src);
@@ -442,6 +461,65 @@ hipError_t lvr_launch_build_groups(lvr_index *ix, int64_t g0, int64_t g1, hipStr
     else
         hipLaunchKernelGGL(build_groups_kernel<lvr_f32_t>, grid, dim3(256), 0, st, ix->K, ix->centres, ix->radii,
                            ix->cap_rows, ix->max_groups, g0, g1, ix->cfg.group_size, ix->cfg.n_subspaces, src);
+    return hipGetLastError();
+}
+
+// Channel exponents of a (sequence, KV head): with L_c = log2(rms of coordinate c) over a sample of the rows,
+// e_c = round(L_c - o), held to [-8, 8]; a coordinate that is zero throughout keeps e_c = 0.  The offset o (the same for
+// all 128 channels, so it only moves the block scales) is the circular mean of the fractional parts of L_c: channels of
+// about the same size then sit in the middle of one rounding interval and get the same exponent, instead of being split
+// by a boundary that happens to fall among them.  One workgroup per (sequence, KV head), thread t takes coordinate
+// t % 128 of every second sampled row.  Any exponents give a correct index (the radii are measured in the rescaled space
+// against the centres as stored there); these make the coordinates of a key comparable in size, so that the 32
+// coordinates that share a scale in the 6-bit code are not drowned by one large channel.
+__global__ void __launch_bounds__(256)
+channel_scale_kernel(const char *__restrict__ K, int64_t sb, int64_t sh, int64_t stt, int n_kv_heads, int64_t n, int64_t step,
+                     int8_t *__restrict__ chan_exp) {
+    __shared__ float s_sum[2][LVR_D];
+    const int bh = blockIdx.x;
+    const int c = threadIdx.x & (LVR_D - 1), half = threadIdx.x >> 7;
+    const uint16_t *base = reinterpret_cast<const uint16_t *>(K) + (int64_t)(bh / n_kv_heads) * sb + (int64_t)(bh % n_kv_heads) * sh;
+    float ss = 0.f;
+    for (int64_t row = half * step; row < n; row += 2 * step) {
+        const float x = __uint_as_float((uint32_t)base[row * stt + c] << 16);
+        ss += x * x;
+    }
+    s_sum[half][c] = ss;
+    __syncthreads();
+    const int64_t rows = (n + step - 1) / step;
+    const float ms = (s_sum[0][c] + s_sum[1][c]) / (float)(rows > 0 ? rows : 1);
+    const bool live = ms > 0.f && ms < INFINITY;
+    const float L = live ? 0.5f * log2f(ms) : 0.f;
+    __syncthreads();
+    constexpr float kTwoPi = 6.283185307179586f;
+    if (half == 0) {
+        s_sum[0][c] = live ? cosf(kTwoPi * L) : 0.f;
+        s_sum[1][c] = live ? sinf(kTwoPi * L) : 0.f;
+    }
+    __syncthreads();
+    if (half == 0) {
+        float sc = 0.f, sn = 0.f;
+        for (int i = 0; i < LVR_D; ++i) {   // the same order in every thread: one offset for the head
+            sc += s_sum[0][i];
+            sn += s_sum[1][i];
+        }
+        const float o = (sc != 0.f || sn != 0.f) ? atan2f(sn, sc) / kTwoPi : 0.f;
+        int e = 0;
+        if (live) {
+            e = (int)rintf(L - o);
+            e = e < -8 ? -8 : (e > 8 ? 8 : e);
+        }
+        int8_t *mine = chan_exp + (int64_t)bh * LVR_CHAN_STRIDE;
+        mine[c] = (int8_t)e;
+        reinterpret_cast<float *>(mine + LVR_D)[c] = __uint_as_float((uint32_t)(127 + e) << 23);
+    }
+}
+
+hipError_t lvr_launch_channel_scales(lvr_index *ix, const void *K, const int64_t ks[3], int64_t n, hipStream_t st) {
+    if (!ix->chan_scaled || n <= 0) return hipSuccess;
+    const int64_t step = (n + 4095) / 4096;   // at most 4096 rows are looked at
+    hipLaunchKernelGGL(channel_scale_kernel, dim3((unsigned)lvr_n_bh(ix)), dim3(256), 0, st, static_cast<const char *>(K), ks[0],
+                       ks[1], ks[2], ix->cfg.n_kv_heads, n, step, lvr_chan_exp(ix));
     return hipGetLastError();
 }
 

@@ -26,6 +26,8 @@ struct lvr_index {
     int cf6;               // 1: centres are stored as e2m3 codes with a scale per 32 coordinates, 96 bytes per group,
                            //    in matrix-operand order; `radii` holds 12 bytes per group (four bf16 radii, four scale bytes)
     int centre_bytes;      // bytes of one enclosure row in `centres` (256 / 512 in the cache's format, 128, 96)
+    int chan_scaled;       // 1: the 6-bit index lives in a rescaled space, coordinate c of every key divided by 2^e_c
+                           //    (e_c per (sequence, KV head), see lvr_chan_exp); the query multiplies q_c by 2^e_c
     int64_t cap_rows;      // arena rows per (sequence, KV head), multiple of 64
     int64_t max_groups;    // cap_rows / r
     int64_t n_total;       // keys held
@@ -97,6 +99,7 @@ static inline int lvr_n_bhq(const lvr_index *ix) { return ix->cfg.batch * ix->cf
 // Device counters.  Atomics that hit one 128-byte line are served one after the other
 // (about 12 ns each on this part), so every counter that takes atomics owns a whole line.
 #define LVR_CNT_STRIDE 32   // ints per counter slot (128 bytes)
+#define LVR_CHAN_STRIDE (LVR_D + LVR_D * 4)   // bytes of channel scaling per (sequence, KV head): 128 exponents, 128 factors
 #define LVR_MIN_SEG_GROUPS 64
 // per query head: size of the retrieved set of the running query (padded).  Zero between
 // queries: the kernel that publishes the counts clears them.
@@ -108,7 +111,8 @@ static inline int32_t *lvr_head_stat(const lvr_index *ix) { return ix->counters 
 static inline int32_t *lvr_seg_count(const lvr_index *ix) { return ix->counters + ((size_t)lvr_n_bhq(ix) + 1) * LVR_CNT_STRIDE + (size_t)lvr_n_bhq(ix); }
 static inline int64_t lvr_max_segs(int64_t max_groups) { return max_groups / LVR_MIN_SEG_GROUPS + 2; }
 static inline size_t lvr_counter_ints(int n_bh, int n_bhq, int64_t max_groups) {
-    return ((size_t)n_bhq + 1) * LVR_CNT_STRIDE + (size_t)n_bhq + (size_t)n_bh * (size_t)lvr_max_segs(max_groups) + (size_t)n_bhq;
+    return ((size_t)n_bhq + 1) * LVR_CNT_STRIDE + (size_t)n_bhq + (size_t)n_bh * (size_t)lvr_max_segs(max_groups) + (size_t)n_bhq +
+           (size_t)n_bh * (LVR_CHAN_STRIDE / 4) + 32;   // + room to start the channel exponents on a 128-byte boundary
 }
 // per query head: tickets drawn by the workgroups that share the head in the attention launch (zero between launches)
 static inline int32_t *lvr_head_ticket(const lvr_index *ix) {
@@ -116,7 +120,17 @@ static inline int32_t *lvr_head_ticket(const lvr_index *ix) {
            (size_t)lvr_n_bh(ix) * (size_t)lvr_max_segs(ix->max_groups);
 }
 
+// per (sequence, KV head), LVR_CHAN_STRIDE bytes: 128 signed bytes, the channel exponents e_c of a rescaled 6-bit index
+// (all zero: no rescaling), then the 128 factors 2^e_c as floats (all 1), which is the form the query kernel multiplies
+// q with
+static inline int8_t *lvr_chan_exp(const lvr_index *ix) {
+    const uintptr_t p = reinterpret_cast<uintptr_t>(lvr_head_ticket(ix) + lvr_n_bhq(ix));
+    return reinterpret_cast<int8_t *>((p + 127) & ~(uintptr_t)127);
+}
+
 // ---- launchers (each returns a hipError_t from hipGetLastError after the launch) ----
+// channel exponents from the keys about to be indexed (element strides ks for (sequence, head, token))
+hipError_t lvr_launch_channel_scales(lvr_index *ix, const void *K, const int64_t ks[3], int64_t n, hipStream_t st);
 // copies `rows` key rows and value rows into the arena starting at arena row dst_row0 (one launch)
 hipError_t lvr_launch_copy_kv(lvr_index *ix, const void *K, const int64_t ks[3], const void *V, const int64_t vs[3],
                               int64_t dst_row0, int64_t rows, hipStream_t st, int64_t k_first = 0);

@@ -26,14 +26,18 @@
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 lvr_bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float lvr_f32x4;
 
-// Exact three-way split of an fp32 value into bf16 bit patterns (part 0 = leading term).
+// Exact three-way split of an fp32 value into bf16 bit patterns (part 0 = leading term): each term is the remainder
+// cut off after its eight leading significant bits, so the three of them hold all 24 bits of x and add up to x exactly.
+// (Cutting instead of rounding to nearest costs a third of the instructions; every workgroup of a query launch does
+// this 8 times per lane before its first matrix instruction.)
 __device__ __forceinline__ uint32_t lvr_split_part(float x, int part) {
-    const uint32_t hi = lvr_f32_to_bf16_bits(x);
-    const float r1 = x - __uint_as_float(hi << 16);
-    const uint32_t mid = lvr_f32_to_bf16_bits(r1);
-    const float r2 = r1 - __uint_as_float(mid << 16);
-    const uint32_t lo = lvr_f32_to_bf16_bits(r2);
-    return part == 0 ? hi : (part == 1 ? mid : lo);
+    const uint32_t hi = __float_as_uint(x) & 0xffff0000u;
+    const float r1 = x - __uint_as_float(hi);
+    const uint32_t mid = __float_as_uint(r1) & 0xffff0000u;
+    const float r2 = r1 - __uint_as_float(mid);   // at most eight significant bits are left: its low half is zero
+    // picked with masks: written as nested selects this becomes two levels of divergent branches per value
+    const uint32_t m0 = part == 0 ? 0xffffffffu : 0u, m1 = part == 1 ? 0xffffffffu : 0u, m2 = part == 2 ? 0xffffffffu : 0u;
+    return ((hi & m0) | (mid & m1) | (__float_as_uint(r2) & m2)) >> 16;
 }
 
 // One B fragment: head block hb (heads hb*4 .. hb*4+3 of the KV group, those >= G are zero),
@@ -77,15 +81,23 @@ __device__ __forceinline__ void lvr_q_frag_make(const float (&raw)[8], int G, in
     const int n = lane & 15;
     const int part = n >> 2, h = hb * 4 + (n & 3);
     const bool live = part < 3 && h < G;
-    uint32_t w[8];
+    // The term this lane needs is what is left of x after `part` cuts (see lvr_split_part), cut once more: a lane that
+    // needs the leading term subtracts zero twice.  Four instructions per value, and the last cut is the packing.
+    const uint32_t cut1 = part >= 1 ? 0xffff0000u : 0u, cut2 = part >= 2 ? 0xffff0000u : 0u;
+    uint32_t y[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        float x = live ? raw[e] * scale : 0.f;
+        float x = raw[e] * scale;
         if (sign > 0) x = fmaxf(x, 0.f);
         if (sign < 0) x = fminf(x, 0.f);
-        w[e] = live ? lvr_split_part(x, part) : 0u;
+        x -= __uint_as_float(__float_as_uint(x) & cut1);
+        x -= __uint_as_float(__float_as_uint(x) & cut2);
+        y[e] = __float_as_uint(x);
     }
-    uint4 packed = make_uint4(w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16));
+    // upper halves of two words side by side
+    uint4 packed = make_uint4(__builtin_amdgcn_perm(y[1], y[0], 0x07060302u), __builtin_amdgcn_perm(y[3], y[2], 0x07060302u),
+                              __builtin_amdgcn_perm(y[5], y[4], 0x07060302u), __builtin_amdgcn_perm(y[7], y[6], 0x07060302u));
+    if (!live) packed = make_uint4(0u, 0u, 0u, 0u);
     out = __builtin_bit_cast(lvr_bf16x8, packed);
 }
 
@@ -102,6 +114,26 @@ __device__ __forceinline__ void lvr_exchange_q_frags_wg(const float (&raw)[HB][8
         s_bq[hb][wave][lane] = __builtin_bit_cast(uint4, f);
     }
     __syncthreads();
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) bq[hb][kk] = __builtin_bit_cast(lvr_bf16x8, s_bq[hb][kk][lane]);
+}
+
+// A second operand set put aside in LDS (no barrier here: the caller's next barrier publishes it) and fetched later.
+template <int HB>
+__device__ __forceinline__ void lvr_stash_q_frags(const float (&raw)[HB][8], int G, float scale, uint4 (&s_bq)[HB][4][64]) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) {
+        lvr_bf16x8 f;
+        lvr_q_frag_make(raw[hb], G, hb, scale, f, 0);
+        s_bq[hb][wave][lane] = __builtin_bit_cast(uint4, f);
+    }
+}
+template <int HB>
+__device__ __forceinline__ void lvr_fetch_q_frags(const uint4 (&s_bq)[HB][4][64], lvr_bf16x8 (&bq)[HB][4]) {
+    const int lane = threadIdx.x & 63;
 #pragma unroll
     for (int hb = 0; hb < HB; ++hb)
 #pragma unroll

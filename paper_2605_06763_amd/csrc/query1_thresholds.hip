@@ -28,7 +28,8 @@ __device__ __forceinline__ float seg_sum16(float v, int lanes_per_sub) {
 template <int G, int CF, bool BOX = false>
 __global__ void __launch_bounds__(256)
 subspace_max_kernel(const void *__restrict__ centres, const float *__restrict__ radii, const float *__restrict__ q,
-                    float *__restrict__ part, int64_t max_groups, int64_t n_groups, int S, int n_kv_heads, int n_q_heads) {
+                    float *__restrict__ part, int64_t max_groups, int64_t n_groups, int S, int n_kv_heads, int n_q_heads,
+                    const int8_t *__restrict__ chan_exp = nullptr) {
     __shared__ float s_m[16][G][16];
     const int bh = blockIdx.y, b = bh / n_kv_heads, hkv = bh % n_kv_heads;
     const int quarter = threadIdx.x >> 4, li = threadIdx.x & 15;
@@ -41,6 +42,8 @@ subspace_max_kernel(const void *__restrict__ centres, const float *__restrict__ 
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             qv[h][e] = qh[e];
+            // a 6-bit index in a rescaled space (coordinate c of the keys divided by 2^e_c): q_c times 2^e_c
+            if (CF == 2 && chan_exp) qv[h][e] *= __uint_as_float((uint32_t)(127 + (int)chan_exp[(int64_t)bh * LVR_CHAN_STRIDE + li * 8 + e]) << 23);
             n2 += qv[h][e] * qv[h][e];
         }
         // rounded up a little: the norm multiplies a non-negative radius in an upper bound
@@ -151,7 +154,8 @@ void launch_max(lvr_index *ix, const float *q, float *part, int NB, int64_t n_gr
     dim3 grid((unsigned)NB, (unsigned)lvr_n_bh(ix));
     if (ix->cf6)
         hipLaunchKernelGGL((subspace_max_kernel<G, 2>), grid, dim3(256), 0, st, ix->centres, ix->radii, q, part,
-                           ix->max_groups, n_groups, ix->cfg.n_subspaces, ix->cfg.n_kv_heads, ix->cfg.n_q_heads);
+                           ix->max_groups, n_groups, ix->cfg.n_subspaces, ix->cfg.n_kv_heads, ix->cfg.n_q_heads,
+                           ix->chan_scaled ? lvr_chan_exp(ix) : nullptr);
     else if (ix->box && ix->cf8)
         hipLaunchKernelGGL((subspace_max_kernel<G, 1, true>), grid, dim3(256), 0, st, ix->centres, ix->radii, q, part,
                            ix->max_groups, n_groups, ix->cfg.n_subspaces, ix->cfg.n_kv_heads, ix->cfg.n_q_heads);

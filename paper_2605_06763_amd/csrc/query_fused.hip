@@ -33,6 +33,8 @@ struct FusedArgs {
     const float *q;
     const float *tau;
     const float *tau_s;      // Query 1: [batch][H_q][S] per-block thresholds; NULL: Query 2
+    const int8_t *chan_exp;  // per (sequence, KV head) LVR_CHAN_STRIDE bytes: channel exponents of a 6-bit index in a rescaled
+                             // space (else all zero), then the factors 2^e_c as floats (else all 1)
     const void *k_new, *v_new;   // rows appended by this launch ([batch][H_kv][m_new][d]), or NULL
     void *V;
     int m_new;               // n_total already counts them
@@ -79,7 +81,13 @@ query_fused_kernel(const FusedArgs a) {
     __shared__ uint4 s_bq2[ENC ? HB : 1][4][64];
     __shared__ float s_qn[HB * W][16];
     __shared__ float s_qpart[HB * 4][4];   // squared norm of q_h over the 32 coordinates of MFMA step kk (NQ only)
-    __shared__ int32_t s_queue[4][HB][W][LVR_QCAP];
+    // the emission queues belong to the key-row phase; until then their bytes keep the query operand of that phase
+    // when the bound phase works with a rescaled one (see CS below)
+    __shared__ union {
+        int32_t queue[4][HB][W][LVR_QCAP];
+        uint4 stash[HB][4][64];
+    } s_qu;
+    auto &s_queue = s_qu.queue;
     __shared__ uint16_t s_list[SEG_MAX_GROUPS];   // surviving groups, as offsets from the segment's first group
     __shared__ int s_tot[4];
     __shared__ int s_wcnt[4][HB * W], s_wbase[HB * W];
@@ -127,6 +135,7 @@ query_fused_kernel(const FusedArgs a) {
             const int64_t g0 = (tile0 + it + u) * 16;
             int64_t g = g0 + n;
             if (g >= a.n_groups) g = a.n_groups - 1;
+            if (g < 0) g = 0;   // an empty index: the first trip is requested all the same (see below), from row 0
             if constexpr (C6) {
                 lvr_load_a_codes6(Cb, g, c6[u]);
                 sc[u] = reinterpret_cast<const uint32_t *>(Rb)[g * 3 + 2];
@@ -160,6 +169,7 @@ query_fused_kernel(const FusedArgs a) {
                 for (int j = 0; j < 4; ++j) {
                     int64_t gj = g0 + 4 * kq + j;
                     if (gj >= a.n_groups) gj = a.n_groups - 1;
+                    if (gj < 0) gj = 0;
                     const float *rp = Rb + gj * (ENC ? 1 : S);
                     if constexpr (ENC) {   // the box's allowance; S only counts the blocks of Query 1
                         rad[u][j][0] = rp[0];
@@ -187,9 +197,22 @@ query_fused_kernel(const FusedArgs a) {
     float qraw[W == 4 ? HB : 1][8];   // this lane's share of q for the operand pieces it builds
     float qnv[8];                     // and for the norms
     (void)qraw; (void)qnv;
+    // CS: the 6-bit index describes the keys with coordinate c divided by 2^e_c (one exponent per channel of this
+    // (sequence, KV head)); the bound phase therefore works with q_c * 2^e_c, which leaves every product <q,k> as it
+    // was, and the key-row phase with q itself.  Both operands are built here; the second waits in LDS.
+    // No branch on whether the exponents are all zero: a branch here would make the wait for q a wait for the first
+    // trip's centres as well.
+    constexpr bool CSP = CF == 2 && W == 4 && !ENC && sizeof(s_qu.stash) <= sizeof(s_qu.queue);
+    float4 cfac[2];   // 2^e_c of this lane's eight coordinates
+    (void)cfac;
     if constexpr (W == 4) {
 #pragma unroll
         for (int hb = 0; hb < HB; ++hb) lvr_q_frag_load(a.q + hq0 * LVR_D, a.G, hb, wave, qraw[hb]);
+        if constexpr (CSP) {
+            const float4 *cf = reinterpret_cast<const float4 *>(a.chan_exp + (int64_t)bh * LVR_CHAN_STRIDE + LVR_D) + wave * 8 + kq * 2;
+            cfac[0] = cf[0];
+            cfac[1] = cf[1];
+        }
     }
     // NQ: with at most four coordinate blocks every block is a whole number of MFMA steps, and wave kk has just asked
     // for the 32 coordinates of step kk of every head: the norms come out of those values, and q is read once per
@@ -207,13 +230,26 @@ query_fused_kernel(const FusedArgs a) {
 #pragma unroll
     for (int hb = 0; hb < HB; ++hb) {
         const int h = hb * W + n - 8;
-        tau_raw[hb] = (n >= 8 && n < 8 + W && h < a.G) ? a.tau[hq0 + h] : INFINITY;
+        const bool mine = n >= 8 && n < 8 + W && h < a.G;
+        const float tv = a.tau[hq0 + (mine ? h : 0)];
+        tau_raw[hb] = mine ? tv : INFINITY;
     }
     __builtin_amdgcn_sched_barrier(0);
-    if (phaseA) issueA(t0, 0);
+    // Every wave requests a first trip, also one that has no tile to test (its rows are clamped into the arena and
+    // never looked at), and every lane a threshold: with no branch around any of these loads the compiler can count
+    // them, and the prologue waits for q alone instead of for everything in flight.
+    issueA(t0, 0);
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- prologue: subspace norms of q (phase A only) and the B operand of q ----
+    if constexpr (CSP) {
+        lvr_stash_q_frags<HB>(qraw, a.G, 1.0f, s_qu.stash);   // q itself, for the key-row phase
+        const float f[8] = {cfac[0].x, cfac[0].y, cfac[0].z, cfac[0].w, cfac[1].x, cfac[1].y, cfac[1].z, cfac[1].w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+#pragma unroll
+            for (int hb = 0; hb < HB; ++hb) qraw[hb][e] *= f[e];
+    }
     if constexpr (NQ) {
         // the lanes that build the leading terms (columns 0..3) hold q itself: 8 values per lane, 32 per head over
         // the four lane quarters
@@ -338,6 +374,7 @@ query_fused_kernel(const FusedArgs a) {
         if (threadIdx.x == 0) a.seg_count[(int64_t)bh * a.max_segs + blockIdx.x] = (int32_t)total;
         rows = total << a.log2r;
         buf_row0 = g0 << a.log2r;
+        if constexpr (CSP) lvr_fetch_q_frags<HB>(s_qu.stash, bq);   // the key-row phase scores with q itself
         __syncthreads();   // no wave still reads the operand staging area that the score queues reuse
     } else if (!buffer_wg) {
         // ---------------- phase A: bound test over this segment's centres ----------------
@@ -562,6 +599,11 @@ query_fused_kernel(const FusedArgs a) {
         }
         if (lane == 63) s_tot[wave] = incl;
         __syncthreads();
+        if constexpr (CSP) {
+            // every wave takes the key-row phase's operand out of the bytes that become the emission queues
+            // behind the next barrier
+            lvr_fetch_q_frags<HB>(s_qu.stash, bq);
+        }
         int before = 0, total = 0;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
@@ -595,6 +637,7 @@ query_fused_kernel(const FusedArgs a) {
                 else vd[i - pieces] = vs[i - pieces];
             }
         }
+        if constexpr (CSP) lvr_fetch_q_frags<HB>(s_qu.stash, bq);
         // the new rows are in place for every wave of this workgroup, and no wave still reads the
         // operand staging area that the score queues are about to reuse
         __syncthreads();
@@ -739,6 +782,7 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
     if (tau_s && ((ix->box || ix->cf8 || ix->cf6) && ix->cfg.n_subspaces > 4)) return hipErrorInvalidValue;
     FusedArgs a;
     a.tau_s = tau_s;
+    a.chan_exp = lvr_chan_exp(ix);   // exponents 0 and factors 1 unless the index is a rescaled one
     a.k_new = k_new;
     a.v_new = v_new;
     a.V = ix->V;

@@ -109,6 +109,11 @@ class Index:
     def export(self):
         return L.lvr_export_index(self.h, self.cfg)
 
+    def channel_factors(self):
+        """[batch][hkv][128] float64: 2^e_c of the space the index is stored in (ones unless it is a rescaled 6-bit
+        index).  The stored balls enclose K / factors around centres / factors, and bound <q * factors, .>."""
+        return 2.0 ** L.lvr_export_channel_scales(self.h, self.cfg).astype(np.float64)
+
 
 def check_head(oracle, q, Kh, Vh, tau, got_idx, got_count, got_out, sigma, *, extra_from=-1, where=""):
     """Parity of one (sequence, head): retrieved set by the band rule, attention against the

@@ -164,9 +164,10 @@ def test_config2_library_thresholds_query1_and_offload(G, oracle):
         centres, radii, _, _ = ix.export()
         tau = G.oracle_taus(oracle, ix, q, frac=0.01)
         tau_s = np.empty((1, 32, 4), dtype=np.float32)
+        chan = ix.channel_factors()   # the default index is stored in a per-channel rescaled space
         for h in range(32):
-            c = W.bf16_bits_to_f32(centres[0, h // 4]).reshape(-1, 128).astype(np.float64)
-            top = oracle.ball_bounds(q[0, h], c, radii[0, h // 4].astype(np.float64)).max(axis=1)
+            c = W.bf16_bits_to_f32(centres[0, h // 4]).reshape(-1, 128).astype(np.float64) / chan[0, h // 4]
+            top = oracle.ball_bounds(q[0, h] * chan[0, h // 4], c, radii[0, h // 4].astype(np.float64)).max(axis=1)
             tau_s[0, h] = (tau[0, h] - (top.sum() - top) - 1e-3).astype(np.float32)
         idx, cnt, out = G.query1(ix, q, tau_s, tau, cap=2048)
         G.check_step(oracle, ix, q, tau, idx, cnt, out, tag="config2 query1")

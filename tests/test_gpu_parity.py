@@ -296,13 +296,14 @@ def test_surviving_groups_match_oracle_bounds(G, oracle, S):
     q = W.make_queries(2, n_q_heads=4)
     with G.Index(K, V, "bf16", 4, group_size=r, n_subspaces=S) as ix:
         centres, radii, _, _ = ix.export()
-        c = W.bf16_bits_to_f32(centres[0, 0]).reshape(n // r, 128).astype(np.float64)
+        a = ix.channel_factors()[0, 0]     # the default index may live in a rescaled space
+        c = W.bf16_bits_to_f32(centres[0, 0]).reshape(n // r, 128).astype(np.float64) / a
         seen = []
         for frac in (0.001, 0.02, 0.3):
             t = G.oracle_taus(oracle, ix, q, frac=frac)
             ix.query(q, t)
             st = ix.stats()
-            ub = np.stack([oracle.ball_bounds(q[0, h], c, radii[0, 0].astype(np.float64)).sum(0) for h in range(4)])
+            ub = np.stack([oracle.ball_bounds(q[0, h] * a, c, radii[0, 0].astype(np.float64)).sum(0) for h in range(4)])
             te = t[0] - 0.5e-4 * np.abs(t[0])
             lo = int(np.any(ub >= te[:, None] * (1 + 1e-5) + 1e-3, axis=0).sum())
             hi = int(np.any(ub >= te[:, None] * (1 - 1e-5) - 1e-3, axis=0).sum())
@@ -494,8 +495,9 @@ def test_tree_grouping_queries(G, oracle, n, r, S):
             if n_idx:
                 label = np.empty(n_idx, dtype=np.int32)
                 label[slot_pos[0, h, :n_idx]] = np.arange(n_idx) // r
-                c = W.bf16_bits_to_f32(centres[0, h]).reshape(n_idx // r, 128).astype(np.float64)
-                need = oracle.ball_radii_for_centres(cache.K[0, h, :n_idx], label, c, S)
+                a = ix.channel_factors()[0, h]
+                c = W.bf16_bits_to_f32(centres[0, h]).reshape(n_idx // r, 128).astype(np.float64) / a
+                need = oracle.ball_radii_for_centres(cache.K[0, h, :n_idx].astype(np.float64) / a, label, c, S)
                 assert np.all(radii[0, h] >= need)
         for frac, fused in ((0.02, True), (0.3, False)):
             tau = G.oracle_taus(oracle, ix, q, frac=frac)
@@ -896,11 +898,12 @@ def _exported_bounds(G, oracle, ix, q, r):
     """Eq. (2) per block, evaluated by the oracle (fp64) on the index as the library stores it:
     f [hq][S][groups] for sequence 0 (one KV head per G query heads)."""
     centres, radii, _, _ = ix.export()
+    a = ix.channel_factors()
     out = []
     for h in range(ix.hq):
         g = h // ix.G
-        c = W.bf16_bits_to_f32(centres[0, g]).reshape(-1, 128).astype(np.float64)
-        out.append(oracle.ball_bounds(q[0, h], c, radii[0, g].astype(np.float64)))
+        c = W.bf16_bits_to_f32(centres[0, g]).reshape(-1, 128).astype(np.float64) / a[0, g]
+        out.append(oracle.ball_bounds(q[0, h] * a[0, g], c, radii[0, g].astype(np.float64)))
     return np.stack(out)
 
 
@@ -1307,10 +1310,16 @@ def test_fp6_centres_enclose_members(G, oracle, S, r):
         st_bytes = G.L.lvr_arena_bytes(G.L.make_config(batch=1, n_q_heads=2, n_kv_heads=2, capacity=n, group_size=r,
                                                        n_subspaces=S, index_dtype=G.L.LVR_INDEX_FP6))
         assert st_bytes > 0
+        chan = ix.channel_factors()
         for h in range(2):
-            c = W.bf16_bits_to_f32(centres[0, h]).reshape(n // r, 128).astype(np.float64)
+            # the index is stored in the space k_c / 2^e_c: the exported centres come back in the keys' own space, the
+            # radii, the grid and the scale blocks belong to the stored one
+            a = chan[0, h]
+            assert np.all(np.log2(a) == np.rint(np.log2(a))) and np.all(np.abs(np.log2(a)) <= 8)
+            c = W.bf16_bits_to_f32(centres[0, h]).reshape(n // r, 128).astype(np.float64) / a
             label = (np.arange(n) // r).astype(np.int32)
-            mean, _ = oracle.ball_index(Kc[0, h], label, n // r, S)
+            Ks = Kc[0, h].astype(np.float64) / a
+            mean, _ = oracle.ball_index(Ks, label, n // r, S)
             mb, cb = _scale_blocks(mean), _scale_blocks(c)
             amax = np.abs(mb).max(axis=-1)
             E = np.ceil(np.log2(np.maximum(amax, 1e-300) / 7.5))
@@ -1327,7 +1336,7 @@ def test_fp6_centres_enclose_members(G, oracle, S, r):
             hi = _E2M3[np.clip(pos, 0, _E2M3.size - 1)]
             best = np.minimum(np.abs(target - lo), np.abs(target - hi))
             assert np.all((np.abs(scaled - target) <= best + 1e-5)[sure])
-            need = oracle.ball_radii_for_centres(Kc[0, h], label, c, S)
+            need = oracle.ball_radii_for_centres(Ks, label, c, S)
             assert np.all(radii[0, h] >= need), "a member lies outside its ball"
             cn = np.stack([np.linalg.norm(c[:, a:b], axis=1)
                            for a, b in (oracle.subspace_range(128, S, s) for s in range(S))], axis=1)
@@ -1366,7 +1375,8 @@ def test_fp6_centres_surviving_groups_and_pruning(G, oracle, S):
     with G.Index(K, V, "bf16", 4, group_size=r, n_subspaces=S, index_dtype=G.L.LVR_INDEX_FP6) as ix, \
          G.Index(K, V, "bf16", 4, group_size=r, n_subspaces=S, index_dtype=G.L.LVR_INDEX_SAME) as ref:
         centres, radii, _, _ = ix.export()
-        c = W.bf16_bits_to_f32(centres[0, 0]).reshape(n // r, 128).astype(np.float64)
+        a = ix.channel_factors()[0, 0]
+        c = W.bf16_bits_to_f32(centres[0, 0]).reshape(n // r, 128).astype(np.float64) / a
         for frac in (0.002, 0.02):
             t = G.oracle_taus(oracle, ix, q, frac=frac)
             idx, cnt, out = ix.query(q, t)
@@ -1374,7 +1384,7 @@ def test_fp6_centres_surviving_groups_and_pruning(G, oracle, S):
             st = ix.stats()
             ref.query(q, t)
             st_ref = ref.stats()
-            ub = np.stack([oracle.ball_bounds(q[0, h], c, radii[0, 0].astype(np.float64)).sum(0) for h in range(4)])
+            ub = np.stack([oracle.ball_bounds(q[0, h] * a, c, radii[0, 0].astype(np.float64)).sum(0) for h in range(4)])
             te = t[0] - 0.5e-4 * np.abs(t[0])
             lo = int(np.any(ub >= te[:, None] * (1 + 1e-5) + 1e-3, axis=0).sum())
             hi = int(np.any(ub >= te[:, None] * (1 - 1e-5) - 1e-3, axis=0).sum())
