@@ -54,6 +54,11 @@ struct FusedArgs {
 // Four waves per SIMD (four workgroups per compute unit) are asked for wherever the kernel fits 128 registers: one
 // head block of balls with at most four coordinate blocks, and the eight-head operand.  Left to itself the compiler
 // has filled 128 vector registers and then needed four accumulator registers more, which costs a quarter of the waves.
+// And no more than four: the launches aim at 1024 workgroups (four per compute unit) and larger batches run as whole
+// rounds of 1024; a fifth resident workgroup makes the rounds uneven (1280 + 768 for 2048 workgroups: 1.2 % slower at
+// 16 sequences of 32k keys).  The launcher sees to that with unused dynamic LDS (a fifth of a compute unit's LDS and a
+// little more per workgroup) whenever a launch has more workgroups than fit at once; a launch that fits takes whatever
+// residency the registers allow, which is where the few workgroups beyond 1024 (the buffer's) find room.
 template <int HB, int S, int UA, int ENC, int Q1 = 0, int CF = 0, int W = 4>
 __global__ void __launch_bounds__(256, ((HB == 1 && !ENC && S <= 4) || W == 8) ? 4 : 1)
 query_fused_kernel(const FusedArgs a) {
@@ -92,10 +97,11 @@ query_fused_kernel(const FusedArgs a) {
     __shared__ int s_tot[4];
     __shared__ int s_wcnt[4][HB * W], s_wbase[HB * W];
     const int bh = blockIdx.y;
-    const int b = bh / a.n_kv_heads, kvh = bh % a.n_kv_heads;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // the wave's number is the same in all its lanes: said so, what depends on it alone is computed on the scalar unit
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 15, kq = lane >> 4;
-    const int64_t hq0 = (int64_t)b * a.n_q_heads + kvh * a.G;
+    // first query head of this (sequence, KV head): (bh / H_kv) * H_q + (bh % H_kv) * G with H_q = H_kv * G
+    const int64_t hq0 = (int64_t)bh * a.G;
     const bool buffer_wg = (int)blockIdx.x >= a.n_segs;
 
     // ---- phase A, first trip: the centre and radius loads do not depend on q, so they are put
@@ -763,13 +769,13 @@ query_fused_kernel(const FusedArgs a) {
 }
 
 template <int UA, int W>
-void launch_s(dim3 grid, hipStream_t st, const FusedArgs &a, int S) {
+void launch_s(dim3 grid, unsigned dyn_lds, hipStream_t st, const FusedArgs &a, int S) {
     switch (S) {
-        case 1: hipLaunchKernelGGL((query_fused_kernel<1, 1, UA, 0, 0, 0, W>), grid, dim3(256), 0, st, a); break;
-        case 2: hipLaunchKernelGGL((query_fused_kernel<1, 2, UA, 0, 0, 0, W>), grid, dim3(256), 0, st, a); break;
-        case 4: hipLaunchKernelGGL((query_fused_kernel<1, 4, UA, 0, 0, 0, W>), grid, dim3(256), 0, st, a); break;
-        case 8: hipLaunchKernelGGL((query_fused_kernel<1, 8, UA, 0, 0, 0, W>), grid, dim3(256), 0, st, a); break;
-        default: hipLaunchKernelGGL((query_fused_kernel<1, 16, UA, 0, 0, 0, W>), grid, dim3(256), 0, st, a); break;
+        case 1: hipLaunchKernelGGL((query_fused_kernel<1, 1, UA, 0, 0, 0, W>), grid, dim3(256), dyn_lds, st, a); break;
+        case 2: hipLaunchKernelGGL((query_fused_kernel<1, 2, UA, 0, 0, 0, W>), grid, dim3(256), dyn_lds, st, a); break;
+        case 4: hipLaunchKernelGGL((query_fused_kernel<1, 4, UA, 0, 0, 0, W>), grid, dim3(256), dyn_lds, st, a); break;
+        case 8: hipLaunchKernelGGL((query_fused_kernel<1, 8, UA, 0, 0, 0, W>), grid, dim3(256), dyn_lds, st, a); break;
+        default: hipLaunchKernelGGL((query_fused_kernel<1, 16, UA, 0, 0, 0, W>), grid, dim3(256), dyn_lds, st, a); break;
     }
 }
 
@@ -827,6 +833,8 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
     ix->n_segs = a.n_segs;
     if (a.n_segs + has_buffer == 0) return hipSuccess;
     dim3 grid((unsigned)(a.n_segs + has_buffer), (unsigned)n_bh);
+    // more workgroups than 5 x 256: hold the residency at four per compute unit, so that the rounds are whole
+    const unsigned dyn_lds = (int64_t)grid.x * grid.y > 1280 ? 20480u : 0u;
     // one centre tile per trip for the small segments of short contexts, two per trip for long ones
     // (measured crossover between 32k and 128k keys); four per trip costs a wave per SIMD and 12 us
     const bool one = tpw == 1;
@@ -834,9 +842,9 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
         const int S = ix->cfg.n_subspaces;
 #define LVR_Q1B_LAUNCH(HB, CF)                                                                                 \
     do {                                                                                                        \
-        if (S == 1) hipLaunchKernelGGL((query_fused_kernel<HB, 1, 1, 1, 1, CF>), grid, dim3(256), 0, st, a);   \
-        else if (S == 2) hipLaunchKernelGGL((query_fused_kernel<HB, 2, 1, 1, 1, CF>), grid, dim3(256), 0, st, a); \
-        else hipLaunchKernelGGL((query_fused_kernel<HB, 4, 1, 1, 1, CF>), grid, dim3(256), 0, st, a);          \
+        if (S == 1) hipLaunchKernelGGL((query_fused_kernel<HB, 1, 1, 1, 1, CF>), grid, dim3(256), dyn_lds, st, a);   \
+        else if (S == 2) hipLaunchKernelGGL((query_fused_kernel<HB, 2, 1, 1, 1, CF>), grid, dim3(256), dyn_lds, st, a); \
+        else hipLaunchKernelGGL((query_fused_kernel<HB, 4, 1, 1, 1, CF>), grid, dim3(256), dyn_lds, st, a);          \
     } while (0)
         if (ix->G <= 4) {
             if (ix->cf8) LVR_Q1B_LAUNCH(1, 1);
@@ -852,12 +860,12 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
         const int S = ix->cfg.n_subspaces;
 #define LVR_Q1_LAUNCH(HB, CF)                                                                                  \
     do {                                                                                                        \
-        if (S == 1) hipLaunchKernelGGL((query_fused_kernel<HB, 1, 1, 0, 1, CF>), grid, dim3(256), 0, st, a);   \
-        else if (S == 2) hipLaunchKernelGGL((query_fused_kernel<HB, 2, 1, 0, 1, CF>), grid, dim3(256), 0, st, a); \
-        else if (S == 4) hipLaunchKernelGGL((query_fused_kernel<HB, 4, 1, 0, 1, CF>), grid, dim3(256), 0, st, a); \
+        if (S == 1) hipLaunchKernelGGL((query_fused_kernel<HB, 1, 1, 0, 1, CF>), grid, dim3(256), dyn_lds, st, a);   \
+        else if (S == 2) hipLaunchKernelGGL((query_fused_kernel<HB, 2, 1, 0, 1, CF>), grid, dim3(256), dyn_lds, st, a); \
+        else if (S == 4) hipLaunchKernelGGL((query_fused_kernel<HB, 4, 1, 0, 1, CF>), grid, dim3(256), dyn_lds, st, a); \
         else if constexpr (!CF) {                                                                              \
-            if (S == 8) hipLaunchKernelGGL((query_fused_kernel<HB, 8, 1, 0, 1, 0>), grid, dim3(256), 0, st, a); \
-            else hipLaunchKernelGGL((query_fused_kernel<HB, 16, 1, 0, 1, 0>), grid, dim3(256), 0, st, a);       \
+            if (S == 8) hipLaunchKernelGGL((query_fused_kernel<HB, 8, 1, 0, 1, 0>), grid, dim3(256), dyn_lds, st, a); \
+            else hipLaunchKernelGGL((query_fused_kernel<HB, 16, 1, 0, 1, 0>), grid, dim3(256), dyn_lds, st, a);       \
         }                                                                                                       \
     } while (0)
         if (ix->G <= 4) {
@@ -873,17 +881,17 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
         return hipGetLastError();
     }
     if (ix->box && ix->cf8) {   // boxes with 8-bit corners
-        if (ix->G <= 4) hipLaunchKernelGGL((query_fused_kernel<1, 1, 1, 1, 0, 1>), grid, dim3(256), 0, st, a);
-        else hipLaunchKernelGGL((query_fused_kernel<2, 1, 1, 1, 0, 1>), grid, dim3(256), 0, st, a);
+        if (ix->G <= 4) hipLaunchKernelGGL((query_fused_kernel<1, 1, 1, 1, 0, 1>), grid, dim3(256), dyn_lds, st, a);
+        else hipLaunchKernelGGL((query_fused_kernel<2, 1, 1, 1, 0, 1>), grid, dim3(256), dyn_lds, st, a);
         return hipGetLastError();
     }
     if (ix->cf8 || ix->cf6) {   // 8-bit or 6-bit centres
         const int S = ix->cfg.n_subspaces;
 #define LVR_CODED_LAUNCH(UA, W, CF)                                                                               \
     do {                                                                                                      \
-        if (S == 1) hipLaunchKernelGGL((query_fused_kernel<1, 1, UA, 0, 0, CF, W>), grid, dim3(256), 0, st, a);  \
-        else if (S == 2) hipLaunchKernelGGL((query_fused_kernel<1, 2, UA, 0, 0, CF, W>), grid, dim3(256), 0, st, a); \
-        else hipLaunchKernelGGL((query_fused_kernel<1, 4, UA, 0, 0, CF, W>), grid, dim3(256), 0, st, a);         \
+        if (S == 1) hipLaunchKernelGGL((query_fused_kernel<1, 1, UA, 0, 0, CF, W>), grid, dim3(256), dyn_lds, st, a);  \
+        else if (S == 2) hipLaunchKernelGGL((query_fused_kernel<1, 2, UA, 0, 0, CF, W>), grid, dim3(256), dyn_lds, st, a); \
+        else hipLaunchKernelGGL((query_fused_kernel<1, 4, UA, 0, 0, CF, W>), grid, dim3(256), dyn_lds, st, a);         \
     } while (0)
 #define LVR_CODED_ANY_LAUNCH(UA, W)            \
     do {                                 \
@@ -902,16 +910,16 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
         return hipGetLastError();
     }
     if (ix->box) {   // boxes: one allowance per group, one tile (two rows per group) per trip
-        if (ix->G <= 4) hipLaunchKernelGGL((query_fused_kernel<1, 1, 1, 1>), grid, dim3(256), 0, st, a);
-        else hipLaunchKernelGGL((query_fused_kernel<2, 1, 1, 1>), grid, dim3(256), 0, st, a);
+        if (ix->G <= 4) hipLaunchKernelGGL((query_fused_kernel<1, 1, 1, 1>), grid, dim3(256), dyn_lds, st, a);
+        else hipLaunchKernelGGL((query_fused_kernel<2, 1, 1, 1>), grid, dim3(256), dyn_lds, st, a);
         return hipGetLastError();
     }
     if (ix->G <= 4) {
-        if (one) launch_s<1, 4>(grid, st, a, ix->cfg.n_subspaces);
-        else launch_s<2, 4>(grid, st, a, ix->cfg.n_subspaces);
+        if (one) launch_s<1, 4>(grid, dyn_lds, st, a, ix->cfg.n_subspaces);
+        else launch_s<2, 4>(grid, dyn_lds, st, a, ix->cfg.n_subspaces);
     } else {   // up to eight heads in one operand
-        if (one) launch_s<1, 8>(grid, st, a, ix->cfg.n_subspaces);
-        else launch_s<2, 8>(grid, st, a, ix->cfg.n_subspaces);
+        if (one) launch_s<1, 8>(grid, dyn_lds, st, a, ix->cfg.n_subspaces);
+        else launch_s<2, 8>(grid, dyn_lds, st, a, ix->cfg.n_subspaces);
     }
     return hipGetLastError();
 }
