@@ -295,8 +295,8 @@ int lvr_create(const lvr_config *cfg, lvr_index **out) {
     ix->centre_bytes = ix->cf6 ? LVR_D * 3 / 4 : (ix->cf8 ? LVR_D : LVR_D * (cfg->kv_dtype == LVR_BF16 ? 2 : 4));
     // 6-bit centres share a scale among 32 coordinates, so one large channel would drown the others: the index is
     // built in a space where every channel is divided by a power of two of its own (taken from the keys at lvr_build).
-    // The kernels that serve up to four heads per KV head carry the rescaled query beside the original one.
-    ix->chan_scaled = ix->cf6 && ix->G <= 4;
+    // The query kernels carry the rescaled query (bound phase) beside the original one (key rows).
+    ix->chan_scaled = ix->cf6;
     ix->cap_rows = s.cap_rows;
     ix->max_groups = s.max_groups;
     ix->P = s.P;

@@ -167,9 +167,10 @@ __device__ __forceinline__ void lvr_build_q_frags_wg(const float *__restrict__ q
 // accumulator only when some head needs it.  After  d + row_shr:8(d)  the lanes with n in [8, 16)
 // hold the finished score of head n - 8.
 // third = false: the main operand; third = true: the operand of the third terms.
+// fac (may be NULL): 128 factors, one per coordinate, applied to q first (powers of two: a rescaled index).
 // Returns true if this lane put a non-zero third term into its piece.
 __device__ __forceinline__ bool lvr_build_q_frag8_one(const float *__restrict__ q_group, int G, int kk, float scale,
-                                                      bool third, lvr_bf16x8 &out) {
+                                                      bool third, lvr_bf16x8 &out, const float *__restrict__ fac = nullptr) {
     const int lane = threadIdx.x & 63;
     const int n = lane & 15, kq = lane >> 4;
     const int h = n & 7;
@@ -180,7 +181,9 @@ __device__ __forceinline__ bool lvr_build_q_frag8_one(const float *__restrict__ 
     const float *src = q_group + (int64_t)(live ? h : 0) * LVR_D + kk * 32 + kq * 8;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        w[e] = live ? lvr_split_part(src[e] * scale, part) : 0u;
+        float x = src[e] * scale;
+        if (fac) x *= fac[kk * 32 + kq * 8 + e];
+        w[e] = live ? lvr_split_part(x, part) : 0u;
         any |= w[e] & 0x7fffu;   // a signed zero contributes nothing either
     }
     uint4 packed = make_uint4(w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16));
@@ -189,17 +192,18 @@ __device__ __forceinline__ bool lvr_build_q_frag8_one(const float *__restrict__ 
 }
 
 // Both operands of a KV group of up to eight heads, built once per 256-thread workgroup into LDS
-// (s_bq[0] = main, s_bq[1] = third terms); wave w builds the pieces of coordinates w*32 .. w*32+31.
+// (s_bq[base] = main, s_bq[base + 1] = third terms); wave w builds the pieces of coordinates w*32 .. w*32+31.
 // Contains a barrier: every thread of the workgroup must call it.  Returns whether the second
 // operand holds anything (the same answer in every thread).
+template <int NB>
 __device__ __forceinline__ bool lvr_build_q_frags8_wg(const float *__restrict__ q_group, int G, float scale,
-                                                      uint4 (&s_bq)[2][4][64]) {
+                                                      uint4 (&s_bq)[NB][4][64], int base = 0, const float *__restrict__ fac = nullptr) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     lvr_bf16x8 f;
-    lvr_build_q_frag8_one(q_group, G, wave, scale, false, f);
-    s_bq[0][wave][lane] = __builtin_bit_cast(uint4, f);
-    const bool nz = lvr_build_q_frag8_one(q_group, G, wave, scale, true, f);
-    s_bq[1][wave][lane] = __builtin_bit_cast(uint4, f);
+    lvr_build_q_frag8_one(q_group, G, wave, scale, false, f, fac);
+    s_bq[base][wave][lane] = __builtin_bit_cast(uint4, f);
+    const bool nz = lvr_build_q_frag8_one(q_group, G, wave, scale, true, f, fac);
+    s_bq[base + 1][wave][lane] = __builtin_bit_cast(uint4, f);
     return __syncthreads_or(nz ? 1 : 0) != 0;
 }
 
@@ -463,21 +467,42 @@ __device__ __forceinline__ lvr_bf16x8 lvr_radius_b_frag(const float (*qn_group)[
     const int n = lane & 15, kq = lane >> 4;
     const int p = n >> 2, h = hb * 4 + (n & 3);
     const bool live = p < 3 && h < G;
+    // every lane reads a row (a dead lane the first one) in as few LDS reads as the row allows, and cuts its own term out
+    // of each value as lvr_q_frag_make does; the terms stay in the upper halves until they are packed
+    const float *row = qn_group[live ? h : 0];
+    float v[S];
+    if constexpr (S == 4) {
+        const float4 r = *reinterpret_cast<const float4 *>(row);
+        v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w;
+    } else if constexpr (S == 2) {
+        const float2 r = *reinterpret_cast<const float2 *>(row);
+        v[0] = r.x; v[1] = r.y;
+    } else {
+#pragma unroll
+        for (int s = 0; s < S; ++s) v[s] = row[s];
+    }
+    const uint32_t cut1 = p >= 1 ? 0xffff0000u : 0u, cut2 = p >= 2 ? 0xffff0000u : 0u;
     uint32_t val[S];
 #pragma unroll
-    for (int s = 0; s < S; ++s) val[s] = live ? lvr_split_part(qn_group[live ? h : 0][s], p) : 0u;
+    for (int s = 0; s < S; ++s) {
+        float x = v[s];
+        x -= __uint_as_float(__float_as_uint(x) & cut1);
+        x -= __uint_as_float(__float_as_uint(x) & cut2);
+        val[s] = live ? __float_as_uint(x) : 0u;
+    }
     uint32_t w[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        uint32_t v = 0;
+        uint32_t t = 0;
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
             const int k = 8 * q4 + j;
-            if (k < NP * S) v = (kq == q4) ? val[k % S] : v;
+            if (k < NP * S) t = (kq == q4) ? val[k % S] : t;
         }
-        w[j] = v;
+        w[j] = t;
     }
-    uint4 packed = make_uint4(w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16));
+    const uint4 packed = make_uint4(__builtin_amdgcn_perm(w[1], w[0], 0x07060302u), __builtin_amdgcn_perm(w[3], w[2], 0x07060302u),
+                                    __builtin_amdgcn_perm(w[5], w[4], 0x07060302u), __builtin_amdgcn_perm(w[7], w[6], 0x07060302u));
     return __builtin_bit_cast(lvr_bf16x8, packed);
 }
 

@@ -76,7 +76,11 @@ query_fused_kernel(const FusedArgs a) {
         float qscore[4][HB][4][LVR_QCAP];
     } s_u;
     static_assert(sizeof(s_u.bq) == sizeof(s_u.qscore), "aliasing assumes equal sizes");
-    __shared__ uint4 s_bq8[W == 8 ? 2 : 1][4][64];   // W = 8: main operand and the operand of the third terms
+    // W = 8: main operand and the operand of the third terms; with a rescaled 6-bit index (CS8) that pair is the bound
+    // phase's (q_c * 2^e_c) and a second pair holds q itself for the key-row phase
+    constexpr bool CS8 = CF == 2 && W == 8;
+    constexpr int KP8 = CS8 ? 2 : 0;   // first operand of the key-row phase
+    __shared__ uint4 s_bq8[W == 8 ? (CS8 ? 4 : 2) : 1][4][64];
     // BL: with eight heads per KV head the query operand (two head blocks, 32 registers) stays in LDS
     // and a lane fetches its pieces right before the matrix instructions that use them; that brings
     // the kernel back under the register budget of four waves per SIMD.  The staging area then keeps
@@ -84,7 +88,7 @@ query_fused_kernel(const FusedArgs a) {
     constexpr bool BL = (HB == 2 && !Q1) || W == 8;
     __shared__ float s_qs2[BL ? 4 : 1][BL ? HB : 1][W][BL ? LVR_QCAP : 1];
     __shared__ uint4 s_bq2[ENC ? HB : 1][4][64];
-    __shared__ float s_qn[HB * W][16];
+    __shared__ __align__(16) float s_qn[HB * W][16];
     __shared__ float s_qpart[HB * 4][4];   // squared norm of q_h over the 32 coordinates of MFMA step kk (NQ only)
     // the emission queues belong to the key-row phase; until then their bytes keep the query operand of that phase
     // when the bound phase works with a rescaled one (see CS below)
@@ -231,6 +235,12 @@ query_fused_kernel(const FusedArgs a) {
         const float4 x = *reinterpret_cast<const float4 *>(qh), y = *reinterpret_cast<const float4 *>(qh + 4);
         qnv[0] = x.x; qnv[1] = x.y; qnv[2] = x.z; qnv[3] = x.w;
         qnv[4] = y.x; qnv[5] = y.y; qnv[6] = y.z; qnv[7] = y.w;
+        if constexpr (CS8) {   // the norms that meet the radii are those of the rescaled query
+            const float4 *cf = reinterpret_cast<const float4 *>(a.chan_exp + (int64_t)bh * LVR_CHAN_STRIDE + LVR_D) + (threadIdx.x & 15) * 2;
+            const float4 f0 = cf[0], f1 = cf[1];
+            qnv[0] *= f0.x; qnv[1] *= f0.y; qnv[2] *= f0.z; qnv[3] *= f0.w;
+            qnv[4] *= f1.x; qnv[5] *= f1.y; qnv[6] *= f1.z; qnv[7] *= f1.w;
+        }
     }
     float tau_raw[HB];
 #pragma unroll
@@ -284,7 +294,11 @@ query_fused_kernel(const FusedArgs a) {
     // negative part (meets the lower corners); q = q+ + q- serves the exact check of phase B
     lvr_bf16x8 bq[HB][4], bq2[ENC ? HB : 1][4];
     bool third = false;   // W = 8: some head's query has more than 16 significant bits (the same in every thread)
-    if constexpr (W == 8) third = lvr_build_q_frags8_wg(a.q + hq0 * LVR_D, a.G, 1.0f, s_bq8);   // syncs
+    if constexpr (CS8) {   // both sync; a third term is there for q exactly when it is there for q times powers of two
+        lvr_build_q_frags8_wg(a.q + hq0 * LVR_D, a.G, 1.0f, s_bq8, KP8);
+        third = lvr_build_q_frags8_wg(a.q + hq0 * LVR_D, a.G, 1.0f, s_bq8, 0,
+                                      reinterpret_cast<const float *>(a.chan_exp + (int64_t)bh * LVR_CHAN_STRIDE + LVR_D));
+    } else if constexpr (W == 8) third = lvr_build_q_frags8_wg(a.q + hq0 * LVR_D, a.G, 1.0f, s_bq8);   // syncs
     else lvr_exchange_q_frags_wg<HB>(qraw, a.G, 1.0f, s_u.bq, bq, ENC ? 1 : 0);   // syncs
     if constexpr (ENC) lvr_exchange_q_frags_wg<HB>(qraw, a.G, 1.0f, s_bq2, bq2, -1);
     if constexpr (NQ) {
@@ -296,7 +310,9 @@ query_fused_kernel(const FusedArgs a) {
             float ss = 0.f;
 #pragma unroll
             for (int k = 0; k < SPB; ++k) ss += s_qpart[h][sb * SPB + k];
-            s_qn[h][sb] = sqrtf(ss) * (1.0f + 0x1p-20f);   // rounded up
+            // rounded up: the hardware's square root is good to an ulp, and where the sum of squares left the normal
+            // range (a norm below 2^-62) the constant alone is an upper bound
+            s_qn[h][sb] = __builtin_amdgcn_sqrtf(ss) * (1.0f + 0x1p-20f) + 0x1p-62f;
         }
         __builtin_amdgcn_wave_barrier();
     }
@@ -696,8 +712,8 @@ query_fused_kernel(const FusedArgs a) {
             } else if constexpr (ENC) s = lvr_score_tile2(av[u], bq[hb], av[u], bq2[hb]);
             else if constexpr (W == 8) {
                 lvr_bf16x8 b[4], b3[4];
-                fetch_bq8(0, b);
-                if (third) fetch_bq8(1, b3);
+                fetch_bq8(KP8, b);
+                if (third) fetch_bq8(KP8 + 1, b3);
                 s = lvr_score_tile8(av[u], b, b3, third);
             } else if constexpr (BL) {
                 lvr_bf16x8 b[4];

@@ -1433,6 +1433,63 @@ def test_fp6_centres_surface_keys_wide_range_and_append(G, oracle):
                 G.check_step(oracle, ix, q, t, idx, cnt, out, tag=f"fp6 surface S={S} r={rr} tau={tau}")
 
 
+def test_fp6_index_follows_channels_of_very_different_size(G, oracle):
+    """Keys whose channels span three decades (and queries that weigh the small channels up, so that every channel
+    matters to a score): a 6-bit code with one scale per 32 coordinates would round the small channels to zero and
+    keep nearly every ball; the index is therefore built on keys divided by a power of two per channel.  The exponents
+    follow the channels' sizes, the results are the oracle's, and most balls are pruned, with four heads per KV head and
+    with eight (another kernel)."""
+    L = G.L
+    g = np.random.default_rng(77)
+    n, hkv = 4096, 2
+    mag = 2.0 ** g.uniform(-5.0, 5.0, size=(hkv, 128))
+    K = W.round_to_bf16((g.standard_normal((1, hkv, n, 128)) * mag[None, :, None, :]).astype(np.float32))
+    V = W.round_to_bf16(g.standard_normal((1, hkv, n, 128)).astype(np.float32))
+    for hq in (8, 16):
+        Gq = hq // hkv
+        q = (g.standard_normal((1, hq, 128)) / np.repeat(mag, Gq, axis=0)[None]).astype(np.float32)
+        with G.Index(K, V, "bf16", hq, group_size=1, index_dtype=L.LVR_INDEX_FP6, capacity=n + 512) as ix:
+            e = L.lvr_export_channel_scales(ix.h, ix.cfg).astype(np.float64)
+            assert e.shape == (1, hkv, 128)
+            rms = np.sqrt((K.astype(np.float64) ** 2).mean(axis=2))     # [1][hkv][128]
+            d = e - np.log2(rms)
+            # one offset per (sequence, KV head), then rounding to the nearest integer; the library estimates the
+            # rms from every row here (4096 is its sample size), in fp32
+            for h in range(hkv):
+                assert d[0, h].max() - d[0, h].min() <= 1.0 + 1e-3, (h, d[0, h].min(), d[0, h].max())
+            for frac in (0.003, 0.03):
+                tau = G.oracle_taus(oracle, ix, q, frac=frac)
+                idx, cnt, out = ix.query(q, tau)
+                G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=f"channels hq={hq} frac={frac}")
+                st = ix.stats()
+                share = st["groups_surviving"] / st["groups_scored"]
+                G.say(f"  channels over three decades, {Gq} heads per KV head, frac={frac}: {share:.3f} of the balls survive")
+                if frac < 0.01:
+                    # what the same code WITHOUT the rescaling keeps (on the CPU: every key rounded to e2m3 with one
+                    # scale per 32 coordinates, exact radii, the sum rule over four blocks)
+                    from oracle import pruning_power as pp
+                    kept = 0
+                    for kv in range(hkv):
+                        Kd = K[0, kv].astype(np.float64)
+                        C = pp.code_keys(Kd, "e2m3")
+                        rad = np.stack([np.sqrt(((Kd - C)[:, 32 * s:32 * s + 32] ** 2).sum(1)) for s in range(4)])
+                        keep = np.zeros(n, dtype=bool)
+                        for h in range(kv * Gq, (kv + 1) * Gq):
+                            qd = q[0, h].astype(np.float64)
+                            ub = C @ qd + sum(rad[s] * np.linalg.norm(qd[32 * s:32 * s + 32]) for s in range(4))
+                            keep |= ub >= tau[0, h]
+                        kept += int(keep.sum())
+                    plain = kept / (hkv * n)
+                    G.say(f"    without the rescaling: {plain:.3f}")
+                    assert share < 0.2 and share < 0.5 * plain
+            # keys appended later are indexed in the same space
+            extra = W.round_to_bf16((g.standard_normal((1, hkv, 300, 128)) * mag[None, :, None, :]).astype(np.float32))
+            ix.append(extra, W.round_to_bf16(g.standard_normal((1, hkv, 300, 128)).astype(np.float32)))
+            tau = G.oracle_taus(oracle, ix, q, frac=0.01)
+            idx, cnt, out = ix.query(q, tau)
+            G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=f"channels hq={hq} after append")
+
+
 def test_fp6_centres_unsupported_configurations(G):
     L = G.L
     ok = dict(batch=1, n_q_heads=8, n_kv_heads=2, capacity=1024, index_dtype=L.LVR_INDEX_FP6)
