@@ -47,8 +47,7 @@ sparse_attention_kernel(const void *__restrict__ K, const void *__restrict__ V, 
                         int P, int n_q_heads, int n_kv_heads, int G, float qscale) {
     const int64_t hq = blockIdx.y;
     const int p = blockIdx.x;
-    const int b = (int)(hq / n_q_heads), h = (int)(hq % n_q_heads);
-    const int bh = b * n_kv_heads + h / G;
+    const int bh = (int)((uint32_t)hq / (uint32_t)G);   // (hq / H_q) * H_kv + (hq % H_q) / G with H_q = H_kv * G: one 32-bit division
     const int lane = threadIdx.x & 63, sub = lane >> 4, li = lane & 15;
 
     const int32_t *my_idx = idx + hq * cap;
@@ -174,8 +173,7 @@ sparse_attention_wg_kernel(const void *__restrict__ K, const void *__restrict__ 
     __shared__ float s_m[NW], s_l[NW];
     __shared__ float s_o[NW][LVR_D];
     const int64_t hq = blockIdx.x;
-    const int b = (int)(hq / n_q_heads), h = (int)(hq % n_q_heads);
-    const int bh = b * n_kv_heads + h / G;
+    const int bh = (int)((uint32_t)hq / (uint32_t)G);   // (hq / H_q) * H_kv + (hq % H_q) / G with H_q = H_kv * G: one 32-bit division
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, sub = lane >> 4, li = lane & 15;
 
     int64_t cnt = count[hq * count_stride];
@@ -307,19 +305,19 @@ sparse_attention_wg_carry_kernel(const void *__restrict__ V, const int32_t *__re
     __shared__ float s_m[NW], s_l[NW];
     __shared__ float s_o[NW][LVR_D];
     const int64_t hq = blockIdx.x;
-    const int b = (int)(hq / n_q_heads), h = (int)(hq % n_q_heads);
-    const int bh = b * n_kv_heads + h / G;
+    const int bh = (int)((uint32_t)hq / (uint32_t)G);   // (hq / H_q) * H_kv + (hq % H_q) / G with H_q = H_kv * G: one 32-bit division
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, sub = lane >> 4, li = lane & 15;
     const int32_t *my_idx = idx + hq * cap;
     const float *my_sc = scores + hq * score_stride;
     const char *Vb = static_cast<const char *>(V) + (int64_t)bh * cap_rows * LVR_D * sizeof(KT);
     const int32_t *pslot = pos_slot ? pos_slot + (int64_t)bh * cap_rows : nullptr;
 
-    // trip 1
+    // trip 1 (the count first: it is read through the scalar unit, whose argument loads and the read itself form a
+    // chain of their own that should start before the vector loads are set up, not after)
+    int64_t cnt = count[hq * count_stride];
     const int64_t e_rel = (int64_t)(wave + NW * sub) * 16 + li;   // this lane's entry within a round of 1024
     int32_t pos = (e_rel < cap) ? my_idx[e_rel] : -1;
     float sc = (e_rel < cap && e_rel < score_stride) ? my_sc[e_rel] : 0.f;
-    int64_t cnt = count[hq * count_stride];
     const int32_t true_cnt = (int32_t)cnt;
     if (cnt > cap) cnt = cap;
     if (cnt < 0) cnt = 0;
@@ -437,8 +435,7 @@ sparse_attention_wg_carry_split_kernel(const void *__restrict__ V, const int32_t
     __shared__ float s_o[NW][CH];
     const int64_t hq = blockIdx.x / SPLIT;
     const int part = blockIdx.x % SPLIT;
-    const int b = (int)(hq / n_q_heads), h = (int)(hq % n_q_heads);
-    const int bh = b * n_kv_heads + h / G;
+    const int bh = (int)((uint32_t)hq / (uint32_t)G);   // (hq / H_q) * H_kv + (hq % H_q) / G with H_q = H_kv * G: one 32-bit division
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, sub = lane >> 4, li = lane & 15;
     const int grp = lane / LPR, lp = lane % LPR;   // this lane's row within a load, its 16-byte piece of the row part
     const int32_t *my_idx = idx + hq * cap;
@@ -446,11 +443,12 @@ sparse_attention_wg_carry_split_kernel(const void *__restrict__ V, const int32_t
     const char *Vb = static_cast<const char *>(V) + (int64_t)bh * cap_rows * LVR_D * sizeof(KT);
     const int32_t *pslot = pos_slot ? pos_slot + (int64_t)bh * cap_rows : nullptr;
 
-    // trip 1
+    // trip 1 (the count first: it is read through the scalar unit, whose argument loads and the read itself form a
+    // chain of their own that should start before the vector loads are set up, not after)
+    int64_t cnt = count[hq * count_stride];
     const int64_t e_rel = (int64_t)(wave + NW * sub) * 16 + li;   // this lane's entry within a round of 1024
     int32_t pos = (e_rel < cap) ? my_idx[e_rel] : -1;
     float sc = (e_rel < cap && e_rel < score_stride) ? my_sc[e_rel] : 0.f;
-    int64_t cnt = count[hq * count_stride];
     const int32_t true_cnt = (int32_t)cnt;
     if (cnt > cap) cnt = cap;
     if (cnt < 0) cnt = 0;

@@ -199,7 +199,6 @@ query_fused_kernel(const FusedArgs a) {
             }
         }
     };
-    const bool phaseA = !buffer_wg && !a.skip_bounds && tile0 < n_tiles && a.n_groups > 0;   // wave-uniform
     // Order of the first requests.  Vector memory loads return in order, so what the prologue needs (q for the
     // operand and the norms, the thresholds: a few KB that sit in the caches) is requested FIRST and the first
     // trip of centres right behind it: the prologue's arithmetic and its barrier then run while the centres
