@@ -121,13 +121,29 @@ def code_keys(K, coding):
     return np.moveaxis(C.reshape(n, 4, 4, 8), 1, 2).reshape(n, 128)
 
 
+def channel_factors(K):
+    """One power of two per coordinate, 2^round(L_c - o) with L_c = log2 of the coordinate's root mean square over the
+    keys and o the circular mean of the fractional parts of L (coordinates of about the same size then get the same
+    factor instead of being split by a rounding boundary that falls among them); exponents held to [-8, 8]."""
+    ms = (K.astype(np.float64) ** 2).mean(axis=0)
+    live = ms > 0
+    L = np.where(live, 0.5 * np.log2(np.where(live, ms, 1.0)), 0.0)
+    z = np.exp(2j * np.pi * L[live]).sum() if live.any() else 0.0
+    o = float(np.angle(z)) / (2 * np.pi) if z != 0 else 0.0
+    return 2.0 ** np.where(live, np.clip(np.rint(L - o), -8, 8), 0.0)
+
+
 def coded_keep(cid, n, coding, S=4, n_queries=3, kv_head=0):
     """Share of keys whose ball (coded centre, exact radius per coordinate block) reaches tau: per head and for
     the four heads of a KV head together (a key row is read if any head keeps it); also the mean radius relative
-    to the key's norm.  Every bound is checked to lie above the key's score."""
+    to the key's norm.  Every bound is checked to lie above the key's score.  A coding 'x/chan' codes the keys
+    divided coordinate by coordinate by channel_factors and meets them with q times the factors: every product
+    <q,k> is unchanged, the balls (centres, radii, the blocks' scales) live in the rescaled space."""
     c = W.CONFIGS[cid]
-    K = W.make_cache(cid, n=n, n_kv_heads=kv_head + 1).K[0, kv_head].astype(np.float64)
-    C = code_keys(K, coding)
+    K0 = W.make_cache(cid, n=n, n_kv_heads=kv_head + 1).K[0, kv_head].astype(np.float64)
+    a = channel_factors(K0) if coding.endswith("/chan") else np.ones(K0.shape[1])
+    K = K0 / a
+    C = code_keys(K, coding.split("/")[0])
     ds = 128 // S
     rad = np.stack([np.sqrt((((K - C)[:, s * ds:(s + 1) * ds]) ** 2).sum(1)) for s in range(S)])
     frac = c.get("qualify_frac", 0.005)
@@ -137,7 +153,7 @@ def coded_keep(cid, n, coding, S=4, n_queries=3, kv_head=0):
         Q = drift[(t * 85) % 256][0][:4] if drift is not None else W.make_queries(cid, n_q_heads=4, step=t)[0]
         any_keep = np.zeros(n, dtype=bool)
         for hq in range(4):
-            q = Q[hq].astype(np.float64)
+            q = Q[hq].astype(np.float64) * a
             sc = K @ q
             tau = float(W.tau_for_fraction(sc.astype(np.float32), frac))
             ub = C @ q + sum(rad[s] * np.linalg.norm(q[s * ds:(s + 1) * ds]) for s in range(S))
@@ -152,9 +168,9 @@ def coded_keep(cid, n, coding, S=4, n_queries=3, kv_head=0):
 
 if __name__ == "__main__":
     if sys.argv[1] == "codings":   # python -m oracle.pruning_power codings <config id> <n keys>
-        for coding in ("bf16", "e4m3", "e2m3"):
+        for coding in ("bf16", "e4m3", "e2m3", "e2m3/chan"):
             r = coded_keep(int(sys.argv[2]), int(sys.argv[3]), coding)
-            print(f"config {sys.argv[2]} n={sys.argv[3]} r=1 S=4 centres {coding:5s} keep per head {r['per_head']:.4f}  "
+            print(f"config {sys.argv[2]} n={sys.argv[3]} r=1 S=4 centres {coding:9s} keep per head {r['per_head']:.4f}  "
                   f"per KV head {r['per_kv_head']:.4f}  radius / |k| {r['relative_radius']:.4f}", flush=True)
         sys.exit(0)
     cid, n = int(sys.argv[1]), int(sys.argv[2])

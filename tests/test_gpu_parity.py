@@ -1455,8 +1455,15 @@ def test_fp6_index_follows_channels_of_very_different_size(G, oracle):
             d = e - np.log2(rms)
             # one offset per (sequence, KV head), then rounding to the nearest integer; the library estimates the
             # rms from every row here (4096 is its sample size), in fp32
+            from oracle import pruning_power as pp
             for h in range(hkv):
                 assert d[0, h].max() - d[0, h].min() <= 1.0 + 1e-3, (h, d[0, h].min(), d[0, h].max())
+                # the oracle's rule in fp64: the same exponents up to a common shift (the offset is only defined up to
+                # whole numbers), but for a channel that sits on a rounding boundary
+                want = np.log2(pp.channel_factors(K[0, h]))
+                diff = e[0, h] - want
+                shift = np.rint(np.median(diff))
+                assert np.all(np.abs(diff - shift) <= 1) and (diff == shift).mean() >= 0.97, (h, diff)
             for frac in (0.003, 0.03):
                 tau = G.oracle_taus(oracle, ix, q, frac=frac)
                 idx, cnt, out = ix.query(q, tau)
@@ -1467,7 +1474,6 @@ def test_fp6_index_follows_channels_of_very_different_size(G, oracle):
                 if frac < 0.01:
                     # what the same code WITHOUT the rescaling keeps (on the CPU: every key rounded to e2m3 with one
                     # scale per 32 coordinates, exact radii, the sum rule over four blocks)
-                    from oracle import pruning_power as pp
                     kept = 0
                     for kv in range(hkv):
                         Kd = K[0, kv].astype(np.float64)

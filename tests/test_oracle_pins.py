@@ -682,7 +682,7 @@ def test_coded_single_key_balls_on_the_cpu():
     (e4m3: 127 magnitudes up to 448 with eight steps per binade; e2m3: 32 magnitudes up to 7.5), every bound lies
     above its key's score (asserted inside), the exact centre keeps exactly the qualifying share per head, and a
     coarser code keeps more keys: bf16 < e4m3 < e2m3 with a scale per 32 coordinates, at radii of a few percent
-    of the key's norm."""
+    of the key's norm; dividing every coordinate by a power of two of its own first ('/chan') brings e2m3 back down."""
     from oracle import pruning_power as pp
     assert pp.E4M3.size == 127 and pp.E4M3[-1] == 448.0 and pp.E4M3[1] == 2.0 ** -9
     assert np.array_equal(pp.E4M3[(pp.E4M3 >= 1) & (pp.E4M3 < 2)], 1 + np.arange(8) / 8)
@@ -705,3 +705,22 @@ def test_coded_single_key_balls_on_the_cpu():
     assert r["bf16"]["relative_radius"] == 0.0 and abs(r["bf16"]["per_head"] - 0.01) < 1e-3
     assert r["bf16"]["per_kv_head"] < r["e4m3"]["per_kv_head"] < r["e2m3"]["per_kv_head"] < 0.3
     assert 0.015 < r["e4m3"]["relative_radius"] < r["e2m3"]["relative_radius"] < 0.06
+    # channel factors: powers of two that follow each coordinate's size; coordinates of about the same size get the
+    # same factor wherever their common size lies relative to a power of two, a coordinate that is zero keeps 1
+    g = np.random.default_rng(3)
+    base = g.standard_normal((2000, 128))
+    for size in (1.0, 1.4, 0.71, 3.0):          # 1.4 and 0.71 sit next to the rounding boundary of a plain round(log2)
+        a = pp.channel_factors(base * size)
+        assert np.all(a == a[0]) and np.log2(a[0]) == np.rint(np.log2(a[0]))
+    shift = g.integers(-6, 7, size=128)
+    a = pp.channel_factors(base * 2.0 ** shift)
+    assert np.array_equal(np.log2(a) - np.log2(a[0]), (shift - shift[0]).astype(np.float64))
+    z = base.copy()
+    z[:, 5] = 0.0
+    assert pp.channel_factors(z)[5] == 1.0
+    assert np.all(np.abs(np.log2(pp.channel_factors(base * 2.0 ** (3.0 * shift)))) <= 8)
+    # the rescaled code keeps fewer keys where the channels differ in size (config 3's keys), and its bounds hold
+    # (asserted inside coded_keep)
+    plain, chan = (pp.coded_keep(3, 4096, c, n_queries=2) for c in ("e2m3", "e2m3/chan"))
+    assert chan["per_kv_head"] < 0.8 * plain["per_kv_head"]
+    assert abs(pp.coded_keep(3, 4096, "bf16/chan", n_queries=1)["per_head"] - pp.coded_keep(3, 4096, "bf16", n_queries=1)["per_head"]) < 1e-12
