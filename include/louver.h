@@ -75,7 +75,7 @@ enum lvr_enclosing { LVR_ENCLOSE_BALL = 0, LVR_ENCLOSE_AABB = 1 };
  *         query kernel holds (coordinates 32 kk + 8 b + e, kk = 0..3, e = 0..7, for scale block b), so a
  *         lane decodes its share of a centre with one conversion instruction.  Balls with
  *         n_subspaces <= 4, bf16 caches, the fused query kernel (LVR_E_UNSUPPORTED otherwise).
- *         With at most four query heads per KV head such an index lives in a rescaled space:
+ *         Such an index lives in a rescaled space:
  *         coordinate c of every key of a (sequence, KV head) is divided by 2^e_c (e_c in [-8, 8], taken
  *         from the keys handed to lvr_build; zero before the first build), so that one large channel does
  *         not drown the 31 that share its scale; the query kernels multiply q_c by 2^e_c, which leaves
