@@ -22,8 +22,8 @@
 
 namespace {
 
-constexpr int SEG_MAX_TILES = 32;                          // tiles per wave (at most 64: lane `it` of a wave keeps the mask of its tile `it`)
-constexpr int SEG_MAX_GROUPS = 4 * SEG_MAX_TILES * 16;     // 4 waves x 32 tiles x 16 groups; the survivor list holds 16-bit offsets into the segment
+constexpr int SEG_MAX_TILES = 64;                          // tiles per wave (at most 64: lane `it` of a wave keeps the mask of its tile `it`)
+constexpr int SEG_MAX_GROUPS = 4 * SEG_MAX_TILES * 16;     // 4 waves x 64 tiles x 16 groups; the survivor list holds 16-bit offsets into the segment
 
 struct FusedArgs {
     const void *centres;

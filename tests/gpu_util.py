@@ -33,7 +33,8 @@ class Index:
 
     def __init__(self, K: np.ndarray, V: np.ndarray, dtype: str, n_q_heads: int, *, capacity=None,
                  group_size=4, n_subspaces=4, buffer_size=256, flags=0, grouping=L.LVR_GROUP_CONTIGUOUS,
-                 enclosing=L.LVR_ENCLOSE_BALL, scale=0.0, attn_splits=0, reservoir_size=0, seed=0, index_dtype=0):
+                 enclosing=L.LVR_ENCLOSE_BALL, scale=0.0, attn_splits=0, reservoir_size=0, seed=0, index_dtype=0,
+                 query_workgroups=0):
         batch, hkv, n, d = K.shape
         self.dtype = dtype
         self.K, self.V = K.copy(), V.copy()
@@ -45,7 +46,7 @@ class Index:
                                  group_size=group_size, n_subspaces=n_subspaces, buffer_size=buffer_size,
                                  grouping=grouping, enclosing=enclosing, flags=flags, capacity=capacity or max(n, 1), scale=scale,
                                  attn_splits=attn_splits, reservoir_size=reservoir_size, seed=seed,
-                                 index_dtype=index_dtype)
+                                 index_dtype=index_dtype, query_workgroups=query_workgroups)
         self.h = L.lvr_create(self.cfg)
         self.Kd, self.Vd = to_device(K, dtype), to_device(V, dtype)
         L.lvr_build(self.h, self.Kd, self.Vd)

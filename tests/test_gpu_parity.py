@@ -1496,6 +1496,27 @@ def test_fp6_index_follows_channels_of_very_different_size(G, oracle):
             G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=f"channels hq={hq} after append")
 
 
+@pytest.mark.parametrize("index_dtype", ["auto", "same", "fp8"])
+@pytest.mark.parametrize("r,hkv,gq", [(1, 2, 4), (4, 1, 8), (2, 1, 2)])
+def test_every_segment_size_of_the_query_launch(G, oracle, index_dtype, r, hkv, gq):
+    """A query launch cuts the groups of a (sequence, KV head) into segments of 64 * 2^k groups, one workgroup each
+    (k = 0..6: 1 to 64 tiles of 16 groups per wave), sized after the number of workgroups it aims at.  Here that
+    target is set from 1 (the largest segments, 4096 groups) to far more than there are tiles (the smallest), on a
+    cache whose last segment is ragged and which has a buffer; every size must give the oracle's sets."""
+    L = G.L
+    n = 70001 if r != 2 else 35001
+    cache = _small_cache(3, n, hkv=hkv)
+    hq = hkv * gq
+    q = W.make_queries(2, n_q_heads=hq, step=1)
+    dt = {"auto": L.LVR_INDEX_AUTO, "same": L.LVR_INDEX_SAME, "fp8": L.LVR_INDEX_FP8}[index_dtype]
+    # with 2 x 70001 groups: 64, 64, 32, 16, 8, 4, 2, 1 tiles per wave
+    for wgs in (1, 40, 100, 150, 300, 600, 1200, 100000):
+        with G.Index(cache.K, cache.V, "bf16", hq, group_size=r, buffer_size=64, index_dtype=dt, query_workgroups=wgs) as ix:
+            tau = G.oracle_taus(oracle, ix, q, frac=0.004)
+            idx, cnt, out = ix.query(q, tau, fused=True)
+            G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=f"segments r={r} {index_dtype} target {wgs}")
+
+
 def test_fp6_centres_unsupported_configurations(G):
     L = G.L
     ok = dict(batch=1, n_q_heads=8, n_kv_heads=2, capacity=1024, index_dtype=L.LVR_INDEX_FP6)
