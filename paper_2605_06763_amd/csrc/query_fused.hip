@@ -76,11 +76,11 @@ query_fused_kernel(const FusedArgs a) {
         float qscore[4][HB][4][LVR_QCAP];
     } s_u;
     static_assert(sizeof(s_u.bq) == sizeof(s_u.qscore), "aliasing assumes equal sizes");
-    // W = 8: main operand and the operand of the third terms; with a rescaled 6-bit index (CS8) that pair is the bound
-    // phase's (q_c * 2^e_c) and a second pair holds q itself for the key-row phase
+    // W = 8: main operand and the operand of the third terms (q itself).  With a rescaled 6-bit index (CS8) the bound
+    // phase needs the same pair for q_c * 2^e_c: that pair lives in the bytes of the emission queues, which are idle
+    // until the key-row phase (with both pairs held for good the workgroup's LDS goes past a quarter of a compute unit's).
     constexpr bool CS8 = CF == 2 && W == 8;
-    constexpr int KP8 = CS8 ? 2 : 0;   // first operand of the key-row phase
-    __shared__ uint4 s_bq8[W == 8 ? (CS8 ? 4 : 2) : 1][4][64];
+    __shared__ uint4 s_bq8[W == 8 ? 2 : 1][4][64];
     // BL: with eight heads per KV head the query operand (two head blocks, 32 registers) stays in LDS
     // and a lane fetches its pieces right before the matrix instructions that use them; that brings
     // the kernel back under the register budget of four waves per SIMD.  The staging area then keeps
@@ -95,7 +95,9 @@ query_fused_kernel(const FusedArgs a) {
     __shared__ union {
         int32_t queue[4][HB][W][LVR_QCAP];
         uint4 stash[HB][4][64];
+        uint4 bq8s[CS8 ? 2 : 1][CS8 ? 4 : 1][CS8 ? 64 : 1];   // CS8: the bound phase's operands
     } s_qu;
+    static_assert(!CS8 || sizeof(s_qu.bq8s) <= sizeof(s_qu.queue), "the rescaled operands fit the queues' bytes");
     auto &s_queue = s_qu.queue;
     __shared__ uint16_t s_list[SEG_MAX_GROUPS];   // surviving groups, as offsets from the segment's first group
     __shared__ int s_tot[4];
@@ -294,8 +296,8 @@ query_fused_kernel(const FusedArgs a) {
     lvr_bf16x8 bq[HB][4], bq2[ENC ? HB : 1][4];
     bool third = false;   // W = 8: some head's query has more than 16 significant bits (the same in every thread)
     if constexpr (CS8) {   // both sync; a third term is there for q exactly when it is there for q times powers of two
-        lvr_build_q_frags8_wg(a.q + hq0 * LVR_D, a.G, 1.0f, s_bq8, KP8);
-        third = lvr_build_q_frags8_wg(a.q + hq0 * LVR_D, a.G, 1.0f, s_bq8, 0,
+        lvr_build_q_frags8_wg(a.q + hq0 * LVR_D, a.G, 1.0f, s_bq8);
+        third = lvr_build_q_frags8_wg(a.q + hq0 * LVR_D, a.G, 1.0f, s_qu.bq8s, 0,
                                       reinterpret_cast<const float *>(a.chan_exp + (int64_t)bh * LVR_CHAN_STRIDE + LVR_D));
     } else if constexpr (W == 8) third = lvr_build_q_frags8_wg(a.q + hq0 * LVR_D, a.G, 1.0f, s_bq8);   // syncs
     else lvr_exchange_q_frags_wg<HB>(qraw, a.G, 1.0f, s_u.bq, bq, ENC ? 1 : 0);   // syncs
@@ -337,7 +339,16 @@ query_fused_kernel(const FusedArgs a) {
     };
     (void)fetch_bq;
     (void)fetch_bq2;
+    auto fetch_bq8s = [&](int which, lvr_bf16x8 (&b)[4]) {   // the bound phase's operands (CS8: the rescaled ones)
+        if constexpr (CS8) {
+            int z;
+            asm volatile("v_mov_b32 %0, 0" : "=v"(z));
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) b[kk] = __builtin_bit_cast(lvr_bf16x8, s_qu.bq8s[which][kk][lane + z]);
+        } else fetch_bq8(which, b);
+    };
     (void)fetch_bq8;
+    (void)fetch_bq8s;
     (void)third;
     lvr_bf16x8 rbq[RM ? HB : 1];
     if constexpr (RM) {
@@ -523,8 +534,8 @@ query_fused_kernel(const FusedArgs a) {
                         } else if constexpr (ENC) sc = lvr_bound_tile2(ac, bq[hb], ac2, bq2[hb], ra, rbq[hb]);
                         else if constexpr (W == 8) {
                             lvr_bf16x8 b[4], b3[4];
-                            fetch_bq8(0, b);
-                            if (third) fetch_bq8(1, b3);
+                            fetch_bq8s(0, b);
+                            if (third) fetch_bq8s(1, b3);
                             sc = lvr_bound_tile8(ac, b, b3, third, ra, rbq[hb]);
                         } else if constexpr (BL) {
                             lvr_bf16x8 b[4];
@@ -540,8 +551,8 @@ query_fused_kernel(const FusedArgs a) {
                         } else if constexpr (ENC) sc = lvr_score_tile2(ac, bq[hb], ac2, bq2[hb]);
                         else if constexpr (W == 8) {
                             lvr_bf16x8 b[4], b3[4];
-                            fetch_bq8(0, b);
-                            if (third) fetch_bq8(1, b3);
+                            fetch_bq8s(0, b);
+                            if (third) fetch_bq8s(1, b3);
                             sc = lvr_score_tile8(ac, b, b3, third);
                         } else if constexpr (BL) {
                             lvr_bf16x8 b[4];
@@ -711,8 +722,8 @@ query_fused_kernel(const FusedArgs a) {
             } else if constexpr (ENC) s = lvr_score_tile2(av[u], bq[hb], av[u], bq2[hb]);
             else if constexpr (W == 8) {
                 lvr_bf16x8 b[4], b3[4];
-                fetch_bq8(KP8, b);
-                if (third) fetch_bq8(KP8 + 1, b3);
+                fetch_bq8(0, b);
+                if (third) fetch_bq8(1, b3);
                 s = lvr_score_tile8(av[u], b, b3, third);
             } else if constexpr (BL) {
                 lvr_bf16x8 b[4];
