@@ -318,9 +318,10 @@ def measure(cid, args, *, group_size, steps, warmup, full, cpu_seconds, legs=Tru
     roofline = dict(bound="hbm", kernel=kernel_name, achieved=round(achieved, 1), peak=HBM_PEAK_GBS,
                     unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None, traffic_source=None,
                     bytes_per_launch=int(query_bytes), avg_launch_us=round(filt["avg_us"], 2),
-                    launch_time_source="HIP event pairs recorded by the library around every launch of the kernel, in a second pass "
-                                       "over the timed steps; a pair also brackets the launch latency that back-to-back steps hide, so it "
-                                       "reads 2-3 us more than the kernel's duration in a rocprofv3 trace of the same command "
+                    launch_time_source="a HIP event pair per launch of the kernel, handed to the dispatch itself (hipExtLaunchKernelGGL: "
+                                       "the events hold the kernel's own start and end), in a second pass over the timed steps on the "
+                                       "library's stream; the events between the kernels keep a step's launches from running back to back, "
+                                       "so a launch reads about 1 us more than in a rocprofv3 trace of the same command "
                                        "(profiles/decode_step_config3_kernel_trace.md)")
     # HBM bytes per launch measured OFFLINE with rocprofv3 --pmc on this same command (the counters cannot
     # be read from inside the run); only the default options of a workload have a figure

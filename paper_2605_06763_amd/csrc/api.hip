@@ -195,21 +195,29 @@ int publish_pending(lvr_index *ix, hipStream_t st, bool force) {
     return LVR_OK;
 }
 
-// Optional event pair around one kernel launch.
+// Optional event pair around one kernel launch.  in_dispatch: the launcher passes the pair to the dispatch (the events
+// then hold the kernel's own start and end times); otherwise the pair is recorded on the stream before and after the
+// launch, which also brackets the launch latency that back-to-back launches hide (2-3 us on a 25 us kernel).
 struct Timed {
     lvr_index *ix;
     hipStream_t st;
     int slot;
-    Timed(lvr_index *ix_, int kind, hipStream_t st_) : ix(ix_), st(st_), slot(-1) {
+    bool in_dispatch;
+    Timed(lvr_index *ix_, int kind, hipStream_t st_, bool in_dispatch_ = false) : ix(ix_), st(st_), slot(-1), in_dispatch(in_dispatch_) {
         if (ix->prof_on && ix->prof_used + 2 <= ix->prof_cap) {
             slot = ix->prof_used;
             ix->prof_used += 2;
             ix->prof_kind[slot / 2] = (uint8_t)kind;
-            (void)hipEventRecord(ix->prof_events[slot], st);
+            if (in_dispatch) {
+                ix->launch_start = ix->prof_events[slot];
+                ix->launch_stop = ix->prof_events[slot + 1];
+            } else
+                (void)hipEventRecord(ix->prof_events[slot], st);
         }
     }
     ~Timed() {
-        if (slot >= 0) (void)hipEventRecord(ix->prof_events[slot + 1], st);
+        if (slot >= 0 && !in_dispatch) (void)hipEventRecord(ix->prof_events[slot + 1], st);
+        if (in_dispatch) ix->launch_start = ix->launch_stop = nullptr;
     }
 };
 
@@ -576,7 +584,7 @@ int enqueue_query(lvr_index *ix, const float *q, const float *tau, int32_t *out_
         Timed t(ix, LVR_K_FILTER, st);
         LVR_HIP(lvr_launch_label_filter(ix, q, tau, out_idx, cap, st));
     } else if (fused) {
-        Timed t(ix, LVR_K_FILTER, st);
+        Timed t(ix, LVR_K_FILTER, st, true);
         LVR_HIP(lvr_launch_query_fused(ix, q, tau, tau_s, out_idx, cap, st, k_new, v_new, m_new));
         ix->n_total += m_new;
     } else {
@@ -615,7 +623,7 @@ int decode_step_impl(lvr_index *ix, const float *q, const float *tau, float *out
     const bool use_scores = fused && (one_launch || scores_whatever_the_form);
     const float *carried = use_scores ? ix->scores : nullptr;
     if (one_launch) {   // reads the set sizes from the internal counters and hands them to the caller
-        Timed t(ix, LVR_K_ATTN_PARTIAL, st);
+        Timed t(ix, LVR_K_ATTN_PARTIAL, st, true);
         LVR_HIP(lvr_launch_sparse_attention_wg(ix, q, out_idx, carried, lvr_head_count(ix), LVR_CNT_STRIDE, cap, out, out_count, st));
         ix->counters_dirty = 0;
         return LVR_OK;
@@ -692,7 +700,7 @@ int lvr_sparse_attention(lvr_index *ix, const float *q, const int32_t *idx, cons
     if (!aligned4(q) || !aligned4(idx) || !aligned4(count) || !aligned4(out)) return LVR_E_INVALID;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (one_launch_attention(ix)) {
-        Timed t(ix, LVR_K_ATTN_PARTIAL, st);
+        Timed t(ix, LVR_K_ATTN_PARTIAL, st, true);
         LVR_HIP(lvr_launch_sparse_attention_wg(ix, q, idx, nullptr, count, 1, cap, out, nullptr, st));
         return LVR_OK;
     }

@@ -10,6 +10,8 @@
 //
 // Logits are kept in base-2 units (q is pre-multiplied by sigma * log2 e) so the exponentials
 // are single exp2 instructions; the softmax is unchanged by the change of base.
+#include <hip/hip_ext.h>
+
 #include "mfma_score.h"
 
 namespace {
@@ -912,11 +914,18 @@ hipError_t lvr_launch_sparse_attention_wg(lvr_index *ix, const float *q, const i
                                           int32_t *publish_count, hipStream_t st) {
     const int n_bhq = lvr_n_bhq(ix);
     const float qscale = ix->sigma * LOG2E;
+    // a pair of events handed in by the caller goes into the dispatch itself (they then read the kernel's own start and end)
+    hipEvent_t ev0 = ix->launch_start, ev1 = ix->launch_stop;
+#define LVR_AT_LAUNCH(KERNEL, GRID, ...)                                                                    \
+    do {                                                                                                    \
+        if (ev0) hipExtLaunchKernelGGL(KERNEL, GRID, dim3(1024), 0, st, ev0, ev1, 0, __VA_ARGS__);           \
+        else hipLaunchKernelGGL(KERNEL, GRID, dim3(1024), 0, st, __VA_ARGS__);                              \
+    } while (0)
 #define LVR_WG_LAUNCH(KT, CARRY)                                                                                         \
-    hipLaunchKernelGGL((sparse_attention_wg_kernel<KT, CARRY>), dim3((unsigned)n_bhq), dim3(1024), 0, st, ix->K, ix->V,  \
-                       ix->pos_slot, q, idx, scores, ix->cap_rows, count, count_stride, cap, out, ix->cap_rows,          \
-                       ix->n_total, ix->cfg.n_q_heads, ix->cfg.n_kv_heads, ix->G, qscale, lvr_head_count(ix),            \
-                       lvr_head_stat(ix), publish_count)
+    LVR_AT_LAUNCH((sparse_attention_wg_kernel<KT, CARRY>), dim3((unsigned)n_bhq), ix->K, ix->V,                          \
+                  ix->pos_slot, q, idx, scores, ix->cap_rows, count, count_stride, cap, out, ix->cap_rows,               \
+                  ix->n_total, ix->cfg.n_q_heads, ix->cfg.n_kv_heads, ix->G, qscale, lvr_head_count(ix),                 \
+                  lvr_head_stat(ix), publish_count)
     if (ix->cfg.kv_dtype == LVR_BF16) {
         // With more heads than compute units the workgroups queue up behind each other and the lighter kernel wins
         // (512 heads: 24.0 against 26.0 us); with one workgroup per unit the shorter chain of trips does (32 heads:
@@ -928,12 +937,12 @@ hipError_t lvr_launch_sparse_attention_wg(lvr_index *ix, const float *q, const i
         // length stands in as it does for the launch form.
         if (scores && n_bhq > 256) LVR_WG_LAUNCH(lvr_bf16_t, true);
         else if (scores && n_bhq <= 128 && publish_count && ix->n_total > 65536)
-            hipLaunchKernelGGL((sparse_attention_wg_carry_split_kernel<lvr_bf16_t, 2>), dim3((unsigned)n_bhq * 2), dim3(1024), 0, st,
+            LVR_AT_LAUNCH((sparse_attention_wg_carry_split_kernel<lvr_bf16_t, 2>), dim3((unsigned)n_bhq * 2),
                                ix->V, ix->pos_slot, idx, scores, ix->cap_rows, count, count_stride, cap, out, ix->cap_rows,
                                ix->n_total, ix->cfg.n_q_heads, ix->cfg.n_kv_heads, ix->G, qscale, lvr_head_count(ix),
                                lvr_head_stat(ix), publish_count, lvr_head_ticket(ix));
         else if (scores)
-            hipLaunchKernelGGL((sparse_attention_wg_carry_kernel<lvr_bf16_t>), dim3((unsigned)n_bhq), dim3(1024), 0, st, ix->V,
+            LVR_AT_LAUNCH((sparse_attention_wg_carry_kernel<lvr_bf16_t>), dim3((unsigned)n_bhq), ix->V,
                                ix->pos_slot, idx, scores, ix->cap_rows, count, count_stride, cap, out, ix->cap_rows,
                                ix->n_total, ix->cfg.n_q_heads, ix->cfg.n_kv_heads, ix->G, qscale, lvr_head_count(ix),
                                lvr_head_stat(ix), publish_count);
@@ -943,6 +952,7 @@ hipError_t lvr_launch_sparse_attention_wg(lvr_index *ix, const float *q, const i
         else LVR_WG_LAUNCH(lvr_f32_t, false);
     }
 #undef LVR_WG_LAUNCH
+#undef LVR_AT_LAUNCH
     return hipGetLastError();
 }
 

@@ -86,6 +86,9 @@ struct lvr_index {
     int prof_cap;             // events allocated
     hipEvent_t *prof_events;  // [prof_cap]
     uint8_t *prof_kind;       // [prof_cap / 2] kernel kind of each pair
+    hipEvent_t launch_start, launch_stop;   // non-null: the next launch of a kernel that supports it hands these two to
+                                            // the dispatch itself (they then read the kernel's own start and end, as a
+                                            // profiler's trace does, instead of bracketing the launch on the stream)
 };
 
 enum lvr_kernel_kind {

@@ -17,6 +17,8 @@
 // counts (publish_counts_kernel, combine_kernel) clear them for the next query.
 #include <type_traits>
 
+#include <hip/hip_ext.h>
+
 #include "emitter.h"
 #include "mfma_score.h"
 
@@ -794,14 +796,25 @@ query_fused_kernel(const FusedArgs a) {
     }
 }
 
+// One launch of an instantiation.  With a pair of events in `ev` the dispatch itself carries them (they read the kernel's
+// own start and end); without, a plain launch.
+struct LaunchEvents {
+    hipEvent_t start, stop;
+};
+#define LVR_QF_LAUNCH(KERNEL)                                                                                        \
+    do {                                                                                                             \
+        if (ev.start) hipExtLaunchKernelGGL(KERNEL, grid, dim3(256), dyn_lds, st, ev.start, ev.stop, 0, a);           \
+        else hipLaunchKernelGGL(KERNEL, grid, dim3(256), dyn_lds, st, a);                                            \
+    } while (0)
+
 template <int UA, int W>
-void launch_s(dim3 grid, unsigned dyn_lds, hipStream_t st, const FusedArgs &a, int S) {
+void launch_s(dim3 grid, unsigned dyn_lds, hipStream_t st, const FusedArgs &a, int S, const LaunchEvents &ev) {
     switch (S) {
-        case 1: hipLaunchKernelGGL((query_fused_kernel<1, 1, UA, 0, 0, 0, W>), grid, dim3(256), dyn_lds, st, a); break;
-        case 2: hipLaunchKernelGGL((query_fused_kernel<1, 2, UA, 0, 0, 0, W>), grid, dim3(256), dyn_lds, st, a); break;
-        case 4: hipLaunchKernelGGL((query_fused_kernel<1, 4, UA, 0, 0, 0, W>), grid, dim3(256), dyn_lds, st, a); break;
-        case 8: hipLaunchKernelGGL((query_fused_kernel<1, 8, UA, 0, 0, 0, W>), grid, dim3(256), dyn_lds, st, a); break;
-        default: hipLaunchKernelGGL((query_fused_kernel<1, 16, UA, 0, 0, 0, W>), grid, dim3(256), dyn_lds, st, a); break;
+        case 1: LVR_QF_LAUNCH((query_fused_kernel<1, 1, UA, 0, 0, 0, W>)); break;
+        case 2: LVR_QF_LAUNCH((query_fused_kernel<1, 2, UA, 0, 0, 0, W>)); break;
+        case 4: LVR_QF_LAUNCH((query_fused_kernel<1, 4, UA, 0, 0, 0, W>)); break;
+        case 8: LVR_QF_LAUNCH((query_fused_kernel<1, 8, UA, 0, 0, 0, W>)); break;
+        default: LVR_QF_LAUNCH((query_fused_kernel<1, 16, UA, 0, 0, 0, W>)); break;
     }
 }
 
@@ -861,6 +874,7 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
     dim3 grid((unsigned)(a.n_segs + has_buffer), (unsigned)n_bh);
     // more workgroups than 5 x 256: hold the residency at four per compute unit, so that the rounds are whole
     const unsigned dyn_lds = (int64_t)grid.x * grid.y > 1280 ? 20480u : 0u;
+    const LaunchEvents ev = {ix->launch_start, ix->launch_stop};
     // one centre tile per trip for the small segments of short contexts, two per trip for long ones
     // (measured crossover between 32k and 128k keys); four per trip costs a wave per SIMD and 12 us
     const bool one = tpw == 1;
@@ -868,9 +882,9 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
         const int S = ix->cfg.n_subspaces;
 #define LVR_Q1B_LAUNCH(HB, CF)                                                                                 \
     do {                                                                                                        \
-        if (S == 1) hipLaunchKernelGGL((query_fused_kernel<HB, 1, 1, 1, 1, CF>), grid, dim3(256), dyn_lds, st, a);   \
-        else if (S == 2) hipLaunchKernelGGL((query_fused_kernel<HB, 2, 1, 1, 1, CF>), grid, dim3(256), dyn_lds, st, a); \
-        else hipLaunchKernelGGL((query_fused_kernel<HB, 4, 1, 1, 1, CF>), grid, dim3(256), dyn_lds, st, a);          \
+        if (S == 1) LVR_QF_LAUNCH((query_fused_kernel<HB, 1, 1, 1, 1, CF>));   \
+        else if (S == 2) LVR_QF_LAUNCH((query_fused_kernel<HB, 2, 1, 1, 1, CF>)); \
+        else LVR_QF_LAUNCH((query_fused_kernel<HB, 4, 1, 1, 1, CF>));          \
     } while (0)
         if (ix->G <= 4) {
             if (ix->cf8) LVR_Q1B_LAUNCH(1, 1);
@@ -886,12 +900,12 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
         const int S = ix->cfg.n_subspaces;
 #define LVR_Q1_LAUNCH(HB, CF)                                                                                  \
     do {                                                                                                        \
-        if (S == 1) hipLaunchKernelGGL((query_fused_kernel<HB, 1, 1, 0, 1, CF>), grid, dim3(256), dyn_lds, st, a);   \
-        else if (S == 2) hipLaunchKernelGGL((query_fused_kernel<HB, 2, 1, 0, 1, CF>), grid, dim3(256), dyn_lds, st, a); \
-        else if (S == 4) hipLaunchKernelGGL((query_fused_kernel<HB, 4, 1, 0, 1, CF>), grid, dim3(256), dyn_lds, st, a); \
+        if (S == 1) LVR_QF_LAUNCH((query_fused_kernel<HB, 1, 1, 0, 1, CF>));   \
+        else if (S == 2) LVR_QF_LAUNCH((query_fused_kernel<HB, 2, 1, 0, 1, CF>)); \
+        else if (S == 4) LVR_QF_LAUNCH((query_fused_kernel<HB, 4, 1, 0, 1, CF>)); \
         else if constexpr (!CF) {                                                                              \
-            if (S == 8) hipLaunchKernelGGL((query_fused_kernel<HB, 8, 1, 0, 1, 0>), grid, dim3(256), dyn_lds, st, a); \
-            else hipLaunchKernelGGL((query_fused_kernel<HB, 16, 1, 0, 1, 0>), grid, dim3(256), dyn_lds, st, a);       \
+            if (S == 8) LVR_QF_LAUNCH((query_fused_kernel<HB, 8, 1, 0, 1, 0>)); \
+            else LVR_QF_LAUNCH((query_fused_kernel<HB, 16, 1, 0, 1, 0>));       \
         }                                                                                                       \
     } while (0)
         if (ix->G <= 4) {
@@ -907,17 +921,17 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
         return hipGetLastError();
     }
     if (ix->box && ix->cf8) {   // boxes with 8-bit corners
-        if (ix->G <= 4) hipLaunchKernelGGL((query_fused_kernel<1, 1, 1, 1, 0, 1>), grid, dim3(256), dyn_lds, st, a);
-        else hipLaunchKernelGGL((query_fused_kernel<2, 1, 1, 1, 0, 1>), grid, dim3(256), dyn_lds, st, a);
+        if (ix->G <= 4) LVR_QF_LAUNCH((query_fused_kernel<1, 1, 1, 1, 0, 1>));
+        else LVR_QF_LAUNCH((query_fused_kernel<2, 1, 1, 1, 0, 1>));
         return hipGetLastError();
     }
     if (ix->cf8 || ix->cf6) {   // 8-bit or 6-bit centres
         const int S = ix->cfg.n_subspaces;
 #define LVR_CODED_LAUNCH(UA, W, CF)                                                                               \
     do {                                                                                                      \
-        if (S == 1) hipLaunchKernelGGL((query_fused_kernel<1, 1, UA, 0, 0, CF, W>), grid, dim3(256), dyn_lds, st, a);  \
-        else if (S == 2) hipLaunchKernelGGL((query_fused_kernel<1, 2, UA, 0, 0, CF, W>), grid, dim3(256), dyn_lds, st, a); \
-        else hipLaunchKernelGGL((query_fused_kernel<1, 4, UA, 0, 0, CF, W>), grid, dim3(256), dyn_lds, st, a);         \
+        if (S == 1) LVR_QF_LAUNCH((query_fused_kernel<1, 1, UA, 0, 0, CF, W>));  \
+        else if (S == 2) LVR_QF_LAUNCH((query_fused_kernel<1, 2, UA, 0, 0, CF, W>)); \
+        else LVR_QF_LAUNCH((query_fused_kernel<1, 4, UA, 0, 0, CF, W>));         \
     } while (0)
 #define LVR_CODED_ANY_LAUNCH(UA, W)            \
     do {                                 \
@@ -936,16 +950,16 @@ hipError_t lvr_launch_query_fused(lvr_index *ix, const float *q, const float *ta
         return hipGetLastError();
     }
     if (ix->box) {   // boxes: one allowance per group, one tile (two rows per group) per trip
-        if (ix->G <= 4) hipLaunchKernelGGL((query_fused_kernel<1, 1, 1, 1>), grid, dim3(256), dyn_lds, st, a);
-        else hipLaunchKernelGGL((query_fused_kernel<2, 1, 1, 1>), grid, dim3(256), dyn_lds, st, a);
+        if (ix->G <= 4) LVR_QF_LAUNCH((query_fused_kernel<1, 1, 1, 1>));
+        else LVR_QF_LAUNCH((query_fused_kernel<2, 1, 1, 1>));
         return hipGetLastError();
     }
     if (ix->G <= 4) {
-        if (one) launch_s<1, 4>(grid, dyn_lds, st, a, ix->cfg.n_subspaces);
-        else launch_s<2, 4>(grid, dyn_lds, st, a, ix->cfg.n_subspaces);
+        if (one) launch_s<1, 4>(grid, dyn_lds, st, a, ix->cfg.n_subspaces, ev);
+        else launch_s<2, 4>(grid, dyn_lds, st, a, ix->cfg.n_subspaces, ev);
     } else {   // up to eight heads in one operand
-        if (one) launch_s<1, 8>(grid, dyn_lds, st, a, ix->cfg.n_subspaces);
-        else launch_s<2, 8>(grid, dyn_lds, st, a, ix->cfg.n_subspaces);
+        if (one) launch_s<1, 8>(grid, dyn_lds, st, a, ix->cfg.n_subspaces, ev);
+        else launch_s<2, 8>(grid, dyn_lds, st, a, ix->cfg.n_subspaces, ev);
     }
     return hipGetLastError();
 }
