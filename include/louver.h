@@ -338,9 +338,12 @@ int lvr_export_channel_scales(lvr_index *ix, int8_t *exp_host);
 int lvr_export_labels(lvr_index *ix, int32_t *labels_host);
 
 /* Per-kernel GPU time, for measurement (App. "Kernel Implementation Details" names the stages).
- * While enabled, every kernel launch of every call is bracketed by a pair of HIP events on the
- * call's stream (events come from a pool allocated by lvr_profile_enable, so the hot-path
- * calls still allocate nothing); when the pool of `max_launches` pairs is used up further
+ * While enabled, every kernel launch of every call gets a pair of HIP events (from a pool
+ * allocated by lvr_profile_enable, so the hot-path calls still allocate nothing).  The fused
+ * query kernel and the one-launch attention kernels carry their pair in the dispatch itself
+ * (the events hold the kernel's own start and end, as a profiler's trace does); the other
+ * kernels are bracketed by a pair recorded on the call's stream, which also measures the launch
+ * latency (2-3 us).  When the pool of `max_launches` pairs is used up further
  * launches are simply not timed.  lvr_profile_read synchronises the device, adds up the
  * elapsed time of each pair by kernel, and empties the pool. */
 typedef struct lvr_profile {
