@@ -1496,6 +1496,44 @@ def test_fp6_index_follows_channels_of_very_different_size(G, oracle):
             G.check_step(oracle, ix, q, tau, idx, cnt, out, tag=f"channels hq={hq} after append")
 
 
+def test_channel_scales_follow_the_build_and_only_a_6_bit_index_has_them(G, oracle):
+    """The exponents belong to the keys of the last lvr_build: a rebuild on keys with other channel sizes replaces them
+    (and the queries stay the oracle's); an index in another centre format reports zeros; before any build the call is
+    refused."""
+    L = G.L
+    g = np.random.default_rng(91)
+    n, hkv, hq = 2048, 1, 4
+    V = W.round_to_bf16(g.standard_normal((1, hkv, n, 128)).astype(np.float32))
+    mag1 = 2.0 ** g.integers(-4, 5, size=128).astype(np.float64)
+    mag2 = mag1[::-1].copy()
+    K1 = W.round_to_bf16((g.standard_normal((1, hkv, n, 128)) * mag1).astype(np.float32))
+    K2 = W.round_to_bf16((g.standard_normal((1, hkv, n, 128)) * mag2).astype(np.float32))
+    q = g.standard_normal((1, hq, 128)).astype(np.float32)
+    with G.Index(K1, V, "bf16", hq, group_size=1) as ix:       # the default format for balls: 6-bit
+        e1 = L.lvr_export_channel_scales(ix.h, ix.cfg)[0, 0].astype(np.int64)
+        assert np.array_equal(e1 - e1[0], (np.log2(mag1) - np.log2(mag1[0])).astype(np.int64))   # sizes are exact powers of two apart
+        tau = G.oracle_taus(oracle, ix, q, frac=0.01)
+        idx, cnt, out = ix.query(q, tau)
+        G.check_step(oracle, ix, q, tau, idx, cnt, out, tag="scales, first build")
+        L.lvr_build(ix.h, G.to_device(K2, "bf16"), G.to_device(V, "bf16"))
+        ix.K, ix.V = K2.copy(), V.copy()
+        e2 = L.lvr_export_channel_scales(ix.h, ix.cfg)[0, 0].astype(np.int64)
+        assert np.array_equal(e2 - e2[0], (np.log2(mag2) - np.log2(mag2[0])).astype(np.int64))
+        tau = G.oracle_taus(oracle, ix, q, frac=0.01)
+        idx, cnt, out = ix.query(q, tau)
+        G.check_step(oracle, ix, q, tau, idx, cnt, out, tag="scales, rebuilt")
+    for dt in (L.LVR_INDEX_SAME, L.LVR_INDEX_FP8):
+        with G.Index(K1, V, "bf16", hq, group_size=1, index_dtype=dt) as ix:
+            assert not L.lvr_export_channel_scales(ix.h, ix.cfg).any()
+    cfg = L.make_config(batch=1, n_q_heads=hq, n_kv_heads=hkv, capacity=256)
+    h = L.lvr_create(cfg)
+    try:
+        with pytest.raises(L.LouverError):
+            L.lvr_export_channel_scales(h, cfg)
+    finally:
+        L.lvr_destroy(h)
+
+
 @pytest.mark.parametrize("index_dtype", ["auto", "same", "fp8"])
 @pytest.mark.parametrize("r,hkv,gq", [(1, 2, 4), (4, 1, 8), (2, 1, 2)])
 def test_every_segment_size_of_the_query_launch(G, oracle, index_dtype, r, hkv, gq):
