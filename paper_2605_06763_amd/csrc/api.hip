@@ -608,20 +608,15 @@ int decode_step_impl(lvr_index *ix, const float *q, const float *tau, float *out
                      int64_t cap, hipStream_t st, const void *k_new, const void *v_new, int64_t m_new) {
     int rc = enqueue_query(ix, q, tau, out_idx, cap, st, nullptr, k_new, v_new, m_new);
     if (rc != LVR_OK) return rc;
-    // The fused query kernel leaves the raw score of every emitted key beside its position; an
-    // attention that uses it gathers V rows only.  That halves the attention's traffic, but the query
-    // launch that FOLLOWS such an attention was measured ~3 us slower at 128k keys (it no longer finds
-    // the retrieved K rows' pages and lines touched just before it), which is more than the
-    // partials-plus-combine form gains; so the scores are used by the one-launch form and whenever
-    // K and V sit behind the host link.
+    // The fused query kernel leaves the raw score of every emitted key beside its position; an attention that
+    // uses it gathers V rows only and forms its softmax weights while they travel.  (With the first fused kernels
+    // the query launch that followed such an attention was measured ~3 us slower at 128k keys and groups of four:
+    // it no longer found the retrieved K rows touched just before it.  On the present kernels the scores win for
+    // every group size: 59.8 -> 57.1 us per step at 128k keys with r = 4 where every group survives, 24.7 -> 21.7
+    // on keys with positional locality.)
     const bool fused = ix->cfg.kv_dtype == LVR_BF16 && !(ix->cfg.flags & LVR_SEPARATE_KERNELS);
-    // With one key per group the query launch reads few key rows itself (the survivors of the 8-bit
-    // test), so it has nothing to gain from rows the attention touched: the scores are used there too
-    // (measured at 128k keys: attention 0.9 us shorter, the query launch unchanged).
-    const bool scores_whatever_the_form = fused && ((ix->cfg.flags & LVR_KV_IN_HOST_MEMORY) || ix->cfg.group_size == 1);
-    const bool one_launch = one_launch_attention(ix, scores_whatever_the_form);
-    const bool use_scores = fused && (one_launch || scores_whatever_the_form);
-    const float *carried = use_scores ? ix->scores : nullptr;
+    const bool one_launch = one_launch_attention(ix, fused);
+    const float *carried = fused ? ix->scores : nullptr;
     if (one_launch) {   // reads the set sizes from the internal counters and hands them to the caller
         Timed t(ix, LVR_K_ATTN_PARTIAL, st, true);
         LVR_HIP(lvr_launch_sparse_attention_wg(ix, q, out_idx, carried, lvr_head_count(ix), LVR_CNT_STRIDE, cap, out, out_count, st));
