@@ -237,9 +237,10 @@ void prof_free(lvr_index *ix) {
 // at 0.5-1 % retrieved).  The set sizes are not known on the host, so the context length stands in.
 inline bool one_launch_attention(const lvr_index *ix, bool carried = false) {
     if (ix->attn_one_launch >= 0) return ix->attn_one_launch != 0;
-    // lists that carry their scores take the one-launch kernel with two dependent trips, which moves the
-    // crossover up (128k keys, 656 retrieved per head: 33.4 against 34.0 us per step)
-    return lvr_n_bhq(ix) >= 128 || ix->n_total <= (carried ? 131072 : 65536);
+    // lists that carry their scores take the one-launch kernels with two dependent trips (two workgroups per head
+    // beyond 65536 keys), which moves the crossover up: one launch against two, us per step at 0.5 % retrieved,
+    // 32 heads: 39.7 / 41.3 at 196608 keys, 50.2 / 51.3 at 262144, 102.5 / 101.5 at 524288
+    return lvr_n_bhq(ix) >= 128 || ix->n_total <= (carried ? 262144 : 65536);
 }
 
 // One grouping per coordinate block: groups [g0, g0 + ng) are formed from arena rows g0*r .. (g0+ng)*r - 1

@@ -1257,12 +1257,12 @@ def test_fp8_centres_unsupported_configurations(G):
 # ---------------------------------------------------------------------------------------------
 # One-launch attention over lists that carry their scores: set sizes around its batch and round boundaries
 # ---------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("hkv,gq,n", [(2, 4, 6000), (1, 1, 6000), (3, 2, 6000), (2, 4, 66000), (1, 2, 70001), (1, 2, 140001)])
+@pytest.mark.parametrize("hkv,gq,n", [(2, 4, 6000), (1, 1, 6000), (3, 2, 6000), (2, 4, 66000), (1, 2, 70001), (1, 2, 140001), (1, 2, 270001)])
 def test_decode_step_set_sizes_around_batch_and_round_boundaries(G, oracle, hkv, gq, n):
     """The decode step's attention takes entries in batches of 16 dealt to 16 waves and in rounds of 1024; every
     head of one step gets a different set size around those boundaries (0, 1, 15, 16, 17, 255, 256, 257, 1023, 1024,
     1025, 2047, 2049, 3000), with the list capacity at the context and just above the largest set.  Beyond 65536
-    keys of context two workgroups share a head (one per half of the channels); beyond 131072 the attention is two
+    keys of context two workgroups share a head (one per half of the channels); beyond 262144 the attention is two
     launches (partial sums over slices of the list, then a merge), still fed with the carried scores."""
     hq = hkv * gq
     cache = _small_cache(2, n, hkv=hkv)
