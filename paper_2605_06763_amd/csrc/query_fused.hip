@@ -625,12 +625,15 @@ query_fused_kernel(const FusedArgs a) {
         if constexpr (DB) __builtin_amdgcn_s_setprio(0);
         // compaction of the four waves' masks into the LDS list
         const int cnt = __popc(mybits);
+        // inclusive prefix sum over the wave in six DPP steps (within rows of 16 lanes: shifts by 1, 2, 4, 8; then
+        // lane 15 of a row to the next row, lane 31 to the upper half): no trip through LDS, unlike six shuffles
         int incl = cnt;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            int t = __shfl_up(incl, off, 64);
-            if (lane >= off) incl += t;
-        }
+        incl += __builtin_amdgcn_update_dpp(0, incl, 0x111, 0xf, 0xf, false);   // row_shr:1
+        incl += __builtin_amdgcn_update_dpp(0, incl, 0x112, 0xf, 0xf, false);   // row_shr:2
+        incl += __builtin_amdgcn_update_dpp(0, incl, 0x114, 0xf, 0xf, false);   // row_shr:4
+        incl += __builtin_amdgcn_update_dpp(0, incl, 0x118, 0xf, 0xf, false);   // row_shr:8
+        incl += __builtin_amdgcn_update_dpp(0, incl, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
+        incl += __builtin_amdgcn_update_dpp(0, incl, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
         if (lane == 63) s_tot[wave] = incl;
         __syncthreads();
         if constexpr (CSP) {
@@ -645,10 +648,17 @@ query_fused_kernel(const FusedArgs a) {
             total += s_tot[w];
         }
         {
+            // one pass per set bit of the fullest mask in the wave (a few when most groups are pruned) instead
+            // of sixteen tests in every lane
             int o = before + (incl - cnt);
-#pragma unroll
-            for (int k = 0; k < 16; ++k)
-                if (mybits & (1u << k)) s_list[o++] = (uint16_t)((wave * a.tiles_per_wave + lane) * 16 + k);
+            uint32_t left = mybits;
+            while (__ballot(left != 0)) {   // wave-uniform
+                if (left != 0) {
+                    const int k = __builtin_ctz(left);
+                    s_list[o++] = (uint16_t)((wave * a.tiles_per_wave + lane) * 16 + k);
+                    left &= left - 1;
+                }
+            }
         }
         if (threadIdx.x == 0) a.seg_count[(int64_t)bh * a.max_segs + blockIdx.x] = total;
         __syncthreads();
