@@ -50,8 +50,9 @@ struct lvr_emitter {
         constexpr int kUnroll = NH <= 4 ? NH : 2;
 #pragma unroll kUnroll
         for (int h = 0; h < NH; ++h) {
-            const int b_h = __shfl(base, rep_base + h, 64);
-            const int c_h = __shfl(count, rep_base + h, 64);
+            // the reporting lane is the same for the whole wave: a lane read, not a shuffle through LDS
+            const int b_h = __builtin_amdgcn_readlane(base, rep_base + h);
+            const int c_h = __builtin_amdgcn_readlane(count, rep_base + h);
             if (lane < c_h) {
                 const int64_t p = (int64_t)b_h + lane;
                 if (p < a.cap) {

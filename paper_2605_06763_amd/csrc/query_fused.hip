@@ -799,8 +799,9 @@ query_fused_kernel(const FusedArgs a) {
         int base = 0;
         if (rep[hb] && kq == 0) {
             const int h = hb * W + n - 8;
-            base = s_wbase[h];
-            for (int w = 0; w < wave; ++w) base += s_wcnt[w][h];
+            // all three reads at once (a loop up to `wave` would take them one LDS trip after the other)
+            const int c0 = s_wcnt[0][h], c1 = s_wcnt[1][h], c2 = s_wcnt[2][h];
+            base = s_wbase[h] + (wave > 0 ? c0 : 0) + (wave > 1 ? c1 : 0) + (wave > 2 ? c2 : 0);
         }
         if (__ballot(em[hb].count > 0)) em[hb].write_out(a.emit, lane, spos, base);
     }
