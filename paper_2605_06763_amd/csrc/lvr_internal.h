@@ -207,6 +207,18 @@ __device__ __forceinline__ float lvr_bf16_lo(uint32_t w) { return __uint_as_floa
 __device__ __forceinline__ float lvr_bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
 // Round-to-nearest-even fp32 -> bf16 bit pattern (finite inputs).
+// Inclusive prefix sum over the 64 lanes of a wave in six DPP steps (within rows of 16 lanes: shifts by 1, 2, 4, 8;
+// then lane 15 of a row into the next row, lane 31 into the upper half): no trip through LDS, unlike six shuffles.
+__device__ __forceinline__ int lvr_wave_inclusive_sum(int v) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
 __device__ __forceinline__ uint32_t lvr_f32_to_bf16_bits(float f) {
     uint32_t u = __float_as_uint(f);
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;

@@ -55,12 +55,7 @@ __device__ __forceinline__ void compact_segment(const PruneArgs &a, int bh, int 
                                                 int64_t wave_gbase, int64_t seg_base) {
     __shared__ int s_tot[4];
     const int cnt = __popc(mybits);
-    int incl = cnt;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        int t = __shfl_up(incl, off, 64);
-        if (lane >= off) incl += t;
-    }
+    const int incl = lvr_wave_inclusive_sum(cnt);
     if (lane == 63) s_tot[wave] = incl;
     __syncthreads();
     int before = 0, total = 0;
@@ -71,10 +66,15 @@ __device__ __forceinline__ void compact_segment(const PruneArgs &a, int bh, int 
     }
     if (threadIdx.x == 0) a.seg_count[(int64_t)bh * a.max_segs + blockIdx.x] = total;
     int32_t *out = a.surv_list + (int64_t)bh * a.max_groups + seg_base + before + (incl - cnt);
+    // one pass per set bit of the fullest mask in the wave
     int j = 0;
-#pragma unroll
-    for (int k = 0; k < W; ++k)
-        if (mybits & (1u << k)) out[j++] = (int32_t)(wave_gbase + (int64_t)lane * W + k);
+    uint32_t left = mybits;
+    while (__ballot(left != 0)) {   // wave-uniform
+        if (left != 0) {
+            out[j++] = (int32_t)(wave_gbase + (int64_t)lane * W + __builtin_ctz(left));
+            left &= left - 1;
+        }
+    }
 }
 
 // ------------------------------------------------------------------------------------------

@@ -625,15 +625,7 @@ query_fused_kernel(const FusedArgs a) {
         if constexpr (DB) __builtin_amdgcn_s_setprio(0);
         // compaction of the four waves' masks into the LDS list
         const int cnt = __popc(mybits);
-        // inclusive prefix sum over the wave in six DPP steps (within rows of 16 lanes: shifts by 1, 2, 4, 8; then
-        // lane 15 of a row to the next row, lane 31 to the upper half): no trip through LDS, unlike six shuffles
-        int incl = cnt;
-        incl += __builtin_amdgcn_update_dpp(0, incl, 0x111, 0xf, 0xf, false);   // row_shr:1
-        incl += __builtin_amdgcn_update_dpp(0, incl, 0x112, 0xf, 0xf, false);   // row_shr:2
-        incl += __builtin_amdgcn_update_dpp(0, incl, 0x114, 0xf, 0xf, false);   // row_shr:4
-        incl += __builtin_amdgcn_update_dpp(0, incl, 0x118, 0xf, 0xf, false);   // row_shr:8
-        incl += __builtin_amdgcn_update_dpp(0, incl, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
-        incl += __builtin_amdgcn_update_dpp(0, incl, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
+        const int incl = lvr_wave_inclusive_sum(cnt);
         if (lane == 63) s_tot[wave] = incl;
         __syncthreads();
         if constexpr (CSP) {
